@@ -1,0 +1,231 @@
+/*
+ * CPU checker for the fused tensor operators.  TEST INFRASTRUCTURE ONLY:
+ * it exists so that the GPU library's results can be compared with something
+ * obviously correct, and to be timed as a reported CPU baseline.  The GPU
+ * library never calls it and shares no source, header or table with it.
+ *
+ * Every function is the plain mathematical definition of its operator written
+ * as nested loops: fp32 inputs are widened to double, every product and sum
+ * is taken in double (an fp32*fp32 product is exact in double), libm
+ * exp/tanh/sqrt in double, results returned as double.  Chains keep their
+ * intermediates in double.  The only parallelism is an OpenMP pragma on the
+ * outermost independent loop, the style of the CPU code in the paper's
+ * Listing "CPU C Code without TVM dependency" (Section 3.5) and of its
+ * VGG-16 case study (Section 5.3).  No blocking, no SIMD, no BLAS.
+ *
+ * Operator classes follow the paper's Table 1: Elementwise (add, mul, relu),
+ * Reduction (sum, mean, softmax), ComputeIntensive (matmul, conv).
+ *
+ * Parity pins: every function here is pinned by tests that do not run it
+ * against itself (closed forms, invariants, brute force, textbook special
+ * cases); none is "parity unpinned".
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+/* ---- ComputeIntensive: matmul (Table 1) with a column-broadcast bias -------
+ * Z[m][n] = bias[n] + sum_k X[m][k] * W[k][n];  X is [M,K], W is [K,N], both
+ * row-major.  Dn[m][n] = |bias[n]| + sum_k |X[m][k]| |W[k][n]| is the scale
+ * the contraction tolerance is normalised by.  bias may be NULL (= 0);
+ * Dn may be NULL. */
+void ref_gemm_bias(const float *X, const float *W, const float *bias,
+                   int64_t M, int64_t K, int64_t N, double *Z, double *Dn)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            double b = bias ? (double)bias[n] : 0.0;
+            double acc = b, mag = fabs(b);
+            for (int64_t k = 0; k < K; ++k) {
+                double a = (double)X[m * K + k], w = (double)W[k * N + n];
+                acc += a * w;
+                mag += fabs(a) * fabs(w);
+            }
+            Z[m * N + n] = acc;
+            if (Dn) Dn[m * N + n] = mag;
+        }
+    }
+}
+
+/* ---- Elementwise: relu (Table 1), in place ------------------------------ */
+void ref_relu(double *Z, int64_t count)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) Z[i] = Z[i] > 0.0 ? Z[i] : 0.0;
+}
+
+/* ---- Reduction: softmax (Table 1) over the last dimension ---------------
+ * Y[r][n] = exp(Z[r][n] - max_n Z[r][.]) / sum_n exp(Z[r][n] - max). */
+void ref_softmax_rows(const double *Z, int64_t rows, int64_t N, double *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *z = Z + r * N;
+        double *y = Y + r * N;
+        double mx = z[0];
+        for (int64_t n = 1; n < N; ++n) if (z[n] > mx) mx = z[n];
+        double sum = 0.0;
+        for (int64_t n = 0; n < N; ++n) { y[n] = exp(z[n] - mx); sum += y[n]; }
+        for (int64_t n = 0; n < N; ++n) y[n] /= sum;
+    }
+}
+
+/* ---- Elementwise chain: per-channel affine, relu, residual add ----------
+ * T[p][i] = relu(X[p][i] * scale[c] + shift[c]) + R[p][i], with plane
+ * p = n*C + c of an NCHW tensor and i running over the H*W plane.  The
+ * residual is added after the relu. */
+void ref_affine_relu_residual(const float *X, const float *scale, const float *shift,
+                              const float *R, int64_t Nb, int64_t C, int64_t HW, double *T)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < Nb * C; ++p) {
+        int64_t c = p % C;
+        double s = (double)scale[c], t = (double)shift[c];
+        for (int64_t i = 0; i < HW; ++i) {
+            double v = (double)X[p * HW + i] * s + t;
+            v = v > 0.0 ? v : 0.0;
+            T[p * HW + i] = v + (double)R[p * HW + i];
+        }
+    }
+}
+
+/* ---- Reduction: mean (Table 1) over each H*W plane = global average pool */
+void ref_avgpool_planes(const double *T, int64_t planes, int64_t HW, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p) {
+        double sum = 0.0;
+        for (int64_t i = 0; i < HW; ++i) sum += T[p * HW + i];
+        out[p] = sum / (double)HW;
+    }
+}
+
+/* ---- Reduction: layer normalisation over the last dimension -------------
+ * mu = sum x / N; var = sum (x-mu)^2 / N (biased); y = (x-mu)/sqrt(var+eps)
+ * * gamma + beta.  gamma / beta may be NULL (= 1 / 0). */
+void ref_layernorm_rows(const float *X, const float *gamma, const float *beta,
+                        int64_t rows, int64_t N, double eps, double *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *x = X + r * N;
+        double mu = 0.0;
+        for (int64_t n = 0; n < N; ++n) mu += (double)x[n];
+        mu /= (double)N;
+        double var = 0.0;
+        for (int64_t n = 0; n < N; ++n) { double d = (double)x[n] - mu; var += d * d; }
+        var /= (double)N;
+        double inv = 1.0 / sqrt(var + eps);
+        for (int64_t n = 0; n < N; ++n) {
+            double g = gamma ? (double)gamma[n] : 1.0, b = beta ? (double)beta[n] : 0.0;
+            Y[r * N + n] = ((double)x[n] - mu) * inv * g + b;
+        }
+    }
+}
+
+/* ---- Elementwise: tanh-form GELU, in place -------------------------------
+ * 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3))) */
+void ref_gelu_tanh(double *Y, int64_t count)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) {
+        double y = Y[i];
+        Y[i] = 0.5 * y * (1.0 + tanh(0.7978845608028654 * (y + 0.044715 * y * y * y)));
+    }
+}
+
+/* ---- ComputeIntensive: conv (Table 1), NCHW, bias-initialised ------------
+ * Loop nest of the paper's fine-tuned VGG-16 listing (Section 5.3): n, k, h,
+ * w outside, accumulator starts at bias[k], then c, kh, kw; the tap index
+ * ih = h*stride - P + kh, iw = w*stride - P + kw and the zero-padding bounds
+ * test are those of the listing before it; output index
+ * ((n*K + k)*Ho + h)*Wo + w.  Cross-correlation (no kernel flip).  Weights
+ * are [K][C][R][S] contiguous.  Output size (H + 2P - R)/stride + 1.
+ * Dn (may be NULL) = |bias| + sum |in| |wt| over the taps inside the image. */
+void ref_conv2d_nchw_bias(const float *in, const float *wt, const float *bias,
+                          int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t K,
+                          int64_t R, int64_t S, int64_t stride, int64_t P,
+                          double *out, double *Dn)
+{
+    const int64_t Ho = (H + 2 * P - R) / stride + 1, Wo = (W + 2 * P - S) / stride + 1;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t n = 0; n < Nb; ++n) {
+        for (int64_t k = 0; k < K; ++k) {
+            for (int64_t h = 0; h < Ho; ++h) {
+                for (int64_t w = 0; w < Wo; ++w) {
+                    double b = bias ? (double)bias[k] : 0.0;
+                    double sum = b, mag = fabs(b);
+                    for (int64_t c = 0; c < C; ++c) {
+                        for (int64_t kh = 0; kh < R; ++kh) {
+                            for (int64_t kw = 0; kw < S; ++kw) {
+                                int64_t ih = h * stride - P + kh;
+                                int64_t iw = w * stride - P + kw;
+                                if (ih >= 0 && ih < H && iw >= 0 && iw < W) {
+                                    double a = (double)in[((n * C + c) * H + ih) * W + iw];
+                                    double g = (double)wt[((k * C + c) * R + kh) * S + kw];
+                                    sum += a * g;
+                                    mag += fabs(a) * fabs(g);
+                                }
+                            }
+                        }
+                    }
+                    int64_t o = ((n * K + k) * Ho + h) * Wo + w;
+                    out[o] = sum;
+                    if (Dn) Dn[o] = mag;
+                }
+            }
+        }
+    }
+}
+
+/* ---- Batched matmul - softmax - matmul ------------------------------------
+ * For each batch b and query i:  s_j = scale * sum_d Q[b][i][d] K[b][j][d];
+ * p = softmax_j(s) (two passes over one materialised row, not an online
+ * recurrence);  O[b][i][d] = sum_j p_j V[b][j][d].
+ * Dn[b][i][d] = sum_j p_j |V[b][j][d]| (may be NULL).
+ * Q is [B,Lq,D], K and V are [B,Lk,D], row-major; Lk >= 1. */
+void ref_attention(const float *Q, const float *K, const float *V,
+                   int64_t B, int64_t Lq, int64_t Lk, int64_t D, double scale,
+                   double *O, double *Dn)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t bi = 0; bi < B * Lq; ++bi) {
+        int64_t b = bi / Lq;
+        const float *q = Q + bi * D;
+        const float *Kb = K + b * Lk * D, *Vb = V + b * Lk * D;
+        double *s = (double *)malloc((size_t)Lk * sizeof(double));
+        double mx = -INFINITY;
+        for (int64_t j = 0; j < Lk; ++j) {
+            double acc = 0.0;
+            for (int64_t d = 0; d < D; ++d) acc += (double)q[d] * (double)Kb[j * D + d];
+            s[j] = acc * scale;
+            if (s[j] > mx) mx = s[j];
+        }
+        double sum = 0.0;
+        for (int64_t j = 0; j < Lk; ++j) { s[j] = exp(s[j] - mx); sum += s[j]; }
+        for (int64_t j = 0; j < Lk; ++j) s[j] /= sum;
+        for (int64_t d = 0; d < D; ++d) {
+            double acc = 0.0, mag = 0.0;
+            for (int64_t j = 0; j < Lk; ++j) {
+                double v = (double)Vb[j * D + d];
+                acc += s[j] * v;
+                mag += s[j] * fabs(v);
+            }
+            O[bi * D + d] = acc;
+            if (Dn) Dn[bi * D + d] = mag;
+        }
+        free(s);
+    }
+}
+
+/* Threads the OpenMP loops above will use (reported next to baseline timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int ref_max_threads(void) { return omp_get_max_threads(); }
+void ref_set_threads(int n) { if (n > 0) omp_set_num_threads(n); }
+#else
+int ref_max_threads(void) { return 1; }
+void ref_set_threads(int n) { (void)n; }
+#endif

@@ -1,0 +1,178 @@
+"""ctypes front end of the CPU checker (oracle/hpct_ref.c) and the five chains
+composed from its operator definitions.  Inputs are fp32 numpy arrays (the
+exact bits the GPU library is given); every result is fp64.
+
+Test infrastructure only.  Each chain keeps its intermediates in fp64 and is
+the composition, in the order the workload states, of the definitions in
+hpct_ref.c (paper Table 1 operator classes; Section 5.3 for the convolution).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB if os.path.exists(_build.LIB) else _build.build()
+        _lib = C.CDLL(path)
+        i64, dbl, p = C.c_int64, C.c_double, C.c_void_p
+        sig = {
+            "ref_gemm_bias": [p, p, p, i64, i64, i64, p, p],
+            "ref_relu": [p, i64],
+            "ref_softmax_rows": [p, i64, i64, p],
+            "ref_affine_relu_residual": [p, p, p, p, i64, i64, i64, p],
+            "ref_avgpool_planes": [p, i64, i64, p],
+            "ref_layernorm_rows": [p, p, p, i64, i64, dbl, p],
+            "ref_gelu_tanh": [p, i64],
+            "ref_conv2d_nchw_bias": [p, p, p] + [i64] * 9 + [p, p],
+            "ref_attention": [p, p, p, i64, i64, i64, i64, dbl, p, p],
+            "ref_set_threads": [C.c_int],
+        }
+        for name, args in sig.items():
+            f = getattr(_lib, name)
+            f.argtypes, f.restype = args, None
+        _lib.ref_max_threads.argtypes, _lib.ref_max_threads.restype = [], C.c_int
+    return _lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def max_threads() -> int:
+    return int(lib().ref_max_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().ref_set_threads(int(n))
+
+
+# ----------------------------------------------------------------- operators
+def gemm_bias(X, W, bias=None, want_norm=False):
+    X, W = _f32(X), _f32(W)
+    M, K = X.shape
+    K2, N = W.shape
+    assert K == K2
+    b = None if bias is None else _f32(bias)
+    Z = np.empty((M, N), dtype=np.float64)
+    Dn = np.empty((M, N), dtype=np.float64) if want_norm else None
+    lib().ref_gemm_bias(_ptr(X), _ptr(W), _ptr(b), M, K, N, _ptr(Z), _ptr(Dn))
+    return (Z, Dn) if want_norm else Z
+
+
+def relu(Z):
+    Z = np.array(Z, dtype=np.float64, order="C")
+    lib().ref_relu(_ptr(Z), Z.size)
+    return Z
+
+
+def softmax_rows(Z):
+    Z = np.ascontiguousarray(Z, dtype=np.float64)
+    N = Z.shape[-1]
+    rows = Z.size // N if N else 0
+    Y = np.empty_like(Z)
+    if Z.size:
+        lib().ref_softmax_rows(_ptr(Z), rows, N, _ptr(Y))
+    return Y
+
+
+def affine_relu_residual(X, scale, shift, R):
+    X, R, scale, shift = _f32(X), _f32(R), _f32(scale), _f32(shift)
+    Nb, Cc, H, W = X.shape
+    assert R.shape == X.shape and scale.shape == (Cc,) and shift.shape == (Cc,)
+    T = np.empty(X.shape, dtype=np.float64)
+    lib().ref_affine_relu_residual(_ptr(X), _ptr(scale), _ptr(shift), _ptr(R), Nb, Cc, H * W, _ptr(T))
+    return T
+
+
+def avgpool_hw(T):
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    Nb, Cc, H, W = T.shape
+    out = np.empty((Nb, Cc), dtype=np.float64)
+    lib().ref_avgpool_planes(_ptr(T), Nb * Cc, H * W, _ptr(out))
+    return out
+
+
+def layernorm_rows(X, gamma=None, beta=None, eps=1e-5):
+    X = _f32(X)
+    rows, N = X.shape
+    g = None if gamma is None else _f32(gamma)
+    b = None if beta is None else _f32(beta)
+    Y = np.empty((rows, N), dtype=np.float64)
+    lib().ref_layernorm_rows(_ptr(X), _ptr(g), _ptr(b), rows, N, float(eps), _ptr(Y))
+    return Y
+
+
+def gelu_tanh(Y):
+    Y = np.array(Y, dtype=np.float64, order="C")
+    lib().ref_gelu_tanh(_ptr(Y), Y.size)
+    return Y
+
+
+def conv_out_hw(H, W, R, S, stride, pad):
+    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+
+
+def conv2d_nchw_bias(inp, wt, bias=None, stride=1, pad=1, want_norm=False):
+    inp, wt = _f32(inp), _f32(wt)
+    Nb, Cc, H, W = inp.shape
+    K, C2, R, S = wt.shape
+    assert Cc == C2
+    b = None if bias is None else _f32(bias)
+    Ho, Wo = conv_out_hw(H, W, R, S, stride, pad)
+    out = np.empty((Nb, K, Ho, Wo), dtype=np.float64)
+    Dn = np.empty_like(out) if want_norm else None
+    lib().ref_conv2d_nchw_bias(_ptr(inp), _ptr(wt), _ptr(b), Nb, Cc, H, W, K, R, S, stride, pad,
+                               _ptr(out), _ptr(Dn))
+    return (out, Dn) if want_norm else out
+
+
+def attention(Q, K, V, scale, want_norm=False):
+    Q, K, V = _f32(Q), _f32(K), _f32(V)
+    B, Lq, D = Q.shape
+    B2, Lk, D2 = K.shape
+    assert V.shape == K.shape and B2 == B and D2 == D and Lk >= 1
+    O = np.empty((B, Lq, D), dtype=np.float64)
+    Dn = np.empty_like(O) if want_norm else None
+    lib().ref_attention(_ptr(Q), _ptr(K), _ptr(V), B, Lq, Lk, D, float(scale), _ptr(O), _ptr(Dn))
+    return (O, Dn) if want_norm else O
+
+
+# -------------------------------------------------------------------- chains
+def chain1(X, W, bias):
+    """softmax_rows(relu(X @ W + bias))"""
+    return softmax_rows(relu(gemm_bias(X, W, bias)))
+
+
+def chain2(X, scale, shift, R):
+    """avgpool_hw(relu(X * scale[c] + shift[c]) + R)"""
+    return avgpool_hw(affine_relu_residual(X, scale, shift, R))
+
+
+def chain3(X, gamma, beta, eps=1e-5):
+    """gelu_tanh(layernorm(X) * gamma + beta)"""
+    return gelu_tanh(layernorm_rows(X, gamma, beta, eps))
+
+
+def chain4(inp, wt, bias, stride=1, pad=1):
+    """relu(conv2d(inp, wt) + bias) and the contraction's normaliser."""
+    out, Dn = conv2d_nchw_bias(inp, wt, bias, stride, pad, want_norm=True)
+    return relu(out), Dn
+
+
+def chain5(Q, K, V, scale=0.125):
+    """softmax(scale * Q K^T) V and the second contraction's normaliser."""
+    return attention(Q, K, V, scale, want_norm=True)

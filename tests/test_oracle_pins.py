@@ -1,0 +1,450 @@
+"""Pins for the CPU checker: it is compared with closed forms, invariants,
+textbook special cases, library witnesses and brute force on tiny inputs, never
+with itself.  The paper prints no worked numeric example for any operator, so
+none of the pins is a value taken from it.  Runs without a GPU."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from oracle import compare, ref
+
+rng = np.random.default_rng(20250610)
+
+
+def f32(a):
+    return np.asarray(a, dtype=np.float32)
+
+
+# ------------------------------------------------------------------ matmul
+def test_gemm_identity_weight_is_copy_plus_bias():
+    X = f32(rng.uniform(-1, 1, (7, 9)))
+    b = f32(rng.uniform(-1, 1, 9))
+    Z = ref.gemm_bias(X, np.eye(9, dtype=np.float32), b)
+    assert np.array_equal(Z, X.astype(np.float64) + b.astype(np.float64))
+
+
+def test_gemm_ones_weight_gives_row_sums():
+    X = f32(rng.uniform(-1, 1, (5, 33)))
+    Z = ref.gemm_bias(X, np.ones((33, 4), np.float32))
+    want = X.astype(np.float64).sum(axis=1, keepdims=True) * np.ones((1, 4))
+    assert np.allclose(Z, want, rtol=0, atol=1e-13)
+
+
+def test_gemm_not_transposed_and_brute_force():
+    # asymmetric shapes and a non-symmetric W: a transposed operand or swapped
+    # index cannot reproduce this
+    M, K, N = 3, 5, 7
+    X = f32(rng.normal(size=(M, K)))
+    W = f32(rng.normal(size=(K, N)))
+    b = f32(rng.normal(size=N))
+    Z, Dn = ref.gemm_bias(X, W, b, want_norm=True)
+    for m, n in itertools.product(range(M), range(N)):
+        acc, mag = float(b[n]), abs(float(b[n]))
+        for k in range(K):
+            acc += float(X[m, k]) * float(W[k, n])
+            mag += abs(float(X[m, k])) * abs(float(W[k, n]))
+        assert Z[m, n] == pytest.approx(acc, rel=1e-14, abs=1e-15)
+        assert Dn[m, n] == pytest.approx(mag, rel=1e-14)
+
+
+def test_gemm_matches_fp64_library_matmul():
+    X = f32(rng.uniform(-1, 1, (64, 256)))
+    W = f32(rng.uniform(-1 / 16, 1 / 16, (256, 256)))
+    b = f32(rng.uniform(-0.1, 0.1, 256))
+    Z, Dn = ref.gemm_bias(X, W, b, want_norm=True)
+    want = X.astype(np.float64) @ W.astype(np.float64) + b.astype(np.float64)
+    assert np.max(np.abs(Z - want)) <= 1e-12 * np.max(Dn)
+    wantD = np.abs(X).astype(np.float64) @ np.abs(W).astype(np.float64) + np.abs(b)
+    assert np.allclose(Dn, wantD, rtol=1e-12)
+
+
+def test_gemm_linear_in_x():
+    X1 = f32(rng.normal(size=(4, 6)))
+    W = f32(rng.normal(size=(6, 5)))
+    Xs = f32(X1 * 2)  # exact in fp32
+    assert np.allclose(ref.gemm_bias(Xs, W), 2 * ref.gemm_bias(X1, W), rtol=1e-14)
+    # small integers add exactly in fp32, so additivity in X is exact too
+    A = f32(rng.integers(-8, 9, (4, 6)))
+    Bm = f32(rng.integers(-8, 9, (4, 6)))
+    Wi = f32(rng.integers(-8, 9, (6, 5)))
+    assert np.array_equal(ref.gemm_bias(A + Bm, Wi), ref.gemm_bias(A, Wi) + ref.gemm_bias(Bm, Wi))
+
+
+# ---------------------------------------------------------------- relu etc.
+def test_relu_pointwise():
+    z = np.array([-2.0, -0.0, 0.0, 1e-300, 3.5, -1e-300])
+    assert np.array_equal(ref.relu(z), np.array([0.0, 0.0, 0.0, 1e-300, 3.5, 0.0]))
+
+
+def test_affine_scale_zero_gives_relu_shift_plus_r():
+    X = f32(rng.normal(size=(2, 3, 4, 5)))
+    R = f32(rng.normal(size=(2, 3, 4, 5)))
+    shift = f32([-0.5, 0.25, 1.0])
+    T = ref.affine_relu_residual(X, np.zeros(3, np.float32), shift, R)
+    want = np.maximum(shift.astype(np.float64), 0)[None, :, None, None] + R.astype(np.float64)
+    assert np.array_equal(T, want)
+
+
+def test_affine_identity_on_nonnegative_input():
+    X = f32(np.abs(rng.normal(size=(2, 3, 4, 5))))
+    R = f32(rng.normal(size=(2, 3, 4, 5)))
+    T = ref.affine_relu_residual(X, np.ones(3, np.float32), np.zeros(3, np.float32), R)
+    assert np.array_equal(T, X.astype(np.float64) + R.astype(np.float64))
+
+
+def test_affine_residual_is_added_after_relu_and_channel_axis():
+    # X = -1 everywhere, scale = 1, shift = 0: relu kills the affine part, so
+    # T = R exactly (a residual added before the relu would give relu(R-1)).
+    X = -np.ones((2, 3, 2, 2), np.float32)
+    R = f32(rng.normal(size=(2, 3, 2, 2)))
+    T = ref.affine_relu_residual(X, np.ones(3, np.float32), np.zeros(3, np.float32), R)
+    assert np.array_equal(T, R.astype(np.float64))
+    # per-channel parameters index axis 1, not axis 0 or the plane index
+    X = np.ones((2, 3, 2, 2), np.float32)
+    scale = f32([1, 2, 4])
+    shift = f32([0.5, 0.25, 0.125])
+    T = ref.affine_relu_residual(X, scale, shift, np.zeros_like(X))
+    for n, c in itertools.product(range(2), range(3)):
+        assert np.all(T[n, c] == float(scale[c]) + float(shift[c]))
+
+
+def test_affine_brute_force():
+    X = f32(rng.normal(size=(2, 2, 3, 3)))
+    R = f32(rng.normal(size=(2, 2, 3, 3)))
+    sc, sh = f32([0.7, -1.3]), f32([0.2, 0.4])
+    T = ref.affine_relu_residual(X, sc, sh, R)
+    for n, c, h, w in itertools.product(range(2), range(2), range(3), range(3)):
+        v = float(X[n, c, h, w]) * float(sc[c]) + float(sh[c])
+        assert T[n, c, h, w] == pytest.approx(max(v, 0.0) + float(R[n, c, h, w]), rel=1e-15)
+
+
+# ------------------------------------------------------------------ softmax
+def test_softmax_invariants():
+    Z = rng.normal(size=(11, 37)) * 3
+    Y = ref.softmax_rows(Z)
+    assert np.all(np.abs(Y.sum(axis=1) - 1) <= 1e-14 * 37)
+    assert np.all(Y > 0) and np.all(Y <= 1)
+    # shift invariance
+    assert np.allclose(ref.softmax_rows(Z + 5.0), Y, rtol=1e-12)
+    # monotone: order of outputs = order of logits
+    assert np.array_equal(np.argsort(Z, axis=1), np.argsort(Y, axis=1))
+    # ratio identity y_a / y_b = exp(z_a - z_b)
+    assert np.allclose(Y[:, 0] / Y[:, 1], np.exp(Z[:, 0] - Z[:, 1]), rtol=1e-12)
+
+
+def test_softmax_constant_and_onehot_and_is_rowwise():
+    Y = ref.softmax_rows(np.full((3, 8), 2.5))
+    assert np.allclose(Y, 1 / 8, rtol=1e-15)
+    Z = np.zeros((2, 6))
+    Z[0, 4] = 800.0  # would overflow exp() without the max subtraction
+    Z[1, 1] = 800.0
+    Y = ref.softmax_rows(Z)
+    want = np.zeros((2, 6))
+    want[0, 4] = want[1, 1] = 1.0
+    assert np.allclose(Y, want, atol=1e-300)
+    # two-element closed form: softmax([a, b]) = [sigmoid(a-b), sigmoid(b-a)]
+    Y = ref.softmax_rows(np.array([[0.3, -1.1]]))
+    assert Y[0, 0] == pytest.approx(1 / (1 + math.exp(-1.4)), rel=1e-15)
+
+
+# ----------------------------------------------------------------- avg pool
+def test_avgpool_closed_forms():
+    T = np.full((2, 3, 56, 56), 1.25)
+    assert np.array_equal(ref.avgpool_hw(T), np.full((2, 3), 1.25))
+    ramp = np.arange(3136, dtype=np.float64).reshape(1, 1, 56, 56)
+    assert ref.avgpool_hw(ramp)[0, 0] == 1567.5
+    A = rng.normal(size=(2, 2, 5, 7))
+    B = rng.normal(size=(2, 2, 5, 7))
+    assert np.allclose(ref.avgpool_hw(A + B), ref.avgpool_hw(A) + ref.avgpool_hw(B), rtol=1e-13)
+    # each plane separately: plane p filled with p
+    T = np.arange(6, dtype=np.float64).reshape(2, 3, 1, 1) * np.ones((2, 3, 4, 4))
+    assert np.array_equal(ref.avgpool_hw(T), np.arange(6.0).reshape(2, 3))
+
+
+def test_chain2_matches_numpy_definition():
+    X = f32(rng.normal(size=(2, 4, 6, 6)))
+    R = f32(rng.normal(size=(2, 4, 6, 6)))
+    sc, sh = f32(rng.normal(1, 0.1, 4)), f32(rng.normal(0, 0.1, 4))
+    want = (np.maximum(X.astype(np.float64) * sc[None, :, None, None].astype(np.float64)
+                       + sh[None, :, None, None].astype(np.float64), 0) + R).mean(axis=(2, 3))
+    assert np.allclose(ref.chain2(X, sc, sh, R), want, rtol=1e-13, atol=1e-15)
+
+
+# ---------------------------------------------------------------- layernorm
+def test_layernorm_mean_zero_and_variance_closed_form():
+    X = f32(rng.normal(size=(16, 4096)))
+    eps = 1e-5
+    Y = ref.layernorm_rows(X, None, None, eps)
+    assert np.all(np.abs(Y.mean(axis=1)) <= 1e-14)
+    var = X.astype(np.float64).var(axis=1)  # biased
+    assert np.allclose(Y.var(axis=1), var / (var + eps), rtol=1e-12)
+    # an unbiased (N-1) variance would miss this by 1/4096 ~ 2.4e-4
+    assert np.all(np.abs(Y.var(axis=1) - var / (var + eps)) < 1e-9)
+
+
+def test_layernorm_constant_row_gives_beta_and_affine_axis():
+    X = np.full((3, 10), 4.25, np.float32)
+    beta = f32(rng.normal(size=10))
+    gamma = f32(rng.normal(size=10))
+    assert np.array_equal(ref.layernorm_rows(X, gamma, beta, 1e-5), np.tile(beta.astype(np.float64), (3, 1)))
+    # gamma / beta index the normalised (last) dim
+    X = f32(rng.normal(size=(4, 10)))
+    Y0 = ref.layernorm_rows(X, None, None, 1e-5)
+    Y1 = ref.layernorm_rows(X, gamma, beta, 1e-5)
+    assert np.allclose(Y1, Y0 * gamma.astype(np.float64) + beta.astype(np.float64), rtol=1e-14, atol=1e-16)
+
+
+def test_layernorm_affine_invariance_and_permutation_and_eps_placement():
+    X = f32(rng.normal(size=(5, 64)))
+    Xa = f32(X * 4 + 8)  # exact scaling; the sum may round, tolerance covers it
+    Y = ref.layernorm_rows(X, None, None, 0.0)
+    Ya = ref.layernorm_rows(Xa, None, None, 0.0)
+    assert np.allclose(Y, Ya, atol=1e-5)
+    perm = rng.permutation(64)
+    assert np.allclose(ref.layernorm_rows(X[:, perm], None, None, 1e-5),
+                       ref.layernorm_rows(X, None, None, 1e-5)[:, perm], rtol=1e-12, atol=1e-14)
+    # eps is inside the root: row [1,-1] has mu 0, var 1 -> y = x / sqrt(1+eps)
+    Y = ref.layernorm_rows(f32([[1, -1]]), None, None, 3.0)
+    assert np.allclose(Y, [[0.5, -0.5]], rtol=1e-15)
+
+
+# --------------------------------------------------------------------- gelu
+def test_gelu_identities():
+    x = rng.normal(size=1000) * 3
+    g = ref.gelu_tanh(x)
+    gm = ref.gelu_tanh(-x)
+    assert ref.gelu_tanh(np.zeros(1))[0] == 0.0
+    assert np.allclose(g - gm, x, rtol=1e-14, atol=1e-15)  # tanh is odd
+    big = np.array([10.0, 25.0])
+    assert np.allclose(ref.gelu_tanh(big), big, rtol=1e-15)
+    assert np.all(np.abs(ref.gelu_tanh(-big)) < 1e-15)
+    # against the erf form: the tanh form is an approximation of
+    # x * Phi(x) with max abs deviation below 5e-4 (about 2e-4 near |x| ~ 2)
+    erf_form = np.array([0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in x])
+    assert np.max(np.abs(g - erf_form)) < 5e-4
+    # a wrong cubic coefficient or sqrt(2/pi) breaks this printed-constant check
+    assert ref.gelu_tanh(np.array([1.0]))[0] == pytest.approx(
+        0.5 * (1 + math.tanh(math.sqrt(2 / math.pi) * 1.044715)), rel=1e-15)
+
+
+# --------------------------------------------------------------------- conv
+def test_conv_1x1_equals_gemm():
+    Nb, Cc, H, W, K = 2, 5, 3, 4, 6
+    x = f32(rng.normal(size=(Nb, Cc, H, W)))
+    wt = f32(rng.normal(size=(K, Cc, 1, 1)))
+    b = f32(rng.normal(size=K))
+    out = ref.conv2d_nchw_bias(x, wt, b, stride=1, pad=0)
+    # pixels as rows: [N*H*W, C] @ [C, K]
+    Xm = x.transpose(0, 2, 3, 1).reshape(-1, Cc)
+    Z = ref.gemm_bias(Xm, np.ascontiguousarray(wt.reshape(K, Cc).T), b)
+    want = Z.reshape(Nb, H, W, K).transpose(0, 3, 1, 2)
+    assert np.allclose(out, want, rtol=1e-13, atol=1e-15)
+
+
+def test_conv_centre_delta_is_identity_plus_bias():
+    Cc = 4
+    x = f32(rng.normal(size=(2, Cc, 6, 5)))
+    wt = np.zeros((Cc, Cc, 3, 3), np.float32)
+    for c in range(Cc):
+        wt[c, c, 1, 1] = 1
+    b = f32(rng.normal(size=Cc))
+    out = ref.conv2d_nchw_bias(x, wt, b, 1, 1)
+    assert np.array_equal(out, x.astype(np.float64) + b.astype(np.float64)[None, :, None, None])
+
+
+def test_conv_all_ones_counts_valid_taps():
+    Cc = 64
+    x = np.ones((1, Cc, 56, 56), np.float32)
+    wt = np.ones((2, Cc, 3, 3), np.float32)
+    out, Dn = ref.conv2d_nchw_bias(x, wt, None, 1, 1, want_norm=True)
+    assert out.shape == (1, 2, 56, 56)
+    assert np.all(out[:, :, 1:-1, 1:-1] == 576)
+    assert np.all(out[:, :, 0, 1:-1] == 384) and np.all(out[:, :, -1, 1:-1] == 384)
+    assert np.all(out[:, :, 1:-1, 0] == 384) and np.all(out[:, :, 1:-1, -1] == 384)
+    for h, w in [(0, 0), (0, -1), (-1, 0), (-1, -1)]:
+        assert np.all(out[:, :, h, w] == 256)
+    assert np.array_equal(out, Dn)
+
+
+def test_conv_single_offcentre_tap_pins_direction_and_axes():
+    x = f32(rng.normal(size=(1, 1, 5, 6)))
+    wt = np.zeros((1, 1, 3, 3), np.float32)
+    wt[0, 0, 0, 1] = 1  # kh = 0, kw = 1  ->  out[h][w] = in[h-1][w]
+    out = ref.conv2d_nchw_bias(x, wt, None, 1, 1)
+    want = np.zeros((5, 6))
+    want[1:, :] = x[0, 0, :-1, :]
+    assert np.array_equal(out[0, 0], want)
+    wt[:] = 0
+    wt[0, 0, 1, 2] = 1  # kh = 1, kw = 2  ->  out[h][w] = in[h][w+1]
+    out = ref.conv2d_nchw_bias(x, wt, None, 1, 1)
+    want = np.zeros((5, 6))
+    want[:, :-1] = x[0, 0, :, 1:]
+    assert np.array_equal(out[0, 0], want)
+
+
+@pytest.mark.parametrize("stride,pad,R", [(1, 1, 3), (2, 1, 3), (1, 0, 3), (2, 0, 1), (1, 2, 3)])
+def test_conv_brute_force_and_size_formula(stride, pad, R):
+    Nb, Cc, H, W, K = 1, 2, 4, 5, 3
+    x = f32(rng.normal(size=(Nb, Cc, H, W)))
+    wt = f32(rng.normal(size=(K, Cc, R, R)))
+    b = f32(rng.normal(size=K))
+    out, Dn = ref.conv2d_nchw_bias(x, wt, b, stride, pad, want_norm=True)
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    assert out.shape == (Nb, K, Ho, Wo)
+    xp = np.zeros((Nb, Cc, H + 2 * pad, W + 2 * pad))
+    xp[:, :, pad:pad + H, pad:pad + W] = x
+    for k, h, w in itertools.product(range(K), range(Ho), range(Wo)):
+        patch = xp[0, :, h * stride:h * stride + R, w * stride:w * stride + R]
+        want = float(b[k]) + float(np.sum(patch * wt[k].astype(np.float64)))
+        assert out[0, k, h, w] == pytest.approx(want, rel=1e-13, abs=1e-14)
+        wantD = abs(float(b[k])) + float(np.sum(np.abs(patch) * np.abs(wt[k]).astype(np.float64)))
+        assert Dn[0, k, h, w] == pytest.approx(wantD, rel=1e-13)
+
+
+def test_conv_batch_and_channel_layout():
+    # distinct constant per (n, c) plane, one weight per (k, c): out = sum_c w[k,c] * v[n,c] * taps
+    Nb, Cc, K = 2, 3, 2
+    v = np.arange(1, Nb * Cc + 1, dtype=np.float32).reshape(Nb, Cc, 1, 1)
+    x = v * np.ones((Nb, Cc, 4, 4), np.float32)
+    wk = f32([[1, 10, 100], [2, 20, 200]])
+    wt = wk[:, :, None, None] * np.ones((K, Cc, 3, 3), np.float32)
+    out = ref.conv2d_nchw_bias(x, wt, None, 1, 1)
+    for n, k in itertools.product(range(Nb), range(K)):
+        assert out[n, k, 1, 1] == 9 * float(np.sum(wk[k] * v[n, :, 0, 0]))
+
+
+# ---------------------------------------------------------------- attention
+def _attention_unfused(Q, K, V, scale):
+    """Separately written: whole score matrix, numpy ops."""
+    Qd, Kd, Vd = (a.astype(np.float64) for a in (Q, K, V))
+    S = np.einsum("bid,bjd->bij", Qd, Kd) * scale
+    S = S - S.max(axis=2, keepdims=True)
+    P = np.exp(S)
+    P /= P.sum(axis=2, keepdims=True)
+    return np.einsum("bij,bjd->bid", P, Vd), np.einsum("bij,bjd->bid", P, np.abs(Vd))
+
+
+def test_attention_special_cases():
+    B, L, D = 2, 9, 8
+    Q = f32(rng.normal(size=(B, L, D)))
+    K = f32(rng.normal(size=(B, 13, D)))
+    V = f32(rng.normal(size=(B, 13, D)))
+    # constant V
+    Vc = np.full_like(V, 0.75)
+    assert np.allclose(ref.attention(Q, K, Vc, 0.125), 0.75, rtol=1e-14)
+    # Q = 0 -> uniform weights -> column means of V
+    O = ref.attention(np.zeros_like(Q), K, V, 0.125)
+    assert np.allclose(O, np.broadcast_to(V.astype(np.float64).mean(axis=1, keepdims=True), O.shape), rtol=1e-13, atol=1e-15)
+    # one key -> O = V row
+    O = ref.attention(Q, K[:, :1], V[:, :1], 0.125)
+    assert np.allclose(O, np.broadcast_to(V[:, :1].astype(np.float64), O.shape), rtol=1e-15)
+
+
+def test_attention_dominant_key_and_scale():
+    D = 4
+    Q = np.zeros((1, 1, D), np.float32)
+    Q[0, 0, 0] = 10
+    K = np.zeros((1, 6, D), np.float32)
+    K[0, 3, 0] = 40  # score = 400 * scale
+    V = f32(rng.normal(size=(1, 6, D)))
+    O = ref.attention(Q, K, V, 0.125)  # dominant score +50 over the rest
+    assert np.allclose(O[0, 0], V[0, 3], atol=1e-20 + 6 * math.exp(-50) * 4)
+    # scale enters the exponent: two keys, scores q.k = a, 0  ->  p0 = sigmoid(scale * a)
+    K2 = np.zeros((1, 2, D), np.float32)
+    K2[0, 0, 0] = 0.2
+    V2 = np.zeros((1, 2, D), np.float32)
+    V2[0, 0, :] = 1
+    O = ref.attention(Q, K2, V2, 0.125)
+    assert O[0, 0, 0] == pytest.approx(1 / (1 + math.exp(-0.125 * 10 * float(np.float32(0.2)))), rel=1e-14)
+
+
+def test_attention_matches_unfused_composition():
+    B, L, Lk, D = 2, 17, 23, 16
+    Q = f32(rng.normal(size=(B, L, D)))
+    K = f32(rng.normal(size=(B, Lk, D)))
+    V = f32(rng.normal(size=(B, Lk, D)))
+    O, Dn = ref.attention(Q, K, V, 0.25, want_norm=True)
+    wantO, wantD = _attention_unfused(Q, K, V, 0.25)
+    assert np.allclose(O, wantO, rtol=1e-12, atol=1e-14)
+    assert np.allclose(Dn, wantD, rtol=1e-12)
+    # batches are independent: batch 1 alone gives the same rows
+    assert np.array_equal(ref.attention(Q[1:], K[1:], V[1:], 0.25), O[1:])
+
+
+def test_attention_composition_of_pinned_pieces():
+    # GEMM -> scale -> softmax -> GEMM from the separately pinned operators
+    L, Lk, D = 6, 10, 8
+    Q = f32(rng.normal(size=(1, L, D)))
+    K = f32(rng.normal(size=(1, Lk, D)))
+    V = f32(rng.normal(size=(1, Lk, D)))
+    S = ref.gemm_bias(Q[0], np.ascontiguousarray(K[0].T)) * 0.125
+    P = ref.softmax_rows(S)
+    want = P @ V[0].astype(np.float64)
+    assert np.allclose(ref.attention(Q, K, V, 0.125)[0], want, rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- chain 1/3
+def test_chain1_is_composition_with_fp64_intermediates():
+    X = f32(rng.uniform(-1, 1, (8, 32)))
+    W = f32(rng.uniform(-1 / 16, 1 / 16, (32, 16)))
+    b = f32(rng.uniform(-0.1, 0.1, 16))
+    Z = np.maximum(X.astype(np.float64) @ W.astype(np.float64) + b, 0)
+    E = np.exp(Z - Z.max(axis=1, keepdims=True))
+    want = E / E.sum(axis=1, keepdims=True)
+    assert np.allclose(ref.chain1(X, W, b), want, rtol=1e-12)
+
+
+def test_chain3_matches_numpy_definition():
+    X = f32(rng.normal(size=(6, 100)))
+    g, b = f32(rng.normal(1, 0.1, 100)), f32(rng.normal(0, 0.1, 100))
+    Xd = X.astype(np.float64)
+    y = (Xd - Xd.mean(1, keepdims=True)) / np.sqrt(Xd.var(1, keepdims=True) + 1e-5) * g + b
+    want = 0.5 * y * (1 + np.tanh(0.7978845608028654 * (y + 0.044715 * y ** 3)))
+    assert np.allclose(ref.chain3(X, g, b, 1e-5), want, rtol=1e-12, atol=1e-15)
+
+
+# --------------------------------------------------- acceptance-rule machinery
+def test_pointwise_rule_threshold():
+    o = np.array([1.0, -2.0, 0.0, 1e-9])
+    rms = math.sqrt(np.mean(o * o))
+    assert compare.pointwise(o.copy(), o)
+    g = o.copy()
+    g[0] += 0.99e-4
+    assert compare.pointwise(g, o)
+    g[0] = 1.0 + 1.01e-4
+    v = compare.pointwise(g, o)
+    assert not v and v.index == (0,)
+    g = o.copy()
+    g[2] = 0.99e-6 * rms  # floor: 1e-4 * 1e-2 * rms
+    assert compare.pointwise(g, o)
+    g[2] = 1.01e-6 * rms
+    assert not compare.pointwise(g, o)
+    g = o.copy()
+    g[1] = np.nan
+    assert not compare.pointwise(g, o)
+
+
+def test_contraction_rule_threshold():
+    o = np.array([[0.5, -0.25]])
+    Dn = np.array([[10.0, 4.0]])
+    g = o.copy()
+    g[0, 0] += 0.0199
+    assert compare.contraction(g, o, Dn)
+    g[0, 1] -= 0.0081
+    v = compare.contraction(g, o, Dn)
+    assert not v and v.index == (0, 1)
+
+
+def test_planted_mistakes_are_caught():
+    # mistakes planted in copies of the checker's formulas must fail the rules
+    X = f32(rng.normal(size=(4, 256)))
+    good = ref.chain3(X, None, None, 1e-5)
+    Xd = X.astype(np.float64)
+    y = (Xd - Xd.mean(1, keepdims=True)) / np.sqrt(Xd.var(1, ddof=1, keepdims=True) + 1e-5)  # unbiased
+    bad = 0.5 * y * (1 + np.tanh(0.7978845608028654 * (y + 0.044715 * y ** 3)))
+    assert not compare.pointwise(bad, good)
+    erf_form = 0.5 * good * 0 + np.array([[0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in row]
+                                         for row in ref.layernorm_rows(X, None, None, 1e-5)])
+    assert not compare.pointwise(erf_form, good)
