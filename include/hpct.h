@@ -1,0 +1,159 @@
+/*
+ * hpct - fused deep-learning tensor operators for AMD MI355X (gfx950).
+ *
+ * C ABI of the operator library.  One call describes a fused chain
+ *     anchor contraction  ->  elementwise / broadcast epilogues  ->  row reduction
+ * (operator classes of the paper's Table 1: ComputeIntensive "matmul, conv",
+ * Elementwise "add, mul, relu", Reduction "sum, mean, softmax"; fused examples
+ * of its Section 5.3) with an op descriptor; the library validates it, picks a
+ * hand-written HIP kernel and enqueues exactly one kernel per launch on the
+ * caller's stream.
+ *
+ * Conventions
+ *  - All tensors are fp32, described by shape and stride in ELEMENTS.
+ *  - Every data pointer passed to hpct_plan_launch is a DEVICE pointer owned
+ *    by the caller, 16-byte aligned.  Descriptors, plans and the pointer
+ *    arrays themselves live in HOST memory.
+ *  - The library never allocates, frees, copies or synchronises device memory.
+ *    Inputs are never written.  Outputs must not overlap inputs.
+ *  - Calls return a status; on failure hpct_last_error() gives a text for the
+ *    calling thread.  No exception crosses the boundary.
+ *  - Plans are immutable after creation and may be launched from several
+ *    threads at once.
+ *
+ * Operand order in hpct_op_desc.in[] is execution order: the anchor's operands,
+ * then the operands of each epilogue / reduction in the order they run.
+ *
+ *   chain                                             in[]                          out[0]
+ *   GEMM [+BIAS_COL] [+RELU] [+SOFTMAX_LAST]          X[M,K], W[K,N], bias[N]       [M,N]
+ *   NONE  SCALE_SHIFT_CH [+RELU] [+ADD_RESIDUAL]      X[N,C,H,W], scale[C],         [N,C] (AVGPOOL_HW)
+ *         then AVGPOOL_HW or no reduction             shift[C], R[N,C,H,W]          or [N,C,H,W]
+ *   NONE  LAYERNORM_LAST (reduce_before_epi=1)        X[M,N], gamma[N], beta[N]     [M,N]
+ *         [+GELU_TANH]
+ *   NONE  SOFTMAX_LAST                                X[M,N]                        [M,N]
+ *   CONV2D_NCHW [+BIAS_COL] [+RELU]                   in[N,C,H,W], wt[K,C,R,S],     [N,K,Ho,Wo]
+ *                                                     bias[K]
+ *   BGEMM_SOFTMAX_BGEMM (scores scaled by `scale`)    Q[B,L,D], K[B,Lk,D],          [B,L,D]
+ *                                                     V[B,Lk,D]
+ */
+#ifndef HPCT_H
+#define HPCT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HPCT_OK = 0,
+    HPCT_ERR_NULL = 1,            /* a required pointer argument is NULL */
+    HPCT_ERR_BAD_DESC = 2,        /* malformed descriptor: ndim, shape <= 0, negative stride, counts, overlap */
+    HPCT_ERR_SHAPE_MISMATCH = 3,  /* operands of the chain do not agree in shape */
+    HPCT_ERR_ALIGNMENT = 4,       /* a device pointer is not 16-byte aligned */
+    HPCT_ERR_UNSUPPORTED = 5,     /* well-formed, but no kernel covers it (chain, layout, size) */
+    HPCT_ERR_WORKSPACE = 6,       /* workspace missing or smaller than hpct_plan_workspace_bytes */
+    HPCT_ERR_HIP = 7              /* the HIP runtime refused the launch */
+} hpct_status;
+
+typedef enum { HPCT_F32 = 0 } hpct_dtype;
+
+#define HPCT_MAX_DIMS 6
+#define HPCT_MAX_EPI 8
+#define HPCT_MAX_IN 8
+#define HPCT_MAX_OUT 2
+
+typedef struct {
+    int32_t ndim;                    /* 1..HPCT_MAX_DIMS */
+    int64_t shape[HPCT_MAX_DIMS];    /* each > 0 */
+    int64_t stride[HPCT_MAX_DIMS];   /* in elements, each >= 0 */
+    hpct_dtype dtype;
+} hpct_tensor_desc;
+
+/* Anchor contraction (Table 1, ComputeIntensive). */
+typedef enum {
+    HPCT_ANCHOR_NONE = 0,
+    HPCT_ANCHOR_GEMM = 1,                 /* Z[m,n] = sum_k X[m,k] W[k,n] */
+    HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM = 2,  /* O = softmax_j(scale * Q K^T) V, per batch */
+    HPCT_ANCHOR_CONV2D_NCHW = 3           /* cross-correlation, zero padding (Section 5.3 case study) */
+} hpct_anchor;
+
+/* Elementwise / broadcast epilogues (Table 1, Elementwise), applied in list order. */
+typedef enum {
+    HPCT_EPI_BIAS_COL = 0,        /* + bias[n]: last dim of a GEMM output, channel k of a conv output */
+    HPCT_EPI_SCALE_SHIFT_CH = 1,  /* x * scale[c] + shift[c], c = dim 1 of NCHW */
+    HPCT_EPI_RELU = 2,            /* max(x, 0) */
+    HPCT_EPI_ADD_RESIDUAL = 3,    /* + R, same shape as the running value */
+    HPCT_EPI_GELU_TANH = 4,       /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
+    HPCT_EPI_SCALE_CONST = 5      /* * desc.scale */
+} hpct_epilogue;
+
+/* Row reductions (Table 1, Reduction). */
+typedef enum {
+    HPCT_RED_NONE = 0,
+    HPCT_RED_SOFTMAX_LAST = 1,    /* exp(x - max) / sum exp(x - max) over the last dim */
+    HPCT_RED_LAYERNORM_LAST = 2,  /* (x - mean) / sqrt(biased var + eps) * gamma + beta over the last dim */
+    HPCT_RED_AVGPOOL_HW = 3       /* mean over dims 2,3 of NCHW */
+} hpct_reduce;
+
+typedef struct {
+    hpct_anchor anchor;
+    int32_t n_epi;
+    hpct_epilogue epi[HPCT_MAX_EPI];
+    hpct_reduce reduce;
+    int32_t reduce_before_epi;    /* 1: reduction runs first, epilogues act on its output */
+    int32_t n_in;
+    hpct_tensor_desc in[HPCT_MAX_IN];
+    int32_t n_out;
+    hpct_tensor_desc out[HPCT_MAX_OUT];
+    int32_t stride_hw[2];         /* conv only */
+    int32_t pad_hw[2];            /* conv only */
+    float eps;                    /* layernorm */
+    float scale;                  /* SCALE_CONST, and the score scale of BGEMM_SOFTMAX_BGEMM */
+} hpct_op_desc;
+
+typedef struct hpct_plan hpct_plan;   /* opaque; host memory */
+
+/* Validate `desc`, choose the kernel variant and launch shape.  Host-only: no
+ * HIP call is made, so it works (and is tested) without a GPU.
+ * On success *out owns a new plan (release with hpct_plan_destroy); on failure
+ * *out is set to NULL.  Errors: NULL, BAD_DESC, SHAPE_MISMATCH, UNSUPPORTED. */
+hpct_status hpct_plan_create(const hpct_op_desc *desc, hpct_plan **out);
+
+/* Device workspace the plan needs at launch, in bytes (0 for every chain
+ * currently supported).  0 for a NULL plan. */
+size_t hpct_plan_workspace_bytes(const hpct_plan *plan);
+
+/* Enqueue the plan's kernel on `hip_stream` (a hipStream_t; NULL = the default
+ * stream) and return without synchronising.
+ *   in_ptrs[i]  device pointer of desc.in[i]   (host array of n_in pointers)
+ *   out_ptrs[i] device pointer of desc.out[i]  (host array of n_out pointers)
+ *   workspace   device pointer, >= hpct_plan_workspace_bytes; may be NULL when that is 0
+ * Errors: NULL (plan, arrays or any data pointer), ALIGNMENT, BAD_DESC (an
+ * output range overlaps an input range), WORKSPACE, HIP. */
+hpct_status hpct_plan_launch(const hpct_plan *plan, const void *const *in_ptrs, void *const *out_ptrs,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Release a plan.  NULL is ignored. */
+void hpct_plan_destroy(hpct_plan *plan);
+
+/* Name of the kernel variant the plan selected (static string; "" for NULL). */
+const char *hpct_plan_kernel_name(const hpct_plan *plan);
+
+/* Launch shape the plan selected: grid[3], block[3] and dynamic LDS bytes.
+ * Any output pointer may be NULL.  Returns HPCT_ERR_NULL for a NULL plan. */
+hpct_status hpct_plan_launch_shape(const hpct_plan *plan, uint32_t grid[3], uint32_t block[3],
+                                   uint32_t *lds_bytes);
+
+/* Text of the last error on the calling thread ("" if none); valid until the
+ * next hpct call on this thread. */
+const char *hpct_last_error(void);
+
+/* Library version string. */
+const char *hpct_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HPCT_H */

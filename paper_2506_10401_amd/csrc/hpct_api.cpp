@@ -1,0 +1,410 @@
+// Host side of the C ABI: descriptor validation, chain recognition, plan
+// objects, launch-time pointer checks and dispatch to the kernel launchers.
+// Nothing here touches device memory; hpct_plan_create makes no HIP call.
+#include "../../include/hpct.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "kernels.hpp"
+
+using namespace hpct;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+hpct_status fail(hpct_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+void clear_err() { g_err[0] = 0; }
+
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn };
+
+constexpr int64_t kI32Max = 2147483647LL;
+
+}  // namespace
+
+struct hpct_plan {
+    Kind kind;
+    LaunchShape shape;
+    int32_t n_in, n_out;
+    // byte extents of every operand (max offset + 1 element), for the overlap check
+    int64_t in_bytes[HPCT_MAX_IN];
+    int64_t out_bytes[HPCT_MAX_OUT];
+    // which in[] slot feeds which kernel operand; -1 = absent
+    int32_t slot[4];
+    union {
+        GemmParams gemm;
+        AffineParams affine;
+        LayernormParams ln;
+        SoftmaxParams sm;
+        ConvParams conv;
+        AttnParams attn;
+    } u;
+};
+
+namespace {
+
+// ndim / shape / stride / dtype sanity and the byte extent; overflow-safe.
+hpct_status check_tensor(const hpct_tensor_desc& t, const char* what, int idx, int64_t* count, int64_t* extent_bytes) {
+    if (t.ndim < 1 || t.ndim > HPCT_MAX_DIMS)
+        return fail(HPCT_ERR_BAD_DESC, "%s[%d]: ndim %d outside 1..%d", what, idx, t.ndim, HPCT_MAX_DIMS);
+    if (t.dtype != HPCT_F32) return fail(HPCT_ERR_UNSUPPORTED, "%s[%d]: dtype %d (only fp32)", what, idx, (int)t.dtype);
+    int64_t n = 1, maxoff = 0;
+    for (int d = 0; d < t.ndim; ++d) {
+        if (t.shape[d] <= 0) return fail(HPCT_ERR_BAD_DESC, "%s[%d]: shape[%d] = %lld must be > 0", what, idx, d, (long long)t.shape[d]);
+        if (t.stride[d] < 0) return fail(HPCT_ERR_BAD_DESC, "%s[%d]: stride[%d] = %lld must be >= 0", what, idx, d, (long long)t.stride[d]);
+        if (__builtin_mul_overflow(n, t.shape[d], &n))
+            return fail(HPCT_ERR_BAD_DESC, "%s[%d]: element count overflows 63 bits", what, idx);
+        int64_t span;
+        if (__builtin_mul_overflow(t.shape[d] - 1, t.stride[d], &span) || __builtin_add_overflow(maxoff, span, &maxoff))
+            return fail(HPCT_ERR_BAD_DESC, "%s[%d]: largest offset overflows 63 bits", what, idx);
+    }
+    int64_t bytes;
+    if (__builtin_add_overflow(maxoff, (int64_t)1, &bytes) || __builtin_mul_overflow(bytes, (int64_t)4, &bytes))
+        return fail(HPCT_ERR_BAD_DESC, "%s[%d]: byte extent overflows 63 bits", what, idx);
+    *count = n;
+    *extent_bytes = bytes;
+    return HPCT_OK;
+}
+
+bool contiguous(const hpct_tensor_desc& t) {
+    int64_t want = 1;
+    for (int d = t.ndim - 1; d >= 0; --d) {
+        if (t.shape[d] != 1 && t.stride[d] != want) return false;
+        want *= t.shape[d];
+    }
+    return true;
+}
+
+bool shape_is(const hpct_tensor_desc& t, int nd, const int64_t* dims) {
+    if (t.ndim != nd) return false;
+    for (int d = 0; d < nd; ++d)
+        if (t.shape[d] != dims[d]) return false;
+    return true;
+}
+
+#define REQUIRE_SHAPE(t, what, ...)                                                              \
+    do {                                                                                         \
+        const int64_t dims_[] = {__VA_ARGS__};                                                   \
+        if (!shape_is((t), (int)(sizeof dims_ / sizeof dims_[0]), dims_))                        \
+            return fail(HPCT_ERR_SHAPE_MISMATCH, "%s has the wrong shape for this chain", what); \
+    } while (0)
+
+// epilogue list must be a subsequence of `allowed` (in that order, each at most once)
+bool parse_epi(const hpct_op_desc& d, const hpct_epilogue* allowed, int n_allowed, bool* present) {
+    for (int i = 0; i < n_allowed; ++i) present[i] = false;
+    int pos = 0;
+    for (int e = 0; e < d.n_epi; ++e) {
+        while (pos < n_allowed && allowed[pos] != d.epi[e]) ++pos;
+        if (pos == n_allowed) return false;
+        present[pos++] = true;
+    }
+    return true;
+}
+
+hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
+    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_RELU};
+    bool has[2];
+    if (!parse_epi(d, allowed, 2, has)) return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [RELU] in that order");
+    if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_SOFTMAX_LAST)
+        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: reduction must be NONE or SOFTMAX_LAST");
+    if (d.reduce != HPCT_RED_NONE && d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: the reduction runs after the epilogues");
+    const int need = 2 + (has[0] ? 1 : 0);
+    if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "GEMM chain takes %d inputs and 1 output (got %d, %d)", need, d.n_in, d.n_out);
+    const hpct_tensor_desc &X = d.in[0], &W = d.in[1];
+    if (X.ndim != 2 || W.ndim != 2) return fail(HPCT_ERR_SHAPE_MISMATCH, "GEMM operands must be 2-D: X[M,K], W[K,N]");
+    const int64_t M = X.shape[0], K = X.shape[1], N = W.shape[1];
+    if (W.shape[0] != K) return fail(HPCT_ERR_SHAPE_MISMATCH, "W.shape[0] = %lld does not match X.shape[1] = %lld", (long long)W.shape[0], (long long)K);
+    if (has[0]) REQUIRE_SHAPE(d.in[2], "bias", N);
+    REQUIRE_SHAPE(d.out[0], "out[0]", M, N);
+    for (int i = 0; i < d.n_in; ++i)
+        if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous row-major layouts are supported", i);
+    if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous row-major layouts are supported");
+    if (M > kI32Max || K > kI32Max || N > kI32Max || M * N > kI32Max || M * K > kI32Max || K * N > kI32Max)
+        return fail(HPCT_ERR_UNSUPPORTED, "GEMM: operand larger than 2^31-1 elements");
+    const bool sm = d.reduce == HPCT_RED_SOFTMAX_LAST;
+    if (sm && N > kGemmSoftmaxMaxN) return fail(HPCT_ERR_UNSUPPORTED, "GEMM + SOFTMAX_LAST: N = %lld exceeds the fused limit %d", (long long)N, kGemmSoftmaxMaxN);
+    p.kind = Kind::Gemm;
+    p.u.gemm = GemmParams{nullptr, nullptr, nullptr, nullptr, (int32_t)M, (int32_t)K, (int32_t)N, has[1] ? 1 : 0, sm ? 1 : 0};
+    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has[0] ? 2 : -1; p.slot[3] = -1;
+    p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm);
+    return HPCT_OK;
+}
+
+hpct_status plan_rows(const hpct_op_desc& d, hpct_plan& p) {
+    // LAYERNORM_LAST [+GELU_TANH]  or  SOFTMAX_LAST alone
+    const hpct_tensor_desc& X = d.in[0];
+    if (X.ndim != 2) return fail(HPCT_ERR_SHAPE_MISMATCH, "row reductions take a 2-D input X[M,N]");
+    const int64_t M = X.shape[0], N = X.shape[1];
+    if (d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "row reductions produce 1 output");
+    REQUIRE_SHAPE(d.out[0], "out[0]", M, N);
+    if (N > kI32Max || M > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "row reduction: more than 2^31-1 rows or columns");
+    if (d.reduce == HPCT_RED_SOFTMAX_LAST) {
+        if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "SOFTMAX_LAST without an anchor takes no epilogues");
+        if (d.n_in != 1) return fail(HPCT_ERR_BAD_DESC, "SOFTMAX_LAST takes 1 input");
+        if (!contiguous(X) || !contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "only contiguous row-major layouts are supported");
+        p.kind = Kind::Softmax;
+        p.u.sm = SoftmaxParams{nullptr, nullptr, M, (int32_t)N};
+        p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = -1;
+        p.shape = softmax_shape(M, (int32_t)N);
+        return HPCT_OK;
+    }
+    bool gelu = false;
+    if (d.n_epi == 1 && d.epi[0] == HPCT_EPI_GELU_TANH) gelu = true;
+    else if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "LAYERNORM_LAST: the only epilogue supported is GELU_TANH");
+    if (gelu && !d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "LAYERNORM_LAST with GELU_TANH needs reduce_before_epi = 1");
+    if (d.n_in != 3 && d.n_in != 1) return fail(HPCT_ERR_BAD_DESC, "LAYERNORM_LAST takes X, gamma, beta (or X alone)");
+    if (d.n_in == 3) { REQUIRE_SHAPE(d.in[1], "gamma", N); REQUIRE_SHAPE(d.in[2], "beta", N); }
+    for (int i = 0; i < d.n_in; ++i)
+        if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous row-major layouts are supported", i);
+    if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous row-major layouts are supported");
+    if (!(d.eps >= 0.f)) return fail(HPCT_ERR_BAD_DESC, "eps must be >= 0");
+    p.kind = Kind::Layernorm;
+    p.u.ln = LayernormParams{nullptr, nullptr, nullptr, nullptr, M, (int32_t)N, d.eps, gelu ? 1 : 0};
+    p.slot[0] = 0; p.slot[1] = d.n_in == 3 ? 1 : -1; p.slot[2] = d.n_in == 3 ? 2 : -1; p.slot[3] = -1;
+    p.shape = layernorm_shape(M, (int32_t)N);
+    return HPCT_OK;
+}
+
+hpct_status plan_affine(const hpct_op_desc& d, hpct_plan& p) {
+    static const hpct_epilogue allowed[] = {HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL};
+    bool has[3];
+    if (!parse_epi(d, allowed, 3, has))
+        return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain: epilogues must be [SCALE_SHIFT_CH] [RELU] [ADD_RESIDUAL] in that order");
+    if (d.reduce == HPCT_RED_AVGPOOL_HW && d.reduce_before_epi && d.n_epi)
+        return fail(HPCT_ERR_UNSUPPORTED, "AVGPOOL_HW runs after the epilogues");
+    const bool pool = d.reduce == HPCT_RED_AVGPOOL_HW;
+    const int need = 1 + (has[0] ? 2 : 0) + (has[2] ? 1 : 0);
+    if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "this chain takes %d inputs and 1 output (got %d, %d)", need, d.n_in, d.n_out);
+    const hpct_tensor_desc& X = d.in[0];
+    if (X.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "X must be 4-D NCHW");
+    const int64_t Nb = X.shape[0], C = X.shape[1], H = X.shape[2], W = X.shape[3];
+    int s = 1;
+    int s_scale = -1, s_shift = -1, s_res = -1;
+    if (has[0]) {
+        s_scale = s++; s_shift = s++;
+        REQUIRE_SHAPE(d.in[s_scale], "scale", C);
+        REQUIRE_SHAPE(d.in[s_shift], "shift", C);
+    }
+    if (has[2]) { s_res = s++; REQUIRE_SHAPE(d.in[s_res], "residual", Nb, C, H, W); }
+    if (pool) REQUIRE_SHAPE(d.out[0], "out[0]", Nb, C);
+    else REQUIRE_SHAPE(d.out[0], "out[0]", Nb, C, H, W);
+    for (int i = 0; i < d.n_in; ++i)
+        if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous NCHW layouts are supported", i);
+    if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous layouts are supported");
+    if (Nb * C > kI32Max || H * W > kI32Max || C > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "more than 2^31-1 planes or plane elements");
+    p.kind = Kind::Affine;
+    p.u.affine = AffineParams{nullptr, nullptr, nullptr, nullptr, nullptr, Nb * C, (int32_t)C, (int32_t)(H * W),
+                              has[0] ? 1 : 0, has[1] ? 1 : 0, has[2] ? 1 : 0, pool ? 1 : 0};
+    p.slot[0] = 0; p.slot[1] = s_scale; p.slot[2] = s_shift; p.slot[3] = s_res;
+    p.shape = affine_shape(Nb * C, (int32_t)(H * W), pool);
+    return HPCT_OK;
+}
+
+hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
+    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_RELU};
+    bool has[2];
+    if (!parse_epi(d, allowed, 2, has)) return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: epilogues must be [BIAS_COL] [RELU] in that order");
+    if (d.reduce != HPCT_RED_NONE) return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: no reduction is supported after it");
+    const int need = 2 + (has[0] ? 1 : 0);
+    if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "conv chain takes %d inputs and 1 output (got %d, %d)", need, d.n_in, d.n_out);
+    const hpct_tensor_desc &I = d.in[0], &Wt = d.in[1];
+    if (I.ndim != 4 || Wt.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "conv operands must be 4-D: in[N,C,H,W], wt[K,C,R,S]");
+    const int64_t Nb = I.shape[0], C = I.shape[1], H = I.shape[2], W = I.shape[3];
+    const int64_t K = Wt.shape[0], R = Wt.shape[2], S = Wt.shape[3];
+    if (Wt.shape[1] != C) return fail(HPCT_ERR_SHAPE_MISMATCH, "wt.shape[1] = %lld does not match the input channels %lld", (long long)Wt.shape[1], (long long)C);
+    if (d.stride_hw[0] < 1 || d.stride_hw[1] < 1 || d.pad_hw[0] < 0 || d.pad_hw[1] < 0)
+        return fail(HPCT_ERR_BAD_DESC, "conv: stride must be >= 1 and padding >= 0");
+    if (H + 2 * d.pad_hw[0] < R || W + 2 * d.pad_hw[1] < S) return fail(HPCT_ERR_SHAPE_MISMATCH, "conv: filter larger than the padded input");
+    const int64_t Ho = (H + 2 * d.pad_hw[0] - R) / d.stride_hw[0] + 1, Wo = (W + 2 * d.pad_hw[1] - S) / d.stride_hw[1] + 1;
+    if (has[0]) REQUIRE_SHAPE(d.in[2], "bias", K);
+    REQUIRE_SHAPE(d.out[0], "out[0]", Nb, K, Ho, Wo);
+    for (int i = 0; i < d.n_in; ++i)
+        if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous NCHW / KCRS layouts are supported", i);
+    if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous NCHW layouts are supported");
+    if (Nb * C * H * W > kI32Max || Nb * K * Ho * Wo > kI32Max || K * C * R * S > kI32Max)
+        return fail(HPCT_ERR_UNSUPPORTED, "conv: operand larger than 2^31-1 elements");
+    const char* why = "";
+    if (!conv_supported((int32_t)C, (int32_t)H, (int32_t)W, (int32_t)K, (int32_t)R, (int32_t)S, d.stride_hw[0], d.stride_hw[1],
+                        d.pad_hw[0], d.pad_hw[1], &why))
+        return fail(HPCT_ERR_UNSUPPORTED, "conv: %s", why);
+    p.kind = Kind::Conv;
+    p.u.conv = ConvParams{nullptr, nullptr, nullptr, nullptr, (int32_t)Nb, (int32_t)C, (int32_t)H, (int32_t)W,
+                          (int32_t)K, (int32_t)R, (int32_t)S, d.pad_hw[0], has[1] ? 1 : 0};
+    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has[0] ? 2 : -1; p.slot[3] = -1;
+    p.shape = conv_shape(p.u.conv);
+    return HPCT_OK;
+}
+
+hpct_status plan_attn(const hpct_op_desc& d, hpct_plan& p) {
+    float scale = 1.0f;
+    if (d.n_epi == 1 && d.epi[0] == HPCT_EPI_SCALE_CONST) scale = d.scale;
+    else if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "BGEMM_SOFTMAX_BGEMM: the only epilogue supported is SCALE_CONST (on the scores)");
+    if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_SOFTMAX_LAST)
+        return fail(HPCT_ERR_UNSUPPORTED, "BGEMM_SOFTMAX_BGEMM: reduction must be NONE or SOFTMAX_LAST (the softmax is part of the anchor)");
+    if (d.n_in != 3 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "BGEMM_SOFTMAX_BGEMM takes Q, K, V and 1 output");
+    const hpct_tensor_desc &Q = d.in[0], &K = d.in[1], &V = d.in[2];
+    if (Q.ndim != 3 || K.ndim != 3 || V.ndim != 3) return fail(HPCT_ERR_SHAPE_MISMATCH, "Q, K, V must be 3-D: [B,L,D]");
+    const int64_t B = Q.shape[0], L = Q.shape[1], D = Q.shape[2], Lk = K.shape[1];
+    REQUIRE_SHAPE(K, "K", B, Lk, D);
+    REQUIRE_SHAPE(V, "V", B, Lk, D);
+    REQUIRE_SHAPE(d.out[0], "out[0]", B, L, D);
+    for (int i = 0; i < 3; ++i)
+        if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous [B,L,D] layouts are supported", i);
+    if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous layouts are supported");
+    if (B * L * D > kI32Max || B * Lk * D > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "attention: operand larger than 2^31-1 elements");
+    const char* why = "";
+    if (!attn_supported((int32_t)D, &why)) return fail(HPCT_ERR_UNSUPPORTED, "attention: %s", why);
+    if (!(scale == scale) || scale - scale != 0.f) return fail(HPCT_ERR_BAD_DESC, "attention: scale must be finite");
+    p.kind = Kind::Attn;
+    p.u.attn = AttnParams{nullptr, nullptr, nullptr, nullptr, (int32_t)B, (int32_t)L, (int32_t)Lk, (int32_t)D, scale};
+    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = 2; p.slot[3] = -1;
+    p.shape = attn_shape(p.u.attn);
+    return HPCT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
+    clear_err();
+    if (out) *out = nullptr;
+    if (!desc || !out) return fail(HPCT_ERR_NULL, "hpct_plan_create: desc and out must not be NULL");
+    const hpct_op_desc& d = *desc;
+    if (d.n_epi < 0 || d.n_epi > HPCT_MAX_EPI) return fail(HPCT_ERR_BAD_DESC, "n_epi = %d outside 0..%d", d.n_epi, HPCT_MAX_EPI);
+    if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
+    if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
+    if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONV2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_AVGPOOL_HW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    for (int e = 0; e < d.n_epi; ++e)
+        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_SCALE_CONST) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
+
+    hpct_plan tmp;
+    std::memset(&tmp, 0, sizeof tmp);
+    tmp.n_in = d.n_in;
+    tmp.n_out = d.n_out;
+    int64_t cnt;
+    for (int i = 0; i < d.n_in; ++i) {
+        hpct_status st = check_tensor(d.in[i], "in", i, &cnt, &tmp.in_bytes[i]);
+        if (st != HPCT_OK) return st;
+    }
+    for (int i = 0; i < d.n_out; ++i) {
+        hpct_status st = check_tensor(d.out[i], "out", i, &cnt, &tmp.out_bytes[i]);
+        if (st != HPCT_OK) return st;
+        for (int k = 0; k < d.out[i].ndim; ++k)
+            if (d.out[i].stride[k] == 0 && d.out[i].shape[k] > 1)
+                return fail(HPCT_ERR_BAD_DESC, "out[%d]: stride 0 on a dimension of extent > 1 makes output elements overlap", i);
+    }
+
+    hpct_status st;
+    switch (d.anchor) {
+        case HPCT_ANCHOR_GEMM: st = plan_gemm(d, tmp); break;
+        case HPCT_ANCHOR_CONV2D_NCHW: st = plan_conv(d, tmp); break;
+        case HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM: st = plan_attn(d, tmp); break;
+        default:
+            if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
+            else st = plan_affine(d, tmp);
+    }
+    if (st != HPCT_OK) return st;
+    hpct_plan* p = new (std::nothrow) hpct_plan(tmp);
+    if (!p) return fail(HPCT_ERR_BAD_DESC, "out of host memory");
+    *out = p;
+    return HPCT_OK;
+}
+
+size_t hpct_plan_workspace_bytes(const hpct_plan*) { return 0; }
+
+hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, void* const* out_ptrs, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+    clear_err();
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!plan || !in_ptrs || !out_ptrs) return fail(HPCT_ERR_NULL, "hpct_plan_launch: plan, in_ptrs and out_ptrs must not be NULL");
+    for (int i = 0; i < plan->n_in; ++i) {
+        if (!in_ptrs[i]) return fail(HPCT_ERR_NULL, "in_ptrs[%d] is NULL", i);
+        if ((uintptr_t)in_ptrs[i] & 15) return fail(HPCT_ERR_ALIGNMENT, "in_ptrs[%d] is not 16-byte aligned", i);
+    }
+    for (int i = 0; i < plan->n_out; ++i) {
+        if (!out_ptrs[i]) return fail(HPCT_ERR_NULL, "out_ptrs[%d] is NULL", i);
+        if ((uintptr_t)out_ptrs[i] & 15) return fail(HPCT_ERR_ALIGNMENT, "out_ptrs[%d] is not 16-byte aligned", i);
+        const uintptr_t o0 = (uintptr_t)out_ptrs[i], o1 = o0 + (uintptr_t)plan->out_bytes[i];
+        for (int k = 0; k < plan->n_in; ++k) {
+            const uintptr_t a0 = (uintptr_t)in_ptrs[k], a1 = a0 + (uintptr_t)plan->in_bytes[k];
+            if (o0 < a1 && a0 < o1) return fail(HPCT_ERR_BAD_DESC, "out_ptrs[%d] overlaps in_ptrs[%d]", i, k);
+        }
+    }
+    hipStream_t stream = (hipStream_t)hip_stream;
+    auto in = [&](int s) -> const float* { return plan->slot[s] < 0 ? nullptr : (const float*)in_ptrs[plan->slot[s]]; };
+    hipError_t e = hipSuccess;
+    switch (plan->kind) {
+        case Kind::Gemm: {
+            GemmParams q = plan->u.gemm;
+            q.X = in(0); q.W = in(1); q.bias = in(2); q.Y = (float*)out_ptrs[0];
+            e = gemm_launch(q, stream);
+            break;
+        }
+        case Kind::Affine: {
+            AffineParams q = plan->u.affine;
+            q.X = in(0); q.scale = in(1); q.shift = in(2); q.R = in(3); q.out = (float*)out_ptrs[0];
+            e = affine_launch(q, stream);
+            break;
+        }
+        case Kind::Layernorm: {
+            LayernormParams q = plan->u.ln;
+            q.X = in(0); q.gamma = in(1); q.beta = in(2); q.Y = (float*)out_ptrs[0];
+            e = layernorm_launch(q, stream);
+            break;
+        }
+        case Kind::Softmax: {
+            SoftmaxParams q = plan->u.sm;
+            q.X = in(0); q.Y = (float*)out_ptrs[0];
+            e = softmax_launch(q, stream);
+            break;
+        }
+        case Kind::Conv: {
+            ConvParams q = plan->u.conv;
+            q.in = in(0); q.wt = in(1); q.bias = in(2); q.out = (float*)out_ptrs[0];
+            e = conv_launch(q, stream);
+            break;
+        }
+        case Kind::Attn: {
+            AttnParams q = plan->u.attn;
+            q.Q = in(0); q.K = in(1); q.V = in(2); q.O = (float*)out_ptrs[0];
+            e = attn_launch(q, stream);
+            break;
+        }
+    }
+    if (e != hipSuccess) return fail(HPCT_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return HPCT_OK;
+}
+
+void hpct_plan_destroy(hpct_plan* plan) { delete plan; }
+
+const char* hpct_plan_kernel_name(const hpct_plan* plan) { return plan ? plan->shape.kernel : ""; }
+
+hpct_status hpct_plan_launch_shape(const hpct_plan* plan, uint32_t grid[3], uint32_t block[3], uint32_t* lds_bytes) {
+    clear_err();
+    if (!plan) return fail(HPCT_ERR_NULL, "hpct_plan_launch_shape: plan must not be NULL");
+    for (int i = 0; i < 3; ++i) {
+        if (grid) grid[i] = plan->shape.grid[i];
+        if (block) block[i] = plan->shape.block[i];
+    }
+    if (lds_bytes) *lds_bytes = plan->shape.lds_bytes;
+    return HPCT_OK;
+}
+
+const char* hpct_last_error(void) { return g_err; }
+
+const char* hpct_version(void) { return "hpct 0.1 (gfx950)"; }
+
+}  // extern "C"

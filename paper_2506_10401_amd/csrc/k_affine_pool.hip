@@ -1,0 +1,138 @@
+// Per-channel affine, ReLU and residual add over the planes of an NCHW tensor
+// (Elementwise class of the paper's Table 1), followed either by a global
+// average pool over each H*W plane (Reduction class, "mean") or by a plain
+// store of the full tensor.  Memory-bound: both inputs are read once with
+// 128-bit loads; with the pool the intermediate never leaves registers.
+#include "kernels.hpp"
+#include "prim.hpp"
+
+namespace hpct {
+namespace {
+
+constexpr int kUnroll = 4;  // independent 16-byte loads per input in flight per thread
+
+template <bool AFF, bool RELU, bool RES>
+__device__ __forceinline__ float4v chain(float4v x, float4v r, float sc, float sh) {
+    float4v t = x;
+    if (AFF) t = t * sc + sh;
+    if (RELU) { t.x = fmaxf(t.x, 0.f); t.y = fmaxf(t.y, 0.f); t.z = fmaxf(t.z, 0.f); t.w = fmaxf(t.w, 0.f); }
+    if (RES) t = t + r;
+    return t;
+}
+
+// One work-group per plane p = n*C + c.  HW % 4 == 0, so every plane starts on
+// a 16-byte boundary.  Thread t takes vectors t, t+256, ...; kUnroll of them
+// are loaded before any is used.  The plane sum is accumulated per thread in a
+// fixed order, reduced over the wave on DPP and over the four waves through
+// LDS, so the result does not vary from run to run.
+template <bool AFF, bool RELU, bool RES, bool POOL>
+__global__ __launch_bounds__(256) void affine_planes_vec(const float* __restrict__ X, const float* __restrict__ scale,
+                                                         const float* __restrict__ shift, const float* __restrict__ R,
+                                                         float* __restrict__ out, int C, int HW) {
+    __shared__ float slots[16];
+    const int64_t p = blockIdx.x;
+    const int c = (int)(p % C);
+    const float sc = AFF ? scale[c] : 1.f, sh = AFF ? shift[c] : 0.f;
+    const float* x = X + p * (int64_t)HW;
+    const float* r = RES ? R + p * (int64_t)HW : nullptr;
+    float* o = POOL ? nullptr : out + p * (int64_t)HW;
+    const int nv = HW >> 2;
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+    for (int base = 0; base < nv; base += 256 * kUnroll) {
+        float4v xv[kUnroll], rv[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = base + u * 256 + threadIdx.x;
+            const bool ok = j < nv;
+            xv[u] = ok ? load4_nt(x + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+            if (RES) rv[u] = ok ? load4_nt(r + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int j = base + u * 256 + threadIdx.x;
+            if (j < nv) {
+                float4v t = chain<AFF, RELU, RES>(xv[u], rv[u], sc, sh);
+                if (POOL) acc = acc + t; else store4_nt(o + 4 * j, t);
+            }
+        }
+    }
+    if (POOL) {
+        float s = block_reduce<OpSum, 4>((acc.x + acc.y) + (acc.z + acc.w), slots);
+        if (threadIdx.x == 0) out[p] = s / (float)HW;
+    }
+}
+
+// Any HW (planes need not be 16-byte aligned): one element per thread per step.
+template <bool POOL>
+__global__ __launch_bounds__(256) void affine_planes_any(const float* __restrict__ X, const float* __restrict__ scale,
+                                                         const float* __restrict__ shift, const float* __restrict__ R,
+                                                         float* __restrict__ out, int C, int HW, int aff, int relu,
+                                                         int res) {
+    __shared__ float slots[16];
+    const int64_t p = blockIdx.x;
+    const int c = (int)(p % C);
+    const float sc = aff ? scale[c] : 1.f, sh = aff ? shift[c] : 0.f;
+    const float* x = X + p * (int64_t)HW;
+    float acc = 0.f;
+    for (int j = threadIdx.x; j < HW; j += 256) {
+        float t = x[j];
+        if (aff) t = t * sc + sh;
+        if (relu) t = fmaxf(t, 0.f);
+        if (res) t += R[p * (int64_t)HW + j];
+        if (POOL) acc += t; else out[p * (int64_t)HW + j] = t;
+    }
+    if (POOL) {
+        float s = block_reduce<OpSum, 4>(acc, slots);
+        if (threadIdx.x == 0) out[p] = s / (float)HW;
+    }
+}
+
+template <bool AFF, bool RELU, bool RES>
+hipError_t launch_vec(const AffineParams& p, hipStream_t stream) {
+    dim3 grid((unsigned)p.planes), block(256);
+    if (p.pool)
+        hipLaunchKernelGGL((affine_planes_vec<AFF, RELU, RES, true>), grid, block, 0, stream, p.X, p.scale, p.shift, p.R,
+                           p.out, p.C, p.HW);
+    else
+        hipLaunchKernelGGL((affine_planes_vec<AFF, RELU, RES, false>), grid, block, 0, stream, p.X, p.scale, p.shift, p.R,
+                           p.out, p.C, p.HW);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool) {
+    LaunchShape s{};
+    s.grid[0] = (uint32_t)planes; s.grid[1] = s.grid[2] = 1;
+    s.block[0] = 256; s.block[1] = s.block[2] = 1;
+    s.lds_bytes = 64;
+    if (HW % 4 == 0) s.kernel = pool ? "affine_planes_vec<pool>" : "affine_planes_vec<store>";
+    else s.kernel = pool ? "affine_planes_any<pool>" : "affine_planes_any<store>";
+    return s;
+}
+
+hipError_t affine_launch(const AffineParams& p, hipStream_t stream) {
+    if (p.HW % 4 == 0) {
+        const int key = (p.has_affine ? 4 : 0) | (p.relu ? 2 : 0) | (p.has_residual ? 1 : 0);
+        switch (key) {
+            case 0: return launch_vec<false, false, false>(p, stream);
+            case 1: return launch_vec<false, false, true>(p, stream);
+            case 2: return launch_vec<false, true, false>(p, stream);
+            case 3: return launch_vec<false, true, true>(p, stream);
+            case 4: return launch_vec<true, false, false>(p, stream);
+            case 5: return launch_vec<true, false, true>(p, stream);
+            case 6: return launch_vec<true, true, false>(p, stream);
+            default: return launch_vec<true, true, true>(p, stream);
+        }
+    }
+    dim3 grid((unsigned)p.planes), block(256);
+    if (p.pool)
+        hipLaunchKernelGGL(affine_planes_any<true>, grid, block, 0, stream, p.X, p.scale, p.shift, p.R, p.out, p.C, p.HW,
+                           p.has_affine, p.relu, p.has_residual);
+    else
+        hipLaunchKernelGGL(affine_planes_any<false>, grid, block, 0, stream, p.X, p.scale, p.shift, p.R, p.out, p.C, p.HW,
+                           p.has_affine, p.relu, p.has_residual);
+    return hipGetLastError();
+}
+
+}  // namespace hpct

@@ -1,0 +1,241 @@
+// Batched GEMM - softmax - GEMM, O = softmax_j(scale * Q K^T) V, head dim 64
+// (Table 1 of the paper: ComputeIntensive "matmul", Reduction "softmax").  The
+// score matrix is never materialised: K/V are streamed in blocks of 64 keys
+// through LDS (double buffered) and the softmax is evaluated online (running
+// max m, running sum l, rescaled accumulator).
+//
+// Both contractions run transposed on v_mfma_f32_32x32x2_f32 so that a lane
+// owns one query:
+//     S^T[key, query] = sum_d K[key, d] Q[query, d]      A = K block, B = Q^T
+//     O^T[d,   query] = sum_key V[key, d] P^T[key, query] A = V^T,    B = P^T
+// In the 32x32 accumulator layout lane l holds column (query) l%32 and rows
+// (keys) 8*(r/4) + 4*(l/32) + r%4, r = 0..15.  That is exactly the B-operand
+// layout of a 2-deep MFMA step if step r contracts keys {8*(r/4)+r%4,
+// 8*(r/4)+4+r%4}: the probabilities feed the second contraction straight from
+// the accumulator registers, with the V fragment rows permuted to match.
+// Row max needs one exchange between the two lane halves per key block; row
+// sums stay per-half until the end.
+//
+// A wave owns 32 queries.  With KS = 2 the work-group has two wave groups that
+// take alternate 32-key halves of every staged block for the same queries and
+// merge their (m, l, O) states through LDS at the end, which puts two waves on
+// every SIMD so one wave's softmax overlaps the other's MFMAs.
+#include "kernels.hpp"
+#include "prim.hpp"
+
+namespace hpct {
+namespace {
+
+constexpr int D = 64;
+constexpr int KB = 64;        // keys per staged block
+constexpr int QW = 32;        // queries per wave
+constexpr int QT = 4 * QW;    // queries per work-group
+constexpr int KLD = D + 4;    // K row stride in LDS: conflict-free 128-bit fragment reads
+constexpr int VLD = D + 8;    // V row stride: rows 4 apart land 32 banks apart
+constexpr float kNegBig = -1.0e30f;
+
+__device__ __forceinline__ float xchg_half(float v) {  // value held by lane ^ 32
+    return __shfl_xor(v, 32, 64);
+}
+
+template <int KS>
+__global__ __launch_bounds__(256 * KS) void attn_fwd_d64(const float* __restrict__ Q, const float* __restrict__ K,
+                                                         const float* __restrict__ V, float* __restrict__ O, int Lq,
+                                                         int Lk, float scale_log2e) {
+    constexpr int NT = 256 * KS;
+    constexpr int SUB = 2 / KS;                 // 32-key sub-blocks per wave per staged block
+    constexpr int LD4 = KB * D / 4 / NT;        // float4 per thread per matrix per block
+    extern __shared__ __align__(16) float lds[];
+    float* const Ks = lds;                      // [2][KB*KLD]
+    float* const Vs = lds + 2 * KB * KLD;       // [2][KB*VLD]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int qwave = wave & 3, kgrp = wave >> 2;
+    const int b = blockIdx.y;
+    const int q0 = blockIdx.x * QT + qwave * QW;
+    const float* Kb = K + (int64_t)b * Lk * D;
+    const float* Vb = V + (int64_t)b * Lk * D;
+
+    // Q fragment, pre-multiplied by scale*log2(e): lane (query l32, half) holds
+    // Q[q][8c + 4*half + t] in qf[c][t].
+    float4v qf[8];
+    {
+        const int q = q0 + l32;
+        const float* src = Q + ((int64_t)b * Lq + (q < Lq ? q : 0)) * D + 4 * half;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float4v t = load4(src + 8 * c);
+            qf[c] = (q < Lq) ? t * scale_log2e : float4v{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
+    float4v kreg[LD4], vreg[LD4];
+    auto fetch = [&](int key0) {
+#pragma unroll
+        for (int i = 0; i < LD4; ++i) {
+            const int v = tid + i * NT;
+            const int key = key0 + v / (D / 4), d = (v % (D / 4)) * 4;
+            const bool ok = key < Lk;
+            kreg[i] = ok ? load4(Kb + (int64_t)key * D + d) : float4v{0.f, 0.f, 0.f, 0.f};
+            vreg[i] = ok ? load4(Vb + (int64_t)key * D + d) : float4v{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LD4; ++i) {
+            const int v = tid + i * NT;
+            const int kr = v / (D / 4), d = (v % (D / 4)) * 4;
+            *reinterpret_cast<float4v*>(Ks + buf * KB * KLD + kr * KLD + d) = kreg[i];
+            *reinterpret_cast<float4v*>(Vs + buf * KB * VLD + kr * VLD + d) = vreg[i];
+        }
+    };
+
+    float16v o0, o1;  // O^T rows d = 0..31 and 32..63, column = this lane's query
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { o0[i] = 0.f; o1[i] = 0.f; }
+    float m = kNegBig;   // running max (log2 domain), same in both lane halves
+    float lsum = 0.f;    // running sum over this lane half's keys only
+
+    const int nblocks = (Lk + KB - 1) / KB;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int t = 0; t < nblocks; ++t) {
+        const int cur = t & 1;
+        if (t + 1 < nblocks) fetch((t + 1) * KB);
+        const float* Kc = Ks + cur * KB * KLD;
+        const float* Vc = Vs + cur * KB * VLD;
+
+        // ---- scores of this wave's sub-blocks: S^T = K Q^T -------------------
+        float16v s[SUB];
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[u][i] = 0.f;
+            const int kb = (KS == 2 ? kgrp : u) * 32;
+            const float* krow = Kc + (kb + l32) * KLD + 4 * half;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const float4v kf = *reinterpret_cast<const float4v*>(krow + 8 * c);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) s[u] = mfma_32x32x2(kf[j], qf[c][j], s[u]);
+            }
+        }
+        // ---- mask keys past the end, block max ---------------------------------
+        float bm = kNegBig;
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+            const int kb = t * KB + (KS == 2 ? kgrp : u) * 32;
+            if (kb + 32 > Lk) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (kb + 8 * (r >> 2) + 4 * half + (r & 3) >= Lk) s[u][r] = -INFINITY;
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) bm = fmaxf(bm, s[u][r]);
+        }
+        bm = fmaxf(bm, xchg_half(bm));
+        const float m_new = fmaxf(m, bm);
+        const float alpha = fast_exp2(m - m_new);
+        m = m_new;
+        float ps = 0.f;
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(s[u][r] - m_new);
+                s[u][r] = p;
+                ps += p;
+            }
+        }
+        lsum = lsum * alpha + ps;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { o0[i] *= alpha; o1[i] *= alpha; }
+        // ---- O^T += V^T P^T ---------------------------------------------------------
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+            const int kb = (KS == 2 ? kgrp : u) * 32;
+            const float* vbase = Vc + (kb + 4 * half) * VLD + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float* vr = vbase + (8 * (r >> 2) + (r & 3)) * VLD;
+                o0 = mfma_32x32x2(vr[0], s[u][r], o0);
+                o1 = mfma_32x32x2(vr[32], s[u][r], o1);
+            }
+        }
+        if (t + 1 < nblocks) stash(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- combine the two lane halves' sums, merge wave groups, normalise, store
+    lsum += xchg_half(lsum);
+    if (KS == 2) {
+        // group 1 publishes (o0, o1, m, l) as [qwave][34][64]; the loop's last
+        // barrier has retired every read of the stage buffers
+        float* mg = lds + qwave * 34 * 64;
+        if (kgrp == 1) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { mg[i * 64 + lane] = o0[i]; mg[(16 + i) * 64 + lane] = o1[i]; }
+            mg[32 * 64 + lane] = m;
+            mg[33 * 64 + lane] = lsum;
+        }
+        __syncthreads();
+        if (kgrp == 1) return;
+        const float m2 = mg[32 * 64 + lane], l2 = mg[33 * 64 + lane];
+        const float mm = fmaxf(m, m2);
+        const float a1 = fast_exp2(m - mm), a2 = fast_exp2(m2 - mm);
+        lsum = lsum * a1 + l2 * a2;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            o0[i] = o0[i] * a1 + mg[i * 64 + lane] * a2;
+            o1[i] = o1[i] * a1 + mg[(16 + i) * 64 + lane] * a2;
+        }
+    }
+    const int q = q0 + l32;
+    if (q < Lq) {
+        const float inv = 1.0f / lsum;
+        float* dst = O + ((int64_t)b * Lq + q) * D + 4 * half;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            store4(dst + 8 * g, float4v{o0[4 * g] * inv, o0[4 * g + 1] * inv, o0[4 * g + 2] * inv, o0[4 * g + 3] * inv});
+            store4(dst + 32 + 8 * g, float4v{o1[4 * g] * inv, o1[4 * g + 1] * inv, o1[4 * g + 2] * inv, o1[4 * g + 3] * inv});
+        }
+    }
+}
+
+constexpr int kKS = 2;
+constexpr size_t kLds = (size_t)(2 * KB * KLD + 2 * KB * VLD) * 4;
+static_assert(kLds >= 4 * 34 * 64 * 4, "merge area must fit in the stage buffers");
+
+}  // namespace
+
+bool attn_supported(int32_t d, const char** why) {
+    if (d != D) { *why = "only head dimension 64 is supported"; return false; }
+    return true;
+}
+
+LaunchShape attn_shape(const AttnParams& p) {
+    LaunchShape s{};
+    s.grid[0] = (uint32_t)((p.Lq + QT - 1) / QT); s.grid[1] = (uint32_t)p.B; s.grid[2] = 1;
+    s.block[0] = 256 * kKS; s.block[1] = s.block[2] = 1;
+    s.lds_bytes = (uint32_t)kLds;
+    s.kernel = "attn_fwd_d64<ks2>";
+    return s;
+}
+
+hipError_t attn_launch(const AttnParams& p, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_d64<kKS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((unsigned)((p.Lq + QT - 1) / QT), (unsigned)p.B), block(256 * kKS);
+    hipLaunchKernelGGL((attn_fwd_d64<kKS>), grid, block, kLds, stream, p.Q, p.K, p.V, p.O, p.Lq, p.Lk,
+                       p.scale * kLog2e);
+    return hipGetLastError();
+}
+
+}  // namespace hpct

@@ -1,0 +1,190 @@
+// Layer normalisation over the last dimension with an optional tanh-form GELU,
+// and a plain row softmax (Reduction and Elementwise classes of the paper's
+// Table 1).  Memory-bound: each row is read from HBM once with 128-bit loads,
+// held in registers for the two reduction passes and the epilogue, and written
+// once.
+#include "kernels.hpp"
+#include "prim.hpp"
+
+namespace hpct {
+namespace {
+
+constexpr int kMaxVec = 16;  // float4 per thread held in registers
+
+// One row per group of TPR threads (TPR = 64: a wave per row, four rows per
+// work-group, no LDS; TPR = 256: a work-group per row, LDS cross-wave combine).
+// Thread t of the group owns vectors t, t+TPR, ... (< N/4), so consecutive
+// lanes read consecutive 16-byte words.
+template <int TPR, int VPT, bool GELU>
+__global__ __launch_bounds__(256) void layernorm_rows_vec(const float* __restrict__ X, const float* __restrict__ gamma,
+                                                          const float* __restrict__ beta, float* __restrict__ Y,
+                                                          int64_t rows, int N, float eps) {
+    constexpr int RPB = 256 / TPR;
+    constexpr int NW = TPR / kWave;
+    __shared__ float slots[16];
+    const int t = threadIdx.x % TPR;
+    const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
+    const bool live = row < rows;
+    const int nv = N >> 2;
+    const float* x = X + (live ? row : 0) * (int64_t)N;
+
+    float4v v[VPT];
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int j = t + i * TPR;
+        v[i] = (live && j < nv) ? load4_nt(x + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    const float inv_n = 1.0f / (float)N;
+    const float mu = block_reduce<OpSum, NW>(s, slots) * inv_n;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int j = t + i * TPR;
+        float4v d = v[i] - mu;
+        if (j >= nv) d = float4v{0.f, 0.f, 0.f, 0.f};
+        v[i] = d;
+        q += (d.x * d.x + d.y * d.y) + (d.z * d.z + d.w * d.w);
+    }
+    const float var = block_reduce<OpSum, NW>(q, slots) * inv_n;
+    const float rstd = fast_rsq(var + eps);
+    if (!live) return;
+    float* y = Y + row * (int64_t)N;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int j = t + i * TPR;
+        if (j < nv) {
+            float4v g = gamma ? load4(gamma + 4 * j) : float4v{1.f, 1.f, 1.f, 1.f};
+            float4v b = beta ? load4(beta + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+            float4v o = v[i] * rstd * g + b;
+            if (GELU) { o.x = gelu_tanh(o.x); o.y = gelu_tanh(o.y); o.z = gelu_tanh(o.z); o.w = gelu_tanh(o.w); }
+            store4_nt(y + 4 * j, o);
+        }
+    }
+}
+
+// Any N: a work-group per row, three strided passes over the row (the second
+// and third are served by the caches for rows of moderate length).
+template <bool GELU>
+__global__ __launch_bounds__(256) void layernorm_rows_any(const float* __restrict__ X, const float* __restrict__ gamma,
+                                                          const float* __restrict__ beta, float* __restrict__ Y,
+                                                          int64_t rows, int N, float eps) {
+    __shared__ float slots[16];
+    const int64_t row = blockIdx.x;
+    const float* x = X + row * (int64_t)N;
+    float s = 0.f;
+    for (int j = threadIdx.x; j < N; j += 256) s += x[j];
+    const float mu = block_reduce<OpSum, 4>(s, slots) / (float)N;
+    float q = 0.f;
+    for (int j = threadIdx.x; j < N; j += 256) { float d = x[j] - mu; q += d * d; }
+    const float var = block_reduce<OpSum, 4>(q, slots) / (float)N;
+    const float rstd = fast_rsq(var + eps);
+    float* y = Y + row * (int64_t)N;
+    for (int j = threadIdx.x; j < N; j += 256) {
+        float o = (x[j] - mu) * rstd * (gamma ? gamma[j] : 1.f) + (beta ? beta[j] : 0.f);
+        y[j] = GELU ? gelu_tanh(o) : o;
+    }
+}
+
+// Row softmax, a work-group per row, any N.
+__global__ __launch_bounds__(256) void softmax_rows_any(const float* __restrict__ X, float* __restrict__ Y,
+                                                        int64_t rows, int N) {
+    __shared__ float slots[16];
+    const int64_t row = blockIdx.x;
+    const float* x = X + row * (int64_t)N;
+    float m = -INFINITY;
+    for (int j = threadIdx.x; j < N; j += 256) m = fmaxf(m, x[j]);
+    m = block_reduce<OpMax, 4>(m, slots);
+    float s = 0.f;
+    for (int j = threadIdx.x; j < N; j += 256) s += fast_exp2((x[j] - m) * kLog2e);
+    s = block_reduce<OpSum, 4>(s, slots);
+    const float inv = 1.0f / s;
+    float* y = Y + row * (int64_t)N;
+    for (int j = threadIdx.x; j < N; j += 256) y[j] = fast_exp2((x[j] - m) * kLog2e) * inv;
+}
+
+struct LnPick { int tpr; int vpt; };  // tpr = 0: the any-N kernel
+
+LnPick pick(int32_t N) {
+    if (N % 4 != 0) return {0, 0};
+    const int nv = N / 4;
+    if (nv <= 64 * 4) {  // a wave per row up to N = 1024
+        int vpt = (nv + 63) / 64;
+        return {64, vpt <= 1 ? 1 : (vpt <= 2 ? 2 : 4)};
+    }
+    if (nv <= 256 * kMaxVec) {
+        int vpt = (nv + 255) / 256;
+        return {256, vpt <= 2 ? 2 : (vpt <= 4 ? 4 : (vpt <= 8 ? 8 : 16))};
+    }
+    return {0, 0};
+}
+
+template <int TPR, int VPT>
+hipError_t launch_vec(const LayernormParams& p, hipStream_t stream) {
+    constexpr int RPB = 256 / TPR;
+    dim3 grid((unsigned)((p.rows + RPB - 1) / RPB)), block(256);
+    if (p.gelu)
+        hipLaunchKernelGGL((layernorm_rows_vec<TPR, VPT, true>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y,
+                           p.rows, p.N, p.eps);
+    else
+        hipLaunchKernelGGL((layernorm_rows_vec<TPR, VPT, false>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y,
+                           p.rows, p.N, p.eps);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+LaunchShape layernorm_shape(int64_t rows, int32_t N) {
+    const LnPick k = pick(N);
+    LaunchShape s{};
+    s.block[0] = 256; s.block[1] = s.block[2] = 1;
+    s.grid[1] = s.grid[2] = 1;
+    s.lds_bytes = 64;
+    if (k.tpr == 0) { s.grid[0] = (uint32_t)rows; s.kernel = "layernorm_rows_any"; }
+    else if (k.tpr == 64) { s.grid[0] = (uint32_t)((rows + 3) / 4); s.kernel = "layernorm_rows_vec<wave-per-row>"; }
+    else { s.grid[0] = (uint32_t)rows; s.kernel = "layernorm_rows_vec<group-per-row>"; }
+    return s;
+}
+
+hipError_t layernorm_launch(const LayernormParams& p, hipStream_t stream) {
+    const LnPick k = pick(p.N);
+    if (k.tpr == 64) {
+        switch (k.vpt) {
+            case 1: return launch_vec<64, 1>(p, stream);
+            case 2: return launch_vec<64, 2>(p, stream);
+            default: return launch_vec<64, 4>(p, stream);
+        }
+    }
+    if (k.tpr == 256) {
+        switch (k.vpt) {
+            case 2: return launch_vec<256, 2>(p, stream);
+            case 4: return launch_vec<256, 4>(p, stream);
+            case 8: return launch_vec<256, 8>(p, stream);
+            default: return launch_vec<256, 16>(p, stream);
+        }
+    }
+    dim3 grid((unsigned)p.rows), block(256);
+    if (p.gelu)
+        hipLaunchKernelGGL(layernorm_rows_any<true>, grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
+    else
+        hipLaunchKernelGGL(layernorm_rows_any<false>, grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
+    return hipGetLastError();
+}
+
+LaunchShape softmax_shape(int64_t rows, int32_t) {
+    LaunchShape s{};
+    s.grid[0] = (uint32_t)rows; s.grid[1] = s.grid[2] = 1;
+    s.block[0] = 256; s.block[1] = s.block[2] = 1;
+    s.lds_bytes = 64;
+    s.kernel = "softmax_rows_any";
+    return s;
+}
+
+hipError_t softmax_launch(const SoftmaxParams& p, hipStream_t stream) {
+    hipLaunchKernelGGL(softmax_rows_any, dim3((unsigned)p.rows), dim3(256), 0, stream, p.X, p.Y, p.rows, p.N);
+    return hipGetLastError();
+}
+
+}  // namespace hpct

@@ -1,0 +1,69 @@
+// Launch parameters and host-side launchers of the kernel families.  Each
+// launcher enqueues exactly one kernel on `stream` and returns the HIP status
+// of the launch.  Shapes have been validated by the caller (the plan layer);
+// launchers assert nothing beyond what they state here.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace hpct {
+
+struct LaunchShape {
+    uint32_t grid[3];
+    uint32_t block[3];
+    uint32_t lds_bytes;
+    const char* kernel;
+};
+
+// ---- layernorm over the last dim, optional tanh-GELU (Table 1: Reduction + Elementwise)
+struct LayernormParams {
+    const float* X; const float* gamma; const float* beta; float* Y;
+    int64_t rows; int32_t N; float eps; int32_t gelu;
+};
+LaunchShape layernorm_shape(int64_t rows, int32_t N);
+hipError_t layernorm_launch(const LayernormParams& p, hipStream_t stream);
+
+// ---- row softmax over the last dim (Table 1: Reduction)
+struct SoftmaxParams { const float* X; float* Y; int64_t rows; int32_t N; };
+LaunchShape softmax_shape(int64_t rows, int32_t N);
+hipError_t softmax_launch(const SoftmaxParams& p, hipStream_t stream);
+
+// ---- per-channel affine / relu / residual over NCHW planes, then either a
+//      global average pool (out = [planes]) or the full tensor (out = [planes*HW])
+struct AffineParams {
+    const float* X; const float* scale; const float* shift; const float* R; float* out;
+    int64_t planes; int32_t C; int32_t HW;
+    int32_t has_affine, relu, has_residual, pool;
+};
+LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool);
+hipError_t affine_launch(const AffineParams& p, hipStream_t stream);
+
+// ---- GEMM + bias + relu (+ row softmax when the tile spans the whole row)
+struct GemmParams {
+    const float* X; const float* W; const float* bias; float* Y;
+    int32_t M, K, N; int32_t relu, softmax;
+};
+constexpr int kGemmSoftmaxMaxN = 256;
+LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax);
+hipError_t gemm_launch(const GemmParams& p, hipStream_t stream);
+
+// ---- NCHW conv2d (stride 1, RxS in {1x1, 3x3}) + bias + relu
+struct ConvParams {
+    const float* in; const float* wt; const float* bias; float* out;
+    int32_t Nb, C, H, W, K, R, S, pad; int32_t relu;
+};
+bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h,
+                    int32_t stride_w, int32_t pad_h, int32_t pad_w, const char** why);
+LaunchShape conv_shape(const ConvParams& p);
+hipError_t conv_launch(const ConvParams& p, hipStream_t stream);
+
+// ---- batched softmax(scale * Q K^T) V
+struct AttnParams {
+    const float* Q; const float* K; const float* V; float* O;
+    int32_t B, Lq, Lk, D; float scale;
+};
+bool attn_supported(int32_t D, const char** why);
+LaunchShape attn_shape(const AttnParams& p);
+hipError_t attn_launch(const AttnParams& p, hipStream_t stream);
+
+}  // namespace hpct

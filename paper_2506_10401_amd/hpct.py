@@ -1,0 +1,245 @@
+"""ctypes binding of the C-ABI operator library (include/hpct.h).
+
+Argument marshalling only: every function here fills an op descriptor, creates
+(and caches) a plan and launches it; all arithmetic runs in the HIP kernels of
+libhpct.so.  PyTorch is used for device memory (`data_ptr()`) and for the
+current stream handle, nothing else.  There is no CPU fallback: if the library
+is missing and cannot be built, or no GPU is present at launch, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhpct.so")
+
+# ---- enums (mirror include/hpct.h) -------------------------------------------
+HPCT_OK, HPCT_ERR_NULL, HPCT_ERR_BAD_DESC, HPCT_ERR_SHAPE_MISMATCH, HPCT_ERR_ALIGNMENT, \
+    HPCT_ERR_UNSUPPORTED, HPCT_ERR_WORKSPACE, HPCT_ERR_HIP = range(8)
+STATUS_NAMES = ["HPCT_OK", "HPCT_ERR_NULL", "HPCT_ERR_BAD_DESC", "HPCT_ERR_SHAPE_MISMATCH", "HPCT_ERR_ALIGNMENT",
+                "HPCT_ERR_UNSUPPORTED", "HPCT_ERR_WORKSPACE", "HPCT_ERR_HIP"]
+HPCT_F32 = 0
+HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW = range(4)
+HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
+    HPCT_EPI_SCALE_CONST = range(6)
+HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW = range(4)
+HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("ndim", C.c_int32), ("shape", C.c_int64 * HPCT_MAX_DIMS), ("stride", C.c_int64 * HPCT_MAX_DIMS),
+                ("dtype", C.c_int)]
+
+
+class OpDesc(C.Structure):
+    _fields_ = [("anchor", C.c_int), ("n_epi", C.c_int32), ("epi", C.c_int * HPCT_MAX_EPI), ("reduce", C.c_int),
+                ("reduce_before_epi", C.c_int32), ("n_in", C.c_int32), ("in_", TensorDesc * HPCT_MAX_IN),
+                ("n_out", C.c_int32), ("out", TensorDesc * HPCT_MAX_OUT), ("stride_hw", C.c_int32 * 2),
+                ("pad_hw", C.c_int32 * 2), ("eps", C.c_float), ("scale", C.c_float)]
+
+
+class HpctError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("%s: %s" % (STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status, message))
+        self.status = status
+        self.message = message
+
+
+_lib = None
+
+
+def load(path: Optional[str] = None):
+    """Load libhpct.so (building it first if it has never been built)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build()
+    lib = C.CDLL(path)
+    vp = C.c_void_p
+    lib.hpct_plan_create.argtypes = [C.POINTER(OpDesc), C.POINTER(vp)]
+    lib.hpct_plan_create.restype = C.c_int
+    lib.hpct_plan_workspace_bytes.argtypes = [vp]
+    lib.hpct_plan_workspace_bytes.restype = C.c_size_t
+    lib.hpct_plan_launch.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t, vp]
+    lib.hpct_plan_launch.restype = C.c_int
+    lib.hpct_plan_destroy.argtypes = [vp]
+    lib.hpct_plan_destroy.restype = None
+    lib.hpct_plan_kernel_name.argtypes = [vp]
+    lib.hpct_plan_kernel_name.restype = C.c_char_p
+    lib.hpct_plan_launch_shape.argtypes = [vp, C.POINTER(C.c_uint32 * 3), C.POINTER(C.c_uint32 * 3), C.POINTER(C.c_uint32)]
+    lib.hpct_plan_launch_shape.restype = C.c_int
+    lib.hpct_last_error.argtypes = []
+    lib.hpct_last_error.restype = C.c_char_p
+    lib.hpct_version.argtypes = []
+    lib.hpct_version.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def hpct_version() -> str:
+    return load().hpct_version().decode()
+
+
+def hpct_last_error() -> str:
+    return load().hpct_last_error().decode()
+
+
+def tensor_desc(shape: Sequence[int], stride: Optional[Sequence[int]] = None, dtype: int = HPCT_F32) -> TensorDesc:
+    t = TensorDesc()
+    t.ndim = len(shape)
+    if stride is None:
+        stride, acc = [], 1
+        for s in reversed(shape):
+            stride.insert(0, acc)
+            acc *= s
+    for i, (s, st) in enumerate(zip(shape, stride)):
+        if i < HPCT_MAX_DIMS:
+            t.shape[i], t.stride[i] = s, st
+    t.dtype = dtype
+    return t
+
+
+def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before_epi=0, inputs=(), outputs=(),
+            stride_hw=(1, 1), pad_hw=(0, 0), eps=0.0, scale=1.0) -> OpDesc:
+    d = OpDesc()
+    d.anchor = anchor
+    d.n_epi = len(epi)
+    for i, e in enumerate(epi[:HPCT_MAX_EPI]):
+        d.epi[i] = e
+    d.reduce = reduce
+    d.reduce_before_epi = reduce_before_epi
+    d.n_in = len(inputs)
+    for i, t in enumerate(inputs[:HPCT_MAX_IN]):
+        d.in_[i] = t if isinstance(t, TensorDesc) else tensor_desc(t)
+    d.n_out = len(outputs)
+    for i, t in enumerate(outputs[:HPCT_MAX_OUT]):
+        d.out[i] = t if isinstance(t, TensorDesc) else tensor_desc(t)
+    d.stride_hw[0], d.stride_hw[1] = stride_hw
+    d.pad_hw[0], d.pad_hw[1] = pad_hw
+    d.eps = eps
+    d.scale = scale
+    return d
+
+
+class Plan:
+    """Owns one hpct_plan."""
+
+    def __init__(self, desc: OpDesc):
+        lib = load()
+        h = C.c_void_p()
+        st = lib.hpct_plan_create(C.byref(desc), C.byref(h))
+        if st != HPCT_OK:
+            raise HpctError(st, lib.hpct_last_error().decode())
+        self._h = h
+        self.n_in, self.n_out = desc.n_in, desc.n_out
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.hpct_plan_destroy(h)
+
+    @property
+    def kernel_name(self) -> str:
+        return load().hpct_plan_kernel_name(self._h).decode()
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(load().hpct_plan_workspace_bytes(self._h))
+
+    def launch_shape(self) -> Tuple[Tuple[int, ...], Tuple[int, ...], int]:
+        g, b, l = (C.c_uint32 * 3)(), (C.c_uint32 * 3)(), C.c_uint32()
+        st = load().hpct_plan_launch_shape(self._h, C.byref(g), C.byref(b), C.byref(l))
+        if st != HPCT_OK:
+            raise HpctError(st, hpct_last_error())
+        return tuple(g), tuple(b), int(l.value)
+
+    def launch_ptrs(self, in_ptrs: Sequence[int], out_ptrs: Sequence[int], stream: int = 0,
+                    workspace: int = 0, workspace_bytes: int = 0) -> None:
+        ins = (C.c_void_p * max(1, len(in_ptrs)))(*in_ptrs)
+        outs = (C.c_void_p * max(1, len(out_ptrs)))(*out_ptrs)
+        st = load().hpct_plan_launch(self._h, ins, outs, C.c_void_p(workspace), workspace_bytes, C.c_void_p(stream))
+        if st != HPCT_OK:
+            raise HpctError(st, hpct_last_error())
+
+    def launch(self, inputs, outputs, stream=None) -> None:
+        """inputs / outputs: torch tensors on the GPU (fp32, laid out as described)."""
+        import torch
+        for t in list(inputs) + list(outputs):
+            if not t.is_cuda or t.dtype != torch.float32:
+                raise HpctError(HPCT_ERR_BAD_DESC, "operands must be fp32 tensors in GPU memory")
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        self.launch_ptrs([t.data_ptr() for t in inputs], [t.data_ptr() for t in outputs], s)
+
+
+_plans: Dict[tuple, Plan] = {}
+
+
+def _cached(key: tuple, make) -> Plan:
+    p = _plans.get(key)
+    if p is None:
+        p = _plans[key] = Plan(make())
+    return p
+
+
+def _sh(t) -> Tuple[int, ...]:
+    return tuple(int(s) for s in t.shape)
+
+
+# ---- the five chains ---------------------------------------------------------
+def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, stream=None) -> None:
+    """out = softmax_rows(relu(X @ W + bias)); relu / softmax / bias optional."""
+    M, K = _sh(X)
+    N = _sh(W)[1]
+    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_RELU] if relu else [])
+    ins = [X, W] + ([bias] if bias is not None else [])
+    plan = _cached(("gemm", M, K, N, tuple(epi), softmax), lambda: op_desc(
+        HPCT_ANCHOR_GEMM, epi, HPCT_RED_SOFTMAX_LAST if softmax else HPCT_RED_NONE, 0,
+        [_sh(t) for t in ins], [_sh(out)]))
+    plan.launch(ins, [out], stream)
+
+
+def scale_shift_relu_add_pool(X, scale, shift, R, out, relu=True, pool=True, stream=None) -> None:
+    """out[n,c] = mean_hw(relu(X*scale[c]+shift[c]) + R)  (pool=False: the full tensor)."""
+    epi = ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + ([HPCT_EPI_RELU] if relu else []) + \
+          ([HPCT_EPI_ADD_RESIDUAL] if R is not None else [])
+    ins = [X] + ([scale, shift] if scale is not None else []) + ([R] if R is not None else [])
+    plan = _cached(("affine", _sh(X), tuple(epi), pool), lambda: op_desc(
+        HPCT_ANCHOR_NONE, epi, HPCT_RED_AVGPOOL_HW if pool else HPCT_RED_NONE, 0, [_sh(t) for t in ins], [_sh(out)]))
+    plan.launch(ins, [out], stream)
+
+
+def layernorm_gelu(X, gamma, beta, out, eps=1e-5, gelu=True, stream=None) -> None:
+    """out = gelu_tanh(layernorm(X) * gamma + beta)."""
+    ins = [X] + ([gamma, beta] if gamma is not None else [])
+    plan = _cached(("ln", _sh(X), gamma is not None, float(eps), gelu), lambda: op_desc(
+        HPCT_ANCHOR_NONE, [HPCT_EPI_GELU_TANH] if gelu else [], HPCT_RED_LAYERNORM_LAST, 1,
+        [_sh(t) for t in ins], [_sh(out)], eps=eps))
+    plan.launch(ins, [out], stream)
+
+
+def softmax_rows(X, out, stream=None) -> None:
+    plan = _cached(("softmax", _sh(X)), lambda: op_desc(HPCT_ANCHOR_NONE, [], HPCT_RED_SOFTMAX_LAST, 0, [_sh(X)], [_sh(out)]))
+    plan.launch([X], [out], stream)
+
+
+def conv2d_bias_relu(inp, wt, bias, out, stride=1, pad=1, relu=True, stream=None) -> None:
+    """out = relu(conv2d_nchw(inp, wt) + bias[k])."""
+    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_RELU] if relu else [])
+    ins = [inp, wt] + ([bias] if bias is not None else [])
+    plan = _cached(("conv", _sh(inp), _sh(wt), tuple(epi), stride, pad), lambda: op_desc(
+        HPCT_ANCHOR_CONV2D_NCHW, epi, HPCT_RED_NONE, 0, [_sh(t) for t in ins], [_sh(out)],
+        stride_hw=(stride, stride), pad_hw=(pad, pad)))
+    plan.launch(ins, [out], stream)
+
+
+def attention(Q, K, V, out, scale=0.125, stream=None) -> None:
+    """out = softmax(scale * Q K^T) V per batch."""
+    plan = _cached(("attn", _sh(Q), _sh(K), float(scale)), lambda: op_desc(
+        HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, [HPCT_EPI_SCALE_CONST], HPCT_RED_NONE, 0,
+        [_sh(Q), _sh(K), _sh(V)], [_sh(out)], scale=scale))
+    plan.launch([Q, K, V], [out], stream)

@@ -1,0 +1,251 @@
+"""The C-ABI library: loads, exports every symbol the header declares, and its
+host-side logic (descriptor validation, chain recognition, launch shapes,
+launch-time pointer checks) behaves as the header states.  No kernel is
+launched here, so this runs without a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2506_10401_amd import hpct as H
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "hpct.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hpct_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = H.load()
+    names = declared_functions()
+    assert {"hpct_plan_create", "hpct_plan_workspace_bytes", "hpct_plan_launch", "hpct_plan_destroy",
+            "hpct_last_error", "hpct_version"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert "gfx950" in H.hpct_version()
+
+
+def test_struct_sizes_match_the_c_layout():
+    # int32 + pad + 6*int64 + 6*int64 + enum + pad
+    assert C.sizeof(H.TensorDesc) == 112
+    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4
+
+
+def cfg_desc(i):
+    if i == 1:
+        return H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU], H.HPCT_RED_SOFTMAX_LAST, 0,
+                         [(64, 256), (256, 256), (256,)], [(64, 256)])
+    if i == 2:
+        return H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SCALE_SHIFT_CH, H.HPCT_EPI_RELU, H.HPCT_EPI_ADD_RESIDUAL],
+                         H.HPCT_RED_AVGPOOL_HW, 0, [(32, 64, 56, 56), (64,), (64,), (32, 64, 56, 56)], [(32, 64)])
+    if i == 3:
+        return H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_GELU_TANH], H.HPCT_RED_LAYERNORM_LAST, 1,
+                         [(8192, 4096), (4096,), (4096,)], [(8192, 4096)], eps=1e-5)
+    if i == 4:
+        return H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0,
+                         [(32, 64, 56, 56), (128, 64, 3, 3), (128,)], [(32, 128, 56, 56)], pad_hw=(1, 1))
+    return H.op_desc(H.HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, [H.HPCT_EPI_SCALE_CONST], H.HPCT_RED_NONE, 0,
+                     [(16, 2048, 64)] * 3, [(16, 2048, 64)], scale=0.125)
+
+
+def test_the_five_workloads_plan_and_launch_shapes():
+    want = {
+        1: ("gemm_rows16<256>", (4, 1, 1), (256, 1, 1)),
+        2: ("affine_planes_vec<pool>", (2048, 1, 1), (256, 1, 1)),
+        3: ("layernorm_rows_vec<group-per-row>", (8192, 1, 1), (256, 1, 1)),
+        4: ("conv2d_nchw_mfma<3x3>", (1568, 1, 1), (256, 1, 1)),
+        5: ("attn_fwd_d64<ks2>", (16, 16, 1), (512, 1, 1)),
+    }
+    for i in range(1, 6):
+        p = H.Plan(cfg_desc(i))
+        grid, block, lds = p.launch_shape()
+        assert (p.kernel_name, grid, block) == want[i]
+        assert lds <= 160 * 1024
+        assert p.workspace_bytes == 0
+    # shape/index logic that must be exact: tiles cover the outputs
+    g, b, _ = H.Plan(cfg_desc(4)).launch_shape()
+    assert g[0] == 32 * ((56 * 56 + 63) // 64) and g[1] == 1
+    g, b, _ = H.Plan(cfg_desc(5)).launch_shape()
+    assert g[0] * 128 >= 2048 and g[1] == 16
+
+
+def expect(status, desc):
+    with pytest.raises(H.HpctError) as e:
+        H.Plan(desc)
+    assert e.value.status == status, e.value
+    assert e.value.message  # an error text is always set
+    return e.value
+
+
+def test_null_arguments():
+    lib = H.load()
+    h = C.c_void_p()
+    assert lib.hpct_plan_create(None, C.byref(h)) == H.HPCT_ERR_NULL
+    assert lib.hpct_plan_create(C.byref(cfg_desc(1)), None) == H.HPCT_ERR_NULL
+    assert b"NULL" in lib.hpct_last_error()
+    assert lib.hpct_plan_workspace_bytes(None) == 0
+    assert lib.hpct_plan_kernel_name(None) == b""
+    assert lib.hpct_plan_launch_shape(None, None, None, None) == H.HPCT_ERR_NULL
+    lib.hpct_plan_destroy(None)
+    assert lib.hpct_plan_launch(None, None, None, None, 0, None) == H.HPCT_ERR_NULL
+
+
+def test_bad_descriptors():
+    d = cfg_desc(1); d.in_[0].ndim = 0
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.in_[0].ndim = 7
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.in_[1].shape[0] = 0
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.in_[1].shape[1] = -4
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.in_[0].stride[0] = -1
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.n_in = 0
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.n_in = 9
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.n_out = 3
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.n_epi = 9
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.anchor = 17
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.reduce = -1
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.epi[0] = 99
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.n_in = 2  # bias listed in the epilogues but not supplied
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    # overflow of the element count / the largest offset
+    big = 1 << 62
+    d = cfg_desc(3); d.in_[0] = H.tensor_desc((big, 4), (4, 1))
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(3); d.in_[0] = H.tensor_desc((8192, 4096), (big, 1))
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    # overlapping output elements
+    d = cfg_desc(3); d.out[0] = H.tensor_desc((8192, 4096), (0, 1))
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(3); d.eps = -1.0
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(4); d.stride_hw[0] = 0
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(4); d.pad_hw[1] = -1
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(5); d.scale = float("inf")
+    expect(H.HPCT_ERR_BAD_DESC, d)
+
+
+def test_shape_mismatches():
+    d = cfg_desc(1); d.in_[1] = H.tensor_desc((255, 256))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(1); d.in_[2] = H.tensor_desc((255,))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(1); d.out[0] = H.tensor_desc((256, 64))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(1); d.in_[0] = H.tensor_desc((64, 16, 16))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(2); d.in_[1] = H.tensor_desc((63,))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(2); d.in_[3] = H.tensor_desc((32, 64, 56, 55))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(2); d.out[0] = H.tensor_desc((64, 32))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(3); d.in_[1] = H.tensor_desc((8192,))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(4); d.in_[1] = H.tensor_desc((128, 63, 3, 3))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(4); d.out[0] = H.tensor_desc((32, 128, 54, 54))  # that would be pad 0
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(4); d.in_[0] = H.tensor_desc((1, 64, 2, 2)); d.pad_hw[0] = d.pad_hw[1] = 0
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)  # filter larger than the input
+    d = cfg_desc(5); d.in_[2] = H.tensor_desc((16, 2047, 64))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = cfg_desc(5); d.in_[1] = H.tensor_desc((15, 2048, 64)); d.in_[2] = H.tensor_desc((15, 2048, 64))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+
+
+def test_unsupported_but_well_formed():
+    d = cfg_desc(1); d.in_[0].dtype = 1
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(1); d.epi[0], d.epi[1] = H.HPCT_EPI_RELU, H.HPCT_EPI_BIAS_COL  # order not offered
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(1); d.reduce = H.HPCT_RED_AVGPOOL_HW
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    # fused softmax is limited to rows that fit one work-group tile
+    d = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_SOFTMAX_LAST, 0, [(64, 256), (256, 512)], [(64, 512)])
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    # non-contiguous layouts
+    d = cfg_desc(1); d.in_[1] = H.tensor_desc((256, 256), (1, 256))  # transposed W
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(3); d.in_[0] = H.tensor_desc((8192, 4096), (8192, 1))  # row pitch
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(3); d.reduce_before_epi = 0
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(4); d.stride_hw[0] = d.stride_hw[1] = 2
+    d.out[0] = H.tensor_desc((32, 128, 28, 28))
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(4); d.in_[1] = H.tensor_desc((128, 64, 5, 5)); d.pad_hw[0] = d.pad_hw[1] = 2
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(5); d.in_[0] = d.in_[1] = d.in_[2] = H.tensor_desc((16, 2048, 32)); d.out[0] = H.tensor_desc((16, 2048, 32))
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(5); d.epi[0] = H.HPCT_EPI_RELU
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    # index range of the kernels
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_LAYERNORM_LAST, 0, [(4, 1 << 32)], [(4, 1 << 32)])
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+
+
+def test_variants_of_the_chains_are_recognised():
+    ok = [
+        H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_NONE, 0, [(5, 7), (7, 1000)], [(5, 1000)]),
+        H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0, [(5, 7), (7, 9)], [(5, 9)]),
+        H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_SOFTMAX_LAST, 0, [(5, 7)], [(5, 7)]),
+        H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_LAYERNORM_LAST, 0, [(5, 7)], [(5, 7)], eps=1e-5),
+        H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_RELU], H.HPCT_RED_AVGPOOL_HW, 0, [(2, 3, 3, 5)], [(2, 3)]),
+        H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SCALE_SHIFT_CH, H.HPCT_EPI_ADD_RESIDUAL], H.HPCT_RED_NONE, 0,
+                  [(2, 3, 4, 5), (3,), (3,), (2, 3, 4, 5)], [(2, 3, 4, 5)]),
+        H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, [], H.HPCT_RED_NONE, 0, [(1, 3, 8, 8), (5, 3, 1, 1)], [(1, 5, 8, 8)]),
+        H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, [H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0, [(1, 3, 8, 8), (5, 3, 3, 3)],
+                  [(1, 5, 6, 6)]),
+        H.op_desc(H.HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, [], H.HPCT_RED_NONE, 0, [(2, 5, 64), (2, 9, 64), (2, 9, 64)],
+                  [(2, 5, 64)]),
+    ]
+    for d in ok:
+        p = H.Plan(d)
+        assert p.kernel_name
+    # odd sizes pick the unvectorised variants
+    assert "any" in H.Plan(ok[3]).kernel_name
+    assert "any" in H.Plan(ok[4]).kernel_name
+
+
+def test_launch_time_pointer_checks_return_before_any_launch():
+    p = H.Plan(cfg_desc(3))
+    nbytes = 8192 * 4096 * 4
+    base = 0x7F0000000000  # fake device addresses: every case below is rejected on the host
+    x, g, b, y = base, base + nbytes, base + nbytes + 16384, base + 2 * nbytes
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, 0, b], [y])
+    assert e.value.status == H.HPCT_ERR_NULL
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, g, b], [0])
+    assert e.value.status == H.HPCT_ERR_NULL
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x + 4, g, b], [y])
+    assert e.value.status == H.HPCT_ERR_ALIGNMENT
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, g, b], [y + 8])
+    assert e.value.status == H.HPCT_ERR_ALIGNMENT
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, g, b], [x])  # in place
+    assert e.value.status == H.HPCT_ERR_BAD_DESC
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, g, b], [x + nbytes - 16])  # output starts inside X's last row
+    assert e.value.status == H.HPCT_ERR_BAD_DESC
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, g, b], [g - nbytes + 16])  # output's tail reaches gamma
+    assert e.value.status == H.HPCT_ERR_BAD_DESC

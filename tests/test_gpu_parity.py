@@ -1,0 +1,251 @@
+"""Parity of the HIP kernels (called through the C ABI) with the CPU checker,
+element by element on the same seeded inputs.
+
+Acceptance rules (oracle/compare.py): elementwise / reduction outputs within
+1e-4 relative, floored at 1e-2 of the output's rms; fp32 contraction outputs
+within 2e-3 of sum |a||b|.  Shapes span several tiles and ragged tails, plus
+the five full-size workloads in the launch configuration the benchmark times.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import compare, ref  # noqa: E402
+from paper_2506_10401_amd import datagen, hpct  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU visible")
+    hpct.load()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def show(tag, v):
+    print("%s: %r" % (tag, v), flush=True)
+    return v
+
+
+# ------------------------------------------------------------------- chain 1
+def run_chain1(t, relu=True, softmax=True, bias=True):
+    X, W = dev(t["X"]), dev(t["W"])
+    b = dev(t["bias"]) if bias else None
+    out = torch.full((X.shape[0], W.shape[1]), float("nan"), device="cuda")
+    hpct.gemm_bias_relu_softmax(X, W, b, out, relu=relu, softmax=softmax)
+    return host(out)
+
+
+def test_chain1_full_size():
+    t = datagen.make(1)
+    got = run_chain1(t)
+    assert show("chain1 64x256x256 softmax", compare.pointwise(got, ref.chain1(t["X"], t["W"], t["bias"])))
+    # the anchor alone under the contraction rule
+    got = run_chain1(t, relu=False, softmax=False)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    assert show("chain1 anchor", compare.contraction(got, Z, Dn))
+    # and tighter: true fp32 accumulation is far inside the bound
+    assert np.max(np.abs(got - Z) / Dn) < 1e-5
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (17, 5, 10), (70, 100, 63), (16, 256, 200), (33, 36, 256),
+                                   (5, 33, 64), (40, 64, 128), (3, 300, 129)])
+def test_chain1_ragged_shapes(M, K, N):
+    print("chain1 M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    assert show("softmax", compare.pointwise(run_chain1(t), ref.chain1(t["X"], t["W"], t["bias"])))
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], None, want_norm=True)
+    assert show("anchor no bias", compare.contraction(run_chain1(t, relu=False, softmax=False, bias=False), Z, Dn))
+
+
+@pytest.mark.parametrize("M,K,N", [(50, 40, 300), (130, 260, 1000), (256, 64, 257)])
+def test_gemm_bias_relu_wide(M, K, N):
+    print("gemm M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    assert show("gemm+bias+relu", compare.contraction(run_chain1(t, softmax=False), ref.relu(Z), Dn))
+
+
+def test_gemm_identity_weight_is_exact():
+    X = datagen.gen_uniform(5, (48, 64), -1, 1)
+    out = torch.empty(48, 64, device="cuda")
+    hpct.gemm_bias_relu_softmax(dev(X), dev(np.eye(64, dtype=np.float32)), None, out, relu=False, softmax=False)
+    assert np.array_equal(host(out), X)
+
+
+# ------------------------------------------------------------------- chain 2
+def run_chain2(t, pool=True, relu=True, affine=True, residual=True):
+    X = dev(t["X"])
+    sc, sh = (dev(t["scale"]), dev(t["shift"])) if affine else (None, None)
+    R = dev(t["R"]) if residual else None
+    shape = X.shape[:2] if pool else X.shape
+    out = torch.full(tuple(shape), float("nan"), device="cuda")
+    hpct.scale_shift_relu_add_pool(X, sc, sh, R, out, relu=relu, pool=pool)
+    return host(out)
+
+
+def test_chain2_full_size():
+    t = datagen.make(2)
+    want = ref.chain2(t["X"], t["scale"], t["shift"], t["R"])
+    got = run_chain2(t)
+    assert show("chain2 32x64x56x56", compare.pointwise(got, want))
+    got2 = run_chain2(t)
+    assert np.array_equal(got.view(np.uint32), got2.view(np.uint32))  # fixed reduction order
+
+
+@pytest.mark.parametrize("N,C,H,W", [(1, 1, 1, 1), (2, 3, 1, 3), (3, 5, 7, 7), (2, 4, 2, 2), (1, 2, 40, 52),
+                                     (2, 3, 64, 65), (1, 2, 128, 128)])
+def test_chain2_ragged_shapes(N, C, H, W):
+    print("chain2 %s" % ((N, C, H, W),), flush=True)
+    t = datagen.make(2, N=N, C=C, H=H, W=W)
+    assert show("pool", compare.pointwise(run_chain2(t), ref.chain2(t["X"], t["scale"], t["shift"], t["R"])))
+    T = ref.affine_relu_residual(t["X"], t["scale"], t["shift"], t["R"])
+    assert show("store", compare.pointwise(run_chain2(t, pool=False), T))
+    # sub-chains
+    Xd = t["X"].astype(np.float64)
+    assert show("pool only", compare.pointwise(run_chain2(t, relu=False, affine=False, residual=False), ref.avgpool_hw(Xd)))
+    assert show("relu store", compare.pointwise(run_chain2(t, pool=False, affine=False, residual=False), ref.relu(Xd)))
+
+
+# ------------------------------------------------------------------- chain 3
+def run_chain3(t, gelu=True, affine=True, eps=1e-5):
+    X = dev(t["X"])
+    g, b = (dev(t["gamma"]), dev(t["beta"])) if affine else (None, None)
+    out = torch.full(tuple(X.shape), float("nan"), device="cuda")
+    hpct.layernorm_gelu(X, g, b, out, eps=eps, gelu=gelu)
+    return host(out)
+
+
+def test_chain3_full_size():
+    t = datagen.make(3)
+    want = ref.chain3(t["X"], t["gamma"], t["beta"], 1e-5)
+    got = run_chain3(t)
+    assert show("chain3 8192x4096", compare.pointwise(got, want))
+    got2 = run_chain3(t)
+    assert np.array_equal(got.view(np.uint32), got2.view(np.uint32))
+
+
+@pytest.mark.parametrize("M,N", [(1, 1), (3, 2), (5, 3), (7, 64), (9, 100), (33, 256), (6, 1000), (4, 1024),
+                                 (5, 1028), (3, 2048), (5, 4100), (2, 8192), (3, 16384), (2, 16388), (2, 20001)])
+def test_chain3_ragged_shapes(M, N):
+    print("chain3 M=%d N=%d" % (M, N), flush=True)
+    t = datagen.make(3, M=M, N=N)
+    want = ref.chain3(t["X"], t["gamma"], t["beta"], 1e-5)
+    if N == 1:  # x - mean = 0 exactly: output = gelu(beta)
+        want = ref.gelu_tanh(np.tile(t["beta"].astype(np.float64), (M, 1)))
+    assert show("ln+gelu", compare.pointwise(run_chain3(t), want))
+    if N > 1:
+        assert show("ln only, no affine", compare.pointwise(run_chain3(t, gelu=False, affine=False),
+                                                            ref.layernorm_rows(t["X"], None, None, 1e-5)))
+
+
+@pytest.mark.parametrize("M,N", [(1, 1), (5, 7), (3, 256), (4, 1000), (2, 5000)])
+def test_softmax_rows(M, N):
+    X = datagen.gen_normal(77, (M, N), 0.0, 3.0)
+    out = torch.full((M, N), float("nan"), device="cuda")
+    hpct.softmax_rows(dev(X), out)
+    assert show("softmax %dx%d" % (M, N), compare.pointwise(host(out), ref.softmax_rows(X.astype(np.float64))))
+
+
+# ------------------------------------------------------------------- chain 4
+def run_chain4(t, pad=1, relu=True, bias=True):
+    x, w = dev(t["in"]), dev(t["wt"])
+    b = dev(t["bias"]) if bias else None
+    Nb, _, H, W = t["in"].shape
+    K, _, R, S = t["wt"].shape
+    Ho, Wo = ref.conv_out_hw(H, W, R, S, 1, pad)
+    out = torch.full((Nb, K, Ho, Wo), float("nan"), device="cuda")
+    hpct.conv2d_bias_relu(x, w, b, out, stride=1, pad=pad, relu=relu)
+    return host(out)
+
+
+def test_chain4_full_size():
+    t = datagen.make(4)
+    want, Dn = ref.chain4(t["in"], t["wt"], t["bias"], 1, 1)
+    got = run_chain4(t)
+    assert show("chain4 conv3x3 32x64x56x56 -> 128", compare.contraction(got, want, Dn))
+    assert np.max(np.abs(got - want) / Dn) < 1e-5
+    got2 = run_chain4(t)
+    assert np.array_equal(got.view(np.uint32), got2.view(np.uint32))
+
+
+@pytest.mark.parametrize("N,C,H,W,K,R,pad", [
+    (1, 1, 1, 1, 1, 1, 0), (1, 2, 4, 4, 3, 3, 1), (2, 3, 7, 9, 5, 3, 1), (1, 8, 8, 8, 128, 3, 1),
+    (2, 10, 13, 5, 130, 3, 1), (1, 16, 12, 12, 64, 3, 0), (1, 4, 6, 70, 7, 3, 2), (3, 5, 9, 9, 20, 1, 0),
+    (1, 64, 14, 14, 256, 1, 0), (1, 12, 3, 3, 9, 3, 1), (1, 9, 30, 200, 33, 3, 1), (2, 6, 1, 1, 4, 3, 1)])
+def test_chain4_ragged_shapes(N, C, H, W, K, R, pad):
+    print("chain4 %s" % ((N, C, H, W, K, R, pad),), flush=True)
+    t = datagen.make(4, N=N, C=C, H=H, W=W, K=K, R=R, S=R)
+    want, Dn = ref.chain4(t["in"], t["wt"], t["bias"], 1, pad)
+    assert show("conv+bias+relu", compare.contraction(run_chain4(t, pad=pad), want, Dn))
+    raw, Dn0 = ref.conv2d_nchw_bias(t["in"], t["wt"], None, 1, pad, want_norm=True)
+    assert show("conv alone", compare.contraction(run_chain4(t, pad=pad, relu=False, bias=False), raw, Dn0))
+
+
+def test_conv_all_ones_counts_taps_exactly():
+    x = np.ones((1, 8, 10, 11), np.float32)
+    w = np.ones((4, 8, 3, 3), np.float32)
+    got = run_chain4({"in": x, "wt": w}, pad=1, relu=False, bias=False)
+    want = ref.conv2d_nchw_bias(x, w, None, 1, 1)
+    assert np.array_equal(got, want)  # small integers: exact in fp32
+
+
+# ------------------------------------------------------------------- chain 5
+def run_chain5(t, scale=0.125):
+    Q, K, V = dev(t["Q"]), dev(t["K"]), dev(t["V"])
+    out = torch.full(tuple(Q.shape), float("nan"), device="cuda")
+    hpct.attention(Q, K, V, out, scale=scale)
+    return host(out)
+
+
+def test_chain5_full_size():
+    t = datagen.make(5)
+    want, Dn = ref.chain5(t["Q"], t["K"], t["V"], 0.125)
+    got = run_chain5(t)
+    assert show("chain5 16x2048x64", compare.contraction(got, want, Dn))
+    assert np.max(np.abs(got - want) / Dn) < 1e-4
+    got2 = run_chain5(t)
+    assert np.array_equal(got.view(np.uint32), got2.view(np.uint32))
+
+
+@pytest.mark.parametrize("B,L,Lk", [(1, 1, 1), (2, 5, 3), (1, 32, 32), (3, 33, 31), (2, 100, 64), (1, 128, 65),
+                                    (2, 130, 97), (1, 200, 300), (1, 64, 1000)])
+def test_chain5_ragged_shapes(B, L, Lk):
+    print("chain5 B=%d L=%d Lk=%d" % (B, L, Lk), flush=True)
+    t = datagen.make(5, B=B, L=L, Lk=Lk)
+    for scale in (0.125, 1.0):
+        want, Dn = ref.chain5(t["Q"], t["K"], t["V"], scale)
+        assert show("scale %g" % scale, compare.contraction(run_chain5(t, scale), want, Dn))
+
+
+def test_attention_large_scores_do_not_overflow():
+    t = datagen.make(5, B=1, L=40, Lk=70)
+    t["Q"] = (t["Q"] * 30).astype(np.float32)  # scores of order +-2000: needs the running max
+    want, Dn = ref.chain5(t["Q"], t["K"], t["V"], 1.0)
+    got = run_chain5(t, 1.0)
+    assert np.all(np.isfinite(got))
+    assert show("peaked softmax", compare.contraction(got, want, Dn, tol=2e-3))
+
+
+# ------------------------------------------------------------------ launches
+def test_launch_on_a_side_stream():
+    t = datagen.make(3, M=64, N=512)
+    X, g, b = dev(t["X"]), dev(t["gamma"]), dev(t["beta"])
+    out = torch.full((64, 512), float("nan"), device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        hpct.layernorm_gelu(X, g, b, out)
+    s.synchronize()
+    assert compare.pointwise(out.cpu().numpy(), ref.chain3(t["X"], t["gamma"], t["beta"], 1e-5))
