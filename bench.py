@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-operator hot path on one MI355X.
+
+A step is one pass of the whole hot path: one launch of each of the five fused
+chains (GEMM+bias+ReLU+softmax, affine+ReLU+residual+avg-pool, layernorm+GELU,
+conv3x3+bias+ReLU, GEMM-softmax-GEMM) at full size on seeded synthetic inputs
+already resident in HBM.  The memory-bound chains rotate over buffer sets whose
+total exceeds the 256 MB last-level cache, so their reads come from HBM.
+
+Prints ONE JSON line.  `value` is the mean over the five operators of the
+achieved fraction of the MI355X peak that bounds each (HBM 8 TB/s for the
+memory-bound chains, 157.3 TFLOP/s fp32 MFMA for the contraction-anchored
+ones), in percent; `per_op` carries every operator's absolute GB/s or TFLOP/s.
+Per-kernel durations are measured inside the timed region with HIP events
+recorded on the launch stream around every launch.  `roofline` describes the
+kernel that takes the largest share of a step.  `cpu_baseline` is the CPU
+checker timed on this host (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_F32_PEAK_TFLOPS = 157.3
+LLC_BYTES = 256 << 20
+
+# algorithmic work per launch: inputs once, outputs once, fused intermediates never
+OPS = {
+    1: dict(name="gemm_bias_relu_softmax", bound="mfma", flop=2 * 64 * 256 * 256, bytes=(64 * 256 + 256 * 256 + 256 + 64 * 256) * 4),
+    2: dict(name="scale_shift_relu_add_avgpool", bound="hbm", flop=0, bytes=(2 * 32 * 64 * 56 * 56 + 2 * 64 + 32 * 64) * 4),
+    3: dict(name="layernorm_gelu", bound="hbm", flop=0, bytes=(2 * 8192 * 4096 + 2 * 4096) * 4),
+    4: dict(name="conv3x3_bias_relu", bound="mfma", flop=2 * 32 * 128 * 56 * 56 * 64 * 9,
+            bytes=(32 * 64 * 56 * 56 + 128 * 64 * 9 + 128 + 32 * 128 * 56 * 56) * 4),
+    5: dict(name="attention_qk_softmax_v", bound="mfma", flop=4 * 16 * 2048 * 2048 * 64, bytes=4 * 16 * 2048 * 64 * 4),
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU checker")
+    ap.add_argument("--only", type=int, default=0, help="run a single chain (1..5) instead of all five")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this operator library is a one-GPU hot path with no collectives; run it with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2506_10401_amd import datagen, hpct
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
+        return 2
+    hpct.load()
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()  # noqa: E731
+    which = [args.only] if args.only else [1, 2, 3, 4, 5]
+
+    # ---- inputs (seeded, host-generated, uploaded once) -----------------------
+    host = {i: datagen.make(i) for i in which}
+
+    def rotated(t, k):
+        # further buffer sets for cache-cold timing: same values, rolled, in distinct memory
+        return t if k == 0 else torch.roll(t.flatten(), 1001 * k).reshape(t.shape).contiguous()
+
+    sets = {}
+    if 1 in which:
+        h = host[1]
+        sets[1] = [dict(ins=[dev(h["X"]), dev(h["W"]), dev(h["bias"])], out=torch.empty(64, 256, device="cuda"))]
+    if 2 in which:
+        h = host[2]
+        X, R, sc, sh = dev(h["X"]), dev(h["R"]), dev(h["scale"]), dev(h["shift"])
+        n = LLC_BYTES * 2 // (2 * X.numel() * 4) + 1
+        sets[2] = [dict(ins=[rotated(X, k), sc, sh, rotated(R, k)], out=torch.empty(32, 64, device="cuda")) for k in range(n)]
+    if 3 in which:
+        h = host[3]
+        X, g, b = dev(h["X"]), dev(h["gamma"]), dev(h["beta"])
+        sets[3] = [dict(ins=[rotated(X, k), g, b], out=torch.empty(8192, 4096, device="cuda")) for k in range(3)]
+    if 4 in which:
+        h = host[4]
+        sets[4] = [dict(ins=[dev(h["in"]), dev(h["wt"]), dev(h["bias"])], out=torch.empty(32, 128, 56, 56, device="cuda"))]
+    if 5 in which:
+        h = host[5]
+        sets[5] = [dict(ins=[dev(h["Q"]), dev(h["K"]), dev(h["V"])], out=torch.empty(16, 2048, 64, device="cuda"))]
+
+    def launch(i, s):
+        a, o = s["ins"], s["out"]
+        if i == 1:
+            hpct.gemm_bias_relu_softmax(a[0], a[1], a[2], o)
+        elif i == 2:
+            hpct.scale_shift_relu_add_pool(a[0], a[1], a[2], a[3], o)
+        elif i == 3:
+            hpct.layernorm_gelu(a[0], a[1], a[2], o, eps=1e-5)
+        elif i == 4:
+            hpct.conv2d_bias_relu(a[0], a[1], a[2], o, stride=1, pad=1)
+        else:
+            hpct.attention(a[0], a[1], a[2], o, scale=0.125)
+
+    def step(k, ev=None):
+        for i in which:
+            s = sets[i][k % len(sets[i])]
+            if ev is not None:
+                e0, e1 = ev[i][k]
+                e0.record()
+                launch(i, s)
+                e1.record()
+            else:
+                launch(i, s)
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    ev = {i: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+          for i in which}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(k, ev)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    per_op, fracs = [], []
+    for i in which:
+        d = [a.elapsed_time(b) for a, b in ev[i]]  # ms
+        avg_us, min_us = 1e3 * sum(d) / len(d), 1e3 * min(d)
+        op = OPS[i]
+        if op["bound"] == "hbm":
+            ach, peak, unit = op["bytes"] / (avg_us * 1e-6) / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = op["flop"] / (avg_us * 1e-6) / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
+        fracs.append(ach / peak)
+        per_op.append(dict(config=i, op=op["name"], kernel=hpct._plans and None, bound=op["bound"], avg_us=round(avg_us, 3),
+                           min_us=round(min_us, 3), achieved=round(ach, 3), unit=unit, peak=peak,
+                           frac=round(ach / peak, 4), buffer_sets=len(sets[i])))
+    for rec, (key, plan) in zip(per_op, [(k, p) for k, p in hpct._plans.items()]):
+        rec["kernel"] = plan.kernel_name
+    dom = max(per_op, key=lambda r: r["avg_us"])
+    dop = OPS[dom["config"]]
+    roofline = dict(kernel=dom["kernel"], bound=dom["bound"], achieved=dom["achieved"], peak=dom["peak"], unit=dom["unit"],
+                    frac=dom["frac"], traffic=None, avg_us=dom["avg_us"],
+                    algorithmic=dop["flop"] if dom["bound"] == "mfma" else dop["bytes"])
+
+    out = dict(metric="per-op GB/s (memory-bound) or fp32 TFLOP/s (contraction) and % of MI355X peak",
+               value=round(100.0 * sum(fracs) / len(fracs), 3), unit="% of MI355X peak, mean over the ops of a step",
+               n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 4),
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
+               config=dict(workload="five fused chains at full size: gemm64x256x256+softmax, affine+pool 32x64x56x56, "
+                                    "layernorm+gelu 8192x4096, conv3x3 32x64x56x56->128, attention 16x2048x64"
+                           if not args.only else "chain %d only" % args.only,
+                           ops=len(which), hbm_cold_sets={str(i): len(sets[i]) for i in which}),
+               per_op=per_op, roofline=roofline)
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(host, which)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(host, which):
+    """The CPU checker as it stands, timed on this machine's host cores on the
+    same five workloads at full size (one run each after loading the library)."""
+    from oracle import ref
+    ref.lib()
+    threads = ref.max_threads()
+    secs, fracs, per = {}, [], []
+    for i in which:
+        h = host[i]
+        t0 = time.perf_counter()
+        if i == 1:
+            ref.chain1(h["X"], h["W"], h["bias"])
+        elif i == 2:
+            ref.chain2(h["X"], h["scale"], h["shift"], h["R"])
+        elif i == 3:
+            ref.chain3(h["X"], h["gamma"], h["beta"], 1e-5)
+        elif i == 4:
+            ref.conv2d_nchw_bias(h["in"], h["wt"], h["bias"], 1, 1)
+        else:
+            ref.attention(h["Q"], h["K"], h["V"], 0.125)
+        secs[i] = time.perf_counter() - t0
+        op = OPS[i]
+        if op["bound"] == "hbm":
+            ach, peak, unit = op["bytes"] / secs[i] / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = op["flop"] / secs[i] / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
+        fracs.append(ach / peak)
+        per.append(dict(config=i, seconds=round(secs[i], 4), achieved=round(ach, 5), unit=unit))
+    return dict(value=round(100.0 * sum(fracs) / len(fracs), 5), unit="% of MI355X peak, mean over the ops of a step",
+                cores=threads, kind="oracle",
+                sample="all five workloads at full size, one pass each, fp64 accumulation, %.1f s total" % sum(secs.values()),
+                per_op=per)
+
+
+if __name__ == "__main__":
+    sys.exit(main())
