@@ -47,7 +47,9 @@ __host__ __device__ constexpr int wt_chunk_floats() {
 //   [c][g=0,1][k_out][4]  taps 4g..4g+3        (128-bit fragment reads)
 //   [c][k_out]            tap 8, after the two groups
 // for 1x1: [c][k_out].
-template <int R, bool VEC>
+// VEC: W % 4 == 0, C % CC == 0 and K % KT == 0 (aligned vector loads, no channel tails).
+// WIDE: more float4 input slots per chunk than the register-staged 3 per thread.
+template <int R, bool VEC, bool WIDE>
 __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict__ in, const float* __restrict__ wt,
                                                         const float* __restrict__ bias, float* __restrict__ out,
                                                         ConvGeom g, int relu) {
@@ -57,6 +59,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     const int in_chunk = CC * g.ch_ld;  // floats
     auto inS = [&](int buf) { return lds + buf * in_chunk; };
     auto wS = [&](int buf) { return lds + 2 * in_chunk + buf * WCH; };
+    float* const biasS = lds + 2 * in_chunk + 2 * WCH;  // KT floats
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
@@ -69,73 +72,98 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     const int ih0 = h_lo - g.P;                // first staged input row
 
     // ---- staging: global -> registers -> LDS ---------------------------------
-    // input: CC x rows_max x ldw floats as float4 slots, slot s -> (c, row, x4)
+    // input: CC x rows_max x ldw floats as float4 slots, slot s -> (c, row, x4).
+    // The slot geometry does not depend on the chunk, so it is worked out once:
+    // global offset for the chunk starting at channel 0, LDS offset, chunk-local
+    // channel and a 4-bit mask of the elements that lie inside the image.
     const int ldw4 = g.ldw >> 2;
     const int slots = CC * g.rows_max * ldw4;
+    const int HW = g.H * g.W;
     constexpr int IN_PER_T = 3;  // slots staged through registers per thread
     float4v ireg[IN_PER_T];
-    // weights: thread (kk = tid % 128, part = tid / 128) takes CC/2 channels x TAPS
-    // contiguous floats of output channel k0 + kk
-    constexpr int WF = (CC / 2) * TAPS;          // floats per thread
-    constexpr int WF4 = (WF + 3) / 4;
-    float wreg[WF4 * 4];
-    const int wk = tid & 127, wpart = tid >> 7;
-
-    // one float4 slot of the staged input: slot s of the chunk starting at channel c0
-    auto load_slot = [&](int s, int c0) -> float4v {
-        float4v v = {0.f, 0.f, 0.f, 0.f};
-        const int c = s / (g.rows_max * ldw4);
+    int s_goff[IN_PER_T], s_loff[IN_PER_T], s_c[IN_PER_T], s_mask[IN_PER_T];
+    auto slot_geom = [&](int s, int& goff, int& loff, int& c, int& mask) {
+        c = s / (g.rows_max * ldw4);
         const int rem = s - c * (g.rows_max * ldw4);
         const int row = rem / ldw4, x4 = (rem - row * ldw4) * 4;
-        const int ih = ih0 + row, iw = x4 - g.P - g.lpad, ch = c0 + c;
-        if (ch < g.C && ih >= 0 && ih < g.H) {
-            const float* src = in + (((int64_t)n * g.C + ch) * g.H + ih) * g.W;
-            if (VEC && iw >= 0 && iw + 3 < g.W) v = load4(src + iw);
-            else {
-                if (iw >= 0 && iw < g.W) v.x = src[iw];
-                if (iw + 1 >= 0 && iw + 1 < g.W) v.y = src[iw + 1];
-                if (iw + 2 >= 0 && iw + 2 < g.W) v.z = src[iw + 2];
-                if (iw + 3 >= 0 && iw + 3 < g.W) v.w = src[iw + 3];
+        const int ih = ih0 + row, iw = x4 - g.P - g.lpad;
+        loff = c * g.ch_ld + rem * 4;
+        goff = ((n * g.C + c) * g.H + ih) * g.W + iw;
+        mask = 0;
+        if (ih >= 0 && ih < g.H) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (iw + j >= 0 && iw + j < g.W) mask |= 1 << j;
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < IN_PER_T; ++i) {
+        const int s = tid + i * 256;
+        if (s < slots) slot_geom(s, s_goff[i], s_loff[i], s_c[i], s_mask[i]);
+        else { s_goff[i] = 0; s_loff[i] = -1; s_c[i] = 0; s_mask[i] = 0; }
+    }
+    auto load_slot = [&](int goff, int c, int mask, int c0) -> float4v {
+        float4v v = {0.f, 0.f, 0.f, 0.f};
+        if (VEC) {  // W % 4 == 0: a slot lies entirely inside or entirely outside a row; C % CC == 0
+            if (mask == 15) v = load4(in + goff + c0 * HW);
+        } else if (c0 + c < g.C) {
+            const float* src = in + goff + c0 * HW;
+            {
+                if (mask & 1) v.x = src[0];
+                if (mask & 2) v.y = src[1];
+                if (mask & 4) v.z = src[2];
+                if (mask & 8) v.w = src[3];
             }
         }
         return v;
     };
-    auto slot_addr = [&](int s) -> int {  // float offset of slot s inside an input stage buffer
-        const int c = s / (g.rows_max * ldw4);
-        return c * g.ch_ld + (s - c * (g.rows_max * ldw4)) * 4;
-    };
+    // weights: thread (wk = tid % 128, wpart = tid / 128) takes CC/2 channels x TAPS
+    // contiguous floats of output channel k0 + wk
+    constexpr int WF = (CC / 2) * TAPS;      // floats per thread
+    constexpr int WV = WF % 4 == 0 ? 4 : 2;  // widest aligned vector (CC/2 even channels -> 8-byte aligned)
+    float wreg[WF];
+    const int wk = tid & 127, wpart = tid >> 7;
+    const float* const wsrc0 = wt + ((int64_t)(k0 + wk) * g.C + wpart * (CC / 2)) * TAPS;
+
     auto fetch = [&](int c0) {
 #pragma unroll
-        for (int i = 0; i < IN_PER_T; ++i) {
-            const int s = tid + i * 256;
-            ireg[i] = s < slots ? load_slot(s, c0) : float4v{0.f, 0.f, 0.f, 0.f};
-        }
-        const int k = k0 + wk, cfirst = c0 + wpart * (CC / 2);
-        const float* wsrc = wt + ((int64_t)k * g.C + cfirst) * TAPS;
-        const bool full = k < g.K && cfirst + CC / 2 <= g.C;
-        if (VEC && full && (WF % 4 == 0)) {
+        for (int i = 0; i < IN_PER_T; ++i) ireg[i] = load_slot(s_goff[i], s_c[i], s_mask[i], c0);
+        const float* wsrc = wsrc0 + c0 * TAPS;
+        if (VEC) {  // K % KT == 0 and C % CC == 0: no tails
+            if (WV == 4) {
 #pragma unroll
-            for (int i = 0; i < WF4; ++i) {
-                float4v t = load4(wsrc + 4 * i);
-                wreg[4 * i] = t.x; wreg[4 * i + 1] = t.y; wreg[4 * i + 2] = t.z; wreg[4 * i + 3] = t.w;
+                for (int i = 0; i < WF / 4; ++i) {
+                    const float4v t = load4(wsrc + 4 * i);
+                    wreg[4 * i] = t.x; wreg[4 * i + 1] = t.y; wreg[4 * i + 2] = t.z; wreg[4 * i + 3] = t.w;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < WF / 2; ++i) {
+                    const float2v t = *reinterpret_cast<const float2v*>(wsrc + 2 * i);
+                    wreg[2 * i] = t.x; wreg[2 * i + 1] = t.y;
+                }
             }
         } else {
 #pragma unroll
             for (int i = 0; i < WF; ++i) {
-                const int c = cfirst + i / TAPS;
-                wreg[i] = (k < g.K && c < g.C) ? wsrc[i] : 0.f;
+                const int c = c0 + wpart * (CC / 2) + i / TAPS;
+                wreg[i] = (k0 + wk < g.K && c < g.C) ? wsrc[i] : 0.f;
             }
         }
     };
     auto stash = [&](int buf, int c0) {
+        float* const ib = inS(buf);
 #pragma unroll
-        for (int i = 0; i < IN_PER_T; ++i) {
-            const int s = tid + i * 256;
-            if (s < slots) *reinterpret_cast<float4v*>(inS(buf) + slot_addr(s)) = ireg[i];
-        }
+        for (int i = 0; i < IN_PER_T; ++i)
+            if (s_loff[i] >= 0) *reinterpret_cast<float4v*>(ib + s_loff[i]) = ireg[i];
         // wide images: slots beyond the register-staged ones are copied directly
-        for (int s = tid + IN_PER_T * 256; s < slots; s += 256)
-            *reinterpret_cast<float4v*>(inS(buf) + slot_addr(s)) = load_slot(s, c0);
+        if (WIDE) {
+            for (int s = tid + IN_PER_T * 256; s < slots; s += 256) {
+                int goff, loff, c, mask;
+                slot_geom(s, goff, loff, c, mask);
+                *reinterpret_cast<float4v*>(ib + loff) = load_slot(goff, c, mask, c0);
+            }
+        }
         float* w = wS(buf);
 #pragma unroll
         for (int cc = 0; cc < CC / 2; ++cc) {
@@ -167,13 +195,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
 #pragma unroll
     for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; }
 
-    const int nchunks = (g.C + CC - 1) / CC;
-    fetch(0);
-    stash(0, 0);
-    __syncthreads();
-    for (int t = 0; t < nchunks; ++t) {
-        const int cur = t & 1;
-        if (t + 1 < nchunks) fetch((t + 1) * CC);
+    auto compute = [&](int cur) {
         const float* bI = inS(cur) + b_base;
         const float* aW = wS(cur);
 #pragma unroll
@@ -206,9 +228,25 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
                 }
             }
         }
-        if (t + 1 < nchunks) stash(cur ^ 1, (t + 1) * CC);
+    };
+
+    if (tid < KT) biasS[tid] = (bias && k0 + tid < g.K) ? bias[k0 + tid] : 0.f;  // visible after the first barrier
+
+    // software pipeline over channel chunks; the last chunk is peeled so the
+    // loop body has no conditional loads
+    const int nchunks = (g.C + CC - 1) / CC;
+    fetch(0);
+    stash(0, 0);
+    __syncthreads();
+    for (int t = 0; t + 1 < nchunks; ++t) {
+        fetch((t + 1) * CC);
+        __builtin_amdgcn_sched_barrier(0);  // keep the global loads ahead of the MFMAs they overlap with
+        compute(t & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        stash((t + 1) & 1, (t + 1) * CC);
         __syncthreads();
     }
+    compute((nchunks - 1) & 1);
 
     // ---- epilogue: register r of lane holds channel 8*(r/4) + 4*half + r%4 of the block
     if (p_ok) {
@@ -216,9 +254,10 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int k = k0 + kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                const int kl = kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                const int k = k0 + kl;
                 if (k < g.K) {
-                    float v = acc[kb][r] + (bias ? bias[k] : 0.f);
+                    float v = acc[kb][r] + biasS[kl];
                     if (relu) v = fmaxf(v, 0.f);
                     out[((int64_t)n * g.K + k) * g.HoWo + p] = v;
                 }
@@ -246,7 +285,7 @@ ConvGeom geom(const ConvParams& p) {
 
 size_t lds_bytes(const ConvGeom& g, int R) {
     const int w = R == 3 ? wt_chunk_floats<3>() : wt_chunk_floats<1>();
-    return (size_t)(2 * CC * g.ch_ld + 2 * w) * 4;
+    return (size_t)(2 * CC * g.ch_ld + 2 * w + KT) * 4;
 }
 
 }  // namespace
@@ -275,26 +314,31 @@ LaunchShape conv_shape(const ConvParams& p) {
     return s;
 }
 
-template <int R, bool VEC>
+template <int R, bool VEC, bool WIDE>
 static hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
     const size_t lds = lds_bytes(g, R);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, VEC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, VEC, WIDE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)(p.Nb * g.tiles_per_img), (unsigned)((p.K + KT - 1) / KT)), block(256);
-    hipLaunchKernelGGL((conv2d_nchw_mfma<R, VEC>), grid, block, lds, stream, p.in, p.wt, p.bias, p.out, g, p.relu);
+    hipLaunchKernelGGL((conv2d_nchw_mfma<R, VEC, WIDE>), grid, block, lds, stream, p.in, p.wt, p.bias, p.out, g, p.relu);
     return hipGetLastError();
 }
 
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream) {
     const ConvGeom g = geom(p);
-    const bool vec = (p.W % 4 == 0) && (p.C % 4 == 0);
-    if (p.R == 3) return vec ? launch_conv<3, true>(p, g, stream) : launch_conv<3, false>(p, g, stream);
-    return vec ? launch_conv<1, true>(p, g, stream) : launch_conv<1, false>(p, g, stream);
+    const bool vec = (p.W % 4 == 0) && (p.C % CC == 0) && (p.K % KT == 0);
+    const bool wide = CC * g.rows_max * (g.ldw / 4) > 3 * 256;
+    if (p.R == 3) {
+        if (vec) return wide ? launch_conv<3, true, true>(p, g, stream) : launch_conv<3, true, false>(p, g, stream);
+        return wide ? launch_conv<3, false, true>(p, g, stream) : launch_conv<3, false, false>(p, g, stream);
+    }
+    if (vec) return wide ? launch_conv<1, true, true>(p, g, stream) : launch_conv<1, true, false>(p, g, stream);
+    return wide ? launch_conv<1, false, true>(p, g, stream) : launch_conv<1, false, false>(p, g, stream);
 }
 
 }  // namespace hpct
