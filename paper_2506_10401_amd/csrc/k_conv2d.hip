@@ -11,12 +11,19 @@
 // bytes of the NCHW output.
 //
 // A work-group of four waves owns KT = 128 output channels x TP = 64
-// consecutive output pixels of one image.  Channels are processed CC at a time:
-// the input rows the tile touches (with their zero halo) and the CC*R*S weight
-// columns are staged in LDS, double buffered, with the global loads of chunk
-// t+1 in flight while chunk t is multiplied.  One MFMA contracts two channels
-// (lane half 0 / 1 = channel 2cp / 2cp+1) at the same filter tap, so the B
-// fragment of every tap is a plain LDS read at lane base + constant.
+// consecutive output pixels of one image; a wave owns 64 channels x 32 pixels.
+// Channels are processed CC at a time.  Per chunk the LDS holds
+//   * the input rows the tile touches, with their zero halo, per channel, and
+//   * for every output channel its CC*R*S weights in memory order (a plain
+//     copy of a contiguous piece of the KCRS tensor, row stride padded by 4).
+// Both are double buffered: the global loads of chunk t+1 are issued before the
+// MFMAs of chunk t and written to the other buffer after them.
+//
+// Contraction order: within a chunk, lane half 0 multiplies channels
+// 0..CC/2-1 and lane half 1 channels CC/2..CC-1, so MFMA step s contracts
+// (channel s/TAPS, tap s%TAPS) of both halves.  The A fragment is then a run of
+// consecutive floats of the weight row (vector LDS reads) and the B fragment of
+// every step is an LDS read at lane base + a constant.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -25,63 +32,65 @@ namespace {
 
 constexpr int KT = 128;  // output channels per work-group
 constexpr int TP = 64;   // output pixels per work-group
-constexpr int CC = 8;    // input channels per LDS chunk (multiple of 4)
+constexpr int kXcds = 8; // work-groups are dealt round-robin to this many L2 domains
 
 struct ConvGeom {
     int Nb, C, H, W, K, P;
     int Ho, Wo, HoWo;
-    int tiles_per_img;
+    int tiles_per_img, tiles;
     int rows_max;  // input rows staged per tile
     int lpad;      // left pad of an LDS row so that iw = 0 lands on a 16-byte boundary
     int ldw;       // LDS row stride (floats, multiple of 4)
     int ch_ld;     // LDS channel stride (floats)
 };
 
-template <int R>
-__host__ __device__ constexpr int wt_chunk_floats() {
-    // per channel: R*R taps for KT output channels, taps grouped by four
-    return R == 3 ? CC * (2 * KT * 4 + KT) : CC * KT;
-}
+template <int R, int CC> struct Cfg {
+    static constexpr int TAPS = R * R;
+    static constexpr int FPR = CC * TAPS;        // weight floats per output channel per chunk
+    static constexpr int HALF = FPR / 2;         // MFMA steps per chunk
+    static constexpr int WLD = FPR + 4;          // LDS row stride of the weight stage
+    static constexpr int VW = HALF % 4 == 0 ? 4 : 2;  // A-fragment vector width
+    static constexpr int NV4 = KT * FPR / 4;     // float4 of weights per chunk
+    static constexpr int WPT = (NV4 + 255) / 256;
+    static constexpr int W_STAGE = KT * WLD;     // floats
+    static constexpr int IN_PER_T = CC <= 4 ? 2 : 3;  // input float4 slots staged through registers per thread
+};
 
-// LDS weight layout for 3x3, per chunk channel c:
-//   [c][g=0,1][k_out][4]  taps 4g..4g+3        (128-bit fragment reads)
-//   [c][k_out]            tap 8, after the two groups
-// for 1x1: [c][k_out].
-// VEC: W % 4 == 0, C % CC == 0 and K % KT == 0 (aligned vector loads, no channel tails).
-// WIDE: more float4 input slots per chunk than the register-staged 3 per thread.
-template <int R, bool VEC, bool WIDE>
+// FAST: W % 4 == 0, C % CC == 0, K % KT == 0 and the staged input fits the
+// register-staged slots: aligned vector loads, no tails, software pipelined.
+// Otherwise every element is loaded with its own bounds test, chunk by chunk.
+template <int R, int CC, bool FAST>
 __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict__ in, const float* __restrict__ wt,
                                                         const float* __restrict__ bias, float* __restrict__ out,
                                                         ConvGeom g, int relu) {
-    constexpr int TAPS = R * R;
-    constexpr int WCH = wt_chunk_floats<R>();
+    using cfg = Cfg<R, CC>;
+    constexpr int TAPS = cfg::TAPS, FPR = cfg::FPR, HALF = cfg::HALF, WLD = cfg::WLD, VW = cfg::VW;
+    constexpr int IN_PER_T = cfg::IN_PER_T, WPT = cfg::WPT;
     extern __shared__ __align__(16) float lds[];
-    const int in_chunk = CC * g.ch_ld;  // floats
-    auto inS = [&](int buf) { return lds + buf * in_chunk; };
-    auto wS = [&](int buf) { return lds + 2 * in_chunk + buf * WCH; };
-    float* const biasS = lds + 2 * in_chunk + 2 * WCH;  // KT floats
+    const int in_stage = CC * g.ch_ld;  // floats
+    auto inS = [&](int buf) { return lds + buf * in_stage; };
+    auto wS = [&](int buf) { return lds + 2 * in_stage + buf * cfg::W_STAGE; };
+    float* const biasS = lds + 2 * in_stage + 2 * cfg::W_STAGE;  // KT floats
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
 
-    const int tile = blockIdx.x;
+    // consecutive tiles (same image, shared halo rows) go to the same L2 domain
+    int tile;
+    {
+        const int x = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
+        const int q = g.tiles / kXcds, r = g.tiles % kXcds;
+        tile = x * q + (x < r ? x : r) + j;
+    }
     const int n = tile / g.tiles_per_img;
     const int p0 = (tile % g.tiles_per_img) * TP;
     const int k0 = blockIdx.y * KT;
-    const int h_lo = p0 / g.Wo;                // first output row of the tile
-    const int ih0 = h_lo - g.P;                // first staged input row
-
-    // ---- staging: global -> registers -> LDS ---------------------------------
-    // input: CC x rows_max x ldw floats as float4 slots, slot s -> (c, row, x4).
-    // The slot geometry does not depend on the chunk, so it is worked out once:
-    // global offset for the chunk starting at channel 0, LDS offset, chunk-local
-    // channel and a 4-bit mask of the elements that lie inside the image.
-    const int ldw4 = g.ldw >> 2;
-    const int slots = CC * g.rows_max * ldw4;
+    const int h_lo = p0 / g.Wo;  // first output row of the tile
+    const int ih0 = h_lo - g.P;  // first staged input row
     const int HW = g.H * g.W;
-    constexpr int IN_PER_T = 3;  // slots staged through registers per thread
-    float4v ireg[IN_PER_T];
-    int s_goff[IN_PER_T], s_loff[IN_PER_T], s_c[IN_PER_T], s_mask[IN_PER_T];
+    const int ldw4 = g.ldw >> 2;
+    const int slots = CC * g.rows_max * ldw4;  // float4 slots of one input stage: slot -> (c, row, x4)
+
     auto slot_geom = [&](int s, int& goff, int& loff, int& c, int& mask) {
         c = s / (g.rows_max * ldw4);
         const int rem = s - c * (g.rows_max * ldw4);
@@ -96,100 +105,82 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
                 if (iw + j >= 0 && iw + j < g.W) mask |= 1 << j;
         }
     };
+
+    // ---- FAST staging: geometry worked out once, loads through registers ------
+    float4v ireg[IN_PER_T], wreg[WPT];
+    int s_goff[IN_PER_T], s_loff[IN_PER_T];
+    int w_goff[WPT], w_loff[WPT];
+    if (FAST) {
 #pragma unroll
-    for (int i = 0; i < IN_PER_T; ++i) {
-        const int s = tid + i * 256;
-        if (s < slots) slot_geom(s, s_goff[i], s_loff[i], s_c[i], s_mask[i]);
-        else { s_goff[i] = 0; s_loff[i] = -1; s_c[i] = 0; s_mask[i] = 0; }
+        for (int i = 0; i < IN_PER_T; ++i) {
+            const int s = tid + i * 256;
+            int c, mask;
+            s_goff[i] = -1; s_loff[i] = -1;
+            if (s < slots) {
+                slot_geom(s, s_goff[i], s_loff[i], c, mask);
+                if (mask != 15) s_goff[i] = -1;  // whole slot outside the image: stays zero
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) {
+            const int v = tid + i * 256;
+            const int k = v / (FPR / 4), f4 = v % (FPR / 4);
+            w_goff[i] = v < cfg::NV4 ? ((k0 + k) * g.C) * TAPS + 4 * f4 : -1;
+            w_loff[i] = k * WLD + 4 * f4;
+        }
     }
-    auto load_slot = [&](int goff, int c, int mask, int c0) -> float4v {
-        float4v v = {0.f, 0.f, 0.f, 0.f};
-        if (VEC) {  // W % 4 == 0: a slot lies entirely inside or entirely outside a row; C % CC == 0
-            if (mask == 15) v = load4(in + goff + c0 * HW);
-        } else if (c0 + c < g.C) {
-            const float* src = in + goff + c0 * HW;
-            {
+    auto fetch = [&](int c0) {
+#pragma unroll
+        for (int i = 0; i < IN_PER_T; ++i)
+            ireg[i] = s_goff[i] >= 0 ? load4(in + s_goff[i] + c0 * HW) : float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < WPT; ++i)
+            wreg[i] = w_goff[i] >= 0 ? load4(wt + w_goff[i] + c0 * TAPS) : float4v{0.f, 0.f, 0.f, 0.f};
+    };
+    auto stash = [&](int buf) {
+        float* const ib = inS(buf);
+        float* const wb = wS(buf);
+#pragma unroll
+        for (int i = 0; i < IN_PER_T; ++i)
+            if (s_loff[i] >= 0) *reinterpret_cast<float4v*>(ib + s_loff[i]) = ireg[i];
+#pragma unroll
+        for (int i = 0; i < WPT; ++i)
+            if (w_goff[i] >= 0) *reinterpret_cast<float4v*>(wb + w_loff[i]) = wreg[i];
+    };
+    // ---- general staging: every element with its own bounds test ----------------
+    auto copy_chunk = [&](int buf, int c0) {
+        float* const ib = inS(buf);
+        float* const wb = wS(buf);
+        for (int s = tid; s < slots; s += 256) {
+            int goff, loff, c, mask;
+            slot_geom(s, goff, loff, c, mask);
+            float4v v = {0.f, 0.f, 0.f, 0.f};
+            if (c0 + c < g.C) {
+                const float* src = in + goff + c0 * HW;
                 if (mask & 1) v.x = src[0];
                 if (mask & 2) v.y = src[1];
                 if (mask & 4) v.z = src[2];
                 if (mask & 8) v.w = src[3];
             }
+            *reinterpret_cast<float4v*>(ib + loff) = v;
         }
-        return v;
-    };
-    // weights: thread (wk = tid % 128, wpart = tid / 128) takes CC/2 channels x TAPS
-    // contiguous floats of output channel k0 + wk
-    constexpr int WF = (CC / 2) * TAPS;      // floats per thread
-    constexpr int WV = WF % 4 == 0 ? 4 : 2;  // widest aligned vector (CC/2 even channels -> 8-byte aligned)
-    float wreg[WF];
-    const int wk = tid & 127, wpart = tid >> 7;
-    const float* const wsrc0 = wt + ((int64_t)(k0 + wk) * g.C + wpart * (CC / 2)) * TAPS;
-
-    auto fetch = [&](int c0) {
-#pragma unroll
-        for (int i = 0; i < IN_PER_T; ++i) ireg[i] = load_slot(s_goff[i], s_c[i], s_mask[i], c0);
-        const float* wsrc = wsrc0 + c0 * TAPS;
-        if (VEC) {  // K % KT == 0 and C % CC == 0: no tails
-            if (WV == 4) {
-#pragma unroll
-                for (int i = 0; i < WF / 4; ++i) {
-                    const float4v t = load4(wsrc + 4 * i);
-                    wreg[4 * i] = t.x; wreg[4 * i + 1] = t.y; wreg[4 * i + 2] = t.z; wreg[4 * i + 3] = t.w;
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < WF / 2; ++i) {
-                    const float2v t = *reinterpret_cast<const float2v*>(wsrc + 2 * i);
-                    wreg[2 * i] = t.x; wreg[2 * i + 1] = t.y;
-                }
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < WF; ++i) {
-                const int c = c0 + wpart * (CC / 2) + i / TAPS;
-                wreg[i] = (k0 + wk < g.K && c < g.C) ? wsrc[i] : 0.f;
-            }
-        }
-    };
-    auto stash = [&](int buf, int c0) {
-        float* const ib = inS(buf);
-#pragma unroll
-        for (int i = 0; i < IN_PER_T; ++i)
-            if (s_loff[i] >= 0) *reinterpret_cast<float4v*>(ib + s_loff[i]) = ireg[i];
-        // wide images: slots beyond the register-staged ones are copied directly
-        if (WIDE) {
-            for (int s = tid + IN_PER_T * 256; s < slots; s += 256) {
-                int goff, loff, c, mask;
-                slot_geom(s, goff, loff, c, mask);
-                *reinterpret_cast<float4v*>(ib + loff) = load_slot(goff, c, mask, c0);
-            }
-        }
-        float* w = wS(buf);
-#pragma unroll
-        for (int cc = 0; cc < CC / 2; ++cc) {
-            const int c = wpart * (CC / 2) + cc;
-            if (R == 3) {
-                float* base = w + c * (2 * KT * 4 + KT);
-                *reinterpret_cast<float4v*>(base + wk * 4) =
-                    float4v{wreg[cc * 9 + 0], wreg[cc * 9 + 1], wreg[cc * 9 + 2], wreg[cc * 9 + 3]};
-                *reinterpret_cast<float4v*>(base + KT * 4 + wk * 4) =
-                    float4v{wreg[cc * 9 + 4], wreg[cc * 9 + 5], wreg[cc * 9 + 6], wreg[cc * 9 + 7]};
-                base[2 * KT * 4 + wk] = wreg[cc * 9 + 8];
-            } else {
-                w[c * KT + wk] = wreg[cc];
-            }
+        for (int e = tid; e < KT * FPR; e += 256) {
+            const int k = e / FPR, f = e - k * FPR;
+            const int c = c0 + f / TAPS;
+            wb[k * WLD + f] = (k0 + k < g.K && c < g.C) ? wt[((int64_t)(k0 + k) * g.C + c0) * TAPS + f] : 0.f;
         }
     };
 
     // ---- per-lane fragment addresses -------------------------------------------
-    const int kb0 = (wave & 1) * 64;       // this wave's 64 output channels inside the tile
-    const int pb = (wave >> 1) * 32;       // this wave's 32 pixels inside the tile
+    const int kb0 = (wave & 1) * 64;  // this wave's 64 output channels inside the tile
+    const int pb = (wave >> 1) * 32;  // this wave's 32 pixels inside the tile
     int p = p0 + pb + l32;
     const bool p_ok = p < g.HoWo;
-    if (!p_ok) p = g.HoWo - 1;             // clamp: reads stay inside the staged rows, store is masked
+    if (!p_ok) p = g.HoWo - 1;        // clamp: reads stay inside the staged rows, the store is masked
     const int oh = p / g.Wo, ow = p - oh * g.Wo;
-    // input element of tap (kh, kw), chunk channel c: c*ch_ld + (oh-h_lo+kh)*ldw + ow + kw + lpad
-    const int b_base = half * g.ch_ld + (oh - h_lo) * g.ldw + ow + g.lpad;
+    // input element of (chunk channel c, tap kh,kw): c*ch_ld + (oh-h_lo+kh)*ldw + ow + kw + lpad
+    const int b_base = half * (CC / 2) * g.ch_ld + (oh - h_lo) * g.ldw + ow + g.lpad;
+    const int a_base = (kb0 + l32) * WLD + half * HALF;
 
     float16v acc[2];
 #pragma unroll
@@ -197,56 +188,58 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
 
     auto compute = [&](int cur) {
         const float* bI = inS(cur) + b_base;
-        const float* aW = wS(cur);
+        const float* aW = wS(cur) + a_base;
 #pragma unroll
-        for (int cp = 0; cp < CC / 2; ++cp) {
-            const int c = 2 * cp + half;  // this lane half's channel
-            float a[2][TAPS];
-            if (R == 3) {
-                const float* base = aW + c * (2 * KT * 4 + KT);
+        for (int j = 0; j < HALF / VW; ++j) {
+            float a0[VW], a1[VW];
+            if (VW == 4) {
+                const float4v t0 = *reinterpret_cast<const float4v*>(aW + VW * j);
+                const float4v t1 = *reinterpret_cast<const float4v*>(aW + 32 * WLD + VW * j);
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const int kk = kb0 + kb * 32 + l32;
-                    const float4v lo = *reinterpret_cast<const float4v*>(base + kk * 4);
-                    const float4v hi = *reinterpret_cast<const float4v*>(base + KT * 4 + kk * 4);
-                    a[kb][0] = lo.x; a[kb][1] = lo.y; a[kb][2] = lo.z; a[kb][3] = lo.w;
-                    a[kb][4] = hi.x; a[kb][5] = hi.y; a[kb][6] = hi.z; a[kb][7] = hi.w;
-                    a[kb][8] = base[2 * KT * 4 + kk];
-                }
+                for (int e = 0; e < VW; ++e) { a0[e] = t0[e]; a1[e] = t1[e]; }
             } else {
+                const float2v t0 = *reinterpret_cast<const float2v*>(aW + VW * j);
+                const float2v t1 = *reinterpret_cast<const float2v*>(aW + 32 * WLD + VW * j);
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) a[kb][0] = aW[c * KT + kb0 + kb * 32 + l32];
+                for (int e = 0; e < VW; ++e) { a0[e] = t0[e]; a1[e] = t1[e]; }
             }
-            const float* bc = bI + 2 * cp * g.ch_ld;
 #pragma unroll
-            for (int kh = 0; kh < R; ++kh) {
-#pragma unroll
-                for (int kw = 0; kw < R; ++kw) {
-                    const float b = bc[kh * g.ldw + kw];
-                    acc[0] = mfma_32x32x2(a[0][kh * R + kw], b, acc[0]);
-                    acc[1] = mfma_32x32x2(a[1][kh * R + kw], b, acc[1]);
-                }
+            for (int e = 0; e < VW; ++e) {
+                const int s = VW * j + e;  // MFMA step inside the chunk
+                const int c = s / TAPS, tap = s % TAPS;
+                const float b = bI[c * g.ch_ld + (tap / R) * g.ldw + (tap % R)];
+                acc[0] = mfma_32x32x2(a0[e], b, acc[0]);
+                acc[1] = mfma_32x32x2(a1[e], b, acc[1]);
             }
         }
     };
 
     if (tid < KT) biasS[tid] = (bias && k0 + tid < g.K) ? bias[k0 + tid] : 0.f;  // visible after the first barrier
 
-    // software pipeline over channel chunks; the last chunk is peeled so the
-    // loop body has no conditional loads
     const int nchunks = (g.C + CC - 1) / CC;
-    fetch(0);
-    stash(0, 0);
-    __syncthreads();
-    for (int t = 0; t + 1 < nchunks; ++t) {
-        fetch((t + 1) * CC);
-        __builtin_amdgcn_sched_barrier(0);  // keep the global loads ahead of the MFMAs they overlap with
-        compute(t & 1);
-        __builtin_amdgcn_sched_barrier(0);
-        stash((t + 1) & 1, (t + 1) * CC);
+    if (FAST) {
+        // software pipeline over channel chunks; the last chunk is peeled so the
+        // loop body has no conditional loads
+        fetch(0);
+        stash(0);
         __syncthreads();
+        for (int t = 0; t + 1 < nchunks; ++t) {
+            fetch((t + 1) * CC);
+            __builtin_amdgcn_sched_barrier(0);  // keep the global loads ahead of the MFMAs they overlap with
+            compute(t & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            stash((t + 1) & 1);
+            __syncthreads();
+        }
+        compute((nchunks - 1) & 1);
+    } else {
+        for (int t = 0; t < nchunks; ++t) {
+            copy_chunk(0, t * CC);
+            __syncthreads();
+            compute(0);
+            __syncthreads();
+        }
     }
-    compute((nchunks - 1) & 1);
 
     // ---- epilogue: register r of lane holds channel 8*(r/4) + 4*half + r%4 of the block
     if (p_ok) {
@@ -273,6 +266,7 @@ ConvGeom geom(const ConvParams& p) {
     g.Wo = p.W + 2 * p.pad - p.S + 1;
     g.HoWo = g.Ho * g.Wo;
     g.tiles_per_img = (g.HoWo + TP - 1) / TP;
+    g.tiles = p.Nb * g.tiles_per_img;
     // a run of TP consecutive pixels touches at most (TP-1)/Wo + 2 output rows
     int out_rows = (TP - 1) / g.Wo + 2;
     if (out_rows > g.Ho) out_rows = g.Ho;
@@ -283,16 +277,40 @@ ConvGeom geom(const ConvParams& p) {
     return g;
 }
 
-size_t lds_bytes(const ConvGeom& g, int R) {
-    const int w = R == 3 ? wt_chunk_floats<3>() : wt_chunk_floats<1>();
-    return (size_t)(2 * CC * g.ch_ld + 2 * w + KT) * 4;
+template <int R, int CC>
+size_t lds_bytes(const ConvGeom& g) {
+    return (size_t)(2 * CC * g.ch_ld + 2 * Cfg<R, CC>::W_STAGE + KT) * 4;
+}
+
+// input channels per LDS chunk: 4 keeps a work-group near 50 KB of LDS, so
+// three work-groups share a CU and hide each other's staging
+constexpr int kCC = 4;
+
+template <int R, int CC>
+bool fast_ok(const ConvParams& p, const ConvGeom& g) {
+    return p.W % 4 == 0 && p.C % CC == 0 && p.K % KT == 0 &&
+           CC * g.rows_max * (g.ldw / 4) <= 256 * Cfg<R, CC>::IN_PER_T;
+}
+
+template <int R, int CC, bool FAST>
+hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
+    const size_t lds = lds_bytes<R, CC>(g);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, CC, FAST>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((unsigned)g.tiles, (unsigned)((p.K + KT - 1) / KT)), block(256);
+    hipLaunchKernelGGL((conv2d_nchw_mfma<R, CC, FAST>), grid, block, lds, stream, p.in, p.wt, p.bias, p.out, g, p.relu);
+    return hipGetLastError();
 }
 
 }  // namespace
 
 bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h, int32_t stride_w,
                     int32_t pad_h, int32_t pad_w, const char** why) {
-    (void)C; (void)K;
     if (stride_h != 1 || stride_w != 1) { *why = "only stride 1 is supported"; return false; }
     if (R != S || (R != 1 && R != 3)) { *why = "only 1x1 and 3x3 filters are supported"; return false; }
     if (pad_h != pad_w) { *why = "padding must be the same in both directions"; return false; }
@@ -300,45 +318,28 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
     ConvParams p{};
     p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1;
     const ConvGeom g = geom(p);
-    if (lds_bytes(g, R) > 160 * 1024) { *why = "the input rows of one 64-pixel tile do not fit in LDS (image too wide)"; return false; }
+    const size_t lds = R == 3 ? lds_bytes<3, kCC>(g) : lds_bytes<1, kCC>(g);
+    if (lds > 160 * 1024) { *why = "the input rows of one 64-pixel tile do not fit in LDS (image too wide)"; return false; }
     return true;
 }
 
 LaunchShape conv_shape(const ConvParams& p) {
     const ConvGeom g = geom(p);
     LaunchShape s{};
-    s.grid[0] = (uint32_t)(p.Nb * g.tiles_per_img); s.grid[1] = (uint32_t)((p.K + KT - 1) / KT); s.grid[2] = 1;
+    s.grid[0] = (uint32_t)g.tiles; s.grid[1] = (uint32_t)((p.K + KT - 1) / KT); s.grid[2] = 1;
     s.block[0] = 256; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)lds_bytes(g, p.R);
-    s.kernel = p.R == 3 ? "conv2d_nchw_mfma<3x3>" : "conv2d_nchw_mfma<1x1>";
+    s.lds_bytes = (uint32_t)(p.R == 3 ? lds_bytes<3, kCC>(g) : lds_bytes<1, kCC>(g));
+    const bool fast = p.R == 3 ? fast_ok<3, kCC>(p, g) : fast_ok<1, kCC>(p, g);
+    s.kernel = p.R == 3 ? (fast ? "conv2d_nchw_mfma<3x3,pipelined>" : "conv2d_nchw_mfma<3x3,general>")
+                        : (fast ? "conv2d_nchw_mfma<1x1,pipelined>" : "conv2d_nchw_mfma<1x1,general>");
     return s;
-}
-
-template <int R, bool VEC, bool WIDE>
-static hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
-    const size_t lds = lds_bytes(g, R);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, VEC, WIDE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    dim3 grid((unsigned)(p.Nb * g.tiles_per_img), (unsigned)((p.K + KT - 1) / KT)), block(256);
-    hipLaunchKernelGGL((conv2d_nchw_mfma<R, VEC, WIDE>), grid, block, lds, stream, p.in, p.wt, p.bias, p.out, g, p.relu);
-    return hipGetLastError();
 }
 
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream) {
     const ConvGeom g = geom(p);
-    const bool vec = (p.W % 4 == 0) && (p.C % CC == 0) && (p.K % KT == 0);
-    const bool wide = CC * g.rows_max * (g.ldw / 4) > 3 * 256;
-    if (p.R == 3) {
-        if (vec) return wide ? launch_conv<3, true, true>(p, g, stream) : launch_conv<3, true, false>(p, g, stream);
-        return wide ? launch_conv<3, false, true>(p, g, stream) : launch_conv<3, false, false>(p, g, stream);
-    }
-    if (vec) return wide ? launch_conv<1, true, true>(p, g, stream) : launch_conv<1, true, false>(p, g, stream);
-    return wide ? launch_conv<1, false, true>(p, g, stream) : launch_conv<1, false, false>(p, g, stream);
+    if (p.R == 3)
+        return fast_ok<3, kCC>(p, g) ? launch_conv<3, kCC, true>(p, g, stream) : launch_conv<3, kCC, false>(p, g, stream);
+    return fast_ok<1, kCC>(p, g) ? launch_conv<1, kCC, true>(p, g, stream) : launch_conv<1, kCC, false>(p, g, stream);
 }
 
 }  // namespace hpct
