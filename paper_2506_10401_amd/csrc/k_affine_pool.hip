@@ -9,7 +9,8 @@
 namespace hpct {
 namespace {
 
-constexpr int kUnroll = 4;  // independent 16-byte loads per input in flight per thread
+constexpr int kThreads = 512;  // threads per plane
+constexpr int kUnroll = 2;    // independent 16-byte loads per input in flight per thread
 
 template <bool AFF, bool RELU, bool RES>
 __device__ __forceinline__ float4v chain(float4v x, float4v r, float sc, float sh) {
@@ -21,12 +22,12 @@ __device__ __forceinline__ float4v chain(float4v x, float4v r, float sc, float s
 }
 
 // One work-group per plane p = n*C + c.  HW % 4 == 0, so every plane starts on
-// a 16-byte boundary.  Thread t takes vectors t, t+256, ...; kUnroll of them
+// a 16-byte boundary.  Thread t takes vectors t, t+kThreads, ...; kUnroll of them
 // are loaded before any is used.  The plane sum is accumulated per thread in a
-// fixed order, reduced over the wave on DPP and over the four waves through
+// fixed order, reduced over the wave on DPP and over the waves through
 // LDS, so the result does not vary from run to run.
 template <bool AFF, bool RELU, bool RES, bool POOL>
-__global__ __launch_bounds__(256) void affine_planes_vec(const float* __restrict__ X, const float* __restrict__ scale,
+__global__ __launch_bounds__(kThreads) void affine_planes_vec(const float* __restrict__ X, const float* __restrict__ scale,
                                                          const float* __restrict__ shift, const float* __restrict__ R,
                                                          float* __restrict__ out, int C, int HW) {
     __shared__ float slots[16];
@@ -38,18 +39,18 @@ __global__ __launch_bounds__(256) void affine_planes_vec(const float* __restrict
     float* o = POOL ? nullptr : out + p * (int64_t)HW;
     const int nv = HW >> 2;
     float4v acc = {0.f, 0.f, 0.f, 0.f};
-    for (int base = 0; base < nv; base += 256 * kUnroll) {
+    for (int base = 0; base < nv; base += kThreads * kUnroll) {
         float4v xv[kUnroll], rv[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * 256 + threadIdx.x;
+            const int j = base + u * kThreads + threadIdx.x;
             const bool ok = j < nv;
             xv[u] = ok ? load4_nt(x + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
             if (RES) rv[u] = ok ? load4_nt(r + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * 256 + threadIdx.x;
+            const int j = base + u * kThreads + threadIdx.x;
             if (j < nv) {
                 float4v t = chain<AFF, RELU, RES>(xv[u], rv[u], sc, sh);
                 if (POOL) acc = acc + t; else store4_nt(o + 4 * j, t);
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(256) void affine_planes_vec(const float* __restrict
         }
     }
     if (POOL) {
-        float s = block_reduce<OpSum, 4>((acc.x + acc.y) + (acc.z + acc.w), slots);
+        float s = block_reduce<OpSum, kThreads / kWave>((acc.x + acc.y) + (acc.z + acc.w), slots);
         if (threadIdx.x == 0) out[p] = s / (float)HW;
     }
 }
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(256) void affine_planes_any(const float* __restrict
 
 template <bool AFF, bool RELU, bool RES>
 hipError_t launch_vec(const AffineParams& p, hipStream_t stream) {
-    dim3 grid((unsigned)p.planes), block(256);
+    dim3 grid((unsigned)p.planes), block(kThreads);
     if (p.pool)
         hipLaunchKernelGGL((affine_planes_vec<AFF, RELU, RES, true>), grid, block, 0, stream, p.X, p.scale, p.shift, p.R,
                            p.out, p.C, p.HW);
@@ -104,7 +105,7 @@ hipError_t launch_vec(const AffineParams& p, hipStream_t stream) {
 LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool) {
     LaunchShape s{};
     s.grid[0] = (uint32_t)planes; s.grid[1] = s.grid[2] = 1;
-    s.block[0] = 256; s.block[1] = s.block[2] = 1;
+    s.block[0] = HW % 4 == 0 ? kThreads : 256; s.block[1] = s.block[2] = 1;
     s.lds_bytes = 64;
     if (HW % 4 == 0) s.kernel = pool ? "affine_planes_vec<pool>" : "affine_planes_vec<store>";
     else s.kernel = pool ? "affine_planes_any<pool>" : "affine_planes_any<store>";

@@ -65,6 +65,70 @@ __global__ __launch_bounds__(256) void layernorm_rows_vec(const float* __restric
     }
 }
 
+// Rows of 2048..4096 elements (VPT <= 4): a fixed grid of two work-groups per
+// CU walks the rows with stride gridDim.x.  gamma and beta stay in registers
+// for the whole kernel and the next row's loads are issued before the current
+// row is reduced, so HBM reads never wait for the reductions.
+constexpr int kPersistGrid = 512;  // 2 x 256 CUs
+
+template <int VPT, bool GELU>
+__global__ __launch_bounds__(256) void layernorm_rows_persist(const float* __restrict__ X, const float* __restrict__ gamma,
+                                                              const float* __restrict__ beta, float* __restrict__ Y,
+                                                              int64_t rows, int N, float eps) {
+    __shared__ float slots[16];
+    const int t = threadIdx.x;
+    const int nv = N >> 2;
+    float4v g[VPT], b[VPT], v[VPT], nx[VPT];
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int j = t + i * 256;
+        g[i] = (gamma && j < nv) ? load4(gamma + 4 * j) : float4v{1.f, 1.f, 1.f, 1.f};
+        b[i] = (beta && j < nv) ? load4(beta + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+    }
+    auto load_row = [&](int64_t row, float4v* dst) {
+        const float* x = X + row * (int64_t)N;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int j = t + i * 256;
+            dst[i] = j < nv ? load4_nt(x + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    int64_t row = blockIdx.x;
+    if (row >= rows) return;
+    load_row(row, v);
+    const float inv_n = 1.0f / (float)N;
+    for (; row < rows; row += gridDim.x) {
+        const int64_t nrow = row + gridDim.x;
+        if (nrow < rows) load_row(nrow, nx);
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+        const float mu = block_reduce<OpSum, 4>(s, slots) * inv_n;
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            float4v d = v[i] - mu;
+            if (t + i * 256 >= nv) d = float4v{0.f, 0.f, 0.f, 0.f};
+            v[i] = d;
+            q += (d.x * d.x + d.y * d.y) + (d.z * d.z + d.w * d.w);
+        }
+        const float var = block_reduce<OpSum, 4>(q, slots) * inv_n;
+        const float rstd = fast_rsq(var + eps);
+        float* y = Y + row * (int64_t)N;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int j = t + i * 256;
+            if (j < nv) {
+                float4v o = v[i] * rstd * g[i] + b[i];
+                if (GELU) { o.x = gelu_tanh(o.x); o.y = gelu_tanh(o.y); o.z = gelu_tanh(o.z); o.w = gelu_tanh(o.w); }
+                store4_nt(y + 4 * j, o);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) v[i] = nx[i];
+    }
+}
+
 // Any N: a work-group per row, three strided passes over the row (the second
 // and third are served by the caches for rows of moderate length).
 template <bool GELU>
@@ -121,6 +185,18 @@ LnPick pick(int32_t N) {
     return {0, 0};
 }
 
+template <int VPT>
+hipError_t launch_persist(const LayernormParams& p, hipStream_t stream) {
+    dim3 grid((unsigned)(p.rows < kPersistGrid ? p.rows : kPersistGrid)), block(256);
+    if (p.gelu)
+        hipLaunchKernelGGL((layernorm_rows_persist<VPT, true>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows,
+                           p.N, p.eps);
+    else
+        hipLaunchKernelGGL((layernorm_rows_persist<VPT, false>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows,
+                           p.N, p.eps);
+    return hipGetLastError();
+}
+
 template <int TPR, int VPT>
 hipError_t launch_vec(const LayernormParams& p, hipStream_t stream) {
     constexpr int RPB = 256 / TPR;
@@ -144,7 +220,10 @@ LaunchShape layernorm_shape(int64_t rows, int32_t N) {
     s.lds_bytes = 64;
     if (k.tpr == 0) { s.grid[0] = (uint32_t)rows; s.kernel = "layernorm_rows_any"; }
     else if (k.tpr == 64) { s.grid[0] = (uint32_t)((rows + 3) / 4); s.kernel = "layernorm_rows_vec<wave-per-row>"; }
-    else { s.grid[0] = (uint32_t)rows; s.kernel = "layernorm_rows_vec<group-per-row>"; }
+    else if (k.vpt <= 4) {
+        s.grid[0] = (uint32_t)(rows < kPersistGrid ? rows : kPersistGrid);
+        s.kernel = "layernorm_rows_persist";
+    } else { s.grid[0] = (uint32_t)rows; s.kernel = "layernorm_rows_vec<group-per-row>"; }
     return s;
 }
 
@@ -159,8 +238,8 @@ hipError_t layernorm_launch(const LayernormParams& p, hipStream_t stream) {
     }
     if (k.tpr == 256) {
         switch (k.vpt) {
-            case 2: return launch_vec<256, 2>(p, stream);
-            case 4: return launch_vec<256, 4>(p, stream);
+            case 2: return launch_persist<2>(p, stream);
+            case 4: return launch_persist<4>(p, stream);
             case 8: return launch_vec<256, 8>(p, stream);
             default: return launch_vec<256, 16>(p, stream);
         }

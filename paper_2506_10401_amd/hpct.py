@@ -166,6 +166,26 @@ class Plan:
         if st != HPCT_OK:
             raise HpctError(st, hpct_last_error())
 
+    def bind(self, inputs, outputs, stream=None):
+        """Marshal the pointer arrays once and return a zero-argument callable
+        that enqueues this plan on `stream` (default: the stream current now).
+        For launch loops where per-call Python overhead matters."""
+        import torch
+        for t in list(inputs) + list(outputs):
+            if not t.is_cuda or t.dtype != torch.float32:
+                raise HpctError(HPCT_ERR_BAD_DESC, "operands must be fp32 tensors in GPU memory")
+        lib = load()
+        ins = (C.c_void_p * max(1, len(inputs)))(*[t.data_ptr() for t in inputs])
+        outs = (C.c_void_p * max(1, len(outputs)))(*[t.data_ptr() for t in outputs])
+        s = C.c_void_p(torch.cuda.current_stream().cuda_stream if stream is None else stream)
+        h, fn, keep = self._h, lib.hpct_plan_launch, (list(inputs), list(outputs), self)
+
+        def go(_keep=keep):
+            st = fn(h, ins, outs, None, 0, s)
+            if st != HPCT_OK:
+                raise HpctError(st, hpct_last_error())
+        return go
+
     def launch(self, inputs, outputs, stream=None) -> None:
         """inputs / outputs: torch tensors on the GPU (fp32, laid out as described)."""
         import torch
@@ -191,8 +211,9 @@ def _sh(t) -> Tuple[int, ...]:
 
 
 # ---- the five chains ---------------------------------------------------------
-def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, stream=None) -> None:
-    """out = softmax_rows(relu(X @ W + bias)); relu / softmax / bias optional."""
+# Each chain has a *_plan function (descriptor -> cached Plan plus the operand
+# list in descriptor order) and a convenience function that launches it.
+def gemm_bias_relu_softmax_plan(X, W, bias, out, relu=True, softmax=True):
     M, K = _sh(X)
     N = _sh(W)[1]
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_RELU] if relu else [])
@@ -200,25 +221,41 @@ def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, stream=None
     plan = _cached(("gemm", M, K, N, tuple(epi), softmax), lambda: op_desc(
         HPCT_ANCHOR_GEMM, epi, HPCT_RED_SOFTMAX_LAST if softmax else HPCT_RED_NONE, 0,
         [_sh(t) for t in ins], [_sh(out)]))
+    return plan, ins
+
+
+def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, stream=None) -> None:
+    """out = softmax_rows(relu(X @ W + bias)); relu / softmax / bias optional."""
+    plan, ins = gemm_bias_relu_softmax_plan(X, W, bias, out, relu, softmax)
     plan.launch(ins, [out], stream)
 
 
-def scale_shift_relu_add_pool(X, scale, shift, R, out, relu=True, pool=True, stream=None) -> None:
-    """out[n,c] = mean_hw(relu(X*scale[c]+shift[c]) + R)  (pool=False: the full tensor)."""
+def scale_shift_relu_add_pool_plan(X, scale, shift, R, out, relu=True, pool=True):
     epi = ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + ([HPCT_EPI_RELU] if relu else []) + \
           ([HPCT_EPI_ADD_RESIDUAL] if R is not None else [])
     ins = [X] + ([scale, shift] if scale is not None else []) + ([R] if R is not None else [])
     plan = _cached(("affine", _sh(X), tuple(epi), pool), lambda: op_desc(
         HPCT_ANCHOR_NONE, epi, HPCT_RED_AVGPOOL_HW if pool else HPCT_RED_NONE, 0, [_sh(t) for t in ins], [_sh(out)]))
+    return plan, ins
+
+
+def scale_shift_relu_add_pool(X, scale, shift, R, out, relu=True, pool=True, stream=None) -> None:
+    """out[n,c] = mean_hw(relu(X*scale[c]+shift[c]) + R)  (pool=False: the full tensor)."""
+    plan, ins = scale_shift_relu_add_pool_plan(X, scale, shift, R, out, relu, pool)
     plan.launch(ins, [out], stream)
 
 
-def layernorm_gelu(X, gamma, beta, out, eps=1e-5, gelu=True, stream=None) -> None:
-    """out = gelu_tanh(layernorm(X) * gamma + beta)."""
+def layernorm_gelu_plan(X, gamma, beta, out, eps=1e-5, gelu=True):
     ins = [X] + ([gamma, beta] if gamma is not None else [])
     plan = _cached(("ln", _sh(X), gamma is not None, float(eps), gelu), lambda: op_desc(
         HPCT_ANCHOR_NONE, [HPCT_EPI_GELU_TANH] if gelu else [], HPCT_RED_LAYERNORM_LAST, 1,
         [_sh(t) for t in ins], [_sh(out)], eps=eps))
+    return plan, ins
+
+
+def layernorm_gelu(X, gamma, beta, out, eps=1e-5, gelu=True, stream=None) -> None:
+    """out = gelu_tanh(layernorm(X) * gamma + beta)."""
+    plan, ins = layernorm_gelu_plan(X, gamma, beta, out, eps, gelu)
     plan.launch(ins, [out], stream)
 
 
@@ -227,19 +264,29 @@ def softmax_rows(X, out, stream=None) -> None:
     plan.launch([X], [out], stream)
 
 
-def conv2d_bias_relu(inp, wt, bias, out, stride=1, pad=1, relu=True, stream=None) -> None:
-    """out = relu(conv2d_nchw(inp, wt) + bias[k])."""
+def conv2d_bias_relu_plan(inp, wt, bias, out, stride=1, pad=1, relu=True):
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_RELU] if relu else [])
     ins = [inp, wt] + ([bias] if bias is not None else [])
     plan = _cached(("conv", _sh(inp), _sh(wt), tuple(epi), stride, pad), lambda: op_desc(
         HPCT_ANCHOR_CONV2D_NCHW, epi, HPCT_RED_NONE, 0, [_sh(t) for t in ins], [_sh(out)],
         stride_hw=(stride, stride), pad_hw=(pad, pad)))
+    return plan, ins
+
+
+def conv2d_bias_relu(inp, wt, bias, out, stride=1, pad=1, relu=True, stream=None) -> None:
+    """out = relu(conv2d_nchw(inp, wt) + bias[k])."""
+    plan, ins = conv2d_bias_relu_plan(inp, wt, bias, out, stride, pad, relu)
     plan.launch(ins, [out], stream)
+
+
+def attention_plan(Q, K, V, out, scale=0.125):
+    plan = _cached(("attn", _sh(Q), _sh(K), float(scale)), lambda: op_desc(
+        HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, [HPCT_EPI_SCALE_CONST], HPCT_RED_NONE, 0,
+        [_sh(Q), _sh(K), _sh(V)], [_sh(out)], scale=scale))
+    return plan, [Q, K, V]
 
 
 def attention(Q, K, V, out, scale=0.125, stream=None) -> None:
     """out = softmax(scale * Q K^T) V per batch."""
-    plan = _cached(("attn", _sh(Q), _sh(K), float(scale)), lambda: op_desc(
-        HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, [HPCT_EPI_SCALE_CONST], HPCT_RED_NONE, 0,
-        [_sh(Q), _sh(K), _sh(V)], [_sh(out)], scale=scale))
-    plan.launch([Q, K, V], [out], stream)
+    plan, ins = attention_plan(Q, K, V, out, scale)
+    plan.launch(ins, [out], stream)

@@ -55,8 +55,8 @@ def cfg_desc(i):
 def test_the_five_workloads_plan_and_launch_shapes():
     want = {
         1: ("gemm_rows16<256>", (4, 1, 1), (256, 1, 1)),
-        2: ("affine_planes_vec<pool>", (2048, 1, 1), (256, 1, 1)),
-        3: ("layernorm_rows_vec<group-per-row>", (8192, 1, 1), (256, 1, 1)),
+        2: ("affine_planes_vec<pool>", (2048, 1, 1), (512, 1, 1)),
+        3: ("layernorm_rows_persist", (512, 1, 1), (256, 1, 1)),
         4: ("conv2d_nchw_mfma<3x3,pipelined>", (1568, 1, 1), (256, 1, 1)),
         5: ("attn_fwd_d64<ks2>", (16, 16, 1), (512, 1, 1)),
     }
