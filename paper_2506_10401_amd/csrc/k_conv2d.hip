@@ -10,12 +10,13 @@
 // accumulator register is stored as 32 consecutive pixels = 128 contiguous
 // bytes of the NCHW output.
 //
-// A work-group of four waves owns KT = 128 output channels x TP = 64
-// consecutive output pixels of one image; a wave owns 64 channels x 32 pixels.
+// A work-group of four waves owns KT (64 or 128) output channels x TP = 64
+// consecutive output pixels of one image; a wave owns KT/2 channels x 32 pixels.
 // Channels are processed CC at a time.  Per chunk the LDS holds
 //   * the input rows the tile touches, with their zero halo, per channel, and
 //   * for every output channel its CC*R*S weights in memory order (a plain
-//     copy of a contiguous piece of the KCRS tensor, row stride padded by 4).
+//     copy of a contiguous piece of the KCRS tensor, row stride padded against
+//     bank conflicts).
 // Both are double buffered: the global loads of chunk t+1 are issued before the
 // MFMAs of chunk t and written to the other buffer after them.
 //
@@ -30,7 +31,6 @@
 namespace hpct {
 namespace {
 
-constexpr int KT = 128;  // output channels per work-group
 constexpr int TP = 64;   // output pixels per work-group
 constexpr int kXcds = 8; // work-groups are dealt round-robin to this many L2 domains
 
@@ -44,12 +44,14 @@ struct ConvGeom {
     int ch_ld;     // LDS channel stride (floats)
 };
 
-template <int R, int CC> struct Cfg {
+template <int R, int CC, int KT> struct Cfg {
     static constexpr int TAPS = R * R;
     static constexpr int FPR = CC * TAPS;        // weight floats per output channel per chunk
     static constexpr int HALF = FPR / 2;         // MFMA steps per chunk
-    static constexpr int WLD = FPR + 4;          // LDS row stride of the weight stage
-    static constexpr int VW = HALF % 4 == 0 ? 4 : 2;  // A-fragment vector width
+    static constexpr int VW = HALF % 4 == 0 ? 4 : 2;  // A-fragment vector width (floats)
+    // LDS row stride of the weight stage.  128-bit fragment reads: FPR + 4 (16 lanes cover all 64 banks).
+    // 64-bit fragment reads: FPR + 2, an odd number of 8-byte words, so 32 lanes cover all 64 banks.
+    static constexpr int WLD = FPR + (VW == 4 ? 4 : 2);
     static constexpr int NV4 = KT * FPR / 4;     // float4 of weights per chunk
     static constexpr int WPT = (NV4 + 255) / 256;
     static constexpr int W_STAGE = KT * WLD;     // floats
@@ -59,11 +61,12 @@ template <int R, int CC> struct Cfg {
 // FAST: W % 4 == 0, C % CC == 0, K % KT == 0 and the staged input fits the
 // register-staged slots: aligned vector loads, no tails, software pipelined.
 // Otherwise every element is loaded with its own bounds test, chunk by chunk.
-template <int R, int CC, bool FAST>
+template <int R, int CC, int KT, bool FAST>
 __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict__ in, const float* __restrict__ wt,
                                                         const float* __restrict__ bias, float* __restrict__ out,
                                                         ConvGeom g, int relu) {
-    using cfg = Cfg<R, CC>;
+    using cfg = Cfg<R, CC, KT>;
+    constexpr int KB = KT / 64;  // 32-channel accumulator blocks per wave
     constexpr int TAPS = cfg::TAPS, FPR = cfg::FPR, HALF = cfg::HALF, WLD = cfg::WLD, VW = cfg::VW;
     constexpr int IN_PER_T = cfg::IN_PER_T, WPT = cfg::WPT;
     extern __shared__ __align__(16) float lds[];
@@ -75,16 +78,20 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
 
-    // consecutive tiles (same image, shared halo rows) go to the same L2 domain
-    int tile;
+    // work item = (pixel tile, channel block); consecutive items (same tile, then
+    // the next tile of the same image, sharing halo rows) go to the same L2 domain
+    const int kblocks = (g.K + KT - 1) / KT;
+    int item;
     {
+        const int items = g.tiles * kblocks;
         const int x = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
-        const int q = g.tiles / kXcds, r = g.tiles % kXcds;
-        tile = x * q + (x < r ? x : r) + j;
+        const int q = items / kXcds, r = items % kXcds;
+        item = x * q + (x < r ? x : r) + j;
     }
+    const int tile = item / kblocks;
     const int n = tile / g.tiles_per_img;
     const int p0 = (tile % g.tiles_per_img) * TP;
-    const int k0 = blockIdx.y * KT;
+    const int k0 = (item % kblocks) * KT;
     const int h_lo = p0 / g.Wo;  // first output row of the tile
     const int ih0 = h_lo - g.P;  // first staged input row
     const int HW = g.H * g.W;
@@ -144,8 +151,16 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         for (int i = 0; i < IN_PER_T; ++i)
             if (s_loff[i] >= 0) *reinterpret_cast<float4v*>(ib + s_loff[i]) = ireg[i];
 #pragma unroll
-        for (int i = 0; i < WPT; ++i)
-            if (w_goff[i] >= 0) *reinterpret_cast<float4v*>(wb + w_loff[i]) = wreg[i];
+        for (int i = 0; i < WPT; ++i) {
+            if (w_goff[i] >= 0) {
+                if (WLD % 4 == 0) {
+                    *reinterpret_cast<float4v*>(wb + w_loff[i]) = wreg[i];
+                } else {  // rows are only 8-byte aligned
+                    *reinterpret_cast<float2v*>(wb + w_loff[i]) = float2v{wreg[i].x, wreg[i].y};
+                    *reinterpret_cast<float2v*>(wb + w_loff[i] + 2) = float2v{wreg[i].z, wreg[i].w};
+                }
+            }
+        }
     };
     // ---- general staging: every element with its own bounds test ----------------
     auto copy_chunk = [&](int buf, int c0) {
@@ -172,7 +187,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     };
 
     // ---- per-lane fragment addresses -------------------------------------------
-    const int kb0 = (wave & 1) * 64;  // this wave's 64 output channels inside the tile
+    const int kb0 = (wave & 1) * (KT / 2);  // this wave's output channels inside the tile
     const int pb = (wave >> 1) * 32;  // this wave's 32 pixels inside the tile
     int p = p0 + pb + l32;
     const bool p_ok = p < g.HoWo;
@@ -182,34 +197,37 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     const int b_base = half * (CC / 2) * g.ch_ld + (oh - h_lo) * g.ldw + ow + g.lpad;
     const int a_base = (kb0 + l32) * WLD + half * HALF;
 
-    float16v acc[2];
+    float16v acc[KB];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { acc[0][i] = 0.f; acc[1][i] = 0.f; }
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
 
     auto compute = [&](int cur) {
         const float* bI = inS(cur) + b_base;
         const float* aW = wS(cur) + a_base;
 #pragma unroll
         for (int j = 0; j < HALF / VW; ++j) {
-            float a0[VW], a1[VW];
-            if (VW == 4) {
-                const float4v t0 = *reinterpret_cast<const float4v*>(aW + VW * j);
-                const float4v t1 = *reinterpret_cast<const float4v*>(aW + 32 * WLD + VW * j);
+            float a[KB][VW];
 #pragma unroll
-                for (int e = 0; e < VW; ++e) { a0[e] = t0[e]; a1[e] = t1[e]; }
-            } else {
-                const float2v t0 = *reinterpret_cast<const float2v*>(aW + VW * j);
-                const float2v t1 = *reinterpret_cast<const float2v*>(aW + 32 * WLD + VW * j);
+            for (int kb = 0; kb < KB; ++kb) {
+                if (VW == 4) {
+                    const float4v t = *reinterpret_cast<const float4v*>(aW + kb * 32 * WLD + VW * j);
 #pragma unroll
-                for (int e = 0; e < VW; ++e) { a0[e] = t0[e]; a1[e] = t1[e]; }
+                    for (int e = 0; e < VW; ++e) a[kb][e] = t[e];
+                } else {
+                    const float2v t = *reinterpret_cast<const float2v*>(aW + kb * 32 * WLD + VW * j);
+#pragma unroll
+                    for (int e = 0; e < VW; ++e) a[kb][e] = t[e];
+                }
             }
 #pragma unroll
             for (int e = 0; e < VW; ++e) {
                 const int s = VW * j + e;  // MFMA step inside the chunk
                 const int c = s / TAPS, tap = s % TAPS;
                 const float b = bI[c * g.ch_ld + (tap / R) * g.ldw + (tap % R)];
-                acc[0] = mfma_32x32x2(a0[e], b, acc[0]);
-                acc[1] = mfma_32x32x2(a1[e], b, acc[1]);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) acc[kb] = mfma_32x32x2(a[kb][e], b, acc[kb]);
             }
         }
     };
@@ -244,7 +262,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     // ---- epilogue: register r of lane holds channel 8*(r/4) + 4*half + r%4 of the block
     if (p_ok) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int kl = kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
@@ -277,33 +295,38 @@ ConvGeom geom(const ConvParams& p) {
     return g;
 }
 
-template <int R, int CC>
+template <int R, int CC, int KT>
 size_t lds_bytes(const ConvGeom& g) {
-    return (size_t)(2 * CC * g.ch_ld + 2 * Cfg<R, CC>::W_STAGE + KT) * 4;
+    return (size_t)(2 * CC * g.ch_ld + 2 * Cfg<R, CC, KT>::W_STAGE + KT) * 4;
 }
 
-// input channels per LDS chunk: 4 keeps a work-group near 50 KB of LDS, so
-// three work-groups share a CU and hide each other's staging
+// Input channels per LDS chunk and output channels per work-group.  4 x 64
+// keeps a work-group near 30 KB of LDS (five per CU hide each other's staging
+// and barriers) and makes the work items small enough to balance over 256 CUs.
 constexpr int kCC = 4;
+constexpr int kKT = 64;
 
-template <int R, int CC>
+template <int R>
 bool fast_ok(const ConvParams& p, const ConvGeom& g) {
-    return p.W % 4 == 0 && p.C % CC == 0 && p.K % KT == 0 &&
-           CC * g.rows_max * (g.ldw / 4) <= 256 * Cfg<R, CC>::IN_PER_T;
+    return p.W % 4 == 0 && p.C % kCC == 0 && p.K % kKT == 0 &&
+           kCC * g.rows_max * (g.ldw / 4) <= 256 * Cfg<R, kCC, kKT>::IN_PER_T;
 }
 
-template <int R, int CC, bool FAST>
+int conv_items(const ConvParams& p, const ConvGeom& g) { return g.tiles * ((p.K + kKT - 1) / kKT); }
+
+template <int R, bool FAST>
 hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
-    const size_t lds = lds_bytes<R, CC>(g);
+    const size_t lds = lds_bytes<R, kCC, kKT>(g);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, CC, FAST>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, kCC, kKT, FAST>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((unsigned)g.tiles, (unsigned)((p.K + KT - 1) / KT)), block(256);
-    hipLaunchKernelGGL((conv2d_nchw_mfma<R, CC, FAST>), grid, block, lds, stream, p.in, p.wt, p.bias, p.out, g, p.relu);
+    dim3 grid((unsigned)conv_items(p, g)), block(256);
+    hipLaunchKernelGGL((conv2d_nchw_mfma<R, kCC, kKT, FAST>), grid, block, lds, stream, p.in, p.wt, p.bias, p.out, g,
+                       p.relu);
     return hipGetLastError();
 }
 
@@ -318,7 +341,7 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
     ConvParams p{};
     p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1;
     const ConvGeom g = geom(p);
-    const size_t lds = R == 3 ? lds_bytes<3, kCC>(g) : lds_bytes<1, kCC>(g);
+    const size_t lds = R == 3 ? lds_bytes<3, kCC, kKT>(g) : lds_bytes<1, kCC, kKT>(g);
     if (lds > 160 * 1024) { *why = "the input rows of one 64-pixel tile do not fit in LDS (image too wide)"; return false; }
     return true;
 }
@@ -326,10 +349,10 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
 LaunchShape conv_shape(const ConvParams& p) {
     const ConvGeom g = geom(p);
     LaunchShape s{};
-    s.grid[0] = (uint32_t)g.tiles; s.grid[1] = (uint32_t)((p.K + KT - 1) / KT); s.grid[2] = 1;
+    s.grid[0] = (uint32_t)conv_items(p, g); s.grid[1] = 1; s.grid[2] = 1;
     s.block[0] = 256; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)(p.R == 3 ? lds_bytes<3, kCC>(g) : lds_bytes<1, kCC>(g));
-    const bool fast = p.R == 3 ? fast_ok<3, kCC>(p, g) : fast_ok<1, kCC>(p, g);
+    s.lds_bytes = (uint32_t)(p.R == 3 ? lds_bytes<3, kCC, kKT>(g) : lds_bytes<1, kCC, kKT>(g));
+    const bool fast = p.R == 3 ? fast_ok<3>(p, g) : fast_ok<1>(p, g);
     s.kernel = p.R == 3 ? (fast ? "conv2d_nchw_mfma<3x3,pipelined>" : "conv2d_nchw_mfma<3x3,general>")
                         : (fast ? "conv2d_nchw_mfma<1x1,pipelined>" : "conv2d_nchw_mfma<1x1,general>");
     return s;
@@ -337,9 +360,8 @@ LaunchShape conv_shape(const ConvParams& p) {
 
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream) {
     const ConvGeom g = geom(p);
-    if (p.R == 3)
-        return fast_ok<3, kCC>(p, g) ? launch_conv<3, kCC, true>(p, g, stream) : launch_conv<3, kCC, false>(p, g, stream);
-    return fast_ok<1, kCC>(p, g) ? launch_conv<1, kCC, true>(p, g, stream) : launch_conv<1, kCC, false>(p, g, stream);
+    if (p.R == 3) return fast_ok<3>(p, g) ? launch_conv<3, true>(p, g, stream) : launch_conv<3, false>(p, g, stream);
+    return fast_ok<1>(p, g) ? launch_conv<1, true>(p, g, stream) : launch_conv<1, false>(p, g, stream);
 }
 
 }  // namespace hpct
