@@ -3,11 +3,23 @@
 // Elementwise "add, relu", Reduction "softmax"; the fused Matmul ... Softmax
 // chain of its Section 5.3).
 //
-// A work-group of four waves owns 16 rows x BN columns of the output, so with
-// N <= BN a row's softmax never leaves the work-group.  The contraction runs on
-// v_mfma_f32_16x16x4_f32: each wave accumulates BN/64 16x16 blocks.  X and W
-// tiles of 32 k-values are staged through LDS, double buffered: the global
-// loads of tile t+1 are in flight while tile t is multiplied.
+// A work-group owns 16 rows x BN <= 256 columns of the output, so with N <= BN
+// a row's softmax never leaves the work-group.  It has BN/64 column groups x 4
+// k-groups of waves: a wave multiplies its 16 x 64 output slab over a quarter
+// of K on v_mfma_f32_16x16x4_f32, with both operands loaded from global memory
+// straight into the MFMA register layout (no LDS staging, no barrier in the
+// k-loop, all loads of a 64-k step in flight at once).  The four k-groups'
+// partial sums are combined through LDS in a fixed order.  This shape is chosen
+// for small M, where only a handful of work-groups exist and the kernel is
+// bound by the latency of its load -> MFMA chain rather than by throughput.
+//
+// Register layout.  In a 16x16x4 MFMA lane l supplies A[l%16][l/16] and
+// B[l/16][l%16].  Lane quarter q = l/16 reads k = 4q..4q+3 of its A row with
+// one 128-bit load; step s (0..3) of a 16-k group therefore contracts
+// k = {s, 4+s, 8+s, 12+s} and its B fragment is W[4q+s][col].  The four 16x16
+// blocks of a wave are interleaved in columns: block b, lane column j is output
+// column 4j+b, so one 128-bit load of W[k][4j..4j+3] feeds all four blocks and
+// a lane ends up with four consecutive output columns per row.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -15,173 +27,194 @@ namespace hpct {
 namespace {
 
 constexpr int BM = 16;
-constexpr int BK = 32;
-constexpr int XS_LD = BK + 4;  // padded row of the X tile: conflict-free 128-bit fragment reads
+constexpr int KG = 4;   // k-groups of waves
 
-// k-permutation inside a group of 16 k-values: lane quarter q = lane/16 reads
-// k = 4q..4q+3 of the A row with one 128-bit LDS read; MFMA step t (t = 0..3)
-// therefore contracts k = {t, 4+t, 8+t, 12+t}.  The B fragment of step t is
-// W[4q + t][col], so both operands agree and the sum over k is complete after
-// the four steps.
 template <int BN, bool VEC>
-__global__ __launch_bounds__(256) void gemm_rows16(const float* __restrict__ X, const float* __restrict__ W,
-                                                   const float* __restrict__ bias, float* __restrict__ Y, int M, int K,
-                                                   int N, int relu, int softmax) {
-    constexpr int NB = BN / 64;        // 16-column blocks per wave
-    constexpr int WS_LD = BN + 4;      // 4*WS_LD % 64 == 16: the four lane quarters hit distinct banks
-    constexpr int WV = BK * BN / 4 / 256;  // float4 of the W tile per thread
-    __shared__ float Xs[2][BM * XS_LD];
-    __shared__ float Ws[2][BK * WS_LD];
-    __shared__ float red[4][BM];
+__global__ __launch_bounds__(BN * 4) void gemm_rows16(const float* __restrict__ X, const float* __restrict__ W,
+                                                      const float* __restrict__ bias, float* __restrict__ Y, int M, int K,
+                                                      int N, int relu, int softmax) {
+    constexpr int NG = BN / 64;  // column groups of waves
+    __shared__ float part[(KG - 1) * NG * 16 * 64];
+    __shared__ float red[NG][BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q = lane >> 4, l16 = lane & 15;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int ng = wave % NG, kg = wave / NG;
+    const int m0 = blockIdx.x * BM;
+    const int ncol = blockIdx.y * BN + ng * 64 + 4 * l16;  // first of this lane's four columns
+    const int mrow = m0 + l16;                             // A row this lane loads
 
-    // global -> register staging of one k-tile
-    float4v xg = {0.f, 0.f, 0.f, 0.f};
-    float4v wg[WV];
-    const int xr = tid >> 3, xc = (tid & 7) * 4;  // threads 0..127: X tile row / k offset
-    auto fetch = [&](int k0) {
-        if (tid < 128) {
-            const int m = m0 + xr, k = k0 + xc;
-            xg = float4v{0.f, 0.f, 0.f, 0.f};
-            if (m < M) {
-                const float* src = X + (int64_t)m * K + k;
-                if (VEC && k + 3 < K) xg = load4(src);
-                else {
-                    if (k < K) xg.x = src[0];
-                    if (k + 1 < K) xg.y = src[1];
-                    if (k + 2 < K) xg.z = src[2];
-                    if (k + 3 < K) xg.w = src[3];
-                }
+    // this wave's slice of K: a multiple of 16 per group
+    const int ks = ((K + KG - 1) / KG + 15) & ~15;
+    const int kbeg = kg * ks;
+    const int kend = kbeg + ks < K ? kbeg + ks : K;
+
+    float4v acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[b] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    // Loads are branch-free: a predicate picks between the real address and the
+    // tensor base (always readable) and the value is zeroed after every load of
+    // the step has been issued, so all 20 loads are in flight together.  With
+    // VEC (K % 4 == 0 and N % 4 == 0; kend is then a multiple of 4) a 4-vector
+    // is entirely inside or entirely outside.
+    constexpr int G = VEC ? 4 : 1;  // 16-k groups loaded together (the scalar path keeps fewer loads in registers)
+    for (int k0 = kbeg; k0 < kend; k0 += 16 * G) {
+        float4v a[G], w[G][4];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int k = k0 + 16 * g + 4 * q;
+            const float* src = X + (int64_t)mrow * K + k;
+            if (VEC) {
+                a[g] = load4((mrow < M && k < kend) ? src : X);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[g][e] = *((mrow < M && k + e < kend) ? src + e : X);
             }
-        }
-#pragma unroll
-        for (int i = 0; i < WV; ++i) {
-            const int v = tid + i * 256;
-            const int kr = v / (BN / 4), c = (v % (BN / 4)) * 4;
-            const int k = k0 + kr, n = n0 + c;
-            float4v t = {0.f, 0.f, 0.f, 0.f};
-            if (k < K) {
-                const float* src = W + (int64_t)k * N + n;
-                if (VEC && n + 3 < N) t = load4(src);
-                else {
-                    if (n < N) t.x = src[0];
-                    if (n + 1 < N) t.y = src[1];
-                    if (n + 2 < N) t.z = src[2];
-                    if (n + 3 < N) t.w = src[3];
-                }
-            }
-            wg[i] = t;
-        }
-    };
-    auto stash = [&](int buf) {
-        if (tid < 128) *reinterpret_cast<float4v*>(&Xs[buf][xr * XS_LD + xc]) = xg;
-#pragma unroll
-        for (int i = 0; i < WV; ++i) {
-            const int v = tid + i * 256;
-            const int kr = v / (BN / 4), c = (v % (BN / 4)) * 4;
-            *reinterpret_cast<float4v*>(&Ws[buf][kr * WS_LD + c]) = wg[i];
-        }
-    };
-
-    float4v acc[NB];
-#pragma unroll
-    for (int b = 0; b < NB; ++b) acc[b] = float4v{0.f, 0.f, 0.f, 0.f};
-
-    const int nt = (K + BK - 1) / BK;
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int t = 0; t < nt; ++t) {
-        const int cur = t & 1;
-        if (t + 1 < nt) fetch((t + 1) * BK);
-#pragma unroll
-        for (int g = 0; g < BK / 16; ++g) {
-            const float4v a = *reinterpret_cast<const float4v*>(&Xs[cur][l16 * XS_LD + g * 16 + q * 4]);
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const float* wrow = &Ws[cur][(g * 16 + q * 4 + s) * WS_LD + wave * (BN / 4) + l16];
+                const float* wsrc = W + (int64_t)(k + s) * N + ncol;
+                if (VEC) {
+                    w[g][s] = load4((k + s < kend && ncol < N) ? wsrc : W);
+                } else {
 #pragma unroll
-                for (int b = 0; b < NB; ++b) acc[b] = mfma_16x16x4(a[s], wrow[b * 16], acc[b]);
+                    for (int e = 0; e < 4; ++e) w[g][s][e] = *((k + s < kend && ncol + e < N) ? wsrc + e : W);
+                }
             }
         }
-        if (t + 1 < nt) stash(cur ^ 1);
-        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);  // every load of the step is issued before anything uses one
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int k = k0 + 16 * g + 4 * q;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (!(mrow < M && k + e < kend)) a[g][e] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (!(k + s < kend && ncol + e < N)) w[g][s][e] = 0.f;
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[b] = mfma_16x16x4(a[g][s], w[g][s][b], acc[b]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
-    // epilogue: lane holds rows 4q..4q+3 (register r) of column col(b) per block
-    float bv[NB];
-    bool cok[NB];
+    // ---- combine the k-groups: groups 1..3 publish, group 0 adds them in order
+    if (kg > 0) {
+        float* dst = part + ((kg - 1) * NG + ng) * 16 * 64 + lane;
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int n = n0 + wave * (BN / 4) + b * 16 + l16;
-        cok[b] = n < N;
-        bv[b] = (bias && cok[b]) ? bias[n] : 0.f;
-        acc[b] = acc[b] + bv[b];
-        if (relu) {
-            acc[b].x = fmaxf(acc[b].x, 0.f); acc[b].y = fmaxf(acc[b].y, 0.f);
-            acc[b].z = fmaxf(acc[b].z, 0.f); acc[b].w = fmaxf(acc[b].w, 0.f);
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dst[(b * 4 + r) * 64] = acc[b][r];
+    }
+    __syncthreads();
+    const bool lead = kg == 0;
+    if (lead) {
+#pragma unroll
+        for (int g2 = 0; g2 < KG - 1; ++g2) {
+            const float* src = part + (g2 * NG + ng) * 16 * 64 + lane;
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[b][r] += src[(b * 4 + r) * 64];
         }
     }
-    if (softmax) {
-        // row max over the 16 lanes of a DPP row, the NB blocks and the four waves
-        float4v mx = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+
+    // ---- epilogue (lead waves): lane holds rows 4q..4q+3 (register r) of columns ncol..ncol+3 (block b)
+    bool cok[4];
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
-            if (cok[b]) { mx.x = fmaxf(mx.x, acc[b].x); mx.y = fmaxf(mx.y, acc[b].y); mx.z = fmaxf(mx.z, acc[b].z); mx.w = fmaxf(mx.w, acc[b].w); }
+    for (int b = 0; b < 4; ++b) cok[b] = ncol + b < N;
+    if (lead) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            float v = mx[r];
-            v = fmaxf(v, dpp_mov<0xB1>(v)); v = fmaxf(v, dpp_mov<0x4E>(v));
-            v = fmaxf(v, dpp_mov<0x141>(v)); v = fmaxf(v, dpp_mov<0x140>(v));
-            mx[r] = v;
+        for (int b = 0; b < 4; ++b) {
+            const float bv = (bias && cok[b]) ? bias[ncol + b] : 0.f;
+            acc[b] = acc[b] + bv;
+            if (relu) {
+                acc[b].x = fmaxf(acc[b].x, 0.f); acc[b].y = fmaxf(acc[b].y, 0.f);
+                acc[b].z = fmaxf(acc[b].z, 0.f); acc[b].w = fmaxf(acc[b].w, 0.f);
+            }
         }
-        if (l16 == 0) {
+    }
+    if (softmax) {  // uniform over the work-group: every wave reaches the barriers
+        float4v mx = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (lead) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) red[wave][q * 4 + r] = mx[r];
+            for (int b = 0; b < 4; ++b)
+                if (cok[b]) { mx.x = fmaxf(mx.x, acc[b].x); mx.y = fmaxf(mx.y, acc[b].y); mx.z = fmaxf(mx.z, acc[b].z); mx.w = fmaxf(mx.w, acc[b].w); }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {  // over the 16 lanes that share a row
+                float v = mx[r];
+                v = fmaxf(v, dpp_mov<0xB1>(v)); v = fmaxf(v, dpp_mov<0x4E>(v));
+                v = fmaxf(v, dpp_mov<0x141>(v)); v = fmaxf(v, dpp_mov<0x140>(v));
+                mx[r] = v;
+            }
+            if (l16 == 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) red[ng][q * 4 + r] = mx[r];
+            }
         }
         __syncthreads();
         float4v sum = {0.f, 0.f, 0.f, 0.f};
+        if (lead) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = q * 4 + r;
-            const float m = fmaxf(fmaxf(red[0][row], red[1][row]), fmaxf(red[2][row], red[3][row]));
+            for (int r = 0; r < 4; ++r) {
+                const int row = q * 4 + r;
+                float m = red[0][row];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const float e = cok[b] ? fast_exp2((acc[b][r] - m) * kLog2e) : 0.f;
-                acc[b][r] = e;
-                sum[r] += e;
+                for (int g2 = 1; g2 < NG; ++g2) m = fmaxf(m, red[g2][row]);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const float e = cok[b] ? fast_exp2((acc[b][r] - m) * kLog2e) : 0.f;
+                    acc[b][r] = e;
+                    sum[r] += e;
+                }
             }
         }
         __syncthreads();
+        if (lead) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            float v = sum[r];
-            v += dpp_mov<0xB1>(v); v += dpp_mov<0x4E>(v); v += dpp_mov<0x141>(v); v += dpp_mov<0x140>(v);
-            sum[r] = v;
-        }
-        if (l16 == 0) {
+            for (int r = 0; r < 4; ++r) {
+                float v = sum[r];
+                v += dpp_mov<0xB1>(v); v += dpp_mov<0x4E>(v); v += dpp_mov<0x141>(v); v += dpp_mov<0x140>(v);
+                sum[r] = v;
+            }
+            if (l16 == 0) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) red[wave][q * 4 + r] = sum[r];
+                for (int r = 0; r < 4; ++r) red[ng][q * 4 + r] = sum[r];
+            }
         }
         __syncthreads();
+        if (lead) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = q * 4 + r;
-            const float inv = 1.0f / ((red[0][row] + red[1][row]) + (red[2][row] + red[3][row]));
+            for (int r = 0; r < 4; ++r) {
+                const int row = q * 4 + r;
+                float t = red[0][row];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) acc[b][r] *= inv;
+                for (int g2 = 1; g2 < NG; ++g2) t += red[g2][row];
+                const float inv = 1.0f / t;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[b][r] *= inv;
+            }
         }
     }
+    if (lead) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int m = m0 + q * 4 + r;
-        if (m < M) {
+        for (int r = 0; r < 4; ++r) {
+            const int m = m0 + q * 4 + r;
+            if (m < M) {
+                float* dst = Y + (int64_t)m * N + ncol;
+                if (VEC && cok[3]) store4(dst, float4v{acc[0][r], acc[1][r], acc[2][r], acc[3][r]});
+                else {
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-                if (cok[b]) Y[(int64_t)m * N + n0 + wave * (BN / 4) + b * 16 + l16] = acc[b][r];
+                    for (int b = 0; b < 4; ++b)
+                        if (cok[b]) dst[b] = acc[b][r];
+                }
+            }
         }
     }
 }
@@ -190,7 +223,7 @@ int pick_bn(int32_t N) { return N <= 64 ? 64 : (N <= 128 ? 128 : 256); }
 
 template <int BN>
 hipError_t launch_bn(const GemmParams& p, hipStream_t stream) {
-    dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), block(256);
+    dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), block(BN * 4);
     const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
     if (vec)
         hipLaunchKernelGGL((gemm_rows16<BN, true>), grid, block, 0, stream, p.X, p.W, p.bias, p.Y, p.M, p.K, p.N, p.relu, p.softmax);
@@ -205,8 +238,8 @@ LaunchShape gemm_shape(int32_t M, int32_t, int32_t N, int32_t) {
     const int bn = pick_bn(N);
     LaunchShape s{};
     s.grid[0] = (uint32_t)((M + BM - 1) / BM); s.grid[1] = (uint32_t)((N + bn - 1) / bn); s.grid[2] = 1;
-    s.block[0] = 256; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)(2 * BM * XS_LD * 4 + 2 * BK * (bn + 4) * 4 + 4 * BM * 4);
+    s.block[0] = (uint32_t)(bn * 4); s.block[1] = s.block[2] = 1;
+    s.lds_bytes = (uint32_t)(((KG - 1) * (bn / 64) * 16 * 64 + (bn / 64) * BM) * 4);
     s.kernel = bn == 64 ? "gemm_rows16<64>" : (bn == 128 ? "gemm_rows16<128>" : "gemm_rows16<256>");
     return s;
 }
