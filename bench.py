@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU checker")
     ap.add_argument("--only", type=int, default=0, help="run a single chain (1..5) instead of all five")
+    ap.add_argument("--with-copy", action="store_true",
+                    help="after the timed region also launch the library's plain copy kernel on a 25 690 112-byte "
+                         "tensor (reference dispatches for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this operator library is a one-GPU hot path with no collectives; run it with --gpus 1",
@@ -139,6 +142,16 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    if args.with_copy:
+        # no epilogue, no reduction: the affine chain degenerates to out = X, a copy of known size
+        src = torch.empty(32, 64, 56, 56, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        plan, ins = hpct.scale_shift_relu_add_pool_plan(src, None, None, None, dst, relu=False, pool=False)
+        go = plan.bind(ins, [dst])
+        for _ in range(args.steps):
+            go()
+        torch.cuda.synchronize()
+
     per_op, fracs = [], []
     for i in which:
         avg_us = 1e3 * ev[i][0].elapsed_time(ev[i][1]) / args.steps
@@ -151,10 +164,12 @@ def main() -> int:
         per_op.append(dict(config=i, op=op["name"], kernel=kernels[i], bound=op["bound"], avg_us=round(avg_us, 3),
                            achieved=round(ach, 3), unit=unit, peak=peak, frac=round(ach / peak, 4),
                            buffer_sets=len(sets[i])))
+    for rec in per_op:
+        rec["hbm_traffic_bytes"] = recorded_traffic(rec["kernel"])
     dom = max(per_op, key=lambda r: r["avg_us"])
     dop = OPS[dom["config"]]
     roofline = dict(kernel=dom["kernel"], bound=dom["bound"], achieved=dom["achieved"], peak=dom["peak"], unit=dom["unit"],
-                    frac=dom["frac"], traffic=None, avg_us=dom["avg_us"],
+                    frac=dom["frac"], traffic=dom["hbm_traffic_bytes"], avg_us=dom["avg_us"],
                     algorithmic=dop["flop"] if dom["bound"] == "mfma" else dop["bytes"])
 
     out = dict(metric="per-op GB/s (memory-bound) or fp32 TFLOP/s (contraction) and % of MI355X peak",
@@ -171,6 +186,27 @@ def main() -> int:
         out["cpu_baseline"] = cpu_baseline(host, which)
     print(json.dumps(out))
     return 0
+
+
+def recorded_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed FETCH_SIZE / WRITE_SIZE summary, or None if there is no
+    record or the kernel's source file has changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_five_chains.md")
+    try:
+        for line in open(path):
+            if not line.startswith("TRAFFIC "):
+                continue
+            kv = dict(f.split("=", 1) for f in line.split()[1:])
+            if kv.get("kernel") != kernel:
+                continue
+            src = os.path.join(ROOT, "paper_2506_10401_amd", "csrc", kv["source"])
+            if hashlib.sha256(open(src, "rb").read()).hexdigest()[:16] != kv["sha256_16"]:
+                return None
+            return int(float(kv["bytes"]))
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(host, which):

@@ -16,10 +16,12 @@
 // Row max needs one exchange between the two lane halves per key block; row
 // sums stay per-half until the end.
 //
-// A wave owns 32 queries.  With KS = 2 the work-group has two wave groups that
-// take alternate 32-key halves of every staged block for the same queries and
-// merge their (m, l, O) states through LDS at the end, which puts two waves on
-// every SIMD so one wave's softmax overlaps the other's MFMAs.
+// A wave owns 32 queries.  A work-group has NQW query waves x KS key groups:
+// with KS = 2 the two key groups take alternate 32-key halves of every staged
+// block for the same queries and merge their (m, l, O) states through LDS at
+// the end, which puts two waves on every SIMD.  NQW = 4 (128 queries, eight
+// waves) measured faster than two 64-query groups per CU, which stage every
+// K/V block twice.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -29,20 +31,21 @@ namespace {
 constexpr int D = 64;
 constexpr int KB = 64;        // keys per staged block
 constexpr int QW = 32;        // queries per wave
-constexpr int QT = 4 * QW;    // queries per work-group
 constexpr int KLD = D + 4;    // K row stride in LDS: conflict-free 128-bit fragment reads
 constexpr int VLD = D + 8;    // V row stride: rows 4 apart land 32 banks apart
 constexpr float kNegBig = -1.0e30f;
+constexpr int kXcds = 8;      // work-groups are dealt round-robin to this many L2 domains
 
 __device__ __forceinline__ float xchg_half(float v) {  // value held by lane ^ 32
     return __shfl_xor(v, 32, 64);
 }
 
-template <int KS>
-__global__ __launch_bounds__(256 * KS) void attn_fwd_d64(const float* __restrict__ Q, const float* __restrict__ K,
+template <int KS, int NQW>
+__global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __restrict__ Q, const float* __restrict__ K,
                                                          const float* __restrict__ V, float* __restrict__ O, int Lq,
                                                          int Lk, float scale_log2e) {
-    constexpr int NT = 256 * KS;
+    constexpr int NT = 64 * NQW * KS;
+    constexpr int QT = NQW * QW;                // queries per work-group
     constexpr int SUB = 2 / KS;                 // 32-key sub-blocks per wave per staged block
     constexpr int LD4 = KB * D / 4 / NT;        // float4 per thread per matrix per block
     extern __shared__ __align__(16) float lds[];
@@ -51,9 +54,19 @@ __global__ __launch_bounds__(256 * KS) void attn_fwd_d64(const float* __restrict
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int qwave = wave & 3, kgrp = wave >> 2;
-    const int b = blockIdx.y;
-    const int q0 = blockIdx.x * QT + qwave * QW;
+    const int qwave = wave % NQW, kgrp = wave / NQW;
+    // work item = (batch, query block); consecutive items share a batch's K/V and
+    // are dealt to the same L2 domain, so each K/V block is fetched from HBM once
+    const int nqb = (Lq + QT - 1) / QT;
+    int item;
+    {
+        const int items = gridDim.x;
+        const int x = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
+        const int qq = items / kXcds, r = items % kXcds;
+        item = x * qq + (x < r ? x : r) + j;
+    }
+    const int b = item / nqb;
+    const int q0 = (item % nqb) * QT + qwave * QW;
     const float* Kb = K + (int64_t)b * Lk * D;
     const float* Vb = V + (int64_t)b * Lk * D;
 
@@ -205,8 +218,11 @@ __global__ __launch_bounds__(256 * KS) void attn_fwd_d64(const float* __restrict
 }
 
 constexpr int kKS = 2;
+constexpr int kNQW = 4;
+constexpr int kQT = kNQW * QW;
 constexpr size_t kLds = (size_t)(2 * KB * KLD + 2 * KB * VLD) * 4;
-static_assert(kLds >= 4 * 34 * 64 * 4, "merge area must fit in the stage buffers");
+static_assert(kLds >= kNQW * 34 * 64 * 4, "merge area must fit in the stage buffers");
+static_assert(KB * D / 4 % (64 * kNQW * kKS) == 0, "staging loop must divide evenly");
 
 }  // namespace
 
@@ -217,8 +233,8 @@ bool attn_supported(int32_t d, const char** why) {
 
 LaunchShape attn_shape(const AttnParams& p) {
     LaunchShape s{};
-    s.grid[0] = (uint32_t)((p.Lq + QT - 1) / QT); s.grid[1] = (uint32_t)p.B; s.grid[2] = 1;
-    s.block[0] = 256 * kKS; s.block[1] = s.block[2] = 1;
+    s.grid[0] = (uint32_t)(((p.Lq + kQT - 1) / kQT) * p.B); s.grid[1] = 1; s.grid[2] = 1;
+    s.block[0] = 64 * kNQW * kKS; s.block[1] = s.block[2] = 1;
     s.lds_bytes = (uint32_t)kLds;
     s.kernel = "attn_fwd_d64<ks2>";
     return s;
@@ -227,13 +243,13 @@ LaunchShape attn_shape(const AttnParams& p) {
 hipError_t attn_launch(const AttnParams& p, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_d64<kKS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_d64<kKS, kNQW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((unsigned)((p.Lq + QT - 1) / QT), (unsigned)p.B), block(256 * kKS);
-    hipLaunchKernelGGL((attn_fwd_d64<kKS>), grid, block, kLds, stream, p.Q, p.K, p.V, p.O, p.Lq, p.Lk,
+    dim3 grid((unsigned)(((p.Lq + kQT - 1) / kQT) * p.B)), block(64 * kNQW * kKS);
+    hipLaunchKernelGGL((attn_fwd_d64<kKS, kNQW>), grid, block, kLds, stream, p.Q, p.K, p.V, p.O, p.Lq, p.Lk,
                        p.scale * kLog2e);
     return hipGetLastError();
 }
