@@ -46,8 +46,8 @@ OPS = {
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU checker")
     ap.add_argument("--only", type=int, default=0, help="run a single chain (1..5) instead of all five")
     ap.add_argument("--with-copy", action="store_true",

@@ -34,6 +34,7 @@ constexpr int QW = 32;        // queries per wave
 constexpr int KLD = D + 4;    // K row stride in LDS: conflict-free 128-bit fragment reads
 constexpr int VLD = D + 8;    // V row stride: rows 4 apart land 32 banks apart
 constexpr float kNegBig = -1.0e30f;
+constexpr float kSlack = 8.0f;  // log2 headroom of a probability before the softmax reference is moved
 constexpr int kXcds = 8;      // work-groups are dealt round-robin to this many L2 domains
 
 __device__ __forceinline__ float xchg_half(float v) {  // value held by lane ^ 32
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
     float16v o0, o1;  // O^T rows d = 0..31 and 32..63, column = this lane's query
 #pragma unroll
     for (int i = 0; i < 16; ++i) { o0[i] = 0.f; o1[i] = 0.f; }
-    float m = kNegBig;   // running max (log2 domain), same in both lane halves
+    float m = kNegBig;   // softmax reference (log2 domain), same in both lane halves; within kSlack of the running max
     float lsum = 0.f;    // running sum over this lane half's keys only
 
     const int nblocks = (Lk + KB - 1) / KB;
@@ -149,22 +150,29 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
             for (int r = 0; r < 16; ++r) bm = fmaxf(bm, s[u][r]);
         }
         bm = fmaxf(bm, xchg_half(bm));
-        const float m_new = fmaxf(m, bm);
-        const float alpha = fast_exp2(m - m_new);
-        m = m_new;
+        // The softmax reference m is moved only when a block exceeds it by more
+        // than kSlack (always at the first block, where m = kNegBig): probabilities
+        // stay below 2^kSlack, the result does not depend on the reference, and
+        // the 32-register accumulator rescale almost never runs.
+        if (__any(bm > m + kSlack)) {  // wave-uniform
+            const float m_new = fmaxf(m, bm);
+            const float alpha = fast_exp2(m - m_new);
+            m = m_new;
+            lsum *= alpha;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { o0[i] *= alpha; o1[i] *= alpha; }
+        }
         float ps = 0.f;
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(s[u][r] - m_new);
+                const float p = fast_exp2(s[u][r] - m);
                 s[u][r] = p;
                 ps += p;
             }
         }
-        lsum = lsum * alpha + ps;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { o0[i] *= alpha; o1[i] *= alpha; }
+        lsum += ps;
         // ---- O^T += V^T P^T ---------------------------------------------------------
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
