@@ -152,6 +152,34 @@ def main() -> int:
             go()
         torch.cuda.synchronize()
 
+    # ---- layout transforms (Table 1 LayoutTransform class; outside the step and the headline value)
+    layout_ops = []
+    if not args.only:
+        def time_layout(name, views, outs, nbytes):
+            calls_l = []
+            for v, o in zip(views, outs):
+                plan, ins = hpct.layout_transform_plan(v, o)
+                calls_l.append(plan.bind(ins, [o]))
+            for k in range(min(args.warmup, 10)):
+                calls_l[k % len(calls_l)]()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for k in range(args.steps):
+                calls_l[k % len(calls_l)]()
+            e1.record()
+            torch.cuda.synchronize()
+            us = 1e3 * e0.elapsed_time(e1) / args.steps
+            layout_ops.append(dict(op=name, kernel=plan.kernel_name, avg_us=round(us, 3), achieved=round(nbytes / us / 1e3, 1),
+                                   unit="GB/s", peak=HBM_PEAK_GBS, frac=round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                                   buffer_sets=len(calls_l)))
+        xs = [s["ins"][0] for s in sets[2]]                    # 11 NCHW tensors [32,64,56,56]
+        outs = [torch.empty(32, 56, 56, 64, device="cuda") for _ in xs]
+        time_layout("nchw_to_nhwc_32x64x56x56", [x.permute(0, 2, 3, 1) for x in xs], outs, 2 * xs[0].numel() * 4)
+        del outs
+        ms = [s["ins"][0] for s in sets[3]]                    # 3 matrices [8192,4096]
+        outs = [s["out"].view(4096, 8192) for s in sets[3]]    # reuse the layernorm outputs as destinations
+        time_layout("transpose_8192x4096", [m.t() for m in ms], outs, 2 * ms[0].numel() * 4)
+
     per_op, fracs = [], []
     for i in which:
         avg_us = 1e3 * ev[i][0].elapsed_time(ev[i][1]) / args.steps
@@ -180,7 +208,7 @@ def main() -> int:
                                     "layernorm+gelu 8192x4096, conv3x3 32x64x56x56->128, attention 16x2048x64"
                            if not args.only else "chain %d only" % args.only,
                            ops=len(which), hbm_cold_sets={str(i): len(sets[i]) for i in which}),
-               per_op=per_op, roofline=roofline)
+               per_op=per_op, roofline=roofline, layout_ops=layout_ops)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host, which)

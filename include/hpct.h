@@ -4,7 +4,8 @@
  * C ABI of the operator library.  One call describes a fused chain
  *     anchor contraction  ->  elementwise / broadcast epilogues  ->  row reduction
  * (operator classes of the paper's Table 1: ComputeIntensive "matmul, conv",
- * Elementwise "add, mul, relu", Reduction "sum, mean, softmax"; fused examples
+ * Elementwise "add, mul, relu", Reduction "sum, mean, softmax", LayoutTransform
+ * "reshape, transpose"; fused examples
  * of its Section 5.3) with an op descriptor; the library validates it, picks a
  * hand-written HIP kernel and enqueues exactly one kernel per launch on the
  * caller's stream.
@@ -12,7 +13,8 @@
  * Conventions
  *  - All tensors are fp32, described by shape and stride in ELEMENTS.
  *  - Every data pointer passed to hpct_plan_launch is a DEVICE pointer owned
- *    by the caller, 16-byte aligned.  Descriptors, plans and the pointer
+ *    by the caller, 16-byte aligned (4-byte aligned suffices for a layout
+ *    transform, whose input may be a view that starts anywhere).  Descriptors, plans and the pointer
  *    arrays themselves live in HOST memory.
  *  - The library never allocates, frees, copies or synchronises device memory.
  *    Inputs are never written.  Outputs must not overlap inputs.
@@ -31,6 +33,8 @@
  *   NONE  LAYERNORM_LAST (reduce_before_epi=1)        X[M,N], gamma[N], beta[N]     [M,N]
  *         [+GELU_TANH]
  *   NONE  SOFTMAX_LAST                                X[M,N]                        [M,N]
+ *   NONE  (no epilogue, no reduction): layout         X: any strided view (stride   same shape,
+ *         transform, out = contiguous copy of X       >= 0, up to 6 dims)           contiguous
  *   CONV2D_NCHW [+BIAS_COL] [+RELU]                   in[N,C,H,W], wt[K,C,R,S],     [N,K,Ho,Wo]
  *                                                     bias[K]
  *   BGEMM_SOFTMAX_BGEMM (scores scaled by `scale`)    Q[B,L,D], K[B,Lk,D],          [B,L,D]
@@ -51,7 +55,7 @@ typedef enum {
     HPCT_ERR_NULL = 1,            /* a required pointer argument is NULL */
     HPCT_ERR_BAD_DESC = 2,        /* malformed descriptor: ndim, shape <= 0, negative stride, counts, overlap */
     HPCT_ERR_SHAPE_MISMATCH = 3,  /* operands of the chain do not agree in shape */
-    HPCT_ERR_ALIGNMENT = 4,       /* a device pointer is not 16-byte aligned */
+    HPCT_ERR_ALIGNMENT = 4,       /* a device pointer is not aligned as the chain requires */
     HPCT_ERR_UNSUPPORTED = 5,     /* well-formed, but no kernel covers it (chain, layout, size) */
     HPCT_ERR_WORKSPACE = 6,       /* workspace missing or smaller than hpct_plan_workspace_bytes */
     HPCT_ERR_HIP = 7              /* the HIP runtime refused the launch */

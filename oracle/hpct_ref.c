@@ -229,3 +229,22 @@ void ref_set_threads(int n) { if (n > 0) omp_set_num_threads(n); }
 int ref_max_threads(void) { return 1; }
 void ref_set_threads(int n) { (void)n; }
 #endif
+
+/* ---- LayoutTransform (Table 1: "reshape, transpose"): out = contiguous copy
+ * of a strided view.  out[i0]...[i_{nd-1}] (row-major over `shape`) =
+ * in[sum_d i_d * stride[d]] (strides in elements, >= 0).  Values are copied as
+ * 32-bit patterns, so the result is bit-exact by definition. */
+void ref_layout_copy(const uint32_t *in, int32_t nd, const int64_t *shape, const int64_t *stride, uint32_t *out)
+{
+    int64_t total = 1;
+    for (int32_t d = 0; d < nd; ++d) total *= shape[d];
+#pragma omp parallel for schedule(static)
+    for (int64_t lin = 0; lin < total; ++lin) {
+        int64_t rem = lin, off = 0;
+        for (int32_t d = nd - 1; d >= 0; --d) {
+            off += (rem % shape[d]) * stride[d];
+            rem /= shape[d];
+        }
+        out[lin] = in[off];
+    }
+}

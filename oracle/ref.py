@@ -34,6 +34,7 @@ def lib():
             "ref_gelu_tanh": [p, i64],
             "ref_conv2d_nchw_bias": [p, p, p] + [i64] * 9 + [p, p],
             "ref_attention": [p, p, p, i64, i64, i64, i64, dbl, p, p],
+            "ref_layout_copy": [p, C.c_int32, p, p, p],
             "ref_set_threads": [C.c_int],
         }
         for name, args in sig.items():
@@ -149,6 +150,20 @@ def attention(Q, K, V, scale, want_norm=False):
     Dn = np.empty_like(O) if want_norm else None
     lib().ref_attention(_ptr(Q), _ptr(K), _ptr(V), B, Lq, Lk, D, float(scale), _ptr(O), _ptr(Dn))
     return (O, Dn) if want_norm else O
+
+
+def layout_copy(base, shape, stride):
+    """Contiguous copy of the strided view (shape, stride in elements) of the
+    1-D fp32 array `base`; returned as fp32 with the input's bit patterns."""
+    base = np.ascontiguousarray(base, dtype=np.float32).reshape(-1)
+    nd = len(shape)
+    sh = (C.c_int64 * nd)(*[int(v) for v in shape])
+    st = (C.c_int64 * nd)(*[int(v) for v in stride])
+    assert all(v > 0 for v in shape) and all(v >= 0 for v in stride)
+    assert sum((a - 1) * b for a, b in zip(shape, stride)) < base.size
+    out = np.empty(tuple(int(v) for v in shape), dtype=np.float32)
+    lib().ref_layout_copy(_ptr(base), nd, sh, st, _ptr(out))
+    return out
 
 
 # -------------------------------------------------------------------- chains

@@ -26,7 +26,7 @@ hpct_status fail(hpct_status st, const char* fmt, ...) {
 
 void clear_err() { g_err[0] = 0; }
 
-enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn };
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout };
 
 constexpr int64_t kI32Max = 2147483647LL;
 
@@ -48,6 +48,7 @@ struct hpct_plan {
         SoftmaxParams sm;
         ConvParams conv;
         AttnParams attn;
+        LayoutParams layout;
     } u;
 };
 
@@ -210,6 +211,58 @@ hpct_status plan_affine(const hpct_op_desc& d, hpct_plan& p) {
     return HPCT_OK;
 }
 
+// LayoutTransform: no anchor, no epilogue, no reduction, one input that is any
+// strided view (stride >= 0), one contiguous output of the same shape.
+hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p) {
+    if (d.n_in != 1 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "a layout transform takes 1 input and 1 output");
+    const hpct_tensor_desc &I = d.in[0], &O = d.out[0];
+    if (I.ndim != O.ndim) return fail(HPCT_ERR_SHAPE_MISMATCH, "layout transform: input view and output must have the same shape");
+    for (int k = 0; k < I.ndim; ++k)
+        if (I.shape[k] != O.shape[k]) return fail(HPCT_ERR_SHAPE_MISMATCH, "layout transform: input view and output must have the same shape");
+    if (!contiguous(O)) return fail(HPCT_ERR_UNSUPPORTED, "layout transform: the output must be contiguous");
+    LayoutParams q{};
+    // collapse: drop extent-1 dimensions, merge neighbours that are contiguous with each other in the input
+    int nd = 0;
+    for (int k = 0; k < I.ndim; ++k) {
+        if (I.shape[k] == 1) continue;
+        if (nd > 0 && q.sin[nd - 1] == I.shape[k] * I.stride[k]) {
+            q.shape[nd - 1] *= I.shape[k];
+            q.sin[nd - 1] = I.stride[k];
+        } else {
+            q.shape[nd] = I.shape[k];
+            q.sin[nd] = I.stride[k];
+            ++nd;
+        }
+    }
+    if (nd == 0) { q.shape[0] = 1; q.sin[0] = 1; nd = 1; }
+    q.nd = nd;
+    q.total = 1;
+    for (int k = nd - 1; k >= 0; --k) { q.sout[k] = q.total; q.total *= q.shape[k]; }
+    const int a = nd - 1;
+    q.kind = 0;
+    q.bdim = -1;
+    if (q.sin[a] == 1 || q.shape[a] == 1) {
+        bool vec = q.shape[a] % 4 == 0 && q.sin[a] == 1;
+        for (int k = 0; k < a; ++k) vec = vec && q.sin[k] % 4 == 0;
+        q.kind = vec ? 1 : 0;
+    } else {
+        for (int k = 0; k < a; ++k)
+            if (q.sin[k] == 1) { q.bdim = k; q.kind = 2; break; }
+    }
+    if (q.kind == 2) {
+        // work-groups of the tiled transpose must fit a 32-bit grid
+        int64_t groups = ((q.shape[a] + 63) / 64) * ((q.shape[q.bdim] + 63) / 64);  // upper bound for every tile shape
+        for (int k = 0; k < a; ++k)
+            if (k != q.bdim) groups *= q.shape[k];
+        if (groups > kI32Max) q.kind = 0, q.bdim = -1;
+    }
+    p.kind = Kind::Layout;
+    p.u.layout = q;
+    p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = -1;
+    p.shape = layout_shape(q);
+    return HPCT_OK;
+}
+
 hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
     static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_RELU};
     bool has[2];
@@ -313,6 +366,8 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         case HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM: st = plan_attn(d, tmp); break;
         default:
             if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
+            else if (d.reduce == HPCT_RED_NONE && d.n_epi == 0 && d.n_in >= 1 &&
+                     !(d.in[0].ndim == 4 && contiguous(d.in[0]))) st = plan_layout(d, tmp);
             else st = plan_affine(d, tmp);
     }
     if (st != HPCT_OK) return st;
@@ -330,13 +385,16 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
     (void)workspace;
     (void)workspace_bytes;
     if (!plan || !in_ptrs || !out_ptrs) return fail(HPCT_ERR_NULL, "hpct_plan_launch: plan, in_ptrs and out_ptrs must not be NULL");
+    // layout transforms accept views that start anywhere (element alignment); their vector variant is
+    // replaced by the scalar one at launch when a base is not 16-byte aligned
+    const uintptr_t amask = plan->kind == Kind::Layout ? 3 : 15;
     for (int i = 0; i < plan->n_in; ++i) {
         if (!in_ptrs[i]) return fail(HPCT_ERR_NULL, "in_ptrs[%d] is NULL", i);
-        if ((uintptr_t)in_ptrs[i] & 15) return fail(HPCT_ERR_ALIGNMENT, "in_ptrs[%d] is not 16-byte aligned", i);
+        if ((uintptr_t)in_ptrs[i] & amask) return fail(HPCT_ERR_ALIGNMENT, "in_ptrs[%d] is not %d-byte aligned", i, (int)amask + 1);
     }
     for (int i = 0; i < plan->n_out; ++i) {
         if (!out_ptrs[i]) return fail(HPCT_ERR_NULL, "out_ptrs[%d] is NULL", i);
-        if ((uintptr_t)out_ptrs[i] & 15) return fail(HPCT_ERR_ALIGNMENT, "out_ptrs[%d] is not 16-byte aligned", i);
+        if ((uintptr_t)out_ptrs[i] & amask) return fail(HPCT_ERR_ALIGNMENT, "out_ptrs[%d] is not %d-byte aligned", i, (int)amask + 1);
         const uintptr_t o0 = (uintptr_t)out_ptrs[i], o1 = o0 + (uintptr_t)plan->out_bytes[i];
         for (int k = 0; k < plan->n_in; ++k) {
             const uintptr_t a0 = (uintptr_t)in_ptrs[k], a1 = a0 + (uintptr_t)plan->in_bytes[k];
@@ -375,6 +433,13 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
             ConvParams q = plan->u.conv;
             q.in = in(0); q.wt = in(1); q.bias = in(2); q.out = (float*)out_ptrs[0];
             e = conv_launch(q, stream);
+            break;
+        }
+        case Kind::Layout: {
+            LayoutParams q = plan->u.layout;
+            q.in = in(0); q.out = (float*)out_ptrs[0];
+            if (q.kind == 1 && (((uintptr_t)q.in | (uintptr_t)q.out) & 15)) q.kind = 0;
+            e = layout_launch(q, stream);
             break;
         }
         case Kind::Attn: {

@@ -38,6 +38,21 @@ struct AffineParams {
 LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool);
 hipError_t affine_launch(const AffineParams& p, hipStream_t stream);
 
+// ---- layout transform: out = contiguous copy of a strided view (Table 1: LayoutTransform)
+constexpr int kLayoutDims = 6;
+struct LayoutParams {
+    const float* in; float* out;
+    int32_t nd;                      // collapsed dimensions, 1..kLayoutDims
+    int64_t shape[kLayoutDims];      // collapsed extents
+    int64_t sin[kLayoutDims];        // input strides (elements)
+    int64_t sout[kLayoutDims];       // output strides (contiguous)
+    int64_t total;                   // elements
+    int32_t kind;                    // 0 rows scalar, 1 rows vec4, 2 tiled transpose
+    int32_t bdim;                    // transpose: the dimension with input stride 1
+};
+LaunchShape layout_shape(const LayoutParams& p);
+hipError_t layout_launch(const LayoutParams& p, hipStream_t stream);
+
 // ---- GEMM + bias + relu (+ row softmax when the tile spans the whole row)
 struct GemmParams {
     const float* X; const float* W; const float* bias; float* Y;

@@ -264,6 +264,20 @@ def softmax_rows(X, out, stream=None) -> None:
     plan.launch([X], [out], stream)
 
 
+def layout_transform_plan(x_view, out):
+    """x_view: a (possibly non-contiguous) fp32 GPU tensor view; out: contiguous, same shape."""
+    shape, stride = _sh(x_view), tuple(int(v) for v in x_view.stride())
+    plan = _cached(("layout", shape, stride), lambda: op_desc(
+        HPCT_ANCHOR_NONE, [], HPCT_RED_NONE, 0, [tensor_desc(shape, stride)], [_sh(out)]))
+    return plan, [x_view]
+
+
+def layout_transform(x_view, out, stream=None) -> None:
+    """out = contiguous copy of the strided view x_view (transpose, NCHW <-> NHWC, slices, broadcasts)."""
+    plan, ins = layout_transform_plan(x_view, out)
+    plan.launch(ins, [out], stream)
+
+
 def conv2d_bias_relu_plan(inp, wt, bias, out, stride=1, pad=1, relu=True):
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_RELU] if relu else [])
     ins = [inp, wt] + ([bias] if bias is not None else [])

@@ -249,3 +249,29 @@ def test_launch_time_pointer_checks_return_before_any_launch():
     with pytest.raises(H.HpctError) as e:
         p.launch_ptrs([x, g, b], [g - nbytes + 16])  # output's tail reaches gamma
     assert e.value.status == H.HPCT_ERR_BAD_DESC
+
+
+def test_layout_transform_plans():
+    def plan(shape, stride):
+        return H.Plan(H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_NONE, 0, [H.tensor_desc(shape, stride)], [shape]))
+    # NCHW -> NHWC collapses to [N, HW, C] and is a tiled transpose of C against HW
+    p = plan((32, 56, 56, 64), (64 * 3136, 56, 1, 3136))
+    assert p.kernel_name == "layout_transpose<64x64>"
+    assert p.launch_shape()[0] == (32 * 49 * 1, 1, 1)  # 32 images x ceil(3136/64) x ceil(64/64) tiles
+    assert plan((32, 64, 64, 64), (64 * 4096, 64, 1, 4096)).kernel_name == "layout_transpose<64x128>"
+    assert plan((100, 200), (1, 100)).kernel_name == "layout_transpose<64x64>"
+    assert plan((4096, 8192), (1, 4096)).kernel_name == "layout_transpose<128x128>"
+    assert plan((8, 16, 32, 64), (16 * 32 * 64, 64, 16 * 64, 1)).kernel_name == "layout_rows<vec4>"
+    assert plan((5, 7), (0, 1)).kernel_name == "layout_rows<scalar>"
+    assert plan((4, 6, 8, 4), (6 * 8 * 12, 8 * 12, 12, 3)).kernel_name == "layout_rows<scalar>"  # no unit stride anywhere
+    # the output must be contiguous and of the view's shape
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_NONE, 0, [H.tensor_desc((4, 6), (1, 4))], [H.tensor_desc((4, 6), (1, 4))])
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_NONE, 0, [H.tensor_desc((4, 6), (1, 4))], [(6, 4)])
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    # overlap of the view's extent with the output is caught at launch, before any kernel
+    p = plan((100, 200), (1, 100))
+    base = 0x7F0000000000
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([base], [base + 16])
+    assert e.value.status == H.HPCT_ERR_BAD_DESC

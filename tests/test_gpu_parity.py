@@ -249,3 +249,40 @@ def test_launch_on_a_side_stream():
         hpct.layernorm_gelu(X, g, b, out)
     s.synchronize()
     assert compare.pointwise(out.cpu().numpy(), ref.chain3(t["X"], t["gamma"], t["beta"], 1e-5))
+
+
+# ---------------------------------------------------------- layout transform
+def _layout_case(base_shape, make_view):
+    """base tensor of base_shape -> strided torch view -> library copy vs the CPU checker, bit for bit."""
+    n = int(np.prod(base_shape))
+    base = datagen.gen_normal(4242, (n,), 0.0, 1.0)
+    tb = dev(base).reshape(base_shape)
+    view = make_view(tb)
+    out = torch.full(tuple(view.shape), float("nan"), device="cuda")
+    hpct.layout_transform(view, out)
+    off = (view.data_ptr() - tb.data_ptr()) // 4
+    want = ref.layout_copy(base[off:], tuple(view.shape), tuple(view.stride()))
+    got = host(out)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (base_shape, tuple(view.shape), tuple(view.stride()))
+
+
+def test_layout_nchw_to_nhwc_and_back_full_size():
+    _layout_case((32, 64, 56, 56), lambda t: t.permute(0, 2, 3, 1))   # NCHW -> NHWC
+    _layout_case((32, 56, 56, 64), lambda t: t.permute(0, 3, 1, 2))   # NHWC -> NCHW
+
+
+@pytest.mark.parametrize("shape,perm", [((100, 200), (1, 0)), ((1, 7), (1, 0)), ((65, 63), (1, 0)), ((3, 70, 130), (0, 2, 1)),
+                                        ((2, 3, 5, 7), (0, 2, 3, 1)), ((2, 3, 5, 7), (3, 2, 1, 0)), ((4, 8, 16, 64), (0, 2, 1, 3)),
+                                        ((2, 2, 2, 3, 4, 5), (5, 0, 3, 1, 4, 2)), ((6, 128), (0, 1))])
+def test_layout_permutations(shape, perm):
+    print("layout permute", shape, perm, flush=True)
+    _layout_case(shape, lambda t: t.permute(*perm))
+
+
+def test_layout_slices_and_broadcasts():
+    _layout_case((4, 6, 8, 12), lambda t: t[:, ::2, 1:7, :])          # strided window, inner contiguous
+    _layout_case((4, 6, 8, 12), lambda t: t[:, :, :, 4:8])            # inner slice: aligned vector path
+    _layout_case((4, 6, 8, 12), lambda t: t[:, :, :, 1:10:3])         # inner stride 3: scalar gather
+    _layout_case((1, 64), lambda t: t.expand(33, 64))                 # broadcast rows (stride 0)
+    _layout_case((64, 1), lambda t: t.expand(64, 20))                 # broadcast inner (stride 0)
+    _layout_case((5, 7, 9), lambda t: t)                              # contiguous, odd size

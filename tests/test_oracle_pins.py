@@ -448,3 +448,30 @@ def test_planted_mistakes_are_caught():
     erf_form = 0.5 * good * 0 + np.array([[0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in row]
                                          for row in ref.layernorm_rows(X, None, None, 1e-5)])
     assert not compare.pointwise(erf_form, good)
+
+
+# ---------------------------------------------------------- layout transform
+def test_layout_copy_against_numpy_views():
+    base = f32(rng.normal(size=2 * 3 * 4 * 5))
+    x = base.reshape(2, 3, 4, 5)
+    # NCHW -> NHWC: the view has shape [N,H,W,C] and strides of the permuted axes
+    v = np.transpose(x, (0, 2, 3, 1))
+    got = ref.layout_copy(base, v.shape, [s // 4 for s in v.strides])
+    assert np.array_equal(got.view(np.uint32), np.ascontiguousarray(v).view(np.uint32))
+    # 2-D transpose, element by element
+    m = f32(np.arange(12)).reshape(3, 4)
+    got = ref.layout_copy(m, (4, 3), (1, 4))
+    for i in range(4):
+        for j in range(3):
+            assert got[i, j] == m[j, i]
+    # strided slice and a broadcast (stride 0)
+    v = x[:, ::2, 1:3, :]
+    off = (v.__array_interface__["data"][0] - base.__array_interface__["data"][0]) // 4
+    got = ref.layout_copy(base[off:], v.shape, [s // 4 for s in v.strides])
+    assert np.array_equal(got, v)
+    got = ref.layout_copy(f32([1.5, 2.5]), (3, 2), (0, 1))
+    assert np.array_equal(got, np.array([[1.5, 2.5]] * 3, np.float32))
+    # bit patterns survive (NaN payload, -0)
+    odd = np.array([0x7FC12345, 0x80000000, 0x00000001], np.uint32).view(np.float32)
+    got = ref.layout_copy(odd, (3,), (1,))
+    assert np.array_equal(got.view(np.uint32), odd.view(np.uint32))
