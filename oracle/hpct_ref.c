@@ -248,3 +248,44 @@ void ref_layout_copy(const uint32_t *in, int32_t nd, const int64_t *shape, const
         out[lin] = in[off];
     }
 }
+
+/* ---- Hash-based dropout of the fused [Matmul, Dropout, Mean, Softmax] case
+ * study (Section 5.3, the listing generated after fine-tuning).  For the
+ * element at row i, column j of an [M,N] tensor
+ *     offset = i * N + j,  h = offset + seed   (unsigned 64-bit, wrapping)
+ *     h ^= h >> 17;  h ^= h << 31;  h ^= h >> 8;
+ *     rand = (float)(h % 1000) / 1000.0f        (fp32, as the paper computes it)
+ * The listing elides what is done with `rand`; the reading taken here is the
+ * usual training-mode dropout: the element is zeroed when rand < p (compared
+ * in fp32) and multiplied by 1 / (1 - p) otherwise. */
+float ref_dropout_rand(uint64_t h)
+{
+    h ^= h >> 17;
+    h ^= h << 31;
+    h ^= h >> 8;
+    return (float)(h % 1000u) / 1000.0f;
+}
+
+void ref_dropout_hash(double *Z, int64_t M, int64_t N, float p, uint64_t seed)
+{
+    const double keep_scale = 1.0 / (1.0 - (double)p);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            uint64_t offset = (uint64_t)i * (uint64_t)N + (uint64_t)j;
+            float rand_val = ref_dropout_rand(offset + seed);
+            Z[i * N + j] = rand_val < p ? 0.0 : Z[i * N + j] * keep_scale;
+        }
+    }
+}
+
+/* ---- Reduction: mean (Table 1) over the last dimension: out[r] = (1/N) sum_n Z[r][n]. */
+void ref_mean_rows(const double *Z, int64_t rows, int64_t N, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        double s = 0.0;
+        for (int64_t n = 0; n < N; ++n) s += Z[r * N + n];
+        out[r] = s / (double)N;
+    }
+}

@@ -36,11 +36,14 @@ def lib():
             "ref_attention": [p, p, p, i64, i64, i64, i64, dbl, p, p],
             "ref_layout_copy": [p, C.c_int32, p, p, p],
             "ref_set_threads": [C.c_int],
+            "ref_dropout_hash": [p, i64, i64, C.c_float, C.c_uint64],
+            "ref_mean_rows": [p, i64, i64, p],
         }
         for name, args in sig.items():
             f = getattr(_lib, name)
             f.argtypes, f.restype = args, None
         _lib.ref_max_threads.argtypes, _lib.ref_max_threads.restype = [], C.c_int
+        _lib.ref_dropout_rand.argtypes, _lib.ref_dropout_rand.restype = [C.c_uint64], C.c_float
     return _lib
 
 
@@ -166,6 +169,27 @@ def layout_copy(base, shape, stride):
     return out
 
 
+def dropout_rand(h: int) -> float:
+    """rand value the hash of Section 5.3 gives for h = offset + seed (fp32)."""
+    return float(lib().ref_dropout_rand(int(h) & 0xFFFFFFFFFFFFFFFF))
+
+
+def dropout_hash(Z, p, seed):
+    """Training-mode dropout of a 2-D fp64 array with the hash mask of Section 5.3."""
+    Z = np.array(Z, dtype=np.float64, order="C")
+    assert Z.ndim == 2
+    lib().ref_dropout_hash(_ptr(Z), Z.shape[0], Z.shape[1], float(np.float32(p)), int(seed) & 0xFFFFFFFFFFFFFFFF)
+    return Z
+
+
+def mean_rows(Z):
+    Z = np.ascontiguousarray(Z, dtype=np.float64)
+    N = Z.shape[-1]
+    out = np.empty(Z.shape[:-1], dtype=np.float64)
+    lib().ref_mean_rows(_ptr(Z), Z.size // N, N, _ptr(out))
+    return out
+
+
 # -------------------------------------------------------------------- chains
 def chain1(X, W, bias):
     """softmax_rows(relu(X @ W + bias))"""
@@ -191,3 +215,16 @@ def chain4(inp, wt, bias, stride=1, pad=1):
 def chain5(Q, K, V, scale=0.125):
     """softmax(scale * Q K^T) V and the second contraction's normaliser."""
     return attention(Q, K, V, scale, want_norm=True)
+
+
+def chain6(X, W, bias, p, seed, stop_after="softmax"):
+    """[Matmul, Dropout, Mean, Softmax] of Section 5.3: dropout(X @ W + bias), mean over the
+    feature axis (one value per row), softmax over those M values.  `stop_after` in
+    {"dropout", "mean", "softmax"} returns the intermediate of that name."""
+    Z = dropout_hash(gemm_bias(X, W, bias), p, seed)
+    if stop_after == "dropout":
+        return Z
+    mu = mean_rows(Z)
+    if stop_after == "mean":
+        return mu
+    return softmax_rows(mu.reshape(1, -1)).reshape(-1)

@@ -134,7 +134,21 @@ def chain5_specs(B=16, L=2048, D=64, Lk=None) -> Dict[str, Spec]:
             "V": (2, (B, Lk, D), "n", 0.0, 1.0)}
 
 
-CONFIGS = {1: chain1_specs, 2: chain2_specs, 3: chain3_specs, 4: chain4_specs, 5: chain5_specs}
+def chain6_specs(M=4096, K=1024, N=4096) -> Dict[str, Spec]:
+    """GEMM + bias + hash dropout + mean over features + softmax over the row means
+    (the fused group of the paper's first case study, Section 5.3); W ~ N(0, 1/sqrt(K))
+    keeps the pre-dropout activations at unit scale."""
+    return {"X": (0, (M, K), "n", 0.0, 1.0),
+            "W": (1, (K, N), "n", 0.0, 1.0 / math.sqrt(K)),
+            "bias": (2, (N,), "u", -0.5, 0.5)}
+
+
+# dropout probability and seed of workload 6 (scalars, not tensors)
+CHAIN6_P = 0.25
+CHAIN6_SEED = 0x2506_1040_1
+
+
+CONFIGS = {1: chain1_specs, 2: chain2_specs, 3: chain3_specs, 4: chain4_specs, 5: chain5_specs, 6: chain6_specs}
 
 
 def make(config_index: int, variant: int = 0, **dims) -> Dict[str, np.ndarray]:

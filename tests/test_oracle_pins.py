@@ -475,3 +475,101 @@ def test_layout_copy_against_numpy_views():
     odd = np.array([0x7FC12345, 0x80000000, 0x00000001], np.uint32).view(np.float32)
     got = ref.layout_copy(odd, (3,), (1,))
     assert np.array_equal(got.view(np.uint32), odd.view(np.uint32))
+
+
+# ------------------------------------------- hash dropout, mean (Section 5.3)
+def _hash_bigint(h):
+    """The three xor-shift steps in arbitrary-precision integers, reduced mod 2^64
+    only where a 64-bit register would drop bits (the left shift)."""
+    h ^= h >> 17
+    h ^= (h << 31) % (1 << 64)
+    h ^= h >> 8
+    return h
+
+
+def test_dropout_rand_matches_worked_values():
+    import json, os
+    cases = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "dropout_hash_cases.json")))["cases"]
+    for h0, want in cases:
+        assert ref.dropout_rand(h0) == np.float32(want) / np.float32(1000.0), h0
+    # shift directions and amounts: a one-bit input lands on the bits the three steps say
+    for bit in (0, 5, 17, 30, 33, 40, 63):
+        h0 = 1 << bit
+        assert ref.dropout_rand(h0) == np.float32(_hash_bigint(h0) % 1000) / np.float32(1000.0)
+
+
+def test_dropout_mask_uses_row_major_offset_plus_seed():
+    M, N, p = 6, 11, 0.5
+    ones = np.ones((M, N))
+    a = ref.dropout_hash(ones, p, 12345)
+    # element (i, j) depends on i*N + j only: the same data flattened to one row gives the same mask
+    b = ref.dropout_hash(np.ones((1, M * N)), p, 12345)
+    assert np.array_equal(a.reshape(-1), b.reshape(-1))
+    # ... and on offset + seed only: seed s is seed 0 shifted by s elements
+    c = ref.dropout_hash(np.ones((1, M * N + 7)), p, 12338)
+    assert np.array_equal(a.reshape(-1), c.reshape(-1)[7:])
+    # the mask itself, element by element, from the worked hash
+    for i in range(M):
+        for j in range(N):
+            r = np.float32(_hash_bigint(i * N + j + 12345) % 1000) / np.float32(1000.0)
+            assert a[i, j] == (0.0 if r < np.float32(p) else 2.0)
+    # a transposed offset (j*M + i) would give another mask
+    t = ref.dropout_hash(np.ones((N, M)), p, 12345).T
+    assert not np.array_equal(a, t)
+
+
+def test_dropout_limits_scale_and_rate():
+    Z = rng.normal(size=(50, 40))
+    assert np.array_equal(ref.dropout_hash(Z, 0.0, 99), Z)          # p = 0: nothing dropped, scale 1
+    out = ref.dropout_hash(Z, 0.25, 99)
+    kept = out != 0.0
+    assert np.allclose(out[kept], Z[kept] / 0.75, rtol=1e-15, atol=0)  # survivors scaled by 1/(1-p)
+    # rand takes the values u/1000, u = h % 1000; exactly those with u/1000 < p are dropped
+    big = ref.dropout_hash(np.ones((400, 500)), 0.25, 7)
+    rate = 1.0 - np.count_nonzero(big) / big.size
+    assert abs(rate - 0.25) < 5 * math.sqrt(0.25 * 0.75 / big.size)
+    # the boundary is strict: rand == p survives (p = 0.5 = 500/1000 exactly in fp32)
+    h0 = next(h for h in range(10**6) if _hash_bigint(h) % 1000 == 500)
+    assert ref.dropout_hash(np.ones((1, 1)), 0.5, h0)[0, 0] == 2.0
+    h1 = next(h for h in range(10**6) if _hash_bigint(h) % 1000 == 499)
+    assert ref.dropout_hash(np.ones((1, 1)), 0.5, h1)[0, 0] == 0.0
+    # the comparison is made in fp32: 0.3 rounds up in fp32, so rand = 300/1000 (which rounds the same way) is kept
+    h2 = next(h for h in range(10**6) if _hash_bigint(h) % 1000 == 300)
+    assert ref.dropout_hash(np.ones((1, 1)), 0.3, h2)[0, 0] != 0.0
+
+
+def test_dropout_wraps_in_64_bits():
+    # offset + seed wraps, and the left shift drops the high bits
+    seed = (1 << 64) - 3
+    out = ref.dropout_hash(np.ones((1, 8)), 0.5, seed)
+    for j in range(8):
+        r = np.float32(_hash_bigint((j + seed) % (1 << 64)) % 1000) / np.float32(1000.0)
+        assert out[0, j] == (0.0 if r < np.float32(0.5) else 2.0)
+
+
+def test_mean_rows_closed_forms():
+    assert np.array_equal(ref.mean_rows(np.full((3, 17), 2.5)), np.full(3, 2.5))
+    ramp = np.arange(5 * 64, dtype=np.float64).reshape(5, 64)
+    assert np.array_equal(ref.mean_rows(ramp), 64 * np.arange(5) + 31.5)   # (N-1)/2 + row start
+    Z = rng.normal(size=(9, 37))
+    assert np.allclose(ref.mean_rows(Z), Z.sum(axis=1) / 37, rtol=0, atol=1e-15)
+    # last axis, not the first: a tall constant-per-column matrix has equal row means
+    cols = np.tile(np.arange(4.0), (6, 1))
+    assert np.array_equal(ref.mean_rows(cols), np.full(6, 1.5))
+
+
+def test_chain6_composition_and_softmax_axis():
+    M, K, N, p, seed = 12, 9, 20, 0.25, 2506
+    X = f32(rng.normal(size=(M, K))); W = f32(rng.normal(size=(K, N))); b = f32(rng.normal(size=N))
+    Z = X.astype(np.float64) @ W.astype(np.float64) + b
+    mask = np.array([[np.float32(_hash_bigint(i * N + j + seed) % 1000) / np.float32(1000.0) >= np.float32(p)
+                      for j in range(N)] for i in range(M)])
+    D = np.where(mask, Z / 0.75, 0.0)
+    assert np.allclose(ref.chain6(X, W, b, p, seed, "dropout"), D, rtol=0, atol=1e-13)
+    mu = D.mean(axis=1)
+    assert np.allclose(ref.chain6(X, W, b, p, seed, "mean"), mu, rtol=0, atol=1e-13)
+    out = ref.chain6(X, W, b, p, seed)
+    e = np.exp(mu - mu.max())
+    assert out.shape == (M,)
+    assert np.allclose(out, e / e.sum(), rtol=0, atol=1e-15)
+    assert abs(out.sum() - 1.0) < 1e-14          # one softmax over the M row means
