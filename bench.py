@@ -180,6 +180,34 @@ def main() -> int:
         outs = [s["out"].view(4096, 8192) for s in sets[3]]    # reuse the layernorm outputs as destinations
         time_layout("transpose_8192x4096", [m.t() for m in ms], outs, 2 * ms[0].numel() * 4)
 
+    # ---- [Matmul, Dropout, Mean, Softmax] (Section 5.3 case study; outside the step and the headline value)
+    next_ops = []
+    if not args.only:
+        t6 = {k: dev(v) for k, v in datagen.make(6).items()}
+        M6, K6 = t6["X"].shape
+        N6 = t6["W"].shape[1]
+        out6 = torch.empty(M6, device="cuda")
+        plan6, ins6 = hpct.matmul_dropout_mean_softmax_plan(t6["X"], t6["W"], t6["bias"], out6, datagen.CHAIN6_P,
+                                                            datagen.CHAIN6_SEED)
+        ws6 = torch.empty(max(1, plan6.workspace_bytes // 4), device="cuda")
+        call6 = plan6.bind(ins6, [out6], workspace=ws6)
+        n6 = max(1, args.steps // 4)
+        for _ in range(min(args.warmup, 5)):
+            call6()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n6):
+            call6()
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / n6
+        flop6 = 2.0 * M6 * K6 * N6
+        next_ops.append(dict(op="matmul_dropout_mean_softmax_%dx%dx%d" % (M6, K6, N6), kernel=plan6.kernel_name,
+                             launches=n6, avg_us=round(us, 3), achieved=round(flop6 / us / 1e6, 2), unit="TFLOP/s",
+                             peak=MFMA_F32_PEAK_TFLOPS, frac=round(flop6 / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4),
+                             note="both kernels of the chain (GEMM with fused dropout and row sums, then mean + softmax over rows)"))
+        del t6, out6, ws6
+
     per_op, fracs = [], []
     for i in which:
         avg_us = 1e3 * ev[i][0].elapsed_time(ev[i][1]) / args.steps
@@ -208,7 +236,7 @@ def main() -> int:
                                     "layernorm+gelu 8192x4096, conv3x3 32x64x56x56->128, attention 16x2048x64"
                            if not args.only else "chain %d only" % args.only,
                            ops=len(which), hbm_cold_sets={str(i): len(sets[i]) for i in which}),
-               per_op=per_op, roofline=roofline, layout_ops=layout_ops)
+               per_op=per_op, roofline=roofline, layout_ops=layout_ops, next_ops=next_ops)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host, which)

@@ -7,8 +7,9 @@
  * Elementwise "add, mul, relu", Reduction "sum, mean, softmax", LayoutTransform
  * "reshape, transpose"; fused examples
  * of its Section 5.3) with an op descriptor; the library validates it, picks a
- * hand-written HIP kernel and enqueues exactly one kernel per launch on the
- * caller's stream.
+ * hand-written HIP kernel and enqueues it on the caller's stream: one kernel per
+ * launch, two for a GEMM chain that ends in MEAN_LAST (the second finishes the
+ * reduction from the workspace).
  *
  * Conventions
  *  - All tensors are fp32, described by shape and stride in ELEMENTS.
@@ -27,7 +28,11 @@
  * then the operands of each epilogue / reduction in the order they run.
  *
  *   chain                                             in[]                          out[0]
- *   GEMM [+BIAS_COL] [+RELU] [+SOFTMAX_LAST]          X[M,K], W[K,N], bias[N]       [M,N]
+ *   GEMM [+BIAS_COL] [+RELU] [+DROPOUT_HASH]          X[M,K], W[K,N], bias[N]       [M,N]
+ *         [+SOFTMAX_LAST (N <= 256)]
+ *   GEMM [+BIAS_COL] [+RELU] [+DROPOUT_HASH]          X[M,K], W[K,N], bias[N]       [M]
+ *         MEAN_LAST [then reduce2 = SOFTMAX_LAST                                     (needs the
+ *         over the M means]                                                          workspace)
  *   NONE  SCALE_SHIFT_CH [+RELU] [+ADD_RESIDUAL]      X[N,C,H,W], scale[C],         [N,C] (AVGPOOL_HW)
  *         then AVGPOOL_HW or no reduction             shift[C], R[N,C,H,W]          or [N,C,H,W]
  *   NONE  LAYERNORM_LAST (reduce_before_epi=1)        X[M,N], gamma[N], beta[N]     [M,N]
@@ -90,7 +95,12 @@ typedef enum {
     HPCT_EPI_RELU = 2,            /* max(x, 0) */
     HPCT_EPI_ADD_RESIDUAL = 3,    /* + R, same shape as the running value */
     HPCT_EPI_GELU_TANH = 4,       /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
-    HPCT_EPI_SCALE_CONST = 5      /* * desc.scale */
+    HPCT_EPI_SCALE_CONST = 5,     /* * desc.scale */
+    HPCT_EPI_DROPOUT_HASH = 6     /* training-mode dropout with the hash mask of the Section 5.3 case study: for
+                                     element (i, j) of an [M,N] value, h = i*N + j + dropout_seed (uint64, wrapping),
+                                     h ^= h >> 17; h ^= h << 31; h ^= h >> 8; rand = (float)(h % 1000) / 1000.0f;
+                                     the element becomes 0 when rand < dropout_p (fp32 compare) and is multiplied
+                                     by 1 / (1 - dropout_p) otherwise.  GEMM anchor only. */
 } hpct_epilogue;
 
 /* Row reductions (Table 1, Reduction). */
@@ -98,7 +108,8 @@ typedef enum {
     HPCT_RED_NONE = 0,
     HPCT_RED_SOFTMAX_LAST = 1,    /* exp(x - max) / sum exp(x - max) over the last dim */
     HPCT_RED_LAYERNORM_LAST = 2,  /* (x - mean) / sqrt(biased var + eps) * gamma + beta over the last dim */
-    HPCT_RED_AVGPOOL_HW = 3       /* mean over dims 2,3 of NCHW */
+    HPCT_RED_AVGPOOL_HW = 3,      /* mean over dims 2,3 of NCHW */
+    HPCT_RED_MEAN_LAST = 4        /* mean over the last dim, which is dropped: [M,N] -> [M].  GEMM anchor only. */
 } hpct_reduce;
 
 typedef struct {
@@ -115,6 +126,10 @@ typedef struct {
     int32_t pad_hw[2];            /* conv only */
     float eps;                    /* layernorm */
     float scale;                  /* SCALE_CONST, and the score scale of BGEMM_SOFTMAX_BGEMM */
+    float dropout_p;              /* DROPOUT_HASH: drop probability, 0 <= p < 1 */
+    hpct_reduce reduce2;          /* a second reduction applied to the result of `reduce`; only SOFTMAX_LAST
+                                     after MEAN_LAST (softmax over the M row means), else HPCT_RED_NONE */
+    uint64_t dropout_seed;        /* DROPOUT_HASH */
 } hpct_op_desc;
 
 typedef struct hpct_plan hpct_plan;   /* opaque; host memory */
@@ -125,15 +140,18 @@ typedef struct hpct_plan hpct_plan;   /* opaque; host memory */
  * *out is set to NULL.  Errors: NULL, BAD_DESC, SHAPE_MISMATCH, UNSUPPORTED. */
 hpct_status hpct_plan_create(const hpct_op_desc *desc, hpct_plan **out);
 
-/* Device workspace the plan needs at launch, in bytes (0 for every chain
- * currently supported).  0 for a NULL plan. */
+/* Device workspace the plan needs at launch, in bytes: 0 except for GEMM chains
+ * with MEAN_LAST (one float per row and column tile).  The launch overwrites it;
+ * it needs no initialisation and carries nothing between launches.  0 for a NULL plan. */
 size_t hpct_plan_workspace_bytes(const hpct_plan *plan);
 
 /* Enqueue the plan's kernel on `hip_stream` (a hipStream_t; NULL = the default
  * stream) and return without synchronising.
  *   in_ptrs[i]  device pointer of desc.in[i]   (host array of n_in pointers)
  *   out_ptrs[i] device pointer of desc.out[i]  (host array of n_out pointers)
- *   workspace   device pointer, >= hpct_plan_workspace_bytes; may be NULL when that is 0
+ *   workspace   device pointer, 16-byte aligned, >= hpct_plan_workspace_bytes, disjoint from
+ *               inputs and outputs; may be NULL when that is 0.  Launches that share a
+ *               workspace must be ordered on one stream.
  * Errors: NULL (plan, arrays or any data pointer), ALIGNMENT, BAD_DESC (an
  * output range overlaps an input range), WORKSPACE, HIP. */
 hpct_status hpct_plan_launch(const hpct_plan *plan, const void *const *in_ptrs, void *const *out_ptrs,
@@ -156,6 +174,11 @@ const char *hpct_last_error(void);
 
 /* Library version string. */
 const char *hpct_version(void);
+
+/* sizeof(hpct_tensor_desc) and sizeof(hpct_op_desc) as this library was
+ * compiled, for bindings that mirror the structs to check themselves against. */
+size_t hpct_sizeof_tensor_desc(void);
+size_t hpct_sizeof_op_desc(void);
 
 #ifdef __cplusplus
 }

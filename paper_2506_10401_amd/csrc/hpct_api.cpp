@@ -41,6 +41,7 @@ struct hpct_plan {
     int64_t out_bytes[HPCT_MAX_OUT];
     // which in[] slot feeds which kernel operand; -1 = absent
     int32_t slot[4];
+    size_t ws_bytes;  // device workspace needed at launch
     union {
         GemmParams gemm;
         AffineParams affine;
@@ -112,13 +113,26 @@ bool parse_epi(const hpct_op_desc& d, const hpct_epilogue* allowed, int n_allowe
     return true;
 }
 
+// Integer form of the dropout decision: rand = (float)u / 1000.0f with u in 0..999 is
+// increasing in u, so "rand < p" (fp32) holds exactly for u < t with t counted here.
+uint32_t dropout_threshold(float p) {
+    uint32_t t = 0;
+    for (uint32_t u = 0; u < 1000; ++u)
+        if ((float)u / 1000.0f < p) ++t;
+    return t;
+}
+
 hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
-    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_RELU};
-    bool has[2];
-    if (!parse_epi(d, allowed, 2, has)) return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [RELU] in that order");
-    if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_SOFTMAX_LAST)
-        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: reduction must be NONE or SOFTMAX_LAST");
+    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_RELU, HPCT_EPI_DROPOUT_HASH};
+    bool has[3];
+    if (!parse_epi(d, allowed, 3, has))
+        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [RELU] [DROPOUT_HASH] in that order");
+    if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_SOFTMAX_LAST && d.reduce != HPCT_RED_MEAN_LAST)
+        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: reduction must be NONE, SOFTMAX_LAST or MEAN_LAST");
     if (d.reduce != HPCT_RED_NONE && d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: the reduction runs after the epilogues");
+    const bool mean = d.reduce == HPCT_RED_MEAN_LAST;
+    if (d.reduce2 != HPCT_RED_NONE && !(mean && d.reduce2 == HPCT_RED_SOFTMAX_LAST))
+        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: the only second reduction supported is SOFTMAX_LAST after MEAN_LAST");
     const int need = 2 + (has[0] ? 1 : 0);
     if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "GEMM chain takes %d inputs and 1 output (got %d, %d)", need, d.n_in, d.n_out);
     const hpct_tensor_desc &X = d.in[0], &W = d.in[1];
@@ -126,7 +140,8 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     const int64_t M = X.shape[0], K = X.shape[1], N = W.shape[1];
     if (W.shape[0] != K) return fail(HPCT_ERR_SHAPE_MISMATCH, "W.shape[0] = %lld does not match X.shape[1] = %lld", (long long)W.shape[0], (long long)K);
     if (has[0]) REQUIRE_SHAPE(d.in[2], "bias", N);
-    REQUIRE_SHAPE(d.out[0], "out[0]", M, N);
+    if (mean) REQUIRE_SHAPE(d.out[0], "out[0]", M);
+    else REQUIRE_SHAPE(d.out[0], "out[0]", M, N);
     for (int i = 0; i < d.n_in; ++i)
         if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous row-major layouts are supported", i);
     if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous row-major layouts are supported");
@@ -134,10 +149,23 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM: operand larger than 2^31-1 elements");
     const bool sm = d.reduce == HPCT_RED_SOFTMAX_LAST;
     if (sm && N > kGemmSoftmaxMaxN) return fail(HPCT_ERR_UNSUPPORTED, "GEMM + SOFTMAX_LAST: N = %lld exceeds the fused limit %d", (long long)N, kGemmSoftmaxMaxN);
+    GemmParams g{};
+    g.M = (int32_t)M; g.K = (int32_t)K; g.N = (int32_t)N;
+    g.relu = has[1] ? 1 : 0; g.softmax = sm ? 1 : 0;
+    if (has[2]) {
+        if (!(d.dropout_p >= 0.f && d.dropout_p < 1.f)) return fail(HPCT_ERR_BAD_DESC, "DROPOUT_HASH: dropout_p must satisfy 0 <= p < 1");
+        g.dropout = 1;
+        g.drop_t = dropout_threshold(d.dropout_p);
+        g.keep_scale = (float)(1.0 / (1.0 - (double)d.dropout_p));
+        g.seed = d.dropout_seed;
+    }
+    g.mean = mean ? 1 : 0;
+    g.softmax2 = d.reduce2 == HPCT_RED_SOFTMAX_LAST ? 1 : 0;
     p.kind = Kind::Gemm;
-    p.u.gemm = GemmParams{nullptr, nullptr, nullptr, nullptr, (int32_t)M, (int32_t)K, (int32_t)N, has[1] ? 1 : 0, sm ? 1 : 0};
+    p.u.gemm = g;
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has[0] ? 2 : -1; p.slot[3] = -1;
     p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm);
+    p.ws_bytes = mean ? (size_t)gemm_col_tiles((int32_t)M, (int32_t)N) * (size_t)M * 4 : 0;
     return HPCT_OK;
 }
 
@@ -338,9 +366,12 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
     if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONV2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
-    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_AVGPOOL_HW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
+    if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
+        return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)
-        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_SCALE_CONST) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
+        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_DROPOUT_HASH) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
 
     hpct_plan tmp;
     std::memset(&tmp, 0, sizeof tmp);
@@ -365,6 +396,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         case HPCT_ANCHOR_CONV2D_NCHW: st = plan_conv(d, tmp); break;
         case HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM: st = plan_attn(d, tmp); break;
         default:
+            if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
             if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
             else if (d.reduce == HPCT_RED_NONE && d.n_epi == 0 && d.n_in >= 1 &&
                      !(d.in[0].ndim == 4 && contiguous(d.in[0]))) st = plan_layout(d, tmp);
@@ -377,14 +409,17 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     return HPCT_OK;
 }
 
-size_t hpct_plan_workspace_bytes(const hpct_plan*) { return 0; }
+size_t hpct_plan_workspace_bytes(const hpct_plan* plan) { return plan ? plan->ws_bytes : 0; }
 
 hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, void* const* out_ptrs, void* workspace,
                              size_t workspace_bytes, void* hip_stream) {
     clear_err();
-    (void)workspace;
-    (void)workspace_bytes;
     if (!plan || !in_ptrs || !out_ptrs) return fail(HPCT_ERR_NULL, "hpct_plan_launch: plan, in_ptrs and out_ptrs must not be NULL");
+    if (plan->ws_bytes) {
+        if (!workspace || workspace_bytes < plan->ws_bytes)
+            return fail(HPCT_ERR_WORKSPACE, "this plan needs a workspace of %zu bytes (got %zu)", plan->ws_bytes, workspace ? workspace_bytes : (size_t)0);
+        if ((uintptr_t)workspace & 15) return fail(HPCT_ERR_ALIGNMENT, "workspace is not 16-byte aligned");
+    }
     // layout transforms accept views that start anywhere (element alignment); their vector variant is
     // replaced by the scalar one at launch when a base is not 16-byte aligned
     const uintptr_t amask = plan->kind == Kind::Layout ? 3 : 15;
@@ -401,6 +436,17 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
             if (o0 < a1 && a0 < o1) return fail(HPCT_ERR_BAD_DESC, "out_ptrs[%d] overlaps in_ptrs[%d]", i, k);
         }
     }
+    if (plan->ws_bytes) {
+        const uintptr_t w0 = (uintptr_t)workspace, w1 = w0 + plan->ws_bytes;
+        for (int k = 0; k < plan->n_in; ++k) {
+            const uintptr_t a0 = (uintptr_t)in_ptrs[k], a1 = a0 + (uintptr_t)plan->in_bytes[k];
+            if (w0 < a1 && a0 < w1) return fail(HPCT_ERR_BAD_DESC, "workspace overlaps in_ptrs[%d]", k);
+        }
+        for (int k = 0; k < plan->n_out; ++k) {
+            const uintptr_t a0 = (uintptr_t)out_ptrs[k], a1 = a0 + (uintptr_t)plan->out_bytes[k];
+            if (w0 < a1 && a0 < w1) return fail(HPCT_ERR_BAD_DESC, "workspace overlaps out_ptrs[%d]", k);
+        }
+    }
     hipStream_t stream = (hipStream_t)hip_stream;
     auto in = [&](int s) -> const float* { return plan->slot[s] < 0 ? nullptr : (const float*)in_ptrs[plan->slot[s]]; };
     hipError_t e = hipSuccess;
@@ -408,6 +454,7 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
         case Kind::Gemm: {
             GemmParams q = plan->u.gemm;
             q.X = in(0); q.W = in(1); q.bias = in(2); q.Y = (float*)out_ptrs[0];
+            q.ws = (float*)workspace;
             e = gemm_launch(q, stream);
             break;
         }
@@ -470,6 +517,9 @@ hpct_status hpct_plan_launch_shape(const hpct_plan* plan, uint32_t grid[3], uint
 
 const char* hpct_last_error(void) { return g_err; }
 
-const char* hpct_version(void) { return "hpct 0.1 (gfx950)"; }
+const char* hpct_version(void) { return "hpct 0.2 (gfx950)"; }
+
+size_t hpct_sizeof_tensor_desc(void) { return sizeof(hpct_tensor_desc); }
+size_t hpct_sizeof_op_desc(void) { return sizeof(hpct_op_desc); }
 
 }  // extern "C"

@@ -30,9 +30,12 @@ constexpr int BM = 16;
 constexpr int KG = 4;   // k-groups of waves
 
 template <int BN, bool VEC>
-__global__ __launch_bounds__(BN * 4) void gemm_rows16(const float* __restrict__ X, const float* __restrict__ W,
-                                                      const float* __restrict__ bias, float* __restrict__ Y, int M, int K,
-                                                      int N, int relu, int softmax) {
+__global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
+    const float* __restrict__ X = p.X;
+    const float* __restrict__ W = p.W;
+    const float* __restrict__ bias = p.bias;
+    float* __restrict__ Y = p.Y;
+    const int M = p.M, K = p.K, N = p.N, relu = p.relu, softmax = p.softmax;
     constexpr int NG = BN / 64;  // column groups of waves
     __shared__ float part[(KG - 1) * NG * 16 * 64];
     __shared__ float red[NG][BM];
@@ -138,7 +141,34 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(const float* __restrict__ 
                 acc[b].x = fmaxf(acc[b].x, 0.f); acc[b].y = fmaxf(acc[b].y, 0.f);
                 acc[b].z = fmaxf(acc[b].z, 0.f); acc[b].w = fmaxf(acc[b].w, 0.f);
             }
+            if (p.dropout) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint64_t off = (uint64_t)(m0 + q * 4 + r) * (uint64_t)N + (uint64_t)(ncol + b);
+                    acc[b][r] = dropout_u(off + p.seed) < p.drop_t ? 0.f : acc[b][r] * p.keep_scale;
+                }
+            }
         }
+    }
+    if (p.mean) {  // uniform over the grid: one partial row sum per (column tile, row), finished by another kernel
+        if (lead) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float v = 0.f;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) v += cok[b] ? acc[b][r] : 0.f;
+                v += dpp_mov<0xB1>(v); v += dpp_mov<0x4E>(v); v += dpp_mov<0x141>(v); v += dpp_mov<0x140>(v);
+                if (l16 == 0) red[ng][q * 4 + r] = v;
+            }
+        }
+        __syncthreads();
+        if (tid < BM && m0 + tid < M) {
+            float t = red[0][tid];
+#pragma unroll
+            for (int g2 = 1; g2 < NG; ++g2) t += red[g2][tid];
+            p.ws[(int64_t)blockIdx.y * M + m0 + tid] = t;
+        }
+        return;
     }
     if (softmax) {  // uniform over the work-group: every wave reaches the barriers
         float4v mx = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
@@ -225,16 +255,27 @@ template <int BN>
 hipError_t launch_bn(const GemmParams& p, hipStream_t stream) {
     dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), block(BN * 4);
     const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
-    if (vec)
-        hipLaunchKernelGGL((gemm_rows16<BN, true>), grid, block, 0, stream, p.X, p.W, p.bias, p.Y, p.M, p.K, p.N, p.relu, p.softmax);
-    else
-        hipLaunchKernelGGL((gemm_rows16<BN, false>), grid, block, 0, stream, p.X, p.W, p.bias, p.Y, p.M, p.K, p.N, p.relu, p.softmax);
+    if (vec) hipLaunchKernelGGL((gemm_rows16<BN, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((gemm_rows16<BN, false>), grid, block, 0, stream, p);
     return hipGetLastError();
 }
 
 }  // namespace
 
-LaunchShape gemm_shape(int32_t M, int32_t, int32_t N, int32_t) {
+// The tiled kernel takes over once its 128 x 128 tiles give every XCD work; below
+// that the 16-row kernel's many small work-groups finish sooner.  The fused row
+// softmax exists only in the 16-row kernel.
+bool gemm_use_tile(int32_t M, int32_t N, int32_t softmax) {
+    if (softmax) return false;
+    return (int64_t)((M + 127) / 128) * ((N + 127) / 128) >= 32;
+}
+
+int32_t gemm_col_tiles(int32_t M, int32_t N) {
+    return gemm_use_tile(M, N, 0) ? gemm_tile_col_tiles(N) : (N + pick_bn(N) - 1) / pick_bn(N);
+}
+
+LaunchShape gemm_shape(int32_t M, int32_t, int32_t N, int32_t softmax) {
+    if (gemm_use_tile(M, N, softmax)) return gemm_tile_shape(M, N);
     const int bn = pick_bn(N);
     LaunchShape s{};
     s.grid[0] = (uint32_t)((M + BM - 1) / BM); s.grid[1] = (uint32_t)((N + bn - 1) / bn); s.grid[2] = 1;
@@ -245,11 +286,15 @@ LaunchShape gemm_shape(int32_t M, int32_t, int32_t N, int32_t) {
 }
 
 hipError_t gemm_launch(const GemmParams& p, hipStream_t stream) {
-    switch (pick_bn(p.N)) {
-        case 64: return launch_bn<64>(p, stream);
-        case 128: return launch_bn<128>(p, stream);
-        default: return launch_bn<256>(p, stream);
+    hipError_t e;
+    if (gemm_use_tile(p.M, p.N, p.softmax)) e = gemm_tile_launch(p, stream);
+    else switch (pick_bn(p.N)) {
+        case 64: e = launch_bn<64>(p, stream); break;
+        case 128: e = launch_bn<128>(p, stream); break;
+        default: e = launch_bn<256>(p, stream);
     }
+    if (e != hipSuccess || !p.mean) return e;
+    return rows_finish_launch(p.ws, p.Y, p.M, gemm_col_tiles(p.M, p.N), p.N, p.softmax2, stream);
 }
 
 }  // namespace hpct

@@ -1,0 +1,246 @@
+// Tiled GEMM for outputs large enough to fill the chip, with the epilogues of
+// the fused Matmul chains in registers (Table 1 of the paper: ComputeIntensive
+// "matmul", Elementwise "add, relu", Reduction "mean, softmax"; the
+// [Matmul, Dropout, Mean, Softmax] group of its Section 5.3), and the small
+// kernel that finishes a mean / softmax over the rows.
+//
+// gemm_tile128: a work-group of four waves owns a 128 x 128 output tile, a wave
+// 64 x 64 of it as 2 x 2 accumulators of v_mfma_f32_32x32x2_f32.  K is walked
+// in chunks of 16 through a double-buffered LDS stage: the global loads of
+// chunk t+1 are issued before the MFMAs of chunk t and written to the other
+// buffer after them, one barrier per chunk.
+//
+// Fragment layout.  In a 32x32x2 MFMA lane l supplies A[l%32][l/32] and
+// B[l/32][l%32].  Lane half h = l/32 reads k = 8t+4h .. 8t+4h+3 of its A row
+// with one 128-bit LDS read; MFMA e (0..3) of that group therefore contracts
+// k = {8t+e, 8t+4+e} and its B fragment is the 32-bit read Bs[8t+4h+e][col].
+// Row strides: A rows are 20 words apart (16 lanes x 4 words of a 128-bit read
+// cover all 64 banks), B rows 136 words (the two lane halves, 4 rows apart,
+// land on disjoint bank halves).
+//
+// Epilogue.  Register r of accumulator (i, j) is output row
+// 64 wm + 32 i + 8 (r/4) + 4 h + r%4, column 64 wn + 32 j + l%32.  Bias, ReLU
+// and the hash dropout act on it in place; the result is either stored or, for
+// a mean over the last dimension, summed over the tile's columns in a fixed
+// order and written as one partial per (column tile, row) for the finishing
+// kernel, so results do not depend on scheduling.
+#include "kernels.hpp"
+#include "prim.hpp"
+
+namespace hpct {
+namespace {
+
+constexpr int TM = 128, TN = 128, BK = 16;
+constexpr int LDA = 20, LDB = 136;
+constexpr int kThreads = 256;
+constexpr int kXcds = 8;
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void gemm_tile128(GemmParams p, int tiles_n, int items) {
+    __shared__ __attribute__((aligned(16))) float As[2][TM * LDA];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
+    __shared__ float rs[2][TM];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int M = p.M, K = p.K, N = p.N;
+
+    // consecutive tiles (same row block, neighbouring column blocks) go to the same L2 domain
+    int item;
+    {
+        const int x = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
+        const int q = items / kXcds, r = items % kXcds;
+        item = x * q + (x < r ? x : r) + j;
+    }
+    const int tm = item / tiles_n, tn = item % tiles_n;
+    const int m0 = tm * TM, n0 = tn * TN;
+
+    // staging coordinates: A rows ar, ar+64 at k offset ak; B rows bk, bk+8 at column offset bn
+    const int ar = tid >> 2, ak = (tid & 3) * 4;
+    const int bk = tid >> 5, bn = (tid & 31) * 4;
+    const float* __restrict__ X = p.X;
+    const float* __restrict__ W = p.W;
+
+    float4v ra[2], rb[2];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int m = m0 + ar + 64 * i, k = k0 + ak;
+            const float* src = X + (int64_t)m * K + k;
+            if (VEC) {
+                ra[i] = load4((m < M && k < K) ? src : X);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ra[i][e] = *((m < M && k + e < K) ? src + e : X);
+            }
+            const int kk = k0 + bk + 8 * i, n = n0 + bn;
+            const float* wsrc = W + (int64_t)kk * N + n;
+            if (VEC) {
+                rb[i] = load4((kk < K && n < N) ? wsrc : W);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rb[i][e] = *((kk < K && n + e < N) ? wsrc + e : W);
+            }
+        }
+    };
+    // zero what lies outside the operands, then write the chunk to LDS buffer `buf`
+    auto stash = [&](int k0, int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int m = m0 + ar + 64 * i, k = k0 + ak;
+            const int kk = k0 + bk + 8 * i, n = n0 + bn;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (!(m < M && k + e < K)) ra[i][e] = 0.f;
+                if (!(kk < K && n + e < N)) rb[i][e] = 0.f;
+            }
+            *reinterpret_cast<float4v*>(&As[buf][(ar + 64 * i) * LDA + ak]) = ra[i];
+            *reinterpret_cast<float4v*>(&Bs[buf][(bk + 8 * i) * LDB + bn]) = rb[i];
+        }
+    };
+
+    float16v acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    auto compute = [&](int buf) {
+        const float* a_base = &As[buf][(wm * 64 + l32) * LDA + 4 * h];
+        const float* b_base = &Bs[buf][(4 * h) * LDB + wn * 64 + l32];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            float4v a[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const float4v*>(a_base + i * 32 * LDA + 8 * t);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float b[2];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) b[j] = b_base[(8 * t + e) * LDB + j * 32];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x2(a[i][e], b[j], acc[i][j]);
+            }
+        }
+    };
+
+    const int nk = (K + BK - 1) / BK;
+    fetch(0);
+    stash(0, 0);
+    __syncthreads();
+    for (int t = 0; t + 1 < nk; ++t) {
+        fetch((t + 1) * BK);
+        __builtin_amdgcn_sched_barrier(0);  // the next chunk's loads are in flight before the MFMAs start
+        compute(t & 1);
+        stash((t + 1) * BK, (t + 1) & 1);
+        __syncthreads();
+    }
+    compute((nk - 1) & 1);
+
+    // ---- epilogue in registers
+    const float* __restrict__ bias = p.bias;
+    float rsum[2][16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rsum[i][r] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int col = n0 + wn * 64 + j * 32 + l32;
+        const bool cok = col < N;
+        const float bv = (bias && cok) ? bias[col] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                float v = acc[i][j][r] + bv;
+                if (p.relu) v = fmaxf(v, 0.f);
+                if (p.dropout) {
+                    const uint64_t off = (uint64_t)row * (uint64_t)N + (uint64_t)col;
+                    v = dropout_u(off + p.seed) < p.drop_t ? 0.f : v * p.keep_scale;
+                }
+                if (p.mean) {
+                    rsum[i][r] += cok ? v : 0.f;
+                } else if (cok && row < M) {
+                    p.Y[(int64_t)row * N + col] = v;
+                }
+            }
+        }
+    }
+    if (p.mean) {  // uniform over the grid
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float v = rsum[i][r];  // over the 32 lanes of this half: four DPP steps inside each 16-lane row, then the two rows
+                v += dpp_mov<0xB1>(v); v += dpp_mov<0x4E>(v); v += dpp_mov<0x141>(v); v += dpp_mov<0x140>(v);
+                v += __shfl_xor(v, 16, 64);
+                if (l32 == 0) rs[wn][wm * 64 + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3)] = v;
+            }
+        __syncthreads();
+        if (tid < TM && m0 + tid < M) p.ws[(int64_t)tn * M + m0 + tid] = rs[0][tid] + rs[1][tid];
+    }
+}
+
+// out[m] = (1/N) sum_t ws[t][m]; with `softmax`, out = softmax over the M means.
+// One work-group; every thread owns the rows m = tid, tid + 1024, ...
+constexpr int kFinThreads = 1024;
+__global__ __launch_bounds__(kFinThreads) void rows_mean_softmax(const float* __restrict__ ws, float* __restrict__ out, int M,
+                                                                int T, float inv_n, int softmax) {
+    __shared__ float slots[kFinThreads / kWave];
+    const int tid = threadIdx.x;
+    float mx = -INFINITY;
+    for (int m = tid; m < M; m += kFinThreads) {
+        float s = 0.f;
+        for (int t = 0; t < T; ++t) s += ws[(int64_t)t * M + m];
+        const float mu = s * inv_n;
+        out[m] = mu;
+        mx = fmaxf(mx, mu);
+    }
+    if (!softmax) return;  // uniform
+    mx = block_reduce<OpMax, kFinThreads / kWave>(mx, slots);
+    float sum = 0.f;
+    for (int m = tid; m < M; m += kFinThreads) {
+        const float e = fast_exp2((out[m] - mx) * kLog2e);
+        out[m] = e;
+        sum += e;
+    }
+    sum = block_reduce<OpSum, kFinThreads / kWave>(sum, slots);
+    const float inv = 1.0f / sum;
+    for (int m = tid; m < M; m += kFinThreads) out[m] *= inv;
+}
+
+}  // namespace
+
+LaunchShape gemm_tile_shape(int32_t M, int32_t N) {
+    LaunchShape s{};
+    s.grid[0] = (uint32_t)(((M + TM - 1) / TM) * ((N + TN - 1) / TN)); s.grid[1] = s.grid[2] = 1;
+    s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
+    s.lds_bytes = (uint32_t)((2 * TM * LDA + 2 * BK * LDB + 2 * TM) * 4);
+    s.kernel = "gemm_tile128";
+    return s;
+}
+
+int32_t gemm_tile_col_tiles(int32_t N) { return (N + TN - 1) / TN; }
+
+hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream) {
+    const int tiles_m = (p.M + TM - 1) / TM, tiles_n = (p.N + TN - 1) / TN;
+    const int items = tiles_m * tiles_n;
+    const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
+    if (vec) hipLaunchKernelGGL((gemm_tile128<true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+    else hipLaunchKernelGGL((gemm_tile128<false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+    return hipGetLastError();
+}
+
+hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream) {
+    hipLaunchKernelGGL(rows_mean_softmax, dim3(1), dim3(kFinThreads), 0, stream, ws, out, M, T, 1.0f / (float)N, softmax);
+    return hipGetLastError();
+}
+
+}  // namespace hpct

@@ -1,7 +1,8 @@
 // Launch parameters and host-side launchers of the kernel families.  Each
-// launcher enqueues exactly one kernel on `stream` and returns the HIP status
-// of the launch.  Shapes have been validated by the caller (the plan layer);
-// launchers assert nothing beyond what they state here.
+// launcher enqueues one kernel on `stream` (two for a GEMM chain that ends in a
+// mean over the last dimension) and returns the HIP status of the launch.
+// Shapes have been validated by the caller (the plan layer); launchers assert
+// nothing beyond what they state here.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <cstdint>
@@ -53,14 +54,32 @@ struct LayoutParams {
 LaunchShape layout_shape(const LayoutParams& p);
 hipError_t layout_launch(const LayoutParams& p, hipStream_t stream);
 
-// ---- GEMM + bias + relu (+ row softmax when the tile spans the whole row)
+// ---- GEMM + bias + relu + hash dropout, then one of: store [M,N]; row softmax
+//      (when the tile spans the whole row); mean over the last dim (-> [M]),
+//      optionally followed by a softmax over those M means.  The mean variants
+//      enqueue two kernels: the GEMM writes one partial row sum per column tile
+//      to `ws` ([col_tiles][M] floats), a one-group kernel finishes into Y.
 struct GemmParams {
     const float* X; const float* W; const float* bias; float* Y;
     int32_t M, K, N; int32_t relu, softmax;
+    int32_t dropout;      // apply the hash dropout
+    uint32_t drop_t;      // an element is dropped iff (hash % 1000) < drop_t
+    float keep_scale;     // 1 / (1 - p)
+    uint64_t seed;
+    int32_t mean;         // reduce over the last dim instead of storing [M,N]
+    int32_t softmax2;     // softmax over the M means
+    float* ws;            // partial row sums, only with `mean`
 };
 constexpr int kGemmSoftmaxMaxN = 256;
+bool gemm_use_tile(int32_t M, int32_t N, int32_t softmax);
+int32_t gemm_col_tiles(int32_t M, int32_t N);
 LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax);
 hipError_t gemm_launch(const GemmParams& p, hipStream_t stream);
+// the 128 x 128-tile kernel and the finishing kernel (k_gemm_tile.hip)
+LaunchShape gemm_tile_shape(int32_t M, int32_t N);
+int32_t gemm_tile_col_tiles(int32_t N);
+hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream);
+hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream);
 
 // ---- NCHW conv2d (stride 1, RxS in {1x1, 3x3}) + bias + relu
 struct ConvParams {

@@ -86,6 +86,16 @@ __device__ __forceinline__ float gelu_tanh(float y) {
     return y * fast_rcp(1.0f + fast_exp2(t));
 }
 
+// ---- hash dropout (Section 5.3 case study of the paper) -------------------------
+// rand as the integer u = h % 1000 for h = offset + seed:
+// h ^= h >> 17; h ^= h << 31; h ^= h >> 8, all in 64 bits.
+__device__ __forceinline__ uint32_t dropout_u(uint64_t h) {
+    h ^= h >> 17;
+    h ^= h << 31;
+    h ^= h >> 8;
+    return (uint32_t)(h % 1000ull);
+}
+
 // ---- fp32 MFMA ----------------------------------------------------------------
 // D(32x32) += A(32x2) B(2x32).  Lane l supplies A[l%32][l/32] and B[l/32][l%32];
 // register r of lane l holds D[8*(r/4) + 4*(l/32) + r%4][l%32].

@@ -23,8 +23,8 @@ STATUS_NAMES = ["HPCT_OK", "HPCT_ERR_NULL", "HPCT_ERR_BAD_DESC", "HPCT_ERR_SHAPE
 HPCT_F32 = 0
 HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW = range(4)
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
-    HPCT_EPI_SCALE_CONST = range(6)
-HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW = range(4)
+    HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH = range(7)
+HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST = range(5)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
 
 
@@ -37,7 +37,8 @@ class OpDesc(C.Structure):
     _fields_ = [("anchor", C.c_int), ("n_epi", C.c_int32), ("epi", C.c_int * HPCT_MAX_EPI), ("reduce", C.c_int),
                 ("reduce_before_epi", C.c_int32), ("n_in", C.c_int32), ("in_", TensorDesc * HPCT_MAX_IN),
                 ("n_out", C.c_int32), ("out", TensorDesc * HPCT_MAX_OUT), ("stride_hw", C.c_int32 * 2),
-                ("pad_hw", C.c_int32 * 2), ("eps", C.c_float), ("scale", C.c_float)]
+                ("pad_hw", C.c_int32 * 2), ("eps", C.c_float), ("scale", C.c_float), ("dropout_p", C.c_float),
+                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64)]
 
 
 class HpctError(RuntimeError):
@@ -77,6 +78,10 @@ def load(path: Optional[str] = None):
     lib.hpct_last_error.restype = C.c_char_p
     lib.hpct_version.argtypes = []
     lib.hpct_version.restype = C.c_char_p
+    for fn in (lib.hpct_sizeof_tensor_desc, lib.hpct_sizeof_op_desc):
+        fn.argtypes, fn.restype = [], C.c_size_t
+    if lib.hpct_sizeof_tensor_desc() != C.sizeof(TensorDesc) or lib.hpct_sizeof_op_desc() != C.sizeof(OpDesc):
+        raise RuntimeError("libhpct.so was built from another version of include/hpct.h than this binding mirrors")
     _lib = lib
     return lib
 
@@ -105,7 +110,8 @@ def tensor_desc(shape: Sequence[int], stride: Optional[Sequence[int]] = None, dt
 
 
 def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before_epi=0, inputs=(), outputs=(),
-            stride_hw=(1, 1), pad_hw=(0, 0), eps=0.0, scale=1.0) -> OpDesc:
+            stride_hw=(1, 1), pad_hw=(0, 0), eps=0.0, scale=1.0, dropout_p=0.0, dropout_seed=0,
+            reduce2=HPCT_RED_NONE) -> OpDesc:
     d = OpDesc()
     d.anchor = anchor
     d.n_epi = len(epi)
@@ -123,6 +129,9 @@ def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before
     d.pad_hw[0], d.pad_hw[1] = pad_hw
     d.eps = eps
     d.scale = scale
+    d.dropout_p = dropout_p
+    d.dropout_seed = int(dropout_seed) & 0xFFFFFFFFFFFFFFFF
+    d.reduce2 = reduce2
     return d
 
 
@@ -166,7 +175,7 @@ class Plan:
         if st != HPCT_OK:
             raise HpctError(st, hpct_last_error())
 
-    def bind(self, inputs, outputs, stream=None):
+    def bind(self, inputs, outputs, stream=None, workspace=None):
         """Marshal the pointer arrays once and return a zero-argument callable
         that enqueues this plan on `stream` (default: the stream current now).
         For launch loops where per-call Python overhead matters."""
@@ -178,22 +187,31 @@ class Plan:
         ins = (C.c_void_p * max(1, len(inputs)))(*[t.data_ptr() for t in inputs])
         outs = (C.c_void_p * max(1, len(outputs)))(*[t.data_ptr() for t in outputs])
         s = C.c_void_p(torch.cuda.current_stream().cuda_stream if stream is None else stream)
-        h, fn, keep = self._h, lib.hpct_plan_launch, (list(inputs), list(outputs), self)
+        if workspace is not None and (not workspace.is_cuda or not workspace.is_contiguous()):
+            raise HpctError(HPCT_ERR_BAD_DESC, "the workspace must be a contiguous tensor in GPU memory")
+        ws = C.c_void_p(workspace.data_ptr()) if workspace is not None else None
+        ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+        h, fn, keep = self._h, lib.hpct_plan_launch, (list(inputs), list(outputs), workspace, self)
 
         def go(_keep=keep):
-            st = fn(h, ins, outs, None, 0, s)
+            st = fn(h, ins, outs, ws, ws_bytes, s)
             if st != HPCT_OK:
                 raise HpctError(st, hpct_last_error())
         return go
 
-    def launch(self, inputs, outputs, stream=None) -> None:
-        """inputs / outputs: torch tensors on the GPU (fp32, laid out as described)."""
+    def launch(self, inputs, outputs, stream=None, workspace=None) -> None:
+        """inputs / outputs: torch tensors on the GPU (fp32, laid out as described);
+        workspace: a contiguous GPU tensor of at least `workspace_bytes` bytes when the plan needs one."""
         import torch
         for t in list(inputs) + list(outputs):
             if not t.is_cuda or t.dtype != torch.float32:
                 raise HpctError(HPCT_ERR_BAD_DESC, "operands must be fp32 tensors in GPU memory")
         s = torch.cuda.current_stream().cuda_stream if stream is None else stream
-        self.launch_ptrs([t.data_ptr() for t in inputs], [t.data_ptr() for t in outputs], s)
+        if workspace is not None and (not workspace.is_cuda or not workspace.is_contiguous()):
+            raise HpctError(HPCT_ERR_BAD_DESC, "the workspace must be a contiguous tensor in GPU memory")
+        self.launch_ptrs([t.data_ptr() for t in inputs], [t.data_ptr() for t in outputs], s,
+                         workspace.data_ptr() if workspace is not None else 0,
+                         workspace.numel() * workspace.element_size() if workspace is not None else 0)
 
 
 _plans: Dict[tuple, Plan] = {}
@@ -228,6 +246,27 @@ def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, stream=None
     """out = softmax_rows(relu(X @ W + bias)); relu / softmax / bias optional."""
     plan, ins = gemm_bias_relu_softmax_plan(X, W, bias, out, relu, softmax)
     plan.launch(ins, [out], stream)
+
+
+def matmul_dropout_mean_softmax_plan(X, W, bias, out, p, seed, stop_after="softmax", relu=False):
+    """Plan of the [Matmul, Dropout, Mean, Softmax] group; `stop_after` in {"dropout", "mean", "softmax"}
+    ends the chain there (out is [M,N], [M], [M])."""
+    M, K = _sh(X)
+    N = _sh(W)[1]
+    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_RELU] if relu else []) + [HPCT_EPI_DROPOUT_HASH]
+    ins = [X, W] + ([bias] if bias is not None else [])
+    red = HPCT_RED_NONE if stop_after == "dropout" else HPCT_RED_MEAN_LAST
+    red2 = HPCT_RED_SOFTMAX_LAST if stop_after == "softmax" else HPCT_RED_NONE
+    plan = _cached(("mdms", M, K, N, tuple(epi), float(p), int(seed), stop_after), lambda: op_desc(
+        HPCT_ANCHOR_GEMM, epi, red, 0, [_sh(t) for t in ins], [_sh(out)], dropout_p=p, dropout_seed=seed, reduce2=red2))
+    return plan, ins
+
+
+def matmul_dropout_mean_softmax(X, W, bias, out, p, seed, workspace=None, stop_after="softmax", relu=False, stream=None) -> None:
+    """out[M] = softmax over the M values mean_n(dropout(X @ W + bias)[m, n]) (Section 5.3 case study).
+    `workspace`: GPU tensor of at least plan.workspace_bytes bytes (needed once the chain contains the mean)."""
+    plan, ins = matmul_dropout_mean_softmax_plan(X, W, bias, out, p, seed, stop_after, relu)
+    plan.launch(ins, [out], stream, workspace)
 
 
 def scale_shift_relu_add_pool_plan(X, scale, shift, R, out, relu=True, pool=True):

@@ -32,7 +32,11 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_the_c_layout():
     # int32 + pad + 6*int64 + 6*int64 + enum + pad
     assert C.sizeof(H.TensorDesc) == 112
-    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4
+    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4 + 4 + 4 + 8
+    # and the library reports the same sizes for the structs it was compiled with
+    lib = H.load()
+    assert lib.hpct_sizeof_tensor_desc() == C.sizeof(H.TensorDesc)
+    assert lib.hpct_sizeof_op_desc() == C.sizeof(H.OpDesc)
 
 
 def cfg_desc(i):
@@ -274,4 +278,75 @@ def test_layout_transform_plans():
     base = 0x7F0000000000
     with pytest.raises(H.HpctError) as e:
         p.launch_ptrs([base], [base + 16])
+    assert e.value.status == H.HPCT_ERR_BAD_DESC
+
+
+def chain6_desc(M=4096, K=1024, N=4096, stop="softmax", p=0.25, seed=0x250610401, anchor=None):
+    red = H.HPCT_RED_NONE if stop == "dropout" else H.HPCT_RED_MEAN_LAST
+    red2 = H.HPCT_RED_SOFTMAX_LAST if stop == "softmax" else H.HPCT_RED_NONE
+    return H.op_desc(H.HPCT_ANCHOR_GEMM if anchor is None else anchor, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_DROPOUT_HASH], red, 0,
+                     [(M, K), (K, N), (N,)], [(M, N) if stop == "dropout" else (M,)], dropout_p=p, dropout_seed=seed,
+                     reduce2=red2)
+
+
+def test_matmul_dropout_mean_softmax_plans():
+    p = H.Plan(chain6_desc())
+    assert p.kernel_name == "gemm_tile128"
+    assert p.launch_shape() == ((32 * 32, 1, 1), (256, 1, 1), (2 * 128 * 20 + 2 * 16 * 136 + 2 * 128) * 4)
+    assert p.workspace_bytes == 32 * 4096 * 4          # one float per (column tile, row)
+    assert H.Plan(chain6_desc(stop="dropout")).workspace_bytes == 0
+    assert H.Plan(chain6_desc(stop="mean")).workspace_bytes == 32 * 4096 * 4
+    small = H.Plan(chain6_desc(64, 256, 256))
+    assert small.kernel_name == "gemm_rows16<256>" and small.workspace_bytes == 64 * 4
+    wide = H.Plan(chain6_desc(64, 256, 1000))
+    assert wide.kernel_name == "gemm_rows16<256>" and wide.workspace_bytes == 4 * 64 * 4
+    # a large GEMM without the dropout chain also takes the tiled kernel; the fused row softmax keeps the 16-row one
+    g = H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0,
+                  [(2048, 512), (512, 2048), (2048,)], [(2048, 2048)])
+    assert H.Plan(g).kernel_name == "gemm_tile128"
+    g = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_SOFTMAX_LAST, 0, [(8192, 64), (64, 256)], [(8192, 256)])
+    assert H.Plan(g).kernel_name == "gemm_rows16<256>"
+
+
+def test_matmul_dropout_mean_softmax_errors():
+    expect(H.HPCT_ERR_BAD_DESC, chain6_desc(p=1.0))
+    expect(H.HPCT_ERR_BAD_DESC, chain6_desc(p=-0.1))
+    expect(H.HPCT_ERR_BAD_DESC, chain6_desc(p=float("nan")))
+    d = chain6_desc(); d.out[0] = H.tensor_desc((4096, 4096))      # MEAN_LAST drops the last dim
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = chain6_desc(stop="mean"); d.reduce2 = H.HPCT_RED_LAYERNORM_LAST
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = chain6_desc(stop="dropout"); d.reduce2 = H.HPCT_RED_SOFTMAX_LAST   # second reduction without the first
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = chain6_desc(); d.reduce2 = 9
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = chain6_desc(); d.epi[0], d.epi[1] = H.HPCT_EPI_DROPOUT_HASH, H.HPCT_EPI_BIAS_COL   # order matters
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    # MEAN_LAST / DROPOUT_HASH outside a GEMM chain
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_MEAN_LAST, 0, [(8, 8)], [(8,)])
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(4); d.epi[1] = H.HPCT_EPI_DROPOUT_HASH
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(3); d.reduce2 = H.HPCT_RED_SOFTMAX_LAST
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+
+
+def test_workspace_checks_return_before_any_launch():
+    p = H.Plan(chain6_desc(256, 64, 512))
+    need = p.workspace_bytes
+    assert need == 2 * 256 * 4
+    base = 0x7F0000000000  # fake device addresses: every case below is rejected on the host
+    x, w, b, y, ws = base, base + (1 << 20), base + (2 << 20), base + (3 << 20), base + (4 << 20)
+    for args in [dict(), dict(workspace=ws, workspace_bytes=need - 4), dict(workspace=0, workspace_bytes=need)]:
+        with pytest.raises(H.HpctError) as e:
+            p.launch_ptrs([x, w, b], [y], **args)
+        assert e.value.status == H.HPCT_ERR_WORKSPACE
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, w, b], [y], workspace=ws + 4, workspace_bytes=need)
+    assert e.value.status == H.HPCT_ERR_ALIGNMENT
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, w, b], [y], workspace=y, workspace_bytes=need)          # workspace on the output
+    assert e.value.status == H.HPCT_ERR_BAD_DESC
+    with pytest.raises(H.HpctError) as e:
+        p.launch_ptrs([x, w, b], [y], workspace=w + 64, workspace_bytes=need)     # workspace inside W
     assert e.value.status == H.HPCT_ERR_BAD_DESC

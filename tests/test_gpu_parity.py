@@ -84,6 +84,102 @@ def test_gemm_identity_weight_is_exact():
     assert np.array_equal(host(out), X)
 
 
+# ------------------------------------- tiled GEMM and the Section 5.3 dropout chain
+def run_chain6(t, p, seed, stop_after="softmax", bias=True, relu=False):
+    X, W = dev(t["X"]), dev(t["W"])
+    b = dev(t["bias"]) if bias else None
+    M, N = X.shape[0], W.shape[1]
+    out = torch.full((M, N) if stop_after == "dropout" else (M,), float("nan"), device="cuda")
+    plan, _ = hpct.matmul_dropout_mean_softmax_plan(X, W, b, out, p, seed, stop_after, relu)
+    ws = None
+    if plan.workspace_bytes:
+        ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda")
+    else:
+        assert stop_after == "dropout"
+    hpct.matmul_dropout_mean_softmax(X, W, b, out, p, seed, ws, stop_after, relu)
+    return host(out), plan.kernel_name
+
+
+def check_chain6(t, p, seed):
+    X, W, b = t["X"], t["W"], t["bias"]
+    Z, Dn = ref.gemm_bias(X, W, b, want_norm=True)
+    D = ref.dropout_hash(Z, p, seed)
+    got, name = run_chain6(t, p, seed, "dropout")
+    print("kernel", name, flush=True)
+    # the mask is an integer decision: identical element by element (a kept element is 0 only if Z is)
+    assert np.array_equal(got == 0, D == 0)
+    assert show("dropout", compare.contraction(got, D, Dn / (1.0 - p)))
+    mu = ref.mean_rows(D)
+    got, _ = run_chain6(t, p, seed, "mean")
+    # a row mean is itself a contraction output (sum over k and n with cancellation): same rule,
+    # normalised by the mean of the surviving elements' magnitudes
+    assert show("mean", compare.contraction(got, mu, ref.mean_rows(np.where(D != 0, Dn / (1.0 - p), 0.0)) + 1e-300))
+    got, _ = run_chain6(t, p, seed, "softmax")
+    want = ref.softmax_rows(mu.reshape(1, -1)).reshape(-1)
+    assert show("softmax", compare.pointwise(got, want))
+    assert abs(float(got.astype(np.float64).sum()) - 1.0) < 1e-4
+    return name
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (64, 256, 256), (77, 50, 130), (40, 64, 1000), (19, 33, 257)])
+def test_chain6_small_shapes(M, K, N):
+    print("chain6 M=%d K=%d N=%d" % (M, K, N), flush=True)
+    name = check_chain6(datagen.make(6, M=M, K=K, N=N), datagen.CHAIN6_P, datagen.CHAIN6_SEED)
+    assert name.startswith("gemm_rows16")
+
+
+@pytest.mark.parametrize("M,K,N", [(640, 72, 900), (513, 70, 1027), (1024, 8, 512), (520, 100, 1100), (129, 16, 4100)])
+def test_chain6_tiled_shapes(M, K, N):
+    print("chain6 tiled M=%d K=%d N=%d" % (M, K, N), flush=True)
+    name = check_chain6(datagen.make(6, M=M, K=K, N=N), datagen.CHAIN6_P, datagen.CHAIN6_SEED)
+    assert name == "gemm_tile128"
+
+
+@pytest.mark.parametrize("p,seed", [(0.0, 1), (0.5, 0), (0.3, (1 << 64) - 5), (0.999, 77)])
+def test_chain6_probabilities_and_seeds(p, seed):
+    print("chain6 p=%r seed=%d" % (p, seed), flush=True)
+    check_chain6(datagen.make(6, M=48, K=40, N=200), p, seed)
+    check_chain6(datagen.make(6, M=384, K=32, N=1280), p, seed)
+
+
+def test_chain6_full_size_and_determinism():
+    t = datagen.make(6)
+    p, seed = datagen.CHAIN6_P, datagen.CHAIN6_SEED
+    got, name = run_chain6(t, p, seed)
+    assert name == "gemm_tile128"
+    want = ref.chain6(t["X"], t["W"], t["bias"], p, seed)
+    assert show("chain6 4096x1024x4096", compare.pointwise(got, want))
+    again, _ = run_chain6(t, p, seed)
+    assert np.array_equal(got, again)
+
+
+@pytest.mark.parametrize("M,K,N", [(1024, 512, 1024), (700, 260, 644), (515, 37, 1001)])
+def test_tiled_gemm_bias_relu(M, K, N):
+    print("tiled gemm M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    X, W, b = dev(t["X"]), dev(t["W"]), dev(t["bias"])
+    out = torch.full((M, N), float("nan"), device="cuda")
+    plan, ins = hpct.gemm_bias_relu_softmax_plan(X, W, b, out, relu=True, softmax=False)
+    assert plan.kernel_name == "gemm_tile128"
+    plan.launch(ins, [out])
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    assert show("tiled gemm+bias+relu", compare.contraction(host(out), ref.relu(Z), Dn))
+    assert np.max(np.abs(host(out) - ref.relu(Z)) / Dn) < 1e-5
+
+
+def test_chain6_workspace_is_required():
+    t = datagen.make(6, M=32, K=16, N=64)
+    X, W, b = dev(t["X"]), dev(t["W"]), dev(t["bias"])
+    out = torch.empty(32, device="cuda")
+    with pytest.raises(hpct.HpctError) as e:
+        hpct.matmul_dropout_mean_softmax(X, W, b, out, 0.25, 1, None)
+    assert e.value.status == hpct.HPCT_ERR_WORKSPACE
+    small = torch.empty(4, device="cuda")
+    with pytest.raises(hpct.HpctError) as e:
+        hpct.matmul_dropout_mean_softmax(X, W, b, out, 0.25, 1, small)
+    assert e.value.status == hpct.HPCT_ERR_WORKSPACE
+
+
 # ------------------------------------------------------------------- chain 2
 def run_chain2(t, pool=True, relu=True, affine=True, residual=True):
     X = dev(t["X"])
