@@ -29,7 +29,9 @@ namespace {
 constexpr int BM = 16;
 constexpr int KG = 4;   // k-groups of waves
 
-template <int BN, bool VEC>
+// EXT: the instance that also carries the hash dropout and the row-sum output (kept out of the
+// plain instance, whose 128-register budget at 1024 threads it would overflow)
+template <int BN, bool VEC, bool EXT>
 __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
     const float* __restrict__ X = p.X;
     const float* __restrict__ W = p.W;
@@ -61,7 +63,7 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
     // the step has been issued, so all 20 loads are in flight together.  With
     // VEC (K % 4 == 0 and N % 4 == 0; kend is then a multiple of 4) a 4-vector
     // is entirely inside or entirely outside.
-    constexpr int G = VEC ? 4 : 1;  // 16-k groups loaded together (the scalar path keeps fewer loads in registers)
+    constexpr int G = VEC ? ((EXT && BN == 256) ? 2 : 4) : 1;  // 16-k groups loaded together (fewer where registers are short)
     for (int k0 = kbeg; k0 < kend; k0 += 16 * G) {
         float4v a[G], w[G][4];
 #pragma unroll
@@ -141,7 +143,7 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
                 acc[b].x = fmaxf(acc[b].x, 0.f); acc[b].y = fmaxf(acc[b].y, 0.f);
                 acc[b].z = fmaxf(acc[b].z, 0.f); acc[b].w = fmaxf(acc[b].w, 0.f);
             }
-            if (p.dropout) {
+            if (EXT && p.dropout) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const uint64_t off = (uint64_t)(m0 + q * 4 + r) * (uint64_t)N + (uint64_t)(ncol + b);
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
             }
         }
     }
-    if (p.mean) {  // uniform over the grid: one partial row sum per (column tile, row), finished by another kernel
+    if (EXT && p.mean) {  // uniform over the grid: one partial row sum per (column tile, row), finished by another kernel
         if (lead) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -255,8 +257,11 @@ template <int BN>
 hipError_t launch_bn(const GemmParams& p, hipStream_t stream) {
     dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), block(BN * 4);
     const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
-    if (vec) hipLaunchKernelGGL((gemm_rows16<BN, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((gemm_rows16<BN, false>), grid, block, 0, stream, p);
+    const bool ext = p.dropout || p.mean;
+    if (vec && ext) hipLaunchKernelGGL((gemm_rows16<BN, true, true>), grid, block, 0, stream, p);
+    else if (vec) hipLaunchKernelGGL((gemm_rows16<BN, true, false>), grid, block, 0, stream, p);
+    else if (ext) hipLaunchKernelGGL((gemm_rows16<BN, false, true>), grid, block, 0, stream, p);
+    else hipLaunchKernelGGL((gemm_rows16<BN, false, false>), grid, block, 0, stream, p);
     return hipGetLastError();
 }
 

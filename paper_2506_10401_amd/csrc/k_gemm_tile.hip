@@ -36,7 +36,8 @@ constexpr int kThreads = 256;
 constexpr int kXcds = 8;
 
 template <bool VEC>
-__global__ __launch_bounds__(kThreads) void gemm_tile128(GemmParams p, int tiles_n, int items) {
+// four work-groups per CU (one wave of each per SIMD): 128 registers per lane, 64 of them accumulators
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemm_tile128(GemmParams p, int tiles_n, int items) {
     __shared__ __attribute__((aligned(16))) float As[2][TM * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
     __shared__ float rs[2][TM];

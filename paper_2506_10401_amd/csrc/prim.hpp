@@ -93,7 +93,11 @@ __device__ __forceinline__ uint32_t dropout_u(uint64_t h) {
     h ^= h >> 17;
     h ^= h << 31;
     h ^= h >> 8;
-    return (uint32_t)(h % 1000ull);
+    // h % 1000 from 32-bit pieces: 2^32 = 296 (mod 1000), so h = hi * 2^32 + lo is congruent to
+    // (hi % 1000) * 296 + lo % 1000, which is below 2^32; three 32-bit remainders by a constant
+    // instead of a 64-bit division
+    const uint32_t hi = (uint32_t)(h >> 32), lo = (uint32_t)h;
+    return ((hi % 1000u) * 296u + lo % 1000u) % 1000u;
 }
 
 // ---- fp32 MFMA ----------------------------------------------------------------
