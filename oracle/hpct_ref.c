@@ -289,3 +289,40 @@ void ref_mean_rows(const double *Z, int64_t rows, int64_t N, double *out)
         out[r] = s / (double)N;
     }
 }
+
+/* ---- Elementwise: per-channel scale and shift (a folded batch-norm, the
+ * "Conv2d BN" block named in Section 5.2) on an NCHW tensor held in double, in
+ * place:  T[n][c][i] = T[n][c][i] * scale[c] + shift[c].  Either may be NULL. */
+void ref_scale_shift_planes(double *T, const float *scale, const float *shift,
+                            int64_t Nb, int64_t C, int64_t HW)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < Nb * C; ++p) {
+        const int64_t c = p % C;
+        const double s = scale ? (double)scale[c] : 1.0, t = shift ? (double)shift[c] : 0.0;
+        for (int64_t i = 0; i < HW; ++i) T[p * HW + i] = T[p * HW + i] * s + t;
+    }
+}
+
+/* ---- Reduction: 2x2 max pooling with stride 2 over the planes of an NCHW
+ * tensor (the pooling that closes each VGG-16 block, Section 5.3):
+ * out[p][y][x] = max over dy,dx in {0,1} of T[p][2y+dy][2x+dx], for
+ * y < H/2, x < W/2 (integer division: an odd last row or column is dropped). */
+void ref_maxpool2x2_planes(const double *T, int64_t planes, int64_t H, int64_t W, double *out)
+{
+    const int64_t Hp = H / 2, Wp = W / 2;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < planes; ++p) {
+        for (int64_t y = 0; y < Hp; ++y) {
+            for (int64_t x = 0; x < Wp; ++x) {
+                double m = T[(p * H + 2 * y) * W + 2 * x];
+                for (int64_t dy = 0; dy < 2; ++dy)
+                    for (int64_t dx = 0; dx < 2; ++dx) {
+                        double v = T[(p * H + 2 * y + dy) * W + 2 * x + dx];
+                        if (v > m) m = v;
+                    }
+                out[(p * Hp + y) * Wp + x] = m;
+            }
+        }
+    }
+}

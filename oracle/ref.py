@@ -38,6 +38,8 @@ def lib():
             "ref_set_threads": [C.c_int],
             "ref_dropout_hash": [p, i64, i64, C.c_float, C.c_uint64],
             "ref_mean_rows": [p, i64, i64, p],
+            "ref_scale_shift_planes": [p, p, p, i64, i64, i64],
+            "ref_maxpool2x2_planes": [p, i64, i64, i64, p],
         }
         for name, args in sig.items():
             f = getattr(_lib, name)
@@ -190,6 +192,26 @@ def mean_rows(Z):
     return out
 
 
+def scale_shift_ch(T, scale=None, shift=None):
+    """T[n,c,h,w] * scale[c] + shift[c] on an fp64 NCHW array."""
+    T = np.array(T, dtype=np.float64, order="C")
+    Nb, Cc, H, W = T.shape
+    sc = None if scale is None else _f32(scale)
+    sh = None if shift is None else _f32(shift)
+    lib().ref_scale_shift_planes(_ptr(T), _ptr(sc), _ptr(sh), Nb, Cc, H * W)
+    return T
+
+
+def maxpool2x2(T):
+    """2x2 / stride-2 max pooling over the last two dims of an fp64 NCHW array."""
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    Nb, Cc, H, W = T.shape
+    out = np.empty((Nb, Cc, H // 2, W // 2), dtype=np.float64)
+    if out.size:
+        lib().ref_maxpool2x2_planes(_ptr(T), Nb * Cc, H, W, _ptr(out))
+    return out
+
+
 # -------------------------------------------------------------------- chains
 def chain1(X, W, bias):
     """softmax_rows(relu(X @ W + bias))"""
@@ -228,3 +250,17 @@ def chain6(X, W, bias, p, seed, stop_after="softmax"):
     if stop_after == "mean":
         return mu
     return softmax_rows(mu.reshape(1, -1)).reshape(-1)
+
+
+def chain7(inp, wt, bias, scale, shift, stride=1, pad=1, relu_=True, pool=True):
+    """VGG-style block: maxpool2x2(relu((conv2d(inp, wt) + bias) * scale[k] + shift[k])) and the
+    contraction normaliser of the conv output scaled by |scale[k]| (before pooling)."""
+    out, Dn = conv2d_nchw_bias(inp, wt, bias, stride, pad, want_norm=True)
+    if scale is not None or shift is not None:
+        out = scale_shift_ch(out, scale, shift)
+        Dn = scale_shift_ch(Dn, None if scale is None else np.abs(_f32(scale)), None if shift is None else np.abs(_f32(shift)))
+    if relu_:
+        out = relu(out)
+    if pool:
+        out = maxpool2x2(out)
+    return out, Dn

@@ -148,7 +148,16 @@ CHAIN6_P = 0.25
 CHAIN6_SEED = 0x2506_1040_1
 
 
-CONFIGS = {1: chain1_specs, 2: chain2_specs, 3: chain3_specs, 4: chain4_specs, 5: chain5_specs, 6: chain6_specs}
+def chain7_specs(N=32, C=64, H=56, W=56, K=128, R=3, S=3) -> Dict[str, Spec]:
+    """VGG-style block: conv + bias, folded batch-norm scale/shift per output channel, ReLU, 2x2 max pool."""
+    return {"in": (0, (N, C, H, W), "n", 0.0, 1.0),
+            "wt": (1, (K, C, R, S), "n", 0.0, math.sqrt(2.0 / (C * R * S))),
+            "bias": (2, (K,), "u", -0.1, 0.1),
+            "scale": (3, (K,), "n", 1.0, 0.1),
+            "shift": (4, (K,), "n", 0.0, 0.1)}
+
+
+CONFIGS = {1: chain1_specs, 2: chain2_specs, 3: chain3_specs, 4: chain4_specs, 5: chain5_specs, 6: chain6_specs, 7: chain7_specs}
 
 
 def make(config_index: int, variant: int = 0, **dims) -> Dict[str, np.ndarray]:

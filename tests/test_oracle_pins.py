@@ -573,3 +573,49 @@ def test_chain6_composition_and_softmax_axis():
     assert out.shape == (M,)
     assert np.allclose(out, e / e.sum(), rtol=0, atol=1e-15)
     assert abs(out.sum() - 1.0) < 1e-14          # one softmax over the M row means
+
+
+# ------------------------------------ per-channel affine on planes, 2x2 max pool
+def test_scale_shift_planes_channel_axis_and_closed_form():
+    T = rng.normal(size=(3, 4, 5, 6))
+    sc = f32([1.0, 2.0, -0.5, 0.0]); sh = f32([0.0, 1.0, 3.0, -2.0])
+    got = ref.scale_shift_ch(T, sc, sh)
+    want = T * sc.astype(np.float64)[None, :, None, None] + sh.astype(np.float64)[None, :, None, None]
+    assert np.array_equal(got, want)
+    assert np.array_equal(got[:, 3], np.full((3, 5, 6), -2.0))      # scale 0 leaves the shift of channel 3 only
+    assert np.array_equal(ref.scale_shift_ch(T, None, None), T)
+    assert np.array_equal(ref.scale_shift_ch(T, None, sh), T + sh.astype(np.float64)[None, :, None, None])
+
+
+def test_maxpool2x2_windows_stride_and_odd_edges():
+    # one plane whose value encodes its position: the window maximum is its bottom-right element
+    H, W = 6, 8
+    T = (np.arange(H)[:, None] * 100 + np.arange(W)[None, :]).astype(np.float64).reshape(1, 1, H, W)
+    got = ref.maxpool2x2(T)
+    assert got.shape == (1, 1, 3, 4)
+    want = (np.arange(1, H, 2)[:, None] * 100 + np.arange(1, W, 2)[None, :]).astype(np.float64)
+    assert np.array_equal(got[0, 0], want)
+    # a single spike is seen by exactly one window: (y, x) -> (y // 2, x // 2)
+    for (y, x) in [(0, 0), (1, 7), (4, 3), (5, 6)]:
+        S = np.full((1, 1, H, W), -1.0); S[0, 0, y, x] = 5.0
+        P = ref.maxpool2x2(S)
+        assert P[0, 0, y // 2, x // 2] == 5.0 and np.count_nonzero(P == 5.0) == 1
+    # negative values: the maximum, not the maximum magnitude, and no implicit zero
+    N = -np.abs(rng.normal(size=(2, 3, 4, 4))) - 1.0
+    assert np.all(ref.maxpool2x2(N) < 0)
+    # odd sizes drop the last row / column; planes are independent; numpy witness by reshaping
+    Z = rng.normal(size=(2, 3, 7, 9))
+    want = Z[:, :, :6, :8].reshape(2, 3, 3, 2, 4, 2).max(axis=(3, 5))
+    assert np.array_equal(ref.maxpool2x2(Z), want)
+    assert ref.maxpool2x2(np.zeros((1, 1, 1, 5))).shape == (1, 1, 0, 2)
+
+
+def test_chain7_composition():
+    inp = f32(rng.normal(size=(2, 3, 6, 6))); wt = f32(rng.normal(size=(4, 3, 3, 3)) * 0.3)
+    b = f32(rng.normal(size=4)); sc = f32(rng.normal(size=4)); sh = f32(rng.normal(size=4))
+    out, Dn = ref.chain7(inp, wt, b, sc, sh)
+    conv = ref.conv2d_nchw_bias(inp, wt, b)
+    aff = conv * sc.astype(np.float64)[None, :, None, None] + sh.astype(np.float64)[None, :, None, None]
+    want = np.maximum(aff, 0).reshape(2, 4, 3, 2, 3, 2).max(axis=(3, 5))
+    assert np.array_equal(out, want)
+    assert Dn.shape == conv.shape and np.all(Dn >= np.abs(aff) - 1e-12)   # the normaliser bounds the value it scales
