@@ -208,6 +208,30 @@ def main() -> int:
                              note="both kernels of the chain (GEMM with fused dropout and row sums, then mean + softmax over rows)"))
         del t6, out6, ws6
 
+        # VGG-style block: conv3x3 + bias + scale/shift + relu + 2x2 max pool at the shape of chain 4
+        t7 = {k: dev(v) for k, v in datagen.make(7).items()}
+        Nb7, C7, H7, W7 = t7["in"].shape
+        K7 = t7["wt"].shape[0]
+        out7 = torch.empty(Nb7, K7, H7 // 2, W7 // 2, device="cuda")
+        plan7, ins7 = hpct.conv_block_plan(t7["in"], t7["wt"], t7["bias"], t7["scale"], t7["shift"], out7)
+        call7 = plan7.bind(ins7, [out7])
+        for _ in range(min(args.warmup, 10)):
+            call7()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            call7()
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / args.steps
+        flop7 = 2.0 * Nb7 * K7 * H7 * W7 * C7 * 9
+        next_ops.append(dict(op="conv3x3_bias_scale_shift_relu_maxpool2_%dx%dx%dx%d_to_%d" % (Nb7, C7, H7, W7, K7),
+                             kernel=plan7.kernel_name, launches=args.steps, avg_us=round(us, 3),
+                             achieved=round(flop7 / us / 1e6, 2), unit="TFLOP/s", peak=MFMA_F32_PEAK_TFLOPS,
+                             frac=round(flop7 / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4),
+                             note="flop = the convolution's 2*N*K*Ho*Wo*C*R*S; tiles are 2 rows x 32 columns, so 56-wide rows use 56/64 of the MFMA work"))
+        del t7, out7
+
     per_op, fracs = [], []
     for i in which:
         avg_us = 1e3 * ev[i][0].elapsed_time(ev[i][1]) / args.steps

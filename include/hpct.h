@@ -40,8 +40,10 @@
  *   NONE  SOFTMAX_LAST                                X[M,N]                        [M,N]
  *   NONE  (no epilogue, no reduction): layout         X: any strided view (stride   same shape,
  *         transform, out = contiguous copy of X       >= 0, up to 6 dims)           contiguous
- *   CONV2D_NCHW [+BIAS_COL] [+RELU]                   in[N,C,H,W], wt[K,C,R,S],     [N,K,Ho,Wo]
- *                                                     bias[K]
+ *   CONV2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH] [+RELU] in[N,C,H,W], wt[K,C,R,S],     [N,K,Ho,Wo], or
+ *         then MAXPOOL2_HW or no reduction            bias[K], scale[K], shift[K]   [N,K,Ho/2,Wo/2]
+ *         (square 1/3/5/7 filter, stride <= 4,                                       with MAXPOOL2_HW
+ *         Ho = (H + 2 pad - R) / stride + 1)
  *   BGEMM_SOFTMAX_BGEMM (scores scaled by `scale`)    Q[B,L,D], K[B,Lk,D],          [B,L,D]
  *                                                     V[B,Lk,D]
  */
@@ -91,7 +93,7 @@ typedef enum {
 /* Elementwise / broadcast epilogues (Table 1, Elementwise), applied in list order. */
 typedef enum {
     HPCT_EPI_BIAS_COL = 0,        /* + bias[n]: last dim of a GEMM output, channel k of a conv output */
-    HPCT_EPI_SCALE_SHIFT_CH = 1,  /* x * scale[c] + shift[c], c = dim 1 of NCHW */
+    HPCT_EPI_SCALE_SHIFT_CH = 1,  /* x * scale[c] + shift[c], c = dim 1 of NCHW (of the output, after a conv anchor) */
     HPCT_EPI_RELU = 2,            /* max(x, 0) */
     HPCT_EPI_ADD_RESIDUAL = 3,    /* + R, same shape as the running value */
     HPCT_EPI_GELU_TANH = 4,       /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
@@ -109,7 +111,9 @@ typedef enum {
     HPCT_RED_SOFTMAX_LAST = 1,    /* exp(x - max) / sum exp(x - max) over the last dim */
     HPCT_RED_LAYERNORM_LAST = 2,  /* (x - mean) / sqrt(biased var + eps) * gamma + beta over the last dim */
     HPCT_RED_AVGPOOL_HW = 3,      /* mean over dims 2,3 of NCHW */
-    HPCT_RED_MEAN_LAST = 4        /* mean over the last dim, which is dropped: [M,N] -> [M].  GEMM anchor only. */
+    HPCT_RED_MEAN_LAST = 4,       /* mean over the last dim, which is dropped: [M,N] -> [M].  GEMM anchor only. */
+    HPCT_RED_MAXPOOL2_HW = 5      /* max over non-overlapping 2x2 windows of dims 2,3 (stride 2; an odd last row or
+                                     column is dropped): [N,K,Ho,Wo] -> [N,K,Ho/2,Wo/2].  Conv anchor only. */
 } hpct_reduce;
 
 typedef struct {

@@ -40,7 +40,7 @@ struct hpct_plan {
     int64_t in_bytes[HPCT_MAX_IN];
     int64_t out_bytes[HPCT_MAX_OUT];
     // which in[] slot feeds which kernel operand; -1 = absent
-    int32_t slot[4];
+    int32_t slot[6];
     size_t ws_bytes;  // device workspace needed at launch
     union {
         GemmParams gemm;
@@ -292,11 +292,15 @@ hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p) {
 }
 
 hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
-    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_RELU};
-    bool has[2];
-    if (!parse_epi(d, allowed, 2, has)) return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: epilogues must be [BIAS_COL] [RELU] in that order");
-    if (d.reduce != HPCT_RED_NONE) return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: no reduction is supported after it");
-    const int need = 2 + (has[0] ? 1 : 0);
+    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU};
+    bool has[3];
+    if (!parse_epi(d, allowed, 3, has))
+        return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: epilogues must be [BIAS_COL] [SCALE_SHIFT_CH] [RELU] in that order");
+    if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_MAXPOOL2_HW)
+        return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: reduction must be NONE or MAXPOOL2_HW");
+    if (d.reduce != HPCT_RED_NONE && d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: the pooling runs after the epilogues");
+    const bool pool = d.reduce == HPCT_RED_MAXPOOL2_HW;
+    const int need = 2 + (has[0] ? 1 : 0) + (has[1] ? 2 : 0);
     if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "conv chain takes %d inputs and 1 output (got %d, %d)", need, d.n_in, d.n_out);
     const hpct_tensor_desc &I = d.in[0], &Wt = d.in[1];
     if (I.ndim != 4 || Wt.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "conv operands must be 4-D: in[N,C,H,W], wt[K,C,R,S]");
@@ -307,8 +311,20 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
         return fail(HPCT_ERR_BAD_DESC, "conv: stride must be >= 1 and padding >= 0");
     if (H + 2 * d.pad_hw[0] < R || W + 2 * d.pad_hw[1] < S) return fail(HPCT_ERR_SHAPE_MISMATCH, "conv: filter larger than the padded input");
     const int64_t Ho = (H + 2 * d.pad_hw[0] - R) / d.stride_hw[0] + 1, Wo = (W + 2 * d.pad_hw[1] - S) / d.stride_hw[1] + 1;
-    if (has[0]) REQUIRE_SHAPE(d.in[2], "bias", K);
-    REQUIRE_SHAPE(d.out[0], "out[0]", Nb, K, Ho, Wo);
+    int s = 2;
+    int s_bias = -1, s_scale = -1, s_shift = -1;
+    if (has[0]) { s_bias = s++; REQUIRE_SHAPE(d.in[s_bias], "bias", K); }
+    if (has[1]) {
+        s_scale = s++; s_shift = s++;
+        REQUIRE_SHAPE(d.in[s_scale], "scale", K);
+        REQUIRE_SHAPE(d.in[s_shift], "shift", K);
+    }
+    if (pool) {
+        if (Ho < 2 || Wo < 2) return fail(HPCT_ERR_SHAPE_MISMATCH, "MAXPOOL2_HW needs a conv output of at least 2 x 2");
+        REQUIRE_SHAPE(d.out[0], "out[0]", Nb, K, Ho / 2, Wo / 2);
+    } else {
+        REQUIRE_SHAPE(d.out[0], "out[0]", Nb, K, Ho, Wo);
+    }
     for (int i = 0; i < d.n_in; ++i)
         if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous NCHW / KCRS layouts are supported", i);
     if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous NCHW layouts are supported");
@@ -316,12 +332,14 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
         return fail(HPCT_ERR_UNSUPPORTED, "conv: operand larger than 2^31-1 elements");
     const char* why = "";
     if (!conv_supported((int32_t)C, (int32_t)H, (int32_t)W, (int32_t)K, (int32_t)R, (int32_t)S, d.stride_hw[0], d.stride_hw[1],
-                        d.pad_hw[0], d.pad_hw[1], &why))
+                        d.pad_hw[0], d.pad_hw[1], pool ? 1 : 0, &why))
         return fail(HPCT_ERR_UNSUPPORTED, "conv: %s", why);
+    ConvParams q{};
+    q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)H; q.W = (int32_t)W; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
+    q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.relu = has[2] ? 1 : 0; q.pool = pool ? 1 : 0;
     p.kind = Kind::Conv;
-    p.u.conv = ConvParams{nullptr, nullptr, nullptr, nullptr, (int32_t)Nb, (int32_t)C, (int32_t)H, (int32_t)W,
-                          (int32_t)K, (int32_t)R, (int32_t)S, d.pad_hw[0], has[1] ? 1 : 0};
-    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has[0] ? 2 : -1; p.slot[3] = -1;
+    p.u.conv = q;
+    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = s_bias; p.slot[3] = s_scale; p.slot[4] = s_shift; p.slot[5] = -1;
     p.shape = conv_shape(p.u.conv);
     return HPCT_OK;
 }
@@ -366,8 +384,8 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
     if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONV2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
-    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
-    if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_MAXPOOL2_HW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MAXPOOL2_HW) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)
@@ -397,6 +415,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         case HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM: st = plan_attn(d, tmp); break;
         default:
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
+            if (d.reduce == HPCT_RED_MAXPOOL2_HW) return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL2_HW is supported only after a conv anchor");
             if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
             else if (d.reduce == HPCT_RED_NONE && d.n_epi == 0 && d.n_in >= 1 &&
                      !(d.in[0].ndim == 4 && contiguous(d.in[0]))) st = plan_layout(d, tmp);
@@ -478,7 +497,7 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
         }
         case Kind::Conv: {
             ConvParams q = plan->u.conv;
-            q.in = in(0); q.wt = in(1); q.bias = in(2); q.out = (float*)out_ptrs[0];
+            q.in = in(0); q.wt = in(1); q.bias = in(2); q.scale = in(3); q.shift = in(4); q.out = (float*)out_ptrs[0];
             e = conv_launch(q, stream);
             break;
         }

@@ -1,6 +1,8 @@
-// NCHW conv2d (cross-correlation, zero padding, stride 1, 1x1 or 3x3 filter)
-// with the bias / ReLU epilogue held in registers: the convolution of the
-// paper's VGG-16 case study (Section 5.3; Table 1 "conv").  Implicit GEMM on
+// NCHW conv2d (cross-correlation, zero padding, square filter 1/3/5/7, any
+// stride) with its epilogue held in registers - bias, per-channel scale/shift
+// (a folded batch-norm), ReLU and optionally the 2x2 max pooling that closes a
+// VGG block: the convolution of the paper's VGG-16 case study (Section 5.3;
+// Table 1 "conv"; "Conv2d BN" of Section 5.2).  Implicit GEMM on
 // v_mfma_f32_32x32x2_f32:
 //
 //     D[k_out, pixel] = sum_{c,kh,kw} wt[k_out, c, kh, kw] * in[c, h-P+kh, w-P+kw]
@@ -25,6 +27,12 @@
 // (channel s/TAPS, tap s%TAPS) of both halves.  The A fragment is then a run of
 // consecutive floats of the weight row (vector LDS reads) and the B fragment of
 // every step is an LDS read at lane base + a constant.
+//
+// POOL variant: the 64 pixels of a tile are 2 output rows x 32 output columns
+// (the two pixel blocks of the work-group are the two rows), the LDS holds the
+// window of the input those need instead of whole rows, and the epilogue takes
+// the vertical maximum through LDS (the two rows live in different waves), the
+// horizontal one with a DPP lane swap, and stores one value per 2x2 window.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -36,7 +44,10 @@ constexpr int kXcds = 8; // work-groups are dealt round-robin to this many L2 do
 
 struct ConvGeom {
     int Nb, C, H, W, K, P;
+    int St;        // stride
     int Ho, Wo, HoWo;
+    int Hp, Wp;    // pooled output size (POOL)
+    int ctiles;    // 32-column tiles per row pair (POOL)
     int tiles_per_img, tiles;
     int rows_max;  // input rows staged per tile
     int lpad;      // left pad of an LDS row so that iw = 0 lands on a 16-byte boundary
@@ -61,10 +72,16 @@ template <int R, int CC, int KT> struct Cfg {
 // FAST: W % 4 == 0, C % CC == 0, K % KT == 0 and the staged input fits the
 // register-staged slots: aligned vector loads, no tails, software pipelined.
 // Otherwise every element is loaded with its own bounds test, chunk by chunk.
-template <int R, int CC, int KT, bool FAST>
+struct ConvEpi {
+    const float* bias;   // [K] or null
+    const float* scale;  // [K] or null
+    const float* shift;  // [K] or null
+    int relu;
+};
+
+template <int R, int CC, int KT, bool FAST, bool POOL>
 __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict__ in, const float* __restrict__ wt,
-                                                        const float* __restrict__ bias, float* __restrict__ out,
-                                                        ConvGeom g, int relu) {
+                                                        ConvEpi epi, float* __restrict__ out, ConvGeom g) {
     using cfg = Cfg<R, CC, KT>;
     constexpr int KB = KT / 64;  // 32-channel accumulator blocks per wave
     constexpr int TAPS = cfg::TAPS, FPR = cfg::FPR, HALF = cfg::HALF, WLD = cfg::WLD, VW = cfg::VW;
@@ -73,7 +90,8 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     const int in_stage = CC * g.ch_ld;  // floats
     auto inS = [&](int buf) { return lds + buf * in_stage; };
     auto wS = [&](int buf) { return lds + 2 * in_stage + buf * cfg::W_STAGE; };
-    float* const biasS = lds + 2 * in_stage + 2 * cfg::W_STAGE;  // KT floats
+    float* const mulS = lds + 2 * in_stage + 2 * cfg::W_STAGE;  // KT floats: per-channel factor
+    float* const addS = mulS + KT;                              // KT floats: per-channel addend
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
@@ -90,10 +108,13 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     }
     const int tile = item / kblocks;
     const int n = tile / g.tiles_per_img;
-    const int p0 = (tile % g.tiles_per_img) * TP;
+    const int tin = tile % g.tiles_per_img;
+    const int p0 = POOL ? 0 : tin * TP;
     const int k0 = (item % kblocks) * KT;
-    const int h_lo = p0 / g.Wo;  // first output row of the tile
-    const int ih0 = h_lo - g.P;  // first staged input row
+    const int h_lo = POOL ? 2 * (tin / g.ctiles) : p0 / g.Wo;  // first output row of the tile
+    const int w_lo = POOL ? 32 * (tin % g.ctiles) : 0;         // first output column of the tile (POOL)
+    const int ih0 = h_lo * g.St - g.P;  // first staged input row
+    const int iw0 = w_lo * g.St;        // input column the staged window is anchored at (POOL)
     const int HW = g.H * g.W;
     const int ldw4 = g.ldw >> 2;
     const int slots = CC * g.rows_max * ldw4;  // float4 slots of one input stage: slot -> (c, row, x4)
@@ -102,7 +123,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         c = s / (g.rows_max * ldw4);
         const int rem = s - c * (g.rows_max * ldw4);
         const int row = rem / ldw4, x4 = (rem - row * ldw4) * 4;
-        const int ih = ih0 + row, iw = x4 - g.P - g.lpad;
+        const int ih = ih0 + row, iw = iw0 + x4 - g.P - g.lpad;
         loff = c * g.ch_ld + rem * 4;
         goff = ((n * g.C + c) * g.H + ih) * g.W + iw;
         mask = 0;
@@ -190,11 +211,18 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     const int kb0 = (wave & 1) * (KT / 2);  // this wave's output channels inside the tile
     const int pb = (wave >> 1) * 32;  // this wave's 32 pixels inside the tile
     int p = p0 + pb + l32;
-    const bool p_ok = p < g.HoWo;
-    if (!p_ok) p = g.HoWo - 1;        // clamp: reads stay inside the staged rows, the store is masked
-    const int oh = p / g.Wo, ow = p - oh * g.Wo;
-    // input element of (chunk channel c, tap kh,kw): c*ch_ld + (oh-h_lo+kh)*ldw + ow + kw + lpad
-    const int b_base = half * (CC / 2) * g.ch_ld + (oh - h_lo) * g.ldw + ow + g.lpad;
+    bool p_ok;
+    int oh, ow;
+    if (POOL) {  // pixel block = output row of the pair, lane = output column; the staged window covers the whole tile
+        oh = h_lo + (wave >> 1); ow = w_lo + l32;
+        p_ok = true;
+    } else {
+        p_ok = p < g.HoWo;
+        if (!p_ok) p = g.HoWo - 1;    // clamp: reads stay inside the staged rows, the store is masked
+        oh = p / g.Wo; ow = p - oh * g.Wo;
+    }
+    // input element of (chunk channel c, tap kh,kw): c*ch_ld + ((oh-h_lo)*St+kh)*ldw + (ow-w_lo)*St + kw + lpad
+    const int b_base = half * (CC / 2) * g.ch_ld + (oh - h_lo) * g.St * g.ldw + (ow - w_lo) * g.St + g.lpad;
     const int a_base = (kb0 + l32) * WLD + half * HALF;
 
     float16v acc[KB];
@@ -232,7 +260,14 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         }
     };
 
-    if (tid < KT) biasS[tid] = (bias && k0 + tid < g.K) ? bias[k0 + tid] : 0.f;  // visible after the first barrier
+    if (tid < KT) {  // v = (acc + bias) * scale + shift = acc * mul + add; visible after the first barrier
+        const bool ok = k0 + tid < g.K;
+        const float mul = (epi.scale && ok) ? epi.scale[k0 + tid] : 1.f;
+        const float b = (epi.bias && ok) ? epi.bias[k0 + tid] : 0.f;
+        const float sh = (epi.shift && ok) ? epi.shift[k0 + tid] : 0.f;
+        mulS[tid] = mul;
+        addS[tid] = b * mul + sh;
+    }
 
     const int nchunks = (g.C + CC - 1) / CC;
     if (FAST) {
@@ -260,44 +295,92 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     }
 
     // ---- epilogue: register r of lane holds channel 8*(r/4) + 4*half + r%4 of the block
-    if (p_ok) {
+    if (!POOL) {
+        if (p_ok) {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
+            for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kl = kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const int k = k0 + kl;
+                    if (k < g.K) {
+                        float v = acc[kb][r] * mulS[kl] + addS[kl];
+                        if (epi.relu) v = fmaxf(v, 0.f);
+                        out[((int64_t)n * g.K + k) * g.HoWo + p] = v;
+                    }
+                }
+            }
+        }
+    } else {
+        // Waves 2,3 hold output row h_lo+1 of the same channels and columns as waves 0,1 hold of row
+        // h_lo: they hand their values over through LDS (the staging area, free once every wave has
+        // finished its MFMAs), waves 0,1 take the vertical maximum, then the horizontal one with the
+        // neighbouring lane, and even lanes store.
+        float* const xch = lds + (wave & 1) * (KB * 16 * 64) + lane;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int kl = kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                const int k = k0 + kl;
-                if (k < g.K) {
-                    float v = acc[kb][r] + biasS[kl];
-                    if (relu) v = fmaxf(v, 0.f);
-                    out[((int64_t)n * g.K + k) * g.HoWo + p] = v;
-                }
+                float v = acc[kb][r] * mulS[kl] + addS[kl];
+                if (epi.relu) v = fmaxf(v, 0.f);
+                acc[kb][r] = v;
             }
+        __syncthreads();
+        if (wave >> 1) {
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xch[(kb * 16 + r) * 64] = acc[kb][r];
+        }
+        __syncthreads();
+        if ((wave >> 1) == 0) {
+            const int rp = h_lo >> 1, px = ow >> 1;
+            const bool st_ok = (lane & 1) == 0 && rp < g.Hp && px < g.Wp;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float v = fmaxf(acc[kb][r], xch[(kb * 16 + r) * 64]);
+                    v = fmaxf(v, dpp_mov<0xB1>(v));  // lane ^ 1: the other column of the window
+                    const int k = k0 + kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (st_ok && k < g.K) out[(((int64_t)n * g.K + k) * g.Hp + rp) * g.Wp + px] = v;
+                }
         }
     }
 }
 
 ConvGeom geom(const ConvParams& p) {
     ConvGeom g{};
-    g.Nb = p.Nb; g.C = p.C; g.H = p.H; g.W = p.W; g.K = p.K; g.P = p.pad;
-    g.Ho = p.H + 2 * p.pad - p.R + 1;
-    g.Wo = p.W + 2 * p.pad - p.S + 1;
+    g.Nb = p.Nb; g.C = p.C; g.H = p.H; g.W = p.W; g.K = p.K; g.P = p.pad; g.St = p.stride;
+    g.Ho = (p.H + 2 * p.pad - p.R) / p.stride + 1;
+    g.Wo = (p.W + 2 * p.pad - p.S) / p.stride + 1;
     g.HoWo = g.Ho * g.Wo;
-    g.tiles_per_img = (g.HoWo + TP - 1) / TP;
-    g.tiles = p.Nb * g.tiles_per_img;
-    // a run of TP consecutive pixels touches at most (TP-1)/Wo + 2 output rows
-    int out_rows = (TP - 1) / g.Wo + 2;
-    if (out_rows > g.Ho) out_rows = g.Ho;
-    g.rows_max = out_rows + p.R - 1;
     g.lpad = (4 - p.pad % 4) % 4;
-    g.ldw = (p.W + 2 * p.pad + g.lpad + 3) & ~3;
+    if (p.pool) {
+        g.Hp = g.Ho / 2; g.Wp = g.Wo / 2;
+        g.ctiles = (2 * g.Wp + 31) / 32;
+        g.tiles_per_img = g.Hp * g.ctiles;
+        g.rows_max = p.stride + p.R;                                       // two output rows
+        g.ldw = (31 * p.stride + p.S + g.lpad + 3) & ~3;                   // 32 output columns
+    } else {
+        g.tiles_per_img = (g.HoWo + TP - 1) / TP;
+        // a run of TP consecutive pixels touches at most (TP-1)/Wo + 2 output rows
+        int out_rows = (TP - 1) / g.Wo + 2;
+        if (out_rows > g.Ho) out_rows = g.Ho;
+        g.rows_max = (out_rows - 1) * p.stride + p.R;
+        g.ldw = (p.W + 2 * p.pad + g.lpad + 3) & ~3;
+    }
+    g.tiles = p.Nb * g.tiles_per_img;
     g.ch_ld = g.rows_max * g.ldw;
     return g;
 }
 
 template <int R, int CC, int KT>
-size_t lds_bytes(const ConvGeom& g) {
-    return (size_t)(2 * CC * g.ch_ld + 2 * Cfg<R, CC, KT>::W_STAGE + KT) * 4;
+size_t lds_bytes(const ConvGeom& g, bool pool) {
+    size_t b = (size_t)(2 * CC * g.ch_ld + 2 * Cfg<R, CC, KT>::W_STAGE + 2 * KT) * 4;
+    const size_t xch = (size_t)2 * (KT / 64) * 16 * 64 * 4;  // the pooling hand-over reuses the staging area
+    return pool && b < xch ? xch : b;
 }
 
 // Input channels per LDS chunk and output channels per work-group.  4 x 64
@@ -314,35 +397,56 @@ bool fast_ok(const ConvParams& p, const ConvGeom& g) {
 
 int conv_items(const ConvParams& p, const ConvGeom& g) { return g.tiles * ((p.K + kKT - 1) / kKT); }
 
-template <int R, bool FAST>
+template <int R, bool FAST, bool POOL>
 hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
-    const size_t lds = lds_bytes<R, kCC, kKT>(g);
+    const size_t lds = lds_bytes<R, kCC, kKT>(g, POOL);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, kCC, kKT, FAST>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, kCC, kKT, FAST, POOL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)conv_items(p, g)), block(256);
-    hipLaunchKernelGGL((conv2d_nchw_mfma<R, kCC, kKT, FAST>), grid, block, lds, stream, p.in, p.wt, p.bias, p.out, g,
-                       p.relu);
+    const ConvEpi epi{p.bias, p.scale, p.shift, p.relu};
+    hipLaunchKernelGGL((conv2d_nchw_mfma<R, kCC, kKT, FAST, POOL>), grid, block, lds, stream, p.in, p.wt, epi, p.out, g);
     return hipGetLastError();
+}
+
+template <int R>
+size_t lds_for(const ConvParams& p) { return lds_bytes<R, kCC, kKT>(geom(p), p.pool != 0); }
+
+size_t lds_any(const ConvParams& p) {
+    switch (p.R) {
+        case 1: return lds_for<1>(p);
+        case 3: return lds_for<3>(p);
+        case 5: return lds_for<5>(p);
+        default: return lds_for<7>(p);
+    }
+}
+
+// 1x1 and 3x3 have the pipelined variant; 5x5 and 7x7 always take the general one
+bool is_fast(const ConvParams& p, const ConvGeom& g) {
+    return p.R == 3 ? fast_ok<3>(p, g) : (p.R == 1 ? fast_ok<1>(p, g) : false);
+}
+
+template <int R, bool FAST>
+hipError_t launch_pool(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
+    return p.pool ? launch_conv<R, FAST, true>(p, g, stream) : launch_conv<R, FAST, false>(p, g, stream);
 }
 
 }  // namespace
 
 bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h, int32_t stride_w,
-                    int32_t pad_h, int32_t pad_w, const char** why) {
-    if (stride_h != 1 || stride_w != 1) { *why = "only stride 1 is supported"; return false; }
-    if (R != S || (R != 1 && R != 3)) { *why = "only 1x1 and 3x3 filters are supported"; return false; }
+                    int32_t pad_h, int32_t pad_w, int32_t pool, const char** why) {
+    if (stride_h != stride_w) { *why = "the stride must be the same in both directions"; return false; }
+    if (stride_h > 4) { *why = "strides above 4 are not supported"; return false; }
+    if (R != S || (R != 1 && R != 3 && R != 5 && R != 7)) { *why = "only square 1x1, 3x3, 5x5 and 7x7 filters are supported"; return false; }
     if (pad_h != pad_w) { *why = "padding must be the same in both directions"; return false; }
     if (pad_h > R - 1) { *why = "padding larger than the filter extent minus one"; return false; }
     ConvParams p{};
-    p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1;
-    const ConvGeom g = geom(p);
-    const size_t lds = R == 3 ? lds_bytes<3, kCC, kKT>(g) : lds_bytes<1, kCC, kKT>(g);
-    if (lds > 160 * 1024) { *why = "the input rows of one 64-pixel tile do not fit in LDS (image too wide)"; return false; }
+    p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.pool = pool;
+    if (lds_any(p) > 160 * 1024) { *why = "the input rows of one 64-pixel tile do not fit in LDS (image too wide)"; return false; }
     return true;
 }
 
@@ -351,17 +455,30 @@ LaunchShape conv_shape(const ConvParams& p) {
     LaunchShape s{};
     s.grid[0] = (uint32_t)conv_items(p, g); s.grid[1] = 1; s.grid[2] = 1;
     s.block[0] = 256; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)(p.R == 3 ? lds_bytes<3, kCC, kKT>(g) : lds_bytes<1, kCC, kKT>(g));
-    const bool fast = p.R == 3 ? fast_ok<3>(p, g) : fast_ok<1>(p, g);
-    s.kernel = p.R == 3 ? (fast ? "conv2d_nchw_mfma<3x3,pipelined>" : "conv2d_nchw_mfma<3x3,general>")
-                        : (fast ? "conv2d_nchw_mfma<1x1,pipelined>" : "conv2d_nchw_mfma<1x1,general>");
+    s.lds_bytes = (uint32_t)lds_any(p);
+    const bool fast = is_fast(p, g);
+    static const char* const names[4][2][2] = {
+        {{"conv2d_nchw_mfma<1x1,general>", "conv2d_nchw_mfma<1x1,pipelined>"},
+         {"conv2d_nchw_mfma<1x1,general,maxpool2>", "conv2d_nchw_mfma<1x1,pipelined,maxpool2>"}},
+        {{"conv2d_nchw_mfma<3x3,general>", "conv2d_nchw_mfma<3x3,pipelined>"},
+         {"conv2d_nchw_mfma<3x3,general,maxpool2>", "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"}},
+        {{"conv2d_nchw_mfma<5x5,general>", "conv2d_nchw_mfma<5x5,general>"},
+         {"conv2d_nchw_mfma<5x5,general,maxpool2>", "conv2d_nchw_mfma<5x5,general,maxpool2>"}},
+        {{"conv2d_nchw_mfma<7x7,general>", "conv2d_nchw_mfma<7x7,general>"},
+         {"conv2d_nchw_mfma<7x7,general,maxpool2>", "conv2d_nchw_mfma<7x7,general,maxpool2>"}}};
+    s.kernel = names[p.R / 2][p.pool ? 1 : 0][fast ? 1 : 0];
     return s;
 }
 
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream) {
     const ConvGeom g = geom(p);
-    if (p.R == 3) return fast_ok<3>(p, g) ? launch_conv<3, true>(p, g, stream) : launch_conv<3, false>(p, g, stream);
-    return fast_ok<1>(p, g) ? launch_conv<1, true>(p, g, stream) : launch_conv<1, false>(p, g, stream);
+    const bool fast = is_fast(p, g);
+    switch (p.R) {
+        case 1: return fast ? launch_pool<1, true>(p, g, stream) : launch_pool<1, false>(p, g, stream);
+        case 3: return fast ? launch_pool<3, true>(p, g, stream) : launch_pool<3, false>(p, g, stream);
+        case 5: return launch_pool<5, false>(p, g, stream);
+        default: return launch_pool<7, false>(p, g, stream);
+    }
 }
 
 }  // namespace hpct

@@ -24,7 +24,8 @@ HPCT_F32 = 0
 HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW = range(4)
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
     HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH = range(7)
-HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST = range(5)
+HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
+    HPCT_RED_MAXPOOL2_HW = range(6)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
 
 
@@ -329,6 +330,24 @@ def conv2d_bias_relu_plan(inp, wt, bias, out, stride=1, pad=1, relu=True):
 def conv2d_bias_relu(inp, wt, bias, out, stride=1, pad=1, relu=True, stream=None) -> None:
     """out = relu(conv2d_nchw(inp, wt) + bias[k])."""
     plan, ins = conv2d_bias_relu_plan(inp, wt, bias, out, stride, pad, relu)
+    plan.launch(ins, [out], stream)
+
+
+def conv_block_plan(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True):
+    """Plan of conv2d [+bias] [+per-channel scale/shift] [+relu] [+2x2 max pool] (a VGG-style block)."""
+    assert (scale is None) == (shift is None)
+    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + \
+        ([HPCT_EPI_RELU] if relu else [])
+    ins = [inp, wt] + ([bias] if bias is not None else []) + ([scale, shift] if scale is not None else [])
+    plan = _cached(("convblock", _sh(inp), _sh(wt), tuple(epi), stride, pad, pool), lambda: op_desc(
+        HPCT_ANCHOR_CONV2D_NCHW, epi, HPCT_RED_MAXPOOL2_HW if pool else HPCT_RED_NONE, 0, [_sh(t) for t in ins], [_sh(out)],
+        stride_hw=(stride, stride), pad_hw=(pad, pad)))
+    return plan, ins
+
+
+def conv_block(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True, stream=None) -> None:
+    """out = maxpool2x2(relu((conv2d_nchw(inp, wt) + bias[k]) * scale[k] + shift[k])); every stage after the conv optional."""
+    plan, ins = conv_block_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, pool)
     plan.launch(ins, [out], stream)
 
 

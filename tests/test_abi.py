@@ -190,10 +190,15 @@ def test_unsupported_but_well_formed():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = cfg_desc(3); d.reduce_before_epi = 0
     expect(H.HPCT_ERR_UNSUPPORTED, d)
-    d = cfg_desc(4); d.stride_hw[0] = d.stride_hw[1] = 2
-    d.out[0] = H.tensor_desc((32, 128, 28, 28))
+    d = cfg_desc(4); d.stride_hw[0], d.stride_hw[1] = 2, 1           # anisotropic stride
+    d.out[0] = H.tensor_desc((32, 128, 28, 56))
     expect(H.HPCT_ERR_UNSUPPORTED, d)
-    d = cfg_desc(4); d.in_[1] = H.tensor_desc((128, 64, 5, 5)); d.pad_hw[0] = d.pad_hw[1] = 2
+    d = cfg_desc(4); d.stride_hw[0] = d.stride_hw[1] = 5
+    d.out[0] = H.tensor_desc((32, 128, 12, 12))
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(4); d.in_[1] = H.tensor_desc((128, 64, 4, 4)); d.out[0] = H.tensor_desc((32, 128, 55, 55))   # even filter
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(4); d.in_[1] = H.tensor_desc((128, 64, 3, 5)); d.out[0] = H.tensor_desc((32, 128, 56, 54))   # not square
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = cfg_desc(5); d.in_[0] = d.in_[1] = d.in_[2] = H.tensor_desc((16, 2048, 32)); d.out[0] = H.tensor_desc((16, 2048, 32))
     expect(H.HPCT_ERR_UNSUPPORTED, d)
@@ -350,3 +355,40 @@ def test_workspace_checks_return_before_any_launch():
     with pytest.raises(H.HpctError) as e:
         p.launch_ptrs([x, w, b], [y], workspace=w + 64, workspace_bytes=need)     # workspace inside W
     assert e.value.status == H.HPCT_ERR_BAD_DESC
+
+
+def conv_block_desc(pool=True, stride=1, R=3, pad=1, shape=(32, 64, 56, 56), K=128):
+    Nb, Cc, Hh, Ww = shape
+    Ho, Wo = (Hh + 2 * pad - R) // stride + 1, (Ww + 2 * pad - R) // stride + 1
+    return H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SCALE_SHIFT_CH, H.HPCT_EPI_RELU],
+                     H.HPCT_RED_MAXPOOL2_HW if pool else H.HPCT_RED_NONE, 0,
+                     [shape, (K, Cc, R, R), (K,), (K,), (K,)], [(Nb, K, Ho // 2, Wo // 2) if pool else (Nb, K, Ho, Wo)],
+                     stride_hw=(stride, stride), pad_hw=(pad, pad))
+
+
+def test_conv_block_plans():
+    p = H.Plan(conv_block_desc())
+    assert p.kernel_name == "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"
+    # 28 row pairs x 2 column tiles x 32 images x 2 channel blocks
+    assert p.launch_shape()[0] == (28 * 2 * 32 * 2, 1, 1) and p.launch_shape()[1] == (256, 1, 1)
+    assert p.workspace_bytes == 0
+    assert H.Plan(conv_block_desc(pool=False)).kernel_name == "conv2d_nchw_mfma<3x3,pipelined>"
+    assert H.Plan(conv_block_desc(stride=2)).kernel_name == "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"
+    assert H.Plan(conv_block_desc(pool=False, stride=2, R=7, pad=3, shape=(4, 3, 64, 64), K=64)).kernel_name == \
+        "conv2d_nchw_mfma<7x7,general>"
+    assert H.Plan(conv_block_desc(R=5, pad=2, shape=(2, 8, 30, 30), K=16)).kernel_name == "conv2d_nchw_mfma<5x5,general,maxpool2>"
+    assert H.Plan(conv_block_desc(R=1, pad=0)).kernel_name == "conv2d_nchw_mfma<1x1,pipelined,maxpool2>"
+    # errors
+    d = conv_block_desc(); d.out[0] = H.tensor_desc((32, 128, 56, 56))        # pooled output is half the size
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = conv_block_desc(); d.in_[3] = H.tensor_desc((64,))                    # scale is per OUTPUT channel
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = conv_block_desc(shape=(1, 4, 1, 8), pad=1)                            # conv output 1 x 8: nothing to pool
+    d.out[0] = H.tensor_desc((1, 128, 1, 4))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = conv_block_desc(); d.epi[1], d.epi[2] = H.HPCT_EPI_RELU, H.HPCT_EPI_SCALE_SHIFT_CH   # order not offered
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = conv_block_desc(); d.reduce = H.HPCT_RED_AVGPOOL_HW
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(2); d.reduce = H.HPCT_RED_MAXPOOL2_HW                        # pooling without a conv anchor
+    expect(H.HPCT_ERR_UNSUPPORTED, d)

@@ -297,6 +297,68 @@ def test_conv_all_ones_counts_taps_exactly():
     assert np.array_equal(got, want)  # small integers: exact in fp32
 
 
+# ----------------------------- conv block: stride, scale/shift, 2x2 max pool (VGG-style)
+def run_chain7(t, stride=1, pad=1, relu=True, pool=True, bias=True, affine=True):
+    x, w = dev(t["in"]), dev(t["wt"])
+    b = dev(t["bias"]) if bias else None
+    sc, sh = (dev(t["scale"]), dev(t["shift"])) if affine else (None, None)
+    Nb, _, H, W = t["in"].shape
+    K, _, R, S = t["wt"].shape
+    Ho, Wo = ref.conv_out_hw(H, W, R, S, stride, pad)
+    out = torch.full((Nb, K, Ho // 2, Wo // 2) if pool else (Nb, K, Ho, Wo), float("nan"), device="cuda")
+    plan, ins = hpct.conv_block_plan(x, w, b, sc, sh, out, stride, pad, relu, pool)
+    plan.launch(ins, [out])
+    return host(out), plan.kernel_name
+
+
+def check_chain7(t, stride=1, pad=1, relu=True, pool=True, bias=True, affine=True):
+    want, Dn = ref.chain7(t["in"], t["wt"], t["bias"] if bias else None, t["scale"] if affine else None,
+                          t["shift"] if affine else None, stride, pad, relu, pool)
+    if pool:   # |max a - max b| <= max |a_i - b_i|: the window's largest bound
+        Dn = ref.maxpool2x2(Dn)
+    got, name = run_chain7(t, stride, pad, relu, pool, bias, affine)
+    print("kernel", name, flush=True)
+    assert show("conv block", compare.contraction(got, want, Dn))
+    return got, name
+
+
+def test_chain7_full_size():
+    t = datagen.make(7)
+    got, name = check_chain7(t)
+    assert name == "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"
+    again, _ = run_chain7(t)
+    assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
+    # the same block without pooling goes through the kernel of chain 4 with the scale/shift epilogue
+    _, name = check_chain7(t, pool=False)
+    assert name == "conv2d_nchw_mfma<3x3,pipelined>"
+
+
+@pytest.mark.parametrize("N,C,H,W,K,R,stride,pad", [
+    (1, 1, 2, 2, 1, 1, 1, 0), (2, 3, 7, 9, 5, 3, 1, 1), (1, 8, 8, 8, 128, 3, 1, 1), (2, 10, 13, 5, 130, 3, 1, 1),
+    (1, 4, 6, 70, 7, 3, 1, 2), (1, 4, 10, 224, 64, 3, 1, 1), (1, 64, 14, 14, 64, 1, 1, 0), (1, 8, 9, 9, 20, 3, 1, 0),
+    (2, 8, 16, 16, 64, 3, 2, 1), (1, 3, 40, 40, 16, 7, 2, 3), (1, 6, 21, 33, 10, 5, 1, 2), (1, 4, 17, 17, 8, 5, 3, 2),
+    (1, 16, 12, 36, 64, 1, 2, 0), (1, 5, 30, 30, 12, 7, 1, 3), (1, 4, 64, 64, 64, 3, 4, 1)])
+def test_chain7_ragged_shapes(N, C, H, W, K, R, stride, pad):
+    print("chain7 %s" % ((N, C, H, W, K, R, stride, pad),), flush=True)
+    t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=R, S=R)
+    check_chain7(t, stride, pad)                       # the whole block
+    check_chain7(t, stride, pad, pool=False)           # conv + bias + scale/shift + relu
+    check_chain7(t, stride, pad, relu=False)           # pooling sees negative values
+    check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False)   # the bare strided conv
+
+
+def test_chain7_pool_takes_the_maximum_not_a_sum_or_a_corner():
+    # identity 1x1 conv: the block is max pooling of the input, exactly
+    X = datagen.gen_normal(11, (2, 4, 10, 66), 0.0, 1.0)
+    wt = np.zeros((4, 4, 1, 1), np.float32)
+    for k in range(4):
+        wt[k, k, 0, 0] = 1.0
+    out = torch.full((2, 4, 5, 33), float("nan"), device="cuda")
+    hpct.conv_block(dev(X), dev(wt), None, None, None, out, stride=1, pad=0, relu=False, pool=True)
+    want = X.reshape(2, 4, 5, 2, 33, 2).max(axis=(3, 5))
+    assert np.array_equal(host(out), want)
+
+
 # ------------------------------------------------------------------- chain 5
 def run_chain5(t, scale=0.125):
     Q, K, V = dev(t["Q"]), dev(t["K"]), dev(t["V"])
