@@ -28,11 +28,12 @@
 // consecutive floats of the weight row (vector LDS reads) and the B fragment of
 // every step is an LDS read at lane base + a constant.
 //
-// POOL variant: the 64 pixels of a tile are 2 output rows x 32 output columns
-// (the two pixel blocks of the work-group are the two rows), the LDS holds the
-// window of the input those need instead of whole rows, and the epilogue takes
-// the vertical maximum through LDS (the two rows live in different waves), the
-// horizontal one with a DPP lane swap, and stores one value per 2x2 window.
+// POOL variant: the 64 pixels of a tile are 8 output rows x 8 output columns
+// (each 32-pixel block is 4 rows x 8 columns, lane = 8*row + column), the LDS
+// holds the window of the input those need instead of whole rows, and the
+// epilogue takes the 2x2 maximum entirely in registers: the vertical partner
+// is 8 lanes away inside a 16-lane DPP row, the horizontal one the neighbouring
+// lane; one lane in four stores.  8 divides the 224/112/56 extents of VGG maps.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -47,7 +48,7 @@ struct ConvGeom {
     int St;        // stride
     int Ho, Wo, HoWo;
     int Hp, Wp;    // pooled output size (POOL)
-    int ctiles;    // 32-column tiles per row pair (POOL)
+    int ctiles;    // 8-column tiles per 8-row band (POOL)
     int tiles_per_img, tiles;
     int rows_max;  // input rows staged per tile
     int lpad;      // left pad of an LDS row so that iw = 0 lands on a 16-byte boundary
@@ -111,8 +112,8 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     const int tin = tile % g.tiles_per_img;
     const int p0 = POOL ? 0 : tin * TP;
     const int k0 = (item % kblocks) * KT;
-    const int h_lo = POOL ? 2 * (tin / g.ctiles) : p0 / g.Wo;  // first output row of the tile
-    const int w_lo = POOL ? 32 * (tin % g.ctiles) : 0;         // first output column of the tile (POOL)
+    const int h_lo = POOL ? 8 * (tin / g.ctiles) : p0 / g.Wo;  // first output row of the tile
+    const int w_lo = POOL ? 8 * (tin % g.ctiles) : 0;          // first output column of the tile (POOL)
     const int ih0 = h_lo * g.St - g.P;  // first staged input row
     const int iw0 = w_lo * g.St;        // input column the staged window is anchored at (POOL)
     const int HW = g.H * g.W;
@@ -213,8 +214,8 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     int p = p0 + pb + l32;
     bool p_ok;
     int oh, ow;
-    if (POOL) {  // pixel block = output row of the pair, lane = output column; the staged window covers the whole tile
-        oh = h_lo + (wave >> 1); ow = w_lo + l32;
+    if (POOL) {  // pixel block = 4 rows x 8 columns; the staged window covers the whole tile
+        oh = h_lo + 4 * (wave >> 1) + (l32 >> 3); ow = w_lo + (l32 & 7);
         p_ok = true;
     } else {
         p_ok = p < g.HoWo;
@@ -312,11 +313,10 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
             }
         }
     } else {
-        // Waves 2,3 hold output row h_lo+1 of the same channels and columns as waves 0,1 hold of row
-        // h_lo: they hand their values over through LDS (the staging area, free once every wave has
-        // finished its MFMAs), waves 0,1 take the vertical maximum, then the horizontal one with the
-        // neighbouring lane, and even lanes store.
-        float* const xch = lds + (wave & 1) * (KB * 16 * 64) + lane;
+        // lane = 8*row + column inside the block: the vertical partner of a window is lane ^ 8
+        // (a rotation by 8 inside the 16-lane DPP row), the horizontal one lane ^ 1
+        const int rp = oh >> 1, px = ow >> 1;
+        const bool st_ok = (lane & 9) == 0 && rp < g.Hp && px < g.Wp;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -324,29 +324,11 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
                 const int kl = kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                 float v = acc[kb][r] * mulS[kl] + addS[kl];
                 if (epi.relu) v = fmaxf(v, 0.f);
-                acc[kb][r] = v;
+                v = fmaxf(v, dpp_mov<0x128>(v));  // row_ror:8
+                v = fmaxf(v, dpp_mov<0xB1>(v));   // quad_perm [1,0,3,2]
+                const int k = k0 + kl;
+                if (st_ok && k < g.K) out[(((int64_t)n * g.K + k) * g.Hp + rp) * g.Wp + px] = v;
             }
-        __syncthreads();
-        if (wave >> 1) {
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) xch[(kb * 16 + r) * 64] = acc[kb][r];
-        }
-        __syncthreads();
-        if ((wave >> 1) == 0) {
-            const int rp = h_lo >> 1, px = ow >> 1;
-            const bool st_ok = (lane & 1) == 0 && rp < g.Hp && px < g.Wp;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float v = fmaxf(acc[kb][r], xch[(kb * 16 + r) * 64]);
-                    v = fmaxf(v, dpp_mov<0xB1>(v));  // lane ^ 1: the other column of the window
-                    const int k = k0 + kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                    if (st_ok && k < g.K) out[(((int64_t)n * g.K + k) * g.Hp + rp) * g.Wp + px] = v;
-                }
-        }
     }
 }
 
@@ -359,10 +341,10 @@ ConvGeom geom(const ConvParams& p) {
     g.lpad = (4 - p.pad % 4) % 4;
     if (p.pool) {
         g.Hp = g.Ho / 2; g.Wp = g.Wo / 2;
-        g.ctiles = (2 * g.Wp + 31) / 32;
-        g.tiles_per_img = g.Hp * g.ctiles;
-        g.rows_max = p.stride + p.R;                                       // two output rows
-        g.ldw = (31 * p.stride + p.S + g.lpad + 3) & ~3;                   // 32 output columns
+        g.ctiles = (2 * g.Wp + 7) / 8;
+        g.tiles_per_img = ((2 * g.Hp + 7) / 8) * g.ctiles;
+        g.rows_max = 7 * p.stride + p.R;                                   // eight output rows
+        g.ldw = (7 * p.stride + p.S + g.lpad + 3) & ~3;                    // eight output columns
     } else {
         g.tiles_per_img = (g.HoWo + TP - 1) / TP;
         // a run of TP consecutive pixels touches at most (TP-1)/Wo + 2 output rows
@@ -372,15 +354,19 @@ ConvGeom geom(const ConvParams& p) {
         g.ldw = (p.W + 2 * p.pad + g.lpad + 3) & ~3;
     }
     g.tiles = p.Nb * g.tiles_per_img;
+    // The two lane halves read the same pixel pattern of channels kCC/2 apart in one LDS access.
+    // Channel stride = 16 (mod 32) words puts the halves' 32-word runs on complementary bank halves;
+    // in the pooled geometry a half covers words 0-7 of four 16-word rows, and a channel stride of
+    // 4 (mod 32) moves the other half onto words 8-15.
+    const int want = p.pool ? 4 : 16;
     g.ch_ld = g.rows_max * g.ldw;
+    g.ch_ld += ((want - g.ch_ld % 32) + 32) % 32;
     return g;
 }
 
 template <int R, int CC, int KT>
-size_t lds_bytes(const ConvGeom& g, bool pool) {
-    size_t b = (size_t)(2 * CC * g.ch_ld + 2 * Cfg<R, CC, KT>::W_STAGE + 2 * KT) * 4;
-    const size_t xch = (size_t)2 * (KT / 64) * 16 * 64 * 4;  // the pooling hand-over reuses the staging area
-    return pool && b < xch ? xch : b;
+size_t lds_bytes(const ConvGeom& g) {
+    return (size_t)(2 * CC * g.ch_ld + 2 * Cfg<R, CC, KT>::W_STAGE + 2 * KT) * 4;
 }
 
 // Input channels per LDS chunk and output channels per work-group.  4 x 64
@@ -399,7 +385,7 @@ int conv_items(const ConvParams& p, const ConvGeom& g) { return g.tiles * ((p.K 
 
 template <int R, bool FAST, bool POOL>
 hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
-    const size_t lds = lds_bytes<R, kCC, kKT>(g, POOL);
+    const size_t lds = lds_bytes<R, kCC, kKT>(g);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, kCC, kKT, FAST, POOL>),
@@ -414,7 +400,7 @@ hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t strea
 }
 
 template <int R>
-size_t lds_for(const ConvParams& p) { return lds_bytes<R, kCC, kKT>(geom(p), p.pool != 0); }
+size_t lds_for(const ConvParams& p) { return lds_bytes<R, kCC, kKT>(geom(p)); }
 
 size_t lds_any(const ConvParams& p) {
     switch (p.R) {
@@ -446,7 +432,7 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
     if (pad_h > R - 1) { *why = "padding larger than the filter extent minus one"; return false; }
     ConvParams p{};
     p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.pool = pool;
-    if (lds_any(p) > 160 * 1024) { *why = "the input rows of one 64-pixel tile do not fit in LDS (image too wide)"; return false; }
+    if (lds_any(p) > 160 * 1024) { *why = "the input of one 64-pixel tile does not fit in LDS (image too wide)"; return false; }
     return true;
 }
 

@@ -369,8 +369,8 @@ def conv_block_desc(pool=True, stride=1, R=3, pad=1, shape=(32, 64, 56, 56), K=1
 def test_conv_block_plans():
     p = H.Plan(conv_block_desc())
     assert p.kernel_name == "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"
-    # 28 row pairs x 2 column tiles x 32 images x 2 channel blocks
-    assert p.launch_shape()[0] == (28 * 2 * 32 * 2, 1, 1) and p.launch_shape()[1] == (256, 1, 1)
+    # 7 x 7 tiles of 8 x 8 output pixels x 32 images x 2 channel blocks
+    assert p.launch_shape()[0] == (7 * 7 * 32 * 2, 1, 1) and p.launch_shape()[1] == (256, 1, 1)
     assert p.workspace_bytes == 0
     assert H.Plan(conv_block_desc(pool=False)).kernel_name == "conv2d_nchw_mfma<3x3,pipelined>"
     assert H.Plan(conv_block_desc(stride=2)).kernel_name == "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"
