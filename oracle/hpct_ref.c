@@ -326,3 +326,49 @@ void ref_maxpool2x2_planes(const double *T, int64_t planes, int64_t H, int64_t W
         }
     }
 }
+
+/* ---- Reduction (Table 1: "sum, mean" and the arg-reductions) over one axis of
+ * a strided view.  The view has `nd` dims with `shape` and `stride` (elements,
+ * >= 0); the output is the view with dim `axis` removed, row-major.
+ *   op 0: sum      out_val = sum_r x_r
+ *   op 1: mean     out_val = (sum_r x_r) / R
+ *   op 2: argmax   out_idx = the smallest r with x_r = max_r x_r
+ *   op 3: argmin   out_idx = the smallest r with x_r = min_r x_r
+ * For op 0/1 out_abs (may be NULL) receives sum_r |x_r| (divided by R for the
+ * mean), the scale a summation's rounding error is measured against.
+ * Values are widened to double; comparisons of fp32 values are exact. */
+void ref_reduce_axis(const float *in, int32_t nd, const int64_t *shape, const int64_t *stride,
+                     int32_t axis, int32_t op, double *out_val, double *out_abs, int64_t *out_idx)
+{
+    int64_t outer = 1;
+    for (int32_t d = 0; d < nd; ++d) if (d != axis) outer *= shape[d];
+    const int64_t R = shape[axis], sR = stride[axis];
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < outer; ++o) {
+        int64_t rem = o, base = 0;
+        for (int32_t d = nd - 1; d >= 0; --d) {
+            if (d == axis) continue;
+            base += (rem % shape[d]) * stride[d];
+            rem /= shape[d];
+        }
+        if (op <= 1) {
+            double s = 0.0, a = 0.0;
+            for (int64_t r = 0; r < R; ++r) {
+                double x = (double)in[base + r * sR];
+                s += x;
+                a += fabs(x);
+            }
+            if (op == 1) { s /= (double)R; a /= (double)R; }
+            out_val[o] = s;
+            if (out_abs) out_abs[o] = a;
+        } else {
+            int64_t best = 0;
+            double bv = (double)in[base];
+            for (int64_t r = 1; r < R; ++r) {
+                double x = (double)in[base + r * sR];
+                if (op == 2 ? x > bv : x < bv) { bv = x; best = r; }
+            }
+            out_idx[o] = best;
+        }
+    }
+}

@@ -40,6 +40,7 @@ def lib():
             "ref_mean_rows": [p, i64, i64, p],
             "ref_scale_shift_planes": [p, p, p, i64, i64, i64],
             "ref_maxpool2x2_planes": [p, i64, i64, i64, p],
+            "ref_reduce_axis": [p, C.c_int32, p, p, C.c_int32, C.c_int32, p, p, p],
         }
         for name, args in sig.items():
             f = getattr(_lib, name)
@@ -210,6 +211,32 @@ def maxpool2x2(T):
     if out.size:
         lib().ref_maxpool2x2_planes(_ptr(T), Nb * Cc, H, W, _ptr(out))
     return out
+
+
+REDUCE_OPS = {"sum": 0, "mean": 1, "argmax": 2, "argmin": 3}
+
+
+def reduce_axis(base, shape, stride, axis, op, want_abs=False):
+    """Reduction `op` in {"sum","mean","argmax","argmin"} over dim `axis` of the strided view
+    (shape, stride in elements) of the flat fp32 array `base`.  Returns fp64 values (and the
+    sum of magnitudes with want_abs) for sum / mean, int64 indices for the arg-reductions."""
+    base = _f32(base).reshape(-1)
+    nd = len(shape)
+    assert 0 <= axis < nd
+    top = sum((n - 1) * s for n, s in zip(shape, stride))
+    assert all(s >= 0 for s in stride) and top < base.size
+    sh = (C.c_int64 * nd)(*shape)
+    st = (C.c_int64 * nd)(*stride)
+    oshape = tuple(n for d, n in enumerate(shape) if d != axis)
+    code = REDUCE_OPS[op]
+    if code <= 1:
+        val = np.empty(oshape, dtype=np.float64)
+        ab = np.empty(oshape, dtype=np.float64) if want_abs else None
+        lib().ref_reduce_axis(_ptr(base), nd, sh, st, axis, code, _ptr(val), _ptr(ab), None)
+        return (val, ab) if want_abs else val
+    idx = np.empty(oshape, dtype=np.int64)
+    lib().ref_reduce_axis(_ptr(base), nd, sh, st, axis, code, None, None, _ptr(idx))
+    return idx
 
 
 # -------------------------------------------------------------------- chains

@@ -619,3 +619,58 @@ def test_chain7_composition():
     want = np.maximum(aff, 0).reshape(2, 4, 3, 2, 3, 2).max(axis=(3, 5))
     assert np.array_equal(out, want)
     assert Dn.shape == conv.shape and np.all(Dn >= np.abs(aff) - 1e-12)   # the normaliser bounds the value it scales
+
+
+# -------------------------------------------------- reductions over one axis
+def _view(base, shape, stride):
+    return np.lib.stride_tricks.as_strided(base, shape=shape, strides=[4 * s for s in stride])
+
+
+def test_reduce_axis_against_numpy_on_strided_views():
+    base = f32(rng.normal(size=4000))
+    cases = [((6, 7, 8), (56, 8, 1)),          # contiguous
+             ((8, 7, 6), (1, 8, 56)),          # fully permuted
+             ((5, 4, 9), (100, 20, 2)),        # gaps and a strided inner dim
+             ((3, 6, 5), (0, 5, 1)),           # broadcast outer dim
+             ((4, 1, 7), (7, 0, 1)),
+             ((12,), (3,))]
+    for shape, stride in cases:
+        v = _view(base, shape, stride).astype(np.float64)
+        for axis in range(len(shape)):
+            s, a = ref.reduce_axis(base, shape, stride, axis, "sum", want_abs=True)
+            assert np.allclose(s, v.sum(axis=axis), rtol=0, atol=1e-12)
+            assert np.allclose(a, np.abs(v).sum(axis=axis), rtol=0, atol=1e-12)
+            assert np.allclose(ref.reduce_axis(base, shape, stride, axis, "mean"), v.mean(axis=axis), rtol=0, atol=1e-13)
+            assert np.array_equal(ref.reduce_axis(base, shape, stride, axis, "argmax"), v.argmax(axis=axis))
+            assert np.array_equal(ref.reduce_axis(base, shape, stride, axis, "argmin"), v.argmin(axis=axis))
+
+
+def test_reduce_axis_closed_forms_and_output_order():
+    # x[i][j][k] = 100 i + 10 j + k on a 3 x 4 x 5 grid: sums have closed forms and show which axis went away
+    i, j, k = np.meshgrid(np.arange(3), np.arange(4), np.arange(5), indexing="ij")
+    x = f32(100 * i + 10 * j + k)
+    s0 = ref.reduce_axis(x, (3, 4, 5), (20, 5, 1), 0, "sum")
+    assert s0.shape == (4, 5) and np.array_equal(s0, 300 + 3 * (10 * np.arange(4)[:, None] + np.arange(5)[None, :]))
+    s1 = ref.reduce_axis(x, (3, 4, 5), (20, 5, 1), 1, "sum")
+    assert s1.shape == (3, 5) and np.array_equal(s1, 4 * (100 * np.arange(3)[:, None] + np.arange(5)[None, :]) + 60)
+    m2 = ref.reduce_axis(x, (3, 4, 5), (20, 5, 1), 2, "mean")
+    assert m2.shape == (3, 4) and np.array_equal(m2, 100 * np.arange(3)[:, None] + 10 * np.arange(4)[None, :] + 2.0)
+    # increasing along every axis: argmax is the last index, argmin the first
+    for ax, n in enumerate((3, 4, 5)):
+        assert np.all(ref.reduce_axis(x, (3, 4, 5), (20, 5, 1), ax, "argmax") == n - 1)
+        assert np.all(ref.reduce_axis(x, (3, 4, 5), (20, 5, 1), ax, "argmin") == 0)
+
+
+def test_arg_reductions_break_ties_towards_the_lowest_index():
+    x = f32([2, 7, 7, 1, 7, 1, 1, 3])
+    assert ref.reduce_axis(x, (8,), (1,), 0, "argmax") == 1
+    assert ref.reduce_axis(x, (8,), (1,), 0, "argmin") == 3
+    assert ref.reduce_axis(np.zeros(9, np.float32), (9,), (1,), 0, "argmax") == 0
+    # -0 and +0 compare equal: the first of them wins either way
+    z = f32([0.0, -0.0, 0.0])
+    assert ref.reduce_axis(z, (3,), (1,), 0, "argmin") == 0 and ref.reduce_axis(z, (3,), (1,), 0, "argmax") == 0
+    # a broadcast (stride 0) axis is all ties
+    assert np.all(ref.reduce_axis(f32(rng.normal(size=5)), (5, 4), (1, 0), 1, "argmax") == 0)
+    # magnitudes do not matter, order does
+    assert ref.reduce_axis(f32([-5, -1, -9]), (3,), (1,), 0, "argmax") == 1
+    assert ref.reduce_axis(f32([-5, -1, -9]), (3,), (1,), 0, "argmin") == 2
