@@ -12,10 +12,11 @@
  * reduction from the workspace).
  *
  * Conventions
- *  - All tensors are fp32, described by shape and stride in ELEMENTS.
+ *  - All tensors are fp32 (the index output of an arg-reduction is int32), described by
+ *    shape and stride in ELEMENTS.
  *  - Every data pointer passed to hpct_plan_launch is a DEVICE pointer owned
  *    by the caller, 16-byte aligned (4-byte aligned suffices for a layout
- *    transform, whose input may be a view that starts anywhere).  Descriptors, plans and the pointer
+ *    transform or an axis reduction, whose input may be a view that starts anywhere).  Descriptors, plans and the pointer
  *    arrays themselves live in HOST memory.
  *  - The library never allocates, frees, copies or synchronises device memory.
  *    Inputs are never written.  Outputs must not overlap inputs.
@@ -40,6 +41,10 @@
  *   NONE  SOFTMAX_LAST                                X[M,N]                        [M,N]
  *   NONE  (no epilogue, no reduction): layout         X: any strided view (stride   same shape,
  *         transform, out = contiguous copy of X       >= 0, up to 6 dims)           contiguous
+ *   NONE  SUM_AXIS | MEAN_AXIS | ARGMAX_AXIS |        X: any strided view (stride   X's shape without
+ *         ARGMIN_AXIS over dim `axis`, no epilogue    >= 0, up to 6 dims)           dim `axis`, contiguous
+ *                                                                                   (1-D input: shape [1]);
+ *                                                                                   int32 for the arg ops
  *   CONV2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH] [+RELU] in[N,C,H,W], wt[K,C,R,S],     [N,K,Ho,Wo], or
  *         then MAXPOOL2_HW or no reduction            bias[K], scale[K], shift[K]   [N,K,Ho/2,Wo/2]
  *         (square 1/3/5/7 filter, stride <= 4,                                       with MAXPOOL2_HW
@@ -68,7 +73,10 @@ typedef enum {
     HPCT_ERR_HIP = 7              /* the HIP runtime refused the launch */
 } hpct_status;
 
-typedef enum { HPCT_F32 = 0 } hpct_dtype;
+typedef enum {
+    HPCT_F32 = 0,
+    HPCT_I32 = 1   /* only as the output of the arg-reductions */
+} hpct_dtype;
 
 #define HPCT_MAX_DIMS 6
 #define HPCT_MAX_EPI 8
@@ -112,8 +120,12 @@ typedef enum {
     HPCT_RED_LAYERNORM_LAST = 2,  /* (x - mean) / sqrt(biased var + eps) * gamma + beta over the last dim */
     HPCT_RED_AVGPOOL_HW = 3,      /* mean over dims 2,3 of NCHW */
     HPCT_RED_MEAN_LAST = 4,       /* mean over the last dim, which is dropped: [M,N] -> [M].  GEMM anchor only. */
-    HPCT_RED_MAXPOOL2_HW = 5      /* max over non-overlapping 2x2 windows of dims 2,3 (stride 2; an odd last row or
+    HPCT_RED_MAXPOOL2_HW = 5,     /* max over non-overlapping 2x2 windows of dims 2,3 (stride 2; an odd last row or
                                      column is dropped): [N,K,Ho,Wo] -> [N,K,Ho/2,Wo/2].  Conv anchor only. */
+    HPCT_RED_SUM_AXIS = 6,        /* sum over dim `axis`, which is dropped */
+    HPCT_RED_MEAN_AXIS = 7,       /* mean over dim `axis`, which is dropped */
+    HPCT_RED_ARGMAX_AXIS = 8,     /* int32 index of the maximum along dim `axis`; of equal values the lowest index */
+    HPCT_RED_ARGMIN_AXIS = 9      /* int32 index of the minimum along dim `axis`; of equal values the lowest index */
 } hpct_reduce;
 
 typedef struct {
@@ -134,6 +146,7 @@ typedef struct {
     hpct_reduce reduce2;          /* a second reduction applied to the result of `reduce`; only SOFTMAX_LAST
                                      after MEAN_LAST (softmax over the M row means), else HPCT_RED_NONE */
     uint64_t dropout_seed;        /* DROPOUT_HASH */
+    int32_t axis;                 /* *_AXIS reductions: the dimension of in[0] that is reduced, 0 <= axis < ndim */
 } hpct_op_desc;
 
 typedef struct hpct_plan hpct_plan;   /* opaque; host memory */

@@ -26,7 +26,7 @@ hpct_status fail(hpct_status st, const char* fmt, ...) {
 
 void clear_err() { g_err[0] = 0; }
 
-enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout };
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce };
 
 constexpr int64_t kI32Max = 2147483647LL;
 
@@ -50,16 +50,18 @@ struct hpct_plan {
         ConvParams conv;
         AttnParams attn;
         LayoutParams layout;
+        ReduceParams red;
     } u;
 };
 
 namespace {
 
 // ndim / shape / stride / dtype sanity and the byte extent; overflow-safe.
-hpct_status check_tensor(const hpct_tensor_desc& t, const char* what, int idx, int64_t* count, int64_t* extent_bytes) {
+hpct_status check_tensor(const hpct_tensor_desc& t, const char* what, int idx, bool want_i32, int64_t* count, int64_t* extent_bytes) {
     if (t.ndim < 1 || t.ndim > HPCT_MAX_DIMS)
         return fail(HPCT_ERR_BAD_DESC, "%s[%d]: ndim %d outside 1..%d", what, idx, t.ndim, HPCT_MAX_DIMS);
-    if (t.dtype != HPCT_F32) return fail(HPCT_ERR_UNSUPPORTED, "%s[%d]: dtype %d (only fp32)", what, idx, (int)t.dtype);
+    if (t.dtype != (want_i32 ? HPCT_I32 : HPCT_F32))
+        return fail(HPCT_ERR_UNSUPPORTED, "%s[%d]: dtype %d (%s here)", what, idx, (int)t.dtype, want_i32 ? "int32 indices" : "only fp32");
     int64_t n = 1, maxoff = 0;
     for (int d = 0; d < t.ndim; ++d) {
         if (t.shape[d] <= 0) return fail(HPCT_ERR_BAD_DESC, "%s[%d]: shape[%d] = %lld must be > 0", what, idx, d, (long long)t.shape[d]);
@@ -291,6 +293,55 @@ hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p) {
     return HPCT_OK;
 }
 
+// Reduction over one axis of a strided view: no anchor, no epilogue; the output is the view
+// without that axis, contiguous.
+hpct_status plan_reduce(const hpct_op_desc& d, hpct_plan& p) {
+    if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "axis reductions take no epilogues");
+    if (d.n_in != 1 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "an axis reduction takes 1 input and 1 output");
+    const hpct_tensor_desc &I = d.in[0], &O = d.out[0];
+    if (d.axis < 0 || d.axis >= I.ndim) return fail(HPCT_ERR_BAD_DESC, "axis = %d outside 0..%d", d.axis, I.ndim - 1);
+    // expected output shape: the input's without `axis`; a 1-D input reduces to shape [1]
+    int64_t want[HPCT_MAX_DIMS];
+    int nw = 0;
+    for (int k = 0; k < I.ndim; ++k)
+        if (k != d.axis) want[nw++] = I.shape[k];
+    if (nw == 0) want[nw++] = 1;
+    if (!shape_is(O, nw, want)) return fail(HPCT_ERR_SHAPE_MISMATCH, "out[0] must have the input's shape without dim %d", d.axis);
+    if (!contiguous(O)) return fail(HPCT_ERR_UNSUPPORTED, "axis reduction: the output must be contiguous");
+    if (I.shape[d.axis] > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "axis reduction: more than 2^31-1 elements along the axis");
+    ReduceParams q{};
+    q.R = (int32_t)I.shape[d.axis];
+    q.sR = I.stride[d.axis];
+    q.op = d.reduce == HPCT_RED_ARGMAX_AXIS ? 2 : (d.reduce == HPCT_RED_ARGMIN_AXIS ? 3 : 0);
+    q.mean = d.reduce == HPCT_RED_MEAN_AXIS ? 1 : 0;
+    // kept dimensions: drop extent 1, merge neighbours that are contiguous with each other in the input
+    int nk = 0;
+    int64_t sh[HPCT_MAX_DIMS], st[HPCT_MAX_DIMS];
+    for (int k = 0; k < I.ndim; ++k) {
+        if (k == d.axis || I.shape[k] == 1) continue;
+        if (nk > 0 && st[nk - 1] == I.shape[k] * I.stride[k]) {
+            sh[nk - 1] *= I.shape[k];
+            st[nk - 1] = I.stride[k];
+        } else {
+            sh[nk] = I.shape[k]; st[nk] = I.stride[k]; ++nk;
+        }
+    }
+    if (nk > kReduceDims) return fail(HPCT_ERR_UNSUPPORTED, "axis reduction: more than %d kept dimensions after collapsing", kReduceDims);
+    q.nk = nk;
+    q.outputs = 1;
+    for (int k = 0; k < nk; ++k) { q.shape[k] = sh[k]; q.stride[k] = st[k]; q.outputs *= sh[k]; }
+    if (q.sR == 1 || q.R == 1) q.kind = 0;
+    else if (nk > 0 && q.stride[nk - 1] == 1) q.kind = 1;
+    else q.kind = 2;
+    // 32-bit grids
+    if (q.outputs > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "axis reduction: more than 2^31-1 outputs");
+    p.kind = Kind::Reduce;
+    p.u.red = q;
+    p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
+    p.shape = reduce_shape(q);
+    return HPCT_OK;
+}
+
 hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
     static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU};
     bool has[3];
@@ -384,8 +435,8 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
     if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONV2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
-    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_MAXPOOL2_HW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
-    if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MAXPOOL2_HW) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_ARGMIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_ARGMIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)
@@ -397,17 +448,20 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     tmp.n_out = d.n_out;
     int64_t cnt;
     for (int i = 0; i < d.n_in; ++i) {
-        hpct_status st = check_tensor(d.in[i], "in", i, &cnt, &tmp.in_bytes[i]);
+        hpct_status st = check_tensor(d.in[i], "in", i, false, &cnt, &tmp.in_bytes[i]);
         if (st != HPCT_OK) return st;
     }
     for (int i = 0; i < d.n_out; ++i) {
-        hpct_status st = check_tensor(d.out[i], "out", i, &cnt, &tmp.out_bytes[i]);
+        const bool arg = d.reduce == HPCT_RED_ARGMAX_AXIS || d.reduce == HPCT_RED_ARGMIN_AXIS;
+        hpct_status st = check_tensor(d.out[i], "out", i, arg, &cnt, &tmp.out_bytes[i]);
         if (st != HPCT_OK) return st;
         for (int k = 0; k < d.out[i].ndim; ++k)
             if (d.out[i].stride[k] == 0 && d.out[i].shape[k] > 1)
                 return fail(HPCT_ERR_BAD_DESC, "out[%d]: stride 0 on a dimension of extent > 1 makes output elements overlap", i);
     }
 
+    if (d.reduce >= HPCT_RED_SUM_AXIS && d.anchor != HPCT_ANCHOR_NONE)
+        return fail(HPCT_ERR_UNSUPPORTED, "axis reductions are supported only without an anchor");
     hpct_status st;
     switch (d.anchor) {
         case HPCT_ANCHOR_GEMM: st = plan_gemm(d, tmp); break;
@@ -416,7 +470,8 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         default:
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
             if (d.reduce == HPCT_RED_MAXPOOL2_HW) return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL2_HW is supported only after a conv anchor");
-            if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
+            if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);
+            else if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
             else if (d.reduce == HPCT_RED_NONE && d.n_epi == 0 && d.n_in >= 1 &&
                      !(d.in[0].ndim == 4 && contiguous(d.in[0]))) st = plan_layout(d, tmp);
             else st = plan_affine(d, tmp);
@@ -441,7 +496,7 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
     }
     // layout transforms accept views that start anywhere (element alignment); their vector variant is
     // replaced by the scalar one at launch when a base is not 16-byte aligned
-    const uintptr_t amask = plan->kind == Kind::Layout ? 3 : 15;
+    const uintptr_t amask = (plan->kind == Kind::Layout || plan->kind == Kind::Reduce) ? 3 : 15;
     for (int i = 0; i < plan->n_in; ++i) {
         if (!in_ptrs[i]) return fail(HPCT_ERR_NULL, "in_ptrs[%d] is NULL", i);
         if ((uintptr_t)in_ptrs[i] & amask) return fail(HPCT_ERR_ALIGNMENT, "in_ptrs[%d] is not %d-byte aligned", i, (int)amask + 1);
@@ -506,6 +561,12 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
             q.in = in(0); q.out = (float*)out_ptrs[0];
             if (q.kind == 1 && (((uintptr_t)q.in | (uintptr_t)q.out) & 15)) q.kind = 0;
             e = layout_launch(q, stream);
+            break;
+        }
+        case Kind::Reduce: {
+            ReduceParams q = plan->u.red;
+            q.in = in(0); q.out = out_ptrs[0];
+            e = reduce_launch(q, stream);
             break;
         }
         case Kind::Attn: {

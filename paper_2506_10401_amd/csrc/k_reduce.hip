@@ -1,0 +1,340 @@
+// Reduction operators over one axis of a strided view (Table 1 of the paper:
+// Reduction "sum, mean", and the arg-reductions): sum, mean, argmax, argmin.
+// Memory-bound: every input element is read once.  The plan layer removes the
+// reduced axis (extent R, input stride sR), collapses the kept dimensions and
+// picks one of three kernels by where the contiguous direction of the input lies:
+//
+//   reduce_rows   sR == 1: the reduced axis is contiguous.  A wave (or, for few
+//                 and long rows, a work-group) owns one output; its lanes stride
+//                 over the row with 128-bit loads and combine with DPP.
+//   reduce_cols   the innermost kept dimension is contiguous in the input: threads
+//                 lie along it (coalesced loads and stores), the 256 threads of a
+//                 work-group are TC column threads x TR row groups, each row group
+//                 walks every TR-th element of the reduced axis, and the groups'
+//                 partial results are combined through LDS in group order.
+//   reduce_gather anything else: a thread per output walks the reduced axis.
+//
+// All combinations run in a fixed order, so results are bit-identical from run
+// to run.  Arg-reductions compare fp32 values exactly and resolve ties towards
+// the lowest index, whatever the order partial results are combined in.
+#include "kernels.hpp"
+#include "prim.hpp"
+
+namespace hpct {
+namespace {
+
+constexpr int kThreads = 256;
+
+// Running result of a reduction: a sum, or the best value with its index.
+template <int OP> struct Acc;
+template <> struct Acc<0> {  // sum / mean
+    float s = 0.f;
+    __device__ __forceinline__ void take(float x, int) { s += x; }
+    __device__ __forceinline__ void merge(const Acc& o) { s += o.s; }
+};
+template <bool MAX> struct ArgAcc {
+    float v = MAX ? -INFINITY : INFINITY;
+    int i = 0x7fffffff;
+    // elements arrive in increasing index order: a strict comparison keeps the first of equals
+    __device__ __forceinline__ void take(float x, int idx) {
+        if (MAX ? x > v : x < v) { v = x; i = idx; }
+        else if (i == 0x7fffffff) { v = x; i = idx; }   // first element (also when it is +-inf)
+    }
+    __device__ __forceinline__ void merge(const ArgAcc& o) {
+        const bool better = MAX ? o.v > v : o.v < v;
+        if (better || (o.v == v && o.i < i)) { v = o.v; i = o.i; }
+    }
+};
+template <> struct Acc<2> : ArgAcc<true> {};
+template <> struct Acc<3> : ArgAcc<false> {};
+
+template <int CTRL, int OP>
+__device__ __forceinline__ Acc<OP> dpp_acc(const Acc<OP>& a) {
+    Acc<OP> o;
+    if constexpr (OP == 0) {
+        o.s = dpp_mov<CTRL>(a.s);
+    } else {
+        o.v = dpp_mov<CTRL>(a.v);
+        o.i = __builtin_bit_cast(int, dpp_mov<CTRL>(__builtin_bit_cast(float, a.i)));
+    }
+    return o;
+}
+
+template <int OP>
+__device__ __forceinline__ Acc<OP> lane_acc(const Acc<OP>& a, int lane) {
+    Acc<OP> o;
+    if constexpr (OP == 0) {
+        o.s = readlane_f(a.s, lane);
+    } else {
+        o.v = readlane_f(a.v, lane);
+        o.i = __builtin_amdgcn_readlane(a.i, lane);
+    }
+    return o;
+}
+
+// all 64 lanes -> wave-uniform result, fixed order
+template <int OP>
+__device__ __forceinline__ Acc<OP> wave_combine(Acc<OP> a) {
+    a.merge(dpp_acc<0xB1, OP>(a));
+    a.merge(dpp_acc<0x4E, OP>(a));
+    a.merge(dpp_acc<0x141, OP>(a));
+    a.merge(dpp_acc<0x140, OP>(a));
+    Acc<OP> r = lane_acc<OP>(a, 0);
+    r.merge(lane_acc<OP>(a, 16));
+    r.merge(lane_acc<OP>(a, 32));
+    r.merge(lane_acc<OP>(a, 48));
+    return r;
+}
+
+template <int OP>
+__device__ __forceinline__ void emit(const ReduceParams& p, int64_t o, const Acc<OP>& a) {
+    if constexpr (OP == 0) {
+        reinterpret_cast<float*>(p.out)[o] = p.mean ? a.s / (float)p.R : a.s;
+    } else {
+        reinterpret_cast<int32_t*>(p.out)[o] = a.i;
+    }
+}
+
+// input offset of output element o (row-major over the kept dimensions)
+__device__ __forceinline__ int64_t kept_offset(const ReduceParams& p, int64_t o) {
+    int64_t off = 0;
+#pragma unroll
+    for (int d = kReduceDims - 1; d >= 0; --d) {
+        if (d < p.nk) {
+            const int64_t q = o / p.shape[d];
+            off += (o - q * p.shape[d]) * p.stride[d];
+            o = q;
+        }
+    }
+    return off;
+}
+
+// ---- reduced axis contiguous.  WPO = waves per output: 1 (a wave per output) or
+// 4 (a work-group per output).  VEC: R, every kept stride and the base are multiples of 4.
+template <int OP, bool VEC, int WPO>
+__global__ __launch_bounds__(kThreads) void reduce_rows(ReduceParams p) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t o = WPO == 1 ? (int64_t)blockIdx.x * 4 + wave : (int64_t)blockIdx.x;
+    const bool live = o < p.outputs;   // wave-uniform
+    Acc<OP> a;
+    if (live) {
+        const float* row = p.in + kept_offset(p, o);
+        const int R = p.R;
+        constexpr int E = VEC ? 4 : 1;
+        const int step = 64 * E * WPO;
+        for (int i = (wave * (WPO == 1 ? 0 : 64) + lane) * E; i < R; i += step) {
+            if (VEC) {
+                const float4v x = load4_nt(row + i);
+                a.take(x.x, i); a.take(x.y, i + 1); a.take(x.z, i + 2); a.take(x.w, i + 3);
+            } else {
+                a.take(row[(int64_t)i * p.sR], i);
+            }
+        }
+        a = wave_combine<OP>(a);
+    }
+    if (WPO == 1) {
+        if (live && lane == 0) emit<OP>(p, o, a);
+    } else {
+        if (lane == 0) {
+            if constexpr (OP == 0) sv[wave] = a.s; else { sv[wave] = a.v; si[wave] = a.i; }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0 && live) {
+            Acc<OP> r;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                Acc<OP> t;
+                if constexpr (OP == 0) t.s = sv[w]; else { t.v = sv[w]; t.i = si[w]; }
+                if (w == 0) r = t; else r.merge(t);
+            }
+            emit<OP>(p, o, r);
+        }
+    }
+}
+
+// ---- innermost kept dimension contiguous (extent Lc): TC column threads x TR row
+// groups, V columns per thread.  blockIdx.x = strip of TC*V columns, blockIdx.y =
+// index over the other kept dimensions.
+constexpr int kColsUnroll = 8;  // elements of the reduced axis in flight per thread
+
+template <int OP, int V>
+__global__ __launch_bounds__(kThreads) void reduce_cols(ReduceParams p, int tc_log2, int strips) {
+    __shared__ float sv[kThreads * V];
+    __shared__ int si[OP == 0 ? 1 : kThreads * V];
+    const int TC = 1 << tc_log2, TR = kThreads >> tc_log2;
+    const int ct = threadIdx.x & (TC - 1), rg = threadIdx.x >> tc_log2;
+    const int64_t Lc = p.shape[p.nk - 1];
+    const int64_t strip = blockIdx.x % strips, rest0 = blockIdx.x / strips;
+    const int64_t c = (strip * TC + ct) * V;
+    // offset of the other kept dimensions
+    int64_t rest = rest0, off = 0;
+#pragma unroll
+    for (int d = kReduceDims - 2; d >= 0; --d) {
+        if (d < p.nk - 1) {
+            const int64_t q = rest / p.shape[d];
+            off += (rest - q * p.shape[d]) * p.stride[d];
+            rest = q;
+        }
+    }
+    Acc<OP> a[V];
+    if (c < Lc) {
+        const float* src = p.in + off + c;
+        const int R = p.R;
+        const int64_t sR = p.sR;
+        int r = rg;
+        constexpr int U = kColsUnroll;
+        for (; r + (U - 1) * TR < R; r += U * TR) {
+            float x[U][V];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if constexpr (V == 4) {
+                    const float4v t = load4_nt(src + (int64_t)(r + u * TR) * sR);
+                    x[u][0] = t.x; x[u][1] = t.y; x[u][2] = t.z; x[u][3] = t.w;
+                } else {
+                    x[u][0] = __builtin_nontemporal_load(src + (int64_t)(r + u * TR) * sR);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < V; ++v) a[v].take(x[u][v], r + u * TR);
+        }
+        for (; r < R; r += TR) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) a[v].take(src[(int64_t)r * sR + v], r);
+        }
+    }
+    // row groups 1.. publish, group 0 merges them in order
+    if (rg > 0) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int slot = (rg * TC + ct) * V + v;
+            if constexpr (OP == 0) sv[slot] = a[v].s; else { sv[slot] = a[v].v; si[slot] = a[v].i; }
+        }
+    }
+    __syncthreads();
+    if (rg == 0 && c < Lc) {
+        for (int g = 1; g < TR; ++g) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const int slot = (g * TC + ct) * V + v;
+                Acc<OP> t;
+                if constexpr (OP == 0) t.s = sv[slot]; else { t.v = sv[slot]; t.i = si[slot]; }
+                a[v].merge(t);
+            }
+        }
+        const int64_t o = rest0 * Lc + c;
+#pragma unroll
+        for (int v = 0; v < V; ++v) emit<OP>(p, o + v, a[v]);
+    }
+}
+
+// ---- no contiguous direction to exploit: a thread per output
+template <int OP>
+__global__ __launch_bounds__(kThreads) void reduce_gather(ReduceParams p) {
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (o >= p.outputs) return;
+    const float* src = p.in + kept_offset(p, o);
+    Acc<OP> a;
+    for (int r = 0; r < p.R; ++r) a.take(src[(int64_t)r * p.sR], r);
+    emit<OP>(p, o, a);
+}
+
+struct ColsCfg { int v, tc_log2; };
+
+// Widest column strip that still gives the chip enough work-groups (4 per CU).
+ColsCfg cols_cfg(const ReduceParams& p, bool vec_ok) {
+    const int64_t Lc = p.shape[p.nk - 1];
+    const int64_t rest = p.outputs / Lc;
+    const ColsCfg tries[] = {{4, 6}, {4, 4}, {1, 6}, {4, 2}, {1, 4}, {1, 2}};
+    ColsCfg last{1, 2};
+    for (const ColsCfg& c : tries) {
+        if (c.v == 4 && !vec_ok) continue;
+        const int64_t strip = (int64_t)c.v << c.tc_log2;
+        last = c;
+        if (rest * ((Lc + strip - 1) / strip) >= 1024) return c;
+    }
+    return last;
+}
+
+bool aligned4(const ReduceParams& p) {
+    for (int d = 0; d < p.nk; ++d)
+        if (p.stride[d] % 4 && p.shape[d] > 1) return false;
+    return true;
+}
+
+template <int OP>
+hipError_t launch_op(const ReduceParams& p, hipStream_t stream) {
+    const bool base_ok = ((uintptr_t)p.in & 15) == 0;
+    if (p.kind == 0) {
+        const bool vec = base_ok && p.sR == 1 && p.R % 4 == 0 && aligned4(p);
+        const bool wide = reduce_rows_per_group(p);
+        const unsigned grid = wide ? (unsigned)p.outputs : (unsigned)((p.outputs + 3) / 4);
+        if (wide) {
+            if (vec) hipLaunchKernelGGL((reduce_rows<OP, true, 4>), dim3(grid), dim3(kThreads), 0, stream, p);
+            else hipLaunchKernelGGL((reduce_rows<OP, false, 4>), dim3(grid), dim3(kThreads), 0, stream, p);
+        } else {
+            if (vec) hipLaunchKernelGGL((reduce_rows<OP, true, 1>), dim3(grid), dim3(kThreads), 0, stream, p);
+            else hipLaunchKernelGGL((reduce_rows<OP, false, 1>), dim3(grid), dim3(kThreads), 0, stream, p);
+        }
+    } else if (p.kind == 1) {
+        const int64_t Lc = p.shape[p.nk - 1];
+        bool vec_ok = base_ok && Lc % 4 == 0 && p.sR % 4 == 0 && (((uintptr_t)p.out & 15) == 0);
+        for (int d = 0; d + 1 < p.nk; ++d)
+            if (p.stride[d] % 4 && p.shape[d] > 1) vec_ok = false;
+        const ColsCfg c = cols_cfg(p, vec_ok);
+        const int64_t strip = (int64_t)c.v << c.tc_log2;
+        const int strips = (int)((Lc + strip - 1) / strip);
+        dim3 grid((unsigned)(strips * (p.outputs / Lc)));
+        if (c.v == 4) hipLaunchKernelGGL((reduce_cols<OP, 4>), grid, dim3(kThreads), 0, stream, p, c.tc_log2, strips);
+        else hipLaunchKernelGGL((reduce_cols<OP, 1>), grid, dim3(kThreads), 0, stream, p, c.tc_log2, strips);
+    } else {
+        hipLaunchKernelGGL((reduce_gather<OP>), dim3((unsigned)((p.outputs + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, p);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// a work-group per output when there are too few outputs for a wave each to fill the chip
+bool reduce_rows_per_group(const ReduceParams& p) { return p.outputs < 2048 && p.R >= 2048; }
+
+LaunchShape reduce_shape(const ReduceParams& p) {
+    LaunchShape s{};
+    s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
+    s.grid[1] = s.grid[2] = 1;
+    if (p.kind == 0) {
+        const bool wide = reduce_rows_per_group(p);
+        s.grid[0] = wide ? (uint32_t)p.outputs : (uint32_t)((p.outputs + 3) / 4);
+        s.lds_bytes = 32;
+        s.kernel = wide ? "reduce_rows<group>" : "reduce_rows<wave>";
+    } else if (p.kind == 1) {
+        // the strip width depends on pointer alignment only through the vector variant; report the aligned choice
+        const int64_t Lc = p.shape[p.nk - 1];
+        bool vec_ok = Lc % 4 == 0 && p.sR % 4 == 0;
+        for (int d = 0; d + 1 < p.nk; ++d)
+            if (p.stride[d] % 4 && p.shape[d] > 1) vec_ok = false;
+        const ColsCfg c = cols_cfg(p, vec_ok);
+        const int64_t strip = (int64_t)c.v << c.tc_log2;
+        s.grid[0] = (uint32_t)(((Lc + strip - 1) / strip) * (p.outputs / Lc));
+        s.lds_bytes = (uint32_t)(kThreads * c.v * 4 * (p.op >= 2 ? 2 : 1));
+        s.kernel = c.v == 4 ? "reduce_cols<vec4>" : "reduce_cols<scalar>";
+    } else {
+        s.grid[0] = (uint32_t)((p.outputs + kThreads - 1) / kThreads);
+        s.lds_bytes = 0;
+        s.kernel = "reduce_gather";
+    }
+    return s;
+}
+
+hipError_t reduce_launch(const ReduceParams& p, hipStream_t stream) {
+    switch (p.op) {
+        case 0: return launch_op<0>(p, stream);
+        case 2: return launch_op<2>(p, stream);
+        default: return launch_op<3>(p, stream);
+    }
+}
+
+}  // namespace hpct

@@ -54,6 +54,23 @@ struct LayoutParams {
 LaunchShape layout_shape(const LayoutParams& p);
 hipError_t layout_launch(const LayoutParams& p, hipStream_t stream);
 
+// ---- sum / mean / argmax / argmin over one axis of a strided view (Table 1: Reduction)
+constexpr int kReduceDims = 5;
+struct ReduceParams {
+    const float* in; void* out;        // out: float (sum, mean) or int32 (argmax, argmin), contiguous
+    int32_t nk;                        // kept dimensions after collapsing, 0..kReduceDims
+    int64_t shape[kReduceDims];        // their extents
+    int64_t stride[kReduceDims];       // their input strides (elements)
+    int32_t R; int64_t sR;             // extent and input stride of the reduced axis
+    int64_t outputs;                   // product of the kept extents
+    int32_t op;                        // 0 sum, 2 argmax, 3 argmin
+    int32_t mean;                      // op 0: divide by R
+    int32_t kind;                      // 0 reduced axis contiguous, 1 innermost kept dim contiguous, 2 gather
+};
+bool reduce_rows_per_group(const ReduceParams& p);
+LaunchShape reduce_shape(const ReduceParams& p);
+hipError_t reduce_launch(const ReduceParams& p, hipStream_t stream);
+
 // ---- GEMM + bias + relu + hash dropout, then one of: store [M,N]; row softmax
 //      (when the tile spans the whole row); mean over the last dim (-> [M]),
 //      optionally followed by a softmax over those M means.  The mean variants

@@ -20,12 +20,12 @@ HPCT_OK, HPCT_ERR_NULL, HPCT_ERR_BAD_DESC, HPCT_ERR_SHAPE_MISMATCH, HPCT_ERR_ALI
     HPCT_ERR_UNSUPPORTED, HPCT_ERR_WORKSPACE, HPCT_ERR_HIP = range(8)
 STATUS_NAMES = ["HPCT_OK", "HPCT_ERR_NULL", "HPCT_ERR_BAD_DESC", "HPCT_ERR_SHAPE_MISMATCH", "HPCT_ERR_ALIGNMENT",
                 "HPCT_ERR_UNSUPPORTED", "HPCT_ERR_WORKSPACE", "HPCT_ERR_HIP"]
-HPCT_F32 = 0
+HPCT_F32, HPCT_I32 = 0, 1
 HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW = range(4)
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
     HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH = range(7)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
-    HPCT_RED_MAXPOOL2_HW = range(6)
+    HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS = range(10)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
 
 
@@ -39,7 +39,7 @@ class OpDesc(C.Structure):
                 ("reduce_before_epi", C.c_int32), ("n_in", C.c_int32), ("in_", TensorDesc * HPCT_MAX_IN),
                 ("n_out", C.c_int32), ("out", TensorDesc * HPCT_MAX_OUT), ("stride_hw", C.c_int32 * 2),
                 ("pad_hw", C.c_int32 * 2), ("eps", C.c_float), ("scale", C.c_float), ("dropout_p", C.c_float),
-                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64)]
+                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64), ("axis", C.c_int32)]
 
 
 class HpctError(RuntimeError):
@@ -112,7 +112,7 @@ def tensor_desc(shape: Sequence[int], stride: Optional[Sequence[int]] = None, dt
 
 def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before_epi=0, inputs=(), outputs=(),
             stride_hw=(1, 1), pad_hw=(0, 0), eps=0.0, scale=1.0, dropout_p=0.0, dropout_seed=0,
-            reduce2=HPCT_RED_NONE) -> OpDesc:
+            reduce2=HPCT_RED_NONE, axis=0) -> OpDesc:
     d = OpDesc()
     d.anchor = anchor
     d.n_epi = len(epi)
@@ -133,6 +133,7 @@ def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before
     d.dropout_p = dropout_p
     d.dropout_seed = int(dropout_seed) & 0xFFFFFFFFFFFFFFFF
     d.reduce2 = reduce2
+    d.axis = axis
     return d
 
 
@@ -182,8 +183,8 @@ class Plan:
         For launch loops where per-call Python overhead matters."""
         import torch
         for t in list(inputs) + list(outputs):
-            if not t.is_cuda or t.dtype != torch.float32:
-                raise HpctError(HPCT_ERR_BAD_DESC, "operands must be fp32 tensors in GPU memory")
+            if not t.is_cuda or (t.dtype != torch.float32 and not (t.dtype == torch.int32 and any(t is o for o in outputs))):
+                raise HpctError(HPCT_ERR_BAD_DESC, "operands must be fp32 tensors (int32 for index outputs) in GPU memory")
         lib = load()
         ins = (C.c_void_p * max(1, len(inputs)))(*[t.data_ptr() for t in inputs])
         outs = (C.c_void_p * max(1, len(outputs)))(*[t.data_ptr() for t in outputs])
@@ -205,8 +206,8 @@ class Plan:
         workspace: a contiguous GPU tensor of at least `workspace_bytes` bytes when the plan needs one."""
         import torch
         for t in list(inputs) + list(outputs):
-            if not t.is_cuda or t.dtype != torch.float32:
-                raise HpctError(HPCT_ERR_BAD_DESC, "operands must be fp32 tensors in GPU memory")
+            if not t.is_cuda or (t.dtype != torch.float32 and not (t.dtype == torch.int32 and any(t is o for o in outputs))):
+                raise HpctError(HPCT_ERR_BAD_DESC, "operands must be fp32 tensors (int32 for index outputs) in GPU memory")
         s = torch.cuda.current_stream().cuda_stream if stream is None else stream
         if workspace is not None and (not workspace.is_cuda or not workspace.is_contiguous()):
             raise HpctError(HPCT_ERR_BAD_DESC, "the workspace must be a contiguous tensor in GPU memory")
@@ -315,6 +316,27 @@ def layout_transform_plan(x_view, out):
 def layout_transform(x_view, out, stream=None) -> None:
     """out = contiguous copy of the strided view x_view (transpose, NCHW <-> NHWC, slices, broadcasts)."""
     plan, ins = layout_transform_plan(x_view, out)
+    plan.launch(ins, [out], stream)
+
+
+_REDUCE_OPS = {"sum": HPCT_RED_SUM_AXIS, "mean": HPCT_RED_MEAN_AXIS, "argmax": HPCT_RED_ARGMAX_AXIS,
+               "argmin": HPCT_RED_ARGMIN_AXIS}
+
+
+def reduce_axis_plan(x_view, out, axis, op):
+    """x_view: a (possibly non-contiguous) fp32 GPU tensor view; out: contiguous, x_view's shape without dim
+    `axis` (shape [1] for a 1-D input); fp32 for op "sum" / "mean", int32 for "argmax" / "argmin"."""
+    shape, stride = _sh(x_view), tuple(int(v) for v in x_view.stride())
+    arg = op in ("argmax", "argmin")
+    plan = _cached(("reduce", shape, stride, axis, op), lambda: op_desc(
+        HPCT_ANCHOR_NONE, [], _REDUCE_OPS[op], 0, [tensor_desc(shape, stride)],
+        [tensor_desc(_sh(out), None, HPCT_I32 if arg else HPCT_F32)], axis=axis))
+    return plan, [x_view]
+
+
+def reduce_axis(x_view, out, axis, op, stream=None) -> None:
+    """out = sum / mean / argmax / argmin of x_view over dim `axis` (ties of the arg ops go to the lowest index)."""
+    plan, ins = reduce_axis_plan(x_view, out, axis, op)
     plan.launch(ins, [out], stream)
 
 

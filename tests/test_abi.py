@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_the_c_layout():
     # int32 + pad + 6*int64 + 6*int64 + enum + pad
     assert C.sizeof(H.TensorDesc) == 112
-    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4 + 4 + 4 + 8
+    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4 + 4 + 4 + 8 + 4 + 4
     # and the library reports the same sizes for the structs it was compiled with
     lib = H.load()
     assert lib.hpct_sizeof_tensor_desc() == C.sizeof(H.TensorDesc)
@@ -323,7 +323,7 @@ def test_matmul_dropout_mean_softmax_errors():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = chain6_desc(stop="dropout"); d.reduce2 = H.HPCT_RED_SOFTMAX_LAST   # second reduction without the first
     expect(H.HPCT_ERR_UNSUPPORTED, d)
-    d = chain6_desc(); d.reduce2 = 9
+    d = chain6_desc(); d.reduce2 = 99
     expect(H.HPCT_ERR_BAD_DESC, d)
     d = chain6_desc(); d.epi[0], d.epi[1] = H.HPCT_EPI_DROPOUT_HASH, H.HPCT_EPI_BIAS_COL   # order matters
     expect(H.HPCT_ERR_UNSUPPORTED, d)
@@ -391,4 +391,53 @@ def test_conv_block_plans():
     d = conv_block_desc(); d.reduce = H.HPCT_RED_AVGPOOL_HW
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = cfg_desc(2); d.reduce = H.HPCT_RED_MAXPOOL2_HW                        # pooling without a conv anchor
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+
+
+def reduce_desc(shape, stride, axis, red, out_shape=None, out_dtype=None):
+    if out_shape is None:
+        out_shape = tuple(n for k, n in enumerate(shape) if k != axis) or (1,)
+    arg = red in (H.HPCT_RED_ARGMAX_AXIS, H.HPCT_RED_ARGMIN_AXIS)
+    if out_dtype is None:
+        out_dtype = H.HPCT_I32 if arg else H.HPCT_F32
+    return H.op_desc(H.HPCT_ANCHOR_NONE, [], red, 0, [H.tensor_desc(shape, stride)],
+                     [H.tensor_desc(out_shape, None, out_dtype)], axis=axis)
+
+
+def test_axis_reduction_plans():
+    # rows of a matrix: the reduced axis is contiguous, a wave per output
+    p = H.Plan(reduce_desc((8192, 4096), (4096, 1), 1, H.HPCT_RED_SUM_AXIS))
+    assert p.kernel_name == "reduce_rows<wave>" and p.launch_shape()[0] == (2048, 1, 1)
+    # few long rows: a work-group per output
+    p = H.Plan(reduce_desc((16, 1 << 20), (1 << 20, 1), 1, H.HPCT_RED_MEAN_AXIS))
+    assert p.kernel_name == "reduce_rows<group>" and p.launch_shape()[0] == (16, 1, 1)
+    # columns of a matrix, channels of NCHW: threads along the contiguous kept dimension
+    p = H.Plan(reduce_desc((8192, 4096), (4096, 1), 0, H.HPCT_RED_SUM_AXIS))
+    assert p.kernel_name.startswith("reduce_cols")
+    p = H.Plan(reduce_desc((32, 64, 56, 56), (200704, 3136, 56, 1), 1, H.HPCT_RED_ARGMAX_AXIS))
+    assert p.kernel_name == "reduce_cols<vec4>"      # H and W collapse into one contiguous dimension of 3136
+    assert p.launch_shape()[0] == (49 * 32, 1, 1)
+    # nothing contiguous: gather
+    p = H.Plan(reduce_desc((10, 20, 30), (1200, 60, 2), 1, H.HPCT_RED_ARGMIN_AXIS))
+    assert p.kernel_name == "reduce_gather"
+    # a vector reduces to shape [1]
+    assert H.Plan(reduce_desc((1000,), (1,), 0, H.HPCT_RED_SUM_AXIS)).kernel_name.startswith("reduce_rows")
+    assert p.workspace_bytes == 0
+
+
+def test_axis_reduction_errors():
+    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 2, H.HPCT_RED_SUM_AXIS, out_shape=(4,)))
+    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), -1, H.HPCT_RED_SUM_AXIS, out_shape=(4,)))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS, out_shape=(5,)))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS, out_shape=(4, 1)))
+    # dtypes: indices are int32, sums fp32
+    expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_ARGMAX_AXIS, out_dtype=H.HPCT_F32))
+    expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS, out_dtype=H.HPCT_I32))
+    d = cfg_desc(3); d.out[0].dtype = H.HPCT_I32          # int32 anywhere else
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.n_epi = 1; d.epi[0] = H.HPCT_EPI_RELU
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.anchor = H.HPCT_ANCHOR_GEMM
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.out[0] = H.tensor_desc((4,), (2,))   # strided output
     expect(H.HPCT_ERR_UNSUPPORTED, d)

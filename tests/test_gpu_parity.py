@@ -444,3 +444,72 @@ def test_layout_slices_and_broadcasts():
     _layout_case((1, 64), lambda t: t.expand(33, 64))                 # broadcast rows (stride 0)
     _layout_case((64, 1), lambda t: t.expand(64, 20))                 # broadcast inner (stride 0)
     _layout_case((5, 7, 9), lambda t: t)                              # contiguous, odd size
+
+
+# --------------------------------------------------- reductions over one axis
+def check_reduce(view, axis, tag=""):
+    """view: a torch view on the GPU; compares all four reductions over `axis` with the checker."""
+    base = view._base if view._base is not None else view
+    hb = host(base).reshape(-1)
+    off = view.storage_offset() - base.storage_offset()
+    shape, stride = tuple(view.shape), tuple(view.stride())
+    oshape = tuple(n for k, n in enumerate(shape) if k != axis) or (1,)
+    names = set()
+    for op in ("sum", "mean"):
+        out = torch.full(oshape, float("nan"), device="cuda")
+        plan, ins = hpct.reduce_axis_plan(view, out, axis, op)
+        plan.launch(ins, [out])
+        names.add(plan.kernel_name)
+        want, mag = ref.reduce_axis(hb[off:], shape, stride, axis, op, want_abs=True)
+        got = host(out).reshape(want.shape)
+        # a sum of R fp32 terms: error far inside the contraction bound relative to the sum of magnitudes
+        assert show("%s %s axis %d" % (tag, op, axis), compare.contraction(got, want, mag + 1e-300))
+        assert np.all(np.abs(got - want) <= 1e-5 * mag + 1e-30)
+    for op in ("argmax", "argmin"):
+        out = torch.full(oshape, -7, device="cuda", dtype=torch.int32)
+        hpct.reduce_axis(view, out, axis, op)
+        want = ref.reduce_axis(hb[off:], shape, stride, axis, op)
+        assert np.array_equal(host(out).reshape(want.shape).astype(np.int64), want), (tag, op, axis)
+    return names
+
+
+def test_reduce_full_size_rows_cols_channels():
+    X = dev(datagen.make(3)["X"])                       # [8192, 4096]
+    assert check_reduce(X, 1, "8192x4096") == {"reduce_rows<wave>"}
+    assert all(n.startswith("reduce_cols") for n in check_reduce(X, 0, "8192x4096"))
+    T = dev(datagen.make(2)["X"])                       # [32, 64, 56, 56]
+    assert check_reduce(T, 1, "nchw channels") == {"reduce_cols<vec4>"}
+    check_reduce(T, 0, "nchw batch")
+    check_reduce(T, 3, "nchw w")
+    check_reduce(T, 2, "nchw h")
+    # determinism
+    a = torch.empty(4096, device="cuda"); b = torch.empty(4096, device="cuda")
+    hpct.reduce_axis(X, a, 0, "sum"); hpct.reduce_axis(X, b, 0, "sum")
+    assert np.array_equal(host(a).view(np.uint32), host(b).view(np.uint32))
+
+
+@pytest.mark.parametrize("shape", [(1,), (7,), (1000,), (70001,), (3, 5), (33, 65), (257, 130), (5, 1, 9),
+                                   (4, 6, 10, 3), (2, 3, 4, 5, 6), (2, 2, 3, 2, 3, 4), (64, 2048), (3, 40000)])
+def test_reduce_ragged_contiguous(shape):
+    print("reduce", shape, flush=True)
+    n = int(np.prod(shape))
+    x = dev(datagen.gen_normal(77, (n,), 0.0, 1.0)).view(*shape)
+    for axis in range(len(shape)):
+        check_reduce(x, axis, str(shape))
+
+
+def test_reduce_strided_views_ties_and_offsets():
+    base = dev(datagen.gen_normal(78, (6, 40, 50), 0.0, 1.0))
+    check_reduce(base.permute(2, 0, 1), 0, "permuted")
+    check_reduce(base.permute(2, 0, 1), 1, "permuted")
+    check_reduce(base.permute(2, 0, 1), 2, "permuted")
+    check_reduce(base[:, 3:33, 1:50:2], 1, "sliced")
+    check_reduce(base[:, 3:33, 1:50:2], 2, "sliced")          # strided inner dimension: gather / rows scalar
+    check_reduce(base[1:, :, 3:], 0, "offset view")
+    check_reduce(base[0, 0].expand(9, 50), 0, "broadcast")     # stride 0 along the reduced axis: all ties -> index 0
+    check_reduce(base[0, 0].expand(9, 50), 1, "broadcast")
+    # many exact ties: small integers
+    q = dev((datagen.gen_uniform(79, (300, 257), 0.0, 4.0)).astype(np.int32).astype(np.float32))
+    check_reduce(q, 0, "ties")
+    check_reduce(q, 1, "ties")
+    check_reduce(q.t(), 0, "ties transposed")
