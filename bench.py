@@ -180,6 +180,36 @@ def main() -> int:
         outs = [s["out"].view(4096, 8192) for s in sets[3]]    # reuse the layernorm outputs as destinations
         time_layout("transpose_8192x4096", [m.t() for m in ms], outs, 2 * ms[0].numel() * 4)
 
+    # ---- reductions over one axis (Table 1 Reduction class; outside the step and the headline value)
+    reduce_ops = []
+    if not args.only:
+        def time_reduce(name, views, axis, op, out_shape, nbytes):
+            calls_r = []
+            for v in views:
+                o = torch.empty(out_shape, device="cuda", dtype=torch.int32 if op.startswith("arg") else torch.float32)
+                plan, ins = hpct.reduce_axis_plan(v, o, axis, op)
+                ws = torch.empty(plan.workspace_bytes // 4, device="cuda") if plan.workspace_bytes else None
+                calls_r.append(plan.bind(ins, [o], workspace=ws))
+            for k in range(min(args.warmup, 10)):
+                calls_r[k % len(calls_r)]()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for k in range(args.steps):
+                calls_r[k % len(calls_r)]()
+            e1.record()
+            torch.cuda.synchronize()
+            us = 1e3 * e0.elapsed_time(e1) / args.steps
+            reduce_ops.append(dict(op=name, kernel=plan.kernel_name, avg_us=round(us, 3), achieved=round(nbytes / us / 1e3, 1),
+                                   unit="GB/s", peak=HBM_PEAK_GBS, frac=round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                                   buffer_sets=len(calls_r)))
+        ms = [s_["ins"][0] for s_ in sets[3]]                  # 3 matrices [8192,4096]
+        time_reduce("sum_axis1_8192x4096", ms, 1, "sum", (8192,), ms[0].numel() * 4 + 8192 * 4)
+        time_reduce("sum_axis0_8192x4096", ms, 0, "sum", (4096,), ms[0].numel() * 4 + 4096 * 4)
+        time_reduce("argmax_axis1_8192x4096", ms, 1, "argmax", (8192,), ms[0].numel() * 4 + 8192 * 4)
+        xs = [s_["ins"][0] for s_ in sets[2]]                  # 11 NCHW tensors [32,64,56,56]
+        time_reduce("argmax_channels_32x64x56x56", xs, 1, "argmax", (32, 56, 56), xs[0].numel() * 4 + 32 * 3136 * 4)
+        time_reduce("mean_channels_32x64x56x56", xs, 1, "mean", (32, 56, 56), xs[0].numel() * 4 + 32 * 3136 * 4)
+
     # ---- [Matmul, Dropout, Mean, Softmax] (Section 5.3 case study; outside the step and the headline value)
     next_ops = []
     if not args.only:
@@ -260,7 +290,7 @@ def main() -> int:
                                     "layernorm+gelu 8192x4096, conv3x3 32x64x56x56->128, attention 16x2048x64"
                            if not args.only else "chain %d only" % args.only,
                            ops=len(which), hbm_cold_sets={str(i): len(sets[i]) for i in which}),
-               per_op=per_op, roofline=roofline, layout_ops=layout_ops, next_ops=next_ops)
+               per_op=per_op, roofline=roofline, layout_ops=layout_ops, reduce_ops=reduce_ops, next_ops=next_ops)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host, which)

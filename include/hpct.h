@@ -8,8 +8,8 @@
  * "reshape, transpose"; fused examples
  * of its Section 5.3) with an op descriptor; the library validates it, picks a
  * hand-written HIP kernel and enqueues it on the caller's stream: one kernel per
- * launch, two for a GEMM chain that ends in MEAN_LAST (the second finishes the
- * reduction from the workspace).
+ * launch, two for the plans that report a workspace (the second finishes a
+ * reduction from the partial results the first left there).
  *
  * Conventions
  *  - All tensors are fp32 (the index output of an arg-reduction is int32), described by
@@ -158,7 +158,8 @@ typedef struct hpct_plan hpct_plan;   /* opaque; host memory */
 hpct_status hpct_plan_create(const hpct_op_desc *desc, hpct_plan **out);
 
 /* Device workspace the plan needs at launch, in bytes: 0 except for GEMM chains
- * with MEAN_LAST (one float per row and column tile).  The launch overwrites it;
+ * with MEAN_LAST (one float per row and column tile) and for axis reductions with
+ * few outputs and a long strided axis (partial results of the pieces it is cut into).  The launch overwrites it;
  * it needs no initialisation and carries nothing between launches.  0 for a NULL plan. */
 size_t hpct_plan_workspace_bytes(const hpct_plan *plan);
 

@@ -335,6 +335,9 @@ hpct_status plan_reduce(const hpct_op_desc& d, hpct_plan& p) {
     else q.kind = 2;
     // 32-bit grids
     if (q.outputs > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "axis reduction: more than 2^31-1 outputs");
+    q.split = 1;
+    if (q.kind == 1) reduce_plan_cols(q);
+    p.ws_bytes = reduce_workspace_bytes(q);
     p.kind = Kind::Reduce;
     p.u.red = q;
     p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
@@ -565,7 +568,7 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
         }
         case Kind::Reduce: {
             ReduceParams q = plan->u.red;
-            q.in = in(0); q.out = out_ptrs[0];
+            q.in = in(0); q.out = out_ptrs[0]; q.ws = (float*)workspace;
             e = reduce_launch(q, stream);
             break;
         }

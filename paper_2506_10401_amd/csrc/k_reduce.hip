@@ -155,8 +155,11 @@ __global__ __launch_bounds__(kThreads) void reduce_rows(ReduceParams p) {
 }
 
 // ---- innermost kept dimension contiguous (extent Lc): TC column threads x TR row
-// groups, V columns per thread.  blockIdx.x = strip of TC*V columns, blockIdx.y =
-// index over the other kept dimensions.
+// groups, V columns per thread.  blockIdx.x = (strip of TC*V columns, index over the
+// other kept dimensions, chunk of the reduced axis).  With p.split > 1 the reduced
+// axis is cut into p.split chunks handled by different work-groups (few outputs
+// cannot fill the chip otherwise); each writes its partial result to the workspace
+// and reduce_finish merges the chunks in order.
 constexpr int kColsUnroll = 8;  // elements of the reduced axis in flight per thread
 
 template <int OP, int V>
@@ -166,7 +169,10 @@ __global__ __launch_bounds__(kThreads) void reduce_cols(ReduceParams p, int tc_l
     const int TC = 1 << tc_log2, TR = kThreads >> tc_log2;
     const int ct = threadIdx.x & (TC - 1), rg = threadIdx.x >> tc_log2;
     const int64_t Lc = p.shape[p.nk - 1];
-    const int64_t strip = blockIdx.x % strips, rest0 = blockIdx.x / strips;
+    int64_t b = blockIdx.x;
+    const int64_t strip = b % strips; b /= strips;
+    const int chunk_id = (int)(b % p.split);
+    const int64_t rest0 = b / p.split;
     const int64_t c = (strip * TC + ct) * V;
     // offset of the other kept dimensions
     int64_t rest = rest0, off = 0;
@@ -178,22 +184,26 @@ __global__ __launch_bounds__(kThreads) void reduce_cols(ReduceParams p, int tc_l
             rest = q;
         }
     }
+    // this work-group's piece of the reduced axis
+    const int chunk = (p.R + p.split - 1) / p.split;
+    const int r_lo = chunk_id * chunk;
+    const int r_hi = r_lo + chunk < p.R ? r_lo + chunk : p.R;
     Acc<OP> a[V];
     if (c < Lc) {
         const float* src = p.in + off + c;
-        const int R = p.R;
         const int64_t sR = p.sR;
-        int r = rg;
         constexpr int U = kColsUnroll;
-        for (; r + (U - 1) * TR < R; r += U * TR) {
+        int r = r_lo + rg;
+        for (; r + (U - 1) * TR < r_hi; r += U * TR) {   // U loads in flight
             float x[U][V];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                const float* q = src + (int64_t)(r + u * TR) * sR;
                 if constexpr (V == 4) {
-                    const float4v t = load4_nt(src + (int64_t)(r + u * TR) * sR);
+                    const float4v t = load4_nt(q);
                     x[u][0] = t.x; x[u][1] = t.y; x[u][2] = t.z; x[u][3] = t.w;
                 } else {
-                    x[u][0] = __builtin_nontemporal_load(src + (int64_t)(r + u * TR) * sR);
+                    x[u][0] = __builtin_nontemporal_load(q);
                 }
             }
 #pragma unroll
@@ -201,9 +211,27 @@ __global__ __launch_bounds__(kThreads) void reduce_cols(ReduceParams p, int tc_l
 #pragma unroll
                 for (int v = 0; v < V; ++v) a[v].take(x[u][v], r + u * TR);
         }
-        for (; r < R; r += TR) {
+        if (r < r_hi) {   // last, partial pass: rows past the end re-read the first row of the piece and are not taken
+            float x[U][V];
 #pragma unroll
-            for (int v = 0; v < V; ++v) a[v].take(src[(int64_t)r * sR + v], r);
+            for (int u = 0; u < U; ++u) {
+                const int rr = r + u * TR;
+                const float* q = src + (int64_t)(rr < r_hi ? rr : r_lo) * sR;
+                if constexpr (V == 4) {
+                    const float4v t = load4_nt(q);
+                    x[u][0] = t.x; x[u][1] = t.y; x[u][2] = t.z; x[u][3] = t.w;
+                } else {
+                    x[u][0] = __builtin_nontemporal_load(q);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int rr = r + u * TR;
+                if (rr < r_hi) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) a[v].take(x[u][v], rr);
+                }
+            }
         }
     }
     // row groups 1.. publish, group 0 merges them in order
@@ -226,9 +254,34 @@ __global__ __launch_bounds__(kThreads) void reduce_cols(ReduceParams p, int tc_l
             }
         }
         const int64_t o = rest0 * Lc + c;
+        if (p.split == 1) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) emit<OP>(p, o + v, a[v]);
+            for (int v = 0; v < V; ++v) emit<OP>(p, o + v, a[v]);
+        } else {
+            float* wv = p.ws + (int64_t)chunk_id * p.outputs + o;
+            int* wi = reinterpret_cast<int*>(p.ws + (int64_t)p.split * p.outputs) + (int64_t)chunk_id * p.outputs + o;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                if constexpr (OP == 0) wv[v] = a[v].s; else { wv[v] = a[v].v; wi[v] = a[v].i; }
+            }
+        }
     }
+}
+
+// merges the p.split partial results of every output in chunk order
+template <int OP>
+__global__ __launch_bounds__(kThreads) void reduce_finish(ReduceParams p) {
+    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (o >= p.outputs) return;
+    const float* wv = p.ws + o;
+    const int* wi = reinterpret_cast<const int*>(p.ws + (int64_t)p.split * p.outputs) + o;
+    Acc<OP> a;
+    for (int s = 0; s < p.split; ++s) {
+        Acc<OP> t;
+        if constexpr (OP == 0) t.s = wv[(int64_t)s * p.outputs]; else { t.v = wv[(int64_t)s * p.outputs]; t.i = wi[(int64_t)s * p.outputs]; }
+        if (s == 0) a = t; else a.merge(t);
+    }
+    emit<OP>(p, o, a);
 }
 
 // ---- no contiguous direction to exploit: a thread per output
@@ -242,21 +295,12 @@ __global__ __launch_bounds__(kThreads) void reduce_gather(ReduceParams p) {
     emit<OP>(p, o, a);
 }
 
-struct ColsCfg { int v, tc_log2; };
-
-// Widest column strip that still gives the chip enough work-groups (4 per CU).
-ColsCfg cols_cfg(const ReduceParams& p, bool vec_ok) {
-    const int64_t Lc = p.shape[p.nk - 1];
-    const int64_t rest = p.outputs / Lc;
-    const ColsCfg tries[] = {{4, 6}, {4, 4}, {1, 6}, {4, 2}, {1, 4}, {1, 2}};
-    ColsCfg last{1, 2};
-    for (const ColsCfg& c : tries) {
-        if (c.v == 4 && !vec_ok) continue;
-        const int64_t strip = (int64_t)c.v << c.tc_log2;
-        last = c;
-        if (rest * ((Lc + strip - 1) / strip) >= 1024) return c;
-    }
-    return last;
+// strides that allow 128-bit access along the contiguous kept dimension (pointers are checked at launch)
+bool cols_vec_ok(const ReduceParams& p) {
+    if (p.shape[p.nk - 1] % 4 || p.sR % 4) return false;
+    for (int d = 0; d + 1 < p.nk; ++d)
+        if (p.stride[d] % 4 && p.shape[d] > 1) return false;
+    return true;
 }
 
 bool aligned4(const ReduceParams& p) {
@@ -281,15 +325,19 @@ hipError_t launch_op(const ReduceParams& p, hipStream_t stream) {
         }
     } else if (p.kind == 1) {
         const int64_t Lc = p.shape[p.nk - 1];
-        bool vec_ok = base_ok && Lc % 4 == 0 && p.sR % 4 == 0 && (((uintptr_t)p.out & 15) == 0);
-        for (int d = 0; d + 1 < p.nk; ++d)
-            if (p.stride[d] % 4 && p.shape[d] > 1) vec_ok = false;
-        const ColsCfg c = cols_cfg(p, vec_ok);
-        const int64_t strip = (int64_t)c.v << c.tc_log2;
+        // the plan chose the strip for 128-bit access; misaligned pointers keep the strip with scalar access
+        int v = p.cols_v, tc_log2 = p.cols_tc_log2;
+        if (v == 4 && !(base_ok && (((uintptr_t)p.out | (uintptr_t)p.ws) & 15) == 0)) { v = 1; tc_log2 += 2; }
+        const int64_t strip = (int64_t)v << tc_log2;
         const int strips = (int)((Lc + strip - 1) / strip);
-        dim3 grid((unsigned)(strips * (p.outputs / Lc)));
-        if (c.v == 4) hipLaunchKernelGGL((reduce_cols<OP, 4>), grid, dim3(kThreads), 0, stream, p, c.tc_log2, strips);
-        else hipLaunchKernelGGL((reduce_cols<OP, 1>), grid, dim3(kThreads), 0, stream, p, c.tc_log2, strips);
+        dim3 grid((unsigned)(strips * (p.outputs / Lc) * p.split));
+        if (v == 4) hipLaunchKernelGGL((reduce_cols<OP, 4>), grid, dim3(kThreads), 0, stream, p, tc_log2, strips);
+        else hipLaunchKernelGGL((reduce_cols<OP, 1>), grid, dim3(kThreads), 0, stream, p, tc_log2, strips);
+        if (p.split > 1) {
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((reduce_finish<OP>), dim3((unsigned)((p.outputs + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, p);
+        }
     } else {
         hipLaunchKernelGGL((reduce_gather<OP>), dim3((unsigned)((p.outputs + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, p);
     }
@@ -297,6 +345,40 @@ hipError_t launch_op(const ReduceParams& p, hipStream_t stream) {
 }
 
 }  // namespace
+
+// Column kernel configuration.  Candidates in order of preference: wide strips first (a wave load
+// is one contiguous run, few row groups to merge), 128-bit access before 32-bit at equal width; the
+// first that gives about four work-groups per CU wins.  When none does (few outputs) the reduced
+// axis is split over work-groups instead, on 64-column strips, to about one work-group per CU:
+// measured on 8192 x 4096 over axis 0, 256 groups of 2048 rows beat 512 and 1024 smaller ones.
+void reduce_plan_cols(ReduceParams& p) {
+    const int64_t Lc = p.shape[p.nk - 1];
+    const int64_t rest = p.outputs / Lc;
+    const bool vec = cols_vec_ok(p);
+    p.split = 1;
+    struct Cand { int v, tc; };
+    const Cand cands[] = {{4, 6}, {4, 5}, {1, 6}, {4, 4}};
+    for (const Cand& c : cands) {
+        if (c.v == 4 && !vec) continue;
+        const int64_t strip = (int64_t)c.v << c.tc;
+        p.cols_v = c.v; p.cols_tc_log2 = c.tc;
+        if (rest * ((Lc + strip - 1) / strip) >= 1024) return;
+    }
+    // few outputs: 64-column strips, pieces of the reduced axis
+    p.cols_v = vec ? 4 : 1;
+    p.cols_tc_log2 = vec ? 4 : 6;
+    const int64_t groups = rest * ((Lc + 63) / 64);
+    const int tr = kThreads >> p.cols_tc_log2;
+    int64_t split = (256 + groups - 1) / groups;
+    const int64_t most = p.R / (2 * tr * kColsUnroll);   // at least two full unrolled passes per thread
+    if (split > most) split = most;
+    if (split > 64) split = 64;
+    p.split = split < 1 ? 1 : (int32_t)split;
+}
+
+size_t reduce_workspace_bytes(const ReduceParams& p) {
+    return p.split > 1 ? (size_t)p.split * (size_t)p.outputs * 4 * (p.op >= 2 ? 2 : 1) : 0;
+}
 
 // a work-group per output when there are too few outputs for a wave each to fill the chip
 bool reduce_rows_per_group(const ReduceParams& p) { return p.outputs < 2048 && p.R >= 2048; }
@@ -311,16 +393,12 @@ LaunchShape reduce_shape(const ReduceParams& p) {
         s.lds_bytes = 32;
         s.kernel = wide ? "reduce_rows<group>" : "reduce_rows<wave>";
     } else if (p.kind == 1) {
-        // the strip width depends on pointer alignment only through the vector variant; report the aligned choice
         const int64_t Lc = p.shape[p.nk - 1];
-        bool vec_ok = Lc % 4 == 0 && p.sR % 4 == 0;
-        for (int d = 0; d + 1 < p.nk; ++d)
-            if (p.stride[d] % 4 && p.shape[d] > 1) vec_ok = false;
-        const ColsCfg c = cols_cfg(p, vec_ok);
-        const int64_t strip = (int64_t)c.v << c.tc_log2;
-        s.grid[0] = (uint32_t)(((Lc + strip - 1) / strip) * (p.outputs / Lc));
-        s.lds_bytes = (uint32_t)(kThreads * c.v * 4 * (p.op >= 2 ? 2 : 1));
-        s.kernel = c.v == 4 ? "reduce_cols<vec4>" : "reduce_cols<scalar>";
+        const int64_t strip = (int64_t)p.cols_v << p.cols_tc_log2;
+        s.grid[0] = (uint32_t)(((Lc + strip - 1) / strip) * (p.outputs / Lc) * p.split);
+        s.lds_bytes = (uint32_t)(kThreads * p.cols_v * 4 * (p.op >= 2 ? 2 : 1));
+        s.kernel = p.split > 1 ? (p.cols_v == 4 ? "reduce_cols<vec4,split>" : "reduce_cols<scalar,split>")
+                               : (p.cols_v == 4 ? "reduce_cols<vec4>" : "reduce_cols<scalar>");
     } else {
         s.grid[0] = (uint32_t)((p.outputs + kThreads - 1) / kThreads);
         s.lds_bytes = 0;

@@ -66,8 +66,14 @@ struct ReduceParams {
     int32_t op;                        // 0 sum, 2 argmax, 3 argmin
     int32_t mean;                      // op 0: divide by R
     int32_t kind;                      // 0 reduced axis contiguous, 1 innermost kept dim contiguous, 2 gather
+    // kind 1 (set by reduce_plan_cols): columns per thread, log2 of the column threads per group,
+    // pieces the reduced axis is split into (> 1: partial results go through `ws`)
+    int32_t cols_v, cols_tc_log2, split;
+    float* ws;                         // split > 1: split * outputs floats (+ as many ints for the arg ops)
 };
 bool reduce_rows_per_group(const ReduceParams& p);
+void reduce_plan_cols(ReduceParams& p);
+size_t reduce_workspace_bytes(const ReduceParams& p);
 LaunchShape reduce_shape(const ReduceParams& p);
 hipError_t reduce_launch(const ReduceParams& p, hipStream_t stream);
 

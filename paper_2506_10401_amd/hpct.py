@@ -334,10 +334,11 @@ def reduce_axis_plan(x_view, out, axis, op):
     return plan, [x_view]
 
 
-def reduce_axis(x_view, out, axis, op, stream=None) -> None:
-    """out = sum / mean / argmax / argmin of x_view over dim `axis` (ties of the arg ops go to the lowest index)."""
+def reduce_axis(x_view, out, axis, op, workspace=None, stream=None) -> None:
+    """out = sum / mean / argmax / argmin of x_view over dim `axis` (ties of the arg ops go to the lowest index).
+    `workspace`: GPU tensor of at least plan.workspace_bytes bytes when that is not 0."""
     plan, ins = reduce_axis_plan(x_view, out, axis, op)
-    plan.launch(ins, [out], stream)
+    plan.launch(ins, [out], stream, workspace)
 
 
 def conv2d_bias_relu_plan(inp, wt, bias, out, stride=1, pad=1, relu=True):

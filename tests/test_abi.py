@@ -413,10 +413,16 @@ def test_axis_reduction_plans():
     assert p.kernel_name == "reduce_rows<group>" and p.launch_shape()[0] == (16, 1, 1)
     # columns of a matrix, channels of NCHW: threads along the contiguous kept dimension
     p = H.Plan(reduce_desc((8192, 4096), (4096, 1), 0, H.HPCT_RED_SUM_AXIS))
-    assert p.kernel_name.startswith("reduce_cols")
+    assert p.kernel_name == "reduce_cols<vec4,split>"      # 4096 outputs cannot fill the chip: the axis is split
+    split = p.workspace_bytes // (4096 * 4)
+    assert 2 <= split <= 64 and p.workspace_bytes == split * 4096 * 4
+    g = p.launch_shape()[0][0]
+    assert g >= 256 and g % split == 0 and 4096 % (g // split) == 0   # column strips x pieces
+    pa = H.Plan(reduce_desc((8192, 4096), (4096, 1), 0, H.HPCT_RED_ARGMIN_AXIS))
+    assert pa.workspace_bytes == 2 * p.workspace_bytes      # value and index per piece
     p = H.Plan(reduce_desc((32, 64, 56, 56), (200704, 3136, 56, 1), 1, H.HPCT_RED_ARGMAX_AXIS))
-    assert p.kernel_name == "reduce_cols<vec4>"      # H and W collapse into one contiguous dimension of 3136
-    assert p.launch_shape()[0] == (49 * 32, 1, 1)
+    assert p.kernel_name == "reduce_cols<scalar>"    # H and W collapse into one contiguous dimension of 3136
+    assert p.launch_shape()[0] == (49 * 32, 1, 1) and p.workspace_bytes == 0
     # nothing contiguous: gather
     p = H.Plan(reduce_desc((10, 20, 30), (1200, 60, 2), 1, H.HPCT_RED_ARGMIN_AXIS))
     assert p.kernel_name == "reduce_gather"

@@ -458,7 +458,8 @@ def check_reduce(view, axis, tag=""):
     for op in ("sum", "mean"):
         out = torch.full(oshape, float("nan"), device="cuda")
         plan, ins = hpct.reduce_axis_plan(view, out, axis, op)
-        plan.launch(ins, [out])
+        ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda") if plan.workspace_bytes else None
+        plan.launch(ins, [out], workspace=ws)
         names.add(plan.kernel_name)
         want, mag = ref.reduce_axis(hb[off:], shape, stride, axis, op, want_abs=True)
         got = host(out).reshape(want.shape)
@@ -467,7 +468,10 @@ def check_reduce(view, axis, tag=""):
         assert np.all(np.abs(got - want) <= 1e-5 * mag + 1e-30)
     for op in ("argmax", "argmin"):
         out = torch.full(oshape, -7, device="cuda", dtype=torch.int32)
-        hpct.reduce_axis(view, out, axis, op)
+        plan, ins = hpct.reduce_axis_plan(view, out, axis, op)
+        ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda") if plan.workspace_bytes else None
+        plan.launch(ins, [out], workspace=ws)
+        names.add(plan.kernel_name)
         want = ref.reduce_axis(hb[off:], shape, stride, axis, op)
         assert np.array_equal(host(out).reshape(want.shape).astype(np.int64), want), (tag, op, axis)
     return names
@@ -478,18 +482,22 @@ def test_reduce_full_size_rows_cols_channels():
     assert check_reduce(X, 1, "8192x4096") == {"reduce_rows<wave>"}
     assert all(n.startswith("reduce_cols") for n in check_reduce(X, 0, "8192x4096"))
     T = dev(datagen.make(2)["X"])                       # [32, 64, 56, 56]
-    assert check_reduce(T, 1, "nchw channels") == {"reduce_cols<vec4>"}
+    assert check_reduce(T, 1, "nchw channels") == {"reduce_cols<scalar>"}
     check_reduce(T, 0, "nchw batch")
     check_reduce(T, 3, "nchw w")
     check_reduce(T, 2, "nchw h")
     # determinism
     a = torch.empty(4096, device="cuda"); b = torch.empty(4096, device="cuda")
-    hpct.reduce_axis(X, a, 0, "sum"); hpct.reduce_axis(X, b, 0, "sum")
+    plan, _ = hpct.reduce_axis_plan(X, a, 0, "sum")
+    assert plan.kernel_name == "reduce_cols<vec4,split>" and plan.workspace_bytes > 0
+    ws = torch.empty(plan.workspace_bytes // 4, device="cuda")
+    hpct.reduce_axis(X, a, 0, "sum", ws); hpct.reduce_axis(X, b, 0, "sum", ws)
     assert np.array_equal(host(a).view(np.uint32), host(b).view(np.uint32))
 
 
 @pytest.mark.parametrize("shape", [(1,), (7,), (1000,), (70001,), (3, 5), (33, 65), (257, 130), (5, 1, 9),
-                                   (4, 6, 10, 3), (2, 3, 4, 5, 6), (2, 2, 3, 2, 3, 4), (64, 2048), (3, 40000)])
+                                   (4, 6, 10, 3), (2, 3, 4, 5, 6), (2, 2, 3, 2, 3, 4), (64, 2048), (3, 40000),
+                                   (5000, 260), (3000, 7), (2, 1500, 33)])
 def test_reduce_ragged_contiguous(shape):
     print("reduce", shape, flush=True)
     n = int(np.prod(shape))
