@@ -372,3 +372,44 @@ void ref_reduce_axis(const float *in, int32_t nd, const int64_t *shape, const in
         }
     }
 }
+
+/* ---- Batched matmul - softmax - matmul with a causal mask: query i attends
+ * keys j <= i only (scores of later keys are minus infinity, i.e. those keys
+ * are left out of the softmax):
+ *   s_j = scale * sum_d Q[b][i][d] K[b][j][d],  j = 0 .. min(i, Lk-1)
+ *   p = softmax over those j;  O[b][i][d] = sum_j p_j V[b][j][d].
+ * Same layout and Dn as ref_attention. */
+void ref_attention_causal(const float *Q, const float *K, const float *V,
+                          int64_t B, int64_t Lq, int64_t Lk, int64_t D, double scale,
+                          double *O, double *Dn)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t bi = 0; bi < B * Lq; ++bi) {
+        int64_t b = bi / Lq, i = bi % Lq;
+        int64_t n = i + 1 < Lk ? i + 1 : Lk;   /* keys 0 .. n-1 */
+        const float *q = Q + bi * D;
+        const float *Kb = K + b * Lk * D, *Vb = V + b * Lk * D;
+        double *s = (double *)malloc((size_t)n * sizeof(double));
+        double mx = -INFINITY;
+        for (int64_t j = 0; j < n; ++j) {
+            double acc = 0.0;
+            for (int64_t d = 0; d < D; ++d) acc += (double)q[d] * (double)Kb[j * D + d];
+            s[j] = acc * scale;
+            if (s[j] > mx) mx = s[j];
+        }
+        double sum = 0.0;
+        for (int64_t j = 0; j < n; ++j) { s[j] = exp(s[j] - mx); sum += s[j]; }
+        for (int64_t j = 0; j < n; ++j) s[j] /= sum;
+        for (int64_t d = 0; d < D; ++d) {
+            double acc = 0.0, mag = 0.0;
+            for (int64_t j = 0; j < n; ++j) {
+                double v = (double)Vb[j * D + d];
+                acc += s[j] * v;
+                mag += s[j] * fabs(v);
+            }
+            O[bi * D + d] = acc;
+            if (Dn) Dn[bi * D + d] = mag;
+        }
+        free(s);
+    }
+}

@@ -34,6 +34,7 @@ def lib():
             "ref_gelu_tanh": [p, i64],
             "ref_conv2d_nchw_bias": [p, p, p] + [i64] * 9 + [p, p],
             "ref_attention": [p, p, p, i64, i64, i64, i64, dbl, p, p],
+            "ref_attention_causal": [p, p, p, i64, i64, i64, i64, dbl, p, p],
             "ref_layout_copy": [p, C.c_int32, p, p, p],
             "ref_set_threads": [C.c_int],
             "ref_dropout_hash": [p, i64, i64, C.c_float, C.c_uint64],
@@ -147,14 +148,16 @@ def conv2d_nchw_bias(inp, wt, bias=None, stride=1, pad=1, want_norm=False):
     return (out, Dn) if want_norm else out
 
 
-def attention(Q, K, V, scale, want_norm=False):
+def attention(Q, K, V, scale, want_norm=False, causal=False):
+    """softmax(scale * Q K^T) V per batch; causal=True lets query i see keys j <= i only."""
     Q, K, V = _f32(Q), _f32(K), _f32(V)
     B, Lq, D = Q.shape
     B2, Lk, D2 = K.shape
     assert V.shape == K.shape and B2 == B and D2 == D and Lk >= 1
     O = np.empty((B, Lq, D), dtype=np.float64)
     Dn = np.empty_like(O) if want_norm else None
-    lib().ref_attention(_ptr(Q), _ptr(K), _ptr(V), B, Lq, Lk, D, float(scale), _ptr(O), _ptr(Dn))
+    fn = lib().ref_attention_causal if causal else lib().ref_attention
+    fn(_ptr(Q), _ptr(K), _ptr(V), B, Lq, Lk, D, float(scale), _ptr(O), _ptr(Dn))
     return (O, Dn) if want_norm else O
 
 

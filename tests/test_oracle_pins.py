@@ -674,3 +674,30 @@ def test_arg_reductions_break_ties_towards_the_lowest_index():
     # magnitudes do not matter, order does
     assert ref.reduce_axis(f32([-5, -1, -9]), (3,), (1,), 0, "argmax") == 1
     assert ref.reduce_axis(f32([-5, -1, -9]), (3,), (1,), 0, "argmin") == 2
+
+
+# ------------------------------------------------------------ causal attention
+def test_causal_attention_closed_forms_and_dense_witness():
+    B, L, D = 2, 9, 4
+    Q = f32(rng.normal(size=(B, L, D))); K = f32(rng.normal(size=(B, L, D))); V = f32(rng.normal(size=(B, L, D)))
+    O = ref.attention(Q, K, V, 0.5, causal=True)
+    # the first query sees key 0 only; the last one sees every key, like the unmasked operator
+    assert np.allclose(O[:, 0], V[:, 0].astype(np.float64), rtol=0, atol=1e-15)
+    assert np.allclose(O[:, -1], ref.attention(Q, K, V, 0.5)[:, -1], rtol=0, atol=1e-14)
+    # Q = 0: uniform weights over the visible prefix -> running means of V
+    O0 = ref.attention(np.zeros_like(Q), K, V, 0.5, causal=True)
+    want = np.cumsum(V.astype(np.float64), axis=1) / np.arange(1, L + 1)[None, :, None]
+    assert np.allclose(O0, want, rtol=0, atol=1e-14)
+    # dense witness: scores with -inf above the diagonal through the pinned row softmax
+    S = 0.5 * np.einsum("bid,bjd->bij", Q.astype(np.float64), K.astype(np.float64))
+    S[:, np.triu_indices(L, 1)[0], np.triu_indices(L, 1)[1]] = -np.inf
+    P = np.exp(S - S.max(axis=2, keepdims=True)); P /= P.sum(axis=2, keepdims=True)
+    assert np.allclose(O, P @ V.astype(np.float64), rtol=0, atol=1e-14)
+    # more queries than keys: queries past the last key see all keys; fewer queries: the prefix rule still holds
+    Kk, Vv = K[:, :5], V[:, :5]
+    Oc = ref.attention(Q, Kk, Vv, 0.5, causal=True)
+    assert np.allclose(Oc[:, 5:], ref.attention(Q, Kk, Vv, 0.5)[:, 5:], rtol=0, atol=1e-14)
+    assert np.allclose(Oc[:, 2], ref.attention(Q[:, 2:3], Kk[:, :3], Vv[:, :3], 0.5)[:, 0], rtol=0, atol=1e-14)
+    # a future key cannot matter: changing K, V beyond the diagonal leaves earlier rows untouched
+    K2, V2 = K.copy(), V.copy(); K2[:, 6:] += 3.0; V2[:, 6:] -= 5.0
+    assert np.array_equal(ref.attention(Q, K2, V2, 0.5, causal=True)[:, :6], O[:, :6])
