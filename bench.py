@@ -262,6 +262,28 @@ def main() -> int:
                              note="flop = the convolution's 2*N*K*Ho*Wo*C*R*S; tiles are 2 rows x 32 columns, so 56-wide rows use 56/64 of the MFMA work"))
         del t7, out7
 
+        # causal attention at the shape of chain 5 (flop = only the visible (query, key) pairs)
+        if 5 in sets:
+            q5, k5, v5 = sets[5][0]["ins"]
+            o5 = torch.empty_like(q5)
+            plan5, ins5 = hpct.attention_plan(q5, k5, v5, o5, 0.125, causal=True)
+            call5 = plan5.bind(ins5, [o5])
+            for _ in range(min(args.warmup, 10)):
+                call5()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                call5()
+            e1.record()
+            torch.cuda.synchronize()
+            us = 1e3 * e0.elapsed_time(e1) / args.steps
+            B5, L5, D5 = q5.shape
+            flop5 = 4.0 * D5 * B5 * L5 * (L5 + 1) / 2
+            next_ops.append(dict(op="causal_attention_%dx%dx%d" % (B5, L5, D5), kernel=plan5.kernel_name, launches=args.steps,
+                                 avg_us=round(us, 3), achieved=round(flop5 / us / 1e6, 2), unit="TFLOP/s",
+                                 peak=MFMA_F32_PEAK_TFLOPS, frac=round(flop5 / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4),
+                                 note="flop = 4*D per visible (query, key) pair; masked pairs inside diagonal blocks are computed but not counted"))
+
     per_op, fracs = [], []
     for i in which:
         avg_us = 1e3 * ev[i][0].elapsed_time(ev[i][1]) / args.steps

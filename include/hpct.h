@@ -49,8 +49,8 @@
  *         then MAXPOOL2_HW or no reduction            bias[K], scale[K], shift[K]   [N,K,Ho/2,Wo/2]
  *         (square 1/3/5/7 filter, stride <= 4,                                       with MAXPOOL2_HW
  *         Ho = (H + 2 pad - R) / stride + 1)
- *   BGEMM_SOFTMAX_BGEMM (scores scaled by `scale`)    Q[B,L,D], K[B,Lk,D],          [B,L,D]
- *                                                     V[B,Lk,D]
+ *   BGEMM_SOFTMAX_BGEMM [+SCALE_CONST: scores scaled  Q[B,L,D], K[B,Lk,D],          [B,L,D]
+ *         by `scale`] [+CAUSAL_MASK] (D = 64)         V[B,Lk,D]
  */
 #ifndef HPCT_H
 #define HPCT_H
@@ -106,11 +106,12 @@ typedef enum {
     HPCT_EPI_ADD_RESIDUAL = 3,    /* + R, same shape as the running value */
     HPCT_EPI_GELU_TANH = 4,       /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
     HPCT_EPI_SCALE_CONST = 5,     /* * desc.scale */
-    HPCT_EPI_DROPOUT_HASH = 6     /* training-mode dropout with the hash mask of the Section 5.3 case study: for
+    HPCT_EPI_DROPOUT_HASH = 6,    /* training-mode dropout with the hash mask of the Section 5.3 case study: for
                                      element (i, j) of an [M,N] value, h = i*N + j + dropout_seed (uint64, wrapping),
                                      h ^= h >> 17; h ^= h << 31; h ^= h >> 8; rand = (float)(h % 1000) / 1000.0f;
                                      the element becomes 0 when rand < dropout_p (fp32 compare) and is multiplied
                                      by 1 / (1 - dropout_p) otherwise.  GEMM anchor only. */
+    HPCT_EPI_CAUSAL_MASK = 7      /* on the scores of BGEMM_SOFTMAX_BGEMM: query i attends keys j <= i only */
 } hpct_epilogue;
 
 /* Row reductions (Table 1, Reduction). */

@@ -399,9 +399,11 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
 }
 
 hpct_status plan_attn(const hpct_op_desc& d, hpct_plan& p) {
-    float scale = 1.0f;
-    if (d.n_epi == 1 && d.epi[0] == HPCT_EPI_SCALE_CONST) scale = d.scale;
-    else if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "BGEMM_SOFTMAX_BGEMM: the only epilogue supported is SCALE_CONST (on the scores)");
+    static const hpct_epilogue allowed[] = {HPCT_EPI_SCALE_CONST, HPCT_EPI_CAUSAL_MASK};
+    bool has[2];
+    if (!parse_epi(d, allowed, 2, has))
+        return fail(HPCT_ERR_UNSUPPORTED, "BGEMM_SOFTMAX_BGEMM: epilogues (on the scores) must be [SCALE_CONST] [CAUSAL_MASK] in that order");
+    const float scale = has[0] ? d.scale : 1.0f;
     if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_SOFTMAX_LAST)
         return fail(HPCT_ERR_UNSUPPORTED, "BGEMM_SOFTMAX_BGEMM: reduction must be NONE or SOFTMAX_LAST (the softmax is part of the anchor)");
     if (d.n_in != 3 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "BGEMM_SOFTMAX_BGEMM takes Q, K, V and 1 output");
@@ -419,7 +421,7 @@ hpct_status plan_attn(const hpct_op_desc& d, hpct_plan& p) {
     if (!attn_supported((int32_t)D, &why)) return fail(HPCT_ERR_UNSUPPORTED, "attention: %s", why);
     if (!(scale == scale) || scale - scale != 0.f) return fail(HPCT_ERR_BAD_DESC, "attention: scale must be finite");
     p.kind = Kind::Attn;
-    p.u.attn = AttnParams{nullptr, nullptr, nullptr, nullptr, (int32_t)B, (int32_t)L, (int32_t)Lk, (int32_t)D, scale};
+    p.u.attn = AttnParams{nullptr, nullptr, nullptr, nullptr, (int32_t)B, (int32_t)L, (int32_t)Lk, (int32_t)D, scale, has[1] ? 1 : 0};
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = 2; p.slot[3] = -1;
     p.shape = attn_shape(p.u.attn);
     return HPCT_OK;
@@ -443,7 +445,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)
-        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_DROPOUT_HASH) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
+        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_CAUSAL_MASK) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
 
     hpct_plan tmp;
     std::memset(&tmp, 0, sizeof tmp);

@@ -22,6 +22,11 @@
 // the end, which puts two waves on every SIMD.  NQW = 4 (128 queries, eight
 // waves) measured faster than two 64-query groups per CU, which stage every
 // K/V block twice.
+//
+// CAUSAL: query i sees keys j <= i.  A work-group stops at the key block that
+// holds its last query's diagonal; a wave skips (both contractions) every
+// 32-key sub-block that lies wholly above its 32 queries' diagonal and masks
+// inside the sub-blocks the diagonal crosses.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -41,7 +46,7 @@ __device__ __forceinline__ float xchg_half(float v) {  // value held by lane ^ 3
     return __shfl_xor(v, 32, 64);
 }
 
-template <int KS, int NQW>
+template <int KS, int NQW, bool CAUSAL>
 __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __restrict__ Q, const float* __restrict__ K,
                                                          const float* __restrict__ V, float* __restrict__ O, int Lq,
                                                          int Lk, float scale_log2e) {
@@ -111,7 +116,12 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
     float m = kNegBig;   // softmax reference (log2 domain), same in both lane halves; within kSlack of the running max
     float lsum = 0.f;    // running sum over this lane half's keys only
 
-    const int nblocks = (Lk + KB - 1) / KB;
+    int nblocks = (Lk + KB - 1) / KB;
+    if (CAUSAL) {  // same for every wave of the group: the block of the group's last query
+        const int q_last = (item % nqb) * QT + QT - 1 < Lq ? (item % nqb) * QT + QT - 1 : Lq - 1;
+        const int nb = q_last / KB + 1;
+        nblocks = nb < nblocks ? nb : nblocks;
+    }
     fetch(0);
     stash(0);
     __syncthreads();
@@ -123,11 +133,18 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
 
         // ---- scores of this wave's sub-blocks: S^T = K Q^T -------------------
         float16v s[SUB];
+        bool skip[SUB];   // wave-uniform: the sub-block lies above the diagonal of all 32 queries
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s[u][i] = 0.f;
+            for (int i = 0; i < 16; ++i) s[u][i] = CAUSAL ? -INFINITY : 0.f;
             const int kb = (KS == 2 ? kgrp : u) * 32;
+            skip[u] = CAUSAL && t * KB + kb > q0 + QW - 1;
+            if (skip[u]) continue;
+            if (CAUSAL) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[u][i] = 0.f;
+            }
             const float* krow = Kc + (kb + l32) * KLD + 4 * half;
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
@@ -145,6 +162,12 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (kb + 8 * (r >> 2) + 4 * half + (r & 3) >= Lk) s[u][r] = -INFINITY;
+            }
+            if (CAUSAL && !skip[u] && kb + 31 > q0) {  // the diagonal crosses this sub-block
+                const int q = q0 + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (kb + 8 * (r >> 2) + 4 * half + (r & 3) > q) s[u][r] = -INFINITY;
             }
 #pragma unroll
             for (int r = 0; r < 16; ++r) bm = fmaxf(bm, s[u][r]);
@@ -176,6 +199,7 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
         // ---- O^T += V^T P^T ---------------------------------------------------------
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
+            if (skip[u]) continue;
             const int kb = (KS == 2 ? kgrp : u) * 32;
             const float* vbase = Vc + (kb + 4 * half) * VLD + l32;
 #pragma unroll
@@ -244,22 +268,27 @@ LaunchShape attn_shape(const AttnParams& p) {
     s.grid[0] = (uint32_t)(((p.Lq + kQT - 1) / kQT) * p.B); s.grid[1] = 1; s.grid[2] = 1;
     s.block[0] = 64 * kNQW * kKS; s.block[1] = s.block[2] = 1;
     s.lds_bytes = (uint32_t)kLds;
-    s.kernel = "attn_fwd_d64<ks2>";
+    s.kernel = p.causal ? "attn_fwd_d64<ks2,causal>" : "attn_fwd_d64<ks2>";
     return s;
 }
 
-hipError_t attn_launch(const AttnParams& p, hipStream_t stream) {
+template <bool CAUSAL>
+hipError_t launch_attn(const AttnParams& p, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_d64<kKS, kNQW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_d64<kKS, kNQW, CAUSAL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)(((p.Lq + kQT - 1) / kQT) * p.B)), block(64 * kNQW * kKS);
-    hipLaunchKernelGGL((attn_fwd_d64<kKS, kNQW>), grid, block, kLds, stream, p.Q, p.K, p.V, p.O, p.Lq, p.Lk,
+    hipLaunchKernelGGL((attn_fwd_d64<kKS, kNQW, CAUSAL>), grid, block, kLds, stream, p.Q, p.K, p.V, p.O, p.Lq, p.Lk,
                        p.scale * kLog2e);
     return hipGetLastError();
+}
+
+hipError_t attn_launch(const AttnParams& p, hipStream_t stream) {
+    return p.causal ? launch_attn<true>(p, stream) : launch_attn<false>(p, stream);
 }
 
 }  // namespace hpct

@@ -122,6 +122,7 @@ hipError_t conv_launch(const ConvParams& p, hipStream_t stream);
 struct AttnParams {
     const float* Q; const float* K; const float* V; float* O;
     int32_t B, Lq, Lk, D; float scale;
+    int32_t causal;   // query i sees keys j <= i only
 };
 bool attn_supported(int32_t D, const char** why);
 LaunchShape attn_shape(const AttnParams& p);

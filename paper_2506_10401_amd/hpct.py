@@ -23,7 +23,7 @@ STATUS_NAMES = ["HPCT_OK", "HPCT_ERR_NULL", "HPCT_ERR_BAD_DESC", "HPCT_ERR_SHAPE
 HPCT_F32, HPCT_I32 = 0, 1
 HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW = range(4)
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
-    HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH = range(7)
+    HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH, HPCT_EPI_CAUSAL_MASK = range(8)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS = range(10)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
@@ -374,14 +374,15 @@ def conv_block(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, poo
     plan.launch(ins, [out], stream)
 
 
-def attention_plan(Q, K, V, out, scale=0.125):
-    plan = _cached(("attn", _sh(Q), _sh(K), float(scale)), lambda: op_desc(
-        HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, [HPCT_EPI_SCALE_CONST], HPCT_RED_NONE, 0,
+def attention_plan(Q, K, V, out, scale=0.125, causal=False):
+    epi = [HPCT_EPI_SCALE_CONST] + ([HPCT_EPI_CAUSAL_MASK] if causal else [])
+    plan = _cached(("attn", _sh(Q), _sh(K), float(scale), causal), lambda: op_desc(
+        HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, epi, HPCT_RED_NONE, 0,
         [_sh(Q), _sh(K), _sh(V)], [_sh(out)], scale=scale))
     return plan, [Q, K, V]
 
 
-def attention(Q, K, V, out, scale=0.125, stream=None) -> None:
-    """out = softmax(scale * Q K^T) V per batch."""
-    plan, ins = attention_plan(Q, K, V, out, scale)
+def attention(Q, K, V, out, scale=0.125, causal=False, stream=None) -> None:
+    """out = softmax(scale * Q K^T) V per batch; causal: query i attends keys j <= i only."""
+    plan, ins = attention_plan(Q, K, V, out, scale, causal)
     plan.launch(ins, [out], stream)

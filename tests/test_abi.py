@@ -447,3 +447,15 @@ def test_axis_reduction_errors():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.out[0] = H.tensor_desc((4,), (2,))   # strided output
     expect(H.HPCT_ERR_UNSUPPORTED, d)
+
+
+def test_causal_attention_plan():
+    d = cfg_desc(5); d.n_epi = 2; d.epi[1] = H.HPCT_EPI_CAUSAL_MASK
+    p = H.Plan(d)
+    assert p.kernel_name == "attn_fwd_d64<ks2,causal>" and p.launch_shape()[0] == (256, 1, 1)
+    d = cfg_desc(5); d.n_epi = 1; d.epi[0] = H.HPCT_EPI_CAUSAL_MASK       # mask without a scale: scale 1
+    assert H.Plan(d).kernel_name == "attn_fwd_d64<ks2,causal>"
+    d = cfg_desc(5); d.n_epi = 2; d.epi[0], d.epi[1] = H.HPCT_EPI_CAUSAL_MASK, H.HPCT_EPI_SCALE_CONST
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(1); d.epi[1] = H.HPCT_EPI_CAUSAL_MASK                   # only on attention scores
+    expect(H.HPCT_ERR_UNSUPPORTED, d)

@@ -360,10 +360,10 @@ def test_chain7_pool_takes_the_maximum_not_a_sum_or_a_corner():
 
 
 # ------------------------------------------------------------------- chain 5
-def run_chain5(t, scale=0.125):
+def run_chain5(t, scale=0.125, causal=False):
     Q, K, V = dev(t["Q"]), dev(t["K"]), dev(t["V"])
     out = torch.full(tuple(Q.shape), float("nan"), device="cuda")
-    hpct.attention(Q, K, V, out, scale=scale)
+    hpct.attention(Q, K, V, out, scale=scale, causal=causal)
     return host(out)
 
 
@@ -385,6 +385,27 @@ def test_chain5_ragged_shapes(B, L, Lk):
     for scale in (0.125, 1.0):
         want, Dn = ref.chain5(t["Q"], t["K"], t["V"], scale)
         assert show("scale %g" % scale, compare.contraction(run_chain5(t, scale), want, Dn))
+
+
+def test_causal_attention_full_size():
+    t = datagen.make(5)
+    want, Dn = ref.attention(t["Q"], t["K"], t["V"], 0.125, want_norm=True, causal=True)
+    got = run_chain5(t, causal=True)
+    assert show("causal 16x2048x64", compare.contraction(got, want, Dn))
+    assert np.max(np.abs(got - want) / Dn) < 1e-4
+    # row 0 of every batch is V[0] exactly (a single key: p = 1)
+    assert np.array_equal(got[:, 0], t["V"][:, 0])
+    assert np.array_equal(got.view(np.uint32), run_chain5(t, causal=True).view(np.uint32))
+
+
+@pytest.mark.parametrize("B,L,Lk", [(1, 1, 1), (2, 5, 3), (1, 32, 32), (3, 33, 31), (2, 100, 64), (1, 128, 65),
+                                    (2, 130, 97), (1, 200, 300), (1, 64, 1000), (1, 300, 40), (2, 257, 257)])
+def test_causal_attention_ragged_shapes(B, L, Lk):
+    print("causal B=%d L=%d Lk=%d" % (B, L, Lk), flush=True)
+    t = datagen.make(5, B=B, L=L, Lk=Lk)
+    for scale in (0.125, 1.0):
+        want, Dn = ref.attention(t["Q"], t["K"], t["V"], scale, want_norm=True, causal=True)
+        assert show("scale %g" % scale, compare.contraction(run_chain5(t, scale, causal=True), want, Dn))
 
 
 def test_attention_large_scores_do_not_overflow():
