@@ -8,8 +8,8 @@
  * "reshape, transpose"; fused examples
  * of its Section 5.3) with an op descriptor; the library validates it, picks a
  * hand-written HIP kernel and enqueues it on the caller's stream: one kernel per
- * launch, two for the plans that report a workspace (the second finishes a
- * reduction from the partial results the first left there).
+ * launch, two or three for the plans that report a workspace (the later ones finish
+ * a reduction from the partial results the first left there).
  *
  * Conventions
  *  - All tensors are fp32 (the index output of an arg-reduction is int32), described by

@@ -1,8 +1,8 @@
 // Tiled GEMM for outputs large enough to fill the chip, with the epilogues of
 // the fused Matmul chains in registers (Table 1 of the paper: ComputeIntensive
 // "matmul", Elementwise "add, relu", Reduction "mean, softmax"; the
-// [Matmul, Dropout, Mean, Softmax] group of its Section 5.3), and the small
-// kernel that finishes a mean / softmax over the rows.
+// [Matmul, Dropout, Mean, Softmax] group of its Section 5.3), and the two small
+// kernels that finish a mean over the columns and a softmax over the rows.
 //
 // gemm_tile128: a work-group of four waves owns a 128 x 128 output tile, a wave
 // 64 x 64 of it as 2 x 2 accumulators of v_mfma_f32_32x32x2_f32.  K is walked
@@ -189,32 +189,58 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
     }
 }
 
-// out[m] = (1/N) sum_t ws[t][m]; with `softmax`, out = softmax over the M means.
-// One work-group; every thread owns the rows m = tid, tid + 1024, ...
+// out[m] = (1/N) sum_t ws[t][m], the partial row sums added in tile order.  A thread per row;
+// the T loads of a row are independent, so they are all in flight together.
+__global__ __launch_bounds__(256) void rows_mean(const float* __restrict__ ws, float* __restrict__ out, int M, int T, float inv_n) {
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= M) return;
+    float s = 0.f;
+    int t = 0;
+    for (; t + 8 <= T; t += 8) {
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = ws[(int64_t)(t + u) * M + m];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += x[u];
+    }
+    for (; t < T; ++t) s += ws[(int64_t)t * M + m];
+    out[m] = s * inv_n;
+}
+
+// Both steps in one work-group, for small M * T (one launch less): out[m] = mean, then softmax in place.
 constexpr int kFinThreads = 1024;
-__global__ __launch_bounds__(kFinThreads) void rows_mean_softmax(const float* __restrict__ ws, float* __restrict__ out, int M,
-                                                                int T, float inv_n, int softmax) {
-    __shared__ float slots[kFinThreads / kWave];
+__device__ __forceinline__ void softmax_in_place(float* __restrict__ v, int M, float* slots) {
     const int tid = threadIdx.x;
     float mx = -INFINITY;
-    for (int m = tid; m < M; m += kFinThreads) {
-        float s = 0.f;
-        for (int t = 0; t < T; ++t) s += ws[(int64_t)t * M + m];
-        const float mu = s * inv_n;
-        out[m] = mu;
-        mx = fmaxf(mx, mu);
-    }
-    if (!softmax) return;  // uniform
+    for (int m = tid; m < M; m += kFinThreads) mx = fmaxf(mx, v[m]);
     mx = block_reduce<OpMax, kFinThreads / kWave>(mx, slots);
     float sum = 0.f;
     for (int m = tid; m < M; m += kFinThreads) {
-        const float e = fast_exp2((out[m] - mx) * kLog2e);
-        out[m] = e;
+        const float e = fast_exp2((v[m] - mx) * kLog2e);
+        v[m] = e;
         sum += e;
     }
     sum = block_reduce<OpSum, kFinThreads / kWave>(sum, slots);
     const float inv = 1.0f / sum;
-    for (int m = tid; m < M; m += kFinThreads) out[m] *= inv;
+    for (int m = tid; m < M; m += kFinThreads) v[m] *= inv;
+}
+
+__global__ __launch_bounds__(kFinThreads) void rows_mean_softmax(const float* __restrict__ ws, float* __restrict__ out, int M,
+                                                                int T, float inv_n, int softmax) {
+    __shared__ float slots[kFinThreads / kWave];
+    for (int m = threadIdx.x; m < M; m += kFinThreads) {
+        float s = 0.f;
+        for (int t = 0; t < T; ++t) s += ws[(int64_t)t * M + m];
+        out[m] = s * inv_n;
+    }
+    if (softmax) softmax_in_place(out, M, slots);   // uniform; every thread reads back only what it wrote
+}
+
+// v = softmax(v) over a vector of M values, in place.  One work-group; every
+// thread owns the elements tid, tid + 1024, ... in all three passes.
+__global__ __launch_bounds__(kFinThreads) void vector_softmax(float* __restrict__ v, int M) {
+    __shared__ float slots[kFinThreads / kWave];
+    softmax_in_place(v, M, slots);
 }
 
 }  // namespace
@@ -240,7 +266,14 @@ hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream) {
 }
 
 hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream) {
-    hipLaunchKernelGGL(rows_mean_softmax, dim3(1), dim3(kFinThreads), 0, stream, ws, out, M, T, 1.0f / (float)N, softmax);
+    if ((int64_t)M * T <= 16384) {  // a few loads per thread: one work-group does both steps
+        hipLaunchKernelGGL(rows_mean_softmax, dim3(1), dim3(kFinThreads), 0, stream, ws, out, M, T, 1.0f / (float)N, softmax);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(rows_mean, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, stream, ws, out, M, T, 1.0f / (float)N);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !softmax) return e;
+    hipLaunchKernelGGL(vector_softmax, dim3(1), dim3(kFinThreads), 0, stream, out, M);
     return hipGetLastError();
 }
 

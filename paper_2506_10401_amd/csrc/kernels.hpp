@@ -1,6 +1,6 @@
 // Launch parameters and host-side launchers of the kernel families.  Each
-// launcher enqueues one kernel on `stream` (two for a GEMM chain that ends in a
-// mean over the last dimension) and returns the HIP status of the launch.
+// launcher enqueues one kernel on `stream` (up to three for the chains that finish
+// a reduction from a workspace) and returns the HIP status of the launch.
 // Shapes have been validated by the caller (the plan layer); launchers assert
 // nothing beyond what they state here.
 #pragma once
@@ -80,8 +80,9 @@ hipError_t reduce_launch(const ReduceParams& p, hipStream_t stream);
 // ---- GEMM + bias + relu + hash dropout, then one of: store [M,N]; row softmax
 //      (when the tile spans the whole row); mean over the last dim (-> [M]),
 //      optionally followed by a softmax over those M means.  The mean variants
-//      enqueue two kernels: the GEMM writes one partial row sum per column tile
-//      to `ws` ([col_tiles][M] floats), a one-group kernel finishes into Y.
+//      enqueue two or three kernels: the GEMM writes one partial row sum per column
+//      tile to `ws` ([col_tiles][M] floats), a second kernel adds them into the row
+//      means in Y, a one-group kernel turns Y into its softmax.
 struct GemmParams {
     const float* X; const float* W; const float* bias; float* Y;
     int32_t M, K, N; int32_t relu, softmax;

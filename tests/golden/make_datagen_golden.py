@@ -1,5 +1,5 @@
 """Writes tests/golden/datagen_first8.json: the first eight fp32 values (as hex
-bit patterns) of every input tensor of the five workloads at full size.  Calls
+bit patterns) of every input tensor of the workloads at full size.  Calls
 only the input generator.  Re-run after a deliberate change of the generator."""
 import json
 import os

@@ -70,7 +70,7 @@ def test_shapes_dtypes_and_seeds_of_the_five_workloads():
 def test_stored_first_values():
     with open(os.path.join(HERE, "golden", "datagen_first8.json")) as f:
         gold = json.load(f)
-    assert len(gold) == 16
+    assert len(gold) == 24   # 16 tensors of the five workloads + 3 of the dropout chain + 5 of the conv block
     for key, rec in gold.items():
         gen = datagen.gen_uniform if rec["kind"] == "u" else datagen.gen_normal
         got = gen(int(rec["seed"], 16), (8,), rec["p0"], rec["p1"]).view(np.uint32)
