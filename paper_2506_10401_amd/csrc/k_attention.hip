@@ -26,7 +26,11 @@
 // CAUSAL: query i sees keys j <= i.  A work-group stops at the key block that
 // holds its last query's diagonal; a wave skips (both contractions) every
 // 32-key sub-block that lies wholly above its 32 queries' diagonal and masks
-// inside the sub-blocks the diagonal crosses.
+// inside the sub-blocks the diagonal crosses.  The work of a query block grows
+// with its position, so the causal instance is PAIRed: a work-group of 64
+// queries x 4 key groups (128-key staged blocks) handles query block i and then
+// block n-1-i of the same batch, which gives every work-group the same number of
+// key blocks to walk.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -34,7 +38,6 @@ namespace hpct {
 namespace {
 
 constexpr int D = 64;
-constexpr int KB = 64;        // keys per staged block
 constexpr int QW = 32;        // queries per wave
 constexpr int KLD = D + 4;    // K row stride in LDS: conflict-free 128-bit fragment reads
 constexpr int VLD = D + 8;    // V row stride: rows 4 apart land 32 banks apart
@@ -46,14 +49,17 @@ __device__ __forceinline__ float xchg_half(float v) {  // value held by lane ^ 3
     return __shfl_xor(v, 32, 64);
 }
 
-template <int KS, int NQW, bool CAUSAL>
+template <int KS, int NQW, bool CAUSAL, bool PAIR>
 __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __restrict__ Q, const float* __restrict__ K,
                                                          const float* __restrict__ V, float* __restrict__ O, int Lq,
                                                          int Lk, float scale_log2e) {
     constexpr int NT = 64 * NQW * KS;
-    constexpr int QT = NQW * QW;                // queries per work-group
-    constexpr int SUB = 2 / KS;                 // 32-key sub-blocks per wave per staged block
+    constexpr int QT = NQW * QW;                // queries per work-group (and pass)
+    constexpr int KB = KS == 4 ? 128 : 64;      // keys per staged block
+    constexpr int SUB = KB / 32 / KS;           // 32-key sub-blocks per wave per staged block
     constexpr int LD4 = KB * D / 4 / NT;        // float4 per thread per matrix per block
+    static_assert(KB * D / 4 % NT == 0, "staging loop must divide evenly");
+    static_assert((size_t)(2 * KB * (KLD + VLD)) >= (size_t)(KS - 1) * NQW * 34 * 64, "merge area must fit in the stage buffers");
     extern __shared__ __align__(16) float lds[];
     float* const Ks = lds;                      // [2][KB*KLD]
     float* const Vs = lds + 2 * KB * KLD;       // [2][KB*VLD]
@@ -64,6 +70,7 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
     // work item = (batch, query block); consecutive items share a batch's K/V and
     // are dealt to the same L2 domain, so each K/V block is fetched from HBM once
     const int nqb = (Lq + QT - 1) / QT;
+    const int per_batch = PAIR ? (nqb + 1) / 2 : nqb;   // work items per batch
     int item;
     {
         const int items = gridDim.x;
@@ -71,10 +78,14 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
         const int qq = items / kXcds, r = items % kXcds;
         item = x * qq + (x < r ? x : r) + j;
     }
-    const int b = item / nqb;
-    const int q0 = (item % nqb) * QT + qwave * QW;
+    const int b = item / per_batch;
+    const int qb0 = item % per_batch;
     const float* Kb = K + (int64_t)b * Lk * D;
     const float* Vb = V + (int64_t)b * Lk * D;
+    const int npass = (PAIR && nqb - 1 - qb0 != qb0) ? 2 : 1;
+  for (int pass = 0; pass < npass; ++pass) {
+    const int qb = pass == 0 ? qb0 : nqb - 1 - qb0;
+    const int q0 = qb * QT + qwave * QW;
 
     // Q fragment, pre-multiplied by scale*log2(e): lane (query l32, half) holds
     // Q[q][8c + 4*half + t] in qf[c][t].
@@ -118,7 +129,7 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
 
     int nblocks = (Lk + KB - 1) / KB;
     if (CAUSAL) {  // same for every wave of the group: the block of the group's last query
-        const int q_last = (item % nqb) * QT + QT - 1 < Lq ? (item % nqb) * QT + QT - 1 : Lq - 1;
+        const int q_last = qb * QT + QT - 1 < Lq ? qb * QT + QT - 1 : Lq - 1;
         const int nb = q_last / KB + 1;
         nblocks = nb < nblocks ? nb : nblocks;
     }
@@ -138,7 +149,7 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
         for (int u = 0; u < SUB; ++u) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[u][i] = CAUSAL ? -INFINITY : 0.f;
-            const int kb = (KS == 2 ? kgrp : u) * 32;
+            const int kb = (kgrp * SUB + u) * 32;
             skip[u] = CAUSAL && t * KB + kb > q0 + QW - 1;
             if (skip[u]) continue;
             if (CAUSAL) {
@@ -157,7 +168,7 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
         float bm = kNegBig;
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
-            const int kb = t * KB + (KS == 2 ? kgrp : u) * 32;
+            const int kb = t * KB + (kgrp * SUB + u) * 32;
             if (kb + 32 > Lk) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
@@ -200,7 +211,7 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
             if (skip[u]) continue;
-            const int kb = (KS == 2 ? kgrp : u) * 32;
+            const int kb = (kgrp * SUB + u) * 32;
             const float* vbase = Vc + (kb + 4 * half) * VLD + l32;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -215,30 +226,36 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
 
     // ---- combine the two lane halves' sums, merge wave groups, normalise, store
     lsum += xchg_half(lsum);
-    if (KS == 2) {
-        // group 1 publishes (o0, o1, m, l) as [qwave][34][64]; the loop's last
+    if (KS > 1) {
+        // groups 1.. publish (o0, o1, m, l) as [kgrp-1][qwave][34][64]; the loop's last
         // barrier has retired every read of the stage buffers
-        float* mg = lds + qwave * 34 * 64;
-        if (kgrp == 1) {
+        if (kgrp > 0) {
+            float* mg = lds + ((kgrp - 1) * NQW + qwave) * 34 * 64;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { mg[i * 64 + lane] = o0[i]; mg[(16 + i) * 64 + lane] = o1[i]; }
             mg[32 * 64 + lane] = m;
             mg[33 * 64 + lane] = lsum;
         }
         __syncthreads();
-        if (kgrp == 1) return;
-        const float m2 = mg[32 * 64 + lane], l2 = mg[33 * 64 + lane];
-        const float mm = fmaxf(m, m2);
-        const float a1 = fast_exp2(m - mm), a2 = fast_exp2(m2 - mm);
-        lsum = lsum * a1 + l2 * a2;
+        if (kgrp == 0) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            o0[i] = o0[i] * a1 + mg[i * 64 + lane] * a2;
-            o1[i] = o1[i] * a1 + mg[(16 + i) * 64 + lane] * a2;
+            for (int g = 1; g < KS; ++g) {   // in group order
+                const float* mg = lds + ((g - 1) * NQW + qwave) * 34 * 64;
+                const float m2 = mg[32 * 64 + lane], l2 = mg[33 * 64 + lane];
+                const float mm = fmaxf(m, m2);
+                const float a1 = fast_exp2(m - mm), a2 = fast_exp2(m2 - mm);
+                m = mm;
+                lsum = lsum * a1 + l2 * a2;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    o0[i] = o0[i] * a1 + mg[i * 64 + lane] * a2;
+                    o1[i] = o1[i] * a1 + mg[(16 + i) * 64 + lane] * a2;
+                }
+            }
         }
     }
     const int q = q0 + l32;
-    if (q < Lq) {
+    if (kgrp == 0 && q < Lq) {
         const float inv = 1.0f / lsum;
         float* dst = O + ((int64_t)b * Lq + q) * D + 4 * half;
 #pragma unroll
@@ -247,14 +264,40 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
             store4(dst + 32 + 8 * g, float4v{o1[4 * g] * inv, o1[4 * g + 1] * inv, o1[4 * g + 2] * inv, o1[4 * g + 3] * inv});
         }
     }
+    if (pass + 1 < npass) __syncthreads();   // the merge area is the next pass's stage buffer
+  }
 }
 
-constexpr int kKS = 2;
-constexpr int kNQW = 4;
-constexpr int kQT = kNQW * QW;
-constexpr size_t kLds = (size_t)(2 * KB * KLD + 2 * KB * VLD) * 4;
-static_assert(kLds >= kNQW * 34 * 64 * 4, "merge area must fit in the stage buffers");
-static_assert(KB * D / 4 % (64 * kNQW * kKS) == 0, "staging loop must divide evenly");
+// plain: 128 queries x 2 key groups, 64-key blocks; causal: 64 queries x 4 key groups, 128-key blocks, paired
+template <bool CAUSAL> struct AttnCfg {
+    static constexpr int KS = CAUSAL ? 4 : 2;
+    static constexpr int NQW = CAUSAL ? 2 : 4;
+    static constexpr int QT = NQW * QW;
+    static constexpr int KB = KS == 4 ? 128 : 64;
+    static constexpr size_t LDS = (size_t)(2 * KB * KLD + 2 * KB * VLD) * 4;
+    static constexpr int NT = 64 * NQW * KS;
+};
+
+template <bool CAUSAL>
+unsigned attn_items(const AttnParams& p) {
+    const int nqb = (p.Lq + AttnCfg<CAUSAL>::QT - 1) / AttnCfg<CAUSAL>::QT;
+    return (unsigned)((CAUSAL ? (nqb + 1) / 2 : nqb) * p.B);
+}
+
+template <bool CAUSAL>
+hipError_t launch_attn(const AttnParams& p, hipStream_t stream) {
+    using C = AttnCfg<CAUSAL>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_d64<C::KS, C::NQW, CAUSAL, CAUSAL>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((attn_fwd_d64<C::KS, C::NQW, CAUSAL, CAUSAL>), dim3(attn_items<CAUSAL>(p)), dim3(C::NT), C::LDS, stream,
+                       p.Q, p.K, p.V, p.O, p.Lq, p.Lk, p.scale * kLog2e);
+    return hipGetLastError();
+}
 
 }  // namespace
 
@@ -265,26 +308,11 @@ bool attn_supported(int32_t d, const char** why) {
 
 LaunchShape attn_shape(const AttnParams& p) {
     LaunchShape s{};
-    s.grid[0] = (uint32_t)(((p.Lq + kQT - 1) / kQT) * p.B); s.grid[1] = 1; s.grid[2] = 1;
-    s.block[0] = 64 * kNQW * kKS; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)kLds;
-    s.kernel = p.causal ? "attn_fwd_d64<ks2,causal>" : "attn_fwd_d64<ks2>";
+    s.grid[0] = p.causal ? attn_items<true>(p) : attn_items<false>(p); s.grid[1] = 1; s.grid[2] = 1;
+    s.block[0] = p.causal ? AttnCfg<true>::NT : AttnCfg<false>::NT; s.block[1] = s.block[2] = 1;
+    s.lds_bytes = (uint32_t)(p.causal ? AttnCfg<true>::LDS : AttnCfg<false>::LDS);
+    s.kernel = p.causal ? "attn_fwd_d64<ks4,causal,paired>" : "attn_fwd_d64<ks2>";
     return s;
-}
-
-template <bool CAUSAL>
-hipError_t launch_attn(const AttnParams& p, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_d64<kKS, kNQW, CAUSAL>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    dim3 grid((unsigned)(((p.Lq + kQT - 1) / kQT) * p.B)), block(64 * kNQW * kKS);
-    hipLaunchKernelGGL((attn_fwd_d64<kKS, kNQW, CAUSAL>), grid, block, kLds, stream, p.Q, p.K, p.V, p.O, p.Lq, p.Lk,
-                       p.scale * kLog2e);
-    return hipGetLastError();
 }
 
 hipError_t attn_launch(const AttnParams& p, hipStream_t stream) {

@@ -452,9 +452,10 @@ def test_axis_reduction_errors():
 def test_causal_attention_plan():
     d = cfg_desc(5); d.n_epi = 2; d.epi[1] = H.HPCT_EPI_CAUSAL_MASK
     p = H.Plan(d)
-    assert p.kernel_name == "attn_fwd_d64<ks2,causal>" and p.launch_shape()[0] == (256, 1, 1)
+    # 32 query blocks of 64 per batch, handled in pairs (i, 31 - i): 16 work-groups per batch
+    assert p.kernel_name == "attn_fwd_d64<ks4,causal,paired>" and p.launch_shape()[:2] == ((256, 1, 1), (512, 1, 1))
     d = cfg_desc(5); d.n_epi = 1; d.epi[0] = H.HPCT_EPI_CAUSAL_MASK       # mask without a scale: scale 1
-    assert H.Plan(d).kernel_name == "attn_fwd_d64<ks2,causal>"
+    assert H.Plan(d).kernel_name == "attn_fwd_d64<ks4,causal,paired>"
     d = cfg_desc(5); d.n_epi = 2; d.epi[0], d.epi[1] = H.HPCT_EPI_CAUSAL_MASK, H.HPCT_EPI_SCALE_CONST
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = cfg_desc(1); d.epi[1] = H.HPCT_EPI_CAUSAL_MASK                   # only on attention scores

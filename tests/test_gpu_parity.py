@@ -399,7 +399,8 @@ def test_causal_attention_full_size():
 
 
 @pytest.mark.parametrize("B,L,Lk", [(1, 1, 1), (2, 5, 3), (1, 32, 32), (3, 33, 31), (2, 100, 64), (1, 128, 65),
-                                    (2, 130, 97), (1, 200, 300), (1, 64, 1000), (1, 300, 40), (2, 257, 257)])
+                                    (2, 130, 97), (1, 200, 300), (1, 64, 1000), (1, 300, 40), (2, 257, 257),
+                                    (1, 192, 192), (3, 320, 320), (1, 65, 129), (2, 449, 450)])
 def test_causal_attention_ragged_shapes(B, L, Lk):
     print("causal B=%d L=%d Lk=%d" % (B, L, Lk), flush=True)
     t = datagen.make(5, B=B, L=L, Lk=Lk)
