@@ -50,7 +50,7 @@
  *         (square 1/3/5/7 filter, stride <= 4,                                       with MAXPOOL2_HW
  *         Ho = (H + 2 pad - R) / stride + 1)
  *   BGEMM_SOFTMAX_BGEMM [+SCALE_CONST: scores scaled  Q[B,L,D], K[B,Lk,D],          [B,L,D]
- *         by `scale`] [+CAUSAL_MASK] (D = 64)         V[B,Lk,D]
+ *         by `scale`] [+CAUSAL_MASK] (D = 32, 64, 128) V[B,Lk,D]
  */
 #ifndef HPCT_H
 #define HPCT_H

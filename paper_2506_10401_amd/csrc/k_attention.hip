@@ -1,4 +1,4 @@
-// Batched GEMM - softmax - GEMM, O = softmax_j(scale * Q K^T) V, head dim 64
+// Batched GEMM - softmax - GEMM, O = softmax_j(scale * Q K^T) V, head dim 32, 64 or 128
 // (Table 1 of the paper: ComputeIntensive "matmul", Reduction "softmax").  The
 // score matrix is never materialised: K/V are streamed in blocks of 64 keys
 // through LDS (double buffered) and the softmax is evaluated online (running
@@ -37,10 +37,7 @@
 namespace hpct {
 namespace {
 
-constexpr int D = 64;
 constexpr int QW = 32;        // queries per wave
-constexpr int KLD = D + 4;    // K row stride in LDS: conflict-free 128-bit fragment reads
-constexpr int VLD = D + 8;    // V row stride: rows 4 apart land 32 banks apart
 constexpr float kNegBig = -1.0e30f;
 constexpr float kSlack = 8.0f;  // log2 headroom of a probability before the softmax reference is moved
 constexpr int kXcds = 8;      // work-groups are dealt round-robin to this many L2 domains
@@ -49,17 +46,21 @@ __device__ __forceinline__ float xchg_half(float v) {  // value held by lane ^ 3
     return __shfl_xor(v, 32, 64);
 }
 
-template <int KS, int NQW, bool CAUSAL, bool PAIR>
-__global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __restrict__ Q, const float* __restrict__ K,
+template <int D, int KS, int NQW, bool CAUSAL, bool PAIR>
+__global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restrict__ Q, const float* __restrict__ K,
                                                          const float* __restrict__ V, float* __restrict__ O, int Lq,
                                                          int Lk, float scale_log2e) {
+    constexpr int KLD = D + 4;                  // K row stride in LDS: conflict-free 128-bit fragment reads
+    constexpr int VLD = D + 8;                  // V row stride: rows 4 apart land 32 banks apart
+    constexpr int DB = D / 32;                  // 32-row blocks of O^T
+    constexpr int MROWS = 16 * DB + 2;          // rows of 64 floats one wave publishes for the merge
     constexpr int NT = 64 * NQW * KS;
     constexpr int QT = NQW * QW;                // queries per work-group (and pass)
     constexpr int KB = KS == 4 ? 128 : 64;      // keys per staged block
     constexpr int SUB = KB / 32 / KS;           // 32-key sub-blocks per wave per staged block
     constexpr int LD4 = KB * D / 4 / NT;        // float4 per thread per matrix per block
     static_assert(KB * D / 4 % NT == 0, "staging loop must divide evenly");
-    static_assert((size_t)(2 * KB * (KLD + VLD)) >= (size_t)(KS - 1) * NQW * 34 * 64, "merge area must fit in the stage buffers");
+    static_assert((size_t)(2 * KB * (KLD + VLD)) >= (size_t)(KS - 1) * NQW * MROWS * 64, "merge area must fit in the stage buffers");
     extern __shared__ __align__(16) float lds[];
     float* const Ks = lds;                      // [2][KB*KLD]
     float* const Vs = lds + 2 * KB * KLD;       // [2][KB*VLD]
@@ -89,12 +90,12 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
 
     // Q fragment, pre-multiplied by scale*log2(e): lane (query l32, half) holds
     // Q[q][8c + 4*half + t] in qf[c][t].
-    float4v qf[8];
+    float4v qf[D / 8];
     {
         const int q = q0 + l32;
         const float* src = Q + ((int64_t)b * Lq + (q < Lq ? q : 0)) * D + 4 * half;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < D / 8; ++c) {
             float4v t = load4(src + 8 * c);
             qf[c] = (q < Lq) ? t * scale_log2e : float4v{0.f, 0.f, 0.f, 0.f};
         }
@@ -121,9 +122,11 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
         }
     };
 
-    float16v o0, o1;  // O^T rows d = 0..31 and 32..63, column = this lane's query
+    float16v o[DB];  // O^T rows d = 32*db .. 32*db+31, column = this lane's query
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { o0[i] = 0.f; o1[i] = 0.f; }
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float m = kNegBig;   // softmax reference (log2 domain), same in both lane halves; within kSlack of the running max
     float lsum = 0.f;    // running sum over this lane half's keys only
 
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
             }
             const float* krow = Kc + (kb + l32) * KLD + 4 * half;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
+            for (int c = 0; c < D / 8; ++c) {
                 const float4v kf = *reinterpret_cast<const float4v*>(krow + 8 * c);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) s[u] = mfma_32x32x2(kf[j], qf[c][j], s[u]);
@@ -194,7 +197,9 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
             m = m_new;
             lsum *= alpha;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { o0[i] *= alpha; o1[i] *= alpha; }
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
         }
         float ps = 0.f;
 #pragma unroll
@@ -216,8 +221,8 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float* vr = vbase + (8 * (r >> 2) + (r & 3)) * VLD;
-                o0 = mfma_32x32x2(vr[0], s[u][r], o0);
-                o1 = mfma_32x32x2(vr[32], s[u][r], o1);
+#pragma unroll
+                for (int db = 0; db < DB; ++db) o[db] = mfma_32x32x2(vr[32 * db], s[u][r], o[db]);
             }
         }
         if (t + 1 < nblocks) stash(cur ^ 1);
@@ -227,30 +232,31 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
     // ---- combine the two lane halves' sums, merge wave groups, normalise, store
     lsum += xchg_half(lsum);
     if (KS > 1) {
-        // groups 1.. publish (o0, o1, m, l) as [kgrp-1][qwave][34][64]; the loop's last
+        // groups 1.. publish (o, m, l) as [kgrp-1][qwave][MROWS][64]; the loop's last
         // barrier has retired every read of the stage buffers
         if (kgrp > 0) {
-            float* mg = lds + ((kgrp - 1) * NQW + qwave) * 34 * 64;
+            float* mg = lds + ((kgrp - 1) * NQW + qwave) * MROWS * 64;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { mg[i * 64 + lane] = o0[i]; mg[(16 + i) * 64 + lane] = o1[i]; }
-            mg[32 * 64 + lane] = m;
-            mg[33 * 64 + lane] = lsum;
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mg[(16 * db + i) * 64 + lane] = o[db][i];
+            mg[16 * DB * 64 + lane] = m;
+            mg[(16 * DB + 1) * 64 + lane] = lsum;
         }
         __syncthreads();
         if (kgrp == 0) {
 #pragma unroll
             for (int g = 1; g < KS; ++g) {   // in group order
-                const float* mg = lds + ((g - 1) * NQW + qwave) * 34 * 64;
-                const float m2 = mg[32 * 64 + lane], l2 = mg[33 * 64 + lane];
+                const float* mg = lds + ((g - 1) * NQW + qwave) * MROWS * 64;
+                const float m2 = mg[16 * DB * 64 + lane], l2 = mg[(16 * DB + 1) * 64 + lane];
                 const float mm = fmaxf(m, m2);
                 const float a1 = fast_exp2(m - mm), a2 = fast_exp2(m2 - mm);
                 m = mm;
                 lsum = lsum * a1 + l2 * a2;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    o0[i] = o0[i] * a1 + mg[i * 64 + lane] * a2;
-                    o1[i] = o1[i] * a1 + mg[(16 + i) * 64 + lane] * a2;
-                }
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[db][i] = o[db][i] * a1 + mg[(16 * db + i) * 64 + lane] * a2;
             }
         }
     }
@@ -259,64 +265,85 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd_d64(const float* __res
         const float inv = 1.0f / lsum;
         float* dst = O + ((int64_t)b * Lq + q) * D + 4 * half;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            store4(dst + 8 * g, float4v{o0[4 * g] * inv, o0[4 * g + 1] * inv, o0[4 * g + 2] * inv, o0[4 * g + 3] * inv});
-            store4(dst + 32 + 8 * g, float4v{o1[4 * g] * inv, o1[4 * g + 1] * inv, o1[4 * g + 2] * inv, o1[4 * g + 3] * inv});
-        }
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                store4(dst + 32 * db + 8 * g, float4v{o[db][4 * g] * inv, o[db][4 * g + 1] * inv, o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv});
     }
     if (pass + 1 < npass) __syncthreads();   // the merge area is the next pass's stage buffer
   }
 }
 
-// plain: 128 queries x 2 key groups, 64-key blocks; causal: 64 queries x 4 key groups, 128-key blocks, paired
-template <bool CAUSAL> struct AttnCfg {
-    static constexpr int KS = CAUSAL ? 4 : 2;
-    static constexpr int NQW = CAUSAL ? 2 : 4;
+// plain: 128 queries x 2 key groups, 64-key blocks.  causal: 64 queries x 4 key groups, 128-key
+// blocks, paired - except at head dim 128, whose 128-key blocks would not fit in LDS: there the
+// plain shape is used, unpaired.
+template <int D, bool CAUSAL> struct AttnCfg {
+    static constexpr bool PAIR = CAUSAL && D <= 64;
+    static constexpr int KS = PAIR ? 4 : 2;
+    static constexpr int NQW = PAIR ? 2 : 4;
     static constexpr int QT = NQW * QW;
     static constexpr int KB = KS == 4 ? 128 : 64;
-    static constexpr size_t LDS = (size_t)(2 * KB * KLD + 2 * KB * VLD) * 4;
+    static constexpr size_t LDS = (size_t)(2 * KB * (D + 4) + 2 * KB * (D + 8)) * 4;
     static constexpr int NT = 64 * NQW * KS;
+    static_assert(LDS <= 160 * 1024, "stage buffers exceed the LDS of a CU");
 };
 
-template <bool CAUSAL>
+template <int D, bool CAUSAL>
 unsigned attn_items(const AttnParams& p) {
-    const int nqb = (p.Lq + AttnCfg<CAUSAL>::QT - 1) / AttnCfg<CAUSAL>::QT;
-    return (unsigned)((CAUSAL ? (nqb + 1) / 2 : nqb) * p.B);
+    using C = AttnCfg<D, CAUSAL>;
+    const int nqb = (p.Lq + C::QT - 1) / C::QT;
+    return (unsigned)((C::PAIR ? (nqb + 1) / 2 : nqb) * p.B);
 }
 
-template <bool CAUSAL>
+template <int D, bool CAUSAL>
 hipError_t launch_attn(const AttnParams& p, hipStream_t stream) {
-    using C = AttnCfg<CAUSAL>;
+    using C = AttnCfg<D, CAUSAL>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_d64<C::KS, C::NQW, CAUSAL, CAUSAL>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd<D, C::KS, C::NQW, CAUSAL, C::PAIR>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((attn_fwd_d64<C::KS, C::NQW, CAUSAL, CAUSAL>), dim3(attn_items<CAUSAL>(p)), dim3(C::NT), C::LDS, stream,
+    hipLaunchKernelGGL((attn_fwd<D, C::KS, C::NQW, CAUSAL, C::PAIR>), dim3(attn_items<D, CAUSAL>(p)), dim3(C::NT), C::LDS, stream,
                        p.Q, p.K, p.V, p.O, p.Lq, p.Lk, p.scale * kLog2e);
     return hipGetLastError();
+}
+
+template <int D>
+void shape_d(const AttnParams& p, LaunchShape& s) {
+    s.grid[0] = p.causal ? attn_items<D, true>(p) : attn_items<D, false>(p);
+    s.block[0] = p.causal ? AttnCfg<D, true>::NT : AttnCfg<D, false>::NT;
+    s.lds_bytes = (uint32_t)(p.causal ? AttnCfg<D, true>::LDS : AttnCfg<D, false>::LDS);
 }
 
 }  // namespace
 
 bool attn_supported(int32_t d, const char** why) {
-    if (d != D) { *why = "only head dimension 64 is supported"; return false; }
+    if (d != 32 && d != 64 && d != 128) { *why = "head dimension must be 32, 64 or 128"; return false; }
     return true;
 }
 
 LaunchShape attn_shape(const AttnParams& p) {
     LaunchShape s{};
-    s.grid[0] = p.causal ? attn_items<true>(p) : attn_items<false>(p); s.grid[1] = 1; s.grid[2] = 1;
-    s.block[0] = p.causal ? AttnCfg<true>::NT : AttnCfg<false>::NT; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)(p.causal ? AttnCfg<true>::LDS : AttnCfg<false>::LDS);
-    s.kernel = p.causal ? "attn_fwd_d64<ks4,causal,paired>" : "attn_fwd_d64<ks2>";
+    s.grid[1] = s.grid[2] = 1; s.block[1] = s.block[2] = 1;
+    static const char* const names[3][2] = {{"attn_fwd_d32<ks2>", "attn_fwd_d32<ks4,causal,paired>"},
+                                            {"attn_fwd_d64<ks2>", "attn_fwd_d64<ks4,causal,paired>"},
+                                            {"attn_fwd_d128<ks2>", "attn_fwd_d128<ks2,causal>"}};
+    switch (p.D) {
+        case 32: shape_d<32>(p, s); s.kernel = names[0][p.causal ? 1 : 0]; break;
+        case 64: shape_d<64>(p, s); s.kernel = names[1][p.causal ? 1 : 0]; break;
+        default: shape_d<128>(p, s); s.kernel = names[2][p.causal ? 1 : 0];
+    }
     return s;
 }
 
 hipError_t attn_launch(const AttnParams& p, hipStream_t stream) {
-    return p.causal ? launch_attn<true>(p, stream) : launch_attn<false>(p, stream);
+    switch (p.D) {
+        case 32: return p.causal ? launch_attn<32, true>(p, stream) : launch_attn<32, false>(p, stream);
+        case 64: return p.causal ? launch_attn<64, true>(p, stream) : launch_attn<64, false>(p, stream);
+        default: return p.causal ? launch_attn<128, true>(p, stream) : launch_attn<128, false>(p, stream);
+    }
 }
 
 }  // namespace hpct

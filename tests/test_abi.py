@@ -200,8 +200,8 @@ def test_unsupported_but_well_formed():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = cfg_desc(4); d.in_[1] = H.tensor_desc((128, 64, 3, 5)); d.out[0] = H.tensor_desc((32, 128, 56, 54))   # not square
     expect(H.HPCT_ERR_UNSUPPORTED, d)
-    d = cfg_desc(5); d.in_[0] = d.in_[1] = d.in_[2] = H.tensor_desc((16, 2048, 32)); d.out[0] = H.tensor_desc((16, 2048, 32))
-    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = cfg_desc(5); d.in_[0] = d.in_[1] = d.in_[2] = H.tensor_desc((16, 2048, 48)); d.out[0] = H.tensor_desc((16, 2048, 48))
+    expect(H.HPCT_ERR_UNSUPPORTED, d)            # head dims 32, 64, 128 only
     d = cfg_desc(5); d.epi[0] = H.HPCT_EPI_RELU
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     # index range of the kernels
@@ -460,3 +460,14 @@ def test_causal_attention_plan():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = cfg_desc(1); d.epi[1] = H.HPCT_EPI_CAUSAL_MASK                   # only on attention scores
     expect(H.HPCT_ERR_UNSUPPORTED, d)
+
+
+def test_attention_head_dims():
+    for D, plain, causal in [(32, "attn_fwd_d32<ks2>", "attn_fwd_d32<ks4,causal,paired>"),
+                             (128, "attn_fwd_d128<ks2>", "attn_fwd_d128<ks2,causal>")]:
+        d = cfg_desc(5); d.in_[0] = d.in_[1] = d.in_[2] = H.tensor_desc((16, 2048, D)); d.out[0] = H.tensor_desc((16, 2048, D))
+        p = H.Plan(d)
+        assert p.kernel_name == plain and p.launch_shape()[0] == (256, 1, 1)
+        assert p.launch_shape()[2] == 2 * 64 * (2 * D + 12) * 4      # two stages of 64 keys, K and V rows padded by 4 and 8
+        d.n_epi = 2; d.epi[1] = H.HPCT_EPI_CAUSAL_MASK
+        assert H.Plan(d).kernel_name == causal

@@ -409,6 +409,18 @@ def test_causal_attention_ragged_shapes(B, L, Lk):
         assert show("scale %g" % scale, compare.contraction(run_chain5(t, scale, causal=True), want, Dn))
 
 
+@pytest.mark.parametrize("D", [32, 128])
+@pytest.mark.parametrize("B,L,Lk", [(1, 1, 1), (2, 70, 45), (1, 130, 257), (2, 384, 384), (1, 1024, 1024)])
+def test_attention_other_head_dims(D, B, L, Lk):
+    print("attention D=%d B=%d L=%d Lk=%d" % (D, B, L, Lk), flush=True)
+    t = datagen.make(5, B=B, L=L, Lk=Lk, D=D)
+    scale = 1.0 / np.sqrt(D)
+    for causal in (False, True):
+        want, Dn = ref.attention(t["Q"], t["K"], t["V"], scale, want_norm=True, causal=causal)
+        got = run_chain5(t, scale, causal=causal)
+        assert show("causal" if causal else "plain", compare.contraction(got, want, Dn))
+
+
 def test_attention_large_scores_do_not_overflow():
     t = datagen.make(5, B=1, L=40, Lk=70)
     t["Q"] = (t["Q"] * 30).astype(np.float32)  # scores of order +-2000: needs the running max
