@@ -276,7 +276,7 @@ bool gemm_use_tile(int32_t M, int32_t N, int32_t softmax) {
 }
 
 int32_t gemm_col_tiles(int32_t M, int32_t N) {
-    return gemm_use_tile(M, N, 0) ? gemm_tile_col_tiles(N) : (N + pick_bn(N) - 1) / pick_bn(N);
+    return gemm_use_tile(M, N, 0) ? gemm_tile_col_tiles(M, N) : (N + pick_bn(N) - 1) / pick_bn(N);
 }
 
 LaunchShape gemm_shape(int32_t M, int32_t, int32_t N, int32_t softmax) {

@@ -4,8 +4,9 @@
 // [Matmul, Dropout, Mean, Softmax] group of its Section 5.3), and the two small
 // kernels that finish a mean over the columns and a softmax over the rows.
 //
-// gemm_tile128: a work-group of four waves owns a 128 x 128 output tile, a wave
-// 64 x 64 of it as 2 x 2 accumulators of v_mfma_f32_32x32x2_f32.  K is walked
+// gemm_tile: a work-group of four waves owns a 128 x 128 output tile, a wave
+// 64 x 64 of it as 2 x 2 accumulators of v_mfma_f32_32x32x2_f32 (64 x 64 tiles,
+// one accumulator per wave, when 128-tiles would be too few to fill the chip).  K is walked
 // in chunks of 16 through a double-buffered LDS stage: the global loads of
 // chunk t+1 are issued before the MFMAs of chunk t and written to the other
 // buffer after them, one barrier per chunk.
@@ -15,7 +16,7 @@
 // with one 128-bit LDS read; MFMA e (0..3) of that group therefore contracts
 // k = {8t+e, 8t+4+e} and its B fragment is the 32-bit read Bs[8t+4h+e][col].
 // Row strides: A rows are 20 words apart (16 lanes x 4 words of a 128-bit read
-// cover all 64 banks), B rows 136 words (the two lane halves, 4 rows apart,
+// cover all 64 banks), B rows tile + 8 words (the two lane halves, 4 rows apart,
 // land on disjoint bank halves).
 //
 // Epilogue.  Register r of accumulator (i, j) is output row
@@ -30,14 +31,17 @@
 namespace hpct {
 namespace {
 
-constexpr int TM = 128, TN = 128, BK = 16;
-constexpr int LDA = 20, LDB = 136;
+constexpr int BK = 16;
+constexpr int LDA = 20;
 constexpr int kThreads = 256;
 constexpr int kXcds = 8;
 
-template <bool VEC>
-// four work-groups per CU (one wave of each per SIMD): 128 registers per lane, 64 of them accumulators
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gemm_tile128(GemmParams p, int tiles_n, int items) {
+// T = tile edge, 128 or 64: a wave owns (T/2) x (T/2) as WB x WB accumulators, WB = T/64.
+// 128: four work-groups per CU (one wave of each per SIMD), 128 registers per lane, 64 of them
+// accumulators.  64: for outputs with too few 128-tiles to fill the chip; 16 accumulator registers.
+template <int T, bool VEC>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) void gemm_tile(GemmParams p, int tiles_n, int items) {
+    constexpr int TM = T, TN = T, WB = T / 64, LDB = T + 8;
     __shared__ __attribute__((aligned(16))) float As[2][TM * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
     __shared__ float rs[2][TM];
@@ -47,26 +51,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
     const int wm = wave >> 1, wn = wave & 1;
     const int M = p.M, K = p.K, N = p.N;
 
-    // consecutive tiles (same row block, neighbouring column blocks) go to the same L2 domain
+    // a contiguous range of items goes to the same L2 domain (and runs there at the same time)
     int item;
     {
         const int x = blockIdx.x % kXcds, j = blockIdx.x / kXcds;
         const int q = items / kXcds, r = items % kXcds;
         item = x * q + (x < r ? x : r) + j;
     }
-    const int tm = item / tiles_n, tn = item % tiles_n;
+    // grouped order: runs of 8 tile rows, column-major inside a run, so such a range covers a compact
+    // block of tiles (8 rows x n columns) and shares both its A rows and its B columns in L2
+    const int tiles_m = items / tiles_n;
+    const int run = item / (8 * tiles_n), in_run = item - run * 8 * tiles_n;
+    const int rows = tiles_m - run * 8 < 8 ? tiles_m - run * 8 : 8;
+    const int tm = run * 8 + in_run % rows, tn = in_run / rows;
     const int m0 = tm * TM, n0 = tn * TN;
 
-    // staging coordinates: A rows ar, ar+64 at k offset ak; B rows bk, bk+8 at column offset bn
+    // staging coordinates: A rows ar (+64) at k offset ak; B rows bk (+ BSTEP) at column offset bn
+    constexpr int BSTEP = kThreads / (TN / 4);   // B rows covered by one pass of the work-group
     const int ar = tid >> 2, ak = (tid & 3) * 4;
-    const int bk = tid >> 5, bn = (tid & 31) * 4;
+    const int bk = tid / (TN / 4), bn = (tid % (TN / 4)) * 4;
     const float* __restrict__ X = p.X;
     const float* __restrict__ W = p.W;
 
-    float4v ra[2], rb[2];
+    float4v ra[WB], rb[WB];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < WB; ++i) {
             const int m = m0 + ar + 64 * i, k = k0 + ak;
             const float* src = X + (int64_t)m * K + k;
             if (VEC) {
@@ -75,7 +85,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ra[i][e] = *((m < M && k + e < K) ? src + e : X);
             }
-            const int kk = k0 + bk + 8 * i, n = n0 + bn;
+            const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
             const float* wsrc = W + (int64_t)kk * N + n;
             if (VEC) {
                 rb[i] = load4((kk < K && n < N) ? wsrc : W);
@@ -88,44 +98,44 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
     // zero what lies outside the operands, then write the chunk to LDS buffer `buf`
     auto stash = [&](int k0, int buf) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < WB; ++i) {
             const int m = m0 + ar + 64 * i, k = k0 + ak;
-            const int kk = k0 + bk + 8 * i, n = n0 + bn;
+            const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (!(m < M && k + e < K)) ra[i][e] = 0.f;
                 if (!(kk < K && n + e < N)) rb[i][e] = 0.f;
             }
             *reinterpret_cast<float4v*>(&As[buf][(ar + 64 * i) * LDA + ak]) = ra[i];
-            *reinterpret_cast<float4v*>(&Bs[buf][(bk + 8 * i) * LDB + bn]) = rb[i];
+            *reinterpret_cast<float4v*>(&Bs[buf][(bk + BSTEP * i) * LDB + bn]) = rb[i];
         }
     };
 
-    float16v acc[2][2];
+    float16v acc[WB][WB];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WB; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < WB; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     auto compute = [&](int buf) {
-        const float* a_base = &As[buf][(wm * 64 + l32) * LDA + 4 * h];
-        const float* b_base = &Bs[buf][(4 * h) * LDB + wn * 64 + l32];
+        const float* a_base = &As[buf][(wm * (TM / 2) + l32) * LDA + 4 * h];
+        const float* b_base = &Bs[buf][(4 * h) * LDB + wn * (TN / 2) + l32];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            float4v a[2];
+            float4v a[WB];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const float4v*>(a_base + i * 32 * LDA + 8 * t);
+            for (int i = 0; i < WB; ++i) a[i] = *reinterpret_cast<const float4v*>(a_base + i * 32 * LDA + 8 * t);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float b[2];
+                float b[WB];
 #pragma unroll
-                for (int j = 0; j < 2; ++j) b[j] = b_base[(8 * t + e) * LDB + j * 32];
+                for (int j = 0; j < WB; ++j) b[j] = b_base[(8 * t + e) * LDB + j * 32];
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < WB; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x2(a[i][e], b[j], acc[i][j]);
+                    for (int j = 0; j < WB; ++j) acc[i][j] = mfma_32x32x2(a[i][e], b[j], acc[i][j]);
             }
         }
     };
@@ -145,21 +155,21 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
 
     // ---- epilogue in registers
     const float* __restrict__ bias = p.bias;
-    float rsum[2][16];
+    float rsum[WB][16];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WB; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) rsum[i][r] = 0.f;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int col = n0 + wn * 64 + j * 32 + l32;
+    for (int j = 0; j < WB; ++j) {
+        const int col = n0 + wn * (TN / 2) + j * 32 + l32;
         const bool cok = col < N;
         const float bv = (bias && cok) ? bias[col] : 0.f;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < WB; ++i) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                const int row = m0 + wm * (TM / 2) + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
                 float v = acc[i][j][r] + bv;
                 if (p.relu) v = fmaxf(v, 0.f);
                 if (p.dropout) {
@@ -176,13 +186,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4))
     }
     if (p.mean) {  // uniform over the grid
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < WB; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 float v = rsum[i][r];  // over the 32 lanes of this half: four DPP steps inside each 16-lane row, then the two rows
                 v += dpp_mov<0xB1>(v); v += dpp_mov<0x4E>(v); v += dpp_mov<0x141>(v); v += dpp_mov<0x140>(v);
                 v += __shfl_xor(v, 16, 64);
-                if (l32 == 0) rs[wn][wm * 64 + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3)] = v;
+                if (l32 == 0) rs[wn][wm * (TM / 2) + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3)] = v;
             }
         __syncthreads();
         if (tid < TM && m0 + tid < M) p.ws[(int64_t)tn * M + m0 + tid] = rs[0][tid] + rs[1][tid];
@@ -245,24 +255,39 @@ __global__ __launch_bounds__(kFinThreads) void vector_softmax(float* __restrict_
 
 }  // namespace
 
+// 128 x 128 tiles when there are at least two per CU and they spread evenly over the 256 CUs
+// (the busiest CU within 15 % of the average); otherwise 64 x 64 tiles, four times as many.
+// Measured at K = 1024: 2048^2 85 -> 96 TFLOP/s, 2560^2 84 -> 92, 1536^2 47 -> 66 with the small tiles.
+int gemm_tile_edge(int32_t M, int32_t N) {
+    const int64_t tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+    const int64_t per_cu = (tiles + 255) / 256;
+    return (tiles >= 512 && tiles * 100 >= per_cu * 256 * 85) ? 128 : 64;
+}
+
 LaunchShape gemm_tile_shape(int32_t M, int32_t N) {
+    const int t = gemm_tile_edge(M, N);
     LaunchShape s{};
-    s.grid[0] = (uint32_t)(((M + TM - 1) / TM) * ((N + TN - 1) / TN)); s.grid[1] = s.grid[2] = 1;
+    s.grid[0] = (uint32_t)(((M + t - 1) / t) * ((N + t - 1) / t)); s.grid[1] = s.grid[2] = 1;
     s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)((2 * TM * LDA + 2 * BK * LDB + 2 * TM) * 4);
-    s.kernel = "gemm_tile128";
+    s.lds_bytes = (uint32_t)((2 * t * LDA + 2 * BK * (t + 8) + 2 * t) * 4);
+    s.kernel = t == 128 ? "gemm_tile128" : "gemm_tile64";
     return s;
 }
 
-int32_t gemm_tile_col_tiles(int32_t N) { return (N + TN - 1) / TN; }
+int32_t gemm_tile_col_tiles(int32_t M, int32_t N) { const int t = gemm_tile_edge(M, N); return (N + t - 1) / t; }
 
-hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream) {
-    const int tiles_m = (p.M + TM - 1) / TM, tiles_n = (p.N + TN - 1) / TN;
+template <int T>
+hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
+    const int tiles_m = (p.M + T - 1) / T, tiles_n = (p.N + T - 1) / T;
     const int items = tiles_m * tiles_n;
     const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
-    if (vec) hipLaunchKernelGGL((gemm_tile128<true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
-    else hipLaunchKernelGGL((gemm_tile128<false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+    if (vec) hipLaunchKernelGGL((gemm_tile<T, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+    else hipLaunchKernelGGL((gemm_tile<T, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
     return hipGetLastError();
+}
+
+hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream) {
+    return gemm_tile_edge(p.M, p.N) == 128 ? launch_tile<128>(p, stream) : launch_tile<64>(p, stream);
 }
 
 hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream) {

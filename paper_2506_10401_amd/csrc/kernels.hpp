@@ -99,9 +99,9 @@ bool gemm_use_tile(int32_t M, int32_t N, int32_t softmax);
 int32_t gemm_col_tiles(int32_t M, int32_t N);
 LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax);
 hipError_t gemm_launch(const GemmParams& p, hipStream_t stream);
-// the 128 x 128-tile kernel and the finishing kernel (k_gemm_tile.hip)
+// the tiled kernel (128 x 128 or 64 x 64 tiles) and the finishing kernels (k_gemm_tile.hip)
 LaunchShape gemm_tile_shape(int32_t M, int32_t N);
-int32_t gemm_tile_col_tiles(int32_t N);
+int32_t gemm_tile_col_tiles(int32_t M, int32_t N);
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream);
 hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream);
 

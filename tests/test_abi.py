@@ -308,6 +308,10 @@ def test_matmul_dropout_mean_softmax_plans():
     # a large GEMM without the dropout chain also takes the tiled kernel; the fused row softmax keeps the 16-row one
     g = H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0,
                   [(2048, 512), (512, 2048), (2048,)], [(2048, 2048)])
+    pg = H.Plan(g)
+    assert pg.kernel_name == "gemm_tile64" and pg.launch_shape()[0] == (32 * 32, 1, 1)   # 256 128-tiles would be one per CU
+    g = H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0,
+                  [(4096, 512), (512, 2048), (2048,)], [(4096, 2048)])
     assert H.Plan(g).kernel_name == "gemm_tile128"
     g = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_SOFTMAX_LAST, 0, [(8192, 64), (64, 256)], [(8192, 256)])
     assert H.Plan(g).kernel_name == "gemm_rows16<256>"

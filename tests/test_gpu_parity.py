@@ -128,11 +128,12 @@ def test_chain6_small_shapes(M, K, N):
     assert name.startswith("gemm_rows16")
 
 
-@pytest.mark.parametrize("M,K,N", [(640, 72, 900), (513, 70, 1027), (1024, 8, 512), (520, 100, 1100), (129, 16, 4100)])
+@pytest.mark.parametrize("M,K,N", [(640, 72, 900), (513, 70, 1027), (1024, 8, 512), (520, 100, 1100), (129, 16, 4100),
+                                   (2100, 40, 4000), (4100, 24, 2052), (4096, 16, 4096)])
 def test_chain6_tiled_shapes(M, K, N):
     print("chain6 tiled M=%d K=%d N=%d" % (M, K, N), flush=True)
     name = check_chain6(datagen.make(6, M=M, K=K, N=N), datagen.CHAIN6_P, datagen.CHAIN6_SEED)
-    assert name == "gemm_tile128"
+    assert name in ("gemm_tile128", "gemm_tile64")
 
 
 @pytest.mark.parametrize("p,seed", [(0.0, 1), (0.5, 0), (0.3, (1 << 64) - 5), (0.999, 77)])
@@ -153,14 +154,14 @@ def test_chain6_full_size_and_determinism():
     assert np.array_equal(got, again)
 
 
-@pytest.mark.parametrize("M,K,N", [(1024, 512, 1024), (700, 260, 644), (515, 37, 1001)])
+@pytest.mark.parametrize("M,K,N", [(1024, 512, 1024), (700, 260, 644), (515, 37, 1001), (3000, 100, 2900), (2900, 33, 3001)])
 def test_tiled_gemm_bias_relu(M, K, N):
     print("tiled gemm M=%d K=%d N=%d" % (M, K, N), flush=True)
     t = datagen.make(1, M=M, K=K, N=N)
     X, W, b = dev(t["X"]), dev(t["W"]), dev(t["bias"])
     out = torch.full((M, N), float("nan"), device="cuda")
     plan, ins = hpct.gemm_bias_relu_softmax_plan(X, W, b, out, relu=True, softmax=False)
-    assert plan.kernel_name == "gemm_tile128"
+    assert plan.kernel_name in ("gemm_tile128", "gemm_tile64")
     plan.launch(ins, [out])
     Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
     assert show("tiled gemm+bias+relu", compare.contraction(host(out), ref.relu(Z), Dn))
