@@ -233,6 +233,8 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
 
     auto compute = [&](int cur) {
+        // waves inside their MFMA block win the issue arbitration over waves that are staging
+        __builtin_amdgcn_s_setprio(1);
         const float* bI = inS(cur) + b_base;
         const float* aW = wS(cur) + a_base;
 #pragma unroll
@@ -259,6 +261,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
                 for (int kb = 0; kb < KB; ++kb) acc[kb] = mfma_32x32x2(a[kb][e], b, acc[kb]);
             }
         }
+        __builtin_amdgcn_s_setprio(0);
     };
 
     if (tid < KT) {  // v = (acc + bias) * scale + shift = acc * mul + add; visible after the first barrier

@@ -120,6 +120,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     auto compute = [&](int buf) {
+        // waves inside their MFMA block win the issue arbitration over waves that are staging
+        __builtin_amdgcn_s_setprio(1);
         const float* a_base = &As[buf][(wm * (TM / 2) + l32) * LDA + 4 * h];
         const float* b_base = &Bs[buf][(4 * h) * LDB + wn * (TN / 2) + l32];
 #pragma unroll
@@ -138,6 +140,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
                     for (int j = 0; j < WB; ++j) acc[i][j] = mfma_32x32x2(a[i][e], b[j], acc[i][j]);
             }
         }
+        __builtin_amdgcn_s_setprio(0);
     };
 
     const int nk = (K + BK - 1) / BK;
