@@ -212,6 +212,19 @@ def main() -> int:
 
     # ---- [Matmul, Dropout, Mean, Softmax] (Section 5.3 case study; outside the step and the headline value)
     next_ops = []
+
+    def timed(call, launches):
+        """avg us per launch over `launches` launches after the same warm-up the five chains get"""
+        for _ in range(args.warmup):
+            call()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(launches):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+        return 1e3 * a.elapsed_time(b) / launches
+
     if not args.only:
         t6 = {k: dev(v) for k, v in datagen.make(6).items()}
         M6, K6 = t6["X"].shape
@@ -221,21 +234,13 @@ def main() -> int:
                                                             datagen.CHAIN6_SEED)
         ws6 = torch.empty(max(1, plan6.workspace_bytes // 4), device="cuda")
         call6 = plan6.bind(ins6, [out6], workspace=ws6)
-        n6 = max(1, args.steps // 4)
-        for _ in range(min(args.warmup, 5)):
-            call6()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(n6):
-            call6()
-        e1.record()
-        torch.cuda.synchronize()
-        us = 1e3 * e0.elapsed_time(e1) / n6
+        n6 = max(1, args.steps // 2)
+        us = timed(call6, n6)
         flop6 = 2.0 * M6 * K6 * N6
         next_ops.append(dict(op="matmul_dropout_mean_softmax_%dx%dx%d" % (M6, K6, N6), kernel=plan6.kernel_name,
                              launches=n6, avg_us=round(us, 3), achieved=round(flop6 / us / 1e6, 2), unit="TFLOP/s",
                              peak=MFMA_F32_PEAK_TFLOPS, frac=round(flop6 / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4),
-                             note="both kernels of the chain (GEMM with fused dropout and row sums, then mean + softmax over rows)"))
+                             note="all three kernels of the chain (GEMM with fused dropout and row sums, row means, softmax over rows)"))
         del t6, out6, ws6
 
         # VGG-style block: conv3x3 + bias + scale/shift + relu + 2x2 max pool at the shape of chain 4
@@ -245,21 +250,13 @@ def main() -> int:
         out7 = torch.empty(Nb7, K7, H7 // 2, W7 // 2, device="cuda")
         plan7, ins7 = hpct.conv_block_plan(t7["in"], t7["wt"], t7["bias"], t7["scale"], t7["shift"], out7)
         call7 = plan7.bind(ins7, [out7])
-        for _ in range(min(args.warmup, 10)):
-            call7()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            call7()
-        e1.record()
-        torch.cuda.synchronize()
-        us = 1e3 * e0.elapsed_time(e1) / args.steps
+        us = timed(call7, args.steps)
         flop7 = 2.0 * Nb7 * K7 * H7 * W7 * C7 * 9
         next_ops.append(dict(op="conv3x3_bias_scale_shift_relu_maxpool2_%dx%dx%dx%d_to_%d" % (Nb7, C7, H7, W7, K7),
                              kernel=plan7.kernel_name, launches=args.steps, avg_us=round(us, 3),
                              achieved=round(flop7 / us / 1e6, 2), unit="TFLOP/s", peak=MFMA_F32_PEAK_TFLOPS,
                              frac=round(flop7 / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4),
-                             note="flop = the convolution's 2*N*K*Ho*Wo*C*R*S; tiles are 2 rows x 32 columns, so 56-wide rows use 56/64 of the MFMA work"))
+                             note="flop = the convolution's 2*N*K*Ho*Wo*C*R*S; the pooled output is a quarter of the conv output"))
         del t7, out7
 
         # causal attention at the shape of chain 5 (flop = only the visible (query, key) pairs)
@@ -268,15 +265,7 @@ def main() -> int:
             o5 = torch.empty_like(q5)
             plan5, ins5 = hpct.attention_plan(q5, k5, v5, o5, 0.125, causal=True)
             call5 = plan5.bind(ins5, [o5])
-            for _ in range(min(args.warmup, 10)):
-                call5()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(args.steps):
-                call5()
-            e1.record()
-            torch.cuda.synchronize()
-            us = 1e3 * e0.elapsed_time(e1) / args.steps
+            us = timed(call5, args.steps)
             B5, L5, D5 = q5.shape
             flop5 = 4.0 * D5 * B5 * L5 * (L5 + 1) / 2
             next_ops.append(dict(op="causal_attention_%dx%dx%d" % (B5, L5, D5), kernel=plan5.kernel_name, launches=args.steps,
