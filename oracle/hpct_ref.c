@@ -142,14 +142,17 @@ void ref_gelu_tanh(double *Y, int64_t count)
  * ih = h*stride - P + kh, iw = w*stride - P + kw and the zero-padding bounds
  * test are those of the listing before it; output index
  * ((n*K + k)*Ho + h)*Wo + w.  Cross-correlation (no kernel flip).  Weights
- * are [K][C][R][S] contiguous.  Output size (H + 2P - R)/stride + 1.
+ * are [K][C][R][S] contiguous.  With dilation `dil` (1 = the paper's case) tap
+ * kh sits dil rows further each: ih = h*stride - P + kh*dil, likewise iw; the
+ * filter then spans (R-1)*dil + 1 rows and the output size is
+ * (H + 2P - (R-1)*dil - 1)/stride + 1.
  * Dn (may be NULL) = |bias| + sum |in| |wt| over the taps inside the image. */
 void ref_conv2d_nchw_bias(const float *in, const float *wt, const float *bias,
                           int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t K,
-                          int64_t R, int64_t S, int64_t stride, int64_t P,
+                          int64_t R, int64_t S, int64_t stride, int64_t P, int64_t dil,
                           double *out, double *Dn)
 {
-    const int64_t Ho = (H + 2 * P - R) / stride + 1, Wo = (W + 2 * P - S) / stride + 1;
+    const int64_t Ho = (H + 2 * P - (R - 1) * dil - 1) / stride + 1, Wo = (W + 2 * P - (S - 1) * dil - 1) / stride + 1;
 #pragma omp parallel for schedule(static) collapse(2)
     for (int64_t n = 0; n < Nb; ++n) {
         for (int64_t k = 0; k < K; ++k) {
@@ -160,8 +163,8 @@ void ref_conv2d_nchw_bias(const float *in, const float *wt, const float *bias,
                     for (int64_t c = 0; c < C; ++c) {
                         for (int64_t kh = 0; kh < R; ++kh) {
                             for (int64_t kw = 0; kw < S; ++kw) {
-                                int64_t ih = h * stride - P + kh;
-                                int64_t iw = w * stride - P + kw;
+                                int64_t ih = h * stride - P + kh * dil;
+                                int64_t iw = w * stride - P + kw * dil;
                                 if (ih >= 0 && ih < H && iw >= 0 && iw < W) {
                                     double a = (double)in[((n * C + c) * H + ih) * W + iw];
                                     double g = (double)wt[((k * C + c) * R + kh) * S + kw];

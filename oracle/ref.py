@@ -32,7 +32,7 @@ def lib():
             "ref_avgpool_planes": [p, i64, i64, p],
             "ref_layernorm_rows": [p, p, p, i64, i64, dbl, p],
             "ref_gelu_tanh": [p, i64],
-            "ref_conv2d_nchw_bias": [p, p, p] + [i64] * 9 + [p, p],
+            "ref_conv2d_nchw_bias": [p, p, p] + [i64] * 10 + [p, p],
             "ref_attention": [p, p, p, i64, i64, i64, i64, dbl, p, p],
             "ref_attention_causal": [p, p, p, i64, i64, i64, i64, dbl, p, p],
             "ref_layout_copy": [p, C.c_int32, p, p, p],
@@ -130,20 +130,20 @@ def gelu_tanh(Y):
     return Y
 
 
-def conv_out_hw(H, W, R, S, stride, pad):
-    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+def conv_out_hw(H, W, R, S, stride, pad, dil=1):
+    return (H + 2 * pad - (R - 1) * dil - 1) // stride + 1, (W + 2 * pad - (S - 1) * dil - 1) // stride + 1
 
 
-def conv2d_nchw_bias(inp, wt, bias=None, stride=1, pad=1, want_norm=False):
+def conv2d_nchw_bias(inp, wt, bias=None, stride=1, pad=1, want_norm=False, dil=1):
     inp, wt = _f32(inp), _f32(wt)
     Nb, Cc, H, W = inp.shape
     K, C2, R, S = wt.shape
     assert Cc == C2
     b = None if bias is None else _f32(bias)
-    Ho, Wo = conv_out_hw(H, W, R, S, stride, pad)
+    Ho, Wo = conv_out_hw(H, W, R, S, stride, pad, dil)
     out = np.empty((Nb, K, Ho, Wo), dtype=np.float64)
     Dn = np.empty_like(out) if want_norm else None
-    lib().ref_conv2d_nchw_bias(_ptr(inp), _ptr(wt), _ptr(b), Nb, Cc, H, W, K, R, S, stride, pad,
+    lib().ref_conv2d_nchw_bias(_ptr(inp), _ptr(wt), _ptr(b), Nb, Cc, H, W, K, R, S, stride, pad, dil,
                                _ptr(out), _ptr(Dn))
     return (out, Dn) if want_norm else out
 
@@ -282,10 +282,10 @@ def chain6(X, W, bias, p, seed, stop_after="softmax"):
     return softmax_rows(mu.reshape(1, -1)).reshape(-1)
 
 
-def chain7(inp, wt, bias, scale, shift, stride=1, pad=1, relu_=True, pool=True):
+def chain7(inp, wt, bias, scale, shift, stride=1, pad=1, relu_=True, pool=True, dil=1):
     """VGG-style block: maxpool2x2(relu((conv2d(inp, wt) + bias) * scale[k] + shift[k])) and the
     contraction normaliser of the conv output scaled by |scale[k]| (before pooling)."""
-    out, Dn = conv2d_nchw_bias(inp, wt, bias, stride, pad, want_norm=True)
+    out, Dn = conv2d_nchw_bias(inp, wt, bias, stride, pad, want_norm=True, dil=dil)
     if scale is not None or shift is not None:
         out = scale_shift_ch(out, scale, shift)
         Dn = scale_shift_ch(Dn, None if scale is None else np.abs(_f32(scale)), None if shift is None else np.abs(_f32(shift)))

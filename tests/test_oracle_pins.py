@@ -701,3 +701,30 @@ def test_causal_attention_closed_forms_and_dense_witness():
     # a future key cannot matter: changing K, V beyond the diagonal leaves earlier rows untouched
     K2, V2 = K.copy(), V.copy(); K2[:, 6:] += 3.0; V2[:, 6:] -= 5.0
     assert np.array_equal(ref.attention(Q, K2, V2, 0.5, causal=True)[:, :6], O[:, :6])
+
+
+# ------------------------------------------------------------- dilated conv
+def test_dilated_conv_brute_force_and_tap_positions():
+    for (H, W, R, stride, pad, dil) in [(9, 11, 3, 1, 2, 2), (12, 10, 3, 2, 3, 3), (7, 7, 1, 1, 0, 4), (15, 13, 5, 1, 4, 2)]:
+        Nb, C, K = 2, 3, 4
+        x = f32(rng.normal(size=(Nb, C, H, W))); w = f32(rng.normal(size=(K, C, R, R))); b = f32(rng.normal(size=K))
+        got = ref.conv2d_nchw_bias(x, w, b, stride, pad, dil=dil)
+        Re = (R - 1) * dil + 1
+        Ho, Wo = (H + 2 * pad - Re) // stride + 1, (W + 2 * pad - Re) // stride + 1
+        assert got.shape == (Nb, K, Ho, Wo)
+        xp = np.zeros((Nb, C, H + 2 * pad, W + 2 * pad)); xp[:, :, pad:pad + H, pad:pad + W] = x
+        want = np.zeros((Nb, K, Ho, Wo))
+        for kh in range(R):
+            for kw in range(R):
+                patch = xp[:, :, kh * dil:kh * dil + (Ho - 1) * stride + 1:stride, kw * dil:kw * dil + (Wo - 1) * stride + 1:stride]
+                want += np.einsum("nchw,kc->nkhw", patch, w[:, :, kh, kw].astype(np.float64))
+        want += b.astype(np.float64)[None, :, None, None]
+        assert np.allclose(got, want, rtol=0, atol=1e-12)
+    # a filter that is 1 at tap (0, 2) only shifts the image by (-P, 2*dil - P)
+    x = f32(rng.normal(size=(1, 1, 8, 8))); w = np.zeros((1, 1, 3, 3), np.float32); w[0, 0, 0, 2] = 1.0
+    out = ref.conv2d_nchw_bias(x, w, None, 1, 2, dil=2)      # Re = 5, pad 2: same size
+    assert out.shape == (1, 1, 8, 8)
+    assert np.array_equal(out[0, 0, 2:, :6], x[0, 0, :6, 2:].astype(np.float64))
+    # dil = 1 is the undilated operator
+    w3 = f32(rng.normal(size=(2, 1, 3, 3)))
+    assert np.array_equal(ref.conv2d_nchw_bias(x, w3, None, 1, 1, dil=1), ref.conv2d_nchw_bias(x, w3, None, 1, 1))
