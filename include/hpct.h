@@ -47,8 +47,9 @@
  *                                                                                   int32 for the arg ops
  *   CONV2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH] [+RELU] in[N,C,H,W], wt[K,C,R,S],     [N,K,Ho,Wo], or
  *         then MAXPOOL2_HW or no reduction            bias[K], scale[K], shift[K]   [N,K,Ho/2,Wo/2]
- *         (square 1/3/5/7 filter, stride <= 4,                                       with MAXPOOL2_HW
- *         Ho = (H + 2 pad - R) / stride + 1)
+ *         (square 1/3/5/7 filter, stride and                                         with MAXPOOL2_HW
+ *         dilation <= 4, Ho = (H + 2 pad -
+ *         (R-1) dilation - 1) / stride + 1)
  *   BGEMM_SOFTMAX_BGEMM [+SCALE_CONST: scores scaled  Q[B,L,D], K[B,Lk,D],          [B,L,D]
  *         by `scale`] [+CAUSAL_MASK] (D = 32, 64, 128) V[B,Lk,D]
  */
@@ -148,6 +149,7 @@ typedef struct {
                                      after MEAN_LAST (softmax over the M row means), else HPCT_RED_NONE */
     uint64_t dropout_seed;        /* DROPOUT_HASH */
     int32_t axis;                 /* *_AXIS reductions: the dimension of in[0] that is reduced, 0 <= axis < ndim */
+    int32_t dilation_hw[2];       /* conv only: tap kh reads input row h*stride - pad + kh*dilation; 0 means 1 */
 } hpct_op_desc;
 
 typedef struct hpct_plan hpct_plan;   /* opaque; host memory */

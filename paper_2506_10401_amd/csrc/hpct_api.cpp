@@ -363,8 +363,12 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
     if (Wt.shape[1] != C) return fail(HPCT_ERR_SHAPE_MISMATCH, "wt.shape[1] = %lld does not match the input channels %lld", (long long)Wt.shape[1], (long long)C);
     if (d.stride_hw[0] < 1 || d.stride_hw[1] < 1 || d.pad_hw[0] < 0 || d.pad_hw[1] < 0)
         return fail(HPCT_ERR_BAD_DESC, "conv: stride must be >= 1 and padding >= 0");
-    if (H + 2 * d.pad_hw[0] < R || W + 2 * d.pad_hw[1] < S) return fail(HPCT_ERR_SHAPE_MISMATCH, "conv: filter larger than the padded input");
-    const int64_t Ho = (H + 2 * d.pad_hw[0] - R) / d.stride_hw[0] + 1, Wo = (W + 2 * d.pad_hw[1] - S) / d.stride_hw[1] + 1;
+    // dilation 0 (a zero-initialised descriptor) means 1
+    const int32_t dil_h = d.dilation_hw[0] == 0 ? 1 : d.dilation_hw[0], dil_w = d.dilation_hw[1] == 0 ? 1 : d.dilation_hw[1];
+    if (dil_h < 1 || dil_w < 1) return fail(HPCT_ERR_BAD_DESC, "conv: dilation must be >= 1 (or 0 for 1)");
+    const int64_t Re = (R - 1) * dil_h + 1, Se = (S - 1) * dil_w + 1;
+    if (H + 2 * d.pad_hw[0] < Re || W + 2 * d.pad_hw[1] < Se) return fail(HPCT_ERR_SHAPE_MISMATCH, "conv: filter larger than the padded input");
+    const int64_t Ho = (H + 2 * d.pad_hw[0] - Re) / d.stride_hw[0] + 1, Wo = (W + 2 * d.pad_hw[1] - Se) / d.stride_hw[1] + 1;
     int s = 2;
     int s_bias = -1, s_scale = -1, s_shift = -1;
     if (has[0]) { s_bias = s++; REQUIRE_SHAPE(d.in[s_bias], "bias", K); }
@@ -386,11 +390,11 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
         return fail(HPCT_ERR_UNSUPPORTED, "conv: operand larger than 2^31-1 elements");
     const char* why = "";
     if (!conv_supported((int32_t)C, (int32_t)H, (int32_t)W, (int32_t)K, (int32_t)R, (int32_t)S, d.stride_hw[0], d.stride_hw[1],
-                        d.pad_hw[0], d.pad_hw[1], pool ? 1 : 0, &why))
+                        d.pad_hw[0], d.pad_hw[1], dil_h, dil_w, pool ? 1 : 0, &why))
         return fail(HPCT_ERR_UNSUPPORTED, "conv: %s", why);
     ConvParams q{};
     q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)H; q.W = (int32_t)W; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
-    q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.relu = has[2] ? 1 : 0; q.pool = pool ? 1 : 0;
+    q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.dil = dil_h; q.relu = has[2] ? 1 : 0; q.pool = pool ? 1 : 0;
     p.kind = Kind::Conv;
     p.u.conv = q;
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = s_bias; p.slot[3] = s_scale; p.slot[4] = s_shift; p.slot[5] = -1;

@@ -1,5 +1,5 @@
-// NCHW conv2d (cross-correlation, zero padding, square filter 1/3/5/7, any
-// stride) with its epilogue held in registers - bias, per-channel scale/shift
+// NCHW conv2d (cross-correlation, zero padding, square filter 1/3/5/7, stride
+// and dilation up to 4) with its epilogue held in registers - bias, per-channel scale/shift
 // (a folded batch-norm), ReLU and optionally the 2x2 max pooling that closes a
 // VGG block: the convolution of the paper's VGG-16 case study (Section 5.3;
 // Table 1 "conv"; "Conv2d BN" of Section 5.2).  Implicit GEMM on
@@ -46,6 +46,7 @@ constexpr int kXcds = 8; // work-groups are dealt round-robin to this many L2 do
 struct ConvGeom {
     int Nb, C, H, W, K, P;
     int St;        // stride
+    int Dl;        // dilation
     int Ho, Wo, HoWo;
     int Hp, Wp;    // pooled output size (POOL)
     int ctiles;    // 8-column tiles per 8-row band (POOL)
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         if (!p_ok) p = g.HoWo - 1;    // clamp: reads stay inside the staged rows, the store is masked
         oh = p / g.Wo; ow = p - oh * g.Wo;
     }
-    // input element of (chunk channel c, tap kh,kw): c*ch_ld + ((oh-h_lo)*St+kh)*ldw + (ow-w_lo)*St + kw + lpad
+    // input element of (chunk channel c, tap kh,kw): c*ch_ld + ((oh-h_lo)*St+kh*Dl)*ldw + (ow-w_lo)*St + kw*Dl + lpad
     const int b_base = half * (CC / 2) * g.ch_ld + (oh - h_lo) * g.St * g.ldw + (ow - w_lo) * g.St + g.lpad;
     const int a_base = (kb0 + l32) * WLD + half * HALF;
 
@@ -232,6 +233,9 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
 
+    // the pipelined variant is built for dilation 1 only, so that its tap offsets stay compile-time
+    // immediates of the LDS reads (a run-time dilation costs 4.5 % there); dilated convs take the general one
+    const int dl = FAST ? 1 : g.Dl;
     auto compute = [&](int cur) {
         // waves inside their MFMA block win the issue arbitration over waves that are staging
         __builtin_amdgcn_s_setprio(1);
@@ -256,7 +260,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
             for (int e = 0; e < VW; ++e) {
                 const int s = VW * j + e;  // MFMA step inside the chunk
                 const int c = s / TAPS, tap = s % TAPS;
-                const float b = bI[c * g.ch_ld + (tap / R) * g.ldw + (tap % R)];
+                const float b = bI[c * g.ch_ld + (tap / R) * dl * g.ldw + (tap % R) * dl];
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) acc[kb] = mfma_32x32x2(a[kb][e], b, acc[kb]);
             }
@@ -337,23 +341,24 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
 
 ConvGeom geom(const ConvParams& p) {
     ConvGeom g{};
-    g.Nb = p.Nb; g.C = p.C; g.H = p.H; g.W = p.W; g.K = p.K; g.P = p.pad; g.St = p.stride;
-    g.Ho = (p.H + 2 * p.pad - p.R) / p.stride + 1;
-    g.Wo = (p.W + 2 * p.pad - p.S) / p.stride + 1;
+    g.Nb = p.Nb; g.C = p.C; g.H = p.H; g.W = p.W; g.K = p.K; g.P = p.pad; g.St = p.stride; g.Dl = p.dil;
+    const int re = (p.R - 1) * p.dil + 1;   // rows / columns the dilated filter spans
+    g.Ho = (p.H + 2 * p.pad - re) / p.stride + 1;
+    g.Wo = (p.W + 2 * p.pad - re) / p.stride + 1;
     g.HoWo = g.Ho * g.Wo;
     g.lpad = (4 - p.pad % 4) % 4;
     if (p.pool) {
         g.Hp = g.Ho / 2; g.Wp = g.Wo / 2;
         g.ctiles = (2 * g.Wp + 7) / 8;
         g.tiles_per_img = ((2 * g.Hp + 7) / 8) * g.ctiles;
-        g.rows_max = 7 * p.stride + p.R;                                   // eight output rows
-        g.ldw = (7 * p.stride + p.S + g.lpad + 3) & ~3;                    // eight output columns
+        g.rows_max = 7 * p.stride + re;                                    // eight output rows
+        g.ldw = (7 * p.stride + re + g.lpad + 3) & ~3;                     // eight output columns
     } else {
         g.tiles_per_img = (g.HoWo + TP - 1) / TP;
         // a run of TP consecutive pixels touches at most (TP-1)/Wo + 2 output rows
         int out_rows = (TP - 1) / g.Wo + 2;
         if (out_rows > g.Ho) out_rows = g.Ho;
-        g.rows_max = (out_rows - 1) * p.stride + p.R;
+        g.rows_max = (out_rows - 1) * p.stride + re;
         g.ldw = (p.W + 2 * p.pad + g.lpad + 3) & ~3;
     }
     g.tiles = p.Nb * g.tiles_per_img;
@@ -380,7 +385,7 @@ constexpr int kKT = 64;
 
 template <int R>
 bool fast_ok(const ConvParams& p, const ConvGeom& g) {
-    return p.W % 4 == 0 && p.C % kCC == 0 && p.K % kKT == 0 &&
+    return p.dil == 1 && p.W % 4 == 0 && p.C % kCC == 0 && p.K % kKT == 0 &&
            kCC * g.rows_max * (g.ldw / 4) <= 256 * Cfg<R, kCC, kKT>::IN_PER_T;
 }
 
@@ -427,14 +432,16 @@ hipError_t launch_pool(const ConvParams& p, const ConvGeom& g, hipStream_t strea
 }  // namespace
 
 bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h, int32_t stride_w,
-                    int32_t pad_h, int32_t pad_w, int32_t pool, const char** why) {
+                    int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w, int32_t pool, const char** why) {
+    if (dil_h != dil_w) { *why = "the dilation must be the same in both directions"; return false; }
+    if (dil_h < 1 || dil_h > 4) { *why = "dilations outside 1..4 are not supported"; return false; }
     if (stride_h != stride_w) { *why = "the stride must be the same in both directions"; return false; }
     if (stride_h > 4) { *why = "strides above 4 are not supported"; return false; }
     if (R != S || (R != 1 && R != 3 && R != 5 && R != 7)) { *why = "only square 1x1, 3x3, 5x5 and 7x7 filters are supported"; return false; }
     if (pad_h != pad_w) { *why = "padding must be the same in both directions"; return false; }
-    if (pad_h > R - 1) { *why = "padding larger than the filter extent minus one"; return false; }
+    if (pad_h > (R - 1) * dil_h) { *why = "padding larger than the (dilated) filter extent minus one"; return false; }
     ConvParams p{};
-    p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.pool = pool;
+    p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.dil = dil_h; p.pool = pool;
     if (lds_any(p) > 160 * 1024) { *why = "the input of one 64-pixel tile does not fit in LDS (image too wide)"; return false; }
     return true;
 }

@@ -105,7 +105,7 @@ int32_t gemm_tile_col_tiles(int32_t M, int32_t N);
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream);
 hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream);
 
-// ---- NCHW conv2d (square 1/3/5/7 filter, any stride up to 4) + bias + per-channel
+// ---- NCHW conv2d (square 1/3/5/7 filter, stride and dilation up to 4) + bias + per-channel
 //      scale/shift + relu, optionally followed by 2x2 / stride-2 max pooling
 struct ConvParams {
     const float* in; const float* wt; const float* bias; float* out;
@@ -113,9 +113,11 @@ struct ConvParams {
     int32_t stride;
     const float* scale; const float* shift;   // per output channel, either may be null
     int32_t pool;                             // out is [Nb, K, Ho/2, Wo/2]
+    int32_t dil;                              // dilation, >= 1
 };
 bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h,
-                    int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t pool, const char** why);
+                    int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w, int32_t pool,
+                    const char** why);
 LaunchShape conv_shape(const ConvParams& p);
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream);
 

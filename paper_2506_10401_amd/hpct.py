@@ -39,7 +39,7 @@ class OpDesc(C.Structure):
                 ("reduce_before_epi", C.c_int32), ("n_in", C.c_int32), ("in_", TensorDesc * HPCT_MAX_IN),
                 ("n_out", C.c_int32), ("out", TensorDesc * HPCT_MAX_OUT), ("stride_hw", C.c_int32 * 2),
                 ("pad_hw", C.c_int32 * 2), ("eps", C.c_float), ("scale", C.c_float), ("dropout_p", C.c_float),
-                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64), ("axis", C.c_int32)]
+                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64), ("axis", C.c_int32), ("dilation_hw", C.c_int32 * 2)]
 
 
 class HpctError(RuntimeError):
@@ -112,7 +112,7 @@ def tensor_desc(shape: Sequence[int], stride: Optional[Sequence[int]] = None, dt
 
 def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before_epi=0, inputs=(), outputs=(),
             stride_hw=(1, 1), pad_hw=(0, 0), eps=0.0, scale=1.0, dropout_p=0.0, dropout_seed=0,
-            reduce2=HPCT_RED_NONE, axis=0) -> OpDesc:
+            reduce2=HPCT_RED_NONE, axis=0, dilation_hw=(1, 1)) -> OpDesc:
     d = OpDesc()
     d.anchor = anchor
     d.n_epi = len(epi)
@@ -134,6 +134,7 @@ def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before
     d.dropout_seed = int(dropout_seed) & 0xFFFFFFFFFFFFFFFF
     d.reduce2 = reduce2
     d.axis = axis
+    d.dilation_hw[0], d.dilation_hw[1] = dilation_hw
     return d
 
 
@@ -356,21 +357,21 @@ def conv2d_bias_relu(inp, wt, bias, out, stride=1, pad=1, relu=True, stream=None
     plan.launch(ins, [out], stream)
 
 
-def conv_block_plan(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True):
+def conv_block_plan(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True, dilation=1):
     """Plan of conv2d [+bias] [+per-channel scale/shift] [+relu] [+2x2 max pool] (a VGG-style block)."""
     assert (scale is None) == (shift is None)
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + \
         ([HPCT_EPI_RELU] if relu else [])
     ins = [inp, wt] + ([bias] if bias is not None else []) + ([scale, shift] if scale is not None else [])
-    plan = _cached(("convblock", _sh(inp), _sh(wt), tuple(epi), stride, pad, pool), lambda: op_desc(
+    plan = _cached(("convblock", _sh(inp), _sh(wt), tuple(epi), stride, pad, pool, dilation), lambda: op_desc(
         HPCT_ANCHOR_CONV2D_NCHW, epi, HPCT_RED_MAXPOOL2_HW if pool else HPCT_RED_NONE, 0, [_sh(t) for t in ins], [_sh(out)],
-        stride_hw=(stride, stride), pad_hw=(pad, pad)))
+        stride_hw=(stride, stride), pad_hw=(pad, pad), dilation_hw=(dilation, dilation)))
     return plan, ins
 
 
-def conv_block(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True, stream=None) -> None:
+def conv_block(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True, dilation=1, stream=None) -> None:
     """out = maxpool2x2(relu((conv2d_nchw(inp, wt) + bias[k]) * scale[k] + shift[k])); every stage after the conv optional."""
-    plan, ins = conv_block_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, pool)
+    plan, ins = conv_block_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, pool, dilation)
     plan.launch(ins, [out], stream)
 
 

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_the_c_layout():
     # int32 + pad + 6*int64 + 6*int64 + enum + pad
     assert C.sizeof(H.TensorDesc) == 112
-    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4 + 4 + 4 + 8 + 4 + 4
+    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4 + 4 + 4 + 8 + 4 + 8 + 4
     # and the library reports the same sizes for the structs it was compiled with
     lib = H.load()
     assert lib.hpct_sizeof_tensor_desc() == C.sizeof(H.TensorDesc)
@@ -361,13 +361,14 @@ def test_workspace_checks_return_before_any_launch():
     assert e.value.status == H.HPCT_ERR_BAD_DESC
 
 
-def conv_block_desc(pool=True, stride=1, R=3, pad=1, shape=(32, 64, 56, 56), K=128):
+def conv_block_desc(pool=True, stride=1, R=3, pad=1, shape=(32, 64, 56, 56), K=128, dil=1):
     Nb, Cc, Hh, Ww = shape
-    Ho, Wo = (Hh + 2 * pad - R) // stride + 1, (Ww + 2 * pad - R) // stride + 1
+    Re = (R - 1) * dil + 1
+    Ho, Wo = (Hh + 2 * pad - Re) // stride + 1, (Ww + 2 * pad - Re) // stride + 1
     return H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SCALE_SHIFT_CH, H.HPCT_EPI_RELU],
                      H.HPCT_RED_MAXPOOL2_HW if pool else H.HPCT_RED_NONE, 0,
                      [shape, (K, Cc, R, R), (K,), (K,), (K,)], [(Nb, K, Ho // 2, Wo // 2) if pool else (Nb, K, Ho, Wo)],
-                     stride_hw=(stride, stride), pad_hw=(pad, pad))
+                     stride_hw=(stride, stride), pad_hw=(pad, pad), dilation_hw=(dil, dil))
 
 
 def test_conv_block_plans():
@@ -382,6 +383,16 @@ def test_conv_block_plans():
         "conv2d_nchw_mfma<7x7,general>"
     assert H.Plan(conv_block_desc(R=5, pad=2, shape=(2, 8, 30, 30), K=16)).kernel_name == "conv2d_nchw_mfma<5x5,general,maxpool2>"
     assert H.Plan(conv_block_desc(R=1, pad=0)).kernel_name == "conv2d_nchw_mfma<1x1,pipelined,maxpool2>"
+    # dilation: the filter spans (R-1)*dil + 1 rows; 0 in the descriptor means 1
+    assert H.Plan(conv_block_desc(pool=False, dil=2, pad=2)).kernel_name == "conv2d_nchw_mfma<3x3,general>"
+    d = conv_block_desc(); d.dilation_hw[0] = d.dilation_hw[1] = 0
+    assert H.Plan(d).kernel_name == "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"
+    d = conv_block_desc(pool=False, dil=2, pad=2); d.dilation_hw[1] = 1
+    d.out[0] = H.tensor_desc((32, 128, 56, 58))
+    expect(H.HPCT_ERR_UNSUPPORTED, d)                                         # anisotropic dilation
+    expect(H.HPCT_ERR_UNSUPPORTED, conv_block_desc(pool=False, dil=5, pad=5))
+    d = conv_block_desc(); d.dilation_hw[0] = -1
+    expect(H.HPCT_ERR_BAD_DESC, d)
     # errors
     d = conv_block_desc(); d.out[0] = H.tensor_desc((32, 128, 56, 56))        # pooled output is half the size
     expect(H.HPCT_ERR_SHAPE_MISMATCH, d)

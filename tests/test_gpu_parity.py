@@ -299,25 +299,25 @@ def test_conv_all_ones_counts_taps_exactly():
 
 
 # ----------------------------- conv block: stride, scale/shift, 2x2 max pool (VGG-style)
-def run_chain7(t, stride=1, pad=1, relu=True, pool=True, bias=True, affine=True):
+def run_chain7(t, stride=1, pad=1, relu=True, pool=True, bias=True, affine=True, dil=1):
     x, w = dev(t["in"]), dev(t["wt"])
     b = dev(t["bias"]) if bias else None
     sc, sh = (dev(t["scale"]), dev(t["shift"])) if affine else (None, None)
     Nb, _, H, W = t["in"].shape
     K, _, R, S = t["wt"].shape
-    Ho, Wo = ref.conv_out_hw(H, W, R, S, stride, pad)
+    Ho, Wo = ref.conv_out_hw(H, W, R, S, stride, pad, dil)
     out = torch.full((Nb, K, Ho // 2, Wo // 2) if pool else (Nb, K, Ho, Wo), float("nan"), device="cuda")
-    plan, ins = hpct.conv_block_plan(x, w, b, sc, sh, out, stride, pad, relu, pool)
+    plan, ins = hpct.conv_block_plan(x, w, b, sc, sh, out, stride, pad, relu, pool, dil)
     plan.launch(ins, [out])
     return host(out), plan.kernel_name
 
 
-def check_chain7(t, stride=1, pad=1, relu=True, pool=True, bias=True, affine=True):
+def check_chain7(t, stride=1, pad=1, relu=True, pool=True, bias=True, affine=True, dil=1):
     want, Dn = ref.chain7(t["in"], t["wt"], t["bias"] if bias else None, t["scale"] if affine else None,
-                          t["shift"] if affine else None, stride, pad, relu, pool)
+                          t["shift"] if affine else None, stride, pad, relu, pool, dil)
     if pool:   # |max a - max b| <= max |a_i - b_i|: the window's largest bound
         Dn = ref.maxpool2x2(Dn)
-    got, name = run_chain7(t, stride, pad, relu, pool, bias, affine)
+    got, name = run_chain7(t, stride, pad, relu, pool, bias, affine, dil)
     print("kernel", name, flush=True)
     assert show("conv block", compare.contraction(got, want, Dn))
     return got, name
@@ -346,6 +346,17 @@ def test_chain7_ragged_shapes(N, C, H, W, K, R, stride, pad):
     check_chain7(t, stride, pad, pool=False)           # conv + bias + scale/shift + relu
     check_chain7(t, stride, pad, relu=False)           # pooling sees negative values
     check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False)   # the bare strided conv
+
+
+@pytest.mark.parametrize("N,C,H,W,K,R,stride,pad,dil", [
+    (1, 4, 12, 12, 64, 3, 1, 2, 2), (2, 5, 17, 23, 9, 3, 1, 0, 2), (1, 8, 20, 20, 64, 3, 2, 3, 3), (1, 3, 30, 30, 8, 5, 1, 4, 2),
+    (1, 16, 16, 16, 64, 1, 1, 0, 3), (1, 8, 33, 40, 70, 3, 1, 4, 4), (2, 64, 28, 28, 64, 3, 1, 2, 2)])
+def test_chain7_dilated(N, C, H, W, K, R, stride, pad, dil):
+    print("chain7 dilated %s" % ((N, C, H, W, K, R, stride, pad, dil),), flush=True)
+    t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=R, S=R)
+    check_chain7(t, stride, pad, dil=dil)
+    check_chain7(t, stride, pad, pool=False, dil=dil)
+    check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False, dil=dil)
 
 
 def test_chain7_pool_takes_the_maximum_not_a_sum_or_a_corner():
