@@ -8,8 +8,9 @@
  * "reshape, transpose"; fused examples
  * of its Section 5.3) with an op descriptor; the library validates it, picks a
  * hand-written HIP kernel and enqueues it on the caller's stream: one kernel per
- * launch, two or three for the plans that report a workspace (the later ones finish
- * a reduction from the partial results the first left there).
+ * launch; two or three for the plans that report a workspace (the later ones finish
+ * a reduction from the partial results the first left there) and two for a GEMM whose
+ * softmax rows are wider than one work-group.
  *
  * Conventions
  *  - All tensors are fp32 (the index output of an arg-reduction is int32), described by
@@ -30,7 +31,8 @@
  *
  *   chain                                             in[]                          out[0]
  *   GEMM [+BIAS_COL] [+RELU] [+DROPOUT_HASH]          X[M,K], W[K,N], bias[N]       [M,N]
- *         [+SOFTMAX_LAST (N <= 256)]
+ *         [+SOFTMAX_LAST] (one kernel for N <= 256,
+ *         GEMM then an in-place row softmax beyond)
  *   GEMM [+BIAS_COL] [+RELU] [+DROPOUT_HASH]          X[M,K], W[K,N], bias[N]       [M]
  *         MEAN_LAST [then reduce2 = SOFTMAX_LAST                                     (needs the
  *         over the M means]                                                          workspace)

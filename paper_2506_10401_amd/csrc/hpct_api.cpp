@@ -150,7 +150,6 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     if (M > kI32Max || K > kI32Max || N > kI32Max || M * N > kI32Max || M * K > kI32Max || K * N > kI32Max)
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM: operand larger than 2^31-1 elements");
     const bool sm = d.reduce == HPCT_RED_SOFTMAX_LAST;
-    if (sm && N > kGemmSoftmaxMaxN) return fail(HPCT_ERR_UNSUPPORTED, "GEMM + SOFTMAX_LAST: N = %lld exceeds the fused limit %d", (long long)N, kGemmSoftmaxMaxN);
     GemmParams g{};
     g.M = (int32_t)M; g.K = (int32_t)K; g.N = (int32_t)N;
     g.relu = has[1] ? 1 : 0; g.softmax = sm ? 1 : 0;

@@ -271,7 +271,7 @@ hipError_t launch_bn(const GemmParams& p, hipStream_t stream) {
 // that the 16-row kernel's many small work-groups finish sooner.  The fused row
 // softmax exists only in the 16-row kernel.
 bool gemm_use_tile(int32_t M, int32_t N, int32_t softmax) {
-    if (softmax) return false;
+    if (softmax && N <= kGemmSoftmaxMaxN) return false;   // fused: the row fits one work-group
     return (int64_t)((M + 127) / 128) * ((N + 127) / 128) >= 32;
 }
 
@@ -290,14 +290,20 @@ LaunchShape gemm_shape(int32_t M, int32_t, int32_t N, int32_t softmax) {
     return s;
 }
 
-hipError_t gemm_launch(const GemmParams& p, hipStream_t stream) {
+hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
+    GemmParams p = p0;
+    // rows wider than one work-group: the GEMM stores its epilogue's result, a second kernel takes
+    // the row softmax of it in place
+    const bool split_softmax = p.softmax && p.N > kGemmSoftmaxMaxN;
+    if (split_softmax) p.softmax = 0;
     hipError_t e;
-    if (gemm_use_tile(p.M, p.N, p.softmax)) e = gemm_tile_launch(p, stream);
+    if (gemm_use_tile(p.M, p.N, p0.softmax)) e = gemm_tile_launch(p, stream);
     else switch (pick_bn(p.N)) {
         case 64: e = launch_bn<64>(p, stream); break;
         case 128: e = launch_bn<128>(p, stream); break;
         default: e = launch_bn<256>(p, stream);
     }
+    if (e == hipSuccess && split_softmax) return softmax_launch(SoftmaxParams{p.Y, p.Y, p.M, p.N}, stream);
     if (e != hipSuccess || !p.mean) return e;
     return rows_finish_launch(p.ws, p.Y, p.M, gemm_col_tiles(p.M, p.N), p.N, p.softmax2, stream);
 }

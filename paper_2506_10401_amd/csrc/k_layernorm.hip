@@ -152,9 +152,9 @@ __global__ __launch_bounds__(256) void layernorm_rows_any(const float* __restric
     }
 }
 
-// Row softmax, a work-group per row, any N.
-__global__ __launch_bounds__(256) void softmax_rows_any(const float* __restrict__ X, float* __restrict__ Y,
-                                                        int64_t rows, int N) {
+// Row softmax, a work-group per row, any N.  X and Y may be the same buffer: a thread
+// reads and writes only its own elements (no __restrict__ here for that reason).
+__global__ __launch_bounds__(256) void softmax_rows_any(const float* X, float* Y, int64_t rows, int N) {
     __shared__ float slots[16];
     const int64_t row = blockIdx.x;
     const float* x = X + row * (int64_t)N;

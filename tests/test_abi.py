@@ -180,9 +180,9 @@ def test_unsupported_but_well_formed():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = cfg_desc(1); d.reduce = H.HPCT_RED_AVGPOOL_HW
     expect(H.HPCT_ERR_UNSUPPORTED, d)
-    # fused softmax is limited to rows that fit one work-group tile
+    # (a softmax row wider than one work-group tile is supported: GEMM, then an in-place row softmax)
     d = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_SOFTMAX_LAST, 0, [(64, 256), (256, 512)], [(64, 512)])
-    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    assert H.Plan(d).kernel_name == "gemm_rows16<256>" and H.Plan(d).launch_shape()[0] == (4, 2, 1)
     # non-contiguous layouts
     d = cfg_desc(1); d.in_[1] = H.tensor_desc((256, 256), (1, 256))  # transposed W
     expect(H.HPCT_ERR_UNSUPPORTED, d)

@@ -77,6 +77,13 @@ def test_gemm_bias_relu_wide(M, K, N):
     assert show("gemm+bias+relu", compare.contraction(run_chain1(t, softmax=False), ref.relu(Z), Dn))
 
 
+@pytest.mark.parametrize("M,K,N", [(64, 256, 1000), (33, 50, 257), (700, 64, 4096), (4096, 32, 2052)])
+def test_chain1_rows_wider_than_a_tile(M, K, N):
+    print("chain1 wide M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    assert show("softmax", compare.pointwise(run_chain1(t), ref.chain1(t["X"], t["W"], t["bias"])))
+
+
 def test_gemm_identity_weight_is_exact():
     X = datagen.gen_uniform(5, (48, 64), -1, 1)
     out = torch.empty(48, 64, device="cuda")
