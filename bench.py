@@ -206,6 +206,24 @@ def main() -> int:
         time_reduce("sum_axis1_8192x4096", ms, 1, "sum", (8192,), ms[0].numel() * 4 + 8192 * 4)
         time_reduce("sum_axis0_8192x4096", ms, 0, "sum", (4096,), ms[0].numel() * 4 + 4096 * 4)
         time_reduce("argmax_axis1_8192x4096", ms, 1, "argmax", (8192,), ms[0].numel() * 4 + 8192 * 4)
+        # row softmax (Table 1 Reduction "softmax") on the same matrices, into the layernorm outputs
+        calls_s = []
+        for s_ in sets[3]:
+            plan_s, ins_s = hpct.softmax_rows_plan(s_["ins"][0], s_["out"])
+            calls_s.append(plan_s.bind(ins_s, [s_["out"]]))
+        for k in range(min(args.warmup, 10)):
+            calls_s[k % len(calls_s)]()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(args.steps):
+            calls_s[k % len(calls_s)]()
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / args.steps
+        nb = 2 * ms[0].numel() * 4
+        reduce_ops.append(dict(op="softmax_rows_8192x4096", kernel=plan_s.kernel_name, avg_us=round(us, 3),
+                               achieved=round(nb / us / 1e3, 1), unit="GB/s", peak=HBM_PEAK_GBS,
+                               frac=round(nb / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=len(calls_s)))
         xs = [s_["ins"][0] for s_ in sets[2]]                  # 11 NCHW tensors [32,64,56,56]
         time_reduce("argmax_channels_32x64x56x56", xs, 1, "argmax", (32, 56, 56), xs[0].numel() * 4 + 32 * 3136 * 4)
         time_reduce("mean_channels_32x64x56x56", xs, 1, "mean", (32, 56, 56), xs[0].numel() * 4 + 32 * 3136 * 4)

@@ -2,7 +2,8 @@
 // and a plain row softmax (Reduction and Elementwise classes of the paper's
 // Table 1).  Memory-bound: each row is read from HBM once with 128-bit loads,
 // held in registers for the two reduction passes and the epilogue, and written
-// once.
+// once.  The kernels are templated on the row operation: layernorm, layernorm +
+// GELU, or softmax (max, then sum of exponentials, both from registers).
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -10,15 +11,68 @@ namespace hpct {
 namespace {
 
 constexpr int kMaxVec = 16;  // float4 per thread held in registers
+constexpr int kLn = 0, kLnGelu = 1, kSoftmax = 2;  // row operations
+
+// The row operation on the VPT vectors a thread holds (vector i is element j = t + i*TPR of nv;
+// vectors with j >= nv do not exist).  Leaves the row's result in v; NW waves share `slots`.
+template <int OPK, int VPT, int TPR, int NW>
+__device__ __forceinline__ void row_op(float4v* v, int t, int nv, int N, float eps, float* slots) {
+    if constexpr (OPK == kSoftmax) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i)
+            if (t + i * TPR < nv) m = fmaxf(m, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
+        m = block_reduce<OpMax, NW>(m, slots);
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            float4v e = (v[i] - m) * kLog2e;
+            e.x = fast_exp2(e.x); e.y = fast_exp2(e.y); e.z = fast_exp2(e.z); e.w = fast_exp2(e.w);
+            if (t + i * TPR >= nv) e = float4v{0.f, 0.f, 0.f, 0.f};
+            v[i] = e;
+            s += (e.x + e.y) + (e.z + e.w);
+        }
+        const float inv = 1.0f / block_reduce<OpSum, NW>(s, slots);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) v[i] = v[i] * inv;
+    } else {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+        const float inv_n = 1.0f / (float)N;
+        const float mu = block_reduce<OpSum, NW>(s, slots) * inv_n;
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            float4v d = v[i] - mu;
+            if (t + i * TPR >= nv) d = float4v{0.f, 0.f, 0.f, 0.f};
+            v[i] = d;
+            q += (d.x * d.x + d.y * d.y) + (d.z * d.z + d.w * d.w);
+        }
+        const float var = block_reduce<OpSum, NW>(q, slots) * inv_n;
+        const float rstd = fast_rsq(var + eps);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) v[i] = v[i] * rstd;
+    }
+}
+
+// scale / shift / GELU of a normalised vector (layernorm only)
+template <int OPK>
+__device__ __forceinline__ float4v ln_out(float4v o, float4v g, float4v b) {
+    if constexpr (OPK == kSoftmax) return o;
+    o = o * g + b;
+    if (OPK == kLnGelu) { o.x = gelu_tanh(o.x); o.y = gelu_tanh(o.y); o.z = gelu_tanh(o.z); o.w = gelu_tanh(o.w); }
+    return o;
+}
 
 // One row per group of TPR threads (TPR = 64: a wave per row, four rows per
 // work-group, no LDS; TPR = 256: a work-group per row, LDS cross-wave combine).
 // Thread t of the group owns vectors t, t+TPR, ... (< N/4), so consecutive
 // lanes read consecutive 16-byte words.
-template <int TPR, int VPT, bool GELU>
-__global__ __launch_bounds__(256) void layernorm_rows_vec(const float* __restrict__ X, const float* __restrict__ gamma,
-                                                          const float* __restrict__ beta, float* __restrict__ Y,
-                                                          int64_t rows, int N, float eps) {
+template <int TPR, int VPT, int OPK>
+__global__ __launch_bounds__(256) void rows_vec(const float* __restrict__ X, const float* __restrict__ gamma,
+                                                const float* __restrict__ beta, float* __restrict__ Y,
+                                                int64_t rows, int N, float eps) {
     constexpr int RPB = 256 / TPR;
     constexpr int NW = TPR / kWave;
     __shared__ float slots[16];
@@ -34,33 +88,16 @@ __global__ __launch_bounds__(256) void layernorm_rows_vec(const float* __restric
         const int j = t + i * TPR;
         v[i] = (live && j < nv) ? load4_nt(x + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
     }
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-    const float inv_n = 1.0f / (float)N;
-    const float mu = block_reduce<OpSum, NW>(s, slots) * inv_n;
-    float q = 0.f;
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-        const int j = t + i * TPR;
-        float4v d = v[i] - mu;
-        if (j >= nv) d = float4v{0.f, 0.f, 0.f, 0.f};
-        v[i] = d;
-        q += (d.x * d.x + d.y * d.y) + (d.z * d.z + d.w * d.w);
-    }
-    const float var = block_reduce<OpSum, NW>(q, slots) * inv_n;
-    const float rstd = fast_rsq(var + eps);
+    row_op<OPK, VPT, TPR, NW>(v, t, nv, N, eps, slots);
     if (!live) return;
     float* y = Y + row * (int64_t)N;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
         const int j = t + i * TPR;
         if (j < nv) {
-            float4v g = gamma ? load4(gamma + 4 * j) : float4v{1.f, 1.f, 1.f, 1.f};
-            float4v b = beta ? load4(beta + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
-            float4v o = v[i] * rstd * g + b;
-            if (GELU) { o.x = gelu_tanh(o.x); o.y = gelu_tanh(o.y); o.z = gelu_tanh(o.z); o.w = gelu_tanh(o.w); }
-            store4_nt(y + 4 * j, o);
+            float4v g = (OPK != kSoftmax && gamma) ? load4(gamma + 4 * j) : float4v{1.f, 1.f, 1.f, 1.f};
+            float4v b = (OPK != kSoftmax && beta) ? load4(beta + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+            store4_nt(y + 4 * j, ln_out<OPK>(v[i], g, b));
         }
     }
 }
@@ -71,10 +108,10 @@ __global__ __launch_bounds__(256) void layernorm_rows_vec(const float* __restric
 // row is reduced, so HBM reads never wait for the reductions.
 constexpr int kPersistGrid = 512;  // 2 x 256 CUs
 
-template <int VPT, bool GELU>
-__global__ __launch_bounds__(256) void layernorm_rows_persist(const float* __restrict__ X, const float* __restrict__ gamma,
-                                                              const float* __restrict__ beta, float* __restrict__ Y,
-                                                              int64_t rows, int N, float eps) {
+template <int VPT, int OPK>
+__global__ __launch_bounds__(256) void rows_persist(const float* __restrict__ X, const float* __restrict__ gamma,
+                                                    const float* __restrict__ beta, float* __restrict__ Y,
+                                                    int64_t rows, int N, float eps) {
     __shared__ float slots[16];
     const int t = threadIdx.x;
     const int nv = N >> 2;
@@ -82,8 +119,8 @@ __global__ __launch_bounds__(256) void layernorm_rows_persist(const float* __res
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
         const int j = t + i * 256;
-        g[i] = (gamma && j < nv) ? load4(gamma + 4 * j) : float4v{1.f, 1.f, 1.f, 1.f};
-        b[i] = (beta && j < nv) ? load4(beta + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+        g[i] = (OPK != kSoftmax && gamma && j < nv) ? load4(gamma + 4 * j) : float4v{1.f, 1.f, 1.f, 1.f};
+        b[i] = (OPK != kSoftmax && beta && j < nv) ? load4(beta + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
     }
     auto load_row = [&](int64_t row, float4v* dst) {
         const float* x = X + row * (int64_t)N;
@@ -96,33 +133,15 @@ __global__ __launch_bounds__(256) void layernorm_rows_persist(const float* __res
     int64_t row = blockIdx.x;
     if (row >= rows) return;
     load_row(row, v);
-    const float inv_n = 1.0f / (float)N;
     for (; row < rows; row += gridDim.x) {
         const int64_t nrow = row + gridDim.x;
         if (nrow < rows) load_row(nrow, nx);
-        float s = 0.f;
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-        const float mu = block_reduce<OpSum, 4>(s, slots) * inv_n;
-        float q = 0.f;
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            float4v d = v[i] - mu;
-            if (t + i * 256 >= nv) d = float4v{0.f, 0.f, 0.f, 0.f};
-            v[i] = d;
-            q += (d.x * d.x + d.y * d.y) + (d.z * d.z + d.w * d.w);
-        }
-        const float var = block_reduce<OpSum, 4>(q, slots) * inv_n;
-        const float rstd = fast_rsq(var + eps);
+        row_op<OPK, VPT, 256, 4>(v, t, nv, N, eps, slots);
         float* y = Y + row * (int64_t)N;
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             const int j = t + i * 256;
-            if (j < nv) {
-                float4v o = v[i] * rstd * g[i] + b[i];
-                if (GELU) { o.x = gelu_tanh(o.x); o.y = gelu_tanh(o.y); o.z = gelu_tanh(o.z); o.w = gelu_tanh(o.w); }
-                store4_nt(y + 4 * j, o);
-            }
+            if (j < nv) store4_nt(y + 4 * j, ln_out<OPK>(v[i], g[i], b[i]));
         }
 #pragma unroll
         for (int i = 0; i < VPT; ++i) v[i] = nx[i];
@@ -185,65 +204,71 @@ LnPick pick(int32_t N) {
     return {0, 0};
 }
 
-template <int VPT>
+template <int VPT, int OPK>
 hipError_t launch_persist(const LayernormParams& p, hipStream_t stream) {
     dim3 grid((unsigned)(p.rows < kPersistGrid ? p.rows : kPersistGrid)), block(256);
-    if (p.gelu)
-        hipLaunchKernelGGL((layernorm_rows_persist<VPT, true>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows,
-                           p.N, p.eps);
-    else
-        hipLaunchKernelGGL((layernorm_rows_persist<VPT, false>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows,
-                           p.N, p.eps);
+    hipLaunchKernelGGL((rows_persist<VPT, OPK>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
     return hipGetLastError();
 }
 
-template <int TPR, int VPT>
+template <int TPR, int VPT, int OPK>
 hipError_t launch_vec(const LayernormParams& p, hipStream_t stream) {
     constexpr int RPB = 256 / TPR;
     dim3 grid((unsigned)((p.rows + RPB - 1) / RPB)), block(256);
-    if (p.gelu)
-        hipLaunchKernelGGL((layernorm_rows_vec<TPR, VPT, true>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y,
-                           p.rows, p.N, p.eps);
-    else
-        hipLaunchKernelGGL((layernorm_rows_vec<TPR, VPT, false>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y,
-                           p.rows, p.N, p.eps);
+    hipLaunchKernelGGL((rows_vec<TPR, VPT, OPK>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
     return hipGetLastError();
+}
+
+// the register-resident kernels for N % 4 == 0 and N <= 16384; false: the caller takes its any-N kernel
+template <int OPK>
+bool launch_rows(const LayernormParams& p, hipStream_t stream, hipError_t* e) {
+    const LnPick k = pick(p.N);
+    if (k.tpr == 64) {
+        switch (k.vpt) {
+            case 1: *e = launch_vec<64, 1, OPK>(p, stream); break;
+            case 2: *e = launch_vec<64, 2, OPK>(p, stream); break;
+            default: *e = launch_vec<64, 4, OPK>(p, stream);
+        }
+        return true;
+    }
+    if (k.tpr == 256) {
+        switch (k.vpt) {
+            case 2: *e = launch_persist<2, OPK>(p, stream); break;
+            case 4: *e = launch_persist<4, OPK>(p, stream); break;
+            case 8: *e = launch_vec<256, 8, OPK>(p, stream); break;
+            default: *e = launch_vec<256, 16, OPK>(p, stream);
+        }
+        return true;
+    }
+    return false;
+}
+
+void rows_shape(int64_t rows, int32_t N, LaunchShape& s, const char* const names[4]) {
+    const LnPick k = pick(N);
+    s.block[0] = 256; s.block[1] = s.block[2] = 1;
+    s.grid[1] = s.grid[2] = 1;
+    s.lds_bytes = 64;
+    if (k.tpr == 0) { s.grid[0] = (uint32_t)rows; s.kernel = names[0]; }
+    else if (k.tpr == 64) { s.grid[0] = (uint32_t)((rows + 3) / 4); s.kernel = names[1]; }
+    else if (k.vpt <= 4) {
+        s.grid[0] = (uint32_t)(rows < kPersistGrid ? rows : kPersistGrid);
+        s.kernel = names[2];
+    } else { s.grid[0] = (uint32_t)rows; s.kernel = names[3]; }
 }
 
 }  // namespace
 
 LaunchShape layernorm_shape(int64_t rows, int32_t N) {
-    const LnPick k = pick(N);
+    static const char* const names[4] = {"layernorm_rows_any", "layernorm_rows_vec<wave-per-row>", "layernorm_rows_persist",
+                                         "layernorm_rows_vec<group-per-row>"};
     LaunchShape s{};
-    s.block[0] = 256; s.block[1] = s.block[2] = 1;
-    s.grid[1] = s.grid[2] = 1;
-    s.lds_bytes = 64;
-    if (k.tpr == 0) { s.grid[0] = (uint32_t)rows; s.kernel = "layernorm_rows_any"; }
-    else if (k.tpr == 64) { s.grid[0] = (uint32_t)((rows + 3) / 4); s.kernel = "layernorm_rows_vec<wave-per-row>"; }
-    else if (k.vpt <= 4) {
-        s.grid[0] = (uint32_t)(rows < kPersistGrid ? rows : kPersistGrid);
-        s.kernel = "layernorm_rows_persist";
-    } else { s.grid[0] = (uint32_t)rows; s.kernel = "layernorm_rows_vec<group-per-row>"; }
+    rows_shape(rows, N, s, names);
     return s;
 }
 
 hipError_t layernorm_launch(const LayernormParams& p, hipStream_t stream) {
-    const LnPick k = pick(p.N);
-    if (k.tpr == 64) {
-        switch (k.vpt) {
-            case 1: return launch_vec<64, 1>(p, stream);
-            case 2: return launch_vec<64, 2>(p, stream);
-            default: return launch_vec<64, 4>(p, stream);
-        }
-    }
-    if (k.tpr == 256) {
-        switch (k.vpt) {
-            case 2: return launch_persist<2>(p, stream);
-            case 4: return launch_persist<4>(p, stream);
-            case 8: return launch_vec<256, 8>(p, stream);
-            default: return launch_vec<256, 16>(p, stream);
-        }
-    }
+    hipError_t e = hipSuccess;
+    if (p.gelu ? launch_rows<kLnGelu>(p, stream, &e) : launch_rows<kLn>(p, stream, &e)) return e;
     dim3 grid((unsigned)p.rows), block(256);
     if (p.gelu)
         hipLaunchKernelGGL(layernorm_rows_any<true>, grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
@@ -252,16 +277,22 @@ hipError_t layernorm_launch(const LayernormParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-LaunchShape softmax_shape(int64_t rows, int32_t) {
+LaunchShape softmax_shape(int64_t rows, int32_t N) {
+    static const char* const names[4] = {"softmax_rows_any", "softmax_rows_vec<wave-per-row>", "softmax_rows_persist",
+                                         "softmax_rows_vec<group-per-row>"};
     LaunchShape s{};
-    s.grid[0] = (uint32_t)rows; s.grid[1] = s.grid[2] = 1;
-    s.block[0] = 256; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = 64;
-    s.kernel = "softmax_rows_any";
+    rows_shape(rows, N, s, names);
     return s;
 }
 
+// X and Y may be the same buffer (every kernel reads a row completely before it writes it, or
+// touches only a thread's own elements).
 hipError_t softmax_launch(const SoftmaxParams& p, hipStream_t stream) {
+    hipError_t e = hipSuccess;
+    if (p.X != p.Y) {   // the register-resident kernels declare X and Y __restrict__
+        const LayernormParams q{p.X, nullptr, nullptr, p.Y, p.rows, p.N, 0.f, 0};
+        if (launch_rows<kSoftmax>(q, stream, &e)) return e;
+    }
     hipLaunchKernelGGL(softmax_rows_any, dim3((unsigned)p.rows), dim3(256), 0, stream, p.X, p.Y, p.rows, p.N);
     return hipGetLastError();
 }

@@ -301,9 +301,15 @@ def layernorm_gelu(X, gamma, beta, out, eps=1e-5, gelu=True, stream=None) -> Non
     plan.launch(ins, [out], stream)
 
 
-def softmax_rows(X, out, stream=None) -> None:
+def softmax_rows_plan(X, out):
     plan = _cached(("softmax", _sh(X)), lambda: op_desc(HPCT_ANCHOR_NONE, [], HPCT_RED_SOFTMAX_LAST, 0, [_sh(X)], [_sh(out)]))
-    plan.launch([X], [out], stream)
+    return plan, [X]
+
+
+def softmax_rows(X, out, stream=None) -> None:
+    """out = softmax over the last dim of the 2-D tensor X."""
+    plan, ins = softmax_rows_plan(X, out)
+    plan.launch(ins, [out], stream)
 
 
 def layout_transform_plan(x_view, out):

@@ -254,12 +254,28 @@ def test_chain3_ragged_shapes(M, N):
                                                             ref.layernorm_rows(t["X"], None, None, 1e-5)))
 
 
-@pytest.mark.parametrize("M,N", [(1, 1), (5, 7), (3, 256), (4, 1000), (2, 5000)])
+@pytest.mark.parametrize("M,N", [(1, 1), (5, 7), (3, 256), (4, 1000), (2, 5000), (9, 4), (70, 260), (33, 1024), (17, 1028),
+                                 (600, 2048), (515, 4096), (40, 4100), (12, 8192), (7, 16384), (5, 16388), (3, 40000)])
 def test_softmax_rows(M, N):
     X = datagen.gen_normal(77, (M, N), 0.0, 3.0)
     out = torch.full((M, N), float("nan"), device="cuda")
-    hpct.softmax_rows(dev(X), out)
-    assert show("softmax %dx%d" % (M, N), compare.pointwise(host(out), ref.softmax_rows(X.astype(np.float64))))
+    plan, ins = hpct.softmax_rows_plan(dev(X), out)
+    print("softmax %dx%d" % (M, N), plan.kernel_name, flush=True)
+    plan.launch(ins, [out])
+    got = host(out)
+    assert show("softmax %dx%d" % (M, N), compare.pointwise(got, ref.softmax_rows(X.astype(np.float64))))
+    assert np.allclose(got.astype(np.float64).sum(axis=1), 1.0, rtol=0, atol=1e-5)
+
+
+def test_softmax_rows_full_size_and_large_values():
+    X = datagen.make(3)["X"] * np.float32(40.0)          # [8192, 4096], values up to +-200: needs the row max
+    out = torch.full(X.shape, float("nan"), device="cuda")
+    plan, ins = hpct.softmax_rows_plan(dev(X), out)
+    assert plan.kernel_name == "softmax_rows_persist"
+    plan.launch(ins, [out])
+    got = host(out)
+    assert np.all(np.isfinite(got))
+    assert show("softmax 8192x4096", compare.pointwise(got, ref.softmax_rows(X.astype(np.float64))))
 
 
 # ------------------------------------------------------------------- chain 4
