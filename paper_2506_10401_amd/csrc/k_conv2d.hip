@@ -68,12 +68,8 @@ template <int R, int CC, int KT> struct Cfg {
     static constexpr int NV4 = KT * FPR / 4;     // float4 of weights per chunk
     static constexpr int WPT = (NV4 + 255) / 256;
     static constexpr int W_STAGE = KT * WLD;     // floats
-    static constexpr int IN_PER_T = CC <= 4 ? 2 : 3;  // input float4 slots staged through registers per thread
 };
 
-// FAST: W % 4 == 0, C % CC == 0, K % KT == 0 and the staged input fits the
-// register-staged slots: aligned vector loads, no tails, software pipelined.
-// Otherwise every element is loaded with its own bounds test, chunk by chunk.
 struct ConvEpi {
     const float* bias;   // [K] or null
     const float* scale;  // [K] or null
@@ -81,18 +77,34 @@ struct ConvEpi {
     int relu;
 };
 
-template <int R, int CC, int KT, bool FAST, bool POOL>
+// MODE 0 (general): every element is loaded with its own bounds test, chunk by chunk.
+// MODE 1..4 (pipelined): C % CC == 0, K % KT == 0, dilation 1, and the image width is a multiple
+// of the input vector width IV, so input rows are staged with aligned IV-wide loads that lie
+// entirely inside or outside the image; IPT such slots per thread go through registers, software
+// pipelined against the MFMAs.  1: IV 4, IPT 2;  2: IV 4, IPT 4;  3: IV 2, IPT 4;  4: IV 1, IPT 4.
+template <int IV> struct VecOf;
+template <> struct VecOf<4> { typedef float4v type; };
+template <> struct VecOf<2> { typedef float2v type; };
+template <> struct VecOf<1> { typedef float type; };
+constexpr int mode_iv(int mode) { return mode <= 2 ? 4 : (mode == 3 ? 2 : 1); }
+constexpr int mode_ipt(int mode) { return mode == 1 ? 2 : 4; }
+
+template <int R, int CC, int KT, int MODE, bool POOL>
 __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict__ in, const float* __restrict__ wt,
                                                         ConvEpi epi, float* __restrict__ out, ConvGeom g) {
     using cfg = Cfg<R, CC, KT>;
+    constexpr bool FAST = MODE != 0;
+    constexpr int IV = mode_iv(MODE), IN_PER_T = mode_ipt(MODE);
+    typedef typename VecOf<IV>::type ivec;
     constexpr int KB = KT / 64;  // 32-channel accumulator blocks per wave
     constexpr int TAPS = cfg::TAPS, FPR = cfg::FPR, HALF = cfg::HALF, WLD = cfg::WLD, VW = cfg::VW;
-    constexpr int IN_PER_T = cfg::IN_PER_T, WPT = cfg::WPT;
+    constexpr int WPT = cfg::WPT;
     extern __shared__ __align__(16) float lds[];
     const int in_stage = CC * g.ch_ld;  // floats
+    constexpr int NBUF = FAST ? 2 : 1;  // the general variant stages one chunk at a time
     auto inS = [&](int buf) { return lds + buf * in_stage; };
-    auto wS = [&](int buf) { return lds + 2 * in_stage + buf * cfg::W_STAGE; };
-    float* const mulS = lds + 2 * in_stage + 2 * cfg::W_STAGE;  // KT floats: per-channel factor
+    auto wS = [&](int buf) { return lds + NBUF * in_stage + buf * cfg::W_STAGE; };
+    float* const mulS = lds + NBUF * in_stage + NBUF * cfg::W_STAGE;  // KT floats: per-channel factor
     float* const addS = mulS + KT;                              // KT floats: per-channel addend
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -136,19 +148,25 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         }
     };
 
-    // ---- FAST staging: geometry worked out once, loads through registers ------
-    float4v ireg[IN_PER_T], wreg[WPT];
+    // ---- pipelined staging: geometry worked out once, loads through registers ------
+    ivec ireg[IN_PER_T];
+    float4v wreg[WPT];
     int s_goff[IN_PER_T], s_loff[IN_PER_T];
     int w_goff[WPT], w_loff[WPT];
     if (FAST) {
+        const int ldwv = g.ldw / IV;                         // IV-wide slots per staged row
+        const int vslots = CC * g.rows_max * ldwv;           // slot -> (c, row, x)
 #pragma unroll
         for (int i = 0; i < IN_PER_T; ++i) {
             const int s = tid + i * 256;
-            int c, mask;
             s_goff[i] = -1; s_loff[i] = -1;
-            if (s < slots) {
-                slot_geom(s, s_goff[i], s_loff[i], c, mask);
-                if (mask != 15) s_goff[i] = -1;  // whole slot outside the image: stays zero
+            if (s < vslots) {
+                const int c = s / (g.rows_max * ldwv);
+                const int rem = s - c * (g.rows_max * ldwv);
+                const int row = rem / ldwv, x = (rem - row * ldwv) * IV;
+                const int ih = ih0 + row, iw = iw0 + x - g.P - g.lpad;   // a multiple of IV, like W: all in or all out
+                s_loff[i] = c * g.ch_ld + row * g.ldw + x;
+                if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) s_goff[i] = ((n * g.C + c) * g.H + ih) * g.W + iw;
             }
         }
 #pragma unroll
@@ -162,7 +180,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     auto fetch = [&](int c0) {
 #pragma unroll
         for (int i = 0; i < IN_PER_T; ++i)
-            ireg[i] = s_goff[i] >= 0 ? load4(in + s_goff[i] + c0 * HW) : float4v{0.f, 0.f, 0.f, 0.f};
+            ireg[i] = s_goff[i] >= 0 ? *reinterpret_cast<const ivec*>(in + s_goff[i] + c0 * HW) : ivec{};
 #pragma unroll
         for (int i = 0; i < WPT; ++i)
             wreg[i] = w_goff[i] >= 0 ? load4(wt + w_goff[i] + c0 * TAPS) : float4v{0.f, 0.f, 0.f, 0.f};
@@ -172,7 +190,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         float* const wb = wS(buf);
 #pragma unroll
         for (int i = 0; i < IN_PER_T; ++i)
-            if (s_loff[i] >= 0) *reinterpret_cast<float4v*>(ib + s_loff[i]) = ireg[i];
+            if (s_loff[i] >= 0) *reinterpret_cast<ivec*>(ib + s_loff[i]) = ireg[i];
 #pragma unroll
         for (int i = 0; i < WPT; ++i) {
             if (w_goff[i] >= 0) {
@@ -339,14 +357,21 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     }
 }
 
-ConvGeom geom(const ConvParams& p) {
+// input channels per LDS chunk: 4 (x 9 taps = 18 MFMA steps per chunk for 3x3); a 1x1 filter has one
+// tap per channel, so it takes 16 channels per chunk (except in the pooled variant, whose bank
+// layout is worked out for 4)
+constexpr int cc_of(int R, bool pool) { return (R == 1 && !pool) ? 16 : 4; }
+
+// iv: vector width of the input staging (the left pad of an LDS row makes image column 0 land on
+// a multiple of it)
+ConvGeom geom(const ConvParams& p, int iv = 4) {
     ConvGeom g{};
     g.Nb = p.Nb; g.C = p.C; g.H = p.H; g.W = p.W; g.K = p.K; g.P = p.pad; g.St = p.stride; g.Dl = p.dil;
     const int re = (p.R - 1) * p.dil + 1;   // rows / columns the dilated filter spans
     g.Ho = (p.H + 2 * p.pad - re) / p.stride + 1;
     g.Wo = (p.W + 2 * p.pad - re) / p.stride + 1;
     g.HoWo = g.Ho * g.Wo;
-    g.lpad = (4 - p.pad % 4) % 4;
+    g.lpad = (iv - p.pad % iv) % iv;
     if (p.pool) {
         g.Hp = g.Ho / 2; g.Wp = g.Wo / 2;
         g.ctiles = (2 * g.Wp + 7) / 8;
@@ -362,71 +387,94 @@ ConvGeom geom(const ConvParams& p) {
         g.ldw = (p.W + 2 * p.pad + g.lpad + 3) & ~3;
     }
     g.tiles = p.Nb * g.tiles_per_img;
-    // The two lane halves read the same pixel pattern of channels kCC/2 apart in one LDS access.
-    // Channel stride = 16 (mod 32) words puts the halves' 32-word runs on complementary bank halves;
-    // in the pooled geometry a half covers words 0-7 of four 16-word rows, and a channel stride of
-    // 4 (mod 32) moves the other half onto words 8-15.
-    const int want = p.pool ? 4 : 16;
+    // The two lane halves read the same pixel pattern of channels CC/2 apart in one LDS access.
+    // CC = 4: a channel stride of 16 (mod 32) words puts the halves' 32-word runs on complementary
+    // bank halves; in the pooled geometry a half covers words 0-7 of four 16-word rows, and a channel
+    // stride of 4 (mod 32) moves the other half onto words 8-15.  CC = 16 (halves 8 channels apart):
+    // 4 (mod 8) gives the same 32-bank shift.
+    const int cc = cc_of(p.R, p.pool != 0);
+    const int mod = cc == 16 ? 8 : 32, want = cc == 16 ? 4 : (p.pool ? 4 : 16);
     g.ch_ld = g.rows_max * g.ldw;
-    g.ch_ld += ((want - g.ch_ld % 32) + 32) % 32;
+    g.ch_ld += ((want - g.ch_ld % mod) + mod) % mod;
     return g;
 }
 
 template <int R, int CC, int KT>
-size_t lds_bytes(const ConvGeom& g) {
-    return (size_t)(2 * CC * g.ch_ld + 2 * Cfg<R, CC, KT>::W_STAGE + 2 * KT) * 4;
+size_t lds_bytes(const ConvGeom& g, bool fast) {
+    const int nbuf = fast ? 2 : 1;
+    return (size_t)(nbuf * CC * g.ch_ld + nbuf * Cfg<R, CC, KT>::W_STAGE + 2 * KT) * 4;
 }
 
-// Input channels per LDS chunk and output channels per work-group.  4 x 64
-// keeps a work-group near 30 KB of LDS (five per CU hide each other's staging
-// and barriers) and makes the work items small enough to balance over 256 CUs.
-constexpr int kCC = 4;
+// Output channels per work-group.  With 4 input channels per chunk, 64 keeps a work-group near
+// 30 KB of LDS (five per CU hide each other's staging and barriers) and makes the work items small
+// enough to balance over 256 CUs.
 constexpr int kKT = 64;
 
-template <int R>
-bool fast_ok(const ConvParams& p, const ConvGeom& g) {
-    return p.dil == 1 && p.W % 4 == 0 && p.C % kCC == 0 && p.K % kKT == 0 &&
-           kCC * g.rows_max * (g.ldw / 4) <= 256 * Cfg<R, kCC, kKT>::IN_PER_T;
+// Staging mode and the geometry that goes with it.
+int pick_mode(const ConvParams& p, ConvGeom* g_out) {
+    const int cc = cc_of(p.R, p.pool != 0);
+    if ((p.R == 1 || p.R == 3) && p.dil == 1 && p.C % cc == 0 && p.K % kKT == 0) {
+        for (int iv = 4; iv >= 1; iv >>= 1) {
+            if (p.W % iv) continue;
+            const ConvGeom g = geom(p, iv);
+            const int slots = cc * g.rows_max * (g.ldw / iv);
+            if (slots > 256 * 4) break;   // narrower vectors only need more slots
+            *g_out = g;
+            return iv == 4 ? (slots <= 256 * 2 ? 1 : 2) : (iv == 2 ? 3 : 4);
+        }
+    }
+    *g_out = geom(p, 4);
+    return 0;
 }
 
 int conv_items(const ConvParams& p, const ConvGeom& g) { return g.tiles * ((p.K + kKT - 1) / kKT); }
 
-template <int R, bool FAST, bool POOL>
+template <int R, int MODE, bool POOL>
 hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
-    const size_t lds = lds_bytes<R, kCC, kKT>(g);
+    constexpr int CC = cc_of(R, POOL);
+    const size_t lds = lds_bytes<R, CC, kKT>(g, MODE != 0);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, kCC, kKT, FAST, POOL>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, CC, kKT, MODE, POOL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)conv_items(p, g)), block(256);
     const ConvEpi epi{p.bias, p.scale, p.shift, p.relu};
-    hipLaunchKernelGGL((conv2d_nchw_mfma<R, kCC, kKT, FAST, POOL>), grid, block, lds, stream, p.in, p.wt, epi, p.out, g);
+    hipLaunchKernelGGL((conv2d_nchw_mfma<R, CC, kKT, MODE, POOL>), grid, block, lds, stream, p.in, p.wt, epi, p.out, g);
     return hipGetLastError();
 }
 
+template <int R, bool POOL>
+hipError_t launch_mode(const ConvParams& p, const ConvGeom& g, int mode, hipStream_t stream) {
+    if constexpr (R == 1 || R == 3) {
+        switch (mode) {
+            case 1: return launch_conv<R, 1, POOL>(p, g, stream);
+            case 2: return launch_conv<R, 2, POOL>(p, g, stream);
+            case 3: return launch_conv<R, 3, POOL>(p, g, stream);
+            case 4: return launch_conv<R, 4, POOL>(p, g, stream);
+            default: break;
+        }
+    }
+    return launch_conv<R, 0, POOL>(p, g, stream);
+}
+
 template <int R>
-size_t lds_for(const ConvParams& p) { return lds_bytes<R, kCC, kKT>(geom(p)); }
+hipError_t launch_pool(const ConvParams& p, const ConvGeom& g, int mode, hipStream_t stream) {
+    return p.pool ? launch_mode<R, true>(p, g, mode, stream) : launch_mode<R, false>(p, g, mode, stream);
+}
 
 size_t lds_any(const ConvParams& p) {
+    ConvGeom g;
+    const bool fast = pick_mode(p, &g) != 0;
+    const bool pool = p.pool != 0;
     switch (p.R) {
-        case 1: return lds_for<1>(p);
-        case 3: return lds_for<3>(p);
-        case 5: return lds_for<5>(p);
-        default: return lds_for<7>(p);
+        case 1: return pool ? lds_bytes<1, cc_of(1, true), kKT>(g, fast) : lds_bytes<1, cc_of(1, false), kKT>(g, fast);
+        case 3: return lds_bytes<3, cc_of(3, false), kKT>(g, fast);
+        case 5: return lds_bytes<5, cc_of(5, false), kKT>(g, fast);
+        default: return lds_bytes<7, cc_of(7, false), kKT>(g, fast);
     }
-}
-
-// 1x1 and 3x3 have the pipelined variant; 5x5 and 7x7 always take the general one
-bool is_fast(const ConvParams& p, const ConvGeom& g) {
-    return p.R == 3 ? fast_ok<3>(p, g) : (p.R == 1 ? fast_ok<1>(p, g) : false);
-}
-
-template <int R, bool FAST>
-hipError_t launch_pool(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
-    return p.pool ? launch_conv<R, FAST, true>(p, g, stream) : launch_conv<R, FAST, false>(p, g, stream);
 }
 
 }  // namespace
@@ -447,12 +495,12 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
 }
 
 LaunchShape conv_shape(const ConvParams& p) {
-    const ConvGeom g = geom(p);
+    ConvGeom g;
+    const int mode = pick_mode(p, &g);
     LaunchShape s{};
     s.grid[0] = (uint32_t)conv_items(p, g); s.grid[1] = 1; s.grid[2] = 1;
     s.block[0] = 256; s.block[1] = s.block[2] = 1;
     s.lds_bytes = (uint32_t)lds_any(p);
-    const bool fast = is_fast(p, g);
     static const char* const names[4][2][2] = {
         {{"conv2d_nchw_mfma<1x1,general>", "conv2d_nchw_mfma<1x1,pipelined>"},
          {"conv2d_nchw_mfma<1x1,general,maxpool2>", "conv2d_nchw_mfma<1x1,pipelined,maxpool2>"}},
@@ -462,18 +510,18 @@ LaunchShape conv_shape(const ConvParams& p) {
          {"conv2d_nchw_mfma<5x5,general,maxpool2>", "conv2d_nchw_mfma<5x5,general,maxpool2>"}},
         {{"conv2d_nchw_mfma<7x7,general>", "conv2d_nchw_mfma<7x7,general>"},
          {"conv2d_nchw_mfma<7x7,general,maxpool2>", "conv2d_nchw_mfma<7x7,general,maxpool2>"}}};
-    s.kernel = names[p.R / 2][p.pool ? 1 : 0][fast ? 1 : 0];
+    s.kernel = names[p.R / 2][p.pool ? 1 : 0][mode != 0 ? 1 : 0];
     return s;
 }
 
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream) {
-    const ConvGeom g = geom(p);
-    const bool fast = is_fast(p, g);
+    ConvGeom g;
+    const int mode = pick_mode(p, &g);
     switch (p.R) {
-        case 1: return fast ? launch_pool<1, true>(p, g, stream) : launch_pool<1, false>(p, g, stream);
-        case 3: return fast ? launch_pool<3, true>(p, g, stream) : launch_pool<3, false>(p, g, stream);
-        case 5: return launch_pool<5, false>(p, g, stream);
-        default: return launch_pool<7, false>(p, g, stream);
+        case 1: return launch_pool<1>(p, g, mode, stream);
+        case 3: return launch_pool<3>(p, g, mode, stream);
+        case 5: return launch_pool<5>(p, g, mode, stream);
+        default: return launch_pool<7>(p, g, mode, stream);
     }
 }
 

@@ -382,6 +382,27 @@ def test_chain7_dilated(N, C, H, W, K, R, stride, pad, dil):
     check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False, dil=dil)
 
 
+@pytest.mark.parametrize("N,C,H,W,K,R,stride,pad", [
+    (2, 8, 14, 14, 64, 3, 1, 1),      # width 14: two-float staging
+    (1, 16, 7, 7, 128, 3, 1, 1),      # width 7: scalar staging
+    (2, 8, 10, 30, 64, 3, 1, 1),
+    (1, 12, 9, 5, 64, 3, 1, 1),
+    (2, 32, 8, 8, 64, 1, 1, 0),       # 1x1: 16 channels per chunk
+    (1, 64, 6, 10, 128, 1, 1, 0),
+    (1, 48, 7, 7, 64, 1, 1, 0),
+    (2, 8, 28, 28, 64, 3, 2, 1),      # stride 2, pipelined with four slots per thread
+    (1, 8, 6, 120, 64, 3, 1, 1),
+    (3, 256, 14, 14, 64, 3, 1, 1)])
+def test_chain7_pipelined_staging_modes(N, C, H, W, K, R, stride, pad):
+    print("chain7 modes %s" % ((N, C, H, W, K, R, stride, pad),), flush=True)
+    t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=R, S=R)
+    _, name = check_chain7(t, stride, pad, pool=False)
+    assert "pipelined" in name
+    _, name = check_chain7(t, stride, pad)
+    assert "pipelined" in name
+    check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False)
+
+
 def test_chain7_pool_takes_the_maximum_not_a_sum_or_a_corner():
     # identity 1x1 conv: the block is max pooling of the input, exactly
     X = datagen.gen_normal(11, (2, 4, 10, 66), 0.0, 1.0)
