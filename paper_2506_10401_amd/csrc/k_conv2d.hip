@@ -78,7 +78,7 @@ struct ConvEpi {
 };
 
 // MODE 0 (general): every element is loaded with its own bounds test, chunk by chunk.
-// MODE 1..4 (pipelined): C % CC == 0, K % KT == 0, dilation 1, and the image width is a multiple
+// MODE 1..4 (pipelined): C % CC == 0, dilation 1, and the image width is a multiple
 // of the input vector width IV, so input rows are staged with aligned IV-wide loads that lie
 // entirely inside or outside the image; IPT such slots per thread go through registers, software
 // pipelined against the MFMAs.  1: IV 4, IPT 2;  2: IV 4, IPT 4;  3: IV 2, IPT 4;  4: IV 1, IPT 4.
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         for (int i = 0; i < WPT; ++i) {
             const int v = tid + i * 256;
             const int k = v / (FPR / 4), f4 = v % (FPR / 4);
-            w_goff[i] = v < cfg::NV4 ? ((k0 + k) * g.C) * TAPS + 4 * f4 : -1;
+            w_goff[i] = (v < cfg::NV4 && k0 + k < g.K) ? ((k0 + k) * g.C) * TAPS + 4 * f4 : -1;   // rows past K are not staged: their accumulator rows are never stored
             w_loff[i] = k * WLD + 4 * f4;
         }
     }
@@ -413,7 +413,7 @@ constexpr int kKT = 64;
 // Staging mode and the geometry that goes with it.
 int pick_mode(const ConvParams& p, ConvGeom* g_out) {
     const int cc = cc_of(p.R, p.pool != 0);
-    if ((p.R == 1 || p.R == 3) && p.dil == 1 && p.C % cc == 0 && p.K % kKT == 0) {
+    if ((p.R == 1 || p.R == 3) && p.dil == 1 && p.C % cc == 0) {
         for (int iv = 4; iv >= 1; iv >>= 1) {
             if (p.W % iv) continue;
             const ConvGeom g = geom(p, iv);

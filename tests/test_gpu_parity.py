@@ -392,7 +392,10 @@ def test_chain7_dilated(N, C, H, W, K, R, stride, pad, dil):
     (1, 48, 7, 7, 64, 1, 1, 0),
     (2, 8, 28, 28, 64, 3, 2, 1),      # stride 2, pipelined with four slots per thread
     (1, 8, 6, 120, 64, 3, 1, 1),
-    (3, 256, 14, 14, 64, 3, 1, 1)])
+    (3, 256, 14, 14, 64, 3, 1, 1),
+    (1, 8, 16, 16, 72, 3, 1, 1),      # output channels not a multiple of 64
+    (1, 16, 8, 8, 200, 1, 1, 0),
+    (2, 4, 14, 14, 1, 3, 1, 1)])
 def test_chain7_pipelined_staging_modes(N, C, H, W, K, R, stride, pad):
     print("chain7 modes %s" % ((N, C, H, W, K, R, stride, pad),), flush=True)
     t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=R, S=R)
