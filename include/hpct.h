@@ -163,8 +163,9 @@ typedef struct hpct_plan hpct_plan;   /* opaque; host memory */
 hpct_status hpct_plan_create(const hpct_op_desc *desc, hpct_plan **out);
 
 /* Device workspace the plan needs at launch, in bytes: 0 except for GEMM chains
- * with MEAN_LAST (one float per row and column tile) and for axis reductions with
- * few outputs and a long strided axis (partial results of the pieces it is cut into).  The launch overwrites it;
+ * with MEAN_LAST (one float per row and column tile), GEMMs with a small output and
+ * a long K (partial products of the K slices) and axis reductions with few outputs
+ * and a long strided axis (partial results of the pieces it is cut into).  The launch overwrites it;
  * it needs no initialisation and carries nothing between launches.  0 for a NULL plan. */
 size_t hpct_plan_workspace_bytes(const hpct_plan *plan);
 

@@ -165,8 +165,8 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     p.kind = Kind::Gemm;
     p.u.gemm = g;
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has[0] ? 2 : -1; p.slot[3] = -1;
-    p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm);
-    p.ws_bytes = mean ? (size_t)gemm_col_tiles((int32_t)M, (int32_t)N) * (size_t)M * 4 : 0;
+    p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0);
+    p.ws_bytes = gemm_workspace_bytes((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0);
     return HPCT_OK;
 }
 

@@ -267,20 +267,29 @@ hipError_t launch_bn(const GemmParams& p, hipStream_t stream) {
 
 }  // namespace
 
-// The tiled kernel takes over once its 128 x 128 tiles give every XCD work; below
-// that the 16-row kernel's many small work-groups finish sooner.  The fused row
-// softmax exists only in the 16-row kernel.
-bool gemm_use_tile(int32_t M, int32_t N, int32_t softmax) {
+// The tiled kernel takes over once its tiles give every XCD work - 32 tiles of 128 x 128, or fewer
+// if K is long enough to be split into slices that make up for it; below that the 16-row kernel's
+// many small work-groups finish sooner.  The fused row softmax exists only in the 16-row kernel.
+bool gemm_use_tile(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean) {
     if (softmax && N <= kGemmSoftmaxMaxN) return false;   // fused: the row fits one work-group
-    return (int64_t)((M + 127) / 128) * ((N + 127) / 128) >= 32;
+    if ((int64_t)((M + 127) / 128) * ((N + 127) / 128) >= 32) return true;
+    const int64_t tiles64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64);
+    return tiles64 * gemm_ksplit(M, K, N, mean) >= 128 && gemm_ksplit(M, K, N, mean) > 1;
 }
 
-int32_t gemm_col_tiles(int32_t M, int32_t N) {
-    return gemm_use_tile(M, N, 0) ? gemm_tile_col_tiles(M, N) : (N + pick_bn(N) - 1) / pick_bn(N);
+int32_t gemm_col_tiles(int32_t M, int32_t K, int32_t N) {
+    return gemm_use_tile(M, K, N, 0, 1) ? gemm_tile_col_tiles(M, N) : (N + pick_bn(N) - 1) / pick_bn(N);
 }
 
-LaunchShape gemm_shape(int32_t M, int32_t, int32_t N, int32_t softmax) {
-    if (gemm_use_tile(M, N, softmax)) return gemm_tile_shape(M, N);
+size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean) {
+    if (mean) return (size_t)gemm_col_tiles(M, K, N) * (size_t)M * 4;
+    if (!gemm_use_tile(M, K, N, softmax, 0)) return 0;
+    const int32_t s = gemm_ksplit(M, K, N, 0);
+    return s > 1 ? (size_t)s * (size_t)M * (size_t)N * 4 : 0;
+}
+
+LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean) {
+    if (gemm_use_tile(M, K, N, softmax, mean)) return gemm_tile_shape(M, N, gemm_ksplit(M, K, N, mean));
     const int bn = pick_bn(N);
     LaunchShape s{};
     s.grid[0] = (uint32_t)((M + BM - 1) / BM); s.grid[1] = (uint32_t)((N + bn - 1) / bn); s.grid[2] = 1;
@@ -297,7 +306,11 @@ hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
     const bool split_softmax = p.softmax && p.N > kGemmSoftmaxMaxN;
     if (split_softmax) p.softmax = 0;
     hipError_t e;
-    if (gemm_use_tile(p.M, p.N, p0.softmax)) e = gemm_tile_launch(p, stream);
+    p.ksplit = 1;
+    if (gemm_use_tile(p.M, p.K, p.N, p0.softmax, p.mean)) {
+        p.ksplit = gemm_ksplit(p.M, p.K, p.N, p.mean);
+        e = gemm_tile_launch(p, stream);
+    }
     else switch (pick_bn(p.N)) {
         case 64: e = launch_bn<64>(p, stream); break;
         case 128: e = launch_bn<128>(p, stream); break;
@@ -305,7 +318,7 @@ hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
     }
     if (e == hipSuccess && split_softmax) return softmax_launch(SoftmaxParams{p.Y, p.Y, p.M, p.N}, stream);
     if (e != hipSuccess || !p.mean) return e;
-    return rows_finish_launch(p.ws, p.Y, p.M, gemm_col_tiles(p.M, p.N), p.N, p.softmax2, stream);
+    return rows_finish_launch(p.ws, p.Y, p.M, gemm_col_tiles(p.M, p.K, p.N), p.N, p.softmax2, stream);
 }
 
 }  // namespace hpct

@@ -60,11 +60,19 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
     }
     // grouped order: runs of 8 tile rows, column-major inside a run, so such a range covers a compact
     // block of tiles (8 rows x n columns) and shares both its A rows and its B columns in L2
-    const int tiles_m = items / tiles_n;
+    const int tiles = items / p.ksplit;
+    const int ks = item / tiles;          // K slice (0 without split-K); a slice's tiles are neighbours
+    item -= ks * tiles;
+    const int tiles_m = tiles / tiles_n;
     const int run = item / (8 * tiles_n), in_run = item - run * 8 * tiles_n;
     const int rows = tiles_m - run * 8 < 8 ? tiles_m - run * 8 : 8;
     const int tm = run * 8 + in_run % rows, tn = in_run / rows;
     const int m0 = tm * TM, n0 = tn * TN;
+    // this work-group's slice of K (split-K: the slices' partial products go to the workspace and
+    // split_k_finish adds them in slice order and applies the epilogue)
+    const int kc = p.ksplit > 1 ? (((K + p.ksplit - 1) / p.ksplit + BK - 1) / BK) * BK : K;
+    const int k_lo = ks * kc;
+    const int k_hi = k_lo + kc < K ? k_lo + kc : K;
 
     // staging coordinates: A rows ar (+64) at k offset ak; B rows bk (+ BSTEP) at column offset bn
     constexpr int BSTEP = kThreads / (TN / 4);   // B rows covered by one pass of the work-group
@@ -80,18 +88,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
             const int m = m0 + ar + 64 * i, k = k0 + ak;
             const float* src = X + (int64_t)m * K + k;
             if (VEC) {
-                ra[i] = load4((m < M && k < K) ? src : X);
+                ra[i] = load4((m < M && k < k_hi) ? src : X);
             } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) ra[i][e] = *((m < M && k + e < K) ? src + e : X);
+                for (int e = 0; e < 4; ++e) ra[i][e] = *((m < M && k + e < k_hi) ? src + e : X);
             }
             const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
             const float* wsrc = W + (int64_t)kk * N + n;
             if (VEC) {
-                rb[i] = load4((kk < K && n < N) ? wsrc : W);
+                rb[i] = load4((kk < k_hi && n < N) ? wsrc : W);
             } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) rb[i][e] = *((kk < K && n + e < N) ? wsrc + e : W);
+                for (int e = 0; e < 4; ++e) rb[i][e] = *((kk < k_hi && n + e < N) ? wsrc + e : W);
             }
         }
     };
@@ -103,8 +111,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
             const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (!(m < M && k + e < K)) ra[i][e] = 0.f;
-                if (!(kk < K && n + e < N)) rb[i][e] = 0.f;
+                if (!(m < M && k + e < k_hi)) ra[i][e] = 0.f;
+                if (!(kk < k_hi && n + e < N)) rb[i][e] = 0.f;
             }
             *reinterpret_cast<float4v*>(&As[buf][(ar + 64 * i) * LDA + ak]) = ra[i];
             *reinterpret_cast<float4v*>(&Bs[buf][(bk + BSTEP * i) * LDB + bn]) = rb[i];
@@ -143,18 +151,34 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
         __builtin_amdgcn_s_setprio(0);
     };
 
-    const int nk = (K + BK - 1) / BK;
-    fetch(0);
-    stash(0, 0);
+    const int nk = (k_hi - k_lo + BK - 1) / BK;
+    fetch(k_lo);
+    stash(k_lo, 0);
     __syncthreads();
     for (int t = 0; t + 1 < nk; ++t) {
-        fetch((t + 1) * BK);
+        fetch(k_lo + (t + 1) * BK);
         __builtin_amdgcn_sched_barrier(0);  // the next chunk's loads are in flight before the MFMAs start
         compute(t & 1);
-        stash((t + 1) * BK, (t + 1) & 1);
+        stash(k_lo + (t + 1) * BK, (t + 1) & 1);
         __syncthreads();
     }
     compute((nk - 1) & 1);
+
+    if (p.ksplit > 1) {  // uniform over the grid: raw partial products of this K slice
+        float* __restrict__ part = p.ws + (int64_t)ks * M * N;
+#pragma unroll
+        for (int j = 0; j < WB; ++j) {
+            const int col = n0 + wn * (TN / 2) + j * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < WB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wm * (TM / 2) + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    if (col < N && row < M) part[(int64_t)row * N + col] = acc[i][j][r];
+                }
+        }
+        return;
+    }
 
     // ---- epilogue in registers
     const float* __restrict__ bias = p.bias;
@@ -199,6 +223,38 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
             }
         __syncthreads();
         if (tid < TM && m0 + tid < M) p.ws[(int64_t)tn * M + m0 + tid] = rs[0][tid] + rs[1][tid];
+    }
+}
+
+// Y = epilogue(sum_s ws[s]): the K slices' partial products added in slice order, then bias, ReLU
+// and the hash dropout as in the tile kernel's own epilogue.  A thread per four columns when N % 4 == 0.
+template <bool VEC>
+__global__ __launch_bounds__(256) void split_k_finish(GemmParams p) {
+    constexpr int E = VEC ? 4 : 1;
+    const int64_t total = (int64_t)p.M * p.N / E, plane = (int64_t)p.M * p.N;
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < total; v += (int64_t)gridDim.x * 256) {
+        const int64_t idx = v * E;
+        float x[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) x[e] = 0.f;
+        for (int s = 0; s < p.ksplit; ++s) {
+            if (VEC) {
+                const float4v t = load4_nt(p.ws + s * plane + idx);
+                x[0] += t.x; x[1 % E] += t.y; x[2 % E] += t.z; x[3 % E] += t.w;
+            } else {
+                x[0] += p.ws[s * plane + idx];
+            }
+        }
+        const int row = (int)(idx / p.N), col = (int)(idx - (int64_t)row * p.N);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float y = x[e] + (p.bias ? p.bias[col + e] : 0.f);
+            if (p.relu) y = fmaxf(y, 0.f);
+            if (p.dropout) y = dropout_u((uint64_t)idx + (uint64_t)e + p.seed) < p.drop_t ? 0.f : y * p.keep_scale;
+            x[e] = y;
+        }
+        if (VEC) store4_nt(p.Y + idx, float4v{x[0], x[1 % E], x[2 % E], x[3 % E]});
+        else p.Y[idx] = x[0];
     }
 }
 
@@ -258,6 +314,18 @@ __global__ __launch_bounds__(kFinThreads) void vector_softmax(float* __restrict_
 
 }  // namespace
 
+// K slices for outputs whose 64 x 64 tiles alone cannot fill the chip: enough slices for about two
+// work-groups per CU, each at least 256 deep, at most 8.  Not with the fused row sums.
+int32_t gemm_ksplit(int32_t M, int32_t K, int32_t N, int32_t mean) {
+    if (mean) return 1;
+    const int64_t tiles64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64);
+    if (tiles64 >= 512) return 1;
+    int64_t s = (512 + tiles64 - 1) / tiles64;
+    if (s > K / 256) s = K / 256;
+    if (s > 8) s = 8;
+    return s < 2 ? 1 : (int32_t)s;
+}
+
 // 128 x 128 tiles when there are at least two per CU and they spread evenly over the 256 CUs
 // (the busiest CU within 15 % of the average); otherwise 64 x 64 tiles, four times as many.
 // Measured at K = 1024: 2048^2 85 -> 96 TFLOP/s, 2560^2 84 -> 92, 1536^2 47 -> 66 with the small tiles.
@@ -267,13 +335,13 @@ int gemm_tile_edge(int32_t M, int32_t N) {
     return (tiles >= 512 && tiles * 100 >= per_cu * 256 * 85) ? 128 : 64;
 }
 
-LaunchShape gemm_tile_shape(int32_t M, int32_t N) {
+LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit) {
     const int t = gemm_tile_edge(M, N);
     LaunchShape s{};
-    s.grid[0] = (uint32_t)(((M + t - 1) / t) * ((N + t - 1) / t)); s.grid[1] = s.grid[2] = 1;
+    s.grid[0] = (uint32_t)(((M + t - 1) / t) * ((N + t - 1) / t) * ksplit); s.grid[1] = s.grid[2] = 1;
     s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
     s.lds_bytes = (uint32_t)((2 * t * LDA + 2 * BK * (t + 8) + 2 * t) * 4);
-    s.kernel = t == 128 ? "gemm_tile128" : "gemm_tile64";
+    s.kernel = t == 128 ? "gemm_tile128" : (ksplit > 1 ? "gemm_tile64<split-k>" : "gemm_tile64");
     return s;
 }
 
@@ -282,7 +350,7 @@ int32_t gemm_tile_col_tiles(int32_t M, int32_t N) { const int t = gemm_tile_edge
 template <int T>
 hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
     const int tiles_m = (p.M + T - 1) / T, tiles_n = (p.N + T - 1) / T;
-    const int items = tiles_m * tiles_n;
+    const int items = tiles_m * tiles_n * p.ksplit;
     const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
     if (vec) hipLaunchKernelGGL((gemm_tile<T, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
     else hipLaunchKernelGGL((gemm_tile<T, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
@@ -290,7 +358,14 @@ hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
 }
 
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream) {
-    return gemm_tile_edge(p.M, p.N) == 128 ? launch_tile<128>(p, stream) : launch_tile<64>(p, stream);
+    hipError_t e = gemm_tile_edge(p.M, p.N) == 128 ? launch_tile<128>(p, stream) : launch_tile<64>(p, stream);
+    if (e != hipSuccess || p.ksplit <= 1) return e;
+    const bool vec = p.N % 4 == 0;
+    const int64_t work = (int64_t)p.M * p.N / (vec ? 4 : 1);
+    const unsigned grid = (unsigned)((work + 255) / 256 < 4096 ? (work + 255) / 256 : 4096);
+    if (vec) hipLaunchKernelGGL((split_k_finish<true>), dim3(grid), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((split_k_finish<false>), dim3(grid), dim3(256), 0, stream, p);
+    return hipGetLastError();
 }
 
 hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream) {

@@ -245,10 +245,11 @@ def gemm_bias_relu_softmax_plan(X, W, bias, out, relu=True, softmax=True):
     return plan, ins
 
 
-def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, stream=None) -> None:
-    """out = softmax_rows(relu(X @ W + bias)); relu / softmax / bias optional."""
+def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, workspace=None, stream=None) -> None:
+    """out = softmax_rows(relu(X @ W + bias)); relu / softmax / bias optional.  `workspace`: GPU tensor of at
+    least plan.workspace_bytes bytes when that is not 0 (small outputs with a long K are computed in K slices)."""
     plan, ins = gemm_bias_relu_softmax_plan(X, W, bias, out, relu, softmax)
-    plan.launch(ins, [out], stream)
+    plan.launch(ins, [out], stream, workspace)
 
 
 def matmul_dropout_mean_softmax_plan(X, W, bias, out, p, seed, stop_after="softmax", relu=False):

@@ -486,3 +486,15 @@ def test_attention_head_dims():
         assert p.launch_shape()[2] == 2 * 64 * (2 * D + 12) * 4      # two stages of 64 keys, K and V rows padded by 4 and 8
         d.n_epi = 2; d.epi[1] = H.HPCT_EPI_CAUSAL_MASK
         assert H.Plan(d).kernel_name == causal
+
+
+def test_gemm_split_k_plans():
+    g = H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0,
+                  [(1024, 4096), (4096, 1024), (1024,)], [(1024, 1024)])
+    p = H.Plan(g)
+    assert p.kernel_name == "gemm_tile64<split-k>"
+    assert p.workspace_bytes == 2 * 1024 * 1024 * 4 and p.launch_shape()[0] == (16 * 16 * 2, 1, 1)
+    # a short K is not split, and neither is the chain with fused row sums
+    g = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_NONE, 0, [(1024, 256), (256, 1024)], [(1024, 1024)])
+    assert H.Plan(g).kernel_name == "gemm_tile64" and H.Plan(g).workspace_bytes == 0
+    assert H.Plan(chain6_desc(1024, 4096, 1024)).kernel_name == "gemm_tile64"

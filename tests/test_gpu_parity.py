@@ -43,7 +43,9 @@ def run_chain1(t, relu=True, softmax=True, bias=True):
     X, W = dev(t["X"]), dev(t["W"])
     b = dev(t["bias"]) if bias else None
     out = torch.full((X.shape[0], W.shape[1]), float("nan"), device="cuda")
-    hpct.gemm_bias_relu_softmax(X, W, b, out, relu=relu, softmax=softmax)
+    plan, ins = hpct.gemm_bias_relu_softmax_plan(X, W, b, out, relu=relu, softmax=softmax)
+    ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda") if plan.workspace_bytes else None
+    plan.launch(ins, [out], workspace=ws)
     return host(out)
 
 
@@ -82,6 +84,32 @@ def test_chain1_rows_wider_than_a_tile(M, K, N):
     print("chain1 wide M=%d K=%d N=%d" % (M, K, N), flush=True)
     t = datagen.make(1, M=M, K=K, N=N)
     assert show("softmax", compare.pointwise(run_chain1(t), ref.chain1(t["X"], t["W"], t["bias"])))
+
+
+@pytest.mark.parametrize("M,K,N", [(256, 2048, 256), (1024, 4096, 1024), (512, 1030, 512), (200, 3000, 333), (128, 8192, 512)])
+def test_gemm_split_k(M, K, N):
+    print("split-k M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    X, W, b = dev(t["X"]), dev(t["W"]), dev(t["bias"])
+    out = torch.full((M, N), float("nan"), device="cuda")
+    plan, ins = hpct.gemm_bias_relu_softmax_plan(X, W, b, out, relu=True, softmax=False)
+    assert plan.kernel_name == "gemm_tile64<split-k>" and plan.workspace_bytes % (M * N * 4) == 0
+    ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda")
+    plan.launch(ins, [out], workspace=ws)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    got = host(out)
+    assert show("split-k gemm+bias+relu", compare.contraction(got, ref.relu(Z), Dn))
+    assert np.max(np.abs(got - ref.relu(Z)) / Dn) < 1e-5
+    # with the softmax over wide rows behind it, and with the dropout epilogue
+    assert show("softmax", compare.pointwise(run_chain1(t), ref.chain1(t["X"], t["W"], t["bias"])))
+    t6 = dict(t)
+    D = ref.dropout_hash(Z, 0.25, 99)
+    got, name = run_chain6(t6, 0.25, 99, "dropout")
+    assert name == "gemm_tile64<split-k>"
+    assert np.array_equal(got == 0, D == 0)
+    assert show("dropout", compare.contraction(got, D, Dn / 0.75))
+    again, _ = run_chain6(t6, 0.25, 99, "dropout")
+    assert np.array_equal(got, again)
 
 
 def test_gemm_identity_weight_is_exact():
@@ -168,8 +196,9 @@ def test_tiled_gemm_bias_relu(M, K, N):
     X, W, b = dev(t["X"]), dev(t["W"]), dev(t["bias"])
     out = torch.full((M, N), float("nan"), device="cuda")
     plan, ins = hpct.gemm_bias_relu_softmax_plan(X, W, b, out, relu=True, softmax=False)
-    assert plan.kernel_name in ("gemm_tile128", "gemm_tile64")
-    plan.launch(ins, [out])
+    assert plan.kernel_name in ("gemm_tile128", "gemm_tile64", "gemm_tile64<split-k>")
+    ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda") if plan.workspace_bytes else None
+    plan.launch(ins, [out], workspace=ws)
     Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
     assert show("tiled gemm+bias+relu", compare.contraction(host(out), ref.relu(Z), Dn))
     assert np.max(np.abs(host(out) - ref.relu(Z)) / Dn) < 1e-5
