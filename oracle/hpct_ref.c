@@ -416,3 +416,28 @@ void ref_attention_causal(const float *Q, const float *K, const float *V,
         free(s);
     }
 }
+
+/* ---- Elementwise (Table 1: "add, mul, relu") on two strided views of the same
+ * shape; broadcasting is a stride of 0.  out[i0]..[i_{nd-1}] (row-major) =
+ * f(a[sum i_d * sa[d]], b[sum i_d * sb[d]]) with f = a + b (op 0) or a * b
+ * (op 1), followed by max(., 0) when relu != 0.  The fp32 operands are widened
+ * to double (the product of two fp32 values is exact in double). */
+void ref_eltwise_binary(const float *a, const float *b, int32_t nd, const int64_t *shape,
+                        const int64_t *sa, const int64_t *sb, int32_t op, int32_t relu, double *out)
+{
+    int64_t total = 1;
+    for (int32_t d = 0; d < nd; ++d) total *= shape[d];
+#pragma omp parallel for schedule(static)
+    for (int64_t lin = 0; lin < total; ++lin) {
+        int64_t rem = lin, oa = 0, ob = 0;
+        for (int32_t d = nd - 1; d >= 0; --d) {
+            int64_t i = rem % shape[d];
+            oa += i * sa[d];
+            ob += i * sb[d];
+            rem /= shape[d];
+        }
+        double x = (double)a[oa], y = (double)b[ob];
+        double v = op == 0 ? x + y : x * y;
+        out[lin] = (relu && v < 0.0) ? 0.0 : v;
+    }
+}

@@ -42,6 +42,7 @@ def lib():
             "ref_scale_shift_planes": [p, p, p, i64, i64, i64],
             "ref_maxpool2x2_planes": [p, i64, i64, i64, p],
             "ref_reduce_axis": [p, C.c_int32, p, p, C.c_int32, C.c_int32, p, p, p],
+            "ref_eltwise_binary": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p],
         }
         for name, args in sig.items():
             f = getattr(_lib, name)
@@ -213,6 +214,21 @@ def maxpool2x2(T):
     out = np.empty((Nb, Cc, H // 2, W // 2), dtype=np.float64)
     if out.size:
         lib().ref_maxpool2x2_planes(_ptr(T), Nb * Cc, H, W, _ptr(out))
+    return out
+
+
+def eltwise_binary(a_base, b_base, shape, sa, sb, op, relu_=False):
+    """out = [relu](a_view op b_view), op in {"add", "mul"}; the views (shape, strides in elements, stride 0 =
+    broadcast) are taken over the flat fp32 arrays a_base and b_base."""
+    a_base, b_base = _f32(a_base).reshape(-1), _f32(b_base).reshape(-1)
+    nd = len(shape)
+    assert all(s >= 0 for s in sa) and all(s >= 0 for s in sb)
+    assert sum((n - 1) * s for n, s in zip(shape, sa)) < a_base.size
+    assert sum((n - 1) * s for n, s in zip(shape, sb)) < b_base.size
+    sh = (C.c_int64 * nd)(*shape)
+    out = np.empty(tuple(shape), dtype=np.float64)
+    lib().ref_eltwise_binary(_ptr(a_base), _ptr(b_base), nd, sh, (C.c_int64 * nd)(*sa), (C.c_int64 * nd)(*sb),
+                             {"add": 0, "mul": 1}[op], 1 if relu_ else 0, _ptr(out))
     return out
 
 

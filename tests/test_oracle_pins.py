@@ -728,3 +728,26 @@ def test_dilated_conv_brute_force_and_tap_positions():
     # dil = 1 is the undilated operator
     w3 = f32(rng.normal(size=(2, 1, 3, 3)))
     assert np.array_equal(ref.conv2d_nchw_bias(x, w3, None, 1, 1, dil=1), ref.conv2d_nchw_bias(x, w3, None, 1, 1))
+
+
+# ------------------------------------------------ elementwise on strided views
+def test_eltwise_binary_against_numpy_broadcasting():
+    a = f32(rng.normal(size=(4, 5, 6))); row = f32(rng.normal(size=6)); col = f32(rng.normal(size=(4, 1, 1)))
+    A = a.astype(np.float64)
+    # same shape, a bias row broadcast over the leading dims, a per-slab scalar, a transposed operand
+    got = ref.eltwise_binary(a, a[::-1].copy(), (4, 5, 6), (30, 6, 1), (30, 6, 1), "add")
+    assert np.array_equal(got, A + A[::-1])
+    got = ref.eltwise_binary(a, row, (4, 5, 6), (30, 6, 1), (0, 0, 1), "add", relu_=True)
+    assert np.array_equal(got, np.maximum(A + row.astype(np.float64), 0.0))
+    got = ref.eltwise_binary(a, col, (4, 5, 6), (30, 6, 1), (1, 0, 0), "mul")
+    assert np.array_equal(got, A * col.astype(np.float64))
+    sq = f32(rng.normal(size=(7, 7)))
+    got = ref.eltwise_binary(sq, sq, (7, 7), (7, 1), (1, 7), "mul")
+    assert np.array_equal(got, sq.astype(np.float64) * sq.T.astype(np.float64))
+    # closed forms: x + 0 = x, x * 1 = x, relu(x * -1) = relu(-x); an fp32 product is exact in fp64
+    z = np.zeros(1, np.float32); one = np.ones(1, np.float32); neg = -one
+    assert np.array_equal(ref.eltwise_binary(a, z, (4, 5, 6), (30, 6, 1), (0, 0, 0), "add"), A)
+    assert np.array_equal(ref.eltwise_binary(a, one, (4, 5, 6), (30, 6, 1), (0, 0, 0), "mul"), A)
+    assert np.array_equal(ref.eltwise_binary(a, neg, (4, 5, 6), (30, 6, 1), (0, 0, 0), "mul", relu_=True), np.maximum(-A, 0.0))
+    x = f32([1.0000001, 3.3333333]); y = f32([1.0000002, 0.3333333])
+    assert np.array_equal(ref.eltwise_binary(x, y, (2,), (1,), (1,), "mul"), x.astype(np.float64) * y.astype(np.float64))
