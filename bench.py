@@ -224,6 +224,24 @@ def main() -> int:
         reduce_ops.append(dict(op="softmax_rows_8192x4096", kernel=plan_s.kernel_name, avg_us=round(us, 3),
                                achieved=round(nb / us / 1e3, 1), unit="GB/s", peak=HBM_PEAK_GBS,
                                frac=round(nb / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=len(calls_s)))
+        # elementwise chain on views (Table 1 Elementwise "add, relu"): matrix + bias row, ReLU
+        calls_e = []
+        for s_ in sets[3]:
+            plan_e, ins_e = hpct.eltwise_plan(s_["ins"][0], s_["ins"][1].expand(8192, 4096), s_["out"], "add", True)
+            calls_e.append(plan_e.bind(ins_e, [s_["out"]]))
+        for k in range(min(args.warmup, 10)):
+            calls_e[k % len(calls_e)]()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(args.steps):
+            calls_e[k % len(calls_e)]()
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / args.steps
+        nb = 2 * ms[0].numel() * 4 + 4096 * 4
+        reduce_ops.append(dict(op="add_bias_row_relu_8192x4096", kernel=plan_e.kernel_name, avg_us=round(us, 3),
+                               achieved=round(nb / us / 1e3, 1), unit="GB/s", peak=HBM_PEAK_GBS,
+                               frac=round(nb / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=len(calls_e)))
         xs = [s_["ins"][0] for s_ in sets[2]]                  # 11 NCHW tensors [32,64,56,56]
         time_reduce("argmax_channels_32x64x56x56", xs, 1, "argmax", (32, 56, 56), xs[0].numel() * 4 + 32 * 3136 * 4)
         time_reduce("mean_channels_32x64x56x56", xs, 1, "mean", (32, 56, 56), xs[0].numel() * 4 + 32 * 3136 * 4)

@@ -17,7 +17,7 @@
  *    shape and stride in ELEMENTS.
  *  - Every data pointer passed to hpct_plan_launch is a DEVICE pointer owned
  *    by the caller, 16-byte aligned (4-byte aligned suffices for a layout
- *    transform or an axis reduction, whose input may be a view that starts anywhere).  Descriptors, plans and the pointer
+ *    transform, an axis reduction or an elementwise chain on views, whose inputs may start anywhere).  Descriptors, plans and the pointer
  *    arrays themselves live in HOST memory.
  *  - The library never allocates, frees, copies or synchronises device memory.
  *    Inputs are never written.  Outputs must not overlap inputs.
@@ -41,6 +41,9 @@
  *   NONE  LAYERNORM_LAST (reduce_before_epi=1)        X[M,N], gamma[N], beta[N]     [M,N]
  *         [+GELU_TANH]
  *   NONE  SOFTMAX_LAST                                X[M,N]                        [M,N]
+ *   NONE  ADD_TENSOR | MUL_TENSOR [+RELU],            A, B: strided views of one    that shape,
+ *         no reduction: out = [relu](A op B)          shape (stride >= 0, 0 =       contiguous
+ *                                                     broadcast, up to 6 dims)
  *   NONE  (no epilogue, no reduction): layout         X: any strided view (stride   same shape,
  *         transform, out = contiguous copy of X       >= 0, up to 6 dims)           contiguous
  *   NONE  SUM_AXIS | MEAN_AXIS | ARGMAX_AXIS |        X: any strided view (stride   X's shape without
@@ -114,7 +117,9 @@ typedef enum {
                                      h ^= h >> 17; h ^= h << 31; h ^= h >> 8; rand = (float)(h % 1000) / 1000.0f;
                                      the element becomes 0 when rand < dropout_p (fp32 compare) and is multiplied
                                      by 1 / (1 - dropout_p) otherwise.  GEMM anchor only. */
-    HPCT_EPI_CAUSAL_MASK = 7      /* on the scores of BGEMM_SOFTMAX_BGEMM: query i attends keys j <= i only */
+    HPCT_EPI_CAUSAL_MASK = 7,     /* on the scores of BGEMM_SOFTMAX_BGEMM: query i attends keys j <= i only */
+    HPCT_EPI_ADD_TENSOR = 8,      /* + in[1], a strided view of the same shape (stride 0 = broadcast).  No anchor. */
+    HPCT_EPI_MUL_TENSOR = 9       /* * in[1], likewise */
 } hpct_epilogue;
 
 /* Row reductions (Table 1, Reduction). */

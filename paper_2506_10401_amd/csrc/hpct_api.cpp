@@ -26,7 +26,7 @@ hpct_status fail(hpct_status st, const char* fmt, ...) {
 
 void clear_err() { g_err[0] = 0; }
 
-enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce };
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise };
 
 constexpr int64_t kI32Max = 2147483647LL;
 
@@ -51,6 +51,7 @@ struct hpct_plan {
         AttnParams attn;
         LayoutParams layout;
         ReduceParams red;
+        EltwiseParams elt;
     } u;
 };
 
@@ -292,6 +293,47 @@ hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p) {
     return HPCT_OK;
 }
 
+// out = [relu](A op B) on two strided views of one shape; contiguous output.
+hpct_status plan_eltwise(const hpct_op_desc& d, hpct_plan& p) {
+    bool relu = false;
+    if (d.n_epi == 2 && d.epi[1] == HPCT_EPI_RELU) relu = true;
+    else if (d.n_epi != 1) return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: epilogues must be ADD_TENSOR | MUL_TENSOR [RELU]");
+    if (d.reduce != HPCT_RED_NONE) return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: no reduction is supported after it");
+    if (d.n_in != 2 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "an elementwise chain on views takes 2 inputs and 1 output");
+    const hpct_tensor_desc &A = d.in[0], &B = d.in[1], &O = d.out[0];
+    if (A.ndim != B.ndim || A.ndim != O.ndim) return fail(HPCT_ERR_SHAPE_MISMATCH, "elementwise chain: both views and the output must have the same shape");
+    for (int k = 0; k < A.ndim; ++k)
+        if (A.shape[k] != B.shape[k] || A.shape[k] != O.shape[k])
+            return fail(HPCT_ERR_SHAPE_MISMATCH, "elementwise chain: both views and the output must have the same shape");
+    if (!contiguous(O)) return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain: the output must be contiguous");
+    EltwiseParams q{};
+    int nd = 0;
+    for (int k = 0; k < A.ndim; ++k) {   // drop extent 1, merge neighbours that are contiguous with each other in both views
+        if (A.shape[k] == 1) continue;
+        if (nd > 0 && q.sa[nd - 1] == A.shape[k] * A.stride[k] && q.sb[nd - 1] == B.shape[k] * B.stride[k]) {
+            q.shape[nd - 1] *= A.shape[k];
+            q.sa[nd - 1] = A.stride[k];
+            q.sb[nd - 1] = B.stride[k];
+        } else {
+            q.shape[nd] = A.shape[k]; q.sa[nd] = A.stride[k]; q.sb[nd] = B.stride[k]; ++nd;
+        }
+    }
+    if (nd == 0) { q.shape[0] = 1; q.sa[0] = 1; q.sb[0] = 1; nd = 1; }
+    q.nd = nd;
+    q.total = 1;
+    for (int k = 0; k < nd; ++k) q.total *= q.shape[k];
+    q.op = d.epi[0] == HPCT_EPI_ADD_TENSOR ? 0 : 1;
+    q.relu = relu ? 1 : 0;
+    bool vec = q.shape[nd - 1] % 4 == 0 && q.sa[nd - 1] == 1 && (q.sb[nd - 1] == 1 || q.sb[nd - 1] == 0);
+    for (int k = 0; k + 1 < nd; ++k) vec = vec && q.sa[k] % 4 == 0 && (q.sb[k] % 4 == 0 || q.sb[nd - 1] == 0);
+    q.vec = vec ? 1 : 0;
+    p.kind = Kind::Eltwise;
+    p.u.elt = q;
+    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
+    p.shape = eltwise_shape(q);
+    return HPCT_OK;
+}
+
 // Reduction over one axis of a strided view: no anchor, no epilogue; the output is the view
 // without that axis, contiguous.
 hpct_status plan_reduce(const hpct_op_desc& d, hpct_plan& p) {
@@ -448,7 +490,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)
-        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_CAUSAL_MASK) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
+        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_MUL_TENSOR) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
 
     hpct_plan tmp;
     std::memset(&tmp, 0, sizeof tmp);
@@ -478,7 +520,8 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         default:
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
             if (d.reduce == HPCT_RED_MAXPOOL2_HW) return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL2_HW is supported only after a conv anchor");
-            if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);
+            if (d.n_epi >= 1 && (d.epi[0] == HPCT_EPI_ADD_TENSOR || d.epi[0] == HPCT_EPI_MUL_TENSOR)) st = plan_eltwise(d, tmp);
+            else if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);
             else if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
             else if (d.reduce == HPCT_RED_NONE && d.n_epi == 0 && d.n_in >= 1 &&
                      !(d.in[0].ndim == 4 && contiguous(d.in[0]))) st = plan_layout(d, tmp);
@@ -504,7 +547,7 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
     }
     // layout transforms accept views that start anywhere (element alignment); their vector variant is
     // replaced by the scalar one at launch when a base is not 16-byte aligned
-    const uintptr_t amask = (plan->kind == Kind::Layout || plan->kind == Kind::Reduce) ? 3 : 15;
+    const uintptr_t amask = (plan->kind == Kind::Layout || plan->kind == Kind::Reduce || plan->kind == Kind::Eltwise) ? 3 : 15;
     for (int i = 0; i < plan->n_in; ++i) {
         if (!in_ptrs[i]) return fail(HPCT_ERR_NULL, "in_ptrs[%d] is NULL", i);
         if ((uintptr_t)in_ptrs[i] & amask) return fail(HPCT_ERR_ALIGNMENT, "in_ptrs[%d] is not %d-byte aligned", i, (int)amask + 1);
@@ -569,6 +612,13 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
             q.in = in(0); q.out = (float*)out_ptrs[0];
             if (q.kind == 1 && (((uintptr_t)q.in | (uintptr_t)q.out) & 15)) q.kind = 0;
             e = layout_launch(q, stream);
+            break;
+        }
+        case Kind::Eltwise: {
+            EltwiseParams q = plan->u.elt;
+            q.a = in(0); q.b = in(1); q.out = (float*)out_ptrs[0];
+            if (q.vec && (((uintptr_t)q.a | (uintptr_t)q.b | (uintptr_t)q.out) & 15)) q.vec = 0;
+            e = eltwise_launch(q, stream);
             break;
         }
         case Kind::Reduce: {

@@ -54,6 +54,22 @@ struct LayoutParams {
 LaunchShape layout_shape(const LayoutParams& p);
 hipError_t layout_launch(const LayoutParams& p, hipStream_t stream);
 
+// ---- out = [relu](a op b) on two strided views of one shape (Table 1: Elementwise "add, mul, relu")
+constexpr int kEltwiseDims = 6;
+struct EltwiseParams {
+    const float* a; const float* b; float* out;
+    int32_t nd;                      // collapsed dimensions, 1..kEltwiseDims
+    int64_t shape[kEltwiseDims];
+    int64_t sa[kEltwiseDims];        // strides of a (elements), 0 = broadcast
+    int64_t sb[kEltwiseDims];        // strides of b
+    int64_t total;                   // elements
+    int32_t op;                      // 0 add, 1 mul
+    int32_t relu;
+    int32_t vec;                     // 128-bit access possible by the strides (pointers are checked at launch)
+};
+LaunchShape eltwise_shape(const EltwiseParams& p);
+hipError_t eltwise_launch(const EltwiseParams& p, hipStream_t stream);
+
 // ---- sum / mean / argmax / argmin over one axis of a strided view (Table 1: Reduction)
 constexpr int kReduceDims = 5;
 struct ReduceParams {

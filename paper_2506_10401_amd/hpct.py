@@ -23,7 +23,7 @@ STATUS_NAMES = ["HPCT_OK", "HPCT_ERR_NULL", "HPCT_ERR_BAD_DESC", "HPCT_ERR_SHAPE
 HPCT_F32, HPCT_I32 = 0, 1
 HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW = range(4)
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
-    HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH, HPCT_EPI_CAUSAL_MASK = range(8)
+    HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH, HPCT_EPI_CAUSAL_MASK, HPCT_EPI_ADD_TENSOR, HPCT_EPI_MUL_TENSOR = range(10)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS = range(10)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
@@ -324,6 +324,22 @@ def layout_transform_plan(x_view, out):
 def layout_transform(x_view, out, stream=None) -> None:
     """out = contiguous copy of the strided view x_view (transpose, NCHW <-> NHWC, slices, broadcasts)."""
     plan, ins = layout_transform_plan(x_view, out)
+    plan.launch(ins, [out], stream)
+
+
+def eltwise_plan(a_view, b_view, out, op, relu=False):
+    """a_view, b_view: fp32 GPU tensor views of one shape (expand() for broadcasting); out: contiguous, same shape."""
+    shape = _sh(a_view)
+    sa, sb = tuple(int(v) for v in a_view.stride()), tuple(int(v) for v in b_view.stride())
+    epi = [HPCT_EPI_ADD_TENSOR if op == "add" else HPCT_EPI_MUL_TENSOR] + ([HPCT_EPI_RELU] if relu else [])
+    plan = _cached(("eltwise", shape, sa, sb, op, relu), lambda: op_desc(
+        HPCT_ANCHOR_NONE, epi, HPCT_RED_NONE, 0, [tensor_desc(shape, sa), tensor_desc(_sh(b_view), sb)], [_sh(out)]))
+    return plan, [a_view, b_view]
+
+
+def eltwise(a_view, b_view, out, op, relu=False, stream=None) -> None:
+    """out = [relu](a_view + b_view) or [relu](a_view * b_view); op in {"add", "mul"}."""
+    plan, ins = eltwise_plan(a_view, b_view, out, op, relu)
     plan.launch(ins, [out], stream)
 
 

@@ -498,3 +498,30 @@ def test_gemm_split_k_plans():
     g = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_NONE, 0, [(1024, 256), (256, 1024)], [(1024, 1024)])
     assert H.Plan(g).kernel_name == "gemm_tile64" and H.Plan(g).workspace_bytes == 0
     assert H.Plan(chain6_desc(1024, 4096, 1024)).kernel_name == "gemm_tile64"
+
+
+def eltwise_desc(shape, sa, sb, add=True, relu=False, out_shape=None):
+    epi = [H.HPCT_EPI_ADD_TENSOR if add else H.HPCT_EPI_MUL_TENSOR] + ([H.HPCT_EPI_RELU] if relu else [])
+    return H.op_desc(H.HPCT_ANCHOR_NONE, epi, H.HPCT_RED_NONE, 0, [H.tensor_desc(shape, sa), H.tensor_desc(shape, sb)],
+                     [out_shape or shape])
+
+
+def test_eltwise_plans_and_errors():
+    # matrix + bias row broadcast over the rows: the last dim is contiguous in A and B -> 128-bit access
+    p = H.Plan(eltwise_desc((8192, 4096), (4096, 1), (0, 1), relu=True))
+    assert p.kernel_name == "eltwise_binary<vec4>" and p.workspace_bytes == 0
+    # per-row scalar broadcast along the last dim is vectorised too; a transposed operand is not
+    assert H.Plan(eltwise_desc((8192, 4096), (4096, 1), (1, 0), add=False)).kernel_name == "eltwise_binary<vec4>"
+    assert H.Plan(eltwise_desc((64, 64), (64, 1), (1, 64))).kernel_name == "eltwise_binary<scalar>"
+    assert H.Plan(eltwise_desc((5, 7), (7, 1), (7, 1))).kernel_name == "eltwise_binary<scalar>"
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, eltwise_desc((4, 8), (8, 1), (8, 1), out_shape=(8, 4)))
+    d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.in_[1] = H.tensor_desc((4, 4), (4, 1))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.n_epi = 2; d.epi[1] = H.HPCT_EPI_GELU_TANH
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.reduce = H.HPCT_RED_SOFTMAX_LAST
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.n_in = 1
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.epi[0] = H.HPCT_EPI_ADD_TENSOR          # not after an anchor
+    expect(H.HPCT_ERR_UNSUPPORTED, d)

@@ -643,3 +643,47 @@ def test_reduce_strided_views_ties_and_offsets():
     check_reduce(q, 0, "ties")
     check_reduce(q, 1, "ties")
     check_reduce(q.t(), 0, "ties transposed")
+
+
+# ------------------------------------------------- elementwise on strided views
+def check_eltwise(a_view, b_view, tag):
+    def flat(view):
+        base = view._base if view._base is not None else view
+        return host(base).reshape(-1)[view.storage_offset() - base.storage_offset():]
+    shape = tuple(a_view.shape)
+    sa, sb = tuple(a_view.stride()), tuple(b_view.stride())
+    names = set()
+    for op in ("add", "mul"):
+        for relu in (False, True):
+            out = torch.full(shape, float("nan"), device="cuda")
+            plan, ins = hpct.eltwise_plan(a_view, b_view, out, op, relu)
+            plan.launch(ins, [out])
+            names.add(plan.kernel_name)
+            want = ref.eltwise_binary(flat(a_view), flat(b_view), shape, sa, sb, op, relu)
+            # one fp32 rounding of an exactly known sum or product
+            assert np.array_equal(host(out), want.astype(np.float32)), (tag, op, relu)
+    return names
+
+
+def test_eltwise_full_size_bias_row_and_same_shape():
+    X = dev(datagen.make(3)["X"])
+    g = dev(datagen.make(3)["gamma"])
+    assert check_eltwise(X, g.expand(8192, 4096), "bias row") == {"eltwise_binary<vec4>"}
+    Y = dev(datagen.make(3, variant=1)["X"])
+    assert check_eltwise(X, Y, "same shape") == {"eltwise_binary<vec4>"}
+
+
+def test_eltwise_views():
+    a = dev(datagen.gen_normal(91, (6, 10, 12), 0.0, 1.0))
+    b = dev(datagen.gen_normal(92, (6, 10, 12), 0.0, 1.0))
+    check_eltwise(a, b.permute(0, 2, 1).contiguous().permute(0, 2, 1), "b transposed in memory")
+    check_eltwise(a.permute(2, 0, 1), b.permute(2, 0, 1), "both permuted")
+    check_eltwise(a, b[:, :, 0:1].expand(6, 10, 12), "scalar per row")
+    check_eltwise(a, b[0:1, 0:1, :].expand(6, 10, 12), "row")
+    check_eltwise(a, b[:, 0:1, 0:1].expand(6, 10, 12), "scalar per slab")
+    check_eltwise(a[:, 1:9, 3:11], b[:, 1:9, 2:10], "offset slices")
+    check_eltwise(a[0, 0, :7], b[1, 2, 5:12], "vectors")
+    v = dev(datagen.gen_normal(93, (2, 3, 2, 3, 2, 4), 0.0, 1.0))
+    check_eltwise(v, v.permute(1, 0, 3, 2, 5, 4).contiguous().permute(1, 0, 3, 2, 5, 4), "6-D")
+    one = dev(np.ones((1,), np.float32))
+    check_eltwise(one, one, "single element")
