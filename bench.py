@@ -243,6 +243,24 @@ def main() -> int:
                                achieved=round(nb / us / 1e3, 1), unit="GB/s", peak=HBM_PEAK_GBS,
                                frac=round(nb / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=len(calls_e)))
         xs = [s_["ins"][0] for s_ in sets[2]]                  # 11 NCHW tensors [32,64,56,56]
+        calls_p = []
+        for x in xs:
+            o = torch.empty(32, 64, 28, 28, device="cuda")
+            plan_p, ins_p = hpct.maxpool2x2_plan(x, o)
+            calls_p.append(plan_p.bind(ins_p, [o]))
+        for k in range(min(args.warmup, 10)):
+            calls_p[k % len(calls_p)]()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(args.steps):
+            calls_p[k % len(calls_p)]()
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / args.steps
+        nb = xs[0].numel() * 4 * 5 // 4
+        reduce_ops.append(dict(op="maxpool2x2_32x64x56x56", kernel=plan_p.kernel_name, avg_us=round(us, 3),
+                               achieved=round(nb / us / 1e3, 1), unit="GB/s", peak=HBM_PEAK_GBS,
+                               frac=round(nb / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=len(calls_p)))
         time_reduce("argmax_channels_32x64x56x56", xs, 1, "argmax", (32, 56, 56), xs[0].numel() * 4 + 32 * 3136 * 4)
         time_reduce("mean_channels_32x64x56x56", xs, 1, "mean", (32, 56, 56), xs[0].numel() * 4 + 32 * 3136 * 4)
 

@@ -41,6 +41,7 @@
  *   NONE  LAYERNORM_LAST (reduce_before_epi=1)        X[M,N], gamma[N], beta[N]     [M,N]
  *         [+GELU_TANH]
  *   NONE  SOFTMAX_LAST                                X[M,N]                        [M,N]
+ *   NONE  MAXPOOL2_HW (no epilogue)                   X[N,C,H,W]                    [N,C,H/2,W/2]
  *   NONE  ADD_TENSOR | MUL_TENSOR [+RELU],            A, B: strided views of one    that shape,
  *         no reduction: out = [relu](A op B)          shape (stride >= 0, 0 =       contiguous
  *                                                     broadcast, up to 6 dims)
@@ -130,7 +131,7 @@ typedef enum {
     HPCT_RED_AVGPOOL_HW = 3,      /* mean over dims 2,3 of NCHW */
     HPCT_RED_MEAN_LAST = 4,       /* mean over the last dim, which is dropped: [M,N] -> [M].  GEMM anchor only. */
     HPCT_RED_MAXPOOL2_HW = 5,     /* max over non-overlapping 2x2 windows of dims 2,3 (stride 2; an odd last row or
-                                     column is dropped): [N,K,Ho,Wo] -> [N,K,Ho/2,Wo/2].  Conv anchor only. */
+                                     column is dropped): [N,K,Ho,Wo] -> [N,K,Ho/2,Wo/2].  After a conv anchor, or alone. */
     HPCT_RED_SUM_AXIS = 6,        /* sum over dim `axis`, which is dropped */
     HPCT_RED_MEAN_AXIS = 7,       /* mean over dim `axis`, which is dropped */
     HPCT_RED_ARGMAX_AXIS = 8,     /* int32 index of the maximum along dim `axis`; of equal values the lowest index */

@@ -26,7 +26,7 @@ hpct_status fail(hpct_status st, const char* fmt, ...) {
 
 void clear_err() { g_err[0] = 0; }
 
-enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise };
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool };
 
 constexpr int64_t kI32Max = 2147483647LL;
 
@@ -41,6 +41,7 @@ struct hpct_plan {
     int64_t out_bytes[HPCT_MAX_OUT];
     // which in[] slot feeds which kernel operand; -1 = absent
     int32_t slot[6];
+    int64_t pool_planes; int32_t pool_h, pool_w;   // Kind::MaxPool
     size_t ws_bytes;  // device workspace needed at launch
     union {
         GemmParams gemm;
@@ -293,6 +294,24 @@ hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p) {
     return HPCT_OK;
 }
 
+// 2x2 max pooling of an NCHW tensor without an anchor.
+hpct_status plan_maxpool(const hpct_op_desc& d, hpct_plan& p) {
+    if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL2_HW without an anchor takes no epilogues");
+    if (d.n_in != 1 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "MAXPOOL2_HW takes 1 input and 1 output");
+    const hpct_tensor_desc& X = d.in[0];
+    if (X.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "X must be 4-D NCHW");
+    const int64_t Nb = X.shape[0], C = X.shape[1], H = X.shape[2], W = X.shape[3];
+    if (H < 2 || W < 2) return fail(HPCT_ERR_SHAPE_MISMATCH, "MAXPOOL2_HW needs planes of at least 2 x 2");
+    REQUIRE_SHAPE(d.out[0], "out[0]", Nb, C, H / 2, W / 2);
+    if (!contiguous(X) || !contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "only contiguous NCHW layouts are supported");
+    if (H > kI32Max || W > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "plane larger than 2^31-1 rows or columns");
+    p.kind = Kind::MaxPool;
+    p.pool_planes = Nb * C; p.pool_h = (int32_t)H; p.pool_w = (int32_t)W;
+    p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
+    p.shape = maxpool2_shape(Nb * C, (int32_t)H, (int32_t)W);
+    return HPCT_OK;
+}
+
 // out = [relu](A op B) on two strided views of one shape; contiguous output.
 hpct_status plan_eltwise(const hpct_op_desc& d, hpct_plan& p) {
     bool relu = false;
@@ -519,7 +538,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         case HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM: st = plan_attn(d, tmp); break;
         default:
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
-            if (d.reduce == HPCT_RED_MAXPOOL2_HW) return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL2_HW is supported only after a conv anchor");
+            if (d.reduce == HPCT_RED_MAXPOOL2_HW) { st = plan_maxpool(d, tmp); break; }
             if (d.n_epi >= 1 && (d.epi[0] == HPCT_EPI_ADD_TENSOR || d.epi[0] == HPCT_EPI_MUL_TENSOR)) st = plan_eltwise(d, tmp);
             else if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);
             else if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
@@ -614,6 +633,9 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
             e = layout_launch(q, stream);
             break;
         }
+        case Kind::MaxPool:
+            e = maxpool2_launch(in(0), (float*)out_ptrs[0], plan->pool_planes, plan->pool_h, plan->pool_w, stream);
+            break;
         case Kind::Eltwise: {
             EltwiseParams q = plan->u.elt;
             q.a = in(0); q.b = in(1); q.out = (float*)out_ptrs[0];

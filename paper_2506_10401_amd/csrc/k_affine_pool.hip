@@ -88,6 +88,33 @@ __global__ __launch_bounds__(256) void affine_planes_any(const float* __restrict
     }
 }
 
+// 2x2 / stride-2 max pooling of NCHW planes (the pooling of a VGG block as an operator of its own).
+// VEC (W % 4 == 0): a thread reads one 128-bit vector from each of the two input rows and writes two
+// outputs; otherwise a thread per output.  Odd trailing rows / columns are dropped.
+template <bool VEC>
+__global__ __launch_bounds__(256) void maxpool2_planes(const float* __restrict__ X, float* __restrict__ out, int64_t planes,
+                                                       int H, int W) {
+    const int Hp = H >> 1, Wp = W >> 1;
+    constexpr int E = VEC ? 2 : 1;            // outputs per thread
+    const int wq = VEC ? W >> 2 : Wp;         // threads per output row
+    const int64_t total = planes * Hp * wq;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int xq = (int)(t % wq);
+        const int64_t r = t / wq;
+        const int y = (int)(r % Hp);
+        const int64_t pl = r / Hp;
+        const float* src = X + (pl * H + 2 * y) * (int64_t)W + xq * 2 * E;
+        float* dst = out + (pl * Hp + y) * (int64_t)Wp + xq * E;
+        if (VEC) {
+            const float4v a = load4_nt(src), b = load4_nt(src + W);
+            const float m0 = fmaxf(fmaxf(a.x, a.y), fmaxf(b.x, b.y)), m1 = fmaxf(fmaxf(a.z, a.w), fmaxf(b.z, b.w));
+            *reinterpret_cast<float2v*>(dst) = float2v{m0, m1};
+        } else {
+            dst[0] = fmaxf(fmaxf(src[0], src[1]), fmaxf(src[W], src[W + 1]));
+        }
+    }
+}
+
 template <bool AFF, bool RELU, bool RES>
 hipError_t launch_vec(const AffineParams& p, hipStream_t stream) {
     dim3 grid((unsigned)p.planes), block(kThreads);
@@ -110,6 +137,26 @@ LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool) {
     if (HW % 4 == 0) s.kernel = pool ? "affine_planes_vec<pool>" : "affine_planes_vec<store>";
     else s.kernel = pool ? "affine_planes_any<pool>" : "affine_planes_any<store>";
     return s;
+}
+
+LaunchShape maxpool2_shape(int64_t planes, int32_t H, int32_t W) {
+    LaunchShape s{};
+    const bool vec = W % 4 == 0;
+    const int64_t threads = planes * (H / 2) * (vec ? W / 4 : W / 2);
+    const int64_t g = (threads + 255) / 256;
+    s.grid[0] = (uint32_t)(g < 1 ? 1 : (g > 131072 ? 131072 : g)); s.grid[1] = s.grid[2] = 1;
+    s.block[0] = 256; s.block[1] = s.block[2] = 1;
+    s.lds_bytes = 0;
+    s.kernel = vec ? "maxpool2_planes<vec4>" : "maxpool2_planes<scalar>";
+    return s;
+}
+
+hipError_t maxpool2_launch(const float* X, float* out, int64_t planes, int32_t H, int32_t W, hipStream_t stream) {
+    const LaunchShape s = maxpool2_shape(planes, H, W);
+    // 64-bit output vectors need an even pooled width, i.e. W % 4 == 0, and 8-byte aligned rows: both hold with W % 4 == 0
+    if (W % 4 == 0) hipLaunchKernelGGL(maxpool2_planes<true>, dim3(s.grid[0]), dim3(256), 0, stream, X, out, planes, H, W);
+    else hipLaunchKernelGGL(maxpool2_planes<false>, dim3(s.grid[0]), dim3(256), 0, stream, X, out, planes, H, W);
+    return hipGetLastError();
 }
 
 hipError_t affine_launch(const AffineParams& p, hipStream_t stream) {

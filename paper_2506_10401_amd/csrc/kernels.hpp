@@ -37,6 +37,9 @@ struct AffineParams {
     int32_t has_affine, relu, has_residual, pool;
 };
 LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool);
+// 2x2 / stride-2 max pooling of [planes, H, W] -> [planes, H/2, W/2]
+LaunchShape maxpool2_shape(int64_t planes, int32_t H, int32_t W);
+hipError_t maxpool2_launch(const float* X, float* out, int64_t planes, int32_t H, int32_t W, hipStream_t stream);
 hipError_t affine_launch(const AffineParams& p, hipStream_t stream);
 
 // ---- layout transform: out = contiguous copy of a strided view (Table 1: LayoutTransform)

@@ -327,6 +327,17 @@ def layout_transform(x_view, out, stream=None) -> None:
     plan.launch(ins, [out], stream)
 
 
+def maxpool2x2_plan(X, out):
+    plan = _cached(("maxpool2", _sh(X)), lambda: op_desc(HPCT_ANCHOR_NONE, [], HPCT_RED_MAXPOOL2_HW, 0, [_sh(X)], [_sh(out)]))
+    return plan, [X]
+
+
+def maxpool2x2(X, out, stream=None) -> None:
+    """out[n,c,y,x] = max of the 2x2 window of X[n,c] at (2y, 2x); odd trailing rows / columns are dropped."""
+    plan, ins = maxpool2x2_plan(X, out)
+    plan.launch(ins, [out], stream)
+
+
 def eltwise_plan(a_view, b_view, out, op, relu=False):
     """a_view, b_view: fp32 GPU tensor views of one shape (expand() for broadcasting); out: contiguous, same shape."""
     shape = _sh(a_view)

@@ -525,3 +525,16 @@ def test_eltwise_plans_and_errors():
     expect(H.HPCT_ERR_BAD_DESC, d)
     d = cfg_desc(1); d.epi[0] = H.HPCT_EPI_ADD_TENSOR          # not after an anchor
     expect(H.HPCT_ERR_UNSUPPORTED, d)
+
+
+def test_maxpool_alone_plans():
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_MAXPOOL2_HW, 0, [(32, 64, 56, 56)], [(32, 64, 28, 28)])
+    assert H.Plan(d).kernel_name == "maxpool2_planes<vec4>"
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_MAXPOOL2_HW, 0, [(2, 3, 7, 9)], [(2, 3, 3, 4)])
+    assert H.Plan(d).kernel_name == "maxpool2_planes<scalar>"
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_MAXPOOL2_HW, 0, [(2, 3, 7, 9)], [(2, 3, 4, 5)])
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_MAXPOOL2_HW, 0, [(2, 3, 1, 9)], [(2, 3, 1, 4)])
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_MAXPOOL2_HW, 0, [(8, 8)], [(4, 4)])
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)

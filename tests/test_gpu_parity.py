@@ -687,3 +687,12 @@ def test_eltwise_views():
     check_eltwise(v, v.permute(1, 0, 3, 2, 5, 4).contiguous().permute(1, 0, 3, 2, 5, 4), "6-D")
     one = dev(np.ones((1,), np.float32))
     check_eltwise(one, one, "single element")
+
+
+# ------------------------------------------------------- 2x2 max pooling alone
+@pytest.mark.parametrize("shape", [(32, 64, 56, 56), (2, 3, 7, 9), (1, 1, 2, 2), (3, 5, 13, 16), (2, 2, 8, 6), (1, 4, 224, 224)])
+def test_maxpool_alone(shape):
+    X = datagen.gen_normal(55, shape, 0.0, 1.0)
+    out = torch.full((shape[0], shape[1], shape[2] // 2, shape[3] // 2), float("nan"), device="cuda")
+    hpct.maxpool2x2(dev(X), out)
+    assert np.array_equal(host(out), ref.maxpool2x2(X.astype(np.float64)).astype(np.float32))
