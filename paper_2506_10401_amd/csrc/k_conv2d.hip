@@ -380,8 +380,9 @@ ConvGeom geom(const ConvParams& p, int iv = 4) {
         g.ldw = (7 * p.stride + re + g.lpad + 3) & ~3;                     // eight output columns
     } else {
         g.tiles_per_img = (g.HoWo + TP - 1) / TP;
-        // a run of TP consecutive pixels touches at most (TP-1)/Wo + 2 output rows
-        int out_rows = (TP - 1) / g.Wo + 2;
+        // a run of TP consecutive pixels touches at most (TP-1)/Wo + 2 output rows; exactly TP/Wo when
+        // rows divide a tile (tiles then start at row starts)
+        int out_rows = TP % g.Wo == 0 ? TP / g.Wo : (TP - 1) / g.Wo + 2;
         if (out_rows > g.Ho) out_rows = g.Ho;
         g.rows_max = (out_rows - 1) * p.stride + re;
         g.ldw = (p.W + 2 * p.pad + g.lpad + 3) & ~3;
