@@ -203,27 +203,54 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
             }
         }
     };
-    // ---- general staging: every element with its own bounds test ----------------
+    // ---- general staging: every element with its own bounds test; four slots (input) or eight
+    // elements (weights) are loaded before any is written, so their latencies overlap -----------
     auto copy_chunk = [&](int buf, int c0) {
         float* const ib = inS(buf);
         float* const wb = wS(buf);
-        for (int s = tid; s < slots; s += 256) {
-            int goff, loff, c, mask;
-            slot_geom(s, goff, loff, c, mask);
-            float4v v = {0.f, 0.f, 0.f, 0.f};
-            if (c0 + c < g.C) {
-                const float* src = in + goff + c0 * HW;
-                if (mask & 1) v.x = src[0];
-                if (mask & 2) v.y = src[1];
-                if (mask & 4) v.z = src[2];
-                if (mask & 8) v.w = src[3];
+        const bool rows_aligned = (g.W & 3) == 0;
+        for (int s0 = tid; s0 < slots; s0 += 256 * 4) {
+            float4v v[4];
+            int loff[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + u * 256;
+                v[u] = float4v{0.f, 0.f, 0.f, 0.f};
+                loff[u] = -1;
+                if (s < slots) {
+                    int goff, c, mask;
+                    slot_geom(s, goff, loff[u], c, mask);
+                    if (c0 + c < g.C) {
+                        const float* src = in + goff + c0 * HW;
+                        if (mask == 15 && rows_aligned) {   // wholly inside, and rows keep 16-byte alignment
+                            v[u] = load4(src);
+                        } else {
+                            if (mask & 1) v[u].x = src[0];
+                            if (mask & 2) v[u].y = src[1];
+                            if (mask & 4) v[u].z = src[2];
+                            if (mask & 8) v[u].w = src[3];
+                        }
+                    }
+                }
             }
-            *reinterpret_cast<float4v*>(ib + loff) = v;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (loff[u] >= 0) *reinterpret_cast<float4v*>(ib + loff[u]) = v[u];
         }
-        for (int e = tid; e < KT * FPR; e += 256) {
-            const int k = e / FPR, f = e - k * FPR;
-            const int c = c0 + f / TAPS;
-            wb[k * WLD + f] = (k0 + k < g.K && c < g.C) ? wt[((int64_t)(k0 + k) * g.C + c0) * TAPS + f] : 0.f;
+        for (int e0 = tid; e0 < KT * FPR; e0 += 256 * 8) {
+            float w[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + u * 256;
+                const int k = e / FPR, f = e - k * FPR;
+                const int c = c0 + f / TAPS;
+                w[u] = (e < KT * FPR && k0 + k < g.K && c < g.C) ? wt[((int64_t)(k0 + k) * g.C + c0) * TAPS + f] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + u * 256;
+                if (e < KT * FPR) { const int k = e / FPR; wb[k * WLD + (e - k * FPR)] = w[u]; }
+            }
         }
     };
 
