@@ -458,6 +458,7 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
     // A 1x1 filter with stride 1 and no padding acts on pixels independently: the plane is regrouped into rows of
     // 64 pixels, so that a 64-pixel tile stages exactly the pixels it computes instead of the image rows they lie in.
     if (R == 1 && q.stride == 1 && q.pad == 0 && !pool && (H * W) % 64 == 0) { q.H = (int32_t)(H * W / 64); q.W = 64; }
+    q.win = conv_window_geometry(q.W, q.R, q.pool);
     p.kind = Kind::Conv;
     p.u.conv = q;
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = s_bias; p.slot[3] = s_scale; p.slot[4] = s_shift; p.slot[5] = -1;

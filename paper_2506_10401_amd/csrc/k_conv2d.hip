@@ -28,7 +28,8 @@
 // consecutive floats of the weight row (vector LDS reads) and the B fragment of
 // every step is an LDS read at lane base + a constant.
 //
-// POOL variant: the 64 pixels of a tile are 8 output rows x 8 output columns
+// Window geometry (WIN; always with POOL, and without it for images wider than 64, whose whole
+// rows would cost too much LDS): the 64 pixels of a tile are 8 output rows x 8 output columns
 // (each 32-pixel block is 4 rows x 8 columns, lane = 8*row + column), the LDS
 // holds the window of the input those need instead of whole rows, and the
 // epilogue takes the 2x2 maximum entirely in registers: the vertical partner
@@ -49,7 +50,7 @@ struct ConvGeom {
     int Dl;        // dilation
     int Ho, Wo, HoWo;
     int Hp, Wp;    // pooled output size (POOL)
-    int ctiles;    // 8-column tiles per 8-row band (POOL)
+    int ctiles;    // 8-column tiles per 8-row band (window geometry)
     int tiles_per_img, tiles;
     int rows_max;  // input rows staged per tile
     int lpad;      // left pad of an LDS row so that iw = 0 lands on a 16-byte boundary
@@ -89,7 +90,7 @@ template <> struct VecOf<1> { typedef float type; };
 constexpr int mode_iv(int mode) { return mode <= 2 ? 4 : (mode == 3 ? 2 : 1); }
 constexpr int mode_ipt(int mode) { return mode == 1 ? 2 : 4; }
 
-template <int R, int CC, int KT, int MODE, bool POOL>
+template <int R, int CC, int KT, int MODE, bool POOL, bool WIN>
 __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict__ in, const float* __restrict__ wt,
                                                         ConvEpi epi, float* __restrict__ out, ConvGeom g) {
     using cfg = Cfg<R, CC, KT>;
@@ -123,12 +124,13 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     const int tile = item / kblocks;
     const int n = tile / g.tiles_per_img;
     const int tin = tile % g.tiles_per_img;
-    const int p0 = POOL ? 0 : tin * TP;
+    static_assert(WIN || !POOL, "pooling needs the window geometry");
+    const int p0 = WIN ? 0 : tin * TP;
     const int k0 = (item % kblocks) * KT;
-    const int h_lo = POOL ? 8 * (tin / g.ctiles) : p0 / g.Wo;  // first output row of the tile
-    const int w_lo = POOL ? 8 * (tin % g.ctiles) : 0;          // first output column of the tile (POOL)
+    const int h_lo = WIN ? 8 * (tin / g.ctiles) : p0 / g.Wo;  // first output row of the tile
+    const int w_lo = WIN ? 8 * (tin % g.ctiles) : 0;          // first output column of the tile (window geometry)
     const int ih0 = h_lo * g.St - g.P;  // first staged input row
-    const int iw0 = w_lo * g.St;        // input column the staged window is anchored at (POOL)
+    const int iw0 = w_lo * g.St;        // input column the staged window is anchored at (window geometry)
     const int HW = g.H * g.W;
     const int ldw4 = g.ldw >> 2;
     const int slots = CC * g.rows_max * ldw4;  // float4 slots of one input stage: slot -> (c, row, x4)
@@ -260,9 +262,10 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     int p = p0 + pb + l32;
     bool p_ok;
     int oh, ow;
-    if (POOL) {  // pixel block = 4 rows x 8 columns; the staged window covers the whole tile
+    if (WIN) {  // pixel block = 4 rows x 8 columns; the staged window covers the whole tile
         oh = h_lo + 4 * (wave >> 1) + (l32 >> 3); ow = w_lo + (l32 & 7);
-        p_ok = true;
+        p_ok = oh < g.Ho && ow < g.Wo;   // (only the un-pooled store uses it)
+        p = oh * g.Wo + ow;
     } else {
         p_ok = p < g.HoWo;
         if (!p_ok) p = g.HoWo - 1;    // clamp: reads stay inside the staged rows, the store is masked
@@ -385,9 +388,9 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
 }
 
 // input channels per LDS chunk: 4 (x 9 taps = 18 MFMA steps per chunk for 3x3); a 1x1 filter has one
-// tap per channel, so it takes 16 channels per chunk (except in the pooled variant, whose bank
+// tap per channel, so it takes 16 channels per chunk (except in the window geometry, whose bank
 // layout is worked out for 4)
-constexpr int cc_of(int R, bool pool) { return (R == 1 && !pool) ? 16 : 4; }
+constexpr int cc_of(int R, bool win) { return (R == 1 && !win) ? 16 : 4; }
 
 // iv: vector width of the input staging (the left pad of an LDS row makes image column 0 land on
 // a multiple of it)
@@ -399,10 +402,11 @@ ConvGeom geom(const ConvParams& p, int iv = 4) {
     g.Wo = (p.W + 2 * p.pad - re) / p.stride + 1;
     g.HoWo = g.Ho * g.Wo;
     g.lpad = (iv - p.pad % iv) % iv;
-    if (p.pool) {
+    if (p.win) {
         g.Hp = g.Ho / 2; g.Wp = g.Wo / 2;
-        g.ctiles = (2 * g.Wp + 7) / 8;
-        g.tiles_per_img = ((2 * g.Hp + 7) / 8) * g.ctiles;
+        const int rows = p.pool ? 2 * g.Hp : g.Ho, cols = p.pool ? 2 * g.Wp : g.Wo;   // pooling drops an odd last row / column
+        g.ctiles = (cols + 7) / 8;
+        g.tiles_per_img = ((rows + 7) / 8) * g.ctiles;
         g.rows_max = 7 * p.stride + re;                                    // eight output rows
         g.ldw = (7 * p.stride + re + g.lpad + 3) & ~3;                     // eight output columns
     } else {
@@ -420,8 +424,8 @@ ConvGeom geom(const ConvParams& p, int iv = 4) {
     // bank halves; in the pooled geometry a half covers words 0-7 of four 16-word rows, and a channel
     // stride of 4 (mod 32) moves the other half onto words 8-15.  CC = 16 (halves 8 channels apart):
     // 4 (mod 8) gives the same 32-bank shift.
-    const int cc = cc_of(p.R, p.pool != 0);
-    const int mod = cc == 16 ? 8 : 32, want = cc == 16 ? 4 : (p.pool ? 4 : 16);
+    const int cc = cc_of(p.R, p.win != 0);
+    const int mod = cc == 16 ? 8 : 32, want = cc == 16 ? 4 : (p.win ? 4 : 16);
     g.ch_ld = g.rows_max * g.ldw;
     g.ch_ld += ((want - g.ch_ld % mod) + mod) % mod;
     return g;
@@ -440,7 +444,7 @@ constexpr int kKT = 64;
 
 // Staging mode and the geometry that goes with it.
 int pick_mode(const ConvParams& p, ConvGeom* g_out) {
-    const int cc = cc_of(p.R, p.pool != 0);
+    const int cc = cc_of(p.R, p.win != 0);
     if ((p.R == 1 || p.R == 3) && p.dil == 1 && p.C % cc == 0) {
         for (int iv = 4; iv >= 1; iv >>= 1) {
             if (p.W % iv) continue;
@@ -457,48 +461,48 @@ int pick_mode(const ConvParams& p, ConvGeom* g_out) {
 
 int conv_items(const ConvParams& p, const ConvGeom& g) { return g.tiles * ((p.K + kKT - 1) / kKT); }
 
-template <int R, int MODE, bool POOL>
+template <int R, int MODE, bool POOL, bool WIN>
 hipError_t launch_conv(const ConvParams& p, const ConvGeom& g, hipStream_t stream) {
-    constexpr int CC = cc_of(R, POOL);
+    constexpr int CC = cc_of(R, WIN);
     const size_t lds = lds_bytes<R, CC, kKT>(g, MODE != 0);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, CC, kKT, MODE, POOL>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv2d_nchw_mfma<R, CC, kKT, MODE, POOL, WIN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)conv_items(p, g)), block(256);
     const ConvEpi epi{p.bias, p.scale, p.shift, p.relu};
-    hipLaunchKernelGGL((conv2d_nchw_mfma<R, CC, kKT, MODE, POOL>), grid, block, lds, stream, p.in, p.wt, epi, p.out, g);
+    hipLaunchKernelGGL((conv2d_nchw_mfma<R, CC, kKT, MODE, POOL, WIN>), grid, block, lds, stream, p.in, p.wt, epi, p.out, g);
     return hipGetLastError();
 }
 
-template <int R, bool POOL>
+template <int R, bool POOL, bool WIN>
 hipError_t launch_mode(const ConvParams& p, const ConvGeom& g, int mode, hipStream_t stream) {
     if constexpr (R == 1 || R == 3) {
         switch (mode) {
-            case 1: return launch_conv<R, 1, POOL>(p, g, stream);
-            case 2: return launch_conv<R, 2, POOL>(p, g, stream);
-            case 3: return launch_conv<R, 3, POOL>(p, g, stream);
-            case 4: return launch_conv<R, 4, POOL>(p, g, stream);
+            case 1: return launch_conv<R, 1, POOL, WIN>(p, g, stream);
+            case 2: return launch_conv<R, 2, POOL, WIN>(p, g, stream);
+            case 3: return launch_conv<R, 3, POOL, WIN>(p, g, stream);
+            case 4: return launch_conv<R, 4, POOL, WIN>(p, g, stream);
             default: break;
         }
     }
-    return launch_conv<R, 0, POOL>(p, g, stream);
+    return launch_conv<R, 0, POOL, WIN>(p, g, stream);
 }
 
 template <int R>
 hipError_t launch_pool(const ConvParams& p, const ConvGeom& g, int mode, hipStream_t stream) {
-    return p.pool ? launch_mode<R, true>(p, g, mode, stream) : launch_mode<R, false>(p, g, mode, stream);
+    if (p.pool) return launch_mode<R, true, true>(p, g, mode, stream);
+    return p.win ? launch_mode<R, false, true>(p, g, mode, stream) : launch_mode<R, false, false>(p, g, mode, stream);
 }
 
 size_t lds_any(const ConvParams& p) {
     ConvGeom g;
     const bool fast = pick_mode(p, &g) != 0;
-    const bool pool = p.pool != 0;
     switch (p.R) {
-        case 1: return pool ? lds_bytes<1, cc_of(1, true), kKT>(g, fast) : lds_bytes<1, cc_of(1, false), kKT>(g, fast);
+        case 1: return p.win ? lds_bytes<1, cc_of(1, true), kKT>(g, fast) : lds_bytes<1, cc_of(1, false), kKT>(g, fast);
         case 3: return lds_bytes<3, cc_of(3, false), kKT>(g, fast);
         case 5: return lds_bytes<5, cc_of(5, false), kKT>(g, fast);
         default: return lds_bytes<7, cc_of(7, false), kKT>(g, fast);
@@ -506,6 +510,12 @@ size_t lds_any(const ConvParams& p) {
 }
 
 }  // namespace
+
+// Window geometry: always with pooling; without it for filters larger than 1x1 on images wider
+// than 64, where staging whole input rows costs LDS (and occupancy) for nothing: 224-wide 64 -> 64
+// channels 88 -> 116 TFLOP/s, 112-wide 115 -> 122; at 56 the two geometries take the same time.
+// (A 1x1 filter keeps rows: its 16-channel chunks need the row layout.)
+int32_t conv_window_geometry(int32_t W, int32_t R, int32_t pool) { return (pool || (W > 64 && R > 1)) ? 1 : 0; }
 
 bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h, int32_t stride_w,
                     int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w, int32_t pool, const char** why) {
@@ -517,7 +527,7 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
     if (pad_h != pad_w) { *why = "padding must be the same in both directions"; return false; }
     if (pad_h > (R - 1) * dil_h) { *why = "padding larger than the (dilated) filter extent minus one"; return false; }
     ConvParams p{};
-    p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.dil = dil_h; p.pool = pool;
+    p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.dil = dil_h; p.pool = pool; p.win = conv_window_geometry(W, R, pool);
     if (lds_any(p) > 160 * 1024) { *why = "the input of one 64-pixel tile does not fit in LDS (image too wide)"; return false; }
     return true;
 }
@@ -529,16 +539,20 @@ LaunchShape conv_shape(const ConvParams& p) {
     s.grid[0] = (uint32_t)conv_items(p, g); s.grid[1] = 1; s.grid[2] = 1;
     s.block[0] = 256; s.block[1] = s.block[2] = 1;
     s.lds_bytes = (uint32_t)lds_any(p);
-    static const char* const names[4][2][2] = {
+    static const char* const names[4][3][2] = {
         {{"conv2d_nchw_mfma<1x1,general>", "conv2d_nchw_mfma<1x1,pipelined>"},
-         {"conv2d_nchw_mfma<1x1,general,maxpool2>", "conv2d_nchw_mfma<1x1,pipelined,maxpool2>"}},
+         {"conv2d_nchw_mfma<1x1,general,maxpool2>", "conv2d_nchw_mfma<1x1,pipelined,maxpool2>"},
+         {"conv2d_nchw_mfma<1x1,general,window>", "conv2d_nchw_mfma<1x1,pipelined,window>"}},
         {{"conv2d_nchw_mfma<3x3,general>", "conv2d_nchw_mfma<3x3,pipelined>"},
-         {"conv2d_nchw_mfma<3x3,general,maxpool2>", "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"}},
+         {"conv2d_nchw_mfma<3x3,general,maxpool2>", "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"},
+         {"conv2d_nchw_mfma<3x3,general,window>", "conv2d_nchw_mfma<3x3,pipelined,window>"}},
         {{"conv2d_nchw_mfma<5x5,general>", "conv2d_nchw_mfma<5x5,general>"},
-         {"conv2d_nchw_mfma<5x5,general,maxpool2>", "conv2d_nchw_mfma<5x5,general,maxpool2>"}},
+         {"conv2d_nchw_mfma<5x5,general,maxpool2>", "conv2d_nchw_mfma<5x5,general,maxpool2>"},
+         {"conv2d_nchw_mfma<5x5,general,window>", "conv2d_nchw_mfma<5x5,general,window>"}},
         {{"conv2d_nchw_mfma<7x7,general>", "conv2d_nchw_mfma<7x7,general>"},
-         {"conv2d_nchw_mfma<7x7,general,maxpool2>", "conv2d_nchw_mfma<7x7,general,maxpool2>"}}};
-    s.kernel = names[p.R / 2][p.pool ? 1 : 0][mode != 0 ? 1 : 0];
+         {"conv2d_nchw_mfma<7x7,general,maxpool2>", "conv2d_nchw_mfma<7x7,general,maxpool2>"},
+         {"conv2d_nchw_mfma<7x7,general,window>", "conv2d_nchw_mfma<7x7,general,window>"}}};
+    s.kernel = names[p.R / 2][p.pool ? 1 : (p.win ? 2 : 0)][mode != 0 ? 1 : 0];
     return s;
 }
 

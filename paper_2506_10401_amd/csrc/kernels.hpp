@@ -136,7 +136,9 @@ struct ConvParams {
     const float* scale; const float* shift;   // per output channel, either may be null
     int32_t pool;                             // out is [Nb, K, Ho/2, Wo/2]
     int32_t dil;                              // dilation, >= 1
+    int32_t win;                              // 8 x 8 window tiles (set from conv_window_geometry)
 };
+int32_t conv_window_geometry(int32_t W, int32_t R, int32_t pool);
 bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h,
                     int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w, int32_t pool,
                     const char** why);

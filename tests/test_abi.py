@@ -382,6 +382,11 @@ def test_conv_block_plans():
     assert H.Plan(conv_block_desc(pool=False, stride=2, R=7, pad=3, shape=(4, 3, 64, 64), K=64)).kernel_name == \
         "conv2d_nchw_mfma<7x7,general>"
     assert H.Plan(conv_block_desc(R=5, pad=2, shape=(2, 8, 30, 30), K=16)).kernel_name == "conv2d_nchw_mfma<5x5,general,maxpool2>"
+    # images wider than 64 columns: 8 x 8 output windows also without pooling (28 x 28 of them x 2 x 1)
+    p = H.Plan(conv_block_desc(pool=False, shape=(2, 8, 224, 224), K=64))
+    assert p.kernel_name == "conv2d_nchw_mfma<3x3,pipelined,window>" and p.launch_shape()[0] == (28 * 28 * 2, 1, 1)
+    assert H.Plan(conv_block_desc(pool=False, R=1, pad=0, stride=2, shape=(2, 16, 20, 100), K=64)).kernel_name == \
+        "conv2d_nchw_mfma<1x1,general>"                                       # 1x1 filters keep whole rows
     assert H.Plan(conv_block_desc(R=1, pad=0)).kernel_name == "conv2d_nchw_mfma<1x1,pipelined,maxpool2>"
     # dilation: the filter spans (R-1)*dil + 1 rows; 0 in the descriptor means 1
     assert H.Plan(conv_block_desc(pool=False, dil=2, pad=2)).kernel_name == "conv2d_nchw_mfma<3x3,general>"

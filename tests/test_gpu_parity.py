@@ -435,6 +435,24 @@ def test_chain7_pipelined_staging_modes(N, C, H, W, K, R, stride, pad):
     check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False)
 
 
+@pytest.mark.parametrize("N,C,H,W,K,R,stride,pad,dil", [
+    (1, 8, 20, 72, 64, 3, 1, 1, 1),       # 8-column tiles divide the width
+    (2, 4, 13, 77, 70, 3, 1, 1, 1),       # ragged rows, columns and output channels
+    (1, 8, 9, 130, 64, 3, 2, 1, 1),       # stride 2
+    (1, 3, 11, 99, 8, 5, 3, 2, 1),        # 5x5, stride 3
+    (1, 3, 30, 230, 16, 7, 2, 3, 1),      # first-layer shape: 7x7 stride 2
+    (1, 5, 12, 81, 12, 3, 1, 2, 2),       # dilated
+    (1, 4, 3, 1500, 8, 3, 1, 1, 1),       # far wider than whole staged rows would allow
+    (1, 6, 70, 66, 9, 3, 1, 0, 1)])       # no padding
+def test_conv_window_geometry_without_pooling(N, C, H, W, K, R, stride, pad, dil):
+    # images wider than 64 columns are tiled in 8 x 8 output windows also when nothing is pooled
+    print("conv window %s" % ((N, C, H, W, K, R, stride, pad, dil),), flush=True)
+    t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=R, S=R)
+    _, name = check_chain7(t, stride, pad, pool=False, dil=dil)
+    assert "window" in name
+    check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False, dil=dil)
+
+
 def test_chain7_pool_takes_the_maximum_not_a_sum_or_a_corner():
     # identity 1x1 conv: the block is max pooling of the input, exactly
     X = datagen.gen_normal(11, (2, 4, 10, 66), 0.0, 1.0)
