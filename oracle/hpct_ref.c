@@ -13,7 +13,7 @@
  * Listing "CPU C Code without TVM dependency" (Section 3.5) and of its
  * VGG-16 case study (Section 5.3).  No blocking, no SIMD, no BLAS.
  *
- * Operator classes follow the paper's Table 1: Elementwise (add, mul, relu),
+ * Operator classes follow the paper's Table 1: Elementwise (add, sub, mul, div, sqrt, sin, cos, relu, ...),
  * Reduction (sum, mean, softmax), ComputeIntensive (matmul, conv).
  *
  * Parity pins: every function here is pinned by tests that do not run it
@@ -414,6 +414,51 @@ void ref_attention_causal(const float *Q, const float *K, const float *V,
             if (Dn) Dn[bi * D + d] = mag;
         }
         free(s);
+    }
+}
+
+/* ---- Elementwise chain on strided views (Table 1, Elementwise: "add, sub, mul,
+ * div, sqrt, sin, cos, relu and etc.").  v = a[..] alone (bin < 0, b unused) or
+ * a[..] (+, *, -, /) b[..] for bin = 0, 1, 2, 3; then the n_un unary steps un[0],
+ * un[1], ... are applied to v in that order:
+ *   0 max(v, 0)      1 tanh-form GELU      2 v * scale      3 sqrt(v)     4 sin(v)
+ *   5 cos(v)         6 exp(v)              7 tanh(v)        8 1 / (1 + exp(-v))
+ * Everything in double from the widened fp32 operands; libm supplies the
+ * transcendental functions. */
+void ref_eltwise_map(const float *a, const float *b, int32_t nd, const int64_t *shape,
+                     const int64_t *sa, const int64_t *sb, int32_t bin, int32_t n_un,
+                     const int32_t *un, float scale, double *out)
+{
+    int64_t total = 1;
+    for (int32_t d = 0; d < nd; ++d) total *= shape[d];
+#pragma omp parallel for schedule(static)
+    for (int64_t lin = 0; lin < total; ++lin) {
+        int64_t rem = lin, oa = 0, ob = 0;
+        for (int32_t d = nd - 1; d >= 0; --d) {
+            int64_t i = rem % shape[d];
+            oa += i * sa[d];
+            if (bin >= 0) ob += i * sb[d];
+            rem /= shape[d];
+        }
+        double v = (double)a[oa];
+        if (bin >= 0) {
+            double y = (double)b[ob];
+            v = bin == 0 ? v + y : bin == 1 ? v * y : bin == 2 ? v - y : v / y;
+        }
+        for (int32_t k = 0; k < n_un; ++k) {
+            switch (un[k]) {
+                case 0: v = v > 0.0 ? v : 0.0; break;
+                case 1: v = 0.5 * v * (1.0 + tanh(0.7978845608028654 * (v + 0.044715 * v * v * v))); break;
+                case 2: v = v * (double)scale; break;
+                case 3: v = sqrt(v); break;
+                case 4: v = sin(v); break;
+                case 5: v = cos(v); break;
+                case 6: v = exp(v); break;
+                case 7: v = tanh(v); break;
+                default: v = 1.0 / (1.0 + exp(-v)); break;
+            }
+        }
+        out[lin] = v;
     }
 }
 

@@ -43,6 +43,7 @@ def lib():
             "ref_maxpool2x2_planes": [p, i64, i64, i64, p],
             "ref_reduce_axis": [p, C.c_int32, p, p, C.c_int32, C.c_int32, p, p, p],
             "ref_eltwise_binary": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p],
+            "ref_eltwise_map": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p, C.c_float, p],
         }
         for name, args in sig.items():
             f = getattr(_lib, name)
@@ -229,6 +230,29 @@ def eltwise_binary(a_base, b_base, shape, sa, sb, op, relu_=False):
     out = np.empty(tuple(shape), dtype=np.float64)
     lib().ref_eltwise_binary(_ptr(a_base), _ptr(b_base), nd, sh, (C.c_int64 * nd)(*sa), (C.c_int64 * nd)(*sb),
                              {"add": 0, "mul": 1}[op], 1 if relu_ else 0, _ptr(out))
+    return out
+
+
+MAP_BINARY = {"add": 0, "mul": 1, "sub": 2, "div": 3}
+MAP_UNARY = {"relu": 0, "gelu": 1, "scale": 2, "sqrt": 3, "sin": 4, "cos": 5, "exp": 6, "tanh": 7, "sigmoid": 8}
+
+
+def eltwise_map(a_base, shape, sa, unary=(), binary=None, b_base=None, sb=None, scale=1.0):
+    """Elementwise chain on strided views (Table 1, Elementwise): v = a_view, or a_view `binary` b_view with
+    binary in MAP_BINARY; then the steps named in `unary` (MAP_UNARY), in order ("scale" multiplies by the fp32
+    constant `scale`).  Views are (shape, strides in elements, 0 = broadcast) over the flat fp32 arrays."""
+    a_base = _f32(a_base).reshape(-1)
+    nd = len(shape)
+    assert all(s >= 0 for s in sa) and sum((n - 1) * s for n, s in zip(shape, sa)) < a_base.size
+    if binary is None:
+        b_base, sb, code = a_base, tuple(sa), -1
+    else:
+        b_base, code = _f32(b_base).reshape(-1), MAP_BINARY[binary]
+        assert all(s >= 0 for s in sb) and sum((n - 1) * s for n, s in zip(shape, sb)) < b_base.size
+    un = (C.c_int32 * max(1, len(unary)))(*[MAP_UNARY[u] for u in unary])
+    out = np.empty(tuple(shape), dtype=np.float64)
+    lib().ref_eltwise_map(_ptr(a_base), _ptr(b_base), nd, (C.c_int64 * nd)(*shape), (C.c_int64 * nd)(*sa),
+                          (C.c_int64 * nd)(*sb), code, len(unary), un, C.c_float(scale), _ptr(out))
     return out
 
 

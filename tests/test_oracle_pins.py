@@ -751,3 +751,99 @@ def test_eltwise_binary_against_numpy_broadcasting():
     assert np.array_equal(ref.eltwise_binary(a, neg, (4, 5, 6), (30, 6, 1), (0, 0, 0), "mul", relu_=True), np.maximum(-A, 0.0))
     x = f32([1.0000001, 3.3333333]); y = f32([1.0000002, 0.3333333])
     assert np.array_equal(ref.eltwise_binary(x, y, (2,), (1,), (1,), "mul"), x.astype(np.float64) * y.astype(np.float64))
+
+
+# ------------------------------------------------ elementwise chains (add, sub, mul, div, sqrt, sin, cos, ...)
+def emap(a, unary=(), binary=None, b=None, scale=1.0):
+    """contiguous 1-D helper around ref.eltwise_map; a scalar b is broadcast"""
+    a = f32(a).reshape(-1)
+    if binary is None:
+        return ref.eltwise_map(a, (a.size,), (1,), unary, scale=scale)
+    b = f32(b).reshape(-1)
+    return ref.eltwise_map(a, (a.size,), (1,), unary, binary, b, (0,) if b.size == 1 else (1,), scale)
+
+
+def test_eltwise_map_known_values():
+    assert np.array_equal(emap([4.0, 2.25, 0.0, 1e-10 ** 2], ["sqrt"]), np.array([2.0, 1.5, 0.0, float(np.float32(1e-20)) ** 0.5]))
+    assert np.array_equal(emap([0.0], ["sin"]), [0.0]) and np.array_equal(emap([0.0], ["cos"]), [1.0])
+    assert np.array_equal(emap([0.0], ["exp"]), [1.0]) and np.array_equal(emap([0.0], ["tanh"]), [0.0])
+    assert np.array_equal(emap([0.0], ["sigmoid"]), [0.5])
+    assert abs(emap([1.0], ["exp"])[0] - math.e) < 1e-15
+    # first-order expansions around pi/6 and pi/2 at the fp32 arguments: tell sin from cos and fix the signs
+    x6 = float(np.float32(math.pi / 6)); d6 = x6 - math.pi / 6
+    assert abs(emap([x6], ["sin"])[0] - (0.5 + math.sqrt(3) / 2 * d6)) < 1e-14
+    assert abs(emap([x6], ["cos"])[0] - (math.sqrt(3) / 2 - 0.5 * d6)) < 1e-14
+    x2 = float(np.float32(math.pi / 2)); d2 = x2 - math.pi / 2
+    assert abs(emap([x2], ["sin"])[0] - 1.0) < 1e-14 and abs(emap([x2], ["cos"])[0] + d2) < 1e-14
+    assert abs(emap([-x2], ["sin"])[0] + 1.0) < 1e-14
+    # relu and scale
+    assert np.array_equal(emap([-2.0, 0.0, 3.0], ["relu"]), [0.0, 0.0, 3.0])
+    assert np.array_equal(emap([-2.0, 0.5], ["scale"], scale=-4.0), [8.0, -2.0])
+    # the constant is the fp32 one
+    assert emap([1.0], ["scale"], scale=0.1)[0] == float(np.float32(0.1))
+
+
+def test_eltwise_map_identities():
+    x = f32(rng.normal(size=4000) * 3.0)
+    X = x.astype(np.float64)
+    s, c = emap(x, ["sin"]), emap(x, ["cos"])
+    assert np.max(np.abs(s * s + c * c - 1.0)) < 1e-15 * 4
+    # angle addition with an independent second angle: sin(x + y) from the pieces
+    y = f32(rng.normal(size=4000))
+    xy = (X + y.astype(np.float64)).astype(np.float32)      # the sum as fp32 input, its exact value used below
+    dx = xy.astype(np.float64) - X                            # = the second angle actually added
+    sd, cd = np.sin(dx), np.cos(dx)                           # small independent angles (library witness)
+    assert np.max(np.abs(emap(xy, ["sin"]) - (s * cd + c * sd))) < 1e-14
+    assert np.max(np.abs(emap(xy, ["cos"]) - (c * cd - s * sd))) < 1e-14
+    p = f32(rng.uniform(0.01, 50.0, size=4000))
+    r = emap(p, ["sqrt"])
+    assert np.max(np.abs(r * r - p.astype(np.float64)) / p) < 1e-15 * 2 and np.all(r > 0)
+    e, en = emap(x, ["exp"]), emap(-x, ["exp"])
+    assert np.max(np.abs(e * en - 1.0)) < 1e-15 * 4
+    assert np.max(np.abs(emap(x, ["scale", "exp"], scale=2.0) - e * e) / (e * e)) < 1e-15 * 4     # exp(2x) = exp(x)^2
+    # tanh and the logistic function from exp, through chains of their own
+    e2 = emap(x, ["scale", "exp"], scale=2.0)
+    assert np.max(np.abs(emap(x, ["tanh"]) - (e2 - 1.0) / (e2 + 1.0))) < 1e-15 * 4
+    sg = emap(x, ["sigmoid"])
+    assert np.max(np.abs(sg - 1.0 / (1.0 + en))) < 1e-15
+    assert np.max(np.abs(sg + emap(-x, ["sigmoid"]) - 1.0)) < 1e-15
+    assert np.max(np.abs(sg - 0.5 * (1.0 + emap(x, ["scale", "tanh"], scale=0.5)))) < 1e-15 * 2
+    # the GELU step is the tanh-form GELU pinned above
+    assert np.array_equal(emap(x, ["gelu"]), ref.gelu_tanh(X))
+
+
+def test_eltwise_map_binary_ops_and_step_order():
+    a = f32(rng.normal(size=3000)); b = f32(rng.uniform(0.5, 3.0, size=3000) * rng.choice([-1.0, 1.0], size=3000))
+    A, B = a.astype(np.float64), b.astype(np.float64)
+    # an fp32 sum, difference and product are exact in fp64
+    assert np.array_equal(emap(a, (), "add", b), A + B) and np.array_equal(emap(a, (), "mul", b), A * B)
+    sub = emap(a, (), "sub", b)
+    assert np.array_equal(sub, -emap(b, (), "sub", a)) and np.array_equal(sub, emap(a, (), "add", -b))
+    assert np.array_equal(emap(a, (), "sub", a), np.zeros(3000))
+    q = emap(a, (), "div", b)
+    assert np.max(np.abs(q * B - A) / np.abs(A)) < 1e-15 * 2
+    assert np.array_equal(emap(b, (), "div", b), np.ones(3000))
+    assert np.array_equal(emap([1.0, 3.0], (), "div", [2.0]), [0.5, 1.5])          # a / b, not b / a; scalar broadcast
+    assert np.array_equal(emap([1.0, 3.0], (), "sub", [2.0]), [-1.0, 1.0])
+    # the unary steps run after the binary one, in list order
+    assert np.array_equal(emap([3.0, -3.0], ["scale", "relu"], scale=-1.0), [0.0, 3.0])
+    assert np.array_equal(emap([3.0, -3.0], ["relu", "scale"], scale=-1.0), [-3.0, 0.0])
+    assert np.array_equal(emap([3.0, 0.25], ["relu", "sqrt"], "sub", [-1.0]), [2.0, math.sqrt(1.25)])
+    assert np.array_equal(emap([5.0, 1.0], ["relu"], "sub", [3.0]), [2.0, 0.0])
+    # agrees with the two-operand routine pinned above on its cases
+    assert np.array_equal(emap(a, ["relu"], "add", b), ref.eltwise_binary(a, b, (3000,), (1,), (1,), "add", True))
+    assert np.array_equal(emap(a, ["relu"], "mul", b), ref.eltwise_binary(a, b, (3000,), (1,), (1,), "mul", True))
+
+
+def test_eltwise_map_views_by_brute_force():
+    a = f32(rng.normal(size=(5, 6, 7))); b = f32(rng.uniform(1.0, 2.0, size=(7, 5)))
+    # a permuted to (7, 5, 6) = strides (1, 42, 7); b [7,5] broadcast over the last dim = strides (5, 1, 0)
+    got = ref.eltwise_map(a, (7, 5, 6), (1, 42, 7), ["scale"], "div", b, (5, 1, 0), scale=2.0)
+    for i in range(7):
+        for j in range(5):
+            for k in range(6):
+                assert got[i, j, k] == float(a[j, k, i]) / float(b[i, j]) * 2.0
+    # one operand only: a strided slice, every second column of rows 1..3
+    m = f32(rng.uniform(0.0, 9.0, size=(4, 10)))
+    got = ref.eltwise_map(m.reshape(-1)[10:], (3, 5), (10, 2), ["sqrt"])
+    assert np.array_equal(got, np.sqrt(m[1:, ::2].astype(np.float64)))
