@@ -242,6 +242,24 @@ def main() -> int:
         reduce_ops.append(dict(op="add_bias_row_relu_8192x4096", kernel=plan_e.kernel_name, avg_us=round(us, 3),
                                achieved=round(nb / us / 1e3, 1), unit="GB/s", peak=HBM_PEAK_GBS,
                                frac=round(nb / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=len(calls_e)))
+        # one-operand chain (Table 1 Elementwise "sin"): out = sin(X)
+        calls_u = []
+        for s_ in sets[3]:
+            plan_u, ins_u = hpct.eltwise_map_plan(s_["ins"][0], s_["out"], ("sin",))
+            calls_u.append(plan_u.bind(ins_u, [s_["out"]]))
+        for k in range(min(args.warmup, 10)):
+            calls_u[k % len(calls_u)]()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(args.steps):
+            calls_u[k % len(calls_u)]()
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / args.steps
+        nb = 2 * ms[0].numel() * 4
+        reduce_ops.append(dict(op="sin_8192x4096", kernel=plan_u.kernel_name, avg_us=round(us, 3),
+                               achieved=round(nb / us / 1e3, 1), unit="GB/s", peak=HBM_PEAK_GBS,
+                               frac=round(nb / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=len(calls_u)))
         xs = [s_["ins"][0] for s_ in sets[2]]                  # 11 NCHW tensors [32,64,56,56]
         calls_p = []
         for x in xs:

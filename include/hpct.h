@@ -4,7 +4,7 @@
  * C ABI of the operator library.  One call describes a fused chain
  *     anchor contraction  ->  elementwise / broadcast epilogues  ->  row reduction
  * (operator classes of the paper's Table 1: ComputeIntensive "matmul, conv",
- * Elementwise "add, mul, relu", Reduction "sum, mean, softmax", LayoutTransform
+ * Elementwise "add, sub, mul, div, sqrt, sin, cos, relu", Reduction "sum, mean, softmax", LayoutTransform
  * "reshape, transpose"; fused examples
  * of its Section 5.3) with an op descriptor; the library validates it, picks a
  * hand-written HIP kernel and enqueues it on the caller's stream: one kernel per
@@ -42,9 +42,10 @@
  *         [+GELU_TANH]
  *   NONE  SOFTMAX_LAST                                X[M,N]                        [M,N]
  *   NONE  MAXPOOL2_HW (no epilogue)                   X[N,C,H,W]                    [N,C,H/2,W/2]
- *   NONE  ADD_TENSOR | MUL_TENSOR [+RELU],            A, B: strided views of one    that shape,
- *         no reduction: out = [relu](A op B)          shape (stride >= 0, 0 =       contiguous
- *                                                     broadcast, up to 6 dims)
+ *   NONE  [ADD|MUL|SUB|DIV_TENSOR] then up to 8 of    A [, B]: strided views of     that shape,
+ *         RELU GELU_TANH SCALE_CONST SQRT SIN COS     one shape (stride >= 0, 0 =   contiguous
+ *         EXP TANH SIGMOID in list order, no          broadcast, up to 6 dims)
+ *         reduction: out = steps(A op B) or steps(A)
  *   NONE  (no epilogue, no reduction): layout         X: any strided view (stride   same shape,
  *         transform, out = contiguous copy of X       >= 0, up to 6 dims)           contiguous
  *   NONE  SUM_AXIS | MEAN_AXIS | ARGMAX_AXIS |        X: any strided view (stride   X's shape without
@@ -120,7 +121,16 @@ typedef enum {
                                      by 1 / (1 - dropout_p) otherwise.  GEMM anchor only. */
     HPCT_EPI_CAUSAL_MASK = 7,     /* on the scores of BGEMM_SOFTMAX_BGEMM: query i attends keys j <= i only */
     HPCT_EPI_ADD_TENSOR = 8,      /* + in[1], a strided view of the same shape (stride 0 = broadcast).  No anchor. */
-    HPCT_EPI_MUL_TENSOR = 9       /* * in[1], likewise */
+    HPCT_EPI_MUL_TENSOR = 9,      /* * in[1], likewise */
+    HPCT_EPI_SUB_TENSOR = 10,     /* - in[1], likewise */
+    HPCT_EPI_DIV_TENSOR = 11,     /* / in[1], likewise (IEEE division, correctly rounded) */
+    /* unary steps of an elementwise chain without anchor (RELU, GELU_TANH and SCALE_CONST are steps too): */
+    HPCT_EPI_SQRT = 12,           /* sqrt(x), correctly rounded; NaN for x < 0 */
+    HPCT_EPI_SIN = 13,            /* sin(x), full-range argument reduction */
+    HPCT_EPI_COS = 14,            /* cos(x) */
+    HPCT_EPI_EXP = 15,            /* exp(x) */
+    HPCT_EPI_TANH = 16,           /* tanh(x) */
+    HPCT_EPI_SIGMOID = 17         /* 1 / (1 + exp(-x)) */
 } hpct_epilogue;
 
 /* Row reductions (Table 1, Reduction). */

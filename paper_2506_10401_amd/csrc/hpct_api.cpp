@@ -312,14 +312,61 @@ hpct_status plan_maxpool(const hpct_op_desc& d, hpct_plan& p) {
     return HPCT_OK;
 }
 
-// out = [relu](A op B) on two strided views of one shape; contiguous output.
+// Elementwise chain on one or two strided views of one shape; contiguous output.
+// unary step code of an epilogue inside an elementwise chain, or -1
+int unary_code(hpct_epilogue e) {
+    switch (e) {
+        case HPCT_EPI_RELU: return kUnRelu;
+        case HPCT_EPI_GELU_TANH: return kUnGelu;
+        case HPCT_EPI_SCALE_CONST: return kUnScale;
+        case HPCT_EPI_SQRT: return kUnSqrt;
+        case HPCT_EPI_SIN: return kUnSin;
+        case HPCT_EPI_COS: return kUnCos;
+        case HPCT_EPI_EXP: return kUnExp;
+        case HPCT_EPI_TANH: return kUnTanh;
+        case HPCT_EPI_SIGMOID: return kUnSigmoid;
+        default: return -1;
+    }
+}
+
+int binary_code(hpct_epilogue e) {
+    switch (e) {
+        case HPCT_EPI_ADD_TENSOR: return kEltAdd;
+        case HPCT_EPI_MUL_TENSOR: return kEltMul;
+        case HPCT_EPI_SUB_TENSOR: return kEltSub;
+        case HPCT_EPI_DIV_TENSOR: return kEltDiv;
+        default: return -1;
+    }
+}
+
+// A chain without anchor and reduction whose epilogues are [one of the *_TENSOR ops] followed by
+// unary steps only.  (RELU alone on a contiguous NCHW tensor stays with the per-channel chain.)
+bool is_eltwise_chain(const hpct_op_desc& d) {
+    if (d.n_epi < 1) return false;
+    if (binary_code(d.epi[0]) >= 0) return true;
+    bool only_relu = true;
+    for (int i = 0; i < d.n_epi; ++i) {
+        if (unary_code(d.epi[i]) < 0) return false;
+        only_relu = only_relu && d.epi[i] == HPCT_EPI_RELU;
+    }
+    if (d.reduce != HPCT_RED_NONE) return false;
+    return !(only_relu && d.n_in >= 1 && d.in[0].ndim == 4 && contiguous(d.in[0]));
+}
+
 hpct_status plan_eltwise(const hpct_op_desc& d, hpct_plan& p) {
-    bool relu = false;
-    if (d.n_epi == 2 && d.epi[1] == HPCT_EPI_RELU) relu = true;
-    else if (d.n_epi != 1) return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: epilogues must be ADD_TENSOR | MUL_TENSOR [RELU]");
+    const int bin = binary_code(d.epi[0]);
+    const int first = bin >= 0 ? 1 : 0;
+    int un[kEltwiseSteps];
+    for (int i = first; i < d.n_epi; ++i) {
+        un[i - first] = unary_code(d.epi[i]);
+        if (un[i - first] < 0)
+            return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: epilogues must be [ADD|MUL|SUB|DIV_TENSOR] followed by "
+                        "RELU, GELU_TANH, SCALE_CONST, SQRT, SIN, COS, EXP, TANH or SIGMOID steps");
+    }
     if (d.reduce != HPCT_RED_NONE) return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: no reduction is supported after it");
-    if (d.n_in != 2 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "an elementwise chain on views takes 2 inputs and 1 output");
-    const hpct_tensor_desc &A = d.in[0], &B = d.in[1], &O = d.out[0];
+    const int need = bin >= 0 ? 2 : 1;
+    if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "this elementwise chain takes %d input(s) and 1 output", need);
+    const hpct_tensor_desc &A = d.in[0], &B = d.in[need - 1], &O = d.out[0];
     if (A.ndim != B.ndim || A.ndim != O.ndim) return fail(HPCT_ERR_SHAPE_MISMATCH, "elementwise chain: both views and the output must have the same shape");
     for (int k = 0; k < A.ndim; ++k)
         if (A.shape[k] != B.shape[k] || A.shape[k] != O.shape[k])
@@ -341,14 +388,16 @@ hpct_status plan_eltwise(const hpct_op_desc& d, hpct_plan& p) {
     q.nd = nd;
     q.total = 1;
     for (int k = 0; k < nd; ++k) q.total *= q.shape[k];
-    q.op = d.epi[0] == HPCT_EPI_ADD_TENSOR ? 0 : 1;
-    q.relu = relu ? 1 : 0;
+    q.op = bin >= 0 ? bin : kEltNone;
+    q.n_un = d.n_epi - first;
+    for (int i = 0; i < q.n_un; ++i) q.un |= (uint32_t)un[i] << (4 * i);
+    q.scale = d.scale;
     bool vec = q.shape[nd - 1] % 4 == 0 && q.sa[nd - 1] == 1 && (q.sb[nd - 1] == 1 || q.sb[nd - 1] == 0);
     for (int k = 0; k + 1 < nd; ++k) vec = vec && q.sa[k] % 4 == 0 && (q.sb[k] % 4 == 0 || q.sb[nd - 1] == 0);
     q.vec = vec ? 1 : 0;
     p.kind = Kind::Eltwise;
     p.u.elt = q;
-    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
+    p.slot[0] = 0; p.slot[1] = bin >= 0 ? 1 : -1; p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
     p.shape = eltwise_shape(q);
     return HPCT_OK;
 }
@@ -513,7 +562,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)
-        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_MUL_TENSOR) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
+        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_SIGMOID) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
 
     hpct_plan tmp;
     std::memset(&tmp, 0, sizeof tmp);
@@ -543,7 +592,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         default:
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
             if (d.reduce == HPCT_RED_MAXPOOL2_HW) { st = plan_maxpool(d, tmp); break; }
-            if (d.n_epi >= 1 && (d.epi[0] == HPCT_EPI_ADD_TENSOR || d.epi[0] == HPCT_EPI_MUL_TENSOR)) st = plan_eltwise(d, tmp);
+            if (is_eltwise_chain(d)) st = plan_eltwise(d, tmp);
             else if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);
             else if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
             else if (d.reduce == HPCT_RED_NONE && d.n_epi == 0 && d.n_in >= 1 &&

@@ -57,8 +57,12 @@ struct LayoutParams {
 LaunchShape layout_shape(const LayoutParams& p);
 hipError_t layout_launch(const LayoutParams& p, hipStream_t stream);
 
-// ---- out = [relu](a op b) on two strided views of one shape (Table 1: Elementwise "add, mul, relu")
+// ---- elementwise chain on strided views: v = a or a (+,*,-,/) b, then unary steps in order
+// (Table 1: Elementwise "add, sub, mul, div, sqrt, sin, cos, relu and etc.")
 constexpr int kEltwiseDims = 6;
+constexpr int kEltwiseSteps = 8;
+enum : int32_t { kEltAdd = 0, kEltMul = 1, kEltSub = 2, kEltDiv = 3, kEltNone = 4 };
+enum : int32_t { kUnRelu = 0, kUnGelu, kUnScale, kUnSqrt, kUnSin, kUnCos, kUnExp, kUnTanh, kUnSigmoid };
 struct EltwiseParams {
     const float* a; const float* b; float* out;
     int32_t nd;                      // collapsed dimensions, 1..kEltwiseDims
@@ -66,8 +70,10 @@ struct EltwiseParams {
     int64_t sa[kEltwiseDims];        // strides of a (elements), 0 = broadcast
     int64_t sb[kEltwiseDims];        // strides of b
     int64_t total;                   // elements
-    int32_t op;                      // 0 add, 1 mul
-    int32_t relu;
+    int32_t op;                      // kEltAdd .. kEltNone (b unused)
+    int32_t n_un;                    // unary steps, 0..kEltwiseSteps
+    uint32_t un;                     // their codes (kUnRelu ..), 4 bits each, first step in the low bits
+    float scale;                     // the constant of kUnScale
     int32_t vec;                     // 128-bit access possible by the strides (pointers are checked at launch)
 };
 LaunchShape eltwise_shape(const EltwiseParams& p);

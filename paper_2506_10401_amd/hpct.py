@@ -23,7 +23,9 @@ STATUS_NAMES = ["HPCT_OK", "HPCT_ERR_NULL", "HPCT_ERR_BAD_DESC", "HPCT_ERR_SHAPE
 HPCT_F32, HPCT_I32 = 0, 1
 HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW = range(4)
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
-    HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH, HPCT_EPI_CAUSAL_MASK, HPCT_EPI_ADD_TENSOR, HPCT_EPI_MUL_TENSOR = range(10)
+    HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH, HPCT_EPI_CAUSAL_MASK, HPCT_EPI_ADD_TENSOR, HPCT_EPI_MUL_TENSOR, \
+    HPCT_EPI_SUB_TENSOR, HPCT_EPI_DIV_TENSOR, HPCT_EPI_SQRT, HPCT_EPI_SIN, HPCT_EPI_COS, HPCT_EPI_EXP, HPCT_EPI_TANH, \
+    HPCT_EPI_SIGMOID = range(18)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS = range(10)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
@@ -338,18 +340,44 @@ def maxpool2x2(X, out, stream=None) -> None:
     plan.launch(ins, [out], stream)
 
 
-def eltwise_plan(a_view, b_view, out, op, relu=False):
-    """a_view, b_view: fp32 GPU tensor views of one shape (expand() for broadcasting); out: contiguous, same shape."""
+_MAP_BINARY = {"add": HPCT_EPI_ADD_TENSOR, "mul": HPCT_EPI_MUL_TENSOR, "sub": HPCT_EPI_SUB_TENSOR, "div": HPCT_EPI_DIV_TENSOR}
+_MAP_UNARY = {"relu": HPCT_EPI_RELU, "gelu": HPCT_EPI_GELU_TANH, "scale": HPCT_EPI_SCALE_CONST, "sqrt": HPCT_EPI_SQRT,
+              "sin": HPCT_EPI_SIN, "cos": HPCT_EPI_COS, "exp": HPCT_EPI_EXP, "tanh": HPCT_EPI_TANH,
+              "sigmoid": HPCT_EPI_SIGMOID}
+
+
+def eltwise_map_plan(a_view, out, unary=(), binary=None, b_view=None, scale=1.0):
+    """Elementwise chain: a_view [binary b_view], then the steps of `unary` in order.  Views: fp32 GPU tensor views
+    of one shape (expand() for broadcasting); out: contiguous, same shape; `scale` is the constant of "scale"."""
     shape = _sh(a_view)
-    sa, sb = tuple(int(v) for v in a_view.stride()), tuple(int(v) for v in b_view.stride())
-    epi = [HPCT_EPI_ADD_TENSOR if op == "add" else HPCT_EPI_MUL_TENSOR] + ([HPCT_EPI_RELU] if relu else [])
-    plan = _cached(("eltwise", shape, sa, sb, op, relu), lambda: op_desc(
-        HPCT_ANCHOR_NONE, epi, HPCT_RED_NONE, 0, [tensor_desc(shape, sa), tensor_desc(_sh(b_view), sb)], [_sh(out)]))
-    return plan, [a_view, b_view]
+    sa = tuple(int(v) for v in a_view.stride())
+    ins, descs, epi = [a_view], [tensor_desc(shape, sa)], []
+    sb = None
+    if binary is not None:
+        sb = tuple(int(v) for v in b_view.stride())
+        ins.append(b_view)
+        descs.append(tensor_desc(_sh(b_view), sb))
+        epi.append(_MAP_BINARY[binary])
+    epi += [_MAP_UNARY[u] for u in unary]
+    plan = _cached(("eltwise", shape, sa, sb, binary, tuple(unary), float(scale)), lambda: op_desc(
+        HPCT_ANCHOR_NONE, epi, HPCT_RED_NONE, 0, descs, [_sh(out)], scale=scale))
+    return plan, ins
+
+
+def eltwise_map(a_view, out, unary=(), binary=None, b_view=None, scale=1.0, stream=None) -> None:
+    """out = steps(a_view binary b_view) or steps(a_view); binary in {"add","mul","sub","div"}, steps from
+    {"relu","gelu","scale","sqrt","sin","cos","exp","tanh","sigmoid"}."""
+    plan, ins = eltwise_map_plan(a_view, out, unary, binary, b_view, scale)
+    plan.launch(ins, [out], stream)
+
+
+def eltwise_plan(a_view, b_view, out, op, relu=False):
+    """out = [relu](a_view op b_view): the two-operand case of eltwise_map_plan."""
+    return eltwise_map_plan(a_view, out, ("relu",) if relu else (), op, b_view)
 
 
 def eltwise(a_view, b_view, out, op, relu=False, stream=None) -> None:
-    """out = [relu](a_view + b_view) or [relu](a_view * b_view); op in {"add", "mul"}."""
+    """out = [relu](a_view op b_view); op in {"add", "mul", "sub", "div"}."""
     plan, ins = eltwise_plan(a_view, b_view, out, op, relu)
     plan.launch(ins, [out], stream)
 

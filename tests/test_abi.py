@@ -522,7 +522,11 @@ def test_eltwise_plans_and_errors():
     expect(H.HPCT_ERR_SHAPE_MISMATCH, eltwise_desc((4, 8), (8, 1), (8, 1), out_shape=(8, 4)))
     d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.in_[1] = H.tensor_desc((4, 4), (4, 1))
     expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
-    d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.n_epi = 2; d.epi[1] = H.HPCT_EPI_GELU_TANH
+    d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.n_epi = 2; d.epi[1] = H.HPCT_EPI_GELU_TANH   # any unary step may follow
+    assert H.Plan(d).kernel_name == "eltwise_binary<vec4>"
+    d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.n_epi = 2; d.epi[1] = H.HPCT_EPI_BIAS_COL    # ... nothing else
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.n_epi = 2; d.epi[1] = H.HPCT_EPI_SUB_TENSOR  # one tensor operand only
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = eltwise_desc((4, 8), (8, 1), (8, 1)); d.reduce = H.HPCT_RED_SOFTMAX_LAST
     expect(H.HPCT_ERR_UNSUPPORTED, d)
@@ -530,6 +534,34 @@ def test_eltwise_plans_and_errors():
     expect(H.HPCT_ERR_BAD_DESC, d)
     d = cfg_desc(1); d.epi[0] = H.HPCT_EPI_ADD_TENSOR          # not after an anchor
     expect(H.HPCT_ERR_UNSUPPORTED, d)
+
+
+def test_eltwise_chain_plans():
+    un = [H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_SIN, H.HPCT_EPI_COS, H.HPCT_EPI_EXP, H.HPCT_EPI_TANH, H.HPCT_EPI_SIGMOID,
+          H.HPCT_EPI_SQRT, H.HPCT_EPI_RELU]
+    # one operand, eight steps; a strided slice runs through the scalar variant
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, un, H.HPCT_RED_NONE, 0, [(8192, 4096)], [(8192, 4096)], scale=0.5)
+    p = H.Plan(d)
+    assert p.kernel_name == "eltwise_unary<vec4>" and p.workspace_bytes == 0
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SQRT], H.HPCT_RED_NONE, 0, [H.tensor_desc((3, 5), (10, 2))], [(3, 5)])
+    assert H.Plan(d).kernel_name == "eltwise_unary<scalar>"
+    for b in (H.HPCT_EPI_SUB_TENSOR, H.HPCT_EPI_DIV_TENSOR):
+        d = H.op_desc(H.HPCT_ANCHOR_NONE, [b, H.HPCT_EPI_SQRT], H.HPCT_RED_NONE, 0, [(16, 8), H.tensor_desc((16, 8), (0, 1))], [(16, 8)])
+        assert H.Plan(d).kernel_name == "eltwise_binary<vec4>"
+    # RELU alone on a contiguous NCHW tensor stays with the per-channel chain; on any other view it is a step
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0, [(2, 3, 4, 4)], [(2, 3, 4, 4)])
+    assert H.Plan(d).kernel_name.startswith("affine_planes")
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0, [(7, 9)], [(7, 9)])
+    assert H.Plan(d).kernel_name == "eltwise_unary<scalar>"
+    # a unary chain takes one input; the steps are not epilogues of an anchor; the tensor op must come first
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SIN], H.HPCT_RED_NONE, 0, [(7, 9), (7, 9)], [(7, 9)])
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = cfg_desc(1); d.epi[1] = H.HPCT_EPI_SIN
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SIN, H.HPCT_EPI_ADD_TENSOR], H.HPCT_RED_NONE, 0, [(7, 9), (7, 9)], [(7, 9)])
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SIN], H.HPCT_RED_NONE, 0, [(7, 9)], [(7, 9)]); d.epi[0] = 18
+    expect(H.HPCT_ERR_BAD_DESC, d)
 
 
 def test_maxpool_alone_plans():

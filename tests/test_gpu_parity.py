@@ -680,7 +680,75 @@ def check_eltwise(a_view, b_view, tag):
             want = ref.eltwise_binary(flat(a_view), flat(b_view), shape, sa, sb, op, relu)
             # one fp32 rounding of an exactly known sum or product
             assert np.array_equal(host(out), want.astype(np.float32)), (tag, op, relu)
+    for op in ("sub", "div"):
+        # a difference is exact in fp64; a correctly rounded fp32 quotient equals the fp64 quotient rounded once more
+        # (53 >= 2 * 24 + 2 bits)
+        out = torch.full(shape, float("nan"), device="cuda")
+        plan, ins = hpct.eltwise_map_plan(a_view, out, ("relu",), op, b_view)
+        plan.launch(ins, [out])
+        want = ref.eltwise_map(flat(a_view), shape, sa, ("relu",), op, flat(b_view), sb)
+        with np.errstate(over="ignore"):
+            assert np.array_equal(host(out), want.astype(np.float32)), (tag, op)
     return names
+
+
+def view_flat(view):
+    base = view._base if view._base is not None else view
+    return host(base).reshape(-1)[view.storage_offset() - base.storage_offset():]
+
+
+# (chains are kept well conditioned: a step such as cos after exp would turn the fp32 rounding of a large
+# intermediate into an absolute error of the same size, which no fp32 evaluation can avoid)
+UNARY_CHAINS = [("sin",), ("cos",), ("exp",), ("tanh",), ("sigmoid",), ("gelu",), ("sin", "scale"), ("relu", "sqrt"),
+                ("tanh", "scale", "exp", "sqrt"), ("sin", "cos", "tanh", "sigmoid", "exp", "scale", "gelu", "relu")]
+
+
+def check_unary(a_view, tag, chains=UNARY_CHAINS, scale=1.7):
+    shape, sa = tuple(a_view.shape), tuple(a_view.stride())
+    names = set()
+    for steps in chains:
+        out = torch.full(shape, float("nan"), device="cuda")
+        plan, ins = hpct.eltwise_map_plan(a_view, out, steps, scale=scale)
+        plan.launch(ins, [out])
+        names.add(plan.kernel_name)
+        want = ref.eltwise_map(view_flat(a_view), shape, sa, steps, scale=scale)
+        assert show("%s %s" % (tag, "+".join(steps)), compare.pointwise(host(out), want))
+    return names
+
+
+def test_eltwise_unary_full_size():
+    X = dev(datagen.make(3)["X"])                      # N(0,1), 8192 x 4096
+    assert check_unary(X, "full", [("sin",), ("tanh", "scale", "exp", "sqrt")]) == {"eltwise_unary<vec4>"}
+    # sqrt alone is correctly rounded: equal to the fp64 root rounded once more
+    P = dev(datagen.gen_uniform(97, (8192, 4096), 0.0, 100.0))
+    out = torch.full((8192, 4096), float("nan"), device="cuda")
+    hpct.eltwise_map(P, out, ("sqrt",))
+    assert np.array_equal(host(out), ref.eltwise_map(host(P), (8192, 4096), (4096, 1), ("sqrt",)).astype(np.float32))
+
+
+def test_eltwise_unary_views_and_ranges():
+    a = dev(datagen.gen_normal(94, (6, 10, 12), 0.0, 2.0))
+    assert check_unary(a, "contiguous") == {"eltwise_unary<vec4>"}
+    assert check_unary(a.permute(2, 0, 1), "permuted") == {"eltwise_unary<scalar>"}
+    check_unary(a[:, 1:9, 3:11], "offset slice")
+    check_unary(a[1, 2, 5:12], "vector")
+    check_unary(a[:, :, 0:1].expand(6, 10, 12), "broadcast")
+    check_unary(dev(np.full((1,), 0.5, np.float32)), "single element")
+    # arguments far outside one period (the argument reduction must hold), large exponents, saturated tanh / sigmoid
+    big = dev(datagen.gen_uniform(95, (64, 100), -1.0e4, 1.0e4))
+    check_unary(big, "large angles", [("sin",), ("cos",)])
+    wide = dev(datagen.gen_uniform(96, (64, 100), -80.0, 80.0))
+    check_unary(wide, "wide", [("exp",), ("tanh",), ("sigmoid",), ("gelu",)])
+
+
+def test_eltwise_binary_then_steps():
+    a = dev(datagen.gen_uniform(98, (33, 40), 0.5, 4.0))
+    b = dev(datagen.gen_uniform(99, (40,), 0.5, 2.0)).expand(33, 40)
+    for op, steps in (("div", ("sqrt", "sin")), ("sub", ("scale", "sigmoid")), ("mul", ("tanh", "relu")), ("add", ("gelu", "exp"))):
+        out = torch.full((33, 40), float("nan"), device="cuda")
+        hpct.eltwise_map(a, out, steps, op, b, scale=-0.7)
+        want = ref.eltwise_map(host(a), (33, 40), (40, 1), steps, op, view_flat(b), (0, 1), scale=-0.7)
+        assert show("%s %s" % (op, "+".join(steps)), compare.pointwise(host(out), want))
 
 
 def test_eltwise_full_size_bias_row_and_same_shape():
