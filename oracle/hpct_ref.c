@@ -56,6 +56,15 @@ void ref_relu(double *Z, int64_t count)
     for (int64_t i = 0; i < count; ++i) Z[i] = Z[i] > 0.0 ? Z[i] : 0.0;
 }
 
+/* ---- Elementwise: multiplication by a constant, in place (the "Scale" of the
+ * fused Gemm-Scale operator named in Section 5.2).  The constant is the fp32
+ * value the GPU path receives, widened to double. */
+void ref_scale(double *Z, int64_t count, float s)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) Z[i] = Z[i] * (double)s;
+}
+
 /* ---- Reduction: softmax (Table 1) over the last dimension ---------------
  * Y[r][n] = exp(Z[r][n] - max_n Z[r][.]) / sum_n exp(Z[r][n] - max). */
 void ref_softmax_rows(const double *Z, int64_t rows, int64_t N, double *Y)

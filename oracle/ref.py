@@ -27,6 +27,7 @@ def lib():
         sig = {
             "ref_gemm_bias": [p, p, p, i64, i64, i64, p, p],
             "ref_relu": [p, i64],
+            "ref_scale": [p, i64, C.c_float],
             "ref_softmax_rows": [p, i64, i64, p],
             "ref_affine_relu_residual": [p, p, p, p, i64, i64, i64, p],
             "ref_avgpool_planes": [p, i64, i64, p],
@@ -86,6 +87,13 @@ def gemm_bias(X, W, bias=None, want_norm=False):
 def relu(Z):
     Z = np.array(Z, dtype=np.float64, order="C")
     lib().ref_relu(_ptr(Z), Z.size)
+    return Z
+
+
+def scale_const(Z, s):
+    """Z * s with s rounded to fp32 first (the constant the GPU path is given)."""
+    Z = np.array(Z, dtype=np.float64, order="C")
+    lib().ref_scale(_ptr(Z), Z.size, C.c_float(s))
     return Z
 
 

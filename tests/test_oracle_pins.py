@@ -847,3 +847,12 @@ def test_eltwise_map_views_by_brute_force():
     m = f32(rng.uniform(0.0, 9.0, size=(4, 10)))
     got = ref.eltwise_map(m.reshape(-1)[10:], (3, 5), (10, 2), ["sqrt"])
     assert np.array_equal(got, np.sqrt(m[1:, ::2].astype(np.float64)))
+
+
+def test_scale_const_is_multiplication_by_the_fp32_constant():
+    z = rng.normal(size=(5, 7))
+    assert np.array_equal(ref.scale_const(z, 1.0), z)
+    assert np.array_equal(ref.scale_const(z, -4.0), -4.0 * z)            # a power of two: exact
+    assert np.array_equal(ref.scale_const(ref.scale_const(z, 0.5), 8.0), 4.0 * z)
+    assert np.array_equal(ref.scale_const(np.ones(3), 0.1), np.full(3, float(np.float32(0.1))))
+    assert np.array_equal(ref.scale_const(np.array([2.0, -3.0]), 1.5), [3.0, -4.5])
