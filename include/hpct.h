@@ -30,12 +30,13 @@
  * then the operands of each epilogue / reduction in the order they run.
  *
  *   chain                                             in[]                          out[0]
- *   GEMM [+BIAS_COL] [+RELU] [+DROPOUT_HASH]          X[M,K], W[K,N], bias[N]       [M,N]
- *         [+SOFTMAX_LAST] (one kernel for N <= 256,
- *         GEMM then an in-place row softmax beyond)
- *   GEMM [+BIAS_COL] [+RELU] [+DROPOUT_HASH]          X[M,K], W[K,N], bias[N]       [M]
- *         MEAN_LAST [then reduce2 = SOFTMAX_LAST                                     (needs the
- *         over the M means]                                                          workspace)
+ *   GEMM [+BIAS_COL] [+SCALE_CONST] [+RELU]           X[M,K], W[K,N], bias[N]       [M,N]
+ *         [+DROPOUT_HASH] [+SOFTMAX_LAST] (one        (W row-major, strides (N,1),
+ *         kernel for N <= 256, GEMM then an           or stored transposed as an
+ *         in-place row softmax beyond)                [N,K] array: strides (1,K))
+ *   GEMM [+BIAS_COL] [+SCALE_CONST] [+RELU]           X[M,K], W[K,N], bias[N]       [M]
+ *         [+DROPOUT_HASH] MEAN_LAST [then reduce2 =                                  (needs the
+ *         SOFTMAX_LAST over the M means]                                             workspace)
  *   NONE  SCALE_SHIFT_CH [+RELU] [+ADD_RESIDUAL]      X[N,C,H,W], scale[C],         [N,C] (AVGPOOL_HW)
  *         then AVGPOOL_HW or no reduction             shift[C], R[N,C,H,W]          or [N,C,H,W]
  *   NONE  LAYERNORM_LAST (reduce_before_epi=1)        X[M,N], gamma[N], beta[N]     [M,N]
@@ -113,7 +114,7 @@ typedef enum {
     HPCT_EPI_RELU = 2,            /* max(x, 0) */
     HPCT_EPI_ADD_RESIDUAL = 3,    /* + R, same shape as the running value */
     HPCT_EPI_GELU_TANH = 4,       /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
-    HPCT_EPI_SCALE_CONST = 5,     /* * desc.scale */
+    HPCT_EPI_SCALE_CONST = 5,     /* * desc.scale (after BIAS_COL in a GEMM chain; a step of an elementwise chain) */
     HPCT_EPI_DROPOUT_HASH = 6,    /* training-mode dropout with the hash mask of the Section 5.3 case study: for
                                      element (i, j) of an [M,N] value, h = i*N + j + dropout_seed (uint64, wrapping),
                                      h ^= h >> 17; h ^= h << 31; h ^= h >> 8; rand = (float)(h % 1000) / 1000.0f;

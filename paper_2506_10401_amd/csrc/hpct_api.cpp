@@ -127,10 +127,11 @@ uint32_t dropout_threshold(float p) {
 }
 
 hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
-    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_RELU, HPCT_EPI_DROPOUT_HASH};
-    bool has[3];
-    if (!parse_epi(d, allowed, 3, has))
-        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [RELU] [DROPOUT_HASH] in that order");
+    static const hpct_epilogue order[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_CONST, HPCT_EPI_RELU, HPCT_EPI_DROPOUT_HASH};
+    bool has[4], ho[4];
+    if (!parse_epi(d, order, 4, ho))
+        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [SCALE_CONST] [RELU] [DROPOUT_HASH] in that order");
+    has[0] = ho[0]; has[1] = ho[2]; has[2] = ho[3]; has[3] = ho[1];
     if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_SOFTMAX_LAST && d.reduce != HPCT_RED_MEAN_LAST)
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: reduction must be NONE, SOFTMAX_LAST or MEAN_LAST");
     if (d.reduce != HPCT_RED_NONE && d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: the reduction runs after the epilogues");
@@ -146,8 +147,13 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     if (has[0]) REQUIRE_SHAPE(d.in[2], "bias", N);
     if (mean) REQUIRE_SHAPE(d.out[0], "out[0]", M);
     else REQUIRE_SHAPE(d.out[0], "out[0]", M, N);
+    // W: row-major [K,N], or the transposed storage of a linear layer's weight ([N,K] row-major seen as [K,N]
+    // with strides (1, K))
+    const bool wt = !contiguous(W) && W.stride[0] == 1 && W.stride[1] == K;
     for (int i = 0; i < d.n_in; ++i)
-        if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous row-major layouts are supported", i);
+        if (!contiguous(d.in[i]) && !(i == 1 && wt))
+            return fail(HPCT_ERR_UNSUPPORTED, i == 1 ? "in[1]: W must be row-major [K,N] (strides N, 1) or its transpose (strides 1, K)"
+                                                     : "in[%d]: only contiguous row-major layouts are supported", i);
     if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous row-major layouts are supported");
     if (M > kI32Max || K > kI32Max || N > kI32Max || M * N > kI32Max || M * K > kI32Max || K * N > kI32Max)
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM: operand larger than 2^31-1 elements");
@@ -155,6 +161,8 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     GemmParams g{};
     g.M = (int32_t)M; g.K = (int32_t)K; g.N = (int32_t)N;
     g.relu = has[1] ? 1 : 0; g.softmax = sm ? 1 : 0;
+    g.scale = has[3] ? d.scale : 1.0f;
+    g.wt = wt ? 1 : 0;
     if (has[2]) {
         if (!(d.dropout_p >= 0.f && d.dropout_p < 1.f)) return fail(HPCT_ERR_BAD_DESC, "DROPOUT_HASH: dropout_p must satisfy 0 <= p < 1");
         g.dropout = 1;
@@ -167,7 +175,7 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     p.kind = Kind::Gemm;
     p.u.gemm = g;
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has[0] ? 2 : -1; p.slot[3] = -1;
-    p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0);
+    p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.wt);
     p.ws_bytes = gemm_workspace_bytes((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0);
     return HPCT_OK;
 }

@@ -31,7 +31,14 @@ constexpr int KG = 4;   // k-groups of waves
 
 // EXT: the instance that also carries the hash dropout and the row-sum output (kept out of the
 // plain instance, whose 128-register budget at 1024 threads it would overflow)
-template <int BN, bool VEC, bool EXT>
+// BT: W stored transposed ([N,K] row-major).  A lane's four B values of a 16-k group for one output
+// column are then 16 contiguous bytes of that column's row; loading them lane by lane would make
+// neighbouring lanes read different rows (a quarter of the load rate, 27 us instead of 9 for
+// 64 x 256 x 256).  Instead a quad of lanes reads 64 contiguous bytes of one row and the wave
+// turns the 16 rows x 16 k block round through a private LDS strip (rows 20 words apart: the
+// 128-bit reads of 16 lanes cover all 64 banks).  A lane then owns columns l16, l16 + 16,
+// l16 + 32, l16 + 48 of its wave's 64 instead of four neighbours.
+template <int BN, bool VEC, bool EXT, bool BT>
 __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
     const float* __restrict__ X = p.X;
     const float* __restrict__ W = p.W;
@@ -39,15 +46,18 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
     float* __restrict__ Y = p.Y;
     const int M = p.M, K = p.K, N = p.N, relu = p.relu, softmax = p.softmax;
     constexpr int NG = BN / 64;  // column groups of waves
-    __shared__ float part[(KG - 1) * NG * 16 * 64];
+    __shared__ __attribute__((aligned(16))) float part[(KG - 1) * NG * 16 * 64];
     __shared__ float red[NG][BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q = lane >> 4, l16 = lane & 15;
     const int ng = wave % NG, kg = wave / NG;
     const int m0 = blockIdx.x * BM;
-    const int ncol = blockIdx.y * BN + ng * 64 + 4 * l16;  // first of this lane's four columns
+    const int cb = blockIdx.y * BN + ng * 64;              // first column of this wave
+    const int ncol = cb + 4 * l16;                         // first of this lane's four columns (row-major W)
     const int mrow = m0 + l16;                             // A row this lane loads
+    auto colb = [&](int b) { return BT ? cb + l16 + 16 * b : ncol + b; };   // output column of block b in this lane
+    float* const strip = part + wave * (16 * 20);          // BT: this wave's 16 x 16 exchange strip (part is free until the k-loop ends)
 
     // this wave's slice of K: a multiple of 16 per group
     const int ks = ((K + KG - 1) / KG + 15) & ~15;
@@ -63,7 +73,7 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
     // the step has been issued, so all 20 loads are in flight together.  With
     // VEC (K % 4 == 0 and N % 4 == 0; kend is then a multiple of 4) a 4-vector
     // is entirely inside or entirely outside.
-    constexpr int G = VEC ? ((EXT && BN == 256) ? 2 : 4) : 1;  // 16-k groups loaded together (fewer where registers are short)
+    constexpr int G = VEC ? (((EXT || BT) && BN == 256) ? 2 : 4) : 1;  // 16-k groups loaded together (fewer where registers are short)
     for (int k0 = kbeg; k0 < kend; k0 += 16 * G) {
         float4v a[G], w[G][4];
 #pragma unroll
@@ -76,14 +86,28 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) a[g][e] = *((mrow < M && k + e < kend) ? src + e : X);
             }
+            if (BT) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const float* wsrc = W + (int64_t)(k + s) * N + ncol;
-                if (VEC) {
-                    w[g][s] = load4((k + s < kend && ncol < N) ? wsrc : W);
-                } else {
+                for (int b = 0; b < 4; ++b) {   // row (= output column) cb + 16 b + lane / 4, k = kt .. kt + 3
+                    const int wr = cb + 16 * b + (lane >> 2), kt = k0 + 16 * g + 4 * (lane & 3);
+                    const float* wsrc = W + (int64_t)wr * K + kt;
+                    if (VEC) {
+                        w[g][b] = load4((wr < N && kt < kend) ? wsrc : W);
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) w[g][s][e] = *((k + s < kend && ncol + e < N) ? wsrc + e : W);
+                        for (int e = 0; e < 4; ++e) w[g][b][e] = *((wr < N && kt + e < kend) ? wsrc + e : W);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const float* wsrc = W + (int64_t)(k + s) * N + ncol;
+                    if (VEC) {
+                        w[g][s] = load4((k + s < kend && ncol < N) ? wsrc : W);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) w[g][s][e] = *((k + s < kend && ncol + e < N) ? wsrc + e : W);
+                    }
                 }
             }
         }
@@ -97,8 +121,30 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (!(k + s < kend && ncol + e < N)) w[g][s][e] = 0.f;
+                for (int e = 0; e < 4; ++e) {
+                    // BT: w[g][s] is still row cb + 16 s + lane / 4 at k = kt + e
+                    const bool ok = BT ? (cb + 16 * s + (lane >> 2) < N && k0 + 16 * g + 4 * (lane & 3) + e < kend)
+                                       : (k + s < kend && ncol + e < N);
+                    if (!ok) w[g][s][e] = 0.f;
+                }
+        }
+        if (BT) {   // turn each 16-row x 16-k block round: afterwards w[g][s][b] = W(k0 + 16 g + 4 q + s, column colb(b))
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float4v t[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    // LDS operations of one wave execute in order; the fences only keep the compiler from moving them
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    *reinterpret_cast<float4v*>(strip + (lane >> 2) * 20 + 4 * (lane & 3)) = w[g][b];
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    t[b] = *reinterpret_cast<const float4v*>(strip + l16 * 20 + 4 * q);
+                }
+#pragma unroll
+                for (int s2 = 0; s2 < 4; ++s2) w[g][s2] = float4v{t[0][s2], t[1][s2], t[2][s2], t[3][s2]};
+            }
         }
 #pragma unroll
         for (int g = 0; g < G; ++g)
@@ -110,6 +156,7 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
     }
 
     // ---- combine the k-groups: groups 1..3 publish, group 0 adds them in order
+    if (BT) __syncthreads();   // the exchange strips share `part`: every wave has left its k-loop
     if (kg > 0) {
         float* dst = part + ((kg - 1) * NG + ng) * 16 * 64 + lane;
 #pragma unroll
@@ -133,12 +180,12 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
     // ---- epilogue (lead waves): lane holds rows 4q..4q+3 (register r) of columns ncol..ncol+3 (block b)
     bool cok[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) cok[b] = ncol + b < N;
+    for (int b = 0; b < 4; ++b) cok[b] = colb(b) < N;
     if (lead) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const float bv = (bias && cok[b]) ? bias[ncol + b] : 0.f;
-            acc[b] = acc[b] + bv;
+            const float bv = (bias && cok[b]) ? bias[colb(b)] : 0.f;
+            acc[b] = (acc[b] + bv) * p.scale;
             if (relu) {
                 acc[b].x = fmaxf(acc[b].x, 0.f); acc[b].y = fmaxf(acc[b].y, 0.f);
                 acc[b].z = fmaxf(acc[b].z, 0.f); acc[b].w = fmaxf(acc[b].w, 0.f);
@@ -146,7 +193,7 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
             if (EXT && p.dropout) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const uint64_t off = (uint64_t)(m0 + q * 4 + r) * (uint64_t)N + (uint64_t)(ncol + b);
+                    const uint64_t off = (uint64_t)(m0 + q * 4 + r) * (uint64_t)N + (uint64_t)colb(b);
                     acc[b][r] = dropout_u(off + p.seed) < p.drop_t ? 0.f : acc[b][r] * p.keep_scale;
                 }
             }
@@ -239,12 +286,12 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
         for (int r = 0; r < 4; ++r) {
             const int m = m0 + q * 4 + r;
             if (m < M) {
-                float* dst = Y + (int64_t)m * N + ncol;
-                if (VEC && cok[3]) store4(dst, float4v{acc[0][r], acc[1][r], acc[2][r], acc[3][r]});
+                float* dst = Y + (int64_t)m * N;
+                if (!BT && VEC && cok[3]) store4(dst + ncol, float4v{acc[0][r], acc[1][r], acc[2][r], acc[3][r]});
                 else {
 #pragma unroll
                     for (int b = 0; b < 4; ++b)
-                        if (cok[b]) dst[b] = acc[b][r];
+                        if (cok[b]) dst[colb(b)] = acc[b][r];
                 }
             }
         }
@@ -258,10 +305,17 @@ hipError_t launch_bn(const GemmParams& p, hipStream_t stream) {
     dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), block(BN * 4);
     const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
     const bool ext = p.dropout || p.mean;
-    if (vec && ext) hipLaunchKernelGGL((gemm_rows16<BN, true, true>), grid, block, 0, stream, p);
-    else if (vec) hipLaunchKernelGGL((gemm_rows16<BN, true, false>), grid, block, 0, stream, p);
-    else if (ext) hipLaunchKernelGGL((gemm_rows16<BN, false, true>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((gemm_rows16<BN, false, false>), grid, block, 0, stream, p);
+    if (p.wt) {
+        if (vec && ext) hipLaunchKernelGGL((gemm_rows16<BN, true, true, true>), grid, block, 0, stream, p);
+        else if (vec) hipLaunchKernelGGL((gemm_rows16<BN, true, false, true>), grid, block, 0, stream, p);
+        else if (ext) hipLaunchKernelGGL((gemm_rows16<BN, false, true, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((gemm_rows16<BN, false, false, true>), grid, block, 0, stream, p);
+    } else {
+        if (vec && ext) hipLaunchKernelGGL((gemm_rows16<BN, true, true, false>), grid, block, 0, stream, p);
+        else if (vec) hipLaunchKernelGGL((gemm_rows16<BN, true, false, false>), grid, block, 0, stream, p);
+        else if (ext) hipLaunchKernelGGL((gemm_rows16<BN, false, true, false>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((gemm_rows16<BN, false, false, false>), grid, block, 0, stream, p);
+    }
     return hipGetLastError();
 }
 
@@ -288,14 +342,15 @@ size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, in
     return s > 1 ? (size_t)s * (size_t)M * (size_t)N * 4 : 0;
 }
 
-LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean) {
-    if (gemm_use_tile(M, K, N, softmax, mean)) return gemm_tile_shape(M, N, gemm_ksplit(M, K, N, mean));
+LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt) {
+    if (gemm_use_tile(M, K, N, softmax, mean)) return gemm_tile_shape(M, N, gemm_ksplit(M, K, N, mean), wt);
     const int bn = pick_bn(N);
     LaunchShape s{};
     s.grid[0] = (uint32_t)((M + BM - 1) / BM); s.grid[1] = (uint32_t)((N + bn - 1) / bn); s.grid[2] = 1;
     s.block[0] = (uint32_t)(bn * 4); s.block[1] = s.block[2] = 1;
     s.lds_bytes = (uint32_t)(((KG - 1) * (bn / 64) * 16 * 64 + (bn / 64) * BM) * 4);
-    s.kernel = bn == 64 ? "gemm_rows16<64>" : (bn == 128 ? "gemm_rows16<128>" : "gemm_rows16<256>");
+    if (wt) s.kernel = bn == 64 ? "gemm_rows16<64,wt>" : (bn == 128 ? "gemm_rows16<128,wt>" : "gemm_rows16<256,wt>");
+    else s.kernel = bn == 64 ? "gemm_rows16<64>" : (bn == 128 ? "gemm_rows16<128>" : "gemm_rows16<256>");
     return s;
 }
 

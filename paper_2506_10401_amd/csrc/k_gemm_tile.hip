@@ -39,11 +39,14 @@ constexpr int kXcds = 8;
 // T = tile edge, 128 or 64: a wave owns (T/2) x (T/2) as WB x WB accumulators, WB = T/64.
 // 128: four work-groups per CU (one wave of each per SIMD), 128 registers per lane, 64 of them
 // accumulators.  64: for outputs with too few 128-tiles to fill the chip; 16 accumulator registers.
-template <int T, bool VEC>
+// BT: W is stored transposed ([N,K] row-major, the layout of a linear layer's weight).  Its tile is
+// then staged and read exactly like the A tile (rows = output columns, 128-bit reads along k):
+// the MFMA's A and B operands have mirror-image lane layouts.
+template <int T, bool VEC, bool BT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) void gemm_tile(GemmParams p, int tiles_n, int items) {
     constexpr int TM = T, TN = T, WB = T / 64, LDB = T + 8;
     __shared__ __attribute__((aligned(16))) float As[2][TM * LDA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BT ? TN * LDA : BK * LDB];
     __shared__ float rs[2][TM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -93,13 +96,24 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ra[i][e] = *((m < M && k + e < k_hi) ? src + e : X);
             }
-            const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
-            const float* wsrc = W + (int64_t)kk * N + n;
-            if (VEC) {
-                rb[i] = load4((kk < k_hi && n < N) ? wsrc : W);
-            } else {
+            if (BT) {
+                const int n = n0 + ar + 64 * i;
+                const float* wsrc = W + (int64_t)n * K + k;
+                if (VEC) {
+                    rb[i] = load4((n < N && k < k_hi) ? wsrc : W);
+                } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) rb[i][e] = *((kk < k_hi && n + e < N) ? wsrc + e : W);
+                    for (int e = 0; e < 4; ++e) rb[i][e] = *((n < N && k + e < k_hi) ? wsrc + e : W);
+                }
+            } else {
+                const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
+                const float* wsrc = W + (int64_t)kk * N + n;
+                if (VEC) {
+                    rb[i] = load4((kk < k_hi && n < N) ? wsrc : W);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) rb[i][e] = *((kk < k_hi && n + e < N) ? wsrc + e : W);
+                }
             }
         }
     };
@@ -112,10 +126,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (!(m < M && k + e < k_hi)) ra[i][e] = 0.f;
-                if (!(kk < k_hi && n + e < N)) rb[i][e] = 0.f;
+                if (BT ? !(n0 + ar + 64 * i < N && k + e < k_hi) : !(kk < k_hi && n + e < N)) rb[i][e] = 0.f;
             }
             *reinterpret_cast<float4v*>(&As[buf][(ar + 64 * i) * LDA + ak]) = ra[i];
-            *reinterpret_cast<float4v*>(&Bs[buf][(bk + BSTEP * i) * LDB + bn]) = rb[i];
+            if (BT) *reinterpret_cast<float4v*>(&Bs[buf][(ar + 64 * i) * LDA + ak]) = rb[i];
+            else *reinterpret_cast<float4v*>(&Bs[buf][(bk + BSTEP * i) * LDB + bn]) = rb[i];
         }
     };
 
@@ -131,17 +146,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
         // waves inside their MFMA block win the issue arbitration over waves that are staging
         __builtin_amdgcn_s_setprio(1);
         const float* a_base = &As[buf][(wm * (TM / 2) + l32) * LDA + 4 * h];
-        const float* b_base = &Bs[buf][(4 * h) * LDB + wn * (TN / 2) + l32];
+        const float* b_base = BT ? &Bs[buf][(wn * (TN / 2) + l32) * LDA + 4 * h] : &Bs[buf][(4 * h) * LDB + wn * (TN / 2) + l32];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             float4v a[WB];
 #pragma unroll
             for (int i = 0; i < WB; ++i) a[i] = *reinterpret_cast<const float4v*>(a_base + i * 32 * LDA + 8 * t);
+            float4v bt[WB];
+            if (BT) {
+#pragma unroll
+                for (int j = 0; j < WB; ++j) bt[j] = *reinterpret_cast<const float4v*>(b_base + j * 32 * LDA + 8 * t);
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float b[WB];
 #pragma unroll
-                for (int j = 0; j < WB; ++j) b[j] = b_base[(8 * t + e) * LDB + j * 32];
+                for (int j = 0; j < WB; ++j) b[j] = BT ? bt[j][e] : b_base[(8 * t + e) * LDB + j * 32];
 #pragma unroll
                 for (int i = 0; i < WB; ++i)
 #pragma unroll
@@ -197,7 +217,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm * (TM / 2) + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                float v = acc[i][j][r] + bv;
+                float v = (acc[i][j][r] + bv) * p.scale;
                 if (p.relu) v = fmaxf(v, 0.f);
                 if (p.dropout) {
                     const uint64_t off = (uint64_t)row * (uint64_t)N + (uint64_t)col;
@@ -248,7 +268,7 @@ __global__ __launch_bounds__(256) void split_k_finish(GemmParams p) {
         const int row = (int)(idx / p.N), col = (int)(idx - (int64_t)row * p.N);
 #pragma unroll
         for (int e = 0; e < E; ++e) {
-            float y = x[e] + (p.bias ? p.bias[col + e] : 0.f);
+            float y = (x[e] + (p.bias ? p.bias[col + e] : 0.f)) * p.scale;
             if (p.relu) y = fmaxf(y, 0.f);
             if (p.dropout) y = dropout_u((uint64_t)idx + (uint64_t)e + p.seed) < p.drop_t ? 0.f : y * p.keep_scale;
             x[e] = y;
@@ -335,13 +355,14 @@ int gemm_tile_edge(int32_t M, int32_t N) {
     return (tiles >= 512 && tiles * 100 >= per_cu * 256 * 85) ? 128 : 64;
 }
 
-LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit) {
+LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit, int32_t wt) {
     const int t = gemm_tile_edge(M, N);
     LaunchShape s{};
     s.grid[0] = (uint32_t)(((M + t - 1) / t) * ((N + t - 1) / t) * ksplit); s.grid[1] = s.grid[2] = 1;
     s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)((2 * t * LDA + 2 * BK * (t + 8) + 2 * t) * 4);
-    s.kernel = t == 128 ? "gemm_tile128" : (ksplit > 1 ? "gemm_tile64<split-k>" : "gemm_tile64");
+    s.lds_bytes = (uint32_t)((2 * t * LDA + 2 * (wt ? t * LDA : BK * (t + 8)) + 2 * t) * 4);
+    if (wt) s.kernel = t == 128 ? "gemm_tile128<wt>" : (ksplit > 1 ? "gemm_tile64<wt,split-k>" : "gemm_tile64<wt>");
+    else s.kernel = t == 128 ? "gemm_tile128" : (ksplit > 1 ? "gemm_tile64<split-k>" : "gemm_tile64");
     return s;
 }
 
@@ -351,9 +372,14 @@ template <int T>
 hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
     const int tiles_m = (p.M + T - 1) / T, tiles_n = (p.N + T - 1) / T;
     const int items = tiles_m * tiles_n * p.ksplit;
-    const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
-    if (vec) hipLaunchKernelGGL((gemm_tile<T, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
-    else hipLaunchKernelGGL((gemm_tile<T, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+    if (p.wt) {   // both operands are read along k
+        if (p.K % 4 == 0) hipLaunchKernelGGL((gemm_tile<T, true, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+        else hipLaunchKernelGGL((gemm_tile<T, false, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+    } else {
+        const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
+        if (vec) hipLaunchKernelGGL((gemm_tile<T, true, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+        else hipLaunchKernelGGL((gemm_tile<T, false, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+    }
     return hipGetLastError();
 }
 

@@ -236,21 +236,27 @@ def _sh(t) -> Tuple[int, ...]:
 # ---- the five chains ---------------------------------------------------------
 # Each chain has a *_plan function (descriptor -> cached Plan plus the operand
 # list in descriptor order) and a convenience function that launches it.
-def gemm_bias_relu_softmax_plan(X, W, bias, out, relu=True, softmax=True):
+def gemm_bias_relu_softmax_plan(X, W, bias, out, relu=True, softmax=True, scale=None):
+    """W: [K,N] row-major, or the .t() view of an [N,K] row-major tensor (a linear layer's weight).
+    `scale`: constant multiplied in after the bias (the Gemm-Scale operator), None = no such step."""
     M, K = _sh(X)
     N = _sh(W)[1]
-    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_RELU] if relu else [])
+    wst = tuple(int(v) for v in W.stride())
+    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_CONST] if scale is not None else []) + \
+        ([HPCT_EPI_RELU] if relu else [])
     ins = [X, W] + ([bias] if bias is not None else [])
-    plan = _cached(("gemm", M, K, N, tuple(epi), softmax), lambda: op_desc(
-        HPCT_ANCHOR_GEMM, epi, HPCT_RED_SOFTMAX_LAST if softmax else HPCT_RED_NONE, 0,
-        [_sh(t) for t in ins], [_sh(out)]))
+    descs = [_sh(X), tensor_desc(_sh(W), wst)] + ([_sh(bias)] if bias is not None else [])
+    plan = _cached(("gemm", M, K, N, wst, tuple(epi), softmax, scale), lambda: op_desc(
+        HPCT_ANCHOR_GEMM, epi, HPCT_RED_SOFTMAX_LAST if softmax else HPCT_RED_NONE, 0, descs, [_sh(out)],
+        scale=1.0 if scale is None else scale))
     return plan, ins
 
 
-def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, workspace=None, stream=None) -> None:
-    """out = softmax_rows(relu(X @ W + bias)); relu / softmax / bias optional.  `workspace`: GPU tensor of at
-    least plan.workspace_bytes bytes when that is not 0 (small outputs with a long K are computed in K slices)."""
-    plan, ins = gemm_bias_relu_softmax_plan(X, W, bias, out, relu, softmax)
+def gemm_bias_relu_softmax(X, W, bias, out, relu=True, softmax=True, workspace=None, stream=None, scale=None) -> None:
+    """out = softmax_rows(relu((X @ W + bias) * scale)); relu / softmax / bias / scale optional.  `workspace`: GPU
+    tensor of at least plan.workspace_bytes bytes when that is not 0 (small outputs with a long K are computed in
+    K slices)."""
+    plan, ins = gemm_bias_relu_softmax_plan(X, W, bias, out, relu, softmax, scale)
     plan.launch(ins, [out], stream, workspace)
 
 

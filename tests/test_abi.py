@@ -184,7 +184,9 @@ def test_unsupported_but_well_formed():
     d = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_SOFTMAX_LAST, 0, [(64, 256), (256, 512)], [(64, 512)])
     assert H.Plan(d).kernel_name == "gemm_rows16<256>" and H.Plan(d).launch_shape()[0] == (4, 2, 1)
     # non-contiguous layouts
-    d = cfg_desc(1); d.in_[1] = H.tensor_desc((256, 256), (1, 256))  # transposed W
+    d = cfg_desc(1); d.in_[1] = H.tensor_desc((256, 256), (1, 256))  # transposed W: an instance of its own
+    assert H.Plan(d).kernel_name == "gemm_rows16<256,wt>"
+    d = cfg_desc(1); d.in_[1] = H.tensor_desc((256, 256), (512, 2))  # any other stride pattern is refused
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = cfg_desc(3); d.in_[0] = H.tensor_desc((8192, 4096), (8192, 1))  # row pitch
     expect(H.HPCT_ERR_UNSUPPORTED, d)
@@ -503,6 +505,31 @@ def test_gemm_split_k_plans():
     g = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_NONE, 0, [(1024, 256), (256, 1024)], [(1024, 1024)])
     assert H.Plan(g).kernel_name == "gemm_tile64" and H.Plan(g).workspace_bytes == 0
     assert H.Plan(chain6_desc(1024, 4096, 1024)).kernel_name == "gemm_tile64"
+
+
+def test_gemm_transposed_weight_and_scale_plans():
+    def g(M, K, N, wstride, epi=(H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU), red=H.HPCT_RED_NONE, scale=1.0):
+        ins = [(M, K), H.tensor_desc((K, N), wstride)] + ([(N,)] if H.HPCT_EPI_BIAS_COL in epi else [])
+        return H.op_desc(H.HPCT_ANCHOR_GEMM, list(epi), red, 0, ins, [(M, N)], scale=scale)
+    # W as the transposed view of an [N,K] row-major array: strides (1, K)
+    assert H.Plan(g(64, 256, 256, (1, 256), red=H.HPCT_RED_SOFTMAX_LAST)).kernel_name == "gemm_rows16<256,wt>"
+    assert H.Plan(g(4096, 1024, 4096, (1, 1024))).kernel_name == "gemm_tile128<wt>"
+    p = H.Plan(g(256, 2048, 256, (1, 2048)))
+    assert p.kernel_name == "gemm_tile64<wt,split-k>" and p.workspace_bytes == H.Plan(g(256, 2048, 256, (256, 1))).workspace_bytes
+    assert H.Plan(g(64, 256, 256, (256, 1))).kernel_name == "gemm_rows16<256>"
+    # any other W layout is refused; X and the output stay row-major
+    expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (1, 512)))
+    expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (512, 1)))
+    expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (2, 512)))
+    d = g(64, 256, 256, (256, 1)); d.in_[0] = H.tensor_desc((64, 256), (1, 64))
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    # Gemm-Scale: SCALE_CONST sits between the bias and the ReLU
+    e = (H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_RELU)
+    assert H.Plan(g(64, 256, 256, (256, 1), e, scale=0.5)).kernel_name == "gemm_rows16<256>"
+    assert H.Plan(g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST,), scale=0.5)).kernel_name == "gemm_rows16<256>"
+    assert H.Plan(g(4096, 1024, 4096, (1, 1024), e + (H.HPCT_EPI_DROPOUT_HASH,), scale=2.0)).kernel_name == "gemm_tile128<wt>"
+    expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU, H.HPCT_EPI_SCALE_CONST)))
+    expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_BIAS_COL)))
 
 
 def eltwise_desc(shape, sa, sb, add=True, relu=False, out_shape=None):

@@ -112,6 +112,81 @@ def test_gemm_split_k(M, K, N):
     assert np.array_equal(got, again)
 
 
+# ------------------------- W stored transposed (a linear layer's [N,K] weight) and the Gemm-Scale epilogue
+def run_gemm(t, wt=False, relu=True, softmax=False, bias=True, scale=None):
+    """through the C ABI; wt: the device copy of W is [N,K] row-major and its .t() view is passed"""
+    X = dev(t["X"])
+    W = dev(np.ascontiguousarray(t["W"].T)).t() if wt else dev(t["W"])
+    b = dev(t["bias"]) if bias else None
+    M, N = X.shape[0], W.shape[1]
+    out = torch.full((M, N), float("nan"), device="cuda")
+    plan, ins = hpct.gemm_bias_relu_softmax_plan(X, W, b, out, relu=relu, softmax=softmax, scale=scale)
+    ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda") if plan.workspace_bytes else None
+    plan.launch(ins, [out], workspace=ws)
+    return host(out), plan.kernel_name
+
+
+def wt_name(plain):
+    """kernel name of the transposed-W instance of `plain`"""
+    if plain.startswith("gemm_rows16<"):
+        return plain[:-1] + ",wt>"
+    return plain.replace("<", "<wt,") if "<" in plain else plain + "<wt>"
+
+
+@pytest.mark.parametrize("M,K,N", [
+    (64, 256, 256), (17, 5, 10), (70, 100, 63), (33, 36, 130), (3, 300, 129), (2, 1, 3),       # 16-row kernel
+    (4096, 256, 4096), (1024, 512, 1024), (700, 260, 644), (515, 37, 1001), (2900, 33, 3001),  # tiles of 128 and 64
+    (256, 2048, 256), (200, 3000, 333)])                                                       # K slices
+def test_gemm_transposed_weight(M, K, N):
+    print("gemm wt M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    plain, plain_name = run_gemm(t, wt=False)
+    got, name = run_gemm(t, wt=True)
+    # (with K = 1 or N = 1 the transposed storage is also row-major)
+    assert name == (plain_name if K == 1 or N == 1 else wt_name(plain_name)), (name, plain_name)
+    assert show("gemm wt +bias+relu", compare.contraction(got, ref.relu(Z), Dn))
+    assert np.max(np.abs(got - ref.relu(Z)) / Dn) < 1e-5
+    # the same products in the same order as with the row-major copy of W: bit-identical results
+    assert np.array_equal(got.view(np.uint32), plain.view(np.uint32))
+    got, _ = run_gemm(t, wt=True, softmax=True)
+    assert show("softmax", compare.pointwise(got, ref.chain1(t["X"], t["W"], t["bias"])))
+    Z0, Dn0 = ref.gemm_bias(t["X"], t["W"], None, want_norm=True)
+    got, _ = run_gemm(t, wt=True, relu=False, bias=False)
+    assert show("anchor alone", compare.contraction(got, Z0, Dn0))
+
+
+def test_gemm_transposed_weight_is_not_symmetric_in_k_and_n():
+    # W = a shift matrix: (X W)[m, n] = X[m, n-1]; reading W with k and n swapped would give X[m, n+1]
+    X = datagen.gen_uniform(6, (40, 96), -1, 1)
+    Wm = np.zeros((96, 96), np.float32)
+    Wm[np.arange(95), np.arange(1, 96)] = 1.0
+    got, _ = run_gemm({"X": X, "W": Wm}, wt=True, relu=False, bias=False)
+    want = np.zeros_like(X); want[:, 1:] = X[:, :-1]
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("M,K,N,scale", [(64, 256, 256, 0.5), (33, 36, 130, -3.7), (1024, 512, 1024, 0.125), (515, 37, 1001, -0.3),
+                                         (256, 2048, 256, 1.7)])
+def test_gemm_scale(M, K, N, scale):
+    # Gemm-Scale (Section 5.2): (X W + bias) * scale, then ReLU / softmax
+    print("gemm scale M=%d K=%d N=%d s=%r" % (M, K, N, scale), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    Zs, Ds = ref.scale_const(Z, scale), Dn * abs(float(np.float32(scale)))
+    for wt in (False, True):
+        got, _ = run_gemm(t, wt=wt, relu=False, scale=scale)
+        assert show("scaled", compare.contraction(got, Zs, Ds))
+        got, _ = run_gemm(t, wt=wt, relu=True, scale=scale)
+        assert show("scaled + relu", compare.contraction(got, ref.relu(Zs), Ds))
+    got, _ = run_gemm(t, softmax=True, scale=scale)
+    assert show("scaled + relu + softmax", compare.pointwise(got, ref.softmax_rows(ref.relu(Zs))))
+    # scale = 1 is the chain without the step, bit for bit
+    one, _ = run_gemm(t, scale=1.0)
+    none, _ = run_gemm(t)
+    assert np.array_equal(one.view(np.uint32), none.view(np.uint32))
+
+
 def test_gemm_identity_weight_is_exact():
     X = datagen.gen_uniform(5, (48, 64), -1, 1)
     out = torch.empty(48, 64, device="cuda")
