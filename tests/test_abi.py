@@ -60,7 +60,7 @@ def test_the_five_workloads_plan_and_launch_shapes():
     want = {
         1: ("gemm_rows16<256>", (4, 1, 1), (1024, 1, 1)),
         2: ("affine_planes_vec<pool>", (2048, 1, 1), (512, 1, 1)),
-        3: ("layernorm_rows_persist", (512, 1, 1), (256, 1, 1)),
+        3: ("layernorm_rows_persist", (768, 1, 1), (256, 1, 1)),
         4: ("conv2d_nchw_mfma<3x3,pipelined>", (3136, 1, 1), (256, 1, 1)),
         5: ("attn_fwd_d64<ks2>", (256, 1, 1), (512, 1, 1)),
     }
@@ -427,9 +427,11 @@ def reduce_desc(shape, stride, axis, red, out_shape=None, out_dtype=None):
 
 
 def test_axis_reduction_plans():
-    # rows of a matrix: the reduced axis is contiguous, a wave per output
-    p = H.Plan(reduce_desc((8192, 4096), (4096, 1), 1, H.HPCT_RED_SUM_AXIS))
+    # rows of a matrix: the reduced axis is contiguous, a wave per output; a work-group per output from 4096 columns
+    p = H.Plan(reduce_desc((8192, 2048), (2048, 1), 1, H.HPCT_RED_SUM_AXIS))
     assert p.kernel_name == "reduce_rows<wave>" and p.launch_shape()[0] == (2048, 1, 1)
+    p = H.Plan(reduce_desc((8192, 4096), (4096, 1), 1, H.HPCT_RED_SUM_AXIS))
+    assert p.kernel_name == "reduce_rows<group>" and p.launch_shape()[0] == (8192, 1, 1)
     # few long rows: a work-group per output
     p = H.Plan(reduce_desc((16, 1 << 20), (1 << 20, 1), 1, H.HPCT_RED_MEAN_AXIS))
     assert p.kernel_name == "reduce_rows<group>" and p.launch_shape()[0] == (16, 1, 1)

@@ -694,7 +694,7 @@ def check_reduce(view, axis, tag=""):
 
 def test_reduce_full_size_rows_cols_channels():
     X = dev(datagen.make(3)["X"])                       # [8192, 4096]
-    assert check_reduce(X, 1, "8192x4096") == {"reduce_rows<wave>"}
+    assert check_reduce(X, 1, "8192x4096") == {"reduce_rows<group>"}
     assert all(n.startswith("reduce_cols") for n in check_reduce(X, 0, "8192x4096"))
     T = dev(datagen.make(2)["X"])                       # [32, 64, 56, 56]
     assert check_reduce(T, 1, "nchw channels") == {"reduce_cols<scalar>"}
