@@ -87,6 +87,19 @@ template <int IV> struct VecOf;
 template <> struct VecOf<4> { typedef float4v type; };
 template <> struct VecOf<2> { typedef float2v type; };
 template <> struct VecOf<1> { typedef float type; };
+// Raw buffer loads for the pipelined staging: the hardware compares a lane's byte offset with the
+// descriptor's size and returns 0 for a lane beyond it without touching memory.  A slot in the
+// zero padding (or a weight row past K) is given the offset 2^31, larger than any tensor the
+// pipelined modes accept, so the halo costs no branch, no select and no zero fill, and the
+// channel-chunk offset rides in the scalar offset operand.
+constexpr unsigned kBufOob = 0x80000000u;
+constexpr int kBufWord3 = 0x00020000;   // descriptor word 3 for plain 32-bit data
+template <int IV>
+__device__ __forceinline__ typename VecOf<IV>::type buffer_load(__amdgpu_buffer_rsrc_t rs, unsigned voff, int soff) {
+    if constexpr (IV == 4) return __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, soff, 0));
+    else if constexpr (IV == 2) return __builtin_bit_cast(float2v, __builtin_amdgcn_raw_buffer_load_b64(rs, (int)voff, soff, 0));
+    else return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)voff, soff, 0));
+}
 constexpr int mode_iv(int mode) { return mode <= 2 ? 4 : (mode == 3 ? 2 : 1); }
 constexpr int mode_ipt(int mode) { return mode == 1 ? 2 : 4; }
 
@@ -153,39 +166,42 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     // ---- pipelined staging: geometry worked out once, loads through registers ------
     ivec ireg[IN_PER_T];
     float4v wreg[WPT];
-    int s_goff[IN_PER_T], s_loff[IN_PER_T];
-    int w_goff[WPT], w_loff[WPT];
+    unsigned s_goff[IN_PER_T], w_goff[WPT];   // byte offsets inside image n / the weight tensor, or kBufOob
+    int s_loff[IN_PER_T], w_loff[WPT];        // LDS word offsets, -1: nothing to write
+    __amdgpu_buffer_rsrc_t in_rs, wt_rs;
     if (FAST) {
+        in_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(in) + (int64_t)n * g.C * HW, 0, g.C * HW * 4, kBufWord3);
+        wt_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(wt), 0, g.K * g.C * TAPS * 4, kBufWord3);
         const int ldwv = g.ldw / IV;                         // IV-wide slots per staged row
         const int vslots = CC * g.rows_max * ldwv;           // slot -> (c, row, x)
 #pragma unroll
         for (int i = 0; i < IN_PER_T; ++i) {
             const int s = tid + i * 256;
-            s_goff[i] = -1; s_loff[i] = -1;
+            s_goff[i] = kBufOob; s_loff[i] = -1;
             if (s < vslots) {
                 const int c = s / (g.rows_max * ldwv);
                 const int rem = s - c * (g.rows_max * ldwv);
                 const int row = rem / ldwv, x = (rem - row * ldwv) * IV;
                 const int ih = ih0 + row, iw = iw0 + x - g.P - g.lpad;   // a multiple of IV, like W: all in or all out
                 s_loff[i] = c * g.ch_ld + row * g.ldw + x;
-                if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) s_goff[i] = ((n * g.C + c) * g.H + ih) * g.W + iw;
+                if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) s_goff[i] = (unsigned)(((c * g.H + ih) * g.W + iw) * 4);
             }
         }
 #pragma unroll
         for (int i = 0; i < WPT; ++i) {
             const int v = tid + i * 256;
             const int k = v / (FPR / 4), f4 = v % (FPR / 4);
-            w_goff[i] = (v < cfg::NV4 && k0 + k < g.K) ? ((k0 + k) * g.C) * TAPS + 4 * f4 : -1;   // rows past K are not staged: their accumulator rows are never stored
-            w_loff[i] = k * WLD + 4 * f4;
+            const bool live = v < cfg::NV4 && k0 + k < g.K;   // rows past K are not staged: their accumulator rows are never stored
+            w_goff[i] = live ? (unsigned)((((k0 + k) * g.C) * TAPS + 4 * f4) * 4) : kBufOob;
+            w_loff[i] = live ? k * WLD + 4 * f4 : -1;
         }
     }
     auto fetch = [&](int c0) {
 #pragma unroll
         for (int i = 0; i < IN_PER_T; ++i)
-            ireg[i] = s_goff[i] >= 0 ? *reinterpret_cast<const ivec*>(in + s_goff[i] + c0 * HW) : ivec{};
+            ireg[i] = buffer_load<IV>(in_rs, s_goff[i], c0 * HW * 4);
 #pragma unroll
-        for (int i = 0; i < WPT; ++i)
-            wreg[i] = w_goff[i] >= 0 ? load4(wt + w_goff[i] + c0 * TAPS) : float4v{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < WPT; ++i) wreg[i] = buffer_load<4>(wt_rs, w_goff[i], c0 * TAPS * 4);
     };
     auto stash = [&](int buf) {
         float* const ib = inS(buf);
@@ -195,7 +211,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
             if (s_loff[i] >= 0) *reinterpret_cast<ivec*>(ib + s_loff[i]) = ireg[i];
 #pragma unroll
         for (int i = 0; i < WPT; ++i) {
-            if (w_goff[i] >= 0) {
+            if (w_loff[i] >= 0) {
                 if (WLD % 4 == 0) {
                     *reinterpret_cast<float4v*>(wb + w_loff[i]) = wreg[i];
                 } else {  // rows are only 8-byte aligned
@@ -445,7 +461,9 @@ constexpr int kKT = 64;
 // Staging mode and the geometry that goes with it.
 int pick_mode(const ConvParams& p, ConvGeom* g_out) {
     const int cc = cc_of(p.R, p.win != 0);
-    if ((p.R == 1 || p.R == 3) && p.dil == 1 && p.C % cc == 0) {
+    // (the pipelined modes address one image and the weight tensor with 31-bit byte offsets)
+    const bool fits = (int64_t)p.C * p.H * p.W * 4 < (int64_t)1 << 31 && (int64_t)p.K * p.C * p.R * p.R * 4 < (int64_t)1 << 31;
+    if ((p.R == 1 || p.R == 3) && p.dil == 1 && p.C % cc == 0 && fits) {
         for (int iv = 4; iv >= 1; iv >>= 1) {
             if (p.W % iv) continue;
             const ConvGeom g = geom(p, iv);
