@@ -35,6 +35,7 @@
 // epilogue takes the 2x2 maximum entirely in registers: the vertical partner
 // is 8 lanes away inside a 16-lane DPP row, the horizontal one the neighbouring
 // lane; one lane in four stores.  8 divides the 224/112/56 extents of VGG maps.
+#include <type_traits>
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -116,10 +117,12 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     extern __shared__ __align__(16) float lds[];
     const int in_stage = CC * g.ch_ld;  // floats
     constexpr int NBUF = FAST ? 2 : 1;  // the general variant stages one chunk at a time
-    auto inS = [&](int buf) { return lds + buf * in_stage; };
-    auto wS = [&](int buf) { return lds + NBUF * in_stage + buf * cfg::W_STAGE; };
+    // weight stages first: their offsets are compile-time, so A-fragment reads need no address arithmetic
+    auto wS = [&](int buf) { return lds + buf * cfg::W_STAGE; };
+    auto inS = [&](int buf) { return lds + NBUF * cfg::W_STAGE + buf * in_stage; };
     float* const mulS = lds + NBUF * in_stage + NBUF * cfg::W_STAGE;  // KT floats: per-channel factor
     float* const addS = mulS + KT;                              // KT floats: per-channel addend
+    float* const dumpS = addS + KT;                             // 4 floats nobody reads
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
@@ -168,6 +171,12 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     float4v wreg[WPT];
     unsigned s_goff[IN_PER_T], w_goff[WPT];   // byte offsets inside image n / the weight tensor, or kBufOob
     int s_loff[IN_PER_T], w_loff[WPT];        // LDS word offsets, -1: nothing to write
+    // Where slot i goes in either stage.  Row geometry: slots with nothing to stage point at four spare words
+    // and the writes carry no predicate (-2 % of the kernel's time); window geometry: three slots in four are
+    // empty, whole waves skip their write under the predicate, which is cheaper there (+2.5 % without it).
+    constexpr bool PRED = WIN;
+    float* s_lptr[2][IN_PER_T];
+    float* w_lptr[2][WPT];
     __amdgpu_buffer_rsrc_t in_rs, wt_rs;
     if (FAST) {
         in_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(in) + (int64_t)n * g.C * HW, 0, g.C * HW * 4, kBufWord3);
@@ -195,6 +204,14 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
             w_goff[i] = live ? (unsigned)((((k0 + k) * g.C) * TAPS + 4 * f4) * 4) : kBufOob;
             w_loff[i] = live ? k * WLD + 4 * f4 : -1;
         }
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < IN_PER_T; ++i) s_lptr[b][i] = s_loff[i] >= 0 ? inS(b) + s_loff[i] : dumpS;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < WPT; ++i) w_lptr[b][i] = w_loff[i] >= 0 ? wS(b) + w_loff[i] : dumpS;
     }
     auto fetch = [&](int c0) {
 #pragma unroll
@@ -203,21 +220,20 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
 #pragma unroll
         for (int i = 0; i < WPT; ++i) wreg[i] = buffer_load<4>(wt_rs, w_goff[i], c0 * TAPS * 4);
     };
-    auto stash = [&](int buf) {
-        float* const ib = inS(buf);
-        float* const wb = wS(buf);
+    auto stash = [&](auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;
 #pragma unroll
         for (int i = 0; i < IN_PER_T; ++i)
-            if (s_loff[i] >= 0) *reinterpret_cast<ivec*>(ib + s_loff[i]) = ireg[i];
+            if (!PRED || s_loff[i] >= 0) *reinterpret_cast<ivec*>(s_lptr[buf][i]) = ireg[i];
 #pragma unroll
         for (int i = 0; i < WPT; ++i) {
-            if (w_loff[i] >= 0) {
-                if (WLD % 4 == 0) {
-                    *reinterpret_cast<float4v*>(wb + w_loff[i]) = wreg[i];
-                } else {  // rows are only 8-byte aligned
-                    *reinterpret_cast<float2v*>(wb + w_loff[i]) = float2v{wreg[i].x, wreg[i].y};
-                    *reinterpret_cast<float2v*>(wb + w_loff[i] + 2) = float2v{wreg[i].z, wreg[i].w};
-                }
+            if (PRED && w_loff[i] < 0) continue;
+            float* const dst = PRED ? wS(buf) + w_loff[i] : w_lptr[buf][i];
+            if (WLD % 4 == 0) {
+                *reinterpret_cast<float4v*>(dst) = wreg[i];
+            } else {  // rows are only 8-byte aligned
+                *reinterpret_cast<float2v*>(dst) = float2v{wreg[i].x, wreg[i].y};
+                *reinterpret_cast<float2v*>(dst + 2) = float2v{wreg[i].z, wreg[i].w};
             }
         }
     };
@@ -300,10 +316,20 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     // the pipelined variant is built for dilation 1 only, so that its tap offsets stay compile-time
     // immediates of the LDS reads (a run-time dilation costs 4.5 % there); dilated convs take the general one
     const int dl = FAST ? 1 : g.Dl;
-    auto compute = [&](int cur) {
+    // B-fragment rows: one LDS pointer per (stage, chunk channel of this lane half, filter row), worked out
+    // once, so that inside the chunk loop a fragment read is pointer + immediate (kw) and costs no vector ALU
+    // instruction (with run-time pitches every (c, kh) pair was an add per chunk, not overlapped with the MFMAs)
+    const float* brow[NBUF][CC / 2][R];
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b)
+#pragma unroll
+        for (int c = 0; c < CC / 2; ++c)
+#pragma unroll
+            for (int kh = 0; kh < R; ++kh) brow[b][c][kh] = inS(b) + b_base + c * g.ch_ld + kh * dl * g.ldw;
+    auto compute = [&](auto cur_tag) {
+        constexpr int cur = decltype(cur_tag)::value;
         // waves inside their MFMA block win the issue arbitration over waves that are staging
         __builtin_amdgcn_s_setprio(1);
-        const float* bI = inS(cur) + b_base;
         const float* aW = wS(cur) + a_base;
 #pragma unroll
         for (int j = 0; j < HALF / VW; ++j) {
@@ -324,13 +350,15 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
             for (int e = 0; e < VW; ++e) {
                 const int s = VW * j + e;  // MFMA step inside the chunk
                 const int c = s / TAPS, tap = s % TAPS;
-                const float b = bI[c * g.ch_ld + (tap / R) * dl * g.ldw + (tap % R) * dl];
+                const float b = brow[cur][c][tap / R][(tap % R) * dl];
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) acc[kb] = mfma_32x32x2(a[kb][e], b, acc[kb]);
             }
         }
         __builtin_amdgcn_s_setprio(0);
     };
+    constexpr std::integral_constant<int, 0> buf0{};
+    constexpr std::integral_constant<int, NBUF - 1> buf1{};   // (the general variant has one stage)
 
     if (tid < KT) {  // v = (acc + bias) * scale + shift = acc * mul + add; visible after the first barrier
         const bool ok = k0 + tid < g.K;
@@ -345,23 +373,34 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     if (FAST) {
         // software pipeline over channel chunks; the last chunk is peeled so the
         // loop body has no conditional loads
-        fetch(0);
-        stash(0);
-        __syncthreads();
-        for (int t = 0; t + 1 < nchunks; ++t) {
-            fetch((t + 1) * CC);
+        // (two chunks per trip, so that the stage index is a compile-time constant everywhere)
+        auto step = [&](int next_c0, auto cur_tag, auto next_tag) {
+            fetch(next_c0);
             __builtin_amdgcn_sched_barrier(0);  // keep the global loads ahead of the MFMAs they overlap with
-            compute(t & 1);
+            compute(cur_tag);
             __builtin_amdgcn_sched_barrier(0);
-            stash((t + 1) & 1);
+            stash(next_tag);
             __syncthreads();
+        };
+        fetch(0);
+        stash(buf0);
+        __syncthreads();
+        int t = 0;   // chunk t is in stage 0 here
+        for (; t + 2 < nchunks; t += 2) {
+            step((t + 1) * CC, buf0, buf1);
+            step((t + 2) * CC, buf1, buf0);
         }
-        compute((nchunks - 1) & 1);
+        if (t + 1 < nchunks) {
+            step((t + 1) * CC, buf0, buf1);
+            compute(buf1);
+        } else {
+            compute(buf0);
+        }
     } else {
         for (int t = 0; t < nchunks; ++t) {
             copy_chunk(0, t * CC);
             __syncthreads();
-            compute(0);
+            compute(buf0);
             __syncthreads();
         }
     }
@@ -450,7 +489,7 @@ ConvGeom geom(const ConvParams& p, int iv = 4) {
 template <int R, int CC, int KT>
 size_t lds_bytes(const ConvGeom& g, bool fast) {
     const int nbuf = fast ? 2 : 1;
-    return (size_t)(nbuf * CC * g.ch_ld + nbuf * Cfg<R, CC, KT>::W_STAGE + 2 * KT) * 4;
+    return (size_t)(nbuf * CC * g.ch_ld + nbuf * Cfg<R, CC, KT>::W_STAGE + 2 * KT + 4) * 4;
 }
 
 // Output channels per work-group.  With 4 input channels per chunk, 64 keeps a work-group near
