@@ -25,6 +25,7 @@
 // a mean over the last dimension, summed over the tile's columns in a fixed
 // order and written as one partial per (column tile, row) for the finishing
 // kernel, so results do not depend on scheduling.
+#include <type_traits>
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -37,13 +38,15 @@ constexpr int kThreads = 256;
 constexpr int kXcds = 8;
 
 // T = tile edge, 128 or 64: a wave owns (T/2) x (T/2) as WB x WB accumulators, WB = T/64.
-// 128: four work-groups per CU (one wave of each per SIMD), 128 registers per lane, 64 of them
-// accumulators.  64: for outputs with too few 128-tiles to fill the chip; 16 accumulator registers.
+// 128: three work-groups per CU (one wave of each per SIMD), up to 168 registers per lane, 64 of them
+// accumulators (a budget of 128 for four groups spills once the chunk loop keeps its LDS pointers and
+// buffer offsets in registers: 4096 x 1024 x 4096 106 TFLOP/s against 130 with three groups).
+// 64: for outputs with too few 128-tiles to fill the chip; 16 accumulator registers.
 // BT: W is stored transposed ([N,K] row-major, the layout of a linear layer's weight).  Its tile is
 // then staged and read exactly like the A tile (rows = output columns, 128-bit reads along k):
 // the MFMA's A and B operands have mirror-image lane layouts.
 template <int T, bool VEC, bool BT>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) void gemm_tile(GemmParams p, int tiles_n, int items) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void gemm_tile(GemmParams p, int tiles_n, int items) {
     constexpr int TM = T, TN = T, WB = T / 64, LDB = T + 8;
     __shared__ __attribute__((aligned(16))) float As[2][TM * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[2][BT ? TN * LDA : BK * LDB];
@@ -85,48 +88,73 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
     const float* __restrict__ W = p.W;
 
     float4v ra[WB], rb[WB];
-    auto fetch = [&](int k0) {
+    // VEC: raw buffer loads.  A lane's byte offset inside its tile's rows is worked out once; a lane outside
+    // the matrix (row >= M, column >= N) gets an offset beyond the descriptor's size, for which the hardware
+    // returns 0 without touching memory, so the chunk loop has no address arithmetic, select or zero fill on
+    // the vector ALU (which does not overlap the MFMAs) and the chunk offset rides in the scalar operand.
+    // Only the last chunk of a K slice can be partial; that case is a scalar branch.
+    constexpr unsigned kOob = 0x80000000u;
+    constexpr int kWord3 = 0x00020000;   // descriptor word 3 for plain 32-bit data
+    unsigned a_voff[WB], b_voff[WB];
+    __amdgpu_buffer_rsrc_t a_rs, b_rs;
+    if (VEC) {
+        a_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X) + (int64_t)m0 * K, 0, 0x7fffffff, kWord3);
+        if (BT) b_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(W) + (int64_t)n0 * K, 0, 0x7fffffff, kWord3);
 #pragma unroll
         for (int i = 0; i < WB; ++i) {
-            const int m = m0 + ar + 64 * i, k = k0 + ak;
-            const float* src = X + (int64_t)m * K + k;
-            if (VEC) {
-                ra[i] = load4((m < M && k < k_hi) ? src : X);
-            } else {
+            a_voff[i] = m0 + ar + 64 * i < M ? (unsigned)(((ar + 64 * i) * K + ak) * 4) : kOob;
+            if (BT) b_voff[i] = n0 + ar + 64 * i < N ? (unsigned)(((ar + 64 * i) * K + ak) * 4) : kOob;
+            else b_voff[i] = n0 + bn < N ? (unsigned)(((bk + BSTEP * i) * N + bn) * 4) : kOob;
+        }
+    }
+    auto fetch = [&](int k0) {
+        if constexpr (VEC) {
+            const bool tail = k0 + BK > k_hi;   // uniform
+            if (!BT) b_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(W) + (int64_t)k0 * N + n0, 0, 0x7fffffff, kWord3);
+#pragma unroll
+            for (int i = 0; i < WB; ++i) {
+                unsigned va = a_voff[i], vb = b_voff[i];
+                if (tail) {
+                    if (k0 + ak >= k_hi) va = kOob;
+                    if (BT ? k0 + ak >= k_hi : k0 + bk + BSTEP * i >= k_hi) vb = kOob;
+                }
+                ra[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(a_rs, (int)va, k0 * 4, 0));
+                rb[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(b_rs, (int)vb, BT ? k0 * 4 : 0, 0));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < WB; ++i) {
+                const int m = m0 + ar + 64 * i, k = k0 + ak;
+                const float* src = X + (int64_t)m * K + k;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) ra[i][e] = *((m < M && k + e < k_hi) ? src + e : X);
-            }
-            if (BT) {
-                const int n = n0 + ar + 64 * i;
-                const float* wsrc = W + (int64_t)n * K + k;
-                if (VEC) {
-                    rb[i] = load4((n < N && k < k_hi) ? wsrc : W);
-                } else {
+                if (BT) {
+                    const int n = n0 + ar + 64 * i;
+                    const float* wsrc = W + (int64_t)n * K + k;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) rb[i][e] = *((n < N && k + e < k_hi) ? wsrc + e : W);
-                }
-            } else {
-                const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
-                const float* wsrc = W + (int64_t)kk * N + n;
-                if (VEC) {
-                    rb[i] = load4((kk < k_hi && n < N) ? wsrc : W);
                 } else {
+                    const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
+                    const float* wsrc = W + (int64_t)kk * N + n;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) rb[i][e] = *((kk < k_hi && n + e < N) ? wsrc + e : W);
                 }
             }
         }
     };
-    // zero what lies outside the operands, then write the chunk to LDS buffer `buf`
-    auto stash = [&](int k0, int buf) {
+    // write the chunk to LDS stage `buf` (scalar path: zero what lies outside the operands first)
+    auto stash = [&](int k0, auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;
 #pragma unroll
         for (int i = 0; i < WB; ++i) {
-            const int m = m0 + ar + 64 * i, k = k0 + ak;
-            const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
+            if constexpr (!VEC) {
+                const int m = m0 + ar + 64 * i, k = k0 + ak;
+                const int kk = k0 + bk + BSTEP * i, n = n0 + bn;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (!(m < M && k + e < k_hi)) ra[i][e] = 0.f;
-                if (BT ? !(n0 + ar + 64 * i < N && k + e < k_hi) : !(kk < k_hi && n + e < N)) rb[i][e] = 0.f;
+                for (int e = 0; e < 4; ++e) {
+                    if (!(m < M && k + e < k_hi)) ra[i][e] = 0.f;
+                    if (BT ? !(n0 + ar + 64 * i < N && k + e < k_hi) : !(kk < k_hi && n + e < N)) rb[i][e] = 0.f;
+                }
             }
             *reinterpret_cast<float4v*>(&As[buf][(ar + 64 * i) * LDA + ak]) = ra[i];
             if (BT) *reinterpret_cast<float4v*>(&Bs[buf][(ar + 64 * i) * LDA + ak]) = rb[i];
@@ -142,7 +170,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    auto compute = [&](int buf) {
+    auto compute = [&](auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;   // compile-time: fragment reads are lane base + immediate
         // waves inside their MFMA block win the issue arbitration over waves that are staging
         __builtin_amdgcn_s_setprio(1);
         const float* a_base = &As[buf][(wm * (TM / 2) + l32) * LDA + 4 * h];
@@ -172,17 +201,29 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))
     };
 
     const int nk = (k_hi - k_lo + BK - 1) / BK;
-    fetch(k_lo);
-    stash(k_lo, 0);
-    __syncthreads();
-    for (int t = 0; t + 1 < nk; ++t) {
-        fetch(k_lo + (t + 1) * BK);
+    constexpr std::integral_constant<int, 0> buf0{};
+    constexpr std::integral_constant<int, 1> buf1{};
+    auto step = [&](int k_next, auto cur_tag, auto next_tag) {
+        fetch(k_next);
         __builtin_amdgcn_sched_barrier(0);  // the next chunk's loads are in flight before the MFMAs start
-        compute(t & 1);
-        stash(k_lo + (t + 1) * BK, (t + 1) & 1);
+        compute(cur_tag);
+        stash(k_next, next_tag);
         __syncthreads();
+    };
+    fetch(k_lo);
+    stash(k_lo, buf0);
+    __syncthreads();
+    int t = 0;   // chunk t is in stage 0 here; two chunks per trip keep the stage index a compile-time constant
+    for (; t + 2 < nk; t += 2) {
+        step(k_lo + (t + 1) * BK, buf0, buf1);
+        step(k_lo + (t + 2) * BK, buf1, buf0);
     }
-    compute((nk - 1) & 1);
+    if (t + 1 < nk) {
+        step(k_lo + (t + 1) * BK, buf0, buf1);
+        compute(buf1);
+    } else {
+        compute(buf0);
+    }
 
     if (p.ksplit > 1) {  // uniform over the grid: raw partial products of this K slice
         float* __restrict__ part = p.ws + (int64_t)ks * M * N;
@@ -372,11 +413,13 @@ template <int T>
 hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
     const int tiles_m = (p.M + T - 1) / T, tiles_n = (p.N + T - 1) / T;
     const int items = tiles_m * tiles_n * p.ksplit;
+    // (the vector instances address a tile's rows with 31-bit byte offsets)
+    const bool fits = p.K <= (1 << 21) && p.N <= (1 << 24);
     if (p.wt) {   // both operands are read along k
-        if (p.K % 4 == 0) hipLaunchKernelGGL((gemm_tile<T, true, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+        if (p.K % 4 == 0 && fits) hipLaunchKernelGGL((gemm_tile<T, true, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
         else hipLaunchKernelGGL((gemm_tile<T, false, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
     } else {
-        const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
+        const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0) && fits;
         if (vec) hipLaunchKernelGGL((gemm_tile<T, true, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
         else hipLaunchKernelGGL((gemm_tile<T, false, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
     }
