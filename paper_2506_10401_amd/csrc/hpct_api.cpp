@@ -542,6 +542,7 @@ hpct_status plan_attn(const hpct_op_desc& d, hpct_plan& p) {
         if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous [B,L,D] layouts are supported", i);
     if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous layouts are supported");
     if (B * L * D > kI32Max || B * Lk * D > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "attention: operand larger than 2^31-1 elements");
+    if (Lk * D * 4 > kI32Max) return fail(HPCT_ERR_UNSUPPORTED, "attention: one batch of K / V larger than 2^31-1 bytes");
     const char* why = "";
     if (!attn_supported((int32_t)D, &why)) return fail(HPCT_ERR_UNSUPPORTED, "attention: %s", why);
     if (!(scale == scale) || scale - scale != 0.f) return fail(HPCT_ERR_BAD_DESC, "attention: scale must be finite");

@@ -31,6 +31,7 @@
 // queries x 4 key groups (128-key staged blocks) handles query block i and then
 // block n-1-i of the same batch, which gives every work-group the same number of
 // key blocks to walk.
+#include <type_traits>
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -65,7 +66,10 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restric
     float* const Ks = lds;                      // [2][KB*KLD]
     float* const Vs = lds + 2 * KB * KLD;       // [2][KB*VLD]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index as a scalar: everything derived from it (key sub-block, masks' conditions) is then uniform for
+    // the compiler too, so the rare tail / diagonal masking is a scalar branch instead of 32 selects per block
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     const int qwave = wave % NQW, kgrp = wave / NQW;
     // work item = (batch, query block); consecutive items share a batch's K/V and
@@ -84,6 +88,20 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restric
     const float* Kb = K + (int64_t)b * Lk * D;
     const float* Vb = V + (int64_t)b * Lk * D;
     const int npass = (PAIR && nqb - 1 - qb0 != qb0) ? 2 : 1;
+    // staging constants of this thread: float4 i of a block is key v / (D/4), dims 4 (v % (D/4)) .., v = tid + i NT
+    const __amdgpu_buffer_rsrc_t k_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Kb), 0, Lk * D * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t v_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Vb), 0, Lk * D * 4, 0x00020000);
+    unsigned kv_off[LD4];
+    float* ks_ptr[LD4];
+    float* vs_ptr[LD4];
+#pragma unroll
+    for (int i = 0; i < LD4; ++i) {
+        const int v = tid + i * NT;
+        const int kr = v / (D / 4), d = (v % (D / 4)) * 4;
+        kv_off[i] = (unsigned)((kr * D + d) * 4);
+        ks_ptr[i] = Ks + kr * KLD + d;
+        vs_ptr[i] = Vs + kr * VLD + d;
+    }
   for (int pass = 0; pass < npass; ++pass) {
     const int qb = pass == 0 ? qb0 : nqb - 1 - qb0;
     const int q0 = qb * QT + qwave * QW;
@@ -101,24 +119,27 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restric
         }
     }
 
+    // K/V staging through raw buffer loads: a thread's byte offsets inside a block are constants, the block
+    // offset rides in the scalar operand, and only the last block can reach past Lk - then (a scalar branch)
+    // lanes past the end get an offset beyond the descriptor's size, for which the hardware returns 0.  No
+    // address arithmetic, select or zero fill per block on the vector ALU, which does not overlap the MFMAs.
     float4v kreg[LD4], vreg[LD4];
     auto fetch = [&](int key0) {
+        const bool tail = key0 + KB > Lk;   // uniform
 #pragma unroll
         for (int i = 0; i < LD4; ++i) {
-            const int v = tid + i * NT;
-            const int key = key0 + v / (D / 4), d = (v % (D / 4)) * 4;
-            const bool ok = key < Lk;
-            kreg[i] = ok ? load4(Kb + (int64_t)key * D + d) : float4v{0.f, 0.f, 0.f, 0.f};
-            vreg[i] = ok ? load4(Vb + (int64_t)key * D + d) : float4v{0.f, 0.f, 0.f, 0.f};
+            unsigned off = kv_off[i];
+            if (tail && key0 + (tid + i * NT) / (D / 4) >= Lk) off = 0x80000000u;
+            kreg[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(k_rs, (int)off, key0 * D * 4, 0));
+            vreg[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(v_rs, (int)off, key0 * D * 4, 0));
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;
 #pragma unroll
         for (int i = 0; i < LD4; ++i) {
-            const int v = tid + i * NT;
-            const int kr = v / (D / 4), d = (v % (D / 4)) * 4;
-            *reinterpret_cast<float4v*>(Ks + buf * KB * KLD + kr * KLD + d) = kreg[i];
-            *reinterpret_cast<float4v*>(Vs + buf * KB * VLD + kr * VLD + d) = vreg[i];
+            *reinterpret_cast<float4v*>(ks_ptr[i] + buf * KB * KLD) = kreg[i];
+            *reinterpret_cast<float4v*>(vs_ptr[i] + buf * KB * VLD) = vreg[i];
         }
     };
 
@@ -136,15 +157,11 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restric
         const int nb = q_last / KB + 1;
         nblocks = nb < nblocks ? nb : nblocks;
     }
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int t = 0; t < nblocks; ++t) {
-        const int cur = t & 1;
+    auto block = [&](int t, auto cur_tag, auto next_tag) {   // stage index compile-time: fragment reads are base + immediate
+        constexpr int cur = decltype(cur_tag)::value;
         if (t + 1 < nblocks) fetch((t + 1) * KB);
         const float* Kc = Ks + cur * KB * KLD;
         const float* Vc = Vs + cur * KB * VLD;
-
         // ---- scores of this wave's sub-blocks: S^T = K Q^T -------------------
         float16v s[SUB];
         bool skip[SUB];   // wave-uniform: the sub-block lies above the diagonal of all 32 queries
@@ -225,8 +242,17 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restric
                 for (int db = 0; db < DB; ++db) o[db] = mfma_32x32x2(vr[32 * db], s[u][r], o[db]);
             }
         }
-        if (t + 1 < nblocks) stash(cur ^ 1);
+        if (t + 1 < nblocks) stash(next_tag);
         __syncthreads();
+    };
+    constexpr std::integral_constant<int, 0> buf0{};
+    constexpr std::integral_constant<int, 1> buf1{};
+    fetch(0);
+    stash(buf0);
+    __syncthreads();
+    for (int t = 0; t < nblocks; t += 2) {
+        block(t, buf0, buf1);
+        if (t + 1 < nblocks) block(t + 1, buf1, buf0);
     }
 
     // ---- combine the two lane halves' sums, merge wave groups, normalise, store
