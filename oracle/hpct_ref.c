@@ -192,6 +192,59 @@ void ref_conv2d_nchw_bias(const float *in, const float *wt, const float *bias,
     }
 }
 
+/* ---- Grouped conv (depthwise when groups = C = K): the conv above with the
+ * input channels split into `groups` equal runs and the output channels
+ * likewise; output channel k (group g = k / (K/groups)) sums only over the
+ * C/groups input channels of its group, and its filter is wt[k][0 .. C/groups)
+ * [R][S] (weights are [K][C/groups][R][S] contiguous).  groups = 1 is the conv
+ * above; groups = C = K is the depthwise convolution of the MobileNetV2 blocks
+ * (a model the paper's Section 5.2 names).  Same tap index, zero padding,
+ * stride and dilation rules.  Dn as above. */
+void ref_conv2d_nchw_grouped(const float *in, const float *wt, const float *bias,
+                             int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t K,
+                             int64_t R, int64_t S, int64_t stride, int64_t P, int64_t dil,
+                             int64_t groups, double *out, double *Dn)
+{
+    const int64_t Ho = (H + 2 * P - (R - 1) * dil - 1) / stride + 1, Wo = (W + 2 * P - (S - 1) * dil - 1) / stride + 1;
+    const int64_t Cg = C / groups, Kg = K / groups;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t n = 0; n < Nb; ++n) {
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t c_first = (k / Kg) * Cg;
+            for (int64_t h = 0; h < Ho; ++h) {
+                for (int64_t w = 0; w < Wo; ++w) {
+                    double b = bias ? (double)bias[k] : 0.0;
+                    double sum = b, mag = fabs(b);
+                    for (int64_t c = 0; c < Cg; ++c) {
+                        for (int64_t kh = 0; kh < R; ++kh) {
+                            for (int64_t kw = 0; kw < S; ++kw) {
+                                int64_t ih = h * stride - P + kh * dil;
+                                int64_t iw = w * stride - P + kw * dil;
+                                if (ih >= 0 && ih < H && iw >= 0 && iw < W) {
+                                    double a = (double)in[((n * C + c_first + c) * H + ih) * W + iw];
+                                    double g = (double)wt[((k * Cg + c) * R + kh) * S + kw];
+                                    sum += a * g;
+                                    mag += fabs(a) * fabs(g);
+                                }
+                            }
+                        }
+                    }
+                    int64_t o = ((n * K + k) * Ho + h) * Wo + w;
+                    out[o] = sum;
+                    if (Dn) Dn[o] = mag;
+                }
+            }
+        }
+    }
+}
+
+/* ---- Elementwise: relu6 = min(max(z, 0), 6), the activation of those blocks, in place */
+void ref_relu6(double *Z, int64_t count)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; ++i) Z[i] = Z[i] < 0.0 ? 0.0 : (Z[i] > 6.0 ? 6.0 : Z[i]);
+}
+
 /* ---- Batched matmul - softmax - matmul ------------------------------------
  * For each batch b and query i:  s_j = scale * sum_d Q[b][i][d] K[b][j][d];
  * p = softmax_j(s) (two passes over one materialised row, not an online

@@ -34,6 +34,8 @@ def lib():
             "ref_layernorm_rows": [p, p, p, i64, i64, dbl, p],
             "ref_gelu_tanh": [p, i64],
             "ref_conv2d_nchw_bias": [p, p, p] + [i64] * 10 + [p, p],
+            "ref_conv2d_nchw_grouped": [p, p, p] + [i64] * 11 + [p, p],
+            "ref_relu6": [p, i64],
             "ref_attention": [p, p, p, i64, i64, i64, i64, dbl, p, p],
             "ref_attention_causal": [p, p, p, i64, i64, i64, i64, dbl, p, p],
             "ref_layout_copy": [p, C.c_int32, p, p, p],
@@ -156,6 +158,27 @@ def conv2d_nchw_bias(inp, wt, bias=None, stride=1, pad=1, want_norm=False, dil=1
     lib().ref_conv2d_nchw_bias(_ptr(inp), _ptr(wt), _ptr(b), Nb, Cc, H, W, K, R, S, stride, pad, dil,
                                _ptr(out), _ptr(Dn))
     return (out, Dn) if want_norm else out
+
+
+def conv2d_nchw_grouped(inp, wt, bias=None, stride=1, pad=1, groups=1, want_norm=False, dil=1):
+    """Grouped conv: wt is [K, C/groups, R, S]; groups = C = K is the depthwise convolution."""
+    inp, wt = _f32(inp), _f32(wt)
+    Nb, Cc, H, W = inp.shape
+    K, Cg, R, S = wt.shape
+    assert Cc % groups == 0 and K % groups == 0 and Cg == Cc // groups
+    b = None if bias is None else _f32(bias)
+    Ho, Wo = conv_out_hw(H, W, R, S, stride, pad, dil)
+    out = np.empty((Nb, K, Ho, Wo), dtype=np.float64)
+    Dn = np.empty_like(out) if want_norm else None
+    lib().ref_conv2d_nchw_grouped(_ptr(inp), _ptr(wt), _ptr(b), Nb, Cc, H, W, K, R, S, stride, pad, dil, groups,
+                                  _ptr(out), _ptr(Dn))
+    return (out, Dn) if want_norm else out
+
+
+def relu6(Z):
+    Z = np.array(Z, dtype=np.float64, order="C")
+    lib().ref_relu6(_ptr(Z), Z.size)
+    return Z
 
 
 def attention(Q, K, V, scale, want_norm=False, causal=False):

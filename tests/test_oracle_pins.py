@@ -856,3 +856,53 @@ def test_scale_const_is_multiplication_by_the_fp32_constant():
     assert np.array_equal(ref.scale_const(ref.scale_const(z, 0.5), 8.0), 4.0 * z)
     assert np.array_equal(ref.scale_const(np.ones(3), 0.1), np.full(3, float(np.float32(0.1))))
     assert np.array_equal(ref.scale_const(np.array([2.0, -3.0]), 1.5), [3.0, -4.5])
+
+
+# ------------------------------------------------ grouped / depthwise conv, relu6
+def test_grouped_conv_is_the_dense_conv_with_block_diagonal_weights():
+    x = f32(rng.normal(size=(2, 6, 7, 9)))
+    for groups, K in ((1, 4), (2, 4), (3, 6), (6, 6), (6, 12)):
+        Cg, Kg = 6 // groups, K // groups
+        w = f32(rng.normal(size=(K, Cg, 3, 3))); b = f32(rng.normal(size=K))
+        dense = np.zeros((K, 6, 3, 3), np.float32)          # block diagonal: zero outside each group's channels
+        for k in range(K):
+            g = k // Kg
+            dense[k, g * Cg:(g + 1) * Cg] = w[k]
+        for stride, pad, dil in ((1, 1, 1), (2, 1, 1), (1, 2, 2), (1, 0, 1)):
+            got, Dg = ref.conv2d_nchw_grouped(x, w, b, stride, pad, groups, want_norm=True, dil=dil)
+            want, Dw = ref.conv2d_nchw_bias(x, dense, b, stride, pad, want_norm=True, dil=dil)
+            assert got.shape == want.shape
+            assert np.max(np.abs(got - want)) < 1e-13 and np.max(np.abs(Dg - Dw)) < 1e-13
+
+
+def test_depthwise_conv_closed_forms_and_brute_force():
+    x = f32(rng.normal(size=(2, 5, 6, 8)))
+    # centre-tap delta filters scaled per channel: out[n,c] = s_c * in[n,c]
+    s = f32(rng.normal(size=5))
+    w = np.zeros((5, 1, 3, 3), np.float32); w[:, 0, 1, 1] = s
+    got = ref.conv2d_nchw_grouped(x, w, None, 1, 1, groups=5)
+    assert np.array_equal(got, x.astype(np.float64) * s.astype(np.float64)[None, :, None, None])
+    # off-centre tap (kh=0, kw=1): out[h][w] = in[h-1][w], zero in the first row; channels never mix
+    w = np.zeros((5, 1, 3, 3), np.float32); w[:, 0, 0, 1] = 1.0
+    got = ref.conv2d_nchw_grouped(x, w, None, 1, 1, groups=5)
+    assert np.array_equal(got[:, :, 1:, :], x[:, :, :-1, :].astype(np.float64)) and np.all(got[:, :, 0, :] == 0)
+    # all-ones: counts the taps inside the image (9 interior, 6 edges, 4 corners), independent of C
+    ones = np.ones((1, 3, 5, 5), np.float32)
+    got = ref.conv2d_nchw_grouped(ones, np.ones((3, 1, 3, 3), np.float32), None, 1, 1, groups=3)
+    assert got[0, 1, 2, 2] == 9 and got[0, 2, 0, 2] == 6 and got[0, 0, 0, 0] == 4
+    # brute force, stride 2, with bias
+    w = f32(rng.normal(size=(5, 1, 3, 3))); b = f32(rng.normal(size=5))
+    got = ref.conv2d_nchw_grouped(x, w, b, 2, 1, groups=5)
+    assert got.shape == (2, 5, 3, 4)
+    for n, c, h, ww in itertools.product(range(2), range(5), range(3), range(4)):
+        acc = float(b[c])
+        for kh in range(3):
+            for kw in range(3):
+                ih, iw = 2 * h - 1 + kh, 2 * ww - 1 + kw
+                if 0 <= ih < 6 and 0 <= iw < 8:
+                    acc += float(x[n, c, ih, iw]) * float(w[c, 0, kh, kw])
+        assert abs(got[n, c, h, ww] - acc) < 1e-13
+
+
+def test_relu6_clamps_both_ends():
+    assert np.array_equal(ref.relu6(np.array([-3.0, -0.0, 0.5, 6.0, 6.5, 1e9])), [0.0, 0.0, 0.5, 6.0, 6.0, 6.0])
