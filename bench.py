@@ -345,6 +345,26 @@ def main() -> int:
                                  peak=MFMA_F32_PEAK_TFLOPS, frac=round(flop5 / us / 1e6 / MFMA_F32_PEAK_TFLOPS, 4),
                                  note="flop = 4*D per visible (query, key) pair; masked pairs inside diagonal blocks are computed but not counted"))
 
+        # depthwise 3x3 conv + bias + relu6 at a MobileNetV2 shape (memory-bound: bytes = input + output)
+        dsets = []
+        for v in range(3):
+            xd = torch.randn(32, 144, 56, 56, device="cuda")
+            od = torch.empty(32, 144, 56, 56, device="cuda")
+            pland, insd = hpct.depthwise_conv_plan(xd, torch.randn(144, 1, 3, 3, device="cuda"), torch.randn(144, device="cuda"),
+                                                   None, None, od, 1, 1, "relu6")
+            dsets.append(pland.bind(insd, [od]))
+        kd = [0]
+
+        def calld():
+            dsets[kd[0] % 3]()
+            kd[0] += 1
+        us = timed(calld, args.steps)
+        nbd = 2 * 32 * 144 * 56 * 56 * 4
+        next_ops.append(dict(op="depthwise_conv3x3_bias_relu6_32x144x56x56", kernel=pland.kernel_name, launches=args.steps,
+                             avg_us=round(us, 3), achieved=round(nbd / us / 1e3, 1), unit="GB/s", peak=HBM_PEAK_GBS,
+                             frac=round(nbd / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=3))
+        del dsets
+
     per_op, fracs = [], []
     for i in which:
         avg_us = 1e3 * ev[i][0].elapsed_time(ev[i][1]) / args.steps

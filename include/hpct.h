@@ -53,6 +53,8 @@
  *         ARGMIN_AXIS over dim `axis`, no epilogue    >= 0, up to 6 dims)           dim `axis`, contiguous
  *                                                                                   (1-D input: shape [1]);
  *                                                                                   int32 for the arg ops
+ *   CONV2D_NCHW, groups = C: depthwise                in[N,C,H,W], wt[C,1,R,S],     [N,C,Ho,Wo]
+ *         [+BIAS_COL] [+SCALE_SHIFT_CH] [+RELU|RELU6] bias[C], scale[C], shift[C]
  *   CONV2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH] [+RELU] in[N,C,H,W], wt[K,C,R,S],     [N,K,Ho,Wo], or
  *         then MAXPOOL2_HW or no reduction            bias[K], scale[K], shift[K]   [N,K,Ho/2,Wo/2]
  *         (square 1/3/5/7 filter, stride and                                         with MAXPOOL2_HW
@@ -131,7 +133,8 @@ typedef enum {
     HPCT_EPI_COS = 14,            /* cos(x) */
     HPCT_EPI_EXP = 15,            /* exp(x) */
     HPCT_EPI_TANH = 16,           /* tanh(x) */
-    HPCT_EPI_SIGMOID = 17         /* 1 / (1 + exp(-x)) */
+    HPCT_EPI_SIGMOID = 17,        /* 1 / (1 + exp(-x)) */
+    HPCT_EPI_RELU6 = 18           /* min(max(x, 0), 6): in place of RELU in a conv chain, or a unary step */
 } hpct_epilogue;
 
 /* Row reductions (Table 1, Reduction). */
@@ -169,6 +172,8 @@ typedef struct {
     uint64_t dropout_seed;        /* DROPOUT_HASH */
     int32_t axis;                 /* *_AXIS reductions: the dimension of in[0] that is reduced, 0 <= axis < ndim */
     int32_t dilation_hw[2];       /* conv only: tap kh reads input row h*stride - pad + kh*dilation; 0 means 1 */
+    int32_t groups;               /* conv only: 0 or 1 = dense; C (with K = C and wt[K,1,R,S]) = depthwise, every channel
+                                     filtered by its own R x R filter.  Other group counts are not supported. */
 } hpct_op_desc;
 
 typedef struct hpct_plan hpct_plan;   /* opaque; host memory */

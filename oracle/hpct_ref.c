@@ -485,6 +485,7 @@ void ref_attention_causal(const float *Q, const float *K, const float *V,
  * un[1], ... are applied to v in that order:
  *   0 max(v, 0)      1 tanh-form GELU      2 v * scale      3 sqrt(v)     4 sin(v)
  *   5 cos(v)         6 exp(v)              7 tanh(v)        8 1 / (1 + exp(-v))
+ *   9 min(max(v, 0), 6)
  * Everything in double from the widened fp32 operands; libm supplies the
  * transcendental functions. */
 void ref_eltwise_map(const float *a, const float *b, int32_t nd, const int64_t *shape,
@@ -517,7 +518,8 @@ void ref_eltwise_map(const float *a, const float *b, int32_t nd, const int64_t *
                 case 5: v = cos(v); break;
                 case 6: v = exp(v); break;
                 case 7: v = tanh(v); break;
-                default: v = 1.0 / (1.0 + exp(-v)); break;
+                case 8: v = 1.0 / (1.0 + exp(-v)); break;
+                default: v = v < 0.0 ? 0.0 : (v > 6.0 ? 6.0 : v); break;   /* 9: relu6 */
             }
         }
         out[lin] = v;

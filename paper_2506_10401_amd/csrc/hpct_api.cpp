@@ -26,7 +26,7 @@ hpct_status fail(hpct_status st, const char* fmt, ...) {
 
 void clear_err() { g_err[0] = 0; }
 
-enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool };
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool, DwConv };
 
 constexpr int64_t kI32Max = 2147483647LL;
 
@@ -333,6 +333,7 @@ int unary_code(hpct_epilogue e) {
         case HPCT_EPI_EXP: return kUnExp;
         case HPCT_EPI_TANH: return kUnTanh;
         case HPCT_EPI_SIGMOID: return kUnSigmoid;
+        case HPCT_EPI_RELU6: return kUnRelu6;
         default: return -1;
     }
 }
@@ -369,7 +370,7 @@ hpct_status plan_eltwise(const hpct_op_desc& d, hpct_plan& p) {
         un[i - first] = unary_code(d.epi[i]);
         if (un[i - first] < 0)
             return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: epilogues must be [ADD|MUL|SUB|DIV_TENSOR] followed by "
-                        "RELU, GELU_TANH, SCALE_CONST, SQRT, SIN, COS, EXP, TANH or SIGMOID steps");
+                        "RELU, RELU6, GELU_TANH, SCALE_CONST, SQRT, SIN, COS, EXP, TANH or SIGMOID steps");
     }
     if (d.reduce != HPCT_RED_NONE) return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: no reduction is supported after it");
     const int need = bin >= 0 ? 2 : 1;
@@ -463,10 +464,10 @@ hpct_status plan_reduce(const hpct_op_desc& d, hpct_plan& p) {
 }
 
 hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
-    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU};
-    bool has[3];
-    if (!parse_epi(d, allowed, 3, has))
-        return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: epilogues must be [BIAS_COL] [SCALE_SHIFT_CH] [RELU] in that order");
+    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_RELU6};
+    bool has[4];
+    if (!parse_epi(d, allowed, 4, has) || (has[2] && has[3]))
+        return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: epilogues must be [BIAS_COL] [SCALE_SHIFT_CH] [RELU | RELU6] in that order");
     if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_MAXPOOL2_HW)
         return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: reduction must be NONE or MAXPOOL2_HW");
     if (d.reduce != HPCT_RED_NONE && d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: the pooling runs after the epilogues");
@@ -477,7 +478,14 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
     if (I.ndim != 4 || Wt.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "conv operands must be 4-D: in[N,C,H,W], wt[K,C,R,S]");
     const int64_t Nb = I.shape[0], C = I.shape[1], H = I.shape[2], W = I.shape[3];
     const int64_t K = Wt.shape[0], R = Wt.shape[2], S = Wt.shape[3];
-    if (Wt.shape[1] != C) return fail(HPCT_ERR_SHAPE_MISMATCH, "wt.shape[1] = %lld does not match the input channels %lld", (long long)Wt.shape[1], (long long)C);
+    const int64_t groups = d.groups <= 1 ? 1 : d.groups;
+    if (d.groups < 0) return fail(HPCT_ERR_BAD_DESC, "conv: groups = %d", d.groups);
+    const bool depthwise = groups > 1;
+    if (depthwise && !(groups == C && K == C))
+        return fail(HPCT_ERR_UNSUPPORTED, "conv: only groups = 1 (dense) and groups = C = K (depthwise) are supported");
+    if (Wt.shape[1] != C / groups)
+        return fail(HPCT_ERR_SHAPE_MISMATCH, "wt.shape[1] = %lld does not match the input channels per group %lld", (long long)Wt.shape[1], (long long)(C / groups));
+    if (depthwise && pool) return fail(HPCT_ERR_UNSUPPORTED, "conv: MAXPOOL2_HW after a depthwise conv is not supported");
     if (d.stride_hw[0] < 1 || d.stride_hw[1] < 1 || d.pad_hw[0] < 0 || d.pad_hw[1] < 0)
         return fail(HPCT_ERR_BAD_DESC, "conv: stride must be >= 1 and padding >= 0");
     // dilation 0 (a zero-initialised descriptor) means 1
@@ -506,12 +514,25 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
     if (Nb * C * H * W > kI32Max || Nb * K * Ho * Wo > kI32Max || K * C * R * S > kI32Max)
         return fail(HPCT_ERR_UNSUPPORTED, "conv: operand larger than 2^31-1 elements");
     const char* why = "";
+    if (depthwise) {
+        if (R != S || d.stride_hw[0] != d.stride_hw[1] || d.pad_hw[0] != d.pad_hw[1] || dil_h != dil_w)
+            return fail(HPCT_ERR_UNSUPPORTED, "depthwise conv: filter, stride, padding and dilation must be the same in both directions");
+        ConvParams q{};
+        q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)H; q.W = (int32_t)W; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
+        q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.dil = dil_h; q.relu = has[3] ? 2 : (has[2] ? 1 : 0);
+        if (!dwconv_supported(q, &why)) return fail(HPCT_ERR_UNSUPPORTED, "depthwise conv: %s", why);
+        p.kind = Kind::DwConv;
+        p.u.conv = q;
+        p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = s_bias; p.slot[3] = s_scale; p.slot[4] = s_shift; p.slot[5] = -1;
+        p.shape = dwconv_shape(q);
+        return HPCT_OK;
+    }
     if (!conv_supported((int32_t)C, (int32_t)H, (int32_t)W, (int32_t)K, (int32_t)R, (int32_t)S, d.stride_hw[0], d.stride_hw[1],
                         d.pad_hw[0], d.pad_hw[1], dil_h, dil_w, pool ? 1 : 0, &why))
         return fail(HPCT_ERR_UNSUPPORTED, "conv: %s", why);
     ConvParams q{};
     q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)H; q.W = (int32_t)W; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
-    q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.dil = dil_h; q.relu = has[2] ? 1 : 0; q.pool = pool ? 1 : 0;
+    q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.dil = dil_h; q.relu = has[3] ? 2 : (has[2] ? 1 : 0); q.pool = pool ? 1 : 0;
     // A 1x1 filter with stride 1 and no padding acts on pixels independently: the plane is regrouped into rows of
     // 64 pixels, so that a 64-pixel tile stages exactly the pixels it computes instead of the image rows they lie in.
     if (R == 1 && q.stride == 1 && q.pad == 0 && !pool && (H * W) % 64 == 0) { q.H = (int32_t)(H * W / 64); q.W = 64; }
@@ -571,7 +592,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)
-        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_SIGMOID) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
+        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_RELU6) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
 
     hpct_plan tmp;
     std::memset(&tmp, 0, sizeof tmp);
@@ -698,6 +719,12 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
         case Kind::MaxPool:
             e = maxpool2_launch(in(0), (float*)out_ptrs[0], plan->pool_planes, plan->pool_h, plan->pool_w, stream);
             break;
+        case Kind::DwConv: {
+            ConvParams q = plan->u.conv;
+            q.in = in(0); q.wt = in(1); q.bias = in(2); q.scale = in(3); q.shift = in(4); q.out = (float*)out_ptrs[0];
+            e = dwconv_launch(q, stream);
+            break;
+        }
         case Kind::Eltwise: {
             EltwiseParams q = plan->u.elt;
             q.a = in(0); q.b = in(1); q.out = (float*)out_ptrs[0];

@@ -76,7 +76,7 @@ struct ConvEpi {
     const float* bias;   // [K] or null
     const float* scale;  // [K] or null
     const float* shift;  // [K] or null
-    int relu;
+    int relu;            // 0 none, 1 relu, 2 relu6
 };
 
 // MODE 0 (general): every element is loaded with its own bounds test, chunk by chunk.
@@ -417,6 +417,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
                     if (k < g.K) {
                         float v = acc[kb][r] * mulS[kl] + addS[kl];
                         if (epi.relu) v = fmaxf(v, 0.f);
+                        if (epi.relu == 2) v = fminf(v, 6.f);
                         out[((int64_t)n * g.K + k) * g.HoWo + p] = v;
                     }
                 }
@@ -434,6 +435,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
                 const int kl = kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                 float v = acc[kb][r] * mulS[kl] + addS[kl];
                 if (epi.relu) v = fmaxf(v, 0.f);
+                if (epi.relu == 2) v = fminf(v, 6.f);
                 v = fmaxf(v, dpp_mov<0x128>(v));  // row_ror:8
                 v = fmaxf(v, dpp_mov<0xB1>(v));   // quad_perm [1,0,3,2]
                 const int k = k0 + kl;

@@ -53,9 +53,13 @@ __device__ __forceinline__ void unary_step(float (&v)[E], int code, float scale)
 #pragma unroll
             for (int i = 0; i < E; ++i) v[i] = tanhf(v[i]);
             break;
-        default:  // kUnSigmoid
+        case kUnSigmoid:
 #pragma unroll
             for (int i = 0; i < E; ++i) v[i] = 1.f / (1.f + expf(-v[i]));
+            break;
+        default:  // kUnRelu6
+#pragma unroll
+            for (int i = 0; i < E; ++i) v[i] = fminf(fmaxf(v[i], 0.f), 6.f);
             break;
     }
 }

@@ -62,7 +62,7 @@ hipError_t layout_launch(const LayoutParams& p, hipStream_t stream);
 constexpr int kEltwiseDims = 6;
 constexpr int kEltwiseSteps = 8;
 enum : int32_t { kEltAdd = 0, kEltMul = 1, kEltSub = 2, kEltDiv = 3, kEltNone = 4 };
-enum : int32_t { kUnRelu = 0, kUnGelu, kUnScale, kUnSqrt, kUnSin, kUnCos, kUnExp, kUnTanh, kUnSigmoid };
+enum : int32_t { kUnRelu = 0, kUnGelu, kUnScale, kUnSqrt, kUnSin, kUnCos, kUnExp, kUnTanh, kUnSigmoid, kUnRelu6 };
 struct EltwiseParams {
     const float* a; const float* b; float* out;
     int32_t nd;                      // collapsed dimensions, 1..kEltwiseDims
@@ -139,7 +139,7 @@ hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T,
 //      scale/shift + relu, optionally followed by 2x2 / stride-2 max pooling
 struct ConvParams {
     const float* in; const float* wt; const float* bias; float* out;
-    int32_t Nb, C, H, W, K, R, S, pad; int32_t relu;
+    int32_t Nb, C, H, W, K, R, S, pad; int32_t relu;   // relu: 0 none, 1 max(x, 0), 2 min(max(x, 0), 6)
     int32_t stride;
     const float* scale; const float* shift;   // per output channel, either may be null
     int32_t pool;                             // out is [Nb, K, Ho/2, Wo/2]
@@ -152,6 +152,10 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
                     const char** why);
 LaunchShape conv_shape(const ConvParams& p);
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream);
+// depthwise (groups = C = K, wt[C,1,R,R]): a memory-bound stencil kernel of its own (k_dwconv.hip)
+bool dwconv_supported(const ConvParams& p, const char** why);
+LaunchShape dwconv_shape(const ConvParams& p);
+hipError_t dwconv_launch(const ConvParams& p, hipStream_t stream);
 
 // ---- batched softmax(scale * Q K^T) V
 struct AttnParams {

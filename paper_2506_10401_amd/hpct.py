@@ -25,7 +25,7 @@ HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
     HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH, HPCT_EPI_CAUSAL_MASK, HPCT_EPI_ADD_TENSOR, HPCT_EPI_MUL_TENSOR, \
     HPCT_EPI_SUB_TENSOR, HPCT_EPI_DIV_TENSOR, HPCT_EPI_SQRT, HPCT_EPI_SIN, HPCT_EPI_COS, HPCT_EPI_EXP, HPCT_EPI_TANH, \
-    HPCT_EPI_SIGMOID = range(18)
+    HPCT_EPI_SIGMOID, HPCT_EPI_RELU6 = range(19)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS = range(10)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
@@ -41,7 +41,7 @@ class OpDesc(C.Structure):
                 ("reduce_before_epi", C.c_int32), ("n_in", C.c_int32), ("in_", TensorDesc * HPCT_MAX_IN),
                 ("n_out", C.c_int32), ("out", TensorDesc * HPCT_MAX_OUT), ("stride_hw", C.c_int32 * 2),
                 ("pad_hw", C.c_int32 * 2), ("eps", C.c_float), ("scale", C.c_float), ("dropout_p", C.c_float),
-                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64), ("axis", C.c_int32), ("dilation_hw", C.c_int32 * 2)]
+                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64), ("axis", C.c_int32), ("dilation_hw", C.c_int32 * 2), ("groups", C.c_int32)]
 
 
 class HpctError(RuntimeError):
@@ -114,7 +114,7 @@ def tensor_desc(shape: Sequence[int], stride: Optional[Sequence[int]] = None, dt
 
 def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before_epi=0, inputs=(), outputs=(),
             stride_hw=(1, 1), pad_hw=(0, 0), eps=0.0, scale=1.0, dropout_p=0.0, dropout_seed=0,
-            reduce2=HPCT_RED_NONE, axis=0, dilation_hw=(1, 1)) -> OpDesc:
+            reduce2=HPCT_RED_NONE, axis=0, dilation_hw=(1, 1), groups=0) -> OpDesc:
     d = OpDesc()
     d.anchor = anchor
     d.n_epi = len(epi)
@@ -137,6 +137,7 @@ def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before
     d.reduce2 = reduce2
     d.axis = axis
     d.dilation_hw[0], d.dilation_hw[1] = dilation_hw
+    d.groups = groups
     return d
 
 
@@ -349,7 +350,7 @@ def maxpool2x2(X, out, stream=None) -> None:
 _MAP_BINARY = {"add": HPCT_EPI_ADD_TENSOR, "mul": HPCT_EPI_MUL_TENSOR, "sub": HPCT_EPI_SUB_TENSOR, "div": HPCT_EPI_DIV_TENSOR}
 _MAP_UNARY = {"relu": HPCT_EPI_RELU, "gelu": HPCT_EPI_GELU_TANH, "scale": HPCT_EPI_SCALE_CONST, "sqrt": HPCT_EPI_SQRT,
               "sin": HPCT_EPI_SIN, "cos": HPCT_EPI_COS, "exp": HPCT_EPI_EXP, "tanh": HPCT_EPI_TANH,
-              "sigmoid": HPCT_EPI_SIGMOID}
+              "sigmoid": HPCT_EPI_SIGMOID, "relu6": HPCT_EPI_RELU6}
 
 
 def eltwise_map_plan(a_view, out, unary=(), binary=None, b_view=None, scale=1.0):
@@ -425,21 +426,34 @@ def conv2d_bias_relu(inp, wt, bias, out, stride=1, pad=1, relu=True, stream=None
     plan.launch(ins, [out], stream)
 
 
-def conv_block_plan(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True, dilation=1):
-    """Plan of conv2d [+bias] [+per-channel scale/shift] [+relu] [+2x2 max pool] (a VGG-style block)."""
+def conv_block_plan(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True, dilation=1, groups=1):
+    """Plan of conv2d [+bias] [+per-channel scale/shift] [+relu] [+2x2 max pool] (a VGG-style block).
+    relu: False, True, or "relu6"; groups: 1 (dense) or the channel count (depthwise, wt [C,1,R,R], no pooling)."""
     assert (scale is None) == (shift is None)
-    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + \
-        ([HPCT_EPI_RELU] if relu else [])
+    act = [] if not relu else [HPCT_EPI_RELU6 if relu == "relu6" else HPCT_EPI_RELU]
+    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + act
     ins = [inp, wt] + ([bias] if bias is not None else []) + ([scale, shift] if scale is not None else [])
-    plan = _cached(("convblock", _sh(inp), _sh(wt), tuple(epi), stride, pad, pool, dilation), lambda: op_desc(
+    plan = _cached(("convblock", _sh(inp), _sh(wt), tuple(epi), stride, pad, pool, dilation, groups), lambda: op_desc(
         HPCT_ANCHOR_CONV2D_NCHW, epi, HPCT_RED_MAXPOOL2_HW if pool else HPCT_RED_NONE, 0, [_sh(t) for t in ins], [_sh(out)],
-        stride_hw=(stride, stride), pad_hw=(pad, pad), dilation_hw=(dilation, dilation)))
+        stride_hw=(stride, stride), pad_hw=(pad, pad), dilation_hw=(dilation, dilation), groups=groups))
     return plan, ins
 
 
-def conv_block(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True, dilation=1, stream=None) -> None:
+def conv_block(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, pool=True, dilation=1, stream=None,
+               groups=1) -> None:
     """out = maxpool2x2(relu((conv2d_nchw(inp, wt) + bias[k]) * scale[k] + shift[k])); every stage after the conv optional."""
-    plan, ins = conv_block_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, pool, dilation)
+    plan, ins = conv_block_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, pool, dilation, groups)
+    plan.launch(ins, [out], stream)
+
+
+def depthwise_conv_plan(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu="relu6", dilation=1):
+    """Depthwise conv (wt [C,1,R,R]) [+bias] [+per-channel scale/shift] [+relu / relu6]: the depthwise layer of a
+    MobileNetV2 block."""
+    return conv_block_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, False, dilation, groups=_sh(inp)[1])
+
+
+def depthwise_conv(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu="relu6", dilation=1, stream=None) -> None:
+    plan, ins = depthwise_conv_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, dilation)
     plan.launch(ins, [out], stream)
 
 

@@ -589,8 +589,47 @@ def test_eltwise_chain_plans():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SIN, H.HPCT_EPI_ADD_TENSOR], H.HPCT_RED_NONE, 0, [(7, 9), (7, 9)], [(7, 9)])
     expect(H.HPCT_ERR_UNSUPPORTED, d)
-    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SIN], H.HPCT_RED_NONE, 0, [(7, 9)], [(7, 9)]); d.epi[0] = 18
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SIN], H.HPCT_RED_NONE, 0, [(7, 9)], [(7, 9)]); d.epi[0] = 99
     expect(H.HPCT_ERR_BAD_DESC, d)
+
+
+def dw_desc(shape=(32, 96, 56, 56), R=3, stride=1, pad=1, dil=1, act=None, groups=None, K=None, wt_c=1, pool=False):
+    Nb, Cc, Hh, Ww = shape
+    K = Cc if K is None else K
+    Ho = (Hh + 2 * pad - (R - 1) * dil - 1) // stride + 1
+    Wo = (Ww + 2 * pad - (R - 1) * dil - 1) // stride + 1
+    epi = [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SCALE_SHIFT_CH] + ([act] if act is not None else [])
+    return H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, epi, H.HPCT_RED_MAXPOOL2_HW if pool else H.HPCT_RED_NONE, 0,
+                     [shape, (K, wt_c, R, R), (K,), (K,), (K,)], [(Nb, K, Ho // 2, Wo // 2) if pool else (Nb, K, Ho, Wo)],
+                     stride_hw=(stride, stride), pad_hw=(pad, pad), dilation_hw=(dil, dil),
+                     groups=Cc if groups is None else groups)
+
+
+def test_depthwise_conv_plans():
+    p = H.Plan(dw_desc(act=H.HPCT_EPI_RELU6))
+    assert p.kernel_name == "dwconv_planes<3x3>" and p.workspace_bytes == 0
+    # a 56 x 56 plane with its halo is 13.9 KB: one work-group per plane
+    assert p.launch_shape()[0] == (32 * 96, 1, 1) and p.launch_shape()[1] == (256, 1, 1)
+    # larger planes are cut into bands of rows
+    p = H.Plan(dw_desc(shape=(32, 32, 112, 112), act=H.HPCT_EPI_RELU))
+    assert p.launch_shape()[0][0] % (32 * 32) == 0 and p.launch_shape()[0][0] > 32 * 32 and p.launch_shape()[2] <= 16 * 1024
+    assert H.Plan(dw_desc(R=5, pad=2, stride=2)).kernel_name == "dwconv_planes<5x5>"
+    assert H.Plan(dw_desc(R=7, pad=3, shape=(2, 8, 30, 30))).kernel_name == "dwconv_planes<7x7>"
+    assert H.Plan(dw_desc(R=1, pad=0)).kernel_name == "dwconv_planes<1x1>"
+    # groups = 0 / 1 is the dense conv: wt must then be [K, C, R, R]
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, dw_desc(groups=1))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, dw_desc(groups=0))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, dw_desc(wt_c=2))                       # depthwise filters have one input channel
+    expect(H.HPCT_ERR_UNSUPPORTED, dw_desc(groups=48, wt_c=2))                # grouped, not depthwise
+    expect(H.HPCT_ERR_UNSUPPORTED, dw_desc(K=192))                            # channel multiplier 2
+    expect(H.HPCT_ERR_UNSUPPORTED, dw_desc(pool=True))
+    expect(H.HPCT_ERR_UNSUPPORTED, dw_desc(R=3, pad=3))
+    expect(H.HPCT_ERR_BAD_DESC, dw_desc(groups=-1))
+    # RELU6 takes the place of RELU in the dense conv chain too, not beside it
+    d = conv_block_desc(); d.epi[2] = H.HPCT_EPI_RELU6
+    assert H.Plan(d).kernel_name == "conv2d_nchw_mfma<3x3,pipelined,maxpool2>"
+    d = conv_block_desc(); d.n_epi = 4; d.epi[3] = H.HPCT_EPI_RELU6
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
 
 
 def test_maxpool_alone_plans():

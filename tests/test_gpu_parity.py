@@ -850,6 +850,77 @@ def test_eltwise_views():
     check_eltwise(one, one, "single element")
 
 
+# ---------------------------------------- depthwise conv (MobileNetV2's depthwise layer) and relu6
+def check_depthwise(N, C, H, W, R, stride, pad, dil=1, act="relu6", bias=True, affine=True, seed=0):
+    x = datagen.gen_normal(300 + seed, (N, C, H, W), 0.0, 1.0)
+    w = datagen.gen_normal(301 + seed, (C, 1, R, R), 0.0, 1.0 / R)
+    b = datagen.gen_normal(302 + seed, (C,), 0.0, 0.5) if bias else None
+    sc = datagen.gen_uniform(303 + seed, (C,), 0.5, 1.5) if affine else None
+    sh = datagen.gen_normal(304 + seed, (C,), 0.0, 0.5) if affine else None
+    want, Dn = ref.conv2d_nchw_grouped(x, w, b, stride, pad, C, want_norm=True, dil=dil)
+    if affine:
+        want = ref.scale_shift_ch(want, sc, sh)
+        Dn = ref.scale_shift_ch(Dn, np.abs(sc), np.abs(sh))
+    if act == "relu6":
+        want = ref.relu6(want)
+    elif act:
+        want = ref.relu(want)
+    out = torch.full(want.shape, float("nan"), device="cuda")
+    plan, ins = hpct.depthwise_conv_plan(dev(x), dev(w), None if b is None else dev(b), None if sc is None else dev(sc),
+                                         None if sh is None else dev(sh), out, stride, pad, act, dil)
+    plan.launch(ins, [out])
+    assert show("depthwise %s" % plan.kernel_name, compare.contraction(host(out), want, Dn))
+    return host(out), plan
+
+
+def test_depthwise_full_size():
+    # the 3x3 depthwise layers of a MobileNetV2 at batch 32: 96 channels at 112 x 112 (stride 2) and 144 at 56 x 56
+    got, plan = check_depthwise(32, 144, 56, 56, 3, 1, 1)
+    assert plan.kernel_name == "dwconv_planes<3x3>"
+    check_depthwise(32, 96, 112, 112, 3, 2, 1)
+
+
+@pytest.mark.parametrize("N,C,H,W,R,stride,pad,dil", [
+    (1, 1, 1, 1, 1, 1, 0, 1), (2, 3, 7, 9, 3, 1, 1, 1), (1, 5, 13, 5, 3, 2, 1, 1), (2, 4, 10, 30, 5, 1, 2, 1),
+    (1, 6, 33, 41, 7, 2, 3, 1), (1, 3, 17, 23, 3, 1, 2, 2), (1, 2, 40, 40, 3, 3, 0, 1), (1, 7, 9, 200, 3, 1, 1, 1),
+    (1, 2, 300, 20, 5, 1, 2, 3), (3, 8, 28, 28, 3, 1, 1, 1), (1, 4, 6, 6, 1, 2, 0, 1), (1, 2, 12, 12, 3, 1, 0, 4)])
+def test_depthwise_ragged_shapes(N, C, H, W, R, stride, pad, dil):
+    print("depthwise %s" % ((N, C, H, W, R, stride, pad, dil),), flush=True)
+    check_depthwise(N, C, H, W, R, stride, pad, dil)
+    check_depthwise(N, C, H, W, R, stride, pad, dil, act="relu", affine=False, seed=1)
+    check_depthwise(N, C, H, W, R, stride, pad, dil, act=False, bias=False, affine=False, seed=2)
+
+
+def test_depthwise_does_not_mix_channels():
+    # centre-tap delta filters scaled per channel: out[n, c] = s[c] * in[n, c] exactly
+    x = datagen.gen_normal(310, (2, 9, 12, 20), 0.0, 1.0)
+    s = datagen.gen_normal(311, (9,), 0.0, 1.0)
+    w = np.zeros((9, 1, 3, 3), np.float32); w[:, 0, 1, 1] = s
+    out = torch.full((2, 9, 12, 20), float("nan"), device="cuda")
+    hpct.depthwise_conv(dev(x), dev(w), None, None, None, out, 1, 1, relu=False)
+    assert np.array_equal(host(out), x * s[None, :, None, None])
+
+
+def test_relu6_in_the_dense_conv_and_as_a_step():
+    t = datagen.make(7, N=2, C=8, H=14, W=14, K=64, R=3, S=3)
+    x, w, b = t["in"], t["wt"] * 8.0, t["bias"]              # large weights: some outputs pass 6
+    for pool in (False, True):
+        Z, Dn = ref.conv2d_nchw_bias(x, w, b, 1, 1, want_norm=True)
+        want = ref.relu6(Z)
+        if pool:
+            want, Dn = ref.maxpool2x2(want), ref.maxpool2x2(Dn)
+        out = torch.full(want.shape, float("nan"), device="cuda")
+        plan, ins = hpct.conv_block_plan(dev(x), dev(w), dev(b), None, None, out, 1, 1, "relu6", pool)
+        plan.launch(ins, [out])
+        got = host(out)
+        assert show("conv relu6", compare.contraction(got, want, Dn))
+        assert got.max() == 6.0 and got.min() == 0.0
+    a = dev(datagen.gen_normal(312, (33, 40), 0.0, 5.0))
+    out = torch.full((33, 40), float("nan"), device="cuda")
+    hpct.eltwise_map(a, out, ("relu6",))
+    assert np.array_equal(host(out), ref.eltwise_map(host(a), (33, 40), (40, 1), ("relu6",)).astype(np.float32))
+
+
 # ------------------------------------------------------- 2x2 max pooling alone
 @pytest.mark.parametrize("shape", [(32, 64, 56, 56), (2, 3, 7, 9), (1, 1, 2, 2), (3, 5, 13, 16), (2, 2, 8, 6), (1, 4, 224, 224)])
 def test_maxpool_alone(shape):

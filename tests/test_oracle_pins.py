@@ -779,6 +779,8 @@ def test_eltwise_map_known_values():
     # relu and scale
     assert np.array_equal(emap([-2.0, 0.0, 3.0], ["relu"]), [0.0, 0.0, 3.0])
     assert np.array_equal(emap([-2.0, 0.5], ["scale"], scale=-4.0), [8.0, -2.0])
+    assert np.array_equal(emap([-2.0, 0.5, 6.0, 7.5], ["relu6"]), [0.0, 0.5, 6.0, 6.0])
+    assert np.array_equal(emap([-2.0, 0.5, 6.0, 7.5], ["relu6"]), ref.relu6(np.array([-2.0, 0.5, 6.0, 7.5])))
     # the constant is the fp32 one
     assert emap([1.0], ["scale"], scale=0.1)[0] == float(np.float32(0.1))
 
