@@ -152,6 +152,11 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
                     const char** why);
 LaunchShape conv_shape(const ConvParams& p);
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream);
+// 1x1, stride 1, no padding: the weight-stationary streaming kernel (k_conv1x1.hip), taken by conv_shape /
+// conv_launch whenever conv1x1_stream_ok
+bool conv1x1_stream_ok(const ConvParams& p);
+LaunchShape conv1x1_shape(const ConvParams& p);
+hipError_t conv1x1_launch(const ConvParams& p, hipStream_t stream);
 // depthwise (groups = C = K, wt[C,1,R,R]): a memory-bound stencil kernel of its own (k_dwconv.hip)
 bool dwconv_supported(const ConvParams& p, const char** why);
 LaunchShape dwconv_shape(const ConvParams& p);

@@ -504,7 +504,7 @@ def test_chain7_pipelined_staging_modes(N, C, H, W, K, R, stride, pad):
     print("chain7 modes %s" % ((N, C, H, W, K, R, stride, pad),), flush=True)
     t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=R, S=R)
     _, name = check_chain7(t, stride, pad, pool=False)
-    assert "pipelined" in name
+    assert "pipelined" in name or (R == 1 and name.startswith("conv1x1_stream"))
     _, name = check_chain7(t, stride, pad)
     assert "pipelined" in name
     check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False)
@@ -526,6 +526,31 @@ def test_conv_window_geometry_without_pooling(N, C, H, W, K, R, stride, pad, dil
     _, name = check_chain7(t, stride, pad, pool=False, dil=dil)
     assert "window" in name
     check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False, dil=dil)
+
+
+@pytest.mark.parametrize("N,C,H,W,K", [
+    (32, 64, 56, 56, 64),        # a bottleneck's 1x1 at full size: memory-bound
+    (32, 24, 56, 56, 144),       # a MobileNetV2 expansion: one chunk of 32 channels, 8 of them padding
+    (4, 96, 14, 14, 64),         # three chunks of 32 channels
+    (1, 8, 5, 7, 3),             # one ragged block, three output channels
+    (3, 72, 9, 11, 130),         # chunks of 32 with a padded tail; two slices of output channels, the last ragged
+    (5, 16, 3, 3, 32),           # 45 pixels: blocks span images
+    (2, 40, 20, 20, 256)])       # 128 output channels per work-group, twice
+def test_conv1x1_streaming_kernel(N, C, H, W, K):
+    print("conv1x1 %s" % ((N, C, H, W, K),), flush=True)
+    t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=1, S=1)
+    _, name = check_chain7(t, 1, 0, pool=False)
+    assert name.startswith("conv1x1_stream")
+    check_chain7(t, 1, 0, relu=False, pool=False, bias=False, affine=False)
+    # relu6 and the bare bias
+    want, Dn = ref.conv2d_nchw_bias(t["in"], t["wt"] * 16.0, t["bias"], 1, 0, want_norm=True)
+    out = torch.full(want.shape, float("nan"), device="cuda")
+    hpct.conv_block(dev(t["in"]), dev(t["wt"] * 16.0), dev(t["bias"]), None, None, out, 1, 0, "relu6", False)
+    assert show("1x1 relu6", compare.contraction(host(out), ref.relu6(want), Dn))
+    # pooled 1x1 convs stay with the tile kernel
+    if H >= 2 and W >= 2:
+        _, name = check_chain7(t, 1, 0)
+        assert name.startswith("conv2d_nchw_mfma<1x1")
 
 
 def test_chain7_pool_takes_the_maximum_not_a_sum_or_a_corner():
