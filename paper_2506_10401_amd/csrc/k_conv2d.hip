@@ -12,7 +12,7 @@
 // accumulator register is stored as 32 consecutive pixels = 128 contiguous
 // bytes of the NCHW output.
 //
-// A work-group of four waves owns KT (64 or 128) output channels x TP = 64
+// A work-group of four waves owns KT = 64 output channels x TP = 64
 // consecutive output pixels of one image; a wave owns KT/2 channels x 32 pixels.
 // Channels are processed CC at a time.  Per chunk the LDS holds
 //   * the input rows the tile touches, with their zero halo, per channel, and
@@ -20,7 +20,11 @@
 //     copy of a contiguous piece of the KCRS tensor, row stride padded against
 //     bank conflicts).
 // Both are double buffered: the global loads of chunk t+1 are issued before the
-// MFMAs of chunk t and written to the other buffer after them.
+// MFMAs of chunk t and written to the other buffer after them.  Vector-ALU
+// instructions do not overlap MFMAs, so the chunk loop is kept almost free of
+// them: raw buffer loads with per-slot offsets worked out once (the zero halo is
+// an out-of-range offset), two chunks per trip so the LDS stage is a compile-time
+// constant, one precomputed LDS pointer per fragment row.
 //
 // Contraction order: within a chunk, lane half 0 multiplies channels
 // 0..CC/2-1 and lane half 1 channels CC/2..CC-1, so MFMA step s contracts
