@@ -953,3 +953,89 @@ def test_maxpool_alone(shape):
     out = torch.full((shape[0], shape[1], shape[2] // 2, shape[3] // 2), float("nan"), device="cuda")
     hpct.maxpool2x2(dev(X), out)
     assert np.array_equal(host(out), ref.maxpool2x2(X.astype(np.float64)).astype(np.float32))
+
+
+# ------------------------------------------------------------ seeded sweeps of random valid shapes
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def test_sweep_gemm_shapes():
+    r = _rng(20250610401)
+    for case in range(40):
+        # small, tile-sized and split-K-sized problems; K a multiple of 4 in half the cases (vector path)
+        M = int(r.choice([1, 7, 16, 33, 64, 130, 257, 600, 1100]))
+        N = int(r.choice([1, 5, 64, 100, 256, 300, 513, 1030]))
+        K = int(r.choice([1, 3, 4, 8, 12, 16, 20, 36, 64, 100, 260, 1024, 2052]))
+        wt = bool(r.integers(2))
+        scale = None if r.integers(2) else float(r.choice([0.5, -1.25, 3.0]))
+        print("sweep gemm %d: M=%d K=%d N=%d wt=%s scale=%s" % (case, M, K, N, wt, scale), flush=True)
+        t = datagen.make(1, M=M, K=K, N=N)
+        Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+        if scale is not None:
+            Z, Dn = ref.scale_const(Z, scale), Dn * abs(float(np.float32(scale)))
+        got, name = run_gemm(t, wt=wt, relu=True, scale=scale)
+        assert show(name, compare.contraction(got, ref.relu(Z), Dn))
+
+
+def test_sweep_conv_shapes():
+    r = _rng(20250610402)
+    for case in range(40):
+        R = int(r.choice([1, 3, 3, 3, 5, 7]))
+        stride = int(r.choice([1, 1, 2, 3]))
+        dil = int(r.choice([1, 1, 1, 2]))
+        pad = int(r.integers(0, (R - 1) * dil + 1))
+        C = int(r.choice([1, 3, 4, 8, 16, 20, 32, 64]))
+        K = int(r.choice([1, 7, 32, 64, 70, 130]))
+        re = (R - 1) * dil + 1
+        H = int(r.integers(max(1, re - 2 * pad), 40))
+        W = int(r.choice([max(1, re - 2 * pad), 7, 8, 14, 28, 30, 66, 100]))
+        if H + 2 * pad < re or W + 2 * pad < re:
+            continue
+        Ho, Wo = ref.conv_out_hw(H, W, R, R, stride, pad, dil)
+        pool = bool(r.integers(2)) and Ho >= 2 and Wo >= 2
+        relu = [True, False, "relu6"][int(r.integers(3))]
+        N = int(r.choice([1, 2, 3]))
+        print("sweep conv %d: %s" % (case, (N, C, H, W, K, R, stride, pad, dil, pool, relu)), flush=True)
+        t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=R, S=R)
+        out, Dn = ref.conv2d_nchw_bias(t["in"], t["wt"], t["bias"], stride, pad, want_norm=True, dil=dil)
+        out = ref.scale_shift_ch(out, t["scale"], t["shift"])
+        Dn = ref.scale_shift_ch(Dn, np.abs(t["scale"]), np.abs(t["shift"]))
+        out = ref.relu6(out) if relu == "relu6" else (ref.relu(out) if relu else out)
+        if pool:
+            out, Dn = ref.maxpool2x2(out), ref.maxpool2x2(Dn)
+        o = torch.full(out.shape, float("nan"), device="cuda")
+        plan, ins = hpct.conv_block_plan(dev(t["in"]), dev(t["wt"]), dev(t["bias"]), dev(t["scale"]), dev(t["shift"]), o,
+                                         stride, pad, relu, pool, dil)
+        plan.launch(ins, [o])
+        assert show(plan.kernel_name, compare.contraction(host(o), out, Dn))
+
+
+def test_sweep_depthwise_shapes():
+    r = _rng(20250610403)
+    for case in range(30):
+        R = int(r.choice([1, 3, 3, 5, 7]))
+        stride = int(r.choice([1, 1, 2, 3, 4]))
+        dil = int(r.choice([1, 1, 2, 3]))
+        pad = int(r.integers(0, (R - 1) * dil + 1))
+        re = (R - 1) * dil + 1
+        H = int(r.integers(max(1, re - 2 * pad), 70))
+        W = int(r.integers(max(1, re - 2 * pad), 130))
+        N, C = int(r.choice([1, 2, 5])), int(r.choice([1, 3, 8, 17]))
+        print("sweep depthwise %d: %s" % (case, (N, C, H, W, R, stride, pad, dil)), flush=True)
+        check_depthwise(N, C, H, W, R, stride, pad, dil, act=[False, "relu", "relu6"][int(r.integers(3))], seed=case)
+
+
+def test_sweep_attention_shapes():
+    r = _rng(20250610404)
+    for case in range(24):
+        D = int(r.choice([32, 64, 64, 128]))
+        B = int(r.choice([1, 2, 3]))
+        L = int(r.choice([1, 5, 31, 64, 65, 130, 200, 300]))
+        causal = bool(r.integers(2))
+        Lk = L if causal and r.integers(2) else int(r.choice([1, 7, 63, 64, 65, 129, 257, 400]))
+        print("sweep attention %d: %s" % (case, (B, L, Lk, D, causal)), flush=True)
+        t = datagen.make(5, B=B, L=L, Lk=Lk, D=D)
+        scale = 1.0 / np.sqrt(D)
+        want, Dn = ref.attention(t["Q"], t["K"], t["V"], scale, want_norm=True, causal=causal)
+        assert show("attention", compare.contraction(run_chain5(t, scale, causal=causal), want, Dn))
