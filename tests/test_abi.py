@@ -488,7 +488,7 @@ def test_causal_attention_plan():
 
 def test_attention_head_dims():
     for D, plain, causal in [(32, "attn_fwd_d32<ks2>", "attn_fwd_d32<ks4,causal,paired>"),
-                             (128, "attn_fwd_d128<ks2>", "attn_fwd_d128<ks2,causal>")]:
+                             (128, "attn_fwd_d128<ks2>", "attn_fwd_d128<ks2,causal,paired>")]:
         d = cfg_desc(5); d.in_[0] = d.in_[1] = d.in_[2] = H.tensor_desc((16, 2048, D)); d.out[0] = H.tensor_desc((16, 2048, D))
         p = H.Plan(d)
         assert p.kernel_name == plain and p.launch_shape()[0] == (256, 1, 1)
