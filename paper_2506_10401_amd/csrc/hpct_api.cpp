@@ -128,23 +128,23 @@ uint32_t dropout_threshold(float p) {
 
 hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     static const hpct_epilogue order[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_CONST, HPCT_EPI_RELU, HPCT_EPI_DROPOUT_HASH};
-    bool has[4], ho[4];
-    if (!parse_epi(d, order, 4, ho))
+    bool has[4];
+    if (!parse_epi(d, order, 4, has))
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [SCALE_CONST] [RELU] [DROPOUT_HASH] in that order");
-    has[0] = ho[0]; has[1] = ho[2]; has[2] = ho[3]; has[3] = ho[1];
+    const bool has_bias = has[0], has_scale = has[1], has_relu = has[2], has_dropout = has[3];
     if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_SOFTMAX_LAST && d.reduce != HPCT_RED_MEAN_LAST)
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: reduction must be NONE, SOFTMAX_LAST or MEAN_LAST");
     if (d.reduce != HPCT_RED_NONE && d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: the reduction runs after the epilogues");
     const bool mean = d.reduce == HPCT_RED_MEAN_LAST;
     if (d.reduce2 != HPCT_RED_NONE && !(mean && d.reduce2 == HPCT_RED_SOFTMAX_LAST))
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: the only second reduction supported is SOFTMAX_LAST after MEAN_LAST");
-    const int need = 2 + (has[0] ? 1 : 0);
+    const int need = 2 + (has_bias ? 1 : 0);
     if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "GEMM chain takes %d inputs and 1 output (got %d, %d)", need, d.n_in, d.n_out);
     const hpct_tensor_desc &X = d.in[0], &W = d.in[1];
     if (X.ndim != 2 || W.ndim != 2) return fail(HPCT_ERR_SHAPE_MISMATCH, "GEMM operands must be 2-D: X[M,K], W[K,N]");
     const int64_t M = X.shape[0], K = X.shape[1], N = W.shape[1];
     if (W.shape[0] != K) return fail(HPCT_ERR_SHAPE_MISMATCH, "W.shape[0] = %lld does not match X.shape[1] = %lld", (long long)W.shape[0], (long long)K);
-    if (has[0]) REQUIRE_SHAPE(d.in[2], "bias", N);
+    if (has_bias) REQUIRE_SHAPE(d.in[2], "bias", N);
     if (mean) REQUIRE_SHAPE(d.out[0], "out[0]", M);
     else REQUIRE_SHAPE(d.out[0], "out[0]", M, N);
     // W: row-major [K,N], or the transposed storage of a linear layer's weight ([N,K] row-major seen as [K,N]
@@ -160,10 +160,10 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     const bool sm = d.reduce == HPCT_RED_SOFTMAX_LAST;
     GemmParams g{};
     g.M = (int32_t)M; g.K = (int32_t)K; g.N = (int32_t)N;
-    g.relu = has[1] ? 1 : 0; g.softmax = sm ? 1 : 0;
-    g.scale = has[3] ? d.scale : 1.0f;
+    g.relu = has_relu ? 1 : 0; g.softmax = sm ? 1 : 0;
+    g.scale = has_scale ? d.scale : 1.0f;
     g.wt = wt ? 1 : 0;
-    if (has[2]) {
+    if (has_dropout) {
         if (!(d.dropout_p >= 0.f && d.dropout_p < 1.f)) return fail(HPCT_ERR_BAD_DESC, "DROPOUT_HASH: dropout_p must satisfy 0 <= p < 1");
         g.dropout = 1;
         g.drop_t = dropout_threshold(d.dropout_p);
@@ -174,7 +174,7 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     g.softmax2 = d.reduce2 == HPCT_RED_SOFTMAX_LAST ? 1 : 0;
     p.kind = Kind::Gemm;
     p.u.gemm = g;
-    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has[0] ? 2 : -1; p.slot[3] = -1;
+    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has_bias ? 2 : -1; p.slot[3] = -1;
     p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.wt);
     p.ws_bytes = gemm_workspace_bytes((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0);
     return HPCT_OK;
