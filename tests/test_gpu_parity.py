@@ -1039,3 +1039,60 @@ def test_sweep_attention_shapes():
         scale = 1.0 / np.sqrt(D)
         want, Dn = ref.attention(t["Q"], t["K"], t["V"], scale, want_norm=True, causal=causal)
         assert show("attention", compare.contraction(run_chain5(t, scale, causal=causal), want, Dn))
+
+
+# ------------------------------------------------------------------ HIP graph capture
+def test_launches_can_be_captured_in_a_hip_graph_and_replayed():
+    # The library neither allocates nor synchronises nor clears memory through the runtime, so a
+    # sequence of launches can be captured once and replayed: the five chains at small sizes, the
+    # dropout chain (with its workspace and finishing kernels), a depthwise conv and an axis reduction.
+    t1, t2, t3 = datagen.make(1), datagen.make(2, N=2, C=8, H=12, W=12), datagen.make(3, M=64, N=1024)
+    t4, t5 = datagen.make(4, N=2, C=8, H=14, W=14, K=64), datagen.make(5, B=2, L=130, Lk=130)
+    t6 = datagen.make(6, M=256, K=64, N=512)
+    jobs = []
+
+    def job(plan_ins, out):
+        plan, ins = plan_ins
+        ws = torch.empty(plan.workspace_bytes // 4, device="cuda") if plan.workspace_bytes else None
+        jobs.append((plan, ins, out, ws))
+
+    o1 = torch.empty(64, 256, device="cuda")
+    job(hpct.gemm_bias_relu_softmax_plan(dev(t1["X"]), dev(t1["W"]), dev(t1["bias"]), o1), o1)
+    o2 = torch.empty(2, 8, device="cuda")
+    job(hpct.scale_shift_relu_add_pool_plan(dev(t2["X"]), dev(t2["scale"]), dev(t2["shift"]), dev(t2["R"]), o2), o2)
+    o3 = torch.empty(64, 1024, device="cuda")
+    job(hpct.layernorm_gelu_plan(dev(t3["X"]), dev(t3["gamma"]), dev(t3["beta"]), o3), o3)
+    o4 = torch.empty(2, 64, 14, 14, device="cuda")
+    job(hpct.conv2d_bias_relu_plan(dev(t4["in"]), dev(t4["wt"]), dev(t4["bias"]), o4), o4)
+    o5 = torch.empty(2, 130, 64, device="cuda")
+    job(hpct.attention_plan(dev(t5["Q"]), dev(t5["K"]), dev(t5["V"]), o5), o5)
+    o6 = torch.empty(256, device="cuda")
+    job(hpct.matmul_dropout_mean_softmax_plan(dev(t6["X"]), dev(t6["W"]), dev(t6["bias"]), o6, 0.25, 7), o6)
+    xd = dev(datagen.gen_normal(400, (2, 6, 20, 20), 0.0, 1.0))
+    od = torch.empty(2, 6, 20, 20, device="cuda")
+    job(hpct.depthwise_conv_plan(xd, dev(datagen.gen_normal(401, (6, 1, 3, 3), 0.0, 0.5)), None, None, None, od), od)
+    xr = dev(datagen.gen_normal(402, (300, 520), 0.0, 1.0))
+    orr = torch.empty(520, device="cuda")
+    job(hpct.reduce_axis_plan(xr, orr, 0, "sum"), orr)
+    assert any(ws is not None for _, _, _, ws in jobs)
+
+    def run_all():
+        for plan, ins, out, ws in jobs:
+            plan.launch(ins, [out], workspace=ws)      # on the stream current now
+
+    run_all()                                          # eager reference
+    torch.cuda.synchronize()
+    want = [host(o).copy() for _, _, o, _ in jobs]
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):                      # the capture stream is current inside
+        run_all()
+    for rep in range(3):
+        for _, _, o, _ in jobs:
+            o.fill_(float("nan"))                      # eager work between the replays
+        jobs[0][0].launch(jobs[0][1], [jobs[0][2]])    # and an eager launch of the library itself
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (_, _, o, _), w in zip(jobs, want):
+            assert np.array_equal(host(o).view(np.uint32), w.view(np.uint32)), rep
