@@ -238,6 +238,49 @@ void ref_conv2d_nchw_grouped(const float *in, const float *wt, const float *bias
     }
 }
 
+/* ---- Transposed conv ("Conv-Trans", a Level-2 operator the paper's Section 5.2
+ * names), NCHW, the adjoint of the conv above with respect to its input:
+ * every input element is scattered through the filter,
+ *     out[n][k][ih*stride - P + kh*dil][iw*stride - P + kw*dil] += in[n][c][ih][iw] * wt[c][k][kh][kw],
+ * positions outside the output dropped; out starts at bias[k].  Weights are
+ * [C][K][R][S] contiguous (input channels first).  Output size
+ * (H - 1)*stride - 2P + (R - 1)*dil + 1 (no extra output padding).
+ * Dn (may be NULL) = |bias| + the same sum over absolute values. */
+void ref_conv_transpose2d_nchw(const float *in, const float *wt, const float *bias,
+                               int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t K,
+                               int64_t R, int64_t S, int64_t stride, int64_t P, int64_t dil,
+                               double *out, double *Dn)
+{
+    const int64_t Ho = (H - 1) * stride - 2 * P + (R - 1) * dil + 1, Wo = (W - 1) * stride - 2 * P + (S - 1) * dil + 1;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t n = 0; n < Nb; ++n) {
+        for (int64_t k = 0; k < K; ++k) {        /* one output plane per iteration: no two threads write the same element */
+            double *o = out + (n * K + k) * Ho * Wo;
+            double *d = Dn ? Dn + (n * K + k) * Ho * Wo : NULL;
+            double b = bias ? (double)bias[k] : 0.0;
+            for (int64_t i = 0; i < Ho * Wo; ++i) { o[i] = b; if (d) d[i] = fabs(b); }
+            for (int64_t c = 0; c < C; ++c) {
+                for (int64_t ih = 0; ih < H; ++ih) {
+                    for (int64_t iw = 0; iw < W; ++iw) {
+                        double a = (double)in[((n * C + c) * H + ih) * W + iw];
+                        for (int64_t kh = 0; kh < R; ++kh) {
+                            for (int64_t kw = 0; kw < S; ++kw) {
+                                int64_t oh = ih * stride - P + kh * dil;
+                                int64_t ow = iw * stride - P + kw * dil;
+                                if (oh >= 0 && oh < Ho && ow >= 0 && ow < Wo) {
+                                    double g = (double)wt[((c * K + k) * R + kh) * S + kw];
+                                    o[oh * Wo + ow] += a * g;
+                                    if (d) d[oh * Wo + ow] += fabs(a) * fabs(g);
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
 /* ---- Elementwise: relu6 = min(max(z, 0), 6), the activation of those blocks, in place */
 void ref_relu6(double *Z, int64_t count)
 {

@@ -36,6 +36,7 @@ def lib():
             "ref_conv2d_nchw_bias": [p, p, p] + [i64] * 10 + [p, p],
             "ref_conv2d_nchw_grouped": [p, p, p] + [i64] * 11 + [p, p],
             "ref_relu6": [p, i64],
+            "ref_conv_transpose2d_nchw": [p, p, p] + [i64] * 10 + [p, p],
             "ref_attention": [p, p, p, i64, i64, i64, i64, dbl, p, p],
             "ref_attention_causal": [p, p, p, i64, i64, i64, i64, dbl, p, p],
             "ref_layout_copy": [p, C.c_int32, p, p, p],
@@ -172,6 +173,26 @@ def conv2d_nchw_grouped(inp, wt, bias=None, stride=1, pad=1, groups=1, want_norm
     Dn = np.empty_like(out) if want_norm else None
     lib().ref_conv2d_nchw_grouped(_ptr(inp), _ptr(wt), _ptr(b), Nb, Cc, H, W, K, R, S, stride, pad, dil, groups,
                                   _ptr(out), _ptr(Dn))
+    return (out, Dn) if want_norm else out
+
+
+def conv_transpose_out_hw(H, W, R, S, stride, pad, dil=1):
+    return (H - 1) * stride - 2 * pad + (R - 1) * dil + 1, (W - 1) * stride - 2 * pad + (S - 1) * dil + 1
+
+
+def conv_transpose2d_nchw(inp, wt, bias=None, stride=1, pad=0, want_norm=False, dil=1):
+    """Transposed conv: inp [N,C,H,W], wt [C,K,R,S] (input channels first), out [N,K,Ho,Wo]."""
+    inp, wt = _f32(inp), _f32(wt)
+    Nb, Cc, H, W = inp.shape
+    C2, K, R, S = wt.shape
+    assert Cc == C2
+    b = None if bias is None else _f32(bias)
+    Ho, Wo = conv_transpose_out_hw(H, W, R, S, stride, pad, dil)
+    assert Ho >= 1 and Wo >= 1
+    out = np.empty((Nb, K, Ho, Wo), dtype=np.float64)
+    Dn = np.empty_like(out) if want_norm else None
+    lib().ref_conv_transpose2d_nchw(_ptr(inp), _ptr(wt), _ptr(b), Nb, Cc, H, W, K, R, S, stride, pad, dil,
+                                    _ptr(out), _ptr(Dn))
     return (out, Dn) if want_norm else out
 
 

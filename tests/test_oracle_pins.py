@@ -908,3 +908,57 @@ def test_depthwise_conv_closed_forms_and_brute_force():
 
 def test_relu6_clamps_both_ends():
     assert np.array_equal(ref.relu6(np.array([-3.0, -0.0, 0.5, 6.0, 6.5, 1e9])), [0.0, 0.0, 0.5, 6.0, 6.0, 6.0])
+
+
+# ------------------------------------------------ transposed conv
+def test_conv_transpose_is_the_adjoint_of_the_conv():
+    # <conv(x, w), y> = <x, conv_transpose(y, w')> with w' = w seen as [C_of_y = K][K_of_result = C][R][S]:
+    # the defining property, for strides, paddings and dilations
+    for (C, K, H, W, R, stride, pad, dil) in [(3, 4, 7, 8, 3, 1, 1, 1), (2, 5, 9, 9, 3, 2, 1, 1), (4, 2, 10, 7, 5, 2, 2, 1),
+                                              (2, 3, 11, 12, 3, 1, 2, 2), (3, 3, 8, 8, 1, 1, 0, 1), (1, 2, 13, 9, 3, 3, 0, 1)]:
+        w = f32(rng.normal(size=(K, C, R, R)))
+        Hy, Wy = ref.conv_out_hw(H, W, R, R, stride, pad, dil)
+        # the transposed conv (no extra output padding) produces the smallest input size that gives Hy x Wy; with
+        # stride > 1 that can be up to stride - 1 rows / columns short of H x W, so x is zero there
+        Ht, Wt = ref.conv_transpose_out_hw(Hy, Wy, R, R, stride, pad, dil)
+        assert Ht <= H and Wt <= W and H - Ht < stride and W - Wt < stride
+        x = f32(rng.normal(size=(2, C, H, W)))
+        x[:, :, Ht:, :] = 0.0
+        x[:, :, :, Wt:] = 0.0
+        y = f32(rng.normal(size=(2, K, Hy, Wy)))
+        lhs = float(np.sum(ref.conv2d_nchw_bias(x, w, None, stride, pad, dil=dil) * y.astype(np.float64)))
+        # the transposed conv of y maps K channels back to C: its weight tensor [K][C][R][S] is w itself
+        xt = ref.conv_transpose2d_nchw(y, w, None, stride, pad, dil=dil)
+        assert xt.shape == (2, C, Ht, Wt)
+        rhs = float(np.sum(xt * x[:, :, :Ht, :Wt].astype(np.float64)))
+        assert abs(lhs - rhs) < 1e-10 * max(1.0, abs(lhs))
+
+
+def test_conv_transpose_closed_forms_and_brute_force():
+    x = f32(rng.normal(size=(2, 3, 5, 6)))
+    # stride 1: a conv with the filter flipped, input and output channels swapped, padding R - 1 - P
+    w = f32(rng.normal(size=(3, 4, 3, 3))); b = f32(rng.normal(size=4))
+    got = ref.conv_transpose2d_nchw(x, w, b, 1, 1)
+    wf = np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+    assert np.max(np.abs(got - ref.conv2d_nchw_bias(x, wf, b, 1, 3 - 1 - 1))) < 1e-13
+    # 1x1 filter, stride 2: the input lands on the even positions, the rest is the bias
+    w1 = f32(rng.normal(size=(3, 2, 1, 1)))
+    got = ref.conv_transpose2d_nchw(x, w1, f32([0.5, -1.0]), 2, 0)
+    assert got.shape == (2, 2, 9, 11)
+    mix = np.einsum("nchw,ck->nkhw", x.astype(np.float64), w1[:, :, 0, 0].astype(np.float64))
+    assert np.max(np.abs(got[:, :, ::2, ::2] - (mix + np.array([0.5, -1.0])[None, :, None, None]))) < 1e-13
+    assert np.all(got[:, 0, 1::2, :] == 0.5) and np.all(got[:, 1, :, 1::2] == -1.0)
+    # all-ones 2x2 filter at stride 2 tiles the output: every output is one input (no overlaps)
+    ones = np.ones((1, 1, 2, 2), np.float32)
+    got = ref.conv_transpose2d_nchw(x[:1, :1], ones, None, 2, 0)
+    assert np.array_equal(got[0, 0], np.kron(x[0, 0].astype(np.float64), np.ones((2, 2))))
+    # brute force over the scatter definition, stride 2, padding 1, with the magnitude sum
+    w = f32(rng.normal(size=(3, 2, 3, 3)))
+    got, Dn = ref.conv_transpose2d_nchw(x, w, None, 2, 1, want_norm=True)
+    want = np.zeros(got.shape); mag = np.zeros(got.shape)
+    for n, c, ih, iw, k, kh, kw in itertools.product(range(2), range(3), range(5), range(6), range(2), range(3), range(3)):
+        oh, ow = 2 * ih - 1 + kh, 2 * iw - 1 + kw
+        if 0 <= oh < got.shape[2] and 0 <= ow < got.shape[3]:
+            want[n, k, oh, ow] += float(x[n, c, ih, iw]) * float(w[c, k, kh, kw])
+            mag[n, k, oh, ow] += abs(float(x[n, c, ih, iw])) * abs(float(w[c, k, kh, kw]))
+    assert np.max(np.abs(got - want)) < 1e-13 and np.max(np.abs(Dn - mag)) < 1e-13
