@@ -53,6 +53,10 @@
  *         ARGMIN_AXIS over dim `axis`, no epilogue    >= 0, up to 6 dims)           dim `axis`, contiguous
  *                                                                                   (1-D input: shape [1]);
  *                                                                                   int32 for the arg ops
+ *   CONVT2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH]        in[N,C,H,W], wt[C,K,R,S],     [N,K,Ho,Wo]
+ *         [+RELU|RELU6] (needs the workspace: the     bias[K], scale[K], shift[K]
+ *         flipped filter and, for stride > 1, the
+ *         zero-dilated input; two kernels)
  *   CONV2D_NCHW, groups = C: depthwise                in[N,C,H,W], wt[C,1,R,S],     [N,C,Ho,Wo]
  *         [+BIAS_COL] [+SCALE_SHIFT_CH] [+RELU|RELU6] bias[C], scale[C], shift[C]
  *   CONV2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH] [+RELU] in[N,C,H,W], wt[K,C,R,S],     [N,K,Ho,Wo], or
@@ -106,7 +110,10 @@ typedef enum {
     HPCT_ANCHOR_NONE = 0,
     HPCT_ANCHOR_GEMM = 1,                 /* Z[m,n] = sum_k X[m,k] W[k,n] */
     HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM = 2,  /* O = softmax_j(scale * Q K^T) V, per batch */
-    HPCT_ANCHOR_CONV2D_NCHW = 3           /* cross-correlation, zero padding (Section 5.3 case study) */
+    HPCT_ANCHOR_CONV2D_NCHW = 3,          /* cross-correlation, zero padding (Section 5.3 case study) */
+    HPCT_ANCHOR_CONVT2D_NCHW = 4          /* transposed conv ("Conv-Trans", Section 5.2): in[n][c][ih][iw] is scattered through
+                                             wt[c][k][kh][kw] to out[n][k][ih*stride - pad + kh*dilation][iw*stride - pad + kw*dilation];
+                                             output size (H-1)*stride - 2*pad + (R-1)*dilation + 1, no extra output padding */
 } hpct_anchor;
 
 /* Elementwise / broadcast epilogues (Table 1, Elementwise), applied in list order. */

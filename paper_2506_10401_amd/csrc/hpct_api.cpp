@@ -26,7 +26,7 @@ hpct_status fail(hpct_status st, const char* fmt, ...) {
 
 void clear_err() { g_err[0] = 0; }
 
-enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool, DwConv };
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool, DwConv, ConvT };
 
 constexpr int64_t kI32Max = 2147483647LL;
 
@@ -54,6 +54,7 @@ struct hpct_plan {
         ReduceParams red;
         EltwiseParams elt;
     } u;
+    ConvTParams convt;   // Kind::ConvT: the preparation step; u.conv is the stride-1 conv that follows it
 };
 
 namespace {
@@ -544,6 +545,66 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
     return HPCT_OK;
 }
 
+// Transposed conv = preparation of the flipped filter (and, for stride > 1, the zero-dilated input) in the
+// workspace, then the stride-1 conv kernel at padding (R-1)*dilation - pad.
+hpct_status plan_convt(const hpct_op_desc& d, hpct_plan& p) {
+    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_RELU6};
+    bool has[4];
+    if (!parse_epi(d, allowed, 4, has) || (has[2] && has[3]))
+        return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: epilogues must be [BIAS_COL] [SCALE_SHIFT_CH] [RELU | RELU6] in that order");
+    if (d.reduce != HPCT_RED_NONE) return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: no reduction is supported after it");
+    if (d.groups > 1) return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: groups are not supported");
+    const int need = 2 + (has[0] ? 1 : 0) + (has[1] ? 2 : 0);
+    if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "transposed conv chain takes %d inputs and 1 output (got %d, %d)", need, d.n_in, d.n_out);
+    const hpct_tensor_desc &I = d.in[0], &Wt = d.in[1];
+    if (I.ndim != 4 || Wt.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "transposed conv operands must be 4-D: in[N,C,H,W], wt[C,K,R,S]");
+    const int64_t Nb = I.shape[0], C = I.shape[1], H = I.shape[2], W = I.shape[3];
+    const int64_t K = Wt.shape[1], R = Wt.shape[2], S = Wt.shape[3];
+    if (Wt.shape[0] != C) return fail(HPCT_ERR_SHAPE_MISMATCH, "wt.shape[0] = %lld does not match the input channels %lld", (long long)Wt.shape[0], (long long)C);
+    if (d.stride_hw[0] < 1 || d.stride_hw[1] < 1 || d.pad_hw[0] < 0 || d.pad_hw[1] < 0)
+        return fail(HPCT_ERR_BAD_DESC, "transposed conv: stride must be >= 1 and padding >= 0");
+    const int32_t dil_h = d.dilation_hw[0] == 0 ? 1 : d.dilation_hw[0], dil_w = d.dilation_hw[1] == 0 ? 1 : d.dilation_hw[1];
+    if (dil_h < 1 || dil_w < 1) return fail(HPCT_ERR_BAD_DESC, "transposed conv: dilation must be >= 1 (or 0 for 1)");
+    if (R != S || d.stride_hw[0] != d.stride_hw[1] || d.pad_hw[0] != d.pad_hw[1] || dil_h != dil_w)
+        return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: filter, stride, padding and dilation must be the same in both directions");
+    const int64_t st = d.stride_hw[0], pad = d.pad_hw[0], re = (R - 1) * dil_h;
+    if (pad > re) return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: padding larger than the (dilated) filter extent minus one");
+    if (st > 8) return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: strides above 8 are not supported");
+    const int64_t Ho = (H - 1) * st - 2 * pad + re + 1, Wo = (W - 1) * st - 2 * pad + re + 1;
+    if (Ho < 1 || Wo < 1) return fail(HPCT_ERR_SHAPE_MISMATCH, "transposed conv: empty output");
+    int s = 2;
+    int s_bias = -1, s_scale = -1, s_shift = -1;
+    if (has[0]) { s_bias = s++; REQUIRE_SHAPE(d.in[s_bias], "bias", K); }
+    if (has[1]) {
+        s_scale = s++; s_shift = s++;
+        REQUIRE_SHAPE(d.in[s_scale], "scale", K);
+        REQUIRE_SHAPE(d.in[s_shift], "shift", K);
+    }
+    REQUIRE_SHAPE(d.out[0], "out[0]", Nb, K, Ho, Wo);
+    for (int i = 0; i < d.n_in; ++i)
+        if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous NCHW / CKRS layouts are supported", i);
+    if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous NCHW layouts are supported");
+    const int64_t Hd = (H - 1) * st + 1, Wd = (W - 1) * st + 1;
+    if (Nb * C * Hd * Wd > kI32Max || Nb * K * Ho * Wo > kI32Max || K * C * R * S > kI32Max)
+        return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: operand larger than 2^31-1 elements");
+    const char* why = "";
+    if (!conv_supported((int32_t)C, (int32_t)Hd, (int32_t)Wd, (int32_t)K, (int32_t)R, (int32_t)S, 1, 1, (int32_t)(re - pad), (int32_t)(re - pad),
+                        dil_h, dil_w, 0, &why))
+        return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: %s", why);
+    ConvParams q{};
+    q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)Hd; q.W = (int32_t)Wd; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
+    q.pad = (int32_t)(re - pad); q.stride = 1; q.dil = dil_h; q.relu = has[3] ? 2 : (has[2] ? 1 : 0); q.pool = 0;
+    if (R == 1 && (Hd * Wd) % 64 == 0) { q.H = (int32_t)(Hd * Wd / 64); q.W = 64; }   // as in plan_conv (1x1: pad is 0 here)
+    q.win = conv_window_geometry(q.W, q.R, q.pool);
+    p.kind = Kind::ConvT;
+    p.u.conv = q;
+    p.convt = ConvTParams{(int32_t)Nb, (int32_t)C, (int32_t)H, (int32_t)W, (int32_t)K, (int32_t)R, (int32_t)st, (int32_t)Hd, (int32_t)Wd};
+    p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = s_bias; p.slot[3] = s_scale; p.slot[4] = s_shift; p.slot[5] = -1;
+    p.shape = conv_shape(q);
+    p.ws_bytes = convt_workspace_bytes(p.convt);
+    return HPCT_OK;
+}
+
 hpct_status plan_attn(const hpct_op_desc& d, hpct_plan& p) {
     static const hpct_epilogue allowed[] = {HPCT_EPI_SCALE_CONST, HPCT_EPI_CAUSAL_MASK};
     bool has[2];
@@ -586,7 +647,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_epi < 0 || d.n_epi > HPCT_MAX_EPI) return fail(HPCT_ERR_BAD_DESC, "n_epi = %d outside 0..%d", d.n_epi, HPCT_MAX_EPI);
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
-    if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONV2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
+    if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONVT2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
     if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_ARGMIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
     if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_ARGMIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
@@ -618,6 +679,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     switch (d.anchor) {
         case HPCT_ANCHOR_GEMM: st = plan_gemm(d, tmp); break;
         case HPCT_ANCHOR_CONV2D_NCHW: st = plan_conv(d, tmp); break;
+        case HPCT_ANCHOR_CONVT2D_NCHW: st = plan_convt(d, tmp); break;
         case HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM: st = plan_attn(d, tmp); break;
         default:
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
@@ -719,6 +781,17 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
         case Kind::MaxPool:
             e = maxpool2_launch(in(0), (float*)out_ptrs[0], plan->pool_planes, plan->pool_h, plan->pool_w, stream);
             break;
+        case Kind::ConvT: {
+            const ConvTParams& t = plan->convt;
+            e = convt_prep_launch(t, in(0), in(1), (float*)workspace, stream);
+            if (e != hipSuccess) break;
+            ConvParams q = plan->u.conv;
+            q.wt = (const float*)workspace;
+            q.in = t.stride > 1 ? (const float*)((const char*)workspace + convt_weights_bytes(t)) : in(0);
+            q.bias = in(2); q.scale = in(3); q.shift = in(4); q.out = (float*)out_ptrs[0];
+            e = conv_launch(q, stream);
+            break;
+        }
         case Kind::DwConv: {
             ConvParams q = plan->u.conv;
             q.in = in(0); q.wt = in(1); q.bias = in(2); q.scale = in(3); q.shift = in(4); q.out = (float*)out_ptrs[0];

@@ -157,6 +157,14 @@ hipError_t conv_launch(const ConvParams& p, hipStream_t stream);
 bool conv1x1_stream_ok(const ConvParams& p);
 LaunchShape conv1x1_shape(const ConvParams& p);
 hipError_t conv1x1_launch(const ConvParams& p, hipStream_t stream);
+// transposed conv: the operands of the equivalent stride-1 conv, prepared in the workspace (k_convt_prep.hip)
+struct ConvTParams {
+    int32_t Nb, C, H, W, K, R, stride;   // in [Nb,C,H,W], wt [C,K,R,R]
+    int32_t Hd, Wd;                      // zero-dilated input: (H-1)*stride + 1, (W-1)*stride + 1
+};
+size_t convt_weights_bytes(const ConvTParams& p);     // offset of the dilated input inside the workspace
+size_t convt_workspace_bytes(const ConvTParams& p);
+hipError_t convt_prep_launch(const ConvTParams& p, const float* in, const float* wt, float* workspace, hipStream_t stream);
 // depthwise (groups = C = K, wt[C,1,R,R]): a memory-bound stencil kernel of its own (k_dwconv.hip)
 bool dwconv_supported(const ConvParams& p, const char** why);
 LaunchShape dwconv_shape(const ConvParams& p);

@@ -21,7 +21,8 @@ HPCT_OK, HPCT_ERR_NULL, HPCT_ERR_BAD_DESC, HPCT_ERR_SHAPE_MISMATCH, HPCT_ERR_ALI
 STATUS_NAMES = ["HPCT_OK", "HPCT_ERR_NULL", "HPCT_ERR_BAD_DESC", "HPCT_ERR_SHAPE_MISMATCH", "HPCT_ERR_ALIGNMENT",
                 "HPCT_ERR_UNSUPPORTED", "HPCT_ERR_WORKSPACE", "HPCT_ERR_HIP"]
 HPCT_F32, HPCT_I32 = 0, 1
-HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW = range(4)
+HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR_CONV2D_NCHW, \
+    HPCT_ANCHOR_CONVT2D_NCHW = range(5)
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
     HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH, HPCT_EPI_CAUSAL_MASK, HPCT_EPI_ADD_TENSOR, HPCT_EPI_MUL_TENSOR, \
     HPCT_EPI_SUB_TENSOR, HPCT_EPI_DIV_TENSOR, HPCT_EPI_SQRT, HPCT_EPI_SIN, HPCT_EPI_COS, HPCT_EPI_EXP, HPCT_EPI_TANH, \
@@ -444,6 +445,24 @@ def conv_block(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True, poo
     """out = maxpool2x2(relu((conv2d_nchw(inp, wt) + bias[k]) * scale[k] + shift[k])); every stage after the conv optional."""
     plan, ins = conv_block_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, pool, dilation, groups)
     plan.launch(ins, [out], stream)
+
+
+def conv_transpose_plan(inp, wt, bias, scale, shift, out, stride=1, pad=0, relu=False, dilation=1):
+    """Transposed conv (inp [N,C,H,W], wt [C,K,R,R], out [N,K,(H-1)*stride - 2*pad + (R-1)*dilation + 1, ...])
+    [+bias] [+per-channel scale/shift] [+relu / "relu6"].  The plan needs a workspace (plan.workspace_bytes)."""
+    assert (scale is None) == (shift is None)
+    act = [] if not relu else [HPCT_EPI_RELU6 if relu == "relu6" else HPCT_EPI_RELU]
+    epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + act
+    ins = [inp, wt] + ([bias] if bias is not None else []) + ([scale, shift] if scale is not None else [])
+    plan = _cached(("convt", _sh(inp), _sh(wt), tuple(epi), stride, pad, dilation), lambda: op_desc(
+        HPCT_ANCHOR_CONVT2D_NCHW, epi, HPCT_RED_NONE, 0, [_sh(t) for t in ins], [_sh(out)],
+        stride_hw=(stride, stride), pad_hw=(pad, pad), dilation_hw=(dilation, dilation)))
+    return plan, ins
+
+
+def conv_transpose(inp, wt, bias, scale, shift, out, workspace, stride=1, pad=0, relu=False, dilation=1, stream=None) -> None:
+    plan, ins = conv_transpose_plan(inp, wt, bias, scale, shift, out, stride, pad, relu, dilation)
+    plan.launch(ins, [out], stream, workspace)
 
 
 def depthwise_conv_plan(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu="relu6", dilation=1):

@@ -632,6 +632,38 @@ def test_depthwise_conv_plans():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
 
 
+def convt_desc(shape=(32, 128, 28, 28), K=64, R=3, stride=2, pad=1, dil=1, act=None, wt_c=None, out=None):
+    Nb, Cc, Hh, Ww = shape
+    Ho = (Hh - 1) * stride - 2 * pad + (R - 1) * dil + 1
+    Wo = (Ww - 1) * stride - 2 * pad + (R - 1) * dil + 1
+    epi = [H.HPCT_EPI_BIAS_COL] + ([act] if act is not None else [])
+    return H.op_desc(H.HPCT_ANCHOR_CONVT2D_NCHW, epi, H.HPCT_RED_NONE, 0,
+                     [shape, (Cc if wt_c is None else wt_c, K, R, R), (K,)], [out or (Nb, K, Ho, Wo)],
+                     stride_hw=(stride, stride), pad_hw=(pad, pad), dilation_hw=(dil, dil))
+
+
+def test_conv_transpose_plans():
+    p = H.Plan(convt_desc(act=H.HPCT_EPI_RELU))
+    # workspace: the flipped filter (rounded to 256 bytes) and the zero-dilated input [32,128,55,55]
+    assert p.workspace_bytes == 64 * 128 * 9 * 4 + 32 * 128 * 55 * 55 * 4
+    assert p.kernel_name.startswith("conv2d_nchw_mfma<3x3")
+    # stride 1 needs only the filter
+    p = H.Plan(convt_desc(shape=(2, 8, 10, 10), K=5, stride=1))
+    assert p.workspace_bytes == (5 * 8 * 9 * 4 + 255) // 256 * 256
+    assert H.Plan(convt_desc(R=5, pad=2)).workspace_bytes > 0
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, convt_desc(wt_c=64))                         # wt is [C,K,R,S]: input channels first
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, convt_desc(out=(32, 64, 56, 56)))            # (28-1)*2 - 2 + 3 = 55
+    expect(H.HPCT_ERR_UNSUPPORTED, convt_desc(R=3, pad=3))
+    d = convt_desc(); d.reduce = H.HPCT_RED_MAXPOOL2_HW
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = convt_desc(); d.groups = 2
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = convt_desc(); d.stride_hw[1] = 1
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = convt_desc(); d.anchor = 5
+    expect(H.HPCT_ERR_BAD_DESC, d)
+
+
 def test_maxpool_alone_plans():
     d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_MAXPOOL2_HW, 0, [(32, 64, 56, 56)], [(32, 64, 28, 28)])
     assert H.Plan(d).kernel_name == "maxpool2_planes<vec4>"

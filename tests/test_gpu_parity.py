@@ -875,6 +875,63 @@ def test_eltwise_views():
     check_eltwise(one, one, "single element")
 
 
+# ---------------------------------------- transposed conv ("Conv-Trans")
+def check_conv_transpose(N, C, H, W, K, R, stride, pad, dil=1, act=False, bias=True, affine=False, seed=0):
+    x = datagen.gen_normal(500 + seed, (N, C, H, W), 0.0, 1.0)
+    w = datagen.gen_normal(501 + seed, (C, K, R, R), 0.0, 1.0 / (R * np.sqrt(C)))
+    b = datagen.gen_normal(502 + seed, (K,), 0.0, 0.5) if bias else None
+    sc = datagen.gen_uniform(503 + seed, (K,), 0.5, 1.5) if affine else None
+    sh = datagen.gen_normal(504 + seed, (K,), 0.0, 0.5) if affine else None
+    want, Dn = ref.conv_transpose2d_nchw(x, w, b, stride, pad, want_norm=True, dil=dil)
+    if affine:
+        want, Dn = ref.scale_shift_ch(want, sc, sh), ref.scale_shift_ch(Dn, np.abs(sc), np.abs(sh))
+    want = ref.relu6(want) if act == "relu6" else (ref.relu(want) if act else want)
+    out = torch.full(want.shape, float("nan"), device="cuda")
+    plan, ins = hpct.conv_transpose_plan(dev(x), dev(w), None if b is None else dev(b), None if sc is None else dev(sc),
+                                         None if sh is None else dev(sh), out, stride, pad, act, dil)
+    assert plan.workspace_bytes > 0
+    ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda")
+    plan.launch(ins, [out], workspace=ws)
+    assert show("conv transpose %s" % plan.kernel_name, compare.contraction(host(out), want, Dn))
+    return host(out), plan, ins, ws
+
+
+def test_conv_transpose_full_size():
+    # a decoder's 2x upsampling layer: 4x4 filter, stride 2, padding 1, [32,128,28,28] -> [32,64,56,56]
+    got, plan, ins, ws = check_conv_transpose(32, 128, 28, 28, 64, 4 - 1, 2, 1, act="relu")   # 3x3: the filter sizes are odd
+    out2 = torch.full(got.shape, float("nan"), device="cuda")
+    plan.launch(ins, [out2], workspace=ws)
+    assert np.array_equal(host(out2).view(np.uint32), got.view(np.uint32))
+    with pytest.raises(hpct.HpctError):
+        plan.launch(ins, [out2])                                    # the workspace is required
+
+
+@pytest.mark.parametrize("N,C,H,W,K,R,stride,pad,dil", [
+    (1, 1, 1, 1, 1, 1, 1, 0, 1), (2, 3, 5, 6, 4, 3, 1, 1, 1), (1, 8, 7, 9, 64, 3, 2, 1, 1), (2, 5, 6, 6, 7, 3, 2, 0, 1),
+    (1, 4, 9, 5, 10, 5, 2, 2, 1), (1, 16, 8, 8, 130, 3, 3, 1, 1), (1, 6, 10, 12, 9, 3, 1, 2, 2), (2, 64, 14, 14, 64, 3, 2, 1, 1),
+    (1, 8, 5, 5, 8, 1, 2, 0, 1), (1, 3, 4, 40, 5, 7, 2, 3, 1), (1, 2, 6, 6, 3, 3, 4, 2, 1)])
+def test_conv_transpose_ragged_shapes(N, C, H, W, K, R, stride, pad, dil):
+    print("conv transpose %s" % ((N, C, H, W, K, R, stride, pad, dil),), flush=True)
+    check_conv_transpose(N, C, H, W, K, R, stride, pad, dil)
+    check_conv_transpose(N, C, H, W, K, R, stride, pad, dil, act="relu6", affine=True, seed=1)
+    check_conv_transpose(N, C, H, W, K, R, stride, pad, dil, act="relu", bias=False, seed=2)
+
+
+def test_conv_transpose_tiles_with_a_2x2_filter_of_ones():
+    # stride = filter size would tile the output; with odd filters: a 1x1 filter of ones at stride 2 puts every input
+    # on the even positions and zeros between them, exactly
+    x = datagen.gen_normal(510, (2, 3, 5, 7), 0.0, 1.0)
+    w = np.zeros((3, 3, 1, 1), np.float32)
+    for c in range(3):
+        w[c, c, 0, 0] = 1.0
+    out = torch.full((2, 3, 9, 13), float("nan"), device="cuda")
+    plan, ins = hpct.conv_transpose_plan(dev(x), dev(w), None, None, None, out, 2, 0)
+    ws = torch.empty(plan.workspace_bytes // 4, device="cuda")
+    plan.launch(ins, [out], workspace=ws)
+    got = host(out)
+    assert np.array_equal(got[:, :, ::2, ::2], x) and np.all(got[:, :, 1::2, :] == 0) and np.all(got[:, :, :, 1::2] == 0)
+
+
 # ---------------------------------------- depthwise conv (MobileNetV2's depthwise layer) and relu6
 def check_depthwise(N, C, H, W, R, stride, pad, dil=1, act="relu6", bias=True, affine=True, seed=0):
     x = datagen.gen_normal(300 + seed, (N, C, H, W), 0.0, 1.0)
