@@ -537,7 +537,7 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
     // A 1x1 filter with stride 1 and no padding acts on pixels independently: the plane is regrouped into rows of
     // 64 pixels, so that a 64-pixel tile stages exactly the pixels it computes instead of the image rows they lie in.
     if (R == 1 && q.stride == 1 && q.pad == 0 && !pool && (H * W) % 64 == 0) { q.H = (int32_t)(H * W / 64); q.W = 64; }
-    q.win = conv_window_geometry(q.W, q.R, q.pool);
+    q.win = conv_window_geometry(q);
     p.kind = Kind::Conv;
     p.u.conv = q;
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = s_bias; p.slot[3] = s_scale; p.slot[4] = s_shift; p.slot[5] = -1;
@@ -595,7 +595,7 @@ hpct_status plan_convt(const hpct_op_desc& d, hpct_plan& p) {
     q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)Hd; q.W = (int32_t)Wd; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
     q.pad = (int32_t)(re - pad); q.stride = 1; q.dil = dil_h; q.relu = has[3] ? 2 : (has[2] ? 1 : 0); q.pool = 0;
     if (R == 1 && (Hd * Wd) % 64 == 0) { q.H = (int32_t)(Hd * Wd / 64); q.W = 64; }   // as in plan_conv (1x1: pad is 0 here)
-    q.win = conv_window_geometry(q.W, q.R, q.pool);
+    q.win = conv_window_geometry(q);
     p.kind = Kind::ConvT;
     p.u.conv = q;
     p.convt = ConvTParams{(int32_t)Nb, (int32_t)C, (int32_t)H, (int32_t)W, (int32_t)K, (int32_t)R, (int32_t)st, (int32_t)Hd, (int32_t)Wd};

@@ -577,8 +577,21 @@ size_t lds_any(const ConvParams& p) {
 // Window geometry: always with pooling; without it for filters larger than 1x1 on images wider
 // than 64, where staging whole input rows costs LDS (and occupancy) for nothing: 224-wide 64 -> 64
 // channels 88 -> 116 TFLOP/s, 112-wide 115 -> 122; at 56 the two geometries take the same time.
+// Below that width the rows stay unless only the window geometry can be staged by the pipelined
+// variant (odd widths of 47 .. 63 have too many scalar slots per row tile: 55-wide 128 -> 64
+// channels 53 -> 91 TFLOP/s, 63-wide 52 -> 101; at 45, where both can, rows are faster, 102 vs 75).
 // (A 1x1 filter keeps rows: its 16-channel chunks need the row layout.)
-int32_t conv_window_geometry(int32_t W, int32_t R, int32_t pool) { return (pool || (W > 64 && R > 1)) ? 1 : 0; }
+int32_t conv_window_geometry(const ConvParams& p0) {
+    if (p0.pool) return 1;
+    if (p0.R == 1) return 0;
+    if (p0.W > 64) return 1;
+    ConvParams p = p0;
+    ConvGeom g;
+    p.win = 0;
+    if (pick_mode(p, &g) != 0) return 0;
+    p.win = 1;
+    return pick_mode(p, &g) != 0 ? 1 : 0;
+}
 
 bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h, int32_t stride_w,
                     int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w, int32_t pool, const char** why) {
@@ -590,7 +603,7 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
     if (pad_h != pad_w) { *why = "padding must be the same in both directions"; return false; }
     if (pad_h > (R - 1) * dil_h) { *why = "padding larger than the (dilated) filter extent minus one"; return false; }
     ConvParams p{};
-    p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.dil = dil_h; p.pool = pool; p.win = conv_window_geometry(W, R, pool);
+    p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.dil = dil_h; p.pool = pool; p.win = conv_window_geometry(p);
     if (lds_any(p) > 160 * 1024) { *why = "the input of one 64-pixel tile does not fit in LDS (image too wide)"; return false; }
     return true;
 }

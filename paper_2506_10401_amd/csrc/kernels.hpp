@@ -146,7 +146,7 @@ struct ConvParams {
     int32_t dil;                              // dilation, >= 1
     int32_t win;                              // 8 x 8 window tiles (set from conv_window_geometry)
 };
-int32_t conv_window_geometry(int32_t W, int32_t R, int32_t pool);
+int32_t conv_window_geometry(const ConvParams& p);   // from C, H, W, K, R, pad, stride, dil, pool
 bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32_t S, int32_t stride_h,
                     int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w, int32_t pool,
                     const char** why);
