@@ -34,6 +34,10 @@
  *         [+DROPOUT_HASH] [+SOFTMAX_LAST] (one        (W row-major, strides (N,1),
  *         kernel for N <= 256, GEMM then an           or stored transposed as an
  *         in-place row softmax beyond)                [N,K] array: strides (1,K))
+ *   GEMM [+BIAS_COL] [+SCALE_CONST] [+RELU]           X[B,M,K], W[B,K,N] (each      [B,M,N]
+ *         [+SOFTMAX_LAST]: a batch of products,       W[b] row-major or transposed,
+ *         Y[b] = X[b] W[b] (B <= 65535), or one       batch stride K N) or W[K,N],
+ *         W for all of X's rows                       bias[N]
  *   GEMM [+BIAS_COL] [+SCALE_CONST] [+RELU]           X[M,K], W[K,N], bias[N]       [M]
  *         [+DROPOUT_HASH] MEAN_LAST [then reduce2 =                                  (needs the
  *         SOFTMAX_LAST over the M means]                                             workspace)

@@ -142,28 +142,44 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     const int need = 2 + (has_bias ? 1 : 0);
     if (d.n_in != need || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "GEMM chain takes %d inputs and 1 output (got %d, %d)", need, d.n_in, d.n_out);
     const hpct_tensor_desc &X = d.in[0], &W = d.in[1];
-    if (X.ndim != 2 || W.ndim != 2) return fail(HPCT_ERR_SHAPE_MISMATCH, "GEMM operands must be 2-D: X[M,K], W[K,N]");
-    const int64_t M = X.shape[0], K = X.shape[1], N = W.shape[1];
-    if (W.shape[0] != K) return fail(HPCT_ERR_SHAPE_MISMATCH, "W.shape[0] = %lld does not match X.shape[1] = %lld", (long long)W.shape[0], (long long)K);
+    // X[M,K] W[K,N], or a batch X[B,M,K] with W[B,K,N] (one product per b) or W[K,N] (the same W for all:
+    // that is one product of the [B*M,K] matrix)
+    if ((X.ndim != 2 && X.ndim != 3) || (W.ndim != 2 && W.ndim != 3) || W.ndim > X.ndim)
+        return fail(HPCT_ERR_SHAPE_MISMATCH, "GEMM operands must be X[M,K], W[K,N] or X[B,M,K] with W[B,K,N] or W[K,N]");
+    const int xb = X.ndim - 2, wb = W.ndim - 2;
+    const int64_t B = xb ? X.shape[0] : 1;
+    if (wb && W.shape[0] != B) return fail(HPCT_ERR_SHAPE_MISMATCH, "W.shape[0] = %lld does not match the batch %lld", (long long)W.shape[0], (long long)B);
+    const bool fold = xb && !wb;                       // shared W: rows of all batches form one tall matrix
+    const int64_t batch = (xb && wb) ? B : 1;
+    const int64_t M = fold ? B * X.shape[1] : X.shape[xb], K = X.shape[xb + 1], N = W.shape[wb + 1];
+    if (W.shape[wb] != K) return fail(HPCT_ERR_SHAPE_MISMATCH, "W's K extent %lld does not match X's %lld", (long long)W.shape[wb], (long long)K);
     if (has_bias) REQUIRE_SHAPE(d.in[2], "bias", N);
-    if (mean) REQUIRE_SHAPE(d.out[0], "out[0]", M);
-    else REQUIRE_SHAPE(d.out[0], "out[0]", M, N);
+    if (batch > 1 && (mean || has_dropout)) return fail(HPCT_ERR_UNSUPPORTED, "batched GEMM: MEAN_LAST and DROPOUT_HASH are not supported");
+    if (xb) {
+        if (mean) REQUIRE_SHAPE(d.out[0], "out[0]", B, X.shape[1]);
+        else REQUIRE_SHAPE(d.out[0], "out[0]", B, X.shape[1], N);
+    } else {
+        if (mean) REQUIRE_SHAPE(d.out[0], "out[0]", M);
+        else REQUIRE_SHAPE(d.out[0], "out[0]", M, N);
+    }
     // W: row-major [K,N], or the transposed storage of a linear layer's weight ([N,K] row-major seen as [K,N]
-    // with strides (1, K))
-    const bool wt = !contiguous(W) && W.stride[0] == 1 && W.stride[1] == K;
+    // with strides (1, K)); with a batch the matrices follow each other (stride K*N)
+    const bool wt = !contiguous(W) && W.stride[wb] == 1 && W.stride[wb + 1] == K && (!wb || W.stride[0] == K * N || B == 1);
     for (int i = 0; i < d.n_in; ++i)
         if (!contiguous(d.in[i]) && !(i == 1 && wt))
             return fail(HPCT_ERR_UNSUPPORTED, i == 1 ? "in[1]: W must be row-major [K,N] (strides N, 1) or its transpose (strides 1, K)"
                                                      : "in[%d]: only contiguous row-major layouts are supported", i);
     if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous row-major layouts are supported");
-    if (M > kI32Max || K > kI32Max || N > kI32Max || M * N > kI32Max || M * K > kI32Max || K * N > kI32Max)
-        return fail(HPCT_ERR_UNSUPPORTED, "GEMM: operand larger than 2^31-1 elements");
+    if (M > kI32Max || K > kI32Max || N > kI32Max || M * N > kI32Max || M * K > kI32Max || K * N > kI32Max ||
+        batch * M * N > kI32Max || batch * M * K > kI32Max || batch * K * N > kI32Max || batch > 65535)
+        return fail(HPCT_ERR_UNSUPPORTED, "GEMM: operand larger than 2^31-1 elements (or more than 65535 batches)");
     const bool sm = d.reduce == HPCT_RED_SOFTMAX_LAST;
     GemmParams g{};
     g.M = (int32_t)M; g.K = (int32_t)K; g.N = (int32_t)N;
     g.relu = has_relu ? 1 : 0; g.softmax = sm ? 1 : 0;
     g.scale = has_scale ? d.scale : 1.0f;
     g.wt = wt ? 1 : 0;
+    g.batch = (int32_t)batch; g.sX = M * K; g.sW = K * N; g.sY = M * N;
     if (has_dropout) {
         if (!(d.dropout_p >= 0.f && d.dropout_p < 1.f)) return fail(HPCT_ERR_BAD_DESC, "DROPOUT_HASH: dropout_p must satisfy 0 <= p < 1");
         g.dropout = 1;
@@ -176,8 +192,8 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     p.kind = Kind::Gemm;
     p.u.gemm = g;
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has_bias ? 2 : -1; p.slot[3] = -1;
-    p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.wt);
-    p.ws_bytes = gemm_workspace_bytes((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0);
+    p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.wt, g.batch);
+    p.ws_bytes = gemm_workspace_bytes((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.batch);
     return HPCT_OK;
 }
 

@@ -40,10 +40,10 @@ constexpr int KG = 4;   // k-groups of waves
 // l16 + 32, l16 + 48 of its wave's 64 instead of four neighbours.
 template <int BN, bool VEC, bool EXT, bool BT>
 __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
-    const float* __restrict__ X = p.X;
-    const float* __restrict__ W = p.W;
+    const float* __restrict__ X = p.X + blockIdx.z * p.sX;   // blockIdx.z: the matrix of a batch
+    const float* __restrict__ W = p.W + blockIdx.z * p.sW;
     const float* __restrict__ bias = p.bias;
-    float* __restrict__ Y = p.Y;
+    float* __restrict__ Y = p.Y + blockIdx.z * p.sY;
     const int M = p.M, K = p.K, N = p.N, relu = p.relu, softmax = p.softmax;
     constexpr int NG = BN / 64;  // column groups of waves
     __shared__ __attribute__((aligned(16))) float part[(KG - 1) * NG * 16 * 64];
@@ -302,7 +302,7 @@ int pick_bn(int32_t N) { return N <= 64 ? 64 : (N <= 128 ? 128 : 256); }
 
 template <int BN>
 hipError_t launch_bn(const GemmParams& p, hipStream_t stream) {
-    dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), block(BN * 4);
+    dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN), (unsigned)p.batch), block(BN * 4);
     const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0);
     const bool ext = p.dropout || p.mean;
     if (p.wt) {
@@ -324,29 +324,29 @@ hipError_t launch_bn(const GemmParams& p, hipStream_t stream) {
 // The tiled kernel takes over once its tiles give every XCD work - 32 tiles of 128 x 128, or fewer
 // if K is long enough to be split into slices that make up for it; below that the 16-row kernel's
 // many small work-groups finish sooner.  The fused row softmax exists only in the 16-row kernel.
-bool gemm_use_tile(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean) {
+bool gemm_use_tile(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t batch) {
     if (softmax && N <= kGemmSoftmaxMaxN) return false;   // fused: the row fits one work-group
-    if ((int64_t)((M + 127) / 128) * ((N + 127) / 128) >= 32) return true;
+    if ((int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch >= 32) return true;
     const int64_t tiles64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64);
-    return tiles64 * gemm_ksplit(M, K, N, mean) >= 128 && gemm_ksplit(M, K, N, mean) > 1;
+    return tiles64 * gemm_ksplit(M, K, N, mean, batch) >= 128 && gemm_ksplit(M, K, N, mean, batch) > 1;
 }
 
 int32_t gemm_col_tiles(int32_t M, int32_t K, int32_t N) {
     return gemm_use_tile(M, K, N, 0, 1) ? gemm_tile_col_tiles(M, N) : (N + pick_bn(N) - 1) / pick_bn(N);
 }
 
-size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean) {
+size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t batch) {
     if (mean) return (size_t)gemm_col_tiles(M, K, N) * (size_t)M * 4;
-    if (!gemm_use_tile(M, K, N, softmax, 0)) return 0;
-    const int32_t s = gemm_ksplit(M, K, N, 0);
+    if (!gemm_use_tile(M, K, N, softmax, 0, batch)) return 0;
+    const int32_t s = gemm_ksplit(M, K, N, 0, batch);
     return s > 1 ? (size_t)s * (size_t)M * (size_t)N * 4 : 0;
 }
 
-LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt) {
-    if (gemm_use_tile(M, K, N, softmax, mean)) return gemm_tile_shape(M, N, gemm_ksplit(M, K, N, mean), wt);
+LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt, int32_t batch) {
+    if (gemm_use_tile(M, K, N, softmax, mean, batch)) return gemm_tile_shape(M, N, gemm_ksplit(M, K, N, mean, batch), wt, batch);
     const int bn = pick_bn(N);
     LaunchShape s{};
-    s.grid[0] = (uint32_t)((M + BM - 1) / BM); s.grid[1] = (uint32_t)((N + bn - 1) / bn); s.grid[2] = 1;
+    s.grid[0] = (uint32_t)((M + BM - 1) / BM); s.grid[1] = (uint32_t)((N + bn - 1) / bn); s.grid[2] = (uint32_t)batch;
     s.block[0] = (uint32_t)(bn * 4); s.block[1] = s.block[2] = 1;
     s.lds_bytes = (uint32_t)(((KG - 1) * (bn / 64) * 16 * 64 + (bn / 64) * BM) * 4);
     if (wt) s.kernel = bn == 64 ? "gemm_rows16<64,wt>" : (bn == 128 ? "gemm_rows16<128,wt>" : "gemm_rows16<256,wt>");
@@ -362,8 +362,9 @@ hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
     if (split_softmax) p.softmax = 0;
     hipError_t e;
     p.ksplit = 1;
-    if (gemm_use_tile(p.M, p.K, p.N, p0.softmax, p.mean)) {
-        p.ksplit = gemm_ksplit(p.M, p.K, p.N, p.mean);
+    if (p.batch < 1) p.batch = 1;
+    if (gemm_use_tile(p.M, p.K, p.N, p0.softmax, p.mean, p.batch)) {
+        p.ksplit = gemm_ksplit(p.M, p.K, p.N, p.mean, p.batch);
         e = gemm_tile_launch(p, stream);
     }
     else switch (pick_bn(p.N)) {
@@ -371,7 +372,7 @@ hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
         case 128: e = launch_bn<128>(p, stream); break;
         default: e = launch_bn<256>(p, stream);
     }
-    if (e == hipSuccess && split_softmax) return softmax_launch(SoftmaxParams{p.Y, p.Y, p.M, p.N}, stream);
+    if (e == hipSuccess && split_softmax) return softmax_launch(SoftmaxParams{p.Y, p.Y, (int64_t)p.M * p.batch, p.N}, stream);   // sY = M N: the batch is one tall matrix
     if (e != hipSuccess || !p.mean) return e;
     return rows_finish_launch(p.ws, p.Y, p.M, gemm_col_tiles(p.M, p.K, p.N), p.N, p.softmax2, stream);
 }

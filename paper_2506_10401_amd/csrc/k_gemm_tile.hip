@@ -48,8 +48,13 @@ constexpr int kXcds = 8;
 template <int T, bool VEC, bool BT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void gemm_tile(GemmParams p, int tiles_n, int items) {
     constexpr int TM = T, TN = T, WB = T / 64, LDB = T + 8;
-    __shared__ __attribute__((aligned(16))) float As[2][TM * LDA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BT ? TN * LDA : BK * LDB];
+    // one LDS block: the two stages of the A and B tiles, and after the chunk loop the waves' output strips
+    constexpr int kAs = TM * LDA, kBs = BT ? TN * LDA : BK * LDB;
+    constexpr int QW = TN / 2, EXP = QW + 8;   // a wave's quadrant is QW columns wide; pitch of its output strip
+    constexpr int kSmem = 2 * kAs + 2 * kBs > 4 * 32 * EXP ? 2 * kAs + 2 * kBs : 4 * 32 * EXP;
+    __shared__ __attribute__((aligned(16))) float smem[kSmem];
+    float (*As)[kAs] = reinterpret_cast<float (*)[kAs]>(smem);
+    float (*Bs)[kBs] = reinterpret_cast<float (*)[kBs]>(smem + 2 * kAs);
     __shared__ float rs[2][TM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -69,10 +74,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
     const int tiles = items / p.ksplit;
     const int ks = item / tiles;          // K slice (0 without split-K); a slice's tiles are neighbours
     item -= ks * tiles;
-    const int tiles_m = tiles / tiles_n;
+    const int tiles_m = tiles / tiles_n;  // tile rows of all the matrices of a batch, one after the other
     const int run = item / (8 * tiles_n), in_run = item - run * 8 * tiles_n;
     const int rows = tiles_m - run * 8 < 8 ? tiles_m - run * 8 : 8;
-    const int tm = run * 8 + in_run % rows, tn = in_run / rows;
+    const int tmv = run * 8 + in_run % rows, tn = in_run / rows;
+    const int tiles_m1 = (M + TM - 1) / TM;          // tile rows of one matrix
+    const int bz = tmv / tiles_m1, tm = tmv - bz * tiles_m1;
     const int m0 = tm * TM, n0 = tn * TN;
     // this work-group's slice of K (split-K: the slices' partial products go to the workspace and
     // split_k_finish adds them in slice order and applies the epilogue)
@@ -84,8 +91,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
     constexpr int BSTEP = kThreads / (TN / 4);   // B rows covered by one pass of the work-group
     const int ar = tid >> 2, ak = (tid & 3) * 4;
     const int bk = tid / (TN / 4), bn = (tid % (TN / 4)) * 4;
-    const float* __restrict__ X = p.X;
-    const float* __restrict__ W = p.W;
+    const float* __restrict__ X = p.X + bz * p.sX;
+    const float* __restrict__ W = p.W + bz * p.sW;
+    float* __restrict__ Yb = p.Y + bz * p.sY;
 
     float4v ra[WB], rb[WB];
     // VEC: raw buffer loads.  A lane's byte offset inside its tile's rows is worked out once; a lane outside
@@ -243,6 +251,53 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
 
     // ---- epilogue in registers
     const float* __restrict__ bias = p.bias;
+    if constexpr (VEC) {
+        if (!p.mean && (N & 3) == 0) {  // uniform over the grid (a transposed W is read as vectors whatever N is)
+            // An accumulator holds four consecutive rows of one column, so storing it directly writes 128-byte
+            // pieces with 32-bit stores.  Instead each wave passes 32 rows of its quadrant at a time through a
+            // strip of LDS of its own (the tiles' stages are free now) and writes them as 128-bit vectors along
+            // the rows: four times fewer store instructions, which is what bounds products with a short K.
+            // Pitch QW + 8: the two half-waves' rows (4 apart) fall on opposite halves of the 64 banks.
+            constexpr int LPR = QW / 4, RPI = 64 / LPR;   // lanes per strip row, rows per store instruction
+            __syncthreads();   // every wave has read the last chunk's stage
+            float* ex = smem + wave * (32 * EXP);
+            const int colw = n0 + wn * QW;
+            const int rr = lane / LPR, c4 = (lane % LPR) * 4;
+            float bv[WB];
+#pragma unroll
+            for (int j = 0; j < WB; ++j) bv[j] = (bias && colw + j * 32 + l32 < N) ? bias[colw + j * 32 + l32] : 0.f;
+#pragma unroll
+            for (int i = 0; i < WB; ++i) {
+                const int rowq = m0 + wm * (TM / 2) + i * 32;
+#pragma unroll
+                for (int j = 0; j < WB; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int lr = 8 * (r >> 2) + 4 * h + (r & 3);
+                        float v = (acc[i][j][r] + bv[j]) * p.scale;
+                        if (p.relu) v = fmaxf(v, 0.f);
+                        if (p.dropout) {
+                            const uint64_t off = (uint64_t)(rowq + lr) * (uint64_t)N + (uint64_t)(colw + j * 32 + l32);
+                            v = dropout_u(off + p.seed) < p.drop_t ? 0.f : v * p.keep_scale;
+                        }
+                        ex[lr * EXP + j * 32 + l32] = v;
+                    }
+                // LDS operations of one wave execute in order; the fences only keep the compiler from moving them
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < 32 / RPI; ++it) {
+                    const int lr = it * RPI + rr;
+                    const float4v v = *reinterpret_cast<const float4v*>(&ex[lr * EXP + c4]);
+                    if (rowq + lr < M && colw + c4 < N)   // N % 4 == 0: a vector is inside or outside as a whole
+                        *reinterpret_cast<float4v*>(&Yb[(int64_t)(rowq + lr) * N + colw + c4]) = v;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+            return;
+        }
+    }
     float rsum[WB][16];
 #pragma unroll
     for (int i = 0; i < WB; ++i)
@@ -267,7 +322,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
                 if (p.mean) {
                     rsum[i][r] += cok ? v : 0.f;
                 } else if (cok && row < M) {
-                    p.Y[(int64_t)row * N + col] = v;
+                    Yb[(int64_t)row * N + col] = v;
                 }
             }
         }
@@ -377,8 +432,8 @@ __global__ __launch_bounds__(kFinThreads) void vector_softmax(float* __restrict_
 
 // K slices for outputs whose 64 x 64 tiles alone cannot fill the chip: enough slices for about two
 // work-groups per CU, each at least 256 deep, at most 8.  Not with the fused row sums.
-int32_t gemm_ksplit(int32_t M, int32_t K, int32_t N, int32_t mean) {
-    if (mean) return 1;
+int32_t gemm_ksplit(int32_t M, int32_t K, int32_t N, int32_t mean, int32_t batch) {
+    if (mean || batch > 1) return 1;
     const int64_t tiles64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64);
     if (tiles64 >= 512) return 1;
     int64_t s = (512 + tiles64 - 1) / tiles64;
@@ -390,28 +445,29 @@ int32_t gemm_ksplit(int32_t M, int32_t K, int32_t N, int32_t mean) {
 // 128 x 128 tiles when there are at least two per CU and they spread evenly over the 256 CUs
 // (the busiest CU within 15 % of the average); otherwise 64 x 64 tiles, four times as many.
 // Measured at K = 1024: 2048^2 85 -> 96 TFLOP/s, 2560^2 84 -> 92, 1536^2 47 -> 66 with the small tiles.
-int gemm_tile_edge(int32_t M, int32_t N) {
-    const int64_t tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+int gemm_tile_edge(int32_t M, int32_t N, int32_t batch = 1) {
+    const int64_t tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
     const int64_t per_cu = (tiles + 255) / 256;
     return (tiles >= 512 && tiles * 100 >= per_cu * 256 * 85) ? 128 : 64;
 }
 
-LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit, int32_t wt) {
-    const int t = gemm_tile_edge(M, N);
+LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit, int32_t wt, int32_t batch) {
+    const int t = gemm_tile_edge(M, N, batch);
     LaunchShape s{};
-    s.grid[0] = (uint32_t)(((M + t - 1) / t) * ((N + t - 1) / t) * ksplit); s.grid[1] = s.grid[2] = 1;
+    s.grid[0] = (uint32_t)(((M + t - 1) / t) * ((N + t - 1) / t) * ksplit * batch); s.grid[1] = s.grid[2] = 1;
     s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = (uint32_t)((2 * t * LDA + 2 * (wt ? t * LDA : BK * (t + 8)) + 2 * t) * 4);
+    const int stages = 2 * t * LDA + 2 * (wt ? t * LDA : BK * (t + 8)), strips = 4 * 32 * (t / 2 + 8);
+    s.lds_bytes = (uint32_t)(((stages > strips ? stages : strips) + 2 * t) * 4);
     if (wt) s.kernel = t == 128 ? "gemm_tile128<wt>" : (ksplit > 1 ? "gemm_tile64<wt,split-k>" : "gemm_tile64<wt>");
     else s.kernel = t == 128 ? "gemm_tile128" : (ksplit > 1 ? "gemm_tile64<split-k>" : "gemm_tile64");
     return s;
 }
 
-int32_t gemm_tile_col_tiles(int32_t M, int32_t N) { const int t = gemm_tile_edge(M, N); return (N + t - 1) / t; }
+int32_t gemm_tile_col_tiles(int32_t M, int32_t N, int32_t batch) { const int t = gemm_tile_edge(M, N, batch); return (N + t - 1) / t; }
 
 template <int T>
 hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
-    const int tiles_m = (p.M + T - 1) / T, tiles_n = (p.N + T - 1) / T;
+    const int tiles_m = (p.M + T - 1) / T * p.batch, tiles_n = (p.N + T - 1) / T;
     const int items = tiles_m * tiles_n * p.ksplit;
     // (the vector instances address a tile's rows with 31-bit byte offsets)
     const bool fits = p.K <= (1 << 21) && p.N <= (1 << 24);
@@ -427,7 +483,7 @@ hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
 }
 
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream) {
-    hipError_t e = gemm_tile_edge(p.M, p.N) == 128 ? launch_tile<128>(p, stream) : launch_tile<64>(p, stream);
+    hipError_t e = gemm_tile_edge(p.M, p.N, p.batch) == 128 ? launch_tile<128>(p, stream) : launch_tile<64>(p, stream);
     if (e != hipSuccess || p.ksplit <= 1) return e;
     const bool vec = p.N % 4 == 0;
     const int64_t work = (int64_t)p.M * p.N / (vec ? 4 : 1);

@@ -121,17 +121,19 @@ struct GemmParams {
     int32_t ksplit;       // K slices of the tiled kernel, >= 1 (set by the plan from gemm_ksplit)
     float scale;          // (X W + bias) * scale before ReLU; 1 when the chain has no SCALE_CONST
     int32_t wt;           // W is stored transposed: element (k, n) at n * K + k (an [N,K] row-major array)
+    int32_t batch;        // >= 1 independent products; matrix b starts at X + b sX, W + b sW, Y + b sY
+    int64_t sX, sW, sY;   // element strides between the matrices of a batch (sW = 0: one W for all)
 };
 constexpr int kGemmSoftmaxMaxN = 256;
-bool gemm_use_tile(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean);
-int32_t gemm_ksplit(int32_t M, int32_t K, int32_t N, int32_t mean);
-size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean);
+bool gemm_use_tile(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t batch = 1);
+int32_t gemm_ksplit(int32_t M, int32_t K, int32_t N, int32_t mean, int32_t batch = 1);
+size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t batch = 1);
 int32_t gemm_col_tiles(int32_t M, int32_t K, int32_t N);
-LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt);
+LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt, int32_t batch = 1);
 hipError_t gemm_launch(const GemmParams& p, hipStream_t stream);
 // the tiled kernel (128 x 128 or 64 x 64 tiles) and the finishing kernels (k_gemm_tile.hip)
-LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit, int32_t wt);
-int32_t gemm_tile_col_tiles(int32_t M, int32_t N);
+LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit, int32_t wt, int32_t batch = 1);
+int32_t gemm_tile_col_tiles(int32_t M, int32_t N, int32_t batch = 1);
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream);
 hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream);
 

@@ -239,16 +239,15 @@ def _sh(t) -> Tuple[int, ...]:
 # Each chain has a *_plan function (descriptor -> cached Plan plus the operand
 # list in descriptor order) and a convenience function that launches it.
 def gemm_bias_relu_softmax_plan(X, W, bias, out, relu=True, softmax=True, scale=None):
-    """W: [K,N] row-major, or the .t() view of an [N,K] row-major tensor (a linear layer's weight).
-    `scale`: constant multiplied in after the bias (the Gemm-Scale operator), None = no such step."""
-    M, K = _sh(X)
-    N = _sh(W)[1]
+    """X [M,K] or a batch [B,M,K]; W [K,N] row-major, the .t() view of an [N,K] row-major tensor (a linear
+    layer's weight), or one such matrix per batch [B,K,N].  `scale`: constant multiplied in after the bias (the
+    Gemm-Scale operator), None = no such step."""
     wst = tuple(int(v) for v in W.stride())
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_CONST] if scale is not None else []) + \
         ([HPCT_EPI_RELU] if relu else [])
     ins = [X, W] + ([bias] if bias is not None else [])
     descs = [_sh(X), tensor_desc(_sh(W), wst)] + ([_sh(bias)] if bias is not None else [])
-    plan = _cached(("gemm", M, K, N, wst, tuple(epi), softmax, scale), lambda: op_desc(
+    plan = _cached(("gemm", _sh(X), _sh(W), wst, tuple(epi), softmax, scale), lambda: op_desc(
         HPCT_ANCHOR_GEMM, epi, HPCT_RED_SOFTMAX_LAST if softmax else HPCT_RED_NONE, 0, descs, [_sh(out)],
         scale=1.0 if scale is None else scale))
     return plan, ins

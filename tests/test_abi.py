@@ -534,6 +534,29 @@ def test_gemm_transposed_weight_and_scale_plans():
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_BIAS_COL)))
 
 
+def test_batched_gemm_plans():
+    def g(xs, ws, os_, epi=(H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU), red=H.HPCT_RED_NONE, wstride=None):
+        return H.op_desc(H.HPCT_ANCHOR_GEMM, list(epi), red, 0, [xs, H.tensor_desc(ws, wstride), (ws[-1],)], [os_])
+    # 16 products of 256 x 128 x 256: tiles of all the matrices fill one grid
+    p = H.Plan(g((16, 256, 128), (16, 128, 256), (16, 256, 256)))
+    assert p.kernel_name == "gemm_tile64" and p.launch_shape()[0] == (16 * 4 * 4, 1, 1) and p.workspace_bytes == 0
+    # small matrices: the 16-row kernel with the batch in grid.z
+    p = H.Plan(g((3, 64, 256), (3, 256, 256), (3, 64, 256), red=H.HPCT_RED_SOFTMAX_LAST))
+    assert p.kernel_name == "gemm_rows16<256>" and p.launch_shape()[0] == (4, 1, 3)
+    # per-batch transposed W
+    p = H.Plan(g((16, 256, 128), (16, 128, 256), (16, 256, 256), wstride=(128 * 256, 1, 128)))
+    assert p.kernel_name == "gemm_tile64<wt>"
+    # one W for all: a single tall product
+    p = H.Plan(g((16, 256, 128), (128, 256), (16, 256, 256)))
+    assert p.kernel_name == "gemm_tile64" and p.launch_shape()[0] == (64 * 4, 1, 1)
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, g((16, 256, 128), (15, 128, 256), (16, 256, 256)))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, g((16, 256, 128), (16, 128, 256), (16 * 256, 256)))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, g((256, 128), (16, 128, 256), (16, 256, 256)))
+    expect(H.HPCT_ERR_UNSUPPORTED, g((16, 256, 128), (16, 128, 256), (16, 256), red=H.HPCT_RED_MEAN_LAST))
+    expect(H.HPCT_ERR_UNSUPPORTED, g((16, 256, 128), (16, 128, 256), (16, 256, 256),
+                                     epi=(H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_DROPOUT_HASH)))
+
+
 def eltwise_desc(shape, sa, sb, add=True, relu=False, out_shape=None):
     epi = [H.HPCT_EPI_ADD_TENSOR if add else H.HPCT_EPI_MUL_TENSOR] + ([H.HPCT_EPI_RELU] if relu else [])
     return H.op_desc(H.HPCT_ANCHOR_NONE, epi, H.HPCT_RED_NONE, 0, [H.tensor_desc(shape, sa), H.tensor_desc(shape, sb)],

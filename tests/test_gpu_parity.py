@@ -187,6 +187,36 @@ def test_gemm_scale(M, K, N, scale):
     assert np.array_equal(one.view(np.uint32), none.view(np.uint32))
 
 
+@pytest.mark.parametrize("B,M,K,N", [(3, 64, 256, 256), (2, 17, 5, 10), (5, 70, 100, 63), (4, 600, 64, 520), (16, 256, 128, 256),
+                                     (2, 1100, 36, 1030), (3, 33, 300, 300), (1, 40, 64, 128)])
+def test_batched_gemm(B, M, K, N):
+    print("batched gemm B=%d M=%d K=%d N=%d" % (B, M, K, N), flush=True)
+    X = datagen.gen_normal(600, (B, M, K), 0.0, 1.0)
+    W = datagen.gen_normal(601, (B, K, N), 0.0, 1.0 / np.sqrt(K))
+    b = datagen.gen_normal(602, (N,), 0.0, 0.5)
+    Z = np.empty((B, M, N)); Dn = np.empty((B, M, N))
+    for i in range(B):
+        Z[i], Dn[i] = ref.gemm_bias(X[i], W[i], b, want_norm=True)
+    for wt in (False, True):
+        Wd = dev(np.ascontiguousarray(W.transpose(0, 2, 1))).transpose(1, 2) if wt else dev(W)
+        out = torch.full((B, M, N), float("nan"), device="cuda")
+        plan, ins = hpct.gemm_bias_relu_softmax_plan(dev(X), Wd, dev(b), out, relu=True, softmax=False, scale=0.5)
+        assert plan.workspace_bytes == 0
+        plan.launch(ins, [out])
+        assert show("batched %s" % plan.kernel_name, compare.contraction(host(out), ref.relu(ref.scale_const(Z, 0.5)), Dn * 0.5))
+    # with the row softmax behind it (fused up to 256 columns, a second kernel beyond)
+    out = torch.full((B, M, N), float("nan"), device="cuda")
+    hpct.gemm_bias_relu_softmax(dev(X), dev(W), dev(b), out)
+    assert show("batched softmax", compare.pointwise(host(out), ref.softmax_rows(ref.relu(Z).reshape(B * M, N)).reshape(B, M, N)))
+    # one W for the whole batch: the [B*M, K] product
+    out = torch.full((B, M, N), float("nan"), device="cuda")
+    plan, ins = hpct.gemm_bias_relu_softmax_plan(dev(X), dev(W[0]), dev(b), out, relu=False, softmax=False)
+    ws = torch.empty(plan.workspace_bytes // 4, device="cuda") if plan.workspace_bytes else None
+    plan.launch(ins, [out], workspace=ws)
+    Zs, Ds = ref.gemm_bias(X.reshape(B * M, K), W[0], b, want_norm=True)
+    assert show("shared W", compare.contraction(host(out).reshape(B * M, N), Zs, Ds))
+
+
 def test_gemm_identity_weight_is_exact():
     X = datagen.gen_uniform(5, (48, 64), -1, 1)
     out = torch.empty(48, 64, device="cuda")
