@@ -9,6 +9,11 @@
 // registers, and a thread produces four neighbouring outputs of a row per step from
 // whole 128-bit LDS reads and stores them as one 128-bit vector.  Planes too small to
 // occupy a work-group (14 x 14, 7 x 7) are packed several to a work-group.
+//
+// The commonest cases - 3 x 3, stride 1 or 2, pad 1, output rows of a multiple of 4 columns that
+// fill most of a 16-lane row - do not go through LDS at all (dwconv3x3_rows): a lane owns four
+// output columns of a few rows, the input rows under them are 128-bit vectors in registers and
+// the columns it lacks come from the neighbouring lanes by DPP row shifts.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -141,6 +146,117 @@ __global__ __launch_bounds__(kDwThreads) void dwconv_planes(const float* __restr
     }
 }
 
+// ---- 3 x 3, stride 1 or 2, pad 1, without LDS
+// A wave owns a segment of 56 output columns of 4 * CH output rows of one plane.  Each of its four 16-lane rows
+// takes CH of those rows; inside it lanes 1..14 own four output columns each - the ST input quads under them, ST =
+// stride - lanes 0 and 15 load the quads left and right of the segment and compute nothing (beyond the image
+// border they read zeros, like every row above or below the image: offsets past the buffer descriptor's size).
+// So a shift by one lane inside the 16-lane row (DPP, no LDS) brings the input column left of a lane's first and,
+// at stride 1, the one right of its last, and the zero padding needs no special case.
+// A lane issues the loads of all the (CH - 1) ST + 3 input rows of its CH output rows together.
+constexpr int kDwSeg = 56;           // output columns of a segment: 14 computing lanes
+struct DwRowsGeom { int C, H, W, Ho, Wo, nseg, bands; int64_t items; };
+
+template <int ST, int CH>
+__global__ __launch_bounds__(kDwThreads) void dwconv3x3_rows(const float* __restrict__ in, const float* __restrict__ wt,
+                                                             const float* __restrict__ bias, const float* __restrict__ scale,
+                                                             const float* __restrict__ shift, float* __restrict__ out,
+                                                             DwRowsGeom g, int relu) {
+    constexpr int NQ = ST, NR = (CH - 1) * ST + 3;   // input quads per lane and row; input rows per lane
+    const int lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * (kDwThreads / 64) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (item >= g.items) return;   // the whole wave; there are no barriers in this kernel
+    const int seg = (int)(item % g.nseg);
+    const int64_t t = item / g.nseg;
+    const int band = (int)(t % g.bands);
+    const int64_t plane = t / g.bands;
+    const int c = (int)(plane % g.C);
+    float w[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i) w[i] = wt[c * 9 + i];
+    const float mul = scale ? scale[c] : 1.f;
+    const float add = (bias ? bias[c] : 0.f) * mul + (shift ? shift[c] : 0.f);   // (acc + bias) * scale + shift
+
+    const int dr = lane >> 4, cq = lane & 15;
+    const int ox0 = seg * kDwSeg + 4 * (cq - 1);                // first of this lane's four output columns
+    const int xi0 = ox0 * ST;                                   // the input column under it
+    const bool comp = cq >= 1 && cq <= 14 && ox0 < g.Wo;        // Wo % 4 == 0: a quad is inside or outside as a whole
+    const int rr = (band * 4 + dr) * CH;                        // first output row of this lane
+    constexpr unsigned kOob = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(in) + plane * (int64_t)g.H * g.W, 0, g.H * g.W * 4, 0x00020000);
+
+    float4v v[NR][NQ];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        const int y = rr * ST + j - 1;
+        const bool row_ok = y >= 0 && y < g.H;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {   // W % 4 == 0: an input quad is inside or outside as a whole
+            const int xq = xi0 + 4 * q;
+            const unsigned off = (row_ok && xq >= 0 && xq < g.W) ? (unsigned)((y * g.W + xq) * 4) : kOob;
+            v[j][q] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0));
+        }
+    }
+    float x[NR][4 * NQ + 2];   // x[j][1 + e] = input column xi0 + e of row j; x[j][0] the column left of them
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        x[j][0] = dpp_mov<0x111>(v[j][NQ - 1].w);   // row_shr:1 - the last column of the lane to the left
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            x[j][1 + 4 * q] = v[j][q].x; x[j][2 + 4 * q] = v[j][q].y; x[j][3 + 4 * q] = v[j][q].z; x[j][4 + 4 * q] = v[j][q].w;
+        }
+        x[j][4 * NQ + 1] = dpp_mov<0x101>(v[j][0].x);   // row_shl:1 - the first column of the lane to the right (stride 1 only)
+    }
+    float* __restrict__ po = out + plane * (int64_t)g.Ho * g.Wo + ox0;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] += x[i * ST + kh][j * ST + kw] * w[kh * 3 + kw];
+        float o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            o[j] = acc[j] * mul + add;
+            if (relu) o[j] = fmaxf(o[j], 0.f);
+            if (relu == 2) o[j] = fminf(o[j], 6.f);
+        }
+        if (comp && rr + i < g.Ho) store4_nt(po + (int64_t)(rr + i) * g.Wo, float4v{o[0], o[1], o[2], o[3]});
+    }
+}
+
+// Output rows per lane.  Many short waves stream better than fewer long ones (stride 1, 56 x 56 planes, 32 x 144 of
+// them: 4 rows 21.0 us, 7 rows 21.6, 14 rows 25.0; 64 x 144: 38.3 / 38.3 / 42.3), although a lane then loads 6 rows
+// for 4.
+constexpr int kDwRowsCH = 4, kDwRowsCH2 = 4;   // at stride 1, at stride 2
+
+// The register variant: 3 x 3, stride 1 or 2, dilation 1, pad 1, whole quads on both sides (W % 4 == 0 and
+// Wo % 4 == 0), at least three quarters of the lanes computing (Wo = 56: 14 of 16; Wo = 28 would be 7 of 16 and
+// stays with the LDS variant), a plane within the 32-bit byte offsets of a buffer descriptor.
+bool dw_rows_ok(const ConvParams& p) {
+    if (p.R != 3 || (p.stride != 1 && p.stride != 2) || p.dil != 1 || p.pad != 1 || (p.W & 3)) return false;
+    if ((int64_t)p.H * p.W * 4 >= (int64_t)1 << 31) return false;
+    const int Wo = (p.W - 1) / p.stride + 1;
+    if (Wo & 3) return false;
+    const int nseg = (Wo + kDwSeg - 1) / kDwSeg;
+    return Wo >= nseg * 16 * 3;
+}
+
+DwRowsGeom dw_rows_geom(const ConvParams& p) {
+    DwRowsGeom g{};
+    g.C = p.C; g.H = p.H; g.W = p.W;
+    g.Ho = (p.H - 1) / p.stride + 1; g.Wo = (p.W - 1) / p.stride + 1;
+    g.nseg = (g.Wo + kDwSeg - 1) / kDwSeg;
+    const int ch = p.stride == 2 ? kDwRowsCH2 : kDwRowsCH;
+    g.bands = (g.Ho + 4 * ch - 1) / (4 * ch);
+    g.items = (int64_t)p.Nb * p.C * g.bands * g.nseg;
+    return g;
+}
+
 DwGeom dw_geom(const ConvParams& p) {
     DwGeom g{};
     g.C = p.C; g.H = p.H; g.W = p.W; g.St = p.stride; g.P = p.pad; g.Dl = p.dil;
@@ -185,14 +301,23 @@ bool dwconv_supported(const ConvParams& p, const char** why) {
     if (p.R != 1 && p.R != 3 && p.R != 5 && p.R != 7) { *why = "only square 1x1, 3x3, 5x5 and 7x7 filters are supported"; return false; }
     if (p.stride > 4 || p.dil > 4) { *why = "strides and dilations above 4 are not supported"; return false; }
     if (p.pad > (p.R - 1) * p.dil) { *why = "padding larger than the (dilated) filter extent minus one"; return false; }
+    if (dw_rows_ok(p)) return true;   // no LDS
     const DwGeom g = dw_geom(p);
     if (dw_lds(g) > 64 * 1024) { *why = "one band of input rows does not fit in LDS (image too wide)"; return false; }
     return true;
 }
 
 LaunchShape dwconv_shape(const ConvParams& p) {
-    const DwGeom g = dw_geom(p);
     LaunchShape s{};
+    if (dw_rows_ok(p)) {
+        const DwRowsGeom r = dw_rows_geom(p);
+        s.grid[0] = (uint32_t)((r.items + kDwThreads / 64 - 1) / (kDwThreads / 64)); s.grid[1] = s.grid[2] = 1;
+        s.block[0] = kDwThreads; s.block[1] = s.block[2] = 1;
+        s.lds_bytes = 0;
+        s.kernel = p.stride == 2 ? "dwconv3x3_rows<stride2>" : "dwconv3x3_rows";
+        return s;
+    }
+    const DwGeom g = dw_geom(p);
     s.grid[0] = dw_grid(g); s.grid[1] = s.grid[2] = 1;
     s.block[0] = kDwThreads; s.block[1] = s.block[2] = 1;
     s.lds_bytes = (uint32_t)dw_lds(g);
@@ -210,6 +335,13 @@ void dw_launch_r(const ConvParams& p, const DwGeom& g, hipStream_t stream) {
 }
 
 hipError_t dwconv_launch(const ConvParams& p, hipStream_t stream) {
+    if (dw_rows_ok(p)) {
+        const DwRowsGeom r = dw_rows_geom(p);
+        const dim3 grid((unsigned)((r.items + kDwThreads / 64 - 1) / (kDwThreads / 64))), block(kDwThreads);
+        if (p.stride == 2) hipLaunchKernelGGL((dwconv3x3_rows<2, kDwRowsCH2>), grid, block, 0, stream, p.in, p.wt, p.bias, p.scale, p.shift, p.out, r, p.relu);
+        else hipLaunchKernelGGL((dwconv3x3_rows<1, kDwRowsCH>), grid, block, 0, stream, p.in, p.wt, p.bias, p.scale, p.shift, p.out, r, p.relu);
+        return hipGetLastError();
+    }
     const DwGeom g = dw_geom(p);
     switch (p.R) {
         case 1: dw_launch_r<1>(p, g, stream); break;

@@ -629,12 +629,23 @@ def dw_desc(shape=(32, 96, 56, 56), R=3, stride=1, pad=1, dil=1, act=None, group
 
 
 def test_depthwise_conv_plans():
+    # 3x3, stride 1, pad 1, rows of 56: the register variant, a wave per 16 rows of a plane, four waves per group
     p = H.Plan(dw_desc(act=H.HPCT_EPI_RELU6))
-    assert p.kernel_name == "dwconv_planes<3x3>" and p.workspace_bytes == 0
-    # a 56 x 56 plane with its halo is 13.9 KB: one work-group per plane
-    assert p.launch_shape()[0] == (32 * 96, 1, 1) and p.launch_shape()[1] == (256, 1, 1)
+    assert p.kernel_name == "dwconv3x3_rows" and p.workspace_bytes == 0
+    assert p.launch_shape() == ((32 * 96 * 4 // 4, 1, 1), (256, 1, 1), 0)
+    # wide rows: segments of 56 columns
+    assert H.Plan(dw_desc(shape=(8, 32, 112, 112))).launch_shape()[0] == (8 * 32 * 7 * 2 // 4, 1, 1)
+    # rows that would leave most lanes idle, other strides, pads and filters: through LDS
+    p = H.Plan(dw_desc(shape=(32, 96, 28, 28), act=H.HPCT_EPI_RELU6))
+    assert p.kernel_name == "dwconv_planes<3x3>" and p.launch_shape()[0] == (32 * 96, 1, 1) and p.launch_shape()[1] == (256, 1, 1)
+    assert H.Plan(dw_desc(pad=0)).kernel_name == "dwconv_planes<3x3>"
+    assert H.Plan(dw_desc(shape=(2, 4, 56, 54))).kernel_name == "dwconv_planes<3x3>"
     # larger planes are cut into bands of rows
-    p = H.Plan(dw_desc(shape=(32, 32, 112, 112), act=H.HPCT_EPI_RELU))
+    # the same at stride 2, when the output rows fill the lanes: 56 output columns from 112
+    p = H.Plan(dw_desc(shape=(32, 96, 112, 112), stride=2))
+    assert p.kernel_name == "dwconv3x3_rows<stride2>" and p.launch_shape() == ((32 * 96 * 4 // 4, 1, 1), (256, 1, 1), 0)
+    assert H.Plan(dw_desc(stride=2)).kernel_name == "dwconv_planes<3x3>"           # 28 output columns
+    p = H.Plan(dw_desc(shape=(32, 32, 112, 112), R=5, pad=2, act=H.HPCT_EPI_RELU))
     assert p.launch_shape()[0][0] % (32 * 32) == 0 and p.launch_shape()[0][0] > 32 * 32 and p.launch_shape()[2] <= 16 * 1024
     assert H.Plan(dw_desc(R=5, pad=2, stride=2)).kernel_name == "dwconv_planes<5x5>"
     assert H.Plan(dw_desc(R=7, pad=3, shape=(2, 8, 30, 30))).kernel_name == "dwconv_planes<7x7>"

@@ -988,8 +988,24 @@ def check_depthwise(N, C, H, W, R, stride, pad, dil=1, act="relu6", bias=True, a
 def test_depthwise_full_size():
     # the 3x3 depthwise layers of a MobileNetV2 at batch 32: 96 channels at 112 x 112 (stride 2) and 144 at 56 x 56
     got, plan = check_depthwise(32, 144, 56, 56, 3, 1, 1)
+    assert plan.kernel_name == "dwconv3x3_rows"
+    got, plan = check_depthwise(32, 96, 112, 112, 3, 2, 1)
+    assert plan.kernel_name == "dwconv3x3_rows<stride2>"
+    got, plan = check_depthwise(32, 192, 28, 28, 3, 1, 1)
     assert plan.kernel_name == "dwconv_planes<3x3>"
-    check_depthwise(32, 96, 112, 112, 3, 2, 1)
+
+
+@pytest.mark.parametrize("N,C,H,W,stride", [(2, 3, 57, 56, 1), (1, 5, 30, 112, 1), (1, 2, 100, 48, 1), (2, 2, 5, 52, 1), (1, 2, 1, 56, 1),
+                                            (1, 3, 29, 168, 1), (3, 2, 56, 56, 1), (1, 2, 113, 224, 1), (300, 40, 3, 56, 1),
+                                            (2, 3, 57, 112, 2), (1, 2, 112, 112, 2), (1, 4, 31, 96, 2), (2, 2, 1, 104, 2), (1, 2, 100, 336, 2),
+                                            (1, 3, 2, 400, 2), (70, 30, 9, 112, 2)])
+def test_depthwise_3x3_register_variant(N, C, H, W, stride):
+    # bands of 16 output rows that do not divide the image, last segments of fewer than 56 columns, odd and even heights at stride 2
+    print("depthwise rows %s" % ((N, C, H, W, stride),), flush=True)
+    got, plan = check_depthwise(N, C, H, W, 3, stride, 1)
+    assert plan.kernel_name == ("dwconv3x3_rows<stride2>" if stride == 2 else "dwconv3x3_rows")
+    check_depthwise(N, C, H, W, 3, stride, 1, act=None, bias=False, affine=False, seed=1)
+    check_depthwise(N, C, H, W, 3, stride, 1, act="relu", affine=False, seed=2)
 
 
 @pytest.mark.parametrize("N,C,H,W,R,stride,pad,dil", [
