@@ -343,6 +343,7 @@ size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, in
 }
 
 LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt, int32_t batch) {
+    if (gemm_use_tile(M, K, N, softmax, mean, batch) && gemm_direct_ok(M, K, N, mean, wt, batch)) return gemm_direct_shape(M, N, batch);
     if (gemm_use_tile(M, K, N, softmax, mean, batch)) return gemm_tile_shape(M, N, gemm_ksplit(M, K, N, mean, batch), wt, batch);
     const int bn = pick_bn(N);
     LaunchShape s{};
@@ -365,7 +366,7 @@ hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
     if (p.batch < 1) p.batch = 1;
     if (gemm_use_tile(p.M, p.K, p.N, p0.softmax, p.mean, p.batch)) {
         p.ksplit = gemm_ksplit(p.M, p.K, p.N, p.mean, p.batch);
-        e = gemm_tile_launch(p, stream);
+        e = gemm_direct_ok(p.M, p.K, p.N, p.mean, p.wt, p.batch) ? gemm_direct_launch(p, stream) : gemm_tile_launch(p, stream);
     }
     else switch (pick_bn(p.N)) {
         case 64: e = launch_bn<64>(p, stream); break;

@@ -135,6 +135,10 @@ hipError_t gemm_launch(const GemmParams& p, hipStream_t stream);
 LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit, int32_t wt, int32_t batch = 1);
 int32_t gemm_tile_col_tiles(int32_t M, int32_t N, int32_t batch = 1);
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream);
+// k_gemm_direct.hip: products with a short K, operands loaded straight into the MFMA layout (no LDS)
+bool gemm_direct_ok(int32_t M, int32_t K, int32_t N, int32_t mean, int32_t wt, int32_t batch);
+LaunchShape gemm_direct_shape(int32_t M, int32_t N, int32_t batch);
+hipError_t gemm_direct_launch(const GemmParams& p, hipStream_t stream);
 hipError_t rows_finish_launch(const float* ws, float* out, int32_t M, int32_t T, int32_t N, int32_t softmax, hipStream_t stream);
 
 // ---- NCHW conv2d (square 1/3/5/7 filter, stride and dilation up to 4) + bias + per-channel

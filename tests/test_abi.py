@@ -543,6 +543,15 @@ def test_batched_gemm_plans():
     # small matrices: the 16-row kernel with the batch in grid.z
     p = H.Plan(g((3, 64, 256), (3, 256, 256), (3, 64, 256), red=H.HPCT_RED_SOFTMAX_LAST))
     assert p.kernel_name == "gemm_rows16<256>" and p.launch_shape()[0] == (4, 1, 3)
+    # a short K: no LDS staging
+    p = H.Plan(g((64, 512, 64), (64, 64, 512), (64, 512, 512)))
+    assert p.kernel_name == "gemm_direct" and p.launch_shape() == ((64 * 4 * 4, 1, 1), (256, 1, 1), 0) and p.workspace_bytes == 0
+    assert H.Plan(g((16384, 32), (32, 16384), (16384, 16384))).kernel_name == "gemm_direct"
+    assert H.Plan(g((16384, 32), (32, 16384), (16384, 16384), wstride=(1, 32))).kernel_name == "gemm_tile128<wt>"   # row-major W only
+    assert H.Plan(g((256, 64, 64), (256, 64, 64), (256, 64, 64))).kernel_name == "gemm_tile64"   # matrices smaller than its tile
+    assert H.Plan(g((16384, 34), (34, 16384), (16384, 16384))).kernel_name == "gemm_tile128"     # K % 4
+    assert H.Plan(g((16384, 68), (68, 16384), (16384, 16384))).kernel_name == "gemm_tile128"     # K > 64
+    assert H.Plan(g((1024, 32), (32, 1024), (1024, 1024))).kernel_name == "gemm_tile64"          # 64 tiles of 128 x 128
     # per-batch transposed W
     p = H.Plan(g((16, 256, 128), (16, 128, 256), (16, 256, 256), wstride=(128 * 256, 1, 128)))
     assert p.kernel_name == "gemm_tile64<wt>"

@@ -136,19 +136,24 @@ def wt_name(plain):
 @pytest.mark.parametrize("M,K,N", [
     (64, 256, 256), (17, 5, 10), (70, 100, 63), (33, 36, 130), (3, 300, 129), (2, 1, 3),       # 16-row kernel
     (4096, 256, 4096), (1024, 512, 1024), (700, 260, 644), (515, 37, 1001), (2900, 33, 3001),  # tiles of 128 and 64
-    (256, 2048, 256), (200, 3000, 333)])                                                       # K slices
+    (256, 2048, 256), (200, 3000, 333),                                                        # K slices
+    (2100, 36, 2052), (1800, 64, 2304), (2048, 4, 2048), (3000, 20, 1540), (1600, 60, 2944)])  # short K, no LDS
 def test_gemm_transposed_weight(M, K, N):
     print("gemm wt M=%d K=%d N=%d" % (M, K, N), flush=True)
     t = datagen.make(1, M=M, K=K, N=N)
     Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
     plain, plain_name = run_gemm(t, wt=False)
     got, name = run_gemm(t, wt=True)
-    # (with K = 1 or N = 1 the transposed storage is also row-major)
-    assert name == (plain_name if K == 1 or N == 1 else wt_name(plain_name)), (name, plain_name)
     assert show("gemm wt +bias+relu", compare.contraction(got, ref.relu(Z), Dn))
     assert np.max(np.abs(got - ref.relu(Z)) / Dn) < 1e-5
-    # the same products in the same order as with the row-major copy of W: bit-identical results
-    assert np.array_equal(got.view(np.uint32), plain.view(np.uint32))
+    if plain_name == "gemm_direct":
+        # the kernel for a short K takes a row-major W only; a transposed one goes to the tiled kernel
+        assert name in ("gemm_tile128<wt>", "gemm_tile64<wt>")
+    else:
+        # (with K = 1 or N = 1 the transposed storage is also row-major)
+        assert name == (plain_name if K == 1 or N == 1 else wt_name(plain_name)), (name, plain_name)
+        # the same products in the same order as with the row-major copy of W: bit-identical results
+        assert np.array_equal(got.view(np.uint32), plain.view(np.uint32))
     got, _ = run_gemm(t, wt=True, softmax=True)
     assert show("softmax", compare.pointwise(got, ref.chain1(t["X"], t["W"], t["bias"])))
     Z0, Dn0 = ref.gemm_bias(t["X"], t["W"], None, want_norm=True)
@@ -217,6 +222,37 @@ def test_batched_gemm(B, M, K, N):
     assert show("shared W", compare.contraction(host(out).reshape(B * M, N), Zs, Ds))
 
 
+def test_gemm_short_k_direct_kernel():
+    # operands straight into the MFMA layout: K below, at and between the 32-wide chunks, the dropout epilogue
+    # (an integer decision per element), and a batch
+    for (M, K, N) in [(2100, 36, 2052), (1700, 32, 2560), (2176, 64, 2048)]:
+        print("gemm direct M=%d K=%d N=%d" % (M, K, N), flush=True)
+        t = datagen.make(1, M=M, K=K, N=N)
+        Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+        got, name = run_gemm(t)
+        assert name == "gemm_direct"
+        assert show("direct", compare.contraction(got, ref.relu(Z), Dn))
+        D = ref.dropout_hash(Z, 0.3, 11)
+        got, name = run_chain6(t, 0.3, 11, "dropout")
+        assert name == "gemm_direct"
+        differ = (got == 0) != (D == 0)   # the mask is an integer decision; a kept element may still cancel to 0 in fp32
+        assert np.all(np.abs(Z[differ]) < 1e-6 * Dn[differ]), np.argwhere(differ)[:5]
+        assert show("dropout", compare.contraction(got, D, Dn / 0.7))
+    B, M, K, N = 20, 300, 32, 520
+    X = datagen.gen_normal(610, (B, M, K), 0.0, 1.0)
+    W = datagen.gen_normal(611, (B, K, N), 0.0, 1.0 / np.sqrt(K))
+    for wt in (False, True):
+        Wd = dev(np.ascontiguousarray(W.transpose(0, 2, 1))).transpose(1, 2) if wt else dev(W)
+        out = torch.full((B, M, N), float("nan"), device="cuda")
+        plan, ins = hpct.gemm_bias_relu_softmax_plan(dev(X), Wd, None, out, relu=False, softmax=False)
+        assert plan.kernel_name == ("gemm_tile64<wt>" if wt else "gemm_direct")
+        plan.launch(ins, [out])
+        got = host(out)
+        for i in range(B):
+            Zi, Di = ref.gemm_bias(X[i], W[i], None, want_norm=True)
+            assert compare.contraction(got[i], Zi, Di).ok, i
+
+
 def test_gemm_identity_weight_is_exact():
     X = datagen.gen_uniform(5, (48, 64), -1, 1)
     out = torch.empty(48, 64, device="cuda")
@@ -273,7 +309,9 @@ def test_chain6_small_shapes(M, K, N):
 def test_chain6_tiled_shapes(M, K, N):
     print("chain6 tiled M=%d K=%d N=%d" % (M, K, N), flush=True)
     name = check_chain6(datagen.make(6, M=M, K=K, N=N), datagen.CHAIN6_P, datagen.CHAIN6_SEED)
-    assert name in ("gemm_tile128", "gemm_tile64")
+    # (the dropout stage alone, whose kernel is named here, goes to the kernel without LDS when K is short)
+    assert name in ("gemm_tile128", "gemm_tile64", "gemm_direct")
+    assert (name == "gemm_direct") == (K <= 64 and K % 4 == 0 and N % 4 == 0 and ((M + 127) // 128) * ((N + 127) // 128) >= 256)
 
 
 @pytest.mark.parametrize("p,seed", [(0.0, 1), (0.5, 0), (0.3, (1 << 64) - 5), (0.999, 77)])
