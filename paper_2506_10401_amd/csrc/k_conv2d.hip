@@ -610,6 +610,7 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
 
 LaunchShape conv_shape(const ConvParams& p) {
     if (conv1x1_stream_ok(p)) return conv1x1_shape(p);
+    if (conv_fewc_ok(p)) return conv_fewc_shape(p);
     ConvGeom g;
     const int mode = pick_mode(p, &g);
     LaunchShape s{};
@@ -635,6 +636,7 @@ LaunchShape conv_shape(const ConvParams& p) {
 
 hipError_t conv_launch(const ConvParams& p, hipStream_t stream) {
     if (conv1x1_stream_ok(p)) return conv1x1_launch(p, stream);
+    if (conv_fewc_ok(p)) return conv_fewc_launch(p, stream);
     ConvGeom g;
     const int mode = pick_mode(p, &g);
     switch (p.R) {

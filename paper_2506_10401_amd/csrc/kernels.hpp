@@ -163,6 +163,11 @@ hipError_t conv_launch(const ConvParams& p, hipStream_t stream);
 bool conv1x1_stream_ok(const ConvParams& p);
 LaunchShape conv1x1_shape(const ConvParams& p);
 hipError_t conv1x1_launch(const ConvParams& p, hipStream_t stream);
+// 3x3, stride 1, pad 1 on at most 4 input channels (a network's first layer): the kernel without LDS (k_conv_fewc.hip),
+// taken by conv_shape / conv_launch whenever conv_fewc_ok
+bool conv_fewc_ok(const ConvParams& p);
+LaunchShape conv_fewc_shape(const ConvParams& p);
+hipError_t conv_fewc_launch(const ConvParams& p, hipStream_t stream);
 // transposed conv: the operands of the equivalent stride-1 conv, prepared in the workspace (k_convt_prep.hip)
 struct ConvTParams {
     int32_t Nb, C, H, W, K, R, stride;   // in [Nb,C,H,W], wt [C,K,R,R]

@@ -637,6 +637,23 @@ def dw_desc(shape=(32, 96, 56, 56), R=3, stride=1, pad=1, dil=1, act=None, group
                      groups=Cc if groups is None else groups)
 
 
+def test_conv_few_input_channels_plans():
+    def cd(shape, K, stride=1, pad=1, pool=False):
+        Nb, Cc, Hh, Ww = shape
+        Ho = (Hh + 2 * pad - 3) // stride + 1
+        Wo = (Ww + 2 * pad - 3) // stride + 1
+        return H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU],
+                         H.HPCT_RED_MAXPOOL2_HW if pool else H.HPCT_RED_NONE, 0, [shape, (K, Cc, 3, 3), (K,)],
+                         [(Nb, K, Ho // 2, Wo // 2) if pool else (Nb, K, Ho, Wo)], stride_hw=(stride, stride), pad_hw=(pad, pad))
+    # a network's first layer: a wave per 32 channels x 128 pixels x 4 rows, no LDS
+    p = H.Plan(cd((32, 3, 224, 224), 64))
+    assert p.kernel_name == "conv3x3_fewc" and p.launch_shape() == ((32 * 56 * 2 * 2 // 4, 1, 1), (256, 1, 1), 0)
+    assert H.Plan(cd((2, 1, 28, 100), 32)).kernel_name == "conv3x3_fewc"
+    for d in (cd((32, 3, 224, 224), 48), cd((32, 3, 224, 224), 64, stride=2), cd((32, 3, 224, 224), 64, pad=0),
+              cd((32, 3, 224, 224), 64, pool=True), cd((32, 3, 224, 222), 64), cd((32, 5, 224, 224), 64), cd((2, 3, 32, 32), 64)):
+        assert H.Plan(d).kernel_name.startswith("conv2d_nchw_mfma<3x3")
+
+
 def test_depthwise_conv_plans():
     # 3x3, stride 1, pad 1, rows of 56: the register variant, a wave per 16 rows of a plane, four waves per group
     p = H.Plan(dw_desc(act=H.HPCT_EPI_RELU6))

@@ -621,6 +621,29 @@ def test_conv1x1_streaming_kernel(N, C, H, W, K):
         assert name.startswith("conv2d_nchw_mfma<1x1")
 
 
+@pytest.mark.parametrize("N,C,H,W,K", [
+    (2, 3, 30, 224, 64),         # the first layer of a VGG: two segments, the second of 96 pixels
+    (3, 3, 7, 128, 32),          # one full segment, an odd number of rows
+    (1, 1, 28, 100, 32),         # a grey image; a ragged segment
+    (2, 2, 5, 384, 96),          # three segments, three blocks of output channels
+    (1, 4, 1, 112, 64),          # a single row: nothing above or below it
+    (5, 3, 9, 104, 160)])
+def test_conv3x3_few_input_channels(N, C, H, W, K):
+    print("conv fewc %s" % ((N, C, H, W, K),), flush=True)
+    t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=3, S=3)
+    _, name = check_chain7(t, 1, 1, pool=False)
+    assert name == "conv3x3_fewc"
+    check_chain7(t, 1, 1, relu=False, pool=False, bias=False, affine=False)
+    want, Dn = ref.conv2d_nchw_bias(t["in"], t["wt"] * 16.0, t["bias"], 1, 1, want_norm=True)
+    out = torch.full(want.shape, float("nan"), device="cuda")
+    hpct.conv_block(dev(t["in"]), dev(t["wt"] * 16.0), dev(t["bias"]), None, None, out, 1, 1, "relu6", False)
+    assert show("fewc relu6", compare.contraction(host(out), ref.relu6(want), Dn))
+    # pooled, strided or unpadded: the general kernel
+    if H >= 3:
+        _, name = check_chain7(t, 1, 0, pool=False)
+        assert name.startswith("conv2d_nchw_mfma<3x3")
+
+
 def test_chain7_pool_takes_the_maximum_not_a_sum_or_a_corner():
     # identity 1x1 conv: the block is max pooling of the input, exactly
     X = datagen.gen_normal(11, (2, 4, 10, 66), 0.0, 1.0)
