@@ -442,6 +442,8 @@ void ref_maxpool2x2_planes(const double *T, int64_t planes, int64_t H, int64_t W
  *   op 1: mean     out_val = (sum_r x_r) / R
  *   op 2: argmax   out_idx = the smallest r with x_r = max_r x_r
  *   op 3: argmin   out_idx = the smallest r with x_r = min_r x_r
+ *   op 4: max      out_val = max_r x_r
+ *   op 5: min      out_val = min_r x_r
  * For op 0/1 out_abs (may be NULL) receives sum_r |x_r| (divided by R for the
  * mean), the scale a summation's rounding error is measured against.
  * Values are widened to double; comparisons of fp32 values are exact. */
@@ -469,6 +471,13 @@ void ref_reduce_axis(const float *in, int32_t nd, const int64_t *shape, const in
             if (op == 1) { s /= (double)R; a /= (double)R; }
             out_val[o] = s;
             if (out_abs) out_abs[o] = a;
+        } else if (op >= 4) {
+            double bv = (double)in[base];
+            for (int64_t r = 1; r < R; ++r) {
+                double x = (double)in[base + r * sR];
+                if (op == 4 ? x > bv : x < bv) bv = x;
+            }
+            out_val[o] = bv;
         } else {
             int64_t best = 0;
             double bv = (double)in[base];

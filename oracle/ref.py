@@ -308,13 +308,13 @@ def eltwise_map(a_base, shape, sa, unary=(), binary=None, b_base=None, sb=None, 
     return out
 
 
-REDUCE_OPS = {"sum": 0, "mean": 1, "argmax": 2, "argmin": 3}
+REDUCE_OPS = {"sum": 0, "mean": 1, "argmax": 2, "argmin": 3, "max": 4, "min": 5}
 
 
 def reduce_axis(base, shape, stride, axis, op, want_abs=False):
-    """Reduction `op` in {"sum","mean","argmax","argmin"} over dim `axis` of the strided view
+    """Reduction `op` in {"sum","mean","argmax","argmin","max","min"} over dim `axis` of the strided view
     (shape, stride in elements) of the flat fp32 array `base`.  Returns fp64 values (and the
-    sum of magnitudes with want_abs) for sum / mean, int64 indices for the arg-reductions."""
+    sum of magnitudes with want_abs) for sum / mean / max / min, int64 indices for the arg-reductions."""
     base = _f32(base).reshape(-1)
     nd = len(shape)
     assert 0 <= axis < nd
@@ -324,9 +324,9 @@ def reduce_axis(base, shape, stride, axis, op, want_abs=False):
     st = (C.c_int64 * nd)(*stride)
     oshape = tuple(n for d, n in enumerate(shape) if d != axis)
     code = REDUCE_OPS[op]
-    if code <= 1:
+    if code <= 1 or code >= 4:
         val = np.empty(oshape, dtype=np.float64)
-        ab = np.empty(oshape, dtype=np.float64) if want_abs else None
+        ab = np.empty(oshape, dtype=np.float64) if want_abs and code <= 1 else None
         lib().ref_reduce_axis(_ptr(base), nd, sh, st, axis, code, _ptr(val), _ptr(ab), None)
         return (val, ab) if want_abs else val
     idx = np.empty(oshape, dtype=np.int64)

@@ -645,6 +645,26 @@ def test_reduce_axis_against_numpy_on_strided_views():
             assert np.array_equal(ref.reduce_axis(base, shape, stride, axis, "argmin"), v.argmin(axis=axis))
 
 
+def test_reduce_axis_max_min_values():
+    # against numpy on strided views; the value at the arg-reduction's index; min(x) = -max(-x); a ramp; infinities
+    rng = np.random.default_rng(9)
+    base = rng.integers(-5, 6, 4000).astype(np.float32)     # full of ties
+    for shape, stride in [((7, 9, 11), (99, 11, 1)), ((7, 9, 11), (1, 7, 63)), ((5, 6), (12, 2)), ((13,), (3,)), ((4, 1, 6), (30, 0, 5))]:
+        v = np.lib.stride_tricks.as_strided(base, shape, tuple(4 * s for s in stride))
+        for axis in range(len(shape)):
+            mx = ref.reduce_axis(base, shape, stride, axis, "max")
+            mn = ref.reduce_axis(base, shape, stride, axis, "min")
+            assert np.array_equal(mx, v.max(axis=axis)) and np.array_equal(mn, v.min(axis=axis))
+            am = ref.reduce_axis(base, shape, stride, axis, "argmax")
+            assert np.array_equal(mx, np.take_along_axis(v, np.expand_dims(am, axis), axis).squeeze(axis))
+            assert np.array_equal(mn, -ref.reduce_axis(-base, shape, stride, axis, "max"))
+    x = np.arange(60, dtype=np.float32)
+    assert np.array_equal(ref.reduce_axis(x, (3, 4, 5), (20, 5, 1), 1, "max"), x.reshape(3, 4, 5)[:, 3, :])
+    assert np.array_equal(ref.reduce_axis(x, (3, 4, 5), (20, 5, 1), 1, "min"), x.reshape(3, 4, 5)[:, 0, :])
+    y = np.array([1.0, -np.inf, np.inf, 3.0], np.float32)
+    assert ref.reduce_axis(y, (4,), (1,), 0, "max") == np.inf and ref.reduce_axis(y, (4,), (1,), 0, "min") == -np.inf
+
+
 def test_reduce_axis_closed_forms_and_output_order():
     # x[i][j][k] = 100 i + 10 j + k on a 3 x 4 x 5 grid: sums have closed forms and show which axis went away
     i, j, k = np.meshgrid(np.arange(3), np.arange(4), np.arange(5), indexing="ij")
