@@ -53,8 +53,9 @@
  *         reduction: out = steps(A op B) or steps(A)
  *   NONE  (no epilogue, no reduction): layout         X: any strided view (stride   same shape,
  *         transform, out = contiguous copy of X       >= 0, up to 6 dims)           contiguous
- *   NONE  SUM_AXIS | MEAN_AXIS | ARGMAX_AXIS |        X: any strided view (stride   X's shape without
- *         ARGMIN_AXIS over dim `axis`, no epilogue    >= 0, up to 6 dims)           dim `axis`, contiguous
+ *   NONE  SUM_AXIS | MEAN_AXIS | MAX_AXIS | MIN_AXIS  X: any strided view (stride   X's shape without
+ *         | ARGMAX_AXIS | ARGMIN_AXIS over dim        >= 0, up to 6 dims)           dim `axis`, contiguous
+ *         `axis`, no epilogue
  *                                                                                   (1-D input: shape [1]);
  *                                                                                   int32 for the arg ops
  *   CONVT2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH]        in[N,C,H,W], wt[C,K,R,S],     [N,K,Ho,Wo]
@@ -160,7 +161,9 @@ typedef enum {
     HPCT_RED_SUM_AXIS = 6,        /* sum over dim `axis`, which is dropped */
     HPCT_RED_MEAN_AXIS = 7,       /* mean over dim `axis`, which is dropped */
     HPCT_RED_ARGMAX_AXIS = 8,     /* int32 index of the maximum along dim `axis`; of equal values the lowest index */
-    HPCT_RED_ARGMIN_AXIS = 9      /* int32 index of the minimum along dim `axis`; of equal values the lowest index */
+    HPCT_RED_ARGMIN_AXIS = 9,     /* int32 index of the minimum along dim `axis`; of equal values the lowest index */
+    HPCT_RED_MAX_AXIS = 10,       /* maximum over dim `axis`, which is dropped (fp32) */
+    HPCT_RED_MIN_AXIS = 11        /* minimum over dim `axis`, which is dropped (fp32) */
 } hpct_reduce;
 
 typedef struct {

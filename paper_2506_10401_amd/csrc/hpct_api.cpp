@@ -447,7 +447,10 @@ hpct_status plan_reduce(const hpct_op_desc& d, hpct_plan& p) {
     ReduceParams q{};
     q.R = (int32_t)I.shape[d.axis];
     q.sR = I.stride[d.axis];
-    q.op = d.reduce == HPCT_RED_ARGMAX_AXIS ? 2 : (d.reduce == HPCT_RED_ARGMIN_AXIS ? 3 : 0);
+    const bool is_max = d.reduce == HPCT_RED_ARGMAX_AXIS || d.reduce == HPCT_RED_MAX_AXIS;
+    const bool is_min = d.reduce == HPCT_RED_ARGMIN_AXIS || d.reduce == HPCT_RED_MIN_AXIS;
+    q.op = is_max ? 2 : (is_min ? 3 : 0);
+    q.value = (d.reduce == HPCT_RED_MAX_AXIS || d.reduce == HPCT_RED_MIN_AXIS) ? 1 : 0;   // the extreme value itself, not its index
     q.mean = d.reduce == HPCT_RED_MEAN_AXIS ? 1 : 0;
     // kept dimensions: drop extent 1, merge neighbours that are contiguous with each other in the input
     int nk = 0;
@@ -664,8 +667,8 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
     if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONVT2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
-    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_ARGMIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
-    if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_ARGMIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_MIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)

@@ -91,6 +91,8 @@ template <int OP>
 __device__ __forceinline__ void emit(const ReduceParams& p, int64_t o, const Acc<OP>& a) {
     if constexpr (OP == 0) {
         reinterpret_cast<float*>(p.out)[o] = p.mean ? a.s / (float)p.R : a.s;
+    } else if (p.value) {
+        reinterpret_cast<float*>(p.out)[o] = a.v;
     } else {
         reinterpret_cast<int32_t*>(p.out)[o] = a.i;
     }

@@ -83,6 +83,7 @@ hipError_t eltwise_launch(const EltwiseParams& p, hipStream_t stream);
 constexpr int kReduceDims = 5;
 struct ReduceParams {
     const float* in; void* out;        // out: float (sum, mean) or int32 (argmax, argmin), contiguous
+    int32_t value;                     // op 2 / 3: write the extreme value (fp32) instead of its index
     int32_t nk;                        // kept dimensions after collapsing, 0..kReduceDims
     int64_t shape[kReduceDims];        // their extents
     int64_t stride[kReduceDims];       // their input strides (elements)

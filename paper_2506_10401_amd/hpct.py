@@ -28,7 +28,8 @@ HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL
     HPCT_EPI_SUB_TENSOR, HPCT_EPI_DIV_TENSOR, HPCT_EPI_SQRT, HPCT_EPI_SIN, HPCT_EPI_COS, HPCT_EPI_EXP, HPCT_EPI_TANH, \
     HPCT_EPI_SIGMOID, HPCT_EPI_RELU6 = range(19)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
-    HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS = range(10)
+    HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS, HPCT_RED_MAX_AXIS, \
+    HPCT_RED_MIN_AXIS = range(12)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
 
 
@@ -390,12 +391,12 @@ def eltwise(a_view, b_view, out, op, relu=False, stream=None) -> None:
 
 
 _REDUCE_OPS = {"sum": HPCT_RED_SUM_AXIS, "mean": HPCT_RED_MEAN_AXIS, "argmax": HPCT_RED_ARGMAX_AXIS,
-               "argmin": HPCT_RED_ARGMIN_AXIS}
+               "argmin": HPCT_RED_ARGMIN_AXIS, "max": HPCT_RED_MAX_AXIS, "min": HPCT_RED_MIN_AXIS}
 
 
 def reduce_axis_plan(x_view, out, axis, op):
     """x_view: a (possibly non-contiguous) fp32 GPU tensor view; out: contiguous, x_view's shape without dim
-    `axis` (shape [1] for a 1-D input); fp32 for op "sum" / "mean", int32 for "argmax" / "argmin"."""
+    `axis` (shape [1] for a 1-D input); fp32 for op "sum" / "mean" / "max" / "min", int32 for "argmax" / "argmin"."""
     shape, stride = _sh(x_view), tuple(int(v) for v in x_view.stride())
     arg = op in ("argmax", "argmin")
     plan = _cached(("reduce", shape, stride, axis, op), lambda: op_desc(
@@ -405,7 +406,7 @@ def reduce_axis_plan(x_view, out, axis, op):
 
 
 def reduce_axis(x_view, out, axis, op, workspace=None, stream=None) -> None:
-    """out = sum / mean / argmax / argmin of x_view over dim `axis` (ties of the arg ops go to the lowest index).
+    """out = sum / mean / max / min / argmax / argmin of x_view over dim `axis` (ties of the arg ops go to the lowest index).
     `workspace`: GPU tensor of at least plan.workspace_bytes bytes when that is not 0."""
     plan, ins = reduce_axis_plan(x_view, out, axis, op)
     plan.launch(ins, [out], stream, workspace)

@@ -452,6 +452,10 @@ def test_axis_reduction_plans():
     assert p.kernel_name == "reduce_gather"
     # a vector reduces to shape [1]
     assert H.Plan(reduce_desc((1000,), (1,), 0, H.HPCT_RED_SUM_AXIS)).kernel_name.startswith("reduce_rows")
+    # the extreme values themselves: the arg kernels, fp32 out
+    pm = H.Plan(reduce_desc((8192, 4096), (4096, 1), 0, H.HPCT_RED_MAX_AXIS))
+    assert pm.kernel_name == "reduce_cols<vec4,split>" and pm.workspace_bytes == pa.workspace_bytes
+    assert H.Plan(reduce_desc((8192, 4096), (4096, 1), 1, H.HPCT_RED_MIN_AXIS)).kernel_name == "reduce_rows<group>"
     assert p.workspace_bytes == 0
 
 
@@ -463,6 +467,8 @@ def test_axis_reduction_errors():
     # dtypes: indices are int32, sums fp32
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_ARGMAX_AXIS, out_dtype=H.HPCT_F32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS, out_dtype=H.HPCT_I32))
+    expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_MAX_AXIS, out_dtype=H.HPCT_I32))
+    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 12))      # one past MIN_AXIS
     d = cfg_desc(3); d.out[0].dtype = H.HPCT_I32          # int32 anywhere else
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.n_epi = 1; d.epi[0] = H.HPCT_EPI_RELU

@@ -779,7 +779,7 @@ def test_layout_slices_and_broadcasts():
 
 # --------------------------------------------------- reductions over one axis
 def check_reduce(view, axis, tag=""):
-    """view: a torch view on the GPU; compares all four reductions over `axis` with the checker."""
+    """view: a torch view on the GPU; compares all six reductions over `axis` with the checker."""
     base = view._base if view._base is not None else view
     hb = host(base).reshape(-1)
     off = view.storage_offset() - base.storage_offset()
@@ -805,6 +805,14 @@ def check_reduce(view, axis, tag=""):
         names.add(plan.kernel_name)
         want = ref.reduce_axis(hb[off:], shape, stride, axis, op)
         assert np.array_equal(host(out).reshape(want.shape).astype(np.int64), want), (tag, op, axis)
+    for op in ("max", "min"):   # a selection: exact
+        out = torch.full(oshape, float("nan"), device="cuda")
+        plan, ins = hpct.reduce_axis_plan(view, out, axis, op)
+        ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda") if plan.workspace_bytes else None
+        plan.launch(ins, [out], workspace=ws)
+        names.add(plan.kernel_name)
+        want = ref.reduce_axis(hb[off:], shape, stride, axis, op)
+        assert np.array_equal(host(out).reshape(want.shape).astype(np.float64), want), (tag, op, axis)
     return names
 
 
