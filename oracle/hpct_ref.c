@@ -435,6 +435,35 @@ void ref_maxpool2x2_planes(const double *T, int64_t planes, int64_t H, int64_t W
     }
 }
 
+/* ---- Reduction: max pooling with a k x k window, stride s and padding p
+ * (p < k) over the planes of an NCHW tensor - the pooling layers of the
+ * networks that Section 5.1 names as Level-3 tasks (a ResNet's 3x3 / stride 2
+ * / pad 1; the 2x2 / stride 2 above is the case k = 2, s = 2, p = 0):
+ *   out[pl][oy][ox] = max over dy, dx in 0..k-1 of T[pl][oy s - p + dy][ox s - p + dx]
+ * taken over the positions inside the image only (padding never wins), for
+ * oy < (H + 2p - k) / s + 1, ox < (W + 2p - k) / s + 1 (integer division). */
+void ref_maxpool2d_planes(const double *T, int64_t planes, int64_t H, int64_t W, int64_t k, int64_t s, int64_t p,
+                          double *out)
+{
+    const int64_t Ho = (H + 2 * p - k) / s + 1, Wo = (W + 2 * p - k) / s + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t pl = 0; pl < planes; ++pl) {
+        for (int64_t oy = 0; oy < Ho; ++oy) {
+            for (int64_t ox = 0; ox < Wo; ++ox) {
+                double m = -INFINITY;
+                for (int64_t dy = 0; dy < k; ++dy)
+                    for (int64_t dx = 0; dx < k; ++dx) {
+                        int64_t iy = oy * s - p + dy, ix = ox * s - p + dx;
+                        if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+                        double v = T[(pl * H + iy) * W + ix];
+                        if (v > m) m = v;
+                    }
+                out[(pl * Ho + oy) * Wo + ox] = m;
+            }
+        }
+    }
+}
+
 /* ---- Reduction (Table 1: "sum, mean" and the arg-reductions) over one axis of
  * a strided view.  The view has `nd` dims with `shape` and `stride` (elements,
  * >= 0); the output is the view with dim `axis` removed, row-major.

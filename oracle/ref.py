@@ -45,6 +45,7 @@ def lib():
             "ref_mean_rows": [p, i64, i64, p],
             "ref_scale_shift_planes": [p, p, p, i64, i64, i64],
             "ref_maxpool2x2_planes": [p, i64, i64, i64, p],
+            "ref_maxpool2d_planes": [p, i64, i64, i64, i64, i64, i64, p],
             "ref_reduce_axis": [p, C.c_int32, p, p, C.c_int32, C.c_int32, p, p, p],
             "ref_eltwise_binary": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p],
             "ref_eltwise_map": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p, C.c_float, p],
@@ -267,6 +268,18 @@ def maxpool2x2(T):
     out = np.empty((Nb, Cc, H // 2, W // 2), dtype=np.float64)
     if out.size:
         lib().ref_maxpool2x2_planes(_ptr(T), Nb * Cc, H, W, _ptr(out))
+    return out
+
+
+def maxpool2d(T, k, stride, pad):
+    """k x k max pooling with stride and padding (pad < k; padding never wins) over the last two dims of an fp64
+    NCHW array; output extent (H + 2 pad - k) // stride + 1."""
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    Nb, Cc, H, W = T.shape
+    assert 0 <= pad < k and stride >= 1 and H + 2 * pad >= k and W + 2 * pad >= k
+    out = np.empty((Nb, Cc, (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1), dtype=np.float64)
+    if out.size:
+        lib().ref_maxpool2d_planes(_ptr(T), Nb * Cc, H, W, k, stride, pad, _ptr(out))
     return out
 
 

@@ -645,6 +645,32 @@ def test_reduce_axis_against_numpy_on_strided_views():
             assert np.array_equal(ref.reduce_axis(base, shape, stride, axis, "argmin"), v.argmin(axis=axis))
 
 
+def test_maxpool2d_against_sliding_windows_and_special_cases():
+    # numpy: pad with -inf, take every window with sliding_window_view, subsample by the stride
+    rng = np.random.default_rng(21)
+    for (H, W, k, s, p) in [(9, 11, 3, 2, 1), (8, 8, 2, 2, 0), (7, 10, 3, 1, 1), (12, 5, 5, 3, 2), (6, 6, 3, 2, 0), (5, 9, 1, 2, 0),
+                            (10, 10, 7, 2, 3), (4, 4, 4, 4, 0)]:
+        T = rng.standard_normal((2, 3, H, W)) - 2.0          # mostly negative: a zero padding would win
+        P = np.full((2, 3, H + 2 * p, W + 2 * p), -np.inf)
+        P[:, :, p:p + H, p:p + W] = T
+        win = np.lib.stride_tricks.sliding_window_view(P, (k, k), axis=(2, 3))[:, :, ::s, ::s]
+        want = win.max(axis=(4, 5))
+        got = ref.maxpool2d(T, k, s, p)
+        assert got.shape == want.shape and np.array_equal(got, want), (H, W, k, s, p)
+    # k = 2, s = 2, p = 0 is the 2x2 pooling of the VGG block
+    T = rng.standard_normal((2, 2, 9, 7))
+    assert np.array_equal(ref.maxpool2d(T, 2, 2, 0), ref.maxpool2x2(T))
+    # a ramp increasing along both axes: the window's last element inside the image
+    R = (np.arange(8)[:, None] * 100.0 + np.arange(10)[None, :]).reshape(1, 1, 8, 10)
+    got = ref.maxpool2d(R, 3, 2, 1)
+    for oy in range(4):
+        for ox in range(5):
+            assert got[0, 0, oy, ox] == min(2 * oy + 1, 7) * 100.0 + min(2 * ox + 1, 9)
+    # a 1x1 window at stride 1 is the identity; a window as large as the image gives the global maximum
+    assert np.array_equal(ref.maxpool2d(T, 1, 1, 0), T)
+    assert np.array_equal(ref.maxpool2d(T[:, :, :7, :], 7, 1, 0)[:, :, 0, 0], T[:, :, :7, :].max(axis=(2, 3)))
+
+
 def test_reduce_axis_max_min_values():
     # against numpy on strided views; the value at the arg-reduction's index; min(x) = -max(-x); a ramp; infinities
     rng = np.random.default_rng(9)
