@@ -58,6 +58,8 @@
  *         `axis`, no epilogue
  *                                                                                   (1-D input: shape [1]);
  *                                                                                   int32 for the arg ops
+ *   NONE  MAXPOOL_HW (window_hw, stride_hw, pad_hw,    X[N,C,H,W]                    [N,C,Ho,Wo]
+ *         each square), no epilogue
  *   CONVT2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH]        in[N,C,H,W], wt[C,K,R,S],     [N,K,Ho,Wo]
  *         [+RELU|RELU6] (needs the workspace: the     bias[K], scale[K], shift[K]
  *         flipped filter and, for stride > 1, the
@@ -163,7 +165,9 @@ typedef enum {
     HPCT_RED_ARGMAX_AXIS = 8,     /* int32 index of the maximum along dim `axis`; of equal values the lowest index */
     HPCT_RED_ARGMIN_AXIS = 9,     /* int32 index of the minimum along dim `axis`; of equal values the lowest index */
     HPCT_RED_MAX_AXIS = 10,       /* maximum over dim `axis`, which is dropped (fp32) */
-    HPCT_RED_MIN_AXIS = 11        /* minimum over dim `axis`, which is dropped (fp32) */
+    HPCT_RED_MIN_AXIS = 11,       /* minimum over dim `axis`, which is dropped (fp32) */
+    HPCT_RED_MAXPOOL_HW = 12      /* max over window_hw windows of dims 2,3 of NCHW at stride_hw with pad_hw (padding never
+                                     wins; pad < window); output extent (H + 2 pad - window) / stride + 1.  No anchor. */
 } hpct_reduce;
 
 typedef struct {
@@ -188,6 +192,7 @@ typedef struct {
     int32_t dilation_hw[2];       /* conv only: tap kh reads input row h*stride - pad + kh*dilation; 0 means 1 */
     int32_t groups;               /* conv only: 0 or 1 = dense; C (with K = C and wt[K,1,R,S]) = depthwise, every channel
                                      filtered by its own R x R filter.  Other group counts are not supported. */
+    int32_t window_hw[2];         /* MAXPOOL_HW: the pooling window (square: both equal), 1..16 */
 } hpct_op_desc;
 
 typedef struct hpct_plan hpct_plan;   /* opaque; host memory */

@@ -26,7 +26,7 @@ hpct_status fail(hpct_status st, const char* fmt, ...) {
 
 void clear_err() { g_err[0] = 0; }
 
-enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool, DwConv, ConvT };
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool, DwConv, ConvT, MaxPoolGen };
 
 constexpr int64_t kI32Max = 2147483647LL;
 
@@ -42,6 +42,7 @@ struct hpct_plan {
     // which in[] slot feeds which kernel operand; -1 = absent
     int32_t slot[6];
     int64_t pool_planes; int32_t pool_h, pool_w;   // Kind::MaxPool
+    PoolParams pool;                               // Kind::MaxPoolGen
     size_t ws_bytes;  // device workspace needed at launch
     union {
         GemmParams gemm;
@@ -334,6 +335,31 @@ hpct_status plan_maxpool(const hpct_op_desc& d, hpct_plan& p) {
     p.pool_planes = Nb * C; p.pool_h = (int32_t)H; p.pool_w = (int32_t)W;
     p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
     p.shape = maxpool2_shape(Nb * C, (int32_t)H, (int32_t)W);
+    return HPCT_OK;
+}
+
+// k x k max pooling with stride and padding of an NCHW tensor without an anchor.
+hpct_status plan_maxpool_gen(const hpct_op_desc& d, hpct_plan& p) {
+    if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL_HW takes no epilogues");
+    if (d.n_in != 1 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "MAXPOOL_HW takes 1 input and 1 output");
+    const hpct_tensor_desc& X = d.in[0];
+    if (X.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "X must be 4-D NCHW");
+    const int32_t k = d.window_hw[0], st = d.stride_hw[0], pad = d.pad_hw[0];
+    if (d.window_hw[1] != k || d.stride_hw[1] != st || d.pad_hw[1] != pad)
+        return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL_HW: only square windows with equal strides and padding are supported");
+    if (k < 1 || k > 16) return fail(HPCT_ERR_BAD_DESC, "MAXPOOL_HW: window %d outside 1..16", k);
+    if (st < 1 || st > 16) return fail(HPCT_ERR_BAD_DESC, "MAXPOOL_HW: stride %d outside 1..16", st);
+    if (pad < 0 || pad >= k) return fail(HPCT_ERR_BAD_DESC, "MAXPOOL_HW: padding %d must satisfy 0 <= pad < window", pad);
+    const int64_t Nb = X.shape[0], C = X.shape[1], H = X.shape[2], W = X.shape[3];
+    if (H > kI32Max / 2 || W > kI32Max / 2) return fail(HPCT_ERR_UNSUPPORTED, "plane larger than 2^30 rows or columns");
+    if (H + 2 * pad < k || W + 2 * pad < k) return fail(HPCT_ERR_SHAPE_MISMATCH, "MAXPOOL_HW: the window does not fit the padded plane");
+    const int64_t Ho = (H + 2 * pad - k) / st + 1, Wo = (W + 2 * pad - k) / st + 1;
+    REQUIRE_SHAPE(d.out[0], "out[0]", Nb, C, Ho, Wo);
+    if (!contiguous(X) || !contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "only contiguous NCHW layouts are supported");
+    p.kind = Kind::MaxPoolGen;
+    p.pool = PoolParams{Nb * C, (int32_t)H, (int32_t)W, k, st, pad};
+    p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
+    p.shape = maxpool_shape(p.pool);
     return HPCT_OK;
 }
 
@@ -667,7 +693,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
     if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONVT2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
-    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_MIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_MAXPOOL_HW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
     if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
@@ -703,6 +729,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         default:
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
             if (d.reduce == HPCT_RED_MAXPOOL2_HW) { st = plan_maxpool(d, tmp); break; }
+            if (d.reduce == HPCT_RED_MAXPOOL_HW) { st = plan_maxpool_gen(d, tmp); break; }
             if (is_eltwise_chain(d)) st = plan_eltwise(d, tmp);
             else if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);
             else if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
@@ -799,6 +826,9 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
         }
         case Kind::MaxPool:
             e = maxpool2_launch(in(0), (float*)out_ptrs[0], plan->pool_planes, plan->pool_h, plan->pool_w, stream);
+            break;
+        case Kind::MaxPoolGen:
+            e = maxpool_launch(plan->pool, in(0), (float*)out_ptrs[0], stream);
             break;
         case Kind::ConvT: {
             const ConvTParams& t = plan->convt;

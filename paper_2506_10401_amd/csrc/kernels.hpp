@@ -40,6 +40,10 @@ LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool);
 // 2x2 / stride-2 max pooling of [planes, H, W] -> [planes, H/2, W/2]
 LaunchShape maxpool2_shape(int64_t planes, int32_t H, int32_t W);
 hipError_t maxpool2_launch(const float* X, float* out, int64_t planes, int32_t H, int32_t W, hipStream_t stream);
+// k_maxpool.hip: k x k max pooling with stride and padding (pad < k; padding never wins); 2 x 2 / 2 / 0 goes to maxpool2
+struct PoolParams { int64_t planes; int32_t H, W, k, stride, pad; };
+LaunchShape maxpool_shape(const PoolParams& p);
+hipError_t maxpool_launch(const PoolParams& p, const float* in, float* out, hipStream_t stream);
 hipError_t affine_launch(const AffineParams& p, hipStream_t stream);
 
 // ---- layout transform: out = contiguous copy of a strided view (Table 1: LayoutTransform)

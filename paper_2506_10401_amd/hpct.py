@@ -29,7 +29,7 @@ HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL
     HPCT_EPI_SIGMOID, HPCT_EPI_RELU6 = range(19)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS, HPCT_RED_MAX_AXIS, \
-    HPCT_RED_MIN_AXIS = range(12)
+    HPCT_RED_MIN_AXIS, HPCT_RED_MAXPOOL_HW = range(13)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
 
 
@@ -43,7 +43,8 @@ class OpDesc(C.Structure):
                 ("reduce_before_epi", C.c_int32), ("n_in", C.c_int32), ("in_", TensorDesc * HPCT_MAX_IN),
                 ("n_out", C.c_int32), ("out", TensorDesc * HPCT_MAX_OUT), ("stride_hw", C.c_int32 * 2),
                 ("pad_hw", C.c_int32 * 2), ("eps", C.c_float), ("scale", C.c_float), ("dropout_p", C.c_float),
-                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64), ("axis", C.c_int32), ("dilation_hw", C.c_int32 * 2), ("groups", C.c_int32)]
+                ("reduce2", C.c_int), ("dropout_seed", C.c_uint64), ("axis", C.c_int32), ("dilation_hw", C.c_int32 * 2), ("groups", C.c_int32),
+                ("window_hw", C.c_int32 * 2)]
 
 
 class HpctError(RuntimeError):
@@ -116,7 +117,7 @@ def tensor_desc(shape: Sequence[int], stride: Optional[Sequence[int]] = None, dt
 
 def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before_epi=0, inputs=(), outputs=(),
             stride_hw=(1, 1), pad_hw=(0, 0), eps=0.0, scale=1.0, dropout_p=0.0, dropout_seed=0,
-            reduce2=HPCT_RED_NONE, axis=0, dilation_hw=(1, 1), groups=0) -> OpDesc:
+            reduce2=HPCT_RED_NONE, axis=0, dilation_hw=(1, 1), groups=0, window_hw=(0, 0)) -> OpDesc:
     d = OpDesc()
     d.anchor = anchor
     d.n_epi = len(epi)
@@ -140,6 +141,7 @@ def op_desc(anchor=HPCT_ANCHOR_NONE, epi=(), reduce=HPCT_RED_NONE, reduce_before
     d.axis = axis
     d.dilation_hw[0], d.dilation_hw[1] = dilation_hw
     d.groups = groups
+    d.window_hw[0], d.window_hw[1] = window_hw
     return d
 
 
@@ -345,6 +347,20 @@ def maxpool2x2_plan(X, out):
 def maxpool2x2(X, out, stream=None) -> None:
     """out[n,c,y,x] = max of the 2x2 window of X[n,c] at (2y, 2x); odd trailing rows / columns are dropped."""
     plan, ins = maxpool2x2_plan(X, out)
+    plan.launch(ins, [out], stream)
+
+
+def maxpool_plan(X, out, window, stride, pad=0):
+    plan = _cached(("maxpool", _sh(X), window, stride, pad), lambda: op_desc(
+        HPCT_ANCHOR_NONE, [], HPCT_RED_MAXPOOL_HW, 0, [_sh(X)], [_sh(out)], stride_hw=(stride, stride), pad_hw=(pad, pad),
+        window_hw=(window, window)))
+    return plan, [X]
+
+
+def maxpool(X, out, window, stride, pad=0, stream=None) -> None:
+    """out[n,c,y,x] = max of the window x window positions of X[n,c] from (y stride - pad, x stride - pad) that lie
+    inside the image (pad < window); out extents (H + 2 pad - window) // stride + 1."""
+    plan, ins = maxpool_plan(X, out, window, stride, pad)
     plan.launch(ins, [out], stream)
 
 

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_the_c_layout():
     # int32 + pad + 6*int64 + 6*int64 + enum + pad
     assert C.sizeof(H.TensorDesc) == 112
-    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4 + 4 + 4 + 8 + 4 + 8 + 4
+    assert C.sizeof(H.OpDesc) == 4 + 4 + 8 * 4 + 4 + 4 + 4 + 4 + 8 * 112 + 4 + 4 + 2 * 112 + 8 + 8 + 4 + 4 + 4 + 4 + 8 + 4 + 8 + 4 + 8
     # and the library reports the same sizes for the structs it was compiled with
     lib = H.load()
     assert lib.hpct_sizeof_tensor_desc() == C.sizeof(H.TensorDesc)
@@ -468,7 +468,7 @@ def test_axis_reduction_errors():
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_ARGMAX_AXIS, out_dtype=H.HPCT_F32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS, out_dtype=H.HPCT_I32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_MAX_AXIS, out_dtype=H.HPCT_I32))
-    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 12))      # one past MIN_AXIS
+    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 13))      # one past the last reduction
     d = cfg_desc(3); d.out[0].dtype = H.HPCT_I32          # int32 anywhere else
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.n_epi = 1; d.epi[0] = H.HPCT_EPI_RELU
@@ -658,6 +658,37 @@ def test_conv_few_input_channels_plans():
     for d in (cd((32, 3, 224, 224), 48), cd((32, 3, 224, 224), 64, stride=2), cd((32, 3, 224, 224), 64, pad=0),
               cd((32, 3, 224, 224), 64, pool=True), cd((32, 3, 224, 222), 64), cd((32, 5, 224, 224), 64), cd((2, 3, 32, 32), 64)):
         assert H.Plan(d).kernel_name.startswith("conv2d_nchw_mfma<3x3")
+
+
+def pool_desc(shape, k, stride, pad, out_shape=None, epi=()):
+    Nb, Cc, Hh, Ww = shape
+    if out_shape is None:
+        out_shape = (Nb, Cc, (Hh + 2 * pad - k) // stride + 1, (Ww + 2 * pad - k) // stride + 1)
+    return H.op_desc(H.HPCT_ANCHOR_NONE, list(epi), H.HPCT_RED_MAXPOOL_HW, 0, [shape], [out_shape], stride_hw=(stride, stride),
+                     pad_hw=(pad, pad), window_hw=(k, k))
+
+
+def test_maxpool_plans_and_errors():
+    # a ResNet's pooling: 3x3 / 2 / pad 1 on 112 x 112: a wave per 56 output columns x 16 output rows
+    p = H.Plan(pool_desc((32, 64, 112, 112), 3, 2, 1))
+    assert p.kernel_name == "maxpool3x3_rows<stride2>" and p.launch_shape() == ((32 * 64 * 4 // 4, 1, 1), (256, 1, 1), 0)
+    assert H.Plan(pool_desc((8, 16, 56, 56), 3, 1, 1)).kernel_name == "maxpool3x3_rows"
+    # 2x2 / 2 / 0 is the VGG pooling's kernel
+    assert H.Plan(pool_desc((32, 64, 56, 56), 2, 2, 0)).kernel_name == "maxpool2_planes<vec4>"
+    # anything else: an output per thread
+    for (shape, k, s, pad) in [((2, 3, 30, 30), 3, 2, 1), ((2, 3, 112, 112), 3, 2, 0), ((2, 3, 57, 57), 5, 3, 2), ((1, 1, 7, 7), 7, 1, 0),
+                               ((2, 3, 112, 110), 3, 2, 1)]:
+        assert H.Plan(pool_desc(shape, k, s, pad)).kernel_name == "maxpool_any"
+    expect(H.HPCT_ERR_BAD_DESC, pool_desc((2, 3, 8, 8), 3, 2, 3))                    # padding as large as the window
+    expect(H.HPCT_ERR_BAD_DESC, pool_desc((2, 3, 8, 8), 0, 1, 0, out_shape=(2, 3, 8, 8)))
+    expect(H.HPCT_ERR_BAD_DESC, pool_desc((2, 3, 8, 8), 3, 0, 1, out_shape=(2, 3, 8, 8)))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, pool_desc((2, 3, 8, 8), 3, 2, 1, out_shape=(2, 3, 5, 4)))
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, pool_desc((2, 3, 2, 2), 5, 1, 0, out_shape=(2, 3, 1, 1)))
+    expect(H.HPCT_ERR_UNSUPPORTED, pool_desc((2, 3, 8, 8), 3, 2, 1, epi=(H.HPCT_EPI_RELU,)))
+    d = pool_desc((2, 3, 8, 8), 3, 2, 1); d.window_hw[1] = 2
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = pool_desc((2, 3, 8, 8), 3, 2, 1); d.anchor = H.HPCT_ANCHOR_GEMM
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
 
 
 def test_depthwise_conv_plans():

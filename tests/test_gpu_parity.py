@@ -1031,6 +1031,44 @@ def test_conv_transpose_tiles_with_a_2x2_filter_of_ones():
     assert np.array_equal(got[:, :, ::2, ::2], x) and np.all(got[:, :, 1::2, :] == 0) and np.all(got[:, :, :, 1::2] == 0)
 
 
+# ---------------------------------------- max pooling with a window, a stride and padding
+def check_maxpool(shape, k, stride, pad, seed=0, shift=-1.0):
+    x = datagen.gen_normal(700 + seed, shape, shift, 1.0)       # mostly negative: a zero padding would win
+    want = ref.maxpool2d(x, k, stride, pad)
+    out = torch.full(want.shape, float("nan"), device="cuda")
+    plan, ins = hpct.maxpool_plan(dev(x), out, k, stride, pad)
+    plan.launch(ins, [out])
+    got = host(out)
+    assert np.array_equal(got.astype(np.float64), want), (shape, k, stride, pad, plan.kernel_name)   # a selection: exact
+    return plan.kernel_name
+
+
+def test_maxpool_full_size():
+    # the pooling behind a ResNet's first convolution at batch 32, and a 3x3 / 1 / 1 pooling of an inception-style branch
+    assert check_maxpool((32, 64, 112, 112), 3, 2, 1) == "maxpool3x3_rows<stride2>"
+    assert check_maxpool((32, 64, 56, 56), 3, 1, 1) == "maxpool3x3_rows"
+    assert check_maxpool((32, 64, 56, 56), 2, 2, 0) == "maxpool2_planes<vec4>"
+
+
+@pytest.mark.parametrize("shape,k,stride,pad", [
+    ((2, 3, 57, 112), 3, 2, 1), ((1, 2, 112, 104), 3, 2, 1), ((1, 4, 31, 96), 3, 2, 1), ((2, 2, 1, 104), 3, 2, 1), ((1, 2, 100, 336), 3, 2, 1),
+    ((1, 3, 2, 400), 3, 2, 1), ((2, 3, 57, 56), 3, 1, 1), ((1, 5, 30, 112), 3, 1, 1), ((1, 2, 100, 48), 3, 1, 1), ((2, 2, 5, 52), 3, 1, 1),
+    ((1, 2, 1, 56), 3, 1, 1), ((1, 3, 29, 168), 3, 1, 1)])
+def test_maxpool_3x3_register_variant(shape, k, stride, pad):
+    print("maxpool rows %s" % ((shape, k, stride, pad),), flush=True)
+    assert check_maxpool(shape, k, stride, pad).startswith("maxpool3x3_rows")
+    check_maxpool(shape, k, stride, pad, seed=1, shift=2.0)
+
+
+@pytest.mark.parametrize("shape,k,stride,pad", [
+    ((2, 3, 30, 30), 3, 2, 1), ((2, 3, 17, 23), 3, 2, 0), ((1, 3, 57, 57), 5, 3, 2), ((1, 1, 7, 7), 7, 1, 0), ((2, 3, 20, 110), 3, 2, 1),
+    ((1, 2, 9, 9), 1, 2, 0), ((3, 1, 5, 5), 4, 4, 0), ((1, 2, 6, 40), 2, 1, 1), ((1, 1, 3, 3), 3, 1, 2), ((2, 2, 33, 31), 16, 5, 7),
+    ((1, 1, 1, 1), 1, 1, 0)])
+def test_maxpool_general_windows(shape, k, stride, pad):
+    print("maxpool any %s" % ((shape, k, stride, pad),), flush=True)
+    assert check_maxpool(shape, k, stride, pad) == "maxpool_any"
+
+
 # ---------------------------------------- depthwise conv (MobileNetV2's depthwise layer) and relu6
 def check_depthwise(N, C, H, W, R, stride, pad, dil=1, act="relu6", bias=True, affine=True, seed=0):
     x = datagen.gen_normal(300 + seed, (N, C, H, W), 0.0, 1.0)
