@@ -134,6 +134,36 @@ void ref_layernorm_rows(const float *X, const float *gamma, const float *beta,
     }
 }
 
+/* ---- Reduction: group normalisation of an NCHW tensor (the "norm" of the
+ * activation-and-norm fusions that Section 5.1 describes as Level-2 tasks; G = C is
+ * instance normalisation, G = 1 layer normalisation over C, H and W).  The C
+ * channels are split into G groups of C/G neighbours; for image n and group g
+ *   mu = mean of x over the group's (C/G) H W elements, var = mean of (x - mu)^2 (biased),
+ *   y[n][c][i] = (x[n][c][i] - mu) / sqrt(var + eps) * gamma[c] + beta[c].
+ * gamma / beta may be NULL (= 1 / 0). */
+void ref_groupnorm_nchw(const float *X, const float *gamma, const float *beta,
+                        int64_t Nb, int64_t C, int64_t HW, int64_t G, double eps, double *Y)
+{
+    const int64_t Cg = C / G, L = Cg * HW;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < Nb * G; ++r) {
+        const int64_t g = r % G;
+        const float *x = X + r * L;
+        double mu = 0.0;
+        for (int64_t i = 0; i < L; ++i) mu += (double)x[i];
+        mu /= (double)L;
+        double var = 0.0;
+        for (int64_t i = 0; i < L; ++i) { double d = (double)x[i] - mu; var += d * d; }
+        var /= (double)L;
+        double inv = 1.0 / sqrt(var + eps);
+        for (int64_t i = 0; i < L; ++i) {
+            int64_t c = g * Cg + i / HW;
+            double ga = gamma ? (double)gamma[c] : 1.0, be = beta ? (double)beta[c] : 0.0;
+            Y[r * L + i] = ((double)x[i] - mu) * inv * ga + be;
+        }
+    }
+}
+
 /* ---- Elementwise: tanh-form GELU, in place -------------------------------
  * 0.5 y (1 + tanh(sqrt(2/pi) (y + 0.044715 y^3))) */
 void ref_gelu_tanh(double *Y, int64_t count)

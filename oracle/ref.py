@@ -46,6 +46,7 @@ def lib():
             "ref_scale_shift_planes": [p, p, p, i64, i64, i64],
             "ref_maxpool2x2_planes": [p, i64, i64, i64, p],
             "ref_maxpool2d_planes": [p, i64, i64, i64, i64, i64, i64, p],
+            "ref_groupnorm_nchw": [p, p, p, i64, i64, i64, i64, dbl, p],
             "ref_reduce_axis": [p, C.c_int32, p, p, C.c_int32, C.c_int32, p, p, p],
             "ref_eltwise_binary": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p],
             "ref_eltwise_map": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p, C.c_float, p],
@@ -135,6 +136,19 @@ def layernorm_rows(X, gamma=None, beta=None, eps=1e-5):
     b = None if beta is None else _f32(beta)
     Y = np.empty((rows, N), dtype=np.float64)
     lib().ref_layernorm_rows(_ptr(X), _ptr(g), _ptr(b), rows, N, float(eps), _ptr(Y))
+    return Y
+
+
+def groupnorm_nchw(X, groups, gamma=None, beta=None, eps=1e-5):
+    """Group normalisation of an fp32 NCHW array: statistics per image and group of C // groups neighbouring channels,
+    gamma / beta per channel.  groups = C: instance normalisation."""
+    X = _f32(X)
+    Nb, Cc, H, W = X.shape
+    assert groups >= 1 and Cc % groups == 0
+    g = None if gamma is None else _f32(gamma)
+    b = None if beta is None else _f32(beta)
+    Y = np.empty(X.shape, dtype=np.float64)
+    lib().ref_groupnorm_nchw(_ptr(X), _ptr(g), _ptr(b), Nb, Cc, H * W, groups, float(eps), _ptr(Y))
     return Y
 
 

@@ -645,6 +645,45 @@ def test_reduce_axis_against_numpy_on_strided_views():
             assert np.array_equal(ref.reduce_axis(base, shape, stride, axis, "argmin"), v.argmin(axis=axis))
 
 
+def test_groupnorm_reduces_to_layernorm_and_closed_forms():
+    rng = np.random.default_rng(31)
+    X = (rng.standard_normal((3, 12, 5, 7)) * 2.0 + 0.7).astype(np.float32)
+    ga = rng.standard_normal(12).astype(np.float32)
+    be = rng.standard_normal(12).astype(np.float32)
+    # one group: layer normalisation of each image over C*H*W, whose gamma / beta repeat each channel's value over its plane
+    ln = ref.layernorm_rows(X.reshape(3, -1), np.repeat(ga, 35), np.repeat(be, 35), 1e-5).reshape(X.shape)
+    assert np.allclose(ref.groupnorm_nchw(X, 1, ga, be, 1e-5), ln, rtol=0, atol=1e-12)
+    # G groups: layer normalisation of the [N*G, (C/G)*H*W] matrix without affine, then the per-channel affine
+    for G in (2, 3, 4, 12):
+        plain = ref.layernorm_rows(X.reshape(3 * G, -1), None, None, 1e-5).reshape(X.shape)
+        want = plain * ga.astype(np.float64)[None, :, None, None] + be.astype(np.float64)[None, :, None, None]
+        assert np.allclose(ref.groupnorm_nchw(X, G, ga, be, 1e-5), want, rtol=0, atol=1e-12), G
+    # without affine every group has mean 0 and variance var / (var + eps)
+    Y = ref.groupnorm_nchw(X, 4, None, None, 1e-3).reshape(3, 4, -1)
+    var = X.astype(np.float64).reshape(3, 4, -1).var(axis=2)
+    assert np.allclose(Y.mean(axis=2), 0.0, atol=1e-12) and np.allclose(Y.var(axis=2), var / (var + 1e-3), rtol=1e-12)
+    # instance normalisation of a plane of +-1 in equal numbers: mean 0, variance 1 -> +-1 / sqrt(1 + eps)
+    P = np.ones((1, 2, 4, 6), np.float32); P[:, :, :, ::2] = -1.0
+    assert np.allclose(ref.groupnorm_nchw(P, 2, None, None, 0.21), P / np.sqrt(1.21), rtol=0, atol=1e-15)
+    # shifting and scaling the input (a > 0) changes nothing as eps -> 0; a constant group gives beta
+    a = ref.groupnorm_nchw(X, 3, ga, be, 0.0)
+    b = ref.groupnorm_nchw((X.astype(np.float64) * 4.0 + 8.0).astype(np.float32), 3, ga, be, 0.0)
+    assert np.allclose(a, b, rtol=0, atol=1e-5)
+    Cst = np.full((2, 4, 3, 3), 2.5, np.float32)
+    assert np.array_equal(ref.groupnorm_nchw(Cst, 2, ga[:4], be[:4], 1e-5), np.broadcast_to(be[:4].astype(np.float64)[None, :, None, None], Cst.shape))
+    # brute force on a tiny case, element by element
+    T = rng.standard_normal((2, 4, 2, 3)).astype(np.float32)
+    Yt = ref.groupnorm_nchw(T, 2, ga[:4], be[:4], 1e-2)
+    for n in range(2):
+        for c in range(4):
+            grp = T[n, (c // 2) * 2:(c // 2) * 2 + 2].astype(np.float64).ravel()
+            mu = sum(grp) / len(grp)
+            var = sum((v - mu) ** 2 for v in grp) / len(grp)
+            for h in range(2):
+                for w in range(3):
+                    assert abs(Yt[n, c, h, w] - ((float(T[n, c, h, w]) - mu) / (var + 1e-2) ** 0.5 * float(ga[c]) + float(be[c]))) < 1e-12
+
+
 def test_maxpool2d_against_sliding_windows_and_special_cases():
     # numpy: pad with -inf, take every window with sliding_window_view, subsample by the stride
     rng = np.random.default_rng(21)
