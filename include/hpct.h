@@ -58,6 +58,8 @@
  *         `axis`, no epilogue
  *                                                                                   (1-D input: shape [1]);
  *                                                                                   int32 for the arg ops
+ *   NONE  GROUPNORM_NCHW (groups, eps) [+RELU]         X[N,C,H,W], gamma[C],         [N,C,H,W]
+ *         (reduce_before_epi = 1 with the ReLU)        beta[C] (or X alone)
  *   NONE  MAXPOOL_HW (window_hw, stride_hw, pad_hw,    X[N,C,H,W]                    [N,C,Ho,Wo]
  *         each square), no epilogue
  *   CONVT2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH]        in[N,C,H,W], wt[C,K,R,S],     [N,K,Ho,Wo]
@@ -166,8 +168,11 @@ typedef enum {
     HPCT_RED_ARGMIN_AXIS = 9,     /* int32 index of the minimum along dim `axis`; of equal values the lowest index */
     HPCT_RED_MAX_AXIS = 10,       /* maximum over dim `axis`, which is dropped (fp32) */
     HPCT_RED_MIN_AXIS = 11,       /* minimum over dim `axis`, which is dropped (fp32) */
-    HPCT_RED_MAXPOOL_HW = 12      /* max over window_hw windows of dims 2,3 of NCHW at stride_hw with pad_hw (padding never
+    HPCT_RED_MAXPOOL_HW = 12,     /* max over window_hw windows of dims 2,3 of NCHW at stride_hw with pad_hw (padding never
                                      wins; pad < window); output extent (H + 2 pad - window) / stride + 1.  No anchor. */
+    HPCT_RED_GROUPNORM_NCHW = 13  /* group normalisation of X[N,C,H,W] with `groups` groups of C / groups neighbouring channels:
+                                     (x - mean) / sqrt(biased var + eps) over each image's group, * gamma[c] + beta[c];
+                                     groups = C is instance normalisation.  No anchor; reduce_before_epi = 1 with an epilogue. */
 } hpct_reduce;
 
 typedef struct {
@@ -190,7 +195,7 @@ typedef struct {
     uint64_t dropout_seed;        /* DROPOUT_HASH */
     int32_t axis;                 /* *_AXIS reductions: the dimension of in[0] that is reduced, 0 <= axis < ndim */
     int32_t dilation_hw[2];       /* conv only: tap kh reads input row h*stride - pad + kh*dilation; 0 means 1 */
-    int32_t groups;               /* conv only: 0 or 1 = dense; C (with K = C and wt[K,1,R,S]) = depthwise, every channel
+    int32_t groups;               /* GROUPNORM_NCHW: the number of groups.  Conv: 0 or 1 = dense; C (with K = C and wt[K,1,R,S]) = depthwise, every channel
                                      filtered by its own R x R filter.  Other group counts are not supported. */
     int32_t window_hw[2];         /* MAXPOOL_HW: the pooling window (square: both equal), 1..16 */
 } hpct_op_desc;

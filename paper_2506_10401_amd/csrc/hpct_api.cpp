@@ -26,7 +26,7 @@ hpct_status fail(hpct_status st, const char* fmt, ...) {
 
 void clear_err() { g_err[0] = 0; }
 
-enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool, DwConv, ConvT, MaxPoolGen };
+enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool, DwConv, ConvT, MaxPoolGen, Groupnorm };
 
 constexpr int64_t kI32Max = 2147483647LL;
 
@@ -43,6 +43,7 @@ struct hpct_plan {
     int32_t slot[6];
     int64_t pool_planes; int32_t pool_h, pool_w;   // Kind::MaxPool
     PoolParams pool;                               // Kind::MaxPoolGen
+    GroupnormParams gn;                            // Kind::Groupnorm
     size_t ws_bytes;  // device workspace needed at launch
     union {
         GemmParams gemm;
@@ -360,6 +361,33 @@ hpct_status plan_maxpool_gen(const hpct_op_desc& d, hpct_plan& p) {
     p.pool = PoolParams{Nb * C, (int32_t)H, (int32_t)W, k, st, pad};
     p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
     p.shape = maxpool_shape(p.pool);
+    return HPCT_OK;
+}
+
+// Group normalisation of an NCHW tensor [+ ReLU] without an anchor.
+hpct_status plan_groupnorm(const hpct_op_desc& d, hpct_plan& p) {
+    bool relu = false;
+    if (d.n_epi == 1 && d.epi[0] == HPCT_EPI_RELU) relu = true;
+    else if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "GROUPNORM_NCHW: the only epilogue supported is RELU");
+    if (relu && !d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "GROUPNORM_NCHW with RELU needs reduce_before_epi = 1");
+    if ((d.n_in != 3 && d.n_in != 1) || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "GROUPNORM_NCHW takes X, gamma, beta (or X alone) and 1 output");
+    const hpct_tensor_desc& X = d.in[0];
+    if (X.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "X must be 4-D NCHW");
+    const int64_t Nb = X.shape[0], C = X.shape[1], H = X.shape[2], W = X.shape[3];
+    if (d.groups < 1 || C % d.groups != 0) return fail(HPCT_ERR_BAD_DESC, "GROUPNORM_NCHW: groups = %d must divide C = %lld", d.groups, (long long)C);
+    if (d.n_in == 3) { REQUIRE_SHAPE(d.in[1], "gamma", C); REQUIRE_SHAPE(d.in[2], "beta", C); }
+    REQUIRE_SHAPE(d.out[0], "out[0]", Nb, C, H, W);
+    for (int i = 0; i < d.n_in; ++i)
+        if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous layouts are supported", i);
+    if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous layouts are supported");
+    if (!(d.eps >= 0.f)) return fail(HPCT_ERR_BAD_DESC, "eps must be >= 0");
+    const int64_t Cg = C / d.groups;
+    if (H * W > kI32Max || Cg * H * W > kI32Max || Nb * d.groups > kI32Max)
+        return fail(HPCT_ERR_UNSUPPORTED, "GROUPNORM_NCHW: more than 2^31-1 elements per group, or groups in all");
+    p.kind = Kind::Groupnorm;
+    p.gn = GroupnormParams{nullptr, nullptr, nullptr, nullptr, Nb, d.groups, (int32_t)Cg, (int32_t)(H * W), d.eps, relu ? 1 : 0};
+    p.slot[0] = 0; p.slot[1] = d.n_in == 3 ? 1 : -1; p.slot[2] = d.n_in == 3 ? 2 : -1; p.slot[3] = p.slot[4] = p.slot[5] = -1;
+    p.shape = groupnorm_shape(p.gn);
     return HPCT_OK;
 }
 
@@ -693,7 +721,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
     if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONVT2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
-    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_MAXPOOL_HW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_GROUPNORM_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
     if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
@@ -730,6 +758,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
             if (d.reduce == HPCT_RED_MAXPOOL2_HW) { st = plan_maxpool(d, tmp); break; }
             if (d.reduce == HPCT_RED_MAXPOOL_HW) { st = plan_maxpool_gen(d, tmp); break; }
+            if (d.reduce == HPCT_RED_GROUPNORM_NCHW) { st = plan_groupnorm(d, tmp); break; }
             if (is_eltwise_chain(d)) st = plan_eltwise(d, tmp);
             else if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);
             else if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
@@ -827,6 +856,13 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
         case Kind::MaxPool:
             e = maxpool2_launch(in(0), (float*)out_ptrs[0], plan->pool_planes, plan->pool_h, plan->pool_w, stream);
             break;
+        case Kind::Groupnorm: {
+            GroupnormParams q = plan->gn;
+            q.X = in(0); q.gamma = plan->slot[1] >= 0 ? in(1) : nullptr; q.beta = plan->slot[2] >= 0 ? in(2) : nullptr;
+            q.Y = (float*)out_ptrs[0];
+            e = groupnorm_launch(q, stream);
+            break;
+        }
         case Kind::MaxPoolGen:
             e = maxpool_launch(plan->pool, in(0), (float*)out_ptrs[0], stream);
             break;

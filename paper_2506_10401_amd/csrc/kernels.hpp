@@ -46,6 +46,14 @@ LaunchShape maxpool_shape(const PoolParams& p);
 hipError_t maxpool_launch(const PoolParams& p, const float* in, float* out, hipStream_t stream);
 hipError_t affine_launch(const AffineParams& p, hipStream_t stream);
 
+// ---- group normalisation of NCHW [+ ReLU] (k_groupnorm.hip); rows of more than 2^31-1 elements are refused by the plan
+struct GroupnormParams {
+    const float* X; const float* gamma; const float* beta; float* Y;
+    int64_t Nb; int32_t G, Cg, HW; float eps; int32_t relu;
+};
+LaunchShape groupnorm_shape(const GroupnormParams& p);
+hipError_t groupnorm_launch(const GroupnormParams& p, hipStream_t stream);
+
 // ---- layout transform: out = contiguous copy of a strided view (Table 1: LayoutTransform)
 constexpr int kLayoutDims = 6;
 struct LayoutParams {

@@ -29,7 +29,7 @@ HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL
     HPCT_EPI_SIGMOID, HPCT_EPI_RELU6 = range(19)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS, HPCT_RED_MAX_AXIS, \
-    HPCT_RED_MIN_AXIS, HPCT_RED_MAXPOOL_HW = range(13)
+    HPCT_RED_MIN_AXIS, HPCT_RED_MAXPOOL_HW, HPCT_RED_GROUPNORM_NCHW = range(14)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
 
 
@@ -347,6 +347,22 @@ def maxpool2x2_plan(X, out):
 def maxpool2x2(X, out, stream=None) -> None:
     """out[n,c,y,x] = max of the 2x2 window of X[n,c] at (2y, 2x); odd trailing rows / columns are dropped."""
     plan, ins = maxpool2x2_plan(X, out)
+    plan.launch(ins, [out], stream)
+
+
+def groupnorm_plan(X, gamma, beta, out, groups, eps=1e-5, relu=False):
+    """Group normalisation of X[N,C,H,W] (groups = C: instance normalisation) with per-channel gamma / beta (both or
+    neither) and an optional ReLU behind it."""
+    assert (gamma is None) == (beta is None)
+    ins = [X] + ([gamma, beta] if gamma is not None else [])
+    plan = _cached(("groupnorm", _sh(X), groups, eps, relu, gamma is not None), lambda: op_desc(
+        HPCT_ANCHOR_NONE, [HPCT_EPI_RELU] if relu else [], HPCT_RED_GROUPNORM_NCHW, 1, [_sh(t) for t in ins], [_sh(out)],
+        eps=eps, groups=groups))
+    return plan, ins
+
+
+def groupnorm(X, gamma, beta, out, groups, eps=1e-5, relu=False, stream=None) -> None:
+    plan, ins = groupnorm_plan(X, gamma, beta, out, groups, eps, relu)
     plan.launch(ins, [out], stream)
 
 

@@ -468,7 +468,7 @@ def test_axis_reduction_errors():
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_ARGMAX_AXIS, out_dtype=H.HPCT_F32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS, out_dtype=H.HPCT_I32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_MAX_AXIS, out_dtype=H.HPCT_I32))
-    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 13))      # one past the last reduction
+    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 14))      # one past the last reduction
     d = cfg_desc(3); d.out[0].dtype = H.HPCT_I32          # int32 anywhere else
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.n_epi = 1; d.epi[0] = H.HPCT_EPI_RELU
@@ -658,6 +658,36 @@ def test_conv_few_input_channels_plans():
     for d in (cd((32, 3, 224, 224), 48), cd((32, 3, 224, 224), 64, stride=2), cd((32, 3, 224, 224), 64, pad=0),
               cd((32, 3, 224, 224), 64, pool=True), cd((32, 3, 224, 222), 64), cd((32, 5, 224, 224), 64), cd((2, 3, 32, 32), 64)):
         assert H.Plan(d).kernel_name.startswith("conv2d_nchw_mfma<3x3")
+
+
+def gn_desc(shape=(32, 64, 56, 56), groups=8, affine=True, relu=False, rbe=1, eps=1e-5):
+    Cc = shape[1]
+    ins = [shape] + ([(Cc,), (Cc,)] if affine else [])
+    return H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_RELU] if relu else [], H.HPCT_RED_GROUPNORM_NCHW, rbe, ins, [shape],
+                     eps=eps, groups=groups)
+
+
+def test_groupnorm_plans_and_errors():
+    # a work-group per (image, group); rows of up to 8192 elements stay in registers
+    p = H.Plan(gn_desc())
+    assert p.kernel_name == "groupnorm_rows<registers,1024>" and p.launch_shape()[:2] == ((32 * 8, 1, 1), (1024, 1, 1)) and p.workspace_bytes == 0
+    assert H.Plan(gn_desc(shape=(2, 64, 112, 112), groups=8)).kernel_name == "groupnorm_rows<three passes>"
+    assert H.Plan(gn_desc(groups=32, relu=True)).kernel_name == "groupnorm_rows<registers>"
+    p = H.Plan(gn_desc(groups=64, affine=False))                       # instance normalisation
+    assert p.kernel_name == "groupnorm_rows<registers>" and p.launch_shape()[0] == (32 * 64, 1, 1)
+    assert H.Plan(gn_desc(shape=(2, 6, 7, 9), groups=3)).kernel_name == "groupnorm_rows_any"
+    expect(H.HPCT_ERR_BAD_DESC, gn_desc(groups=0))
+    expect(H.HPCT_ERR_BAD_DESC, gn_desc(groups=5))                     # does not divide 64
+    expect(H.HPCT_ERR_BAD_DESC, gn_desc(eps=-1.0))
+    expect(H.HPCT_ERR_UNSUPPORTED, gn_desc(relu=True, rbe=0))
+    d = gn_desc(); d.epi[0] = H.HPCT_EPI_GELU_TANH; d.n_epi = 1
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = gn_desc(); d.in_[1].shape[0] = 63
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = gn_desc(); d.n_in = 2
+    expect(H.HPCT_ERR_BAD_DESC, d)
+    d = gn_desc(); d.out[0].shape[3] = 55
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
 
 
 def pool_desc(shape, k, stride, pad, out_shape=None, epi=()):

@@ -1031,6 +1031,37 @@ def test_conv_transpose_tiles_with_a_2x2_filter_of_ones():
     assert np.array_equal(got[:, :, ::2, ::2], x) and np.all(got[:, :, 1::2, :] == 0) and np.all(got[:, :, :, 1::2] == 0)
 
 
+# ---------------------------------------- group / instance normalisation of NCHW
+def check_groupnorm(shape, groups, affine=True, relu=False, eps=1e-5, seed=0):
+    x = datagen.gen_normal(800 + seed, shape, 0.5, 2.0)
+    C_ = shape[1]
+    ga = datagen.gen_normal(801 + seed, (C_,), 1.0, 0.2) if affine else None
+    be = datagen.gen_normal(802 + seed, (C_,), 0.0, 0.3) if affine else None
+    want = ref.groupnorm_nchw(x, groups, ga, be, eps)
+    if relu:
+        want = ref.relu(want)
+    out = torch.full(shape, float("nan"), device="cuda")
+    plan, ins = hpct.groupnorm_plan(dev(x), None if ga is None else dev(ga), None if be is None else dev(be), out, groups, eps, relu)
+    plan.launch(ins, [out])
+    assert show("groupnorm %s %s G=%d" % (plan.kernel_name, shape, groups), compare.pointwise(host(out), want))
+    return plan.kernel_name
+
+
+def test_groupnorm_full_size():
+    assert check_groupnorm((32, 64, 56, 56), 8) == "groupnorm_rows<registers,1024>"
+    assert check_groupnorm((4, 32, 112, 112), 4) == "groupnorm_rows<three passes>"
+    assert check_groupnorm((32, 64, 56, 56), 32, relu=True) == "groupnorm_rows<registers>"
+    assert check_groupnorm((32, 64, 56, 56), 64, affine=False) == "groupnorm_rows<registers>"      # instance normalisation
+
+
+@pytest.mark.parametrize("shape,groups", [((2, 6, 7, 9), 3), ((1, 4, 1, 1), 2), ((3, 8, 2, 2), 8), ((2, 12, 5, 4), 1), ((1, 2, 64, 66), 1),
+                                          ((2, 10, 6, 6), 5), ((1, 16, 32, 32), 2), ((2, 3, 3, 3), 3), ((1, 8, 30, 34), 4)])
+def test_groupnorm_ragged_shapes(shape, groups):
+    print("groupnorm %s G=%d" % (shape, groups), flush=True)
+    check_groupnorm(shape, groups)
+    check_groupnorm(shape, groups, affine=False, relu=True, eps=1e-3, seed=1)
+
+
 # ---------------------------------------- max pooling with a window, a stride and padding
 def check_maxpool(shape, k, stride, pad, seed=0, shift=-1.0):
     x = datagen.gen_normal(700 + seed, shape, shift, 1.0)       # mostly negative: a zero padding would win
