@@ -31,6 +31,8 @@
  *
  *   chain                                             in[]                          out[0]
  *   GEMM [+BIAS_COL] [+SCALE_CONST] [+RELU]           X[M,K], W[K,N], bias[N]       [M,N]
+ *         (in every GEMM chain RELU6, GELU_TANH,
+ *         SIGMOID or TANH may stand for RELU)
  *         [+DROPOUT_HASH] [+SOFTMAX_LAST] (one        (W row-major, strides (N,1),
  *         kernel for N <= 256, GEMM then an           or stored transposed as an
  *         in-place row softmax beyond)                [N,K] array: strides (1,K))

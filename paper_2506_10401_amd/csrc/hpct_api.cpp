@@ -130,10 +130,25 @@ uint32_t dropout_threshold(float p) {
 }
 
 hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
+    // one activation - RELU, RELU6, GELU_TANH, SIGMOID or TANH - may stand where RELU does; `act` is activate()'s code for it
     static const hpct_epilogue order[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_CONST, HPCT_EPI_RELU, HPCT_EPI_DROPOUT_HASH};
+    hpct_op_desc dd = d;
+    int act = 0;
+    for (int e = 0; e < dd.n_epi && e < HPCT_MAX_EPI; ++e) {
+        int code = 0;
+        switch (dd.epi[e]) {
+            case HPCT_EPI_RELU: code = 1; break;
+            case HPCT_EPI_RELU6: code = 2; break;
+            case HPCT_EPI_GELU_TANH: code = 3; break;
+            case HPCT_EPI_SIGMOID: code = 4; break;
+            case HPCT_EPI_TANH: code = 5; break;
+            default: break;
+        }
+        if (code) { act = code; dd.epi[e] = HPCT_EPI_RELU; }   // (two activations fail the order test below)
+    }
     bool has[4];
-    if (!parse_epi(d, order, 4, has))
-        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [SCALE_CONST] [RELU] [DROPOUT_HASH] in that order");
+    if (!parse_epi(dd, order, 4, has))
+        return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [SCALE_CONST] [RELU | RELU6 | GELU_TANH | SIGMOID | TANH] [DROPOUT_HASH] in that order");
     const bool has_bias = has[0], has_scale = has[1], has_relu = has[2], has_dropout = has[3];
     if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_SOFTMAX_LAST && d.reduce != HPCT_RED_MEAN_LAST)
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: reduction must be NONE, SOFTMAX_LAST or MEAN_LAST");
@@ -178,7 +193,7 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     const bool sm = d.reduce == HPCT_RED_SOFTMAX_LAST;
     GemmParams g{};
     g.M = (int32_t)M; g.K = (int32_t)K; g.N = (int32_t)N;
-    g.relu = has_relu ? 1 : 0; g.softmax = sm ? 1 : 0;
+    g.relu = has_relu ? act : 0; g.softmax = sm ? 1 : 0;
     g.scale = has_scale ? d.scale : 1.0f;
     g.wt = wt ? 1 : 0;
     g.batch = (int32_t)batch; g.sX = M * K; g.sW = K * N; g.sY = M * N;

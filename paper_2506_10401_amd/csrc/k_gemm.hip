@@ -187,8 +187,8 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
             const float bv = (bias && cok[b]) ? bias[colb(b)] : 0.f;
             acc[b] = (acc[b] + bv) * p.scale;
             if (relu) {
-                acc[b].x = fmaxf(acc[b].x, 0.f); acc[b].y = fmaxf(acc[b].y, 0.f);
-                acc[b].z = fmaxf(acc[b].z, 0.f); acc[b].w = fmaxf(acc[b].w, 0.f);
+                acc[b].x = activate(acc[b].x, relu); acc[b].y = activate(acc[b].y, relu);
+                acc[b].z = activate(acc[b].z, relu); acc[b].w = activate(acc[b].w, relu);
             }
             if (EXT && p.dropout) {
 #pragma unroll

@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void gemm_direct(GemmParams p, int tiles_
         const int row = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
         float4v v = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
         v = (v + bv) * p.scale;
-        if (p.relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+        if (p.relu) { v.x = activate(v.x, p.relu); v.y = activate(v.y, p.relu); v.z = activate(v.z, p.relu); v.w = activate(v.w, p.relu); }
         if (p.dropout) {
             const uint64_t off = (uint64_t)row * (uint64_t)N + (uint64_t)(n0 + 4 * l32) + p.seed;
 #pragma unroll

@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
                     for (int r = 0; r < 16; ++r) {
                         const int lr = 8 * (r >> 2) + 4 * h + (r & 3);
                         float v = (acc[i][j][r] + bv[j]) * p.scale;
-                        if (p.relu) v = fmaxf(v, 0.f);
+                        if (p.relu) v = activate(v, p.relu);
                         if (p.dropout) {
                             const uint64_t off = (uint64_t)(rowq + lr) * (uint64_t)N + (uint64_t)(colw + j * 32 + l32);
                             v = dropout_u(off + p.seed) < p.drop_t ? 0.f : v * p.keep_scale;
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm * (TM / 2) + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
                 float v = (acc[i][j][r] + bv) * p.scale;
-                if (p.relu) v = fmaxf(v, 0.f);
+                if (p.relu) v = activate(v, p.relu);
                 if (p.dropout) {
                     const uint64_t off = (uint64_t)row * (uint64_t)N + (uint64_t)col;
                     v = dropout_u(off + p.seed) < p.drop_t ? 0.f : v * p.keep_scale;
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(256) void split_k_finish(GemmParams p) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             float y = (x[e] + (p.bias ? p.bias[col + e] : 0.f)) * p.scale;
-            if (p.relu) y = fmaxf(y, 0.f);
+            if (p.relu) y = activate(y, p.relu);
             if (p.dropout) y = dropout_u((uint64_t)idx + (uint64_t)e + p.seed) < p.drop_t ? 0.f : y * p.keep_scale;
             x[e] = y;
         }

@@ -123,7 +123,7 @@ hipError_t reduce_launch(const ReduceParams& p, hipStream_t stream);
 //      means in Y, a one-group kernel turns Y into its softmax.
 struct GemmParams {
     const float* X; const float* W; const float* bias; float* Y;
-    int32_t M, K, N; int32_t relu, softmax;
+    int32_t M, K, N; int32_t relu, softmax;   // relu: the activation code of prim.hpp's activate() (0 none, 1 ReLU, ...)
     int32_t dropout;      // apply the hash dropout
     uint32_t drop_t;      // an element is dropped iff (hash % 1000) < drop_t
     float keep_scale;     // 1 / (1 - p)

@@ -86,6 +86,19 @@ __device__ __forceinline__ float gelu_tanh(float y) {
     return y * fast_rcp(1.0f + fast_exp2(t));
 }
 
+// The activation at the end of a contraction kernel's epilogue (GemmParams::relu): 0 none, 1 ReLU, 2 ReLU6,
+// 3 tanh-form GELU, 4 logistic, 5 tanh - the same formulas as the elementwise kernels.  The code is uniform.
+__device__ __forceinline__ float activate(float v, int act) {
+    switch (act) {
+        case 0: return v;
+        case 1: return fmaxf(v, 0.f);
+        case 2: return fminf(fmaxf(v, 0.f), 6.f);
+        case 3: return gelu_tanh(v);
+        case 4: return 1.f / (1.f + expf(-v));
+        default: return tanhf(v);
+    }
+}
+
 // ---- hash dropout (Section 5.3 case study of the paper) -------------------------
 // rand as the integer u = h % 1000 for h = offset + seed:
 // h ^= h >> 17; h ^= h << 31; h ^= h >> 8, all in 64 bits.

@@ -540,6 +540,17 @@ def test_gemm_transposed_weight_and_scale_plans():
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_BIAS_COL)))
 
 
+def test_gemm_activation_plans():
+    def g(epi):
+        return H.op_desc(H.HPCT_ANCHOR_GEMM, list(epi), H.HPCT_RED_NONE, 0, [(512, 256), (256, 512), (512,)], [(512, 512)])
+    for act in (H.HPCT_EPI_RELU, H.HPCT_EPI_RELU6, H.HPCT_EPI_GELU_TANH, H.HPCT_EPI_SIGMOID, H.HPCT_EPI_TANH):
+        H.Plan(g([H.HPCT_EPI_BIAS_COL, act]))
+        H.Plan(g([H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SCALE_CONST, act, H.HPCT_EPI_DROPOUT_HASH]))
+        expect(H.HPCT_ERR_UNSUPPORTED, g([act, H.HPCT_EPI_BIAS_COL]))                       # the activation comes after the bias
+    expect(H.HPCT_ERR_UNSUPPORTED, g([H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU, H.HPCT_EPI_TANH]))   # one activation only
+    expect(H.HPCT_ERR_UNSUPPORTED, g([H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SIN]))
+
+
 def test_batched_gemm_plans():
     def g(xs, ws, os_, epi=(H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU), red=H.HPCT_RED_NONE, wstride=None):
         return H.op_desc(H.HPCT_ANCHOR_GEMM, list(epi), red, 0, [xs, H.tensor_desc(ws, wstride), (ws[-1],)], [os_])

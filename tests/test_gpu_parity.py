@@ -222,6 +222,32 @@ def test_batched_gemm(B, M, K, N):
     assert show("shared W", compare.contraction(host(out).reshape(B * M, N), Zs, Ds))
 
 
+@pytest.mark.parametrize("M,K,N", [(64, 256, 256), (33, 36, 130), (700, 260, 644), (2900, 33, 1001), (1024, 512, 4096),
+                                   (256, 2048, 256), (2100, 36, 2052)])
+def test_gemm_activation_epilogues(M, K, N):
+    # the 16-row kernel, tiles of 64 and 128, K slices (activation in the finishing kernel) and the short-K kernel
+    print("gemm act M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"] * 8.0, t["bias"], want_norm=True)       # pre-activations of a few units
+    t8 = dict(t, W=(t["W"] * 8.0).astype(np.float32))
+    Z32 = Z.astype(np.float32).reshape(-1)        # (the checker's elementwise steps take fp32 inputs: 6e-8 relative, far inside the bound)
+    names = set()
+    for act, lip in (("relu6", 1.0), ("gelu", 1.13), ("sigmoid", 0.25), ("tanh", 1.0)):
+        # the activation of the exact pre-activation; |f(a) - f(b)| <= lip |a - b| carries the contraction bound through
+        if act == "relu6":
+            want = ref.relu6(Z)
+        elif act == "gelu":
+            want = ref.gelu_tanh(Z)
+        else:
+            want = ref.eltwise_map(Z32, Z.shape, (Z.shape[1], 1), unary=[act])
+        got, name = run_gemm(t8, relu=act)
+        names.add(name)
+        assert show("gemm + %s (%s)" % (act, name), compare.contraction(got, want, Dn * lip + 1e-6))
+    got, name = run_gemm(t8, relu="gelu", scale=0.5, wt=True)
+    assert show("gemm wt + scale + gelu", compare.contraction(got, ref.gelu_tanh(ref.scale_const(Z, 0.5)), Dn * 0.6 + 1e-6))
+    print("kernels", sorted(names), flush=True)
+
+
 def test_gemm_short_k_direct_kernel():
     # operands straight into the MFMA layout: K below, at and between the 32-wide chunks, the dropout epilogue
     # (an integer decision per element), and a batch
