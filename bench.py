@@ -392,6 +392,71 @@ def main() -> int:
                              frac=round(nbd / us / 1e3 / HBM_PEAK_GBS, 4), buffer_sets=3))
         del dsets
 
+        # operators built after those: one line each (rotated buffer sets for the memory-bound ones)
+        def side_op(op, make, nsets, work, bound, note=None):
+            calls, name = [], None
+            for _ in range(nsets):
+                plan_, ins_, out_, ws_ = make()
+                name = plan_.kernel_name
+                calls.append(plan_.bind(ins_, [out_], workspace=ws_))
+            k = [0]
+
+            def call():
+                calls[k[0] % nsets]()
+                k[0] += 1
+            us_ = timed(call, args.steps)
+            if bound == "hbm":
+                ach, peak, unit = work / us_ / 1e3, HBM_PEAK_GBS, "GB/s"
+            else:
+                ach, peak, unit = work / us_ / 1e6, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
+            e = dict(op=op, kernel=name, launches=args.steps, avg_us=round(us_, 3), achieved=round(ach, 1 if bound == "hbm" else 2),
+                     unit=unit, peak=peak, frac=round(ach / peak, 4), buffer_sets=nsets)
+            if note:
+                e["note"] = note
+            next_ops.append(e)
+
+        def mk_mlp():
+            X = torch.randn(4096, 1024, device="cuda"); W = torch.randn(1024, 4096, device="cuda") * 0.03
+            b = torch.randn(4096, device="cuda"); o = torch.empty(4096, 4096, device="cuda")
+            pl, ins_ = hpct.gemm_bias_relu_softmax_plan(X, W, b, o, relu="gelu", softmax=False)
+            return pl, ins_, o, None
+        side_op("gemm_bias_gelu_4096x1024x4096", mk_mlp, 1, 2.0 * 4096 * 1024 * 4096, "mfma")
+
+        def mk_bmm():
+            X = torch.randn(16, 1024, 1024, device="cuda"); W = torch.randn(16, 1024, 1024, device="cuda") * 0.03
+            o = torch.empty(16, 1024, 1024, device="cuda")
+            pl, ins_ = hpct.gemm_bias_relu_softmax_plan(X, W, None, o, relu=False, softmax=False)
+            return pl, ins_, o, None
+        side_op("batched_gemm_16x1024x1024x1024", mk_bmm, 1, 2.0 * 16 * 1024 ** 3, "mfma")
+
+        def mk_qk():
+            X = torch.randn(64, 512, 64, device="cuda"); W = torch.randn(64, 64, 512, device="cuda")
+            o = torch.empty(64, 512, 512, device="cuda")
+            pl, ins_ = hpct.gemm_bias_relu_softmax_plan(X, W, None, o, relu=False, softmax=False)
+            return pl, ins_, o, None
+        side_op("batched_gemm_short_k_64x512x64x512", mk_qk, 1, 2.0 * 64 * 512 * 64 * 512, "mfma",
+             note="2K flop per 4 bytes written: at K = 64 the store and MFMA bounds are of the same size")
+
+        def mk_first():
+            x = torch.randn(32, 3, 224, 224, device="cuda"); w = torch.randn(64, 3, 3, 3, device="cuda") * 0.2
+            b = torch.randn(64, device="cuda"); o = torch.empty(32, 64, 224, 224, device="cuda")
+            pl, ins_ = hpct.conv_block_plan(x, w, b, None, None, o, 1, 1, True, False)
+            return pl, ins_, o, None
+        side_op("conv3x3_first_layer_32x3x224x224_to_64", mk_first, 1, (32 * 3 + 32 * 64) * 224 * 224 * 4.0, "hbm",
+             note="store-bound: bytes = input + output (411 MB of output)")
+
+        def mk_pool():
+            x = torch.randn(32, 64, 112, 112, device="cuda"); o = torch.empty(32, 64, 56, 56, device="cuda")
+            pl, ins_ = hpct.maxpool_plan(x, o, 3, 2, 1)
+            return pl, ins_, o, None
+        side_op("maxpool3x3_stride2_32x64x112x112", mk_pool, 4, 32 * 64 * (112 * 112 + 56 * 56) * 4.0, "hbm")
+
+        def mk_gn():
+            x = torch.randn(32, 64, 56, 56, device="cuda"); o = torch.empty_like(x)
+            pl, ins_ = hpct.groupnorm_plan(x, torch.randn(64, device="cuda"), torch.randn(64, device="cuda"), o, 8, 1e-5, True)
+            return pl, ins_, o, None
+        side_op("groupnorm8_relu_32x64x56x56", mk_gn, 11, 2.0 * 32 * 64 * 56 * 56 * 4, "hbm")
+
     per_op, fracs = [], []
     for i in which:
         avg_us = 1e3 * ev[i][0].elapsed_time(ev[i][1]) / args.steps
