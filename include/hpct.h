@@ -33,6 +33,8 @@
  *   GEMM [+BIAS_COL] [+SCALE_CONST] [+RELU]           X[M,K], W[K,N], bias[N]       [M,N]
  *         (in every GEMM chain RELU6, GELU_TANH,
  *         SIGMOID or TANH may stand for RELU)
+ *         (X: any strided view; one that is not
+ *         row-major is first copied to the workspace)
  *         [+DROPOUT_HASH] [+SOFTMAX_LAST] (one        (W row-major, strides (N,1),
  *         kernel for N <= 256, GEMM then an           or stored transposed as an
  *         in-place row softmax beyond)                [N,K] array: strides (1,K))
@@ -210,7 +212,7 @@ typedef struct hpct_plan hpct_plan;   /* opaque; host memory */
  * *out is set to NULL.  Errors: NULL, BAD_DESC, SHAPE_MISMATCH, UNSUPPORTED. */
 hpct_status hpct_plan_create(const hpct_op_desc *desc, hpct_plan **out);
 
-/* Device workspace the plan needs at launch, in bytes: 0 except for GEMM chains
+/* Device workspace the plan needs at launch, in bytes: 0 except for GEMM chains whose X is not row-major, GEMM chains
  * with MEAN_LAST (one float per row and column tile), GEMMs with a small output and
  * a long K (partial products of the K slices) and axis reductions with few outputs
  * and a long strided axis (partial results of the pieces it is cut into).  The launch overwrites it;

@@ -44,6 +44,7 @@ struct hpct_plan {
     int64_t pool_planes; int32_t pool_h, pool_w;   // Kind::MaxPool
     PoolParams pool;                               // Kind::MaxPoolGen
     GroupnormParams gn;                            // Kind::Groupnorm
+    int32_t x_copy; LayoutParams x_layout; size_t x_off;   // Kind::Gemm with a strided X: copied to workspace + x_off first
     size_t ws_bytes;  // device workspace needed at launch
     union {
         GemmParams gemm;
@@ -129,6 +130,8 @@ uint32_t dropout_threshold(float p) {
     return t;
 }
 
+hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p);
+
 hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     // one activation - RELU, RELU6, GELU_TANH, SIGMOID or TANH - may stand where RELU does; `act` is activate()'s code for it
     static const hpct_epilogue order[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_CONST, HPCT_EPI_RELU, HPCT_EPI_DROPOUT_HASH};
@@ -182,8 +185,11 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     // W: row-major [K,N], or the transposed storage of a linear layer's weight ([N,K] row-major seen as [K,N]
     // with strides (1, K)); with a batch the matrices follow each other (stride K*N)
     const bool wt = !contiguous(W) && W.stride[wb] == 1 && W.stride[wb + 1] == K && (!wb || W.stride[0] == K * N || B == 1);
+    // X: row-major, or any other strided view (its transpose [K,M] seen as [M,K] with strides (1, M), a slice, ...), which
+    // the layout kernel first copies to the workspace as a row-major matrix
+    const bool x_copy = !contiguous(X);
     for (int i = 0; i < d.n_in; ++i)
-        if (!contiguous(d.in[i]) && !(i == 1 && wt))
+        if (!contiguous(d.in[i]) && !(i == 1 && wt) && !(i == 0 && x_copy))
             return fail(HPCT_ERR_UNSUPPORTED, i == 1 ? "in[1]: W must be row-major [K,N] (strides N, 1) or its transpose (strides 1, K)"
                                                      : "in[%d]: only contiguous row-major layouts are supported", i);
     if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous row-major layouts are supported");
@@ -211,6 +217,22 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has_bias ? 2 : -1; p.slot[3] = -1;
     p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.wt, g.batch);
     p.ws_bytes = gemm_workspace_bytes((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.batch);
+    p.x_copy = 0;
+    if (x_copy) {
+        hpct_op_desc c{};
+        c.anchor = HPCT_ANCHOR_NONE; c.reduce = HPCT_RED_NONE; c.reduce2 = HPCT_RED_NONE;
+        c.n_in = 1; c.in[0] = X;
+        c.n_out = 1; c.out[0] = X;
+        int64_t st = 1;
+        for (int k = X.ndim - 1; k >= 0; --k) { c.out[0].stride[k] = st; st *= X.shape[k]; }
+        hpct_plan lp{};
+        const hpct_status ls = plan_layout(c, lp);
+        if (ls != HPCT_OK) return ls;
+        p.x_copy = 1;
+        p.x_layout = lp.u.layout;
+        p.x_off = (p.ws_bytes + 255) & ~(size_t)255;
+        p.ws_bytes = p.x_off + (size_t)st * 4;
+    }
     return HPCT_OK;
 }
 
@@ -804,7 +826,9 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
     const uintptr_t amask = (plan->kind == Kind::Layout || plan->kind == Kind::Reduce || plan->kind == Kind::Eltwise) ? 3 : 15;
     for (int i = 0; i < plan->n_in; ++i) {
         if (!in_ptrs[i]) return fail(HPCT_ERR_NULL, "in_ptrs[%d] is NULL", i);
-        if ((uintptr_t)in_ptrs[i] & amask) return fail(HPCT_ERR_ALIGNMENT, "in_ptrs[%d] is not %d-byte aligned", i, (int)amask + 1);
+        // (a strided X of a GEMM chain goes through the layout kernel first: element alignment)
+        const uintptr_t m = (i == 0 && plan->kind == Kind::Gemm && plan->x_copy) ? 3 : amask;
+        if ((uintptr_t)in_ptrs[i] & m) return fail(HPCT_ERR_ALIGNMENT, "in_ptrs[%d] is not %d-byte aligned", i, (int)m + 1);
     }
     for (int i = 0; i < plan->n_out; ++i) {
         if (!out_ptrs[i]) return fail(HPCT_ERR_NULL, "out_ptrs[%d] is NULL", i);
@@ -834,6 +858,14 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
             GemmParams q = plan->u.gemm;
             q.X = in(0); q.W = in(1); q.bias = in(2); q.Y = (float*)out_ptrs[0];
             q.ws = (float*)workspace;
+            if (plan->x_copy) {   // a strided X: its row-major copy first
+                LayoutParams l = plan->x_layout;
+                l.in = q.X; l.out = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan->x_off);
+                if (l.kind == 1 && ((uintptr_t)l.in & 15)) l.kind = 0;
+                e = layout_launch(l, stream);
+                if (e != hipSuccess) break;
+                q.X = l.out;
+            }
             e = gemm_launch(q, stream);
             break;
         }

@@ -242,17 +242,19 @@ def _sh(t) -> Tuple[int, ...]:
 # Each chain has a *_plan function (descriptor -> cached Plan plus the operand
 # list in descriptor order) and a convenience function that launches it.
 def gemm_bias_relu_softmax_plan(X, W, bias, out, relu=True, softmax=True, scale=None):
-    """X [M,K] or a batch [B,M,K]; W [K,N] row-major, the .t() view of an [N,K] row-major tensor (a linear
+    """X [M,K] or a batch [B,M,K], row-major or any strided view (e.g. the .t() of a [K,M] tensor: it is then first
+    copied to the plan's workspace as a row-major matrix); W [K,N] row-major, the .t() view of an [N,K] row-major tensor (a linear
     layer's weight), or one such matrix per batch [B,K,N].  `scale`: constant multiplied in after the bias (the
     Gemm-Scale operator), None = no such step.  relu: False, True, or the name of another activation:
     "relu6", "gelu", "sigmoid", "tanh"."""
     wst = tuple(int(v) for v in W.stride())
+    xst = tuple(int(v) for v in X.stride())
     act = {False: [], True: [HPCT_EPI_RELU], "relu": [HPCT_EPI_RELU], "relu6": [HPCT_EPI_RELU6], "gelu": [HPCT_EPI_GELU_TANH],
            "sigmoid": [HPCT_EPI_SIGMOID], "tanh": [HPCT_EPI_TANH]}[relu]
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_CONST] if scale is not None else []) + act
     ins = [X, W] + ([bias] if bias is not None else [])
-    descs = [_sh(X), tensor_desc(_sh(W), wst)] + ([_sh(bias)] if bias is not None else [])
-    plan = _cached(("gemm", _sh(X), _sh(W), wst, tuple(epi), softmax, scale), lambda: op_desc(
+    descs = [tensor_desc(_sh(X), xst), tensor_desc(_sh(W), wst)] + ([_sh(bias)] if bias is not None else [])
+    plan = _cached(("gemm", _sh(X), xst, _sh(W), wst, tuple(epi), softmax, scale), lambda: op_desc(
         HPCT_ANCHOR_GEMM, epi, HPCT_RED_SOFTMAX_LAST if softmax else HPCT_RED_NONE, 0, descs, [_sh(out)],
         scale=1.0 if scale is None else scale))
     return plan, ins

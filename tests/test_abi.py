@@ -525,11 +525,13 @@ def test_gemm_transposed_weight_and_scale_plans():
     p = H.Plan(g(256, 2048, 256, (1, 2048)))
     assert p.kernel_name == "gemm_tile64<wt,split-k>" and p.workspace_bytes == H.Plan(g(256, 2048, 256, (256, 1))).workspace_bytes
     assert H.Plan(g(64, 256, 256, (256, 1))).kernel_name == "gemm_rows16<256>"
-    # any other W layout is refused; X and the output stay row-major
+    # any other W layout is refused; the bias and the output stay contiguous (a strided X is copied: its own test)
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (1, 512)))
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (512, 1)))
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (2, 512)))
-    d = g(64, 256, 256, (256, 1)); d.in_[0] = H.tensor_desc((64, 256), (1, 64))
+    d = g(64, 256, 256, (256, 1)); d.out[0] = H.tensor_desc((64, 256), (1, 64))
+    expect(H.HPCT_ERR_UNSUPPORTED, d)
+    d = g(64, 256, 256, (256, 1)); d.in_[2] = H.tensor_desc((256,), (2,))
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     # Gemm-Scale: SCALE_CONST sits between the bias and the ReLU
     e = (H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_RELU)
@@ -538,6 +540,21 @@ def test_gemm_transposed_weight_and_scale_plans():
     assert H.Plan(g(4096, 1024, 4096, (1, 1024), e + (H.HPCT_EPI_DROPOUT_HASH,), scale=2.0)).kernel_name == "gemm_tile128<wt>"
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU, H.HPCT_EPI_SCALE_CONST)))
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_BIAS_COL)))
+
+
+def test_gemm_strided_x_plans():
+    def g(xstride, M=512, K=256, N=512):
+        return H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_BIAS_COL], H.HPCT_RED_NONE, 0,
+                         [H.tensor_desc((M, K), xstride), (K, N), (N,)], [(M, N)])
+    assert H.Plan(g(None)).workspace_bytes == 0
+    # the transpose of a [K,M] array, a slice of a wider matrix: a row-major copy of X in the workspace
+    assert H.Plan(g((1, 512))).workspace_bytes == 512 * 256 * 4
+    assert H.Plan(g((300, 1))).workspace_bytes == 512 * 256 * 4
+    # behind the K slices' partial products, on a 256-byte boundary
+    p = H.Plan(g((1, 256), M=256, K=2048, N=256))
+    q = H.Plan(g(None, M=256, K=2048, N=256))
+    assert q.workspace_bytes > 0 and p.workspace_bytes == (q.workspace_bytes + 255) // 256 * 256 + 256 * 2048 * 4
+    assert p.kernel_name == q.kernel_name
 
 
 def test_gemm_activation_plans():

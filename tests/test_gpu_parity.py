@@ -248,6 +248,41 @@ def test_gemm_activation_epilogues(M, K, N):
     print("kernels", sorted(names), flush=True)
 
 
+@pytest.mark.parametrize("M,K,N", [(64, 256, 256), (70, 100, 63), (700, 260, 644), (1024, 512, 4096), (256, 2048, 256), (2100, 36, 2052)])
+def test_gemm_strided_x(M, K, N):
+    # X given as the transpose of a [K,M] array, and as a column slice of a wider matrix: copied to the workspace first
+    print("gemm strided X M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    W, b = dev(t["W"]), dev(t["bias"])
+    wide = torch.full((M, K + 5), float("nan"), device="cuda")
+    wide[:, 3:3 + K] = dev(t["X"])
+    for tag, Xv in (("transposed", dev(np.ascontiguousarray(t["X"].T)).t()), ("slice", wide[:, 3:3 + K])):
+        out = torch.full((M, N), float("nan"), device="cuda")
+        plan, ins = hpct.gemm_bias_relu_softmax_plan(Xv, W, b, out, relu=True, softmax=False)
+        assert plan.workspace_bytes >= M * K * 4
+        ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda")
+        plan.launch(ins, [out], workspace=ws)
+        assert show("strided X (%s) %s" % (tag, plan.kernel_name), compare.contraction(host(out), ref.relu(Z), Dn))
+        with pytest.raises(hpct.HpctError):
+            plan.launch(ins, [out])          # no workspace
+    # the same values as from the row-major X, bit for bit (the copy is exact)
+    plain, _ = run_gemm(t)
+    assert np.array_equal(host(out).view(np.uint32), plain.view(np.uint32))
+    # a batch of transposed matrices
+    B2 = 3
+    Xb = datagen.gen_normal(620, (B2, min(M, 200), K), 0.0, 1.0)
+    Wb = datagen.gen_normal(621, (B2, K, min(N, 300)), 0.0, 1.0 / np.sqrt(K))
+    Xt = dev(np.ascontiguousarray(Xb.transpose(0, 2, 1))).transpose(1, 2)
+    out = torch.full((B2, Xb.shape[1], Wb.shape[2]), float("nan"), device="cuda")
+    plan, ins = hpct.gemm_bias_relu_softmax_plan(Xt, dev(Wb), None, out, relu=False, softmax=False)
+    ws = torch.full((plan.workspace_bytes // 4,), float("nan"), device="cuda")
+    plan.launch(ins, [out], workspace=ws)
+    for i in range(B2):
+        Zi, Di = ref.gemm_bias(Xb[i], Wb[i], None, want_norm=True)
+        assert compare.contraction(host(out)[i], Zi, Di).ok, i
+
+
 def test_gemm_short_k_direct_kernel():
     # operands straight into the MFMA layout: K below, at and between the 32-wide chunks, the dropout epilogue
     # (an integer decision per element), and a batch
