@@ -130,12 +130,10 @@ uint32_t dropout_threshold(float p) {
     return t;
 }
 
-hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p);
-
-hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
-    // one activation - RELU, RELU6, GELU_TANH, SIGMOID or TANH - may stand where RELU does; `act` is activate()'s code for it
-    static const hpct_epilogue order[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_CONST, HPCT_EPI_RELU, HPCT_EPI_DROPOUT_HASH};
-    hpct_op_desc dd = d;
+// The activation of a contraction chain: rewrites it to RELU in `dd` (so that the order test sees one name) and
+// returns activate()'s code for it: 1 RELU, 2 RELU6, 3 GELU_TANH, 4 SIGMOID, 5 TANH; 0 if there is none.  (Two
+// activations fail the order test.)
+int take_activation(hpct_op_desc& dd) {
     int act = 0;
     for (int e = 0; e < dd.n_epi && e < HPCT_MAX_EPI; ++e) {
         int code = 0;
@@ -147,8 +145,18 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
             case HPCT_EPI_TANH: code = 5; break;
             default: break;
         }
-        if (code) { act = code; dd.epi[e] = HPCT_EPI_RELU; }   // (two activations fail the order test below)
+        if (code) { act = code; dd.epi[e] = HPCT_EPI_RELU; }
     }
+    return act;
+}
+
+hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p);
+
+hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
+    // one activation - RELU, RELU6, GELU_TANH, SIGMOID or TANH - may stand where RELU does
+    static const hpct_epilogue order[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_CONST, HPCT_EPI_RELU, HPCT_EPI_DROPOUT_HASH};
+    hpct_op_desc dd = d;
+    const int act = take_activation(dd);
     bool has[4];
     if (!parse_epi(dd, order, 4, has))
         return fail(HPCT_ERR_UNSUPPORTED, "GEMM anchor: epilogues must be [BIAS_COL] [SCALE_CONST] [RELU | RELU6 | GELU_TANH | SIGMOID | TANH] [DROPOUT_HASH] in that order");
@@ -575,10 +583,14 @@ hpct_status plan_reduce(const hpct_op_desc& d, hpct_plan& p) {
 }
 
 hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
-    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_RELU6};
-    bool has[4];
-    if (!parse_epi(d, allowed, 4, has) || (has[2] && has[3]))
+    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU};
+    hpct_op_desc dd = d;
+    const int act = take_activation(dd);
+    bool has[3];
+    if (!parse_epi(dd, allowed, 3, has))
         return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: epilogues must be [BIAS_COL] [SCALE_SHIFT_CH] [RELU | RELU6] in that order");
+    // (the other activations of the GEMM chains would cost the conv kernels about 1 % whether used or not: measured)
+    if (act > 2) return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: the activation must be RELU or RELU6");
     if (d.reduce != HPCT_RED_NONE && d.reduce != HPCT_RED_MAXPOOL2_HW)
         return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: reduction must be NONE or MAXPOOL2_HW");
     if (d.reduce != HPCT_RED_NONE && d.reduce_before_epi) return fail(HPCT_ERR_UNSUPPORTED, "conv anchor: the pooling runs after the epilogues");
@@ -630,7 +642,7 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
             return fail(HPCT_ERR_UNSUPPORTED, "depthwise conv: filter, stride, padding and dilation must be the same in both directions");
         ConvParams q{};
         q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)H; q.W = (int32_t)W; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
-        q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.dil = dil_h; q.relu = has[3] ? 2 : (has[2] ? 1 : 0);
+        q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.dil = dil_h; q.relu = has[2] ? act : 0;
         if (!dwconv_supported(q, &why)) return fail(HPCT_ERR_UNSUPPORTED, "depthwise conv: %s", why);
         p.kind = Kind::DwConv;
         p.u.conv = q;
@@ -643,7 +655,7 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
         return fail(HPCT_ERR_UNSUPPORTED, "conv: %s", why);
     ConvParams q{};
     q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)H; q.W = (int32_t)W; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
-    q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.dil = dil_h; q.relu = has[3] ? 2 : (has[2] ? 1 : 0); q.pool = pool ? 1 : 0;
+    q.pad = d.pad_hw[0]; q.stride = d.stride_hw[0]; q.dil = dil_h; q.relu = has[2] ? act : 0; q.pool = pool ? 1 : 0;
     // A 1x1 filter with stride 1 and no padding acts on pixels independently: the plane is regrouped into rows of
     // 64 pixels, so that a 64-pixel tile stages exactly the pixels it computes instead of the image rows they lie in.
     if (R == 1 && q.stride == 1 && q.pad == 0 && !pool && (H * W) % 64 == 0) { q.H = (int32_t)(H * W / 64); q.W = 64; }
@@ -658,10 +670,13 @@ hpct_status plan_conv(const hpct_op_desc& d, hpct_plan& p) {
 // Transposed conv = preparation of the flipped filter (and, for stride > 1, the zero-dilated input) in the
 // workspace, then the stride-1 conv kernel at padding (R-1)*dilation - pad.
 hpct_status plan_convt(const hpct_op_desc& d, hpct_plan& p) {
-    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_RELU6};
-    bool has[4];
-    if (!parse_epi(d, allowed, 4, has) || (has[2] && has[3]))
+    static const hpct_epilogue allowed[] = {HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU};
+    hpct_op_desc dd = d;
+    const int act = take_activation(dd);
+    bool has[3];
+    if (!parse_epi(dd, allowed, 3, has))
         return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: epilogues must be [BIAS_COL] [SCALE_SHIFT_CH] [RELU | RELU6] in that order");
+    if (act > 2) return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: the activation must be RELU or RELU6");
     if (d.reduce != HPCT_RED_NONE) return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: no reduction is supported after it");
     if (d.groups > 1) return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: groups are not supported");
     const int need = 2 + (has[0] ? 1 : 0) + (has[1] ? 2 : 0);
@@ -703,7 +718,7 @@ hpct_status plan_convt(const hpct_op_desc& d, hpct_plan& p) {
         return fail(HPCT_ERR_UNSUPPORTED, "transposed conv: %s", why);
     ConvParams q{};
     q.Nb = (int32_t)Nb; q.C = (int32_t)C; q.H = (int32_t)Hd; q.W = (int32_t)Wd; q.K = (int32_t)K; q.R = (int32_t)R; q.S = (int32_t)S;
-    q.pad = (int32_t)(re - pad); q.stride = 1; q.dil = dil_h; q.relu = has[3] ? 2 : (has[2] ? 1 : 0); q.pool = 0;
+    q.pad = (int32_t)(re - pad); q.stride = 1; q.dil = dil_h; q.relu = has[2] ? act : 0; q.pool = 0;
     if (R == 1 && (Hd * Wd) % 64 == 0) { q.H = (int32_t)(Hd * Wd / 64); q.W = 64; }   // as in plan_conv (1x1: pad is 0 here)
     q.win = conv_window_geometry(q);
     p.kind = Kind::ConvT;

@@ -241,6 +241,12 @@ def _sh(t) -> Tuple[int, ...]:
 # ---- the five chains ---------------------------------------------------------
 # Each chain has a *_plan function (descriptor -> cached Plan plus the operand
 # list in descriptor order) and a convenience function that launches it.
+def _activation(relu):
+    """the epilogue list for an activation argument: False / None, True (= "relu"), "relu", "relu6", "gelu", "sigmoid", "tanh" """
+    return {False: [], None: [], True: [HPCT_EPI_RELU], "relu": [HPCT_EPI_RELU], "relu6": [HPCT_EPI_RELU6],
+            "gelu": [HPCT_EPI_GELU_TANH], "sigmoid": [HPCT_EPI_SIGMOID], "tanh": [HPCT_EPI_TANH]}[relu]
+
+
 def gemm_bias_relu_softmax_plan(X, W, bias, out, relu=True, softmax=True, scale=None):
     """X [M,K] or a batch [B,M,K], row-major or any strided view (e.g. the .t() of a [K,M] tensor: it is then first
     copied to the plan's workspace as a row-major matrix); W [K,N] row-major, the .t() view of an [N,K] row-major tensor (a linear
@@ -249,8 +255,7 @@ def gemm_bias_relu_softmax_plan(X, W, bias, out, relu=True, softmax=True, scale=
     "relu6", "gelu", "sigmoid", "tanh"."""
     wst = tuple(int(v) for v in W.stride())
     xst = tuple(int(v) for v in X.stride())
-    act = {False: [], True: [HPCT_EPI_RELU], "relu": [HPCT_EPI_RELU], "relu6": [HPCT_EPI_RELU6], "gelu": [HPCT_EPI_GELU_TANH],
-           "sigmoid": [HPCT_EPI_SIGMOID], "tanh": [HPCT_EPI_TANH]}[relu]
+    act = _activation(relu)
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_CONST] if scale is not None else []) + act
     ins = [X, W] + ([bias] if bias is not None else [])
     descs = [tensor_desc(_sh(X), xst), tensor_desc(_sh(W), wst)] + ([_sh(bias)] if bias is not None else [])
@@ -467,7 +472,7 @@ def conv_block_plan(inp, wt, bias, scale, shift, out, stride=1, pad=1, relu=True
     """Plan of conv2d [+bias] [+per-channel scale/shift] [+relu] [+2x2 max pool] (a VGG-style block).
     relu: False, True, or "relu6"; groups: 1 (dense) or the channel count (depthwise, wt [C,1,R,R], no pooling)."""
     assert (scale is None) == (shift is None)
-    act = [] if not relu else [HPCT_EPI_RELU6 if relu == "relu6" else HPCT_EPI_RELU]
+    act = _activation(relu)
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + act
     ins = [inp, wt] + ([bias] if bias is not None else []) + ([scale, shift] if scale is not None else [])
     plan = _cached(("convblock", _sh(inp), _sh(wt), tuple(epi), stride, pad, pool, dilation, groups), lambda: op_desc(
@@ -487,7 +492,7 @@ def conv_transpose_plan(inp, wt, bias, scale, shift, out, stride=1, pad=0, relu=
     """Transposed conv (inp [N,C,H,W], wt [C,K,R,R], out [N,K,(H-1)*stride - 2*pad + (R-1)*dilation + 1, ...])
     [+bias] [+per-channel scale/shift] [+relu / "relu6"].  The plan needs a workspace (plan.workspace_bytes)."""
     assert (scale is None) == (shift is None)
-    act = [] if not relu else [HPCT_EPI_RELU6 if relu == "relu6" else HPCT_EPI_RELU]
+    act = _activation(relu)
     epi = ([HPCT_EPI_BIAS_COL] if bias is not None else []) + ([HPCT_EPI_SCALE_SHIFT_CH] if scale is not None else []) + act
     ins = [inp, wt] + ([bias] if bias is not None else []) + ([scale, shift] if scale is not None else [])
     plan = _cached(("convt", _sh(inp), _sh(wt), tuple(epi), stride, pad, dilation), lambda: op_desc(

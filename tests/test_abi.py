@@ -566,6 +566,13 @@ def test_gemm_activation_plans():
         expect(H.HPCT_ERR_UNSUPPORTED, g([act, H.HPCT_EPI_BIAS_COL]))                       # the activation comes after the bias
     expect(H.HPCT_ERR_UNSUPPORTED, g([H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU, H.HPCT_EPI_TANH]))   # one activation only
     expect(H.HPCT_ERR_UNSUPPORTED, g([H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SIN]))
+    # the conv chains keep RELU and RELU6 only
+    def c(epi):
+        return H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, list(epi), H.HPCT_RED_NONE, 0, [(2, 8, 12, 12), (16, 8, 3, 3), (16,)], [(2, 16, 12, 12)],
+                         stride_hw=(1, 1), pad_hw=(1, 1))
+    H.Plan(c([H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU6]))
+    expect(H.HPCT_ERR_UNSUPPORTED, c([H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_GELU_TANH]))
+    expect(H.HPCT_ERR_UNSUPPORTED, c([H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU, H.HPCT_EPI_RELU6]))
 
 
 def test_batched_gemm_plans():
