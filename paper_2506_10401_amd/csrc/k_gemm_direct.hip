@@ -37,6 +37,7 @@ constexpr int kXcds = 8;
 constexpr int DM = 128, DN = 128;   // a work-group's tile: four waves of 32 x 128
 constexpr int DK = 32;              // k per chunk
 
+template <bool ACT>
 __global__ __launch_bounds__(kThreads) void gemm_direct(GemmParams p, int tiles_n, int items) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -114,7 +115,8 @@ __global__ __launch_bounds__(kThreads) void gemm_direct(GemmParams p, int tiles_
         const int row = m0 + 8 * (r >> 2) + 4 * h + (r & 3);
         float4v v = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
         v = (v + bv) * p.scale;
-        if (p.relu) { v.x = activate(v.x, p.relu); v.y = activate(v.y, p.relu); v.z = activate(v.z, p.relu); v.w = activate(v.w, p.relu); }
+        if (ACT) { v.x = activate(v.x, p.relu); v.y = activate(v.y, p.relu); v.z = activate(v.z, p.relu); v.w = activate(v.w, p.relu); }
+        else if (p.relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
         if (p.dropout) {
             const uint64_t off = (uint64_t)row * (uint64_t)N + (uint64_t)(n0 + 4 * l32) + p.seed;
 #pragma unroll
@@ -148,7 +150,8 @@ LaunchShape gemm_direct_shape(int32_t M, int32_t N, int32_t batch) {
 hipError_t gemm_direct_launch(const GemmParams& p, hipStream_t stream) {
     const int tiles_m = (p.M + DM - 1) / DM * p.batch, tiles_n = (p.N + DN - 1) / DN;
     const int items = tiles_m * tiles_n;
-    hipLaunchKernelGGL(gemm_direct, dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+    if (p.relu > 1) hipLaunchKernelGGL(gemm_direct<true>, dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);   // an activation other than ReLU
+    else hipLaunchKernelGGL(gemm_direct<false>, dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
     return hipGetLastError();
 }
 

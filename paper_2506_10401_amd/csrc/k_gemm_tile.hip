@@ -45,7 +45,7 @@ constexpr int kXcds = 8;
 // BT: W is stored transposed ([N,K] row-major, the layout of a linear layer's weight).  Its tile is
 // then staged and read exactly like the A tile (rows = output columns, 128-bit reads along k):
 // the MFMA's A and B operands have mirror-image lane layouts.
-template <int T, bool VEC, bool BT>
+template <int T, bool VEC, bool BT, bool ACT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void gemm_tile(GemmParams p, int tiles_n, int items) {
     constexpr int TM = T, TN = T, WB = T / 64, LDB = T + 8;
     // one LDS block: the two stages of the A and B tiles, and after the chunk loop the waves' output strips
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
                     for (int r = 0; r < 16; ++r) {
                         const int lr = 8 * (r >> 2) + 4 * h + (r & 3);
                         float v = (acc[i][j][r] + bv[j]) * p.scale;
-                        if (p.relu) v = activate(v, p.relu);
+                        if (p.relu) v = ACT ? activate(v, p.relu) : fmaxf(v, 0.f);
                         if (p.dropout) {
                             const uint64_t off = (uint64_t)(rowq + lr) * (uint64_t)N + (uint64_t)(colw + j * 32 + l32);
                             v = dropout_u(off + p.seed) < p.drop_t ? 0.f : v * p.keep_scale;
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm * (TM / 2) + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
                 float v = (acc[i][j][r] + bv) * p.scale;
-                if (p.relu) v = activate(v, p.relu);
+                if (p.relu) v = ACT ? activate(v, p.relu) : fmaxf(v, 0.f);
                 if (p.dropout) {
                     const uint64_t off = (uint64_t)row * (uint64_t)N + (uint64_t)col;
                     v = dropout_u(off + p.seed) < p.drop_t ? 0.f : v * p.keep_scale;
@@ -471,14 +471,17 @@ hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
     const int items = tiles_m * tiles_n * p.ksplit;
     // (the vector instances address a tile's rows with 31-bit byte offsets)
     const bool fits = p.K <= (1 << 21) && p.N <= (1 << 24);
+    // ACT: an activation other than ReLU (its code costs the plain instances 2-3 % when it is merely present)
+    const bool act = p.relu > 1;
+#define HPCT_TILE(V, B) do { \
+        if (act) hipLaunchKernelGGL((gemm_tile<T, V, B, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items); \
+        else hipLaunchKernelGGL((gemm_tile<T, V, B, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items); } while (0)
     if (p.wt) {   // both operands are read along k
-        if (p.K % 4 == 0 && fits) hipLaunchKernelGGL((gemm_tile<T, true, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
-        else hipLaunchKernelGGL((gemm_tile<T, false, true>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+        if (p.K % 4 == 0 && fits) HPCT_TILE(true, true); else HPCT_TILE(false, true);
     } else {
-        const bool vec = (p.K % 4 == 0) && (p.N % 4 == 0) && fits;
-        if (vec) hipLaunchKernelGGL((gemm_tile<T, true, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
-        else hipLaunchKernelGGL((gemm_tile<T, false, false>), dim3(items), dim3(kThreads), 0, stream, p, tiles_n, items);
+        if ((p.K % 4 == 0) && (p.N % 4 == 0) && fits) HPCT_TILE(true, false); else HPCT_TILE(false, false);
     }
+#undef HPCT_TILE
     return hipGetLastError();
 }
 
