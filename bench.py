@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU checker")
     ap.add_argument("--only", type=int, default=0, help="run a single chain (1..5) instead of all five")
+    ap.add_argument("--skip-extra", action="store_true",
+                    help="leave out the side measurements of the later operators (GEMM + GELU, batched GEMM, first-layer conv, "
+                         "pooling, group norm), whose kernels share symbols with the chains' and would mix into per-kernel counters")
     ap.add_argument("--with-copy", action="store_true",
                     help="after the timed region also launch the library's plain copy kernel on a 25 690 112-byte "
                          "tensor (reference dispatches for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -394,6 +397,8 @@ def main() -> int:
 
         # operators built after those: one line each (rotated buffer sets for the memory-bound ones)
         def side_op(op, make, nsets, work, bound, note=None):
+            if args.skip_extra:
+                return
             calls, name = [], None
             for _ in range(nsets):
                 plan_, ins_, out_, ws_ = make()
