@@ -159,6 +159,8 @@ def gelu_tanh(Y):
 
 
 def conv_out_hw(H, W, R, S, stride, pad, dil=1):
+    # the filter must fit the padded image (otherwise the floor division below and the C routine's truncation disagree)
+    assert H + 2 * pad >= (R - 1) * dil + 1 and W + 2 * pad >= (S - 1) * dil + 1, "filter larger than the padded image"
     return (H + 2 * pad - (R - 1) * dil - 1) // stride + 1, (W + 2 * pad - (S - 1) * dil - 1) // stride + 1
 
 

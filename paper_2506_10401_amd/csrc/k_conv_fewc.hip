@@ -123,26 +123,129 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
     }
 }
 
-struct FewcGeom { int nseg, kblocks, ybands; int64_t items; };
+// 7 x 7, stride 2, pad 3 on at most 3 channels (a ResNet's first convolution): the same scheme.  A lane's four
+// output pixels 4 l + j read the input columns 8 l - 3 .. 8 l + 9 of a tap row (c, dy): four aligned quads
+// x[0..15] = columns 8 l - 4 .. 8 l + 11, of which output j at tap dx takes x[2 j + dx + 1]; a quad is inside
+// or outside the row as a whole (W % 4 == 0), so the zero padding is again the out-of-range buffer load.
+// Half-wave h takes the tap rows 2 i + h of the 7 C, and the seven dx of a tap row are seven MFMA steps.
+// The weights of the wave's 32 channels stay in registers (77 per lane for C = 3).
+constexpr int kRows7 = 2;   // output rows per wave
+
+template <int C>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 8))) void conv7x7s2_fewc(ConvParams p, int Ho, int Wo, int nseg, int kblocks, int ybands, int64_t items) {
+    constexpr int T = 7 * C;             // tap rows (c, dy)
+    constexpr int NI = (T + 1) / 2;      // tap rows per half-wave
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int64_t item = (int64_t)blockIdx.x * (kThreads / 64) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (item >= items) return;   // the whole wave; there are no barriers in this kernel
+    const int kb = (int)(item % kblocks);
+    int64_t t = item / kblocks;
+    const int seg = (int)(t % nseg); t /= nseg;
+    const int yb = (int)(t % ybands);
+    const int n = (int)(t / ybands);
+    const int H = p.H, W = p.W, K = p.K;
+    const int oxq = seg * kSeg + 4 * l32;    // first of this lane's four output pixels
+    const int xin = 2 * oxq - 4;             // input column of x[0]
+
+    float wv[NI][7];
+    int rel[NI], dyv[NI];   // byte offset of the tap row's plane relative to (c = 0, input row 2 y); its dy - 3
+    {
+        const float* wch = p.wt + (int64_t)(kb * 32 + l32) * (C * 49);
+        const float sc = p.scale ? p.scale[kb * 32 + l32] : 1.f;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int tap = 2 * i + h;
+            const bool ok = tap < T;
+            const int c = ok ? tap / 7 : 0, dyi = ok ? tap % 7 : 0;
+#pragma unroll
+            for (int dx = 0; dx < 7; ++dx) wv[i][dx] = ok ? wch[(c * 7 + dyi) * 7 + dx] * sc : 0.f;
+            rel[i] = ok ? ((c * H + dyi - 3) * W) * 4 : -1;   // -1: no tap row, nothing is loaded
+            dyv[i] = dyi - 3;
+        }
+    }
+    float add[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int ch = kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+        add[r] = (p.bias ? p.bias[ch] : 0.f) * (p.scale ? p.scale[ch] : 1.f) + (p.shift ? p.shift[ch] : 0.f);
+    }
+    const __amdgpu_buffer_rsrc_t os = __builtin_amdgcn_make_buffer_rsrc(
+        p.out + ((int64_t)n * K + kb * 32) * Ho * Wo, 0, 32 * Ho * Wo * 4, 0x00020000);
+    constexpr unsigned kOob = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(p.in) + (int64_t)n * C * H * W, 0, C * H * W * 4, 0x00020000);
+    bool q_ok[4];   // W % 4 == 0 and xin % 4 == 0: each quad is inside or outside the row as a whole
+#pragma unroll
+    for (int q = 0; q < 4; ++q) q_ok[q] = xin + 4 * q >= 0 && xin + 4 * q < W;
+    const bool o_ok = oxq < Wo;   // Wo % 4 == 0
+
+#pragma unroll 1
+    for (int yy = 0; yy < kRows7; ++yy) {
+        const int y = yb * kRows7 + yy;
+        if (y >= Ho) break;   // uniform
+        float16v acc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = add[r];
+        const int rowoff = (2 * y * W + xin) * 4;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const bool row_ok = rel[i] != -1 && (unsigned)(2 * y + dyv[i]) < (unsigned)H;
+            const unsigned o = (unsigned)(rel[i] + rowoff);
+            float x[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4v v = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)((row_ok && q_ok[q]) ? o + 16 * q : kOob), 0, 0));
+                x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+            }
+#pragma unroll
+            for (int dx = 0; dx < 7; ++dx)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = mfma_32x32x2(wv[i][dx], x[2 * j + dx + 1], acc[j]);
+        }
+        const unsigned ov = o_ok ? (unsigned)(((4 * h) * Ho * Wo + y * Wo + oxq) * 4) : kOob;   // (a store beyond the descriptor is dropped)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float4v v = {acc[0][r], acc[1][r], acc[2][r], acc[3][r]};
+            if (p.relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+            if (p.relu == 2) { v.x = fminf(v.x, 6.f); v.y = fminf(v.y, 6.f); v.z = fminf(v.z, 6.f); v.w = fminf(v.w, 6.f); }
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned, v), os, (int)ov,
+                                                   ((8 * (r >> 2) + (r & 3)) * Ho * Wo) * 4, 0);
+        }
+    }
+}
+
+struct FewcGeom { int Ho, Wo, nseg, kblocks, ybands; int64_t items; };
+bool is7(const ConvParams& p) { return p.R == 7; }
 FewcGeom fewc_geom(const ConvParams& p) {
     FewcGeom g{};
-    g.nseg = (p.W + kSeg - 1) / kSeg;
+    g.Ho = is7(p) ? (p.H - 1) / 2 + 1 : p.H;
+    g.Wo = is7(p) ? (p.W - 1) / 2 + 1 : p.W;
+    const int rows = is7(p) ? kRows7 : kRowsPerWave;
+    g.nseg = (g.Wo + kSeg - 1) / kSeg;
     g.kblocks = p.K / 32;
-    g.ybands = (p.H + kRowsPerWave - 1) / kRowsPerWave;
+    g.ybands = (g.Ho + rows - 1) / rows;
     g.items = (int64_t)p.Nb * g.ybands * g.nseg * g.kblocks;
     return g;
 }
 
 }  // namespace
 
-// 3 x 3, stride 1, pad 1, no dilation, no pooling; at most 4 input channels; output channels in blocks of 32; rows of
-// whole quads that fill at least three quarters of their 128-pixel segments; an image within 31-bit byte offsets.
+// No dilation, no pooling; output channels in blocks of 32; rows of whole quads on both sides that fill at least three
+// quarters of their 128-pixel segments; an image and a block of 32 output planes within 31-bit byte offsets; and either
+// 3 x 3 / stride 1 / pad 1 on at most 4 input channels or 7 x 7 / stride 2 / pad 3 on at most 3.
 bool conv_fewc_ok(const ConvParams& p) {
-    if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1 || p.dil != 1 || p.pool) return false;
-    if (p.C < 1 || p.C > 4 || (p.K & 31) || (p.W & 3)) return false;
-    if ((int64_t)p.C * p.H * p.W * 4 >= (int64_t)1 << 31 || (int64_t)32 * p.H * p.W * 4 >= (int64_t)1 << 31) return false;
-    const int nseg = (p.W + kSeg - 1) / kSeg;
-    return p.W * 4 >= nseg * kSeg * 3;
+    if (p.R != p.S || p.dil != 1 || p.pool || (p.K & 31) || (p.W & 3) || p.C < 1) return false;
+    const bool k3 = p.R == 3 && p.stride == 1 && p.pad == 1 && p.C <= 4;
+    const bool k7 = p.R == 7 && p.stride == 2 && p.pad == 3 && p.C <= 3;
+    if (!k3 && !k7) return false;
+    const int Ho = k7 ? (p.H - 1) / 2 + 1 : p.H, Wo = k7 ? (p.W - 1) / 2 + 1 : p.W;
+    if (Wo & 3) return false;
+    if ((int64_t)p.C * p.H * p.W * 4 >= (int64_t)1 << 31 || (int64_t)32 * Ho * Wo * 4 >= (int64_t)1 << 31) return false;
+    const int nseg = (Wo + kSeg - 1) / kSeg;
+    return Wo * 4 >= nseg * kSeg * 3;
 }
 
 LaunchShape conv_fewc_shape(const ConvParams& p) {
@@ -151,13 +254,21 @@ LaunchShape conv_fewc_shape(const ConvParams& p) {
     s.grid[0] = (uint32_t)((g.items + kThreads / 64 - 1) / (kThreads / 64)); s.grid[1] = s.grid[2] = 1;
     s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
     s.lds_bytes = 0;
-    s.kernel = "conv3x3_fewc";
+    s.kernel = is7(p) ? "conv7x7s2_fewc" : "conv3x3_fewc";
     return s;
 }
 
 hipError_t conv_fewc_launch(const ConvParams& p, hipStream_t stream) {
     const FewcGeom g = fewc_geom(p);
     const dim3 grid((unsigned)((g.items + kThreads / 64 - 1) / (kThreads / 64))), block(kThreads);
+    if (is7(p)) {
+        switch (p.C) {
+            case 1: hipLaunchKernelGGL(conv7x7s2_fewc<1>, grid, block, 0, stream, p, g.Ho, g.Wo, g.nseg, g.kblocks, g.ybands, g.items); break;
+            case 2: hipLaunchKernelGGL(conv7x7s2_fewc<2>, grid, block, 0, stream, p, g.Ho, g.Wo, g.nseg, g.kblocks, g.ybands, g.items); break;
+            default: hipLaunchKernelGGL(conv7x7s2_fewc<3>, grid, block, 0, stream, p, g.Ho, g.Wo, g.nseg, g.kblocks, g.ybands, g.items); break;
+        }
+        return hipGetLastError();
+    }
     switch (p.C) {
         case 1: hipLaunchKernelGGL(conv3x3_fewc<1>, grid, block, 0, stream, p, g.nseg, g.kblocks, g.ybands, g.items); break;
         case 2: hipLaunchKernelGGL(conv3x3_fewc<2>, grid, block, 0, stream, p, g.nseg, g.kblocks, g.ybands, g.items); break;

@@ -705,6 +705,25 @@ def test_conv3x3_few_input_channels(N, C, H, W, K):
         assert name.startswith("conv2d_nchw_mfma<3x3")
 
 
+@pytest.mark.parametrize("N,C,H,W,K", [
+    (2, 3, 30, 224, 64),         # a ResNet's first convolution: 112 output pixels per row, one segment
+    (1, 3, 17, 256, 32),         # a full segment, an odd number of input rows
+    (2, 1, 9, 232, 32),          # a grey image, 116 output pixels
+    (1, 2, 8, 200, 64),
+    (1, 3, 2, 480, 96),          # two segments, one output row
+    (3, 3, 11, 224, 128)])
+def test_conv7x7_stride2_few_input_channels(N, C, H, W, K):
+    print("conv 7x7/2 fewc %s" % ((N, C, H, W, K),), flush=True)
+    t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=7, S=7)
+    _, name = check_chain7(t, 2, 3, pool=False)
+    assert name == "conv7x7s2_fewc"
+    check_chain7(t, 2, 3, relu=False, pool=False, bias=False, affine=False)
+    # other strides and paddings: the general kernel
+    if H + 4 >= 7:
+        _, name = check_chain7(t, 2, 2, pool=False)
+        assert name.startswith("conv2d_nchw_mfma<7x7")
+
+
 def test_chain7_pool_takes_the_maximum_not_a_sum_or_a_corner():
     # identity 1x1 conv: the block is max pooling of the input, exactly
     X = datagen.gen_normal(11, (2, 4, 10, 66), 0.0, 1.0)
