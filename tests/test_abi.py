@@ -694,8 +694,11 @@ def test_conv_few_input_channels_plans():
     d7 = H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0,
                    [(32, 3, 224, 224), (64, 3, 7, 7), (64,)], [(32, 64, 112, 112)], stride_hw=(2, 2), pad_hw=(3, 3))
     p = H.Plan(d7)
-    assert p.kernel_name == "conv7x7s2_fewc" and p.launch_shape() == ((32 * 56 * 1 * 2 // 4, 1, 1), (256, 1, 1), 0)
-    for d in (cd((32, 3, 224, 224), 48), cd((32, 3, 224, 224), 64, stride=2), cd((32, 3, 224, 224), 64, pad=0),
+    assert p.kernel_name == "conv7x7s2_fewc" and p.launch_shape() == ((32 * 112 * 1 * 2 // 4, 1, 1), (256, 1, 1), 0)
+    # a MobileNet's: 3x3 / 2 / pad 1
+    p = H.Plan(cd((32, 3, 224, 224), 32, stride=2))
+    assert p.kernel_name == "conv3x3_fewc<stride2>" and p.launch_shape()[0] == (32 * 112 * 1 * 1 // 4, 1, 1)   # a row per wave: few waves otherwise
+    for d in (cd((32, 3, 224, 224), 48), cd((32, 3, 224, 224), 64, stride=3), cd((32, 3, 224, 224), 64, pad=0), cd((32, 3, 224, 220), 64, stride=2),
               cd((32, 3, 224, 224), 64, pool=True), cd((32, 3, 224, 222), 64), cd((32, 5, 224, 224), 64), cd((2, 3, 32, 32), 64)):
         assert H.Plan(d).kernel_name.startswith("conv2d_nchw_mfma<3x3")
 

@@ -705,6 +705,17 @@ def test_conv3x3_few_input_channels(N, C, H, W, K):
         assert name.startswith("conv2d_nchw_mfma<3x3")
 
 
+@pytest.mark.parametrize("N,C,H,W,K", [(2, 3, 30, 224, 32), (1, 3, 17, 256, 32), (2, 1, 9, 232, 32), (1, 4, 8, 200, 64), (1, 3, 2, 480, 96),
+                                       (3, 2, 1, 224, 64)])
+def test_conv3x3_stride2_few_input_channels(N, C, H, W, K):
+    # a MobileNet's first convolution: odd and even heights, one and two segments, a single row
+    print("conv 3x3/2 fewc %s" % ((N, C, H, W, K),), flush=True)
+    t = datagen.make(7, N=N, C=C, H=H, W=W, K=K, R=3, S=3)
+    _, name = check_chain7(t, 2, 1, pool=False)
+    assert name == "conv3x3_fewc<stride2>"
+    check_chain7(t, 2, 1, relu=False, pool=False, bias=False, affine=False)
+
+
 @pytest.mark.parametrize("N,C,H,W,K", [
     (2, 3, 30, 224, 64),         # a ResNet's first convolution: 112 output pixels per row, one segment
     (1, 3, 17, 256, 32),         # a full segment, an odd number of input rows
