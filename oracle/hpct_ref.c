@@ -596,7 +596,8 @@ void ref_attention_causal(const float *Q, const float *K, const float *V,
  * un[1], ... are applied to v in that order:
  *   0 max(v, 0)      1 tanh-form GELU      2 v * scale      3 sqrt(v)     4 sin(v)
  *   5 cos(v)         6 exp(v)              7 tanh(v)        8 1 / (1 + exp(-v))
- *   9 min(max(v, 0), 6)
+ *   9 min(max(v, 0), 6)      10 |v|        11 -v        12 v * v        13 ln(v)
+ *   14 v / (1 + exp(-v)) (SiLU)         15 v * min(max(v + 3, 0), 6) / 6 (hard swish)
  * Everything in double from the widened fp32 operands; libm supplies the
  * transcendental functions. */
 void ref_eltwise_map(const float *a, const float *b, int32_t nd, const int64_t *shape,
@@ -630,7 +631,13 @@ void ref_eltwise_map(const float *a, const float *b, int32_t nd, const int64_t *
                 case 6: v = exp(v); break;
                 case 7: v = tanh(v); break;
                 case 8: v = 1.0 / (1.0 + exp(-v)); break;
-                default: v = v < 0.0 ? 0.0 : (v > 6.0 ? 6.0 : v); break;   /* 9: relu6 */
+                case 9: v = v < 0.0 ? 0.0 : (v > 6.0 ? 6.0 : v); break;
+                case 10: v = fabs(v); break;
+                case 11: v = -v; break;
+                case 12: v = v * v; break;
+                case 13: v = log(v); break;
+                case 14: v = v / (1.0 + exp(-v)); break;
+                default: { double t = v + 3.0; t = t < 0.0 ? 0.0 : (t > 6.0 ? 6.0 : t); v = v * t / 6.0; } break;   /* 15: hard swish */
             }
         }
         out[lin] = v;

@@ -315,7 +315,8 @@ def eltwise_binary(a_base, b_base, shape, sa, sb, op, relu_=False):
 
 
 MAP_BINARY = {"add": 0, "mul": 1, "sub": 2, "div": 3}
-MAP_UNARY = {"relu": 0, "gelu": 1, "scale": 2, "sqrt": 3, "sin": 4, "cos": 5, "exp": 6, "tanh": 7, "sigmoid": 8, "relu6": 9}
+MAP_UNARY = {"relu": 0, "gelu": 1, "scale": 2, "sqrt": 3, "sin": 4, "cos": 5, "exp": 6, "tanh": 7, "sigmoid": 8, "relu6": 9,
+             "abs": 10, "neg": 11, "square": 12, "log": 13, "silu": 14, "hardswish": 15}
 
 
 def eltwise_map(a_base, shape, sa, unary=(), binary=None, b_base=None, sb=None, scale=1.0):

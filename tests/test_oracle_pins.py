@@ -645,6 +645,32 @@ def test_reduce_axis_against_numpy_on_strided_views():
             assert np.array_equal(ref.reduce_axis(base, shape, stride, axis, "argmin"), v.argmin(axis=axis))
 
 
+def test_eltwise_map_further_unary_steps():
+    rng = np.random.default_rng(41)
+    x = (rng.standard_normal(500) * 3.0).astype(np.float32)
+    x64 = x.astype(np.float64)
+    m = lambda steps, a=x: ref.eltwise_map(a, (a.size,), (1,), unary=steps)   # noqa: E731
+    # library routines and identities
+    assert np.array_equal(m(["abs"]), np.abs(x64)) and np.array_equal(m(["neg"]), -x64) and np.array_equal(m(["square"]), x64 * x64)
+    assert np.array_equal(m(["neg", "neg"]), x64) and np.array_equal(m(["abs", "sqrt", "square"]), np.sqrt(np.abs(x64)) ** 2)
+    pos = (np.abs(x) + np.float32(0.01)).astype(np.float32)
+    assert np.allclose(m(["log"], pos), np.log(pos.astype(np.float64)), rtol=1e-15, atol=0)
+    assert np.allclose(m(["log", "exp"], pos), pos.astype(np.float64), rtol=1e-14)
+    one = np.array([1.0, np.e], np.float32)
+    assert m(["log"], one)[0] == 0.0 and abs(m(["log"], one)[1] - np.log(np.float64(one[1]))) < 1e-16
+    # SiLU = x * logistic(x) (the pinned step 8); silu(x) - silu(-x) = x; silu(0) = 0
+    assert np.allclose(m(["silu"]), x64 * m(["sigmoid"]), rtol=1e-15, atol=0)
+    assert np.allclose(m(["silu"]) - m(["neg", "silu"]), x64, rtol=0, atol=1e-14)
+    assert m(["silu"], np.zeros(1, np.float32))[0] == 0.0
+    # hard swish: 0 below -3, x above 3, x (x + 3) / 6 between; printed values at -1, 0, 1
+    hs = m(["hardswish"])
+    assert np.array_equal(hs[x64 <= -3], np.zeros((x64 <= -3).sum())) and np.array_equal(hs[x64 >= 3], x64[x64 >= 3])
+    mid = (x64 > -3) & (x64 < 3)
+    assert np.allclose(hs[mid], x64[mid] * (x64[mid] + 3.0) / 6.0, rtol=1e-15, atol=0)
+    pts = m(["hardswish"], np.array([-1.0, 0.0, 1.0, 3.0, -3.0], np.float32))
+    assert np.allclose(pts, [-1.0 / 3.0, 0.0, 2.0 / 3.0, 3.0, 0.0], rtol=1e-15, atol=0)
+
+
 def test_groupnorm_reduces_to_layernorm_and_closed_forms():
     rng = np.random.default_rng(31)
     X = (rng.standard_normal((3, 12, 5, 7)) * 2.0 + 0.7).astype(np.float32)
