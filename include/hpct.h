@@ -154,7 +154,13 @@ typedef enum {
     HPCT_EPI_EXP = 15,            /* exp(x) */
     HPCT_EPI_TANH = 16,           /* tanh(x) */
     HPCT_EPI_SIGMOID = 17,        /* 1 / (1 + exp(-x)) */
-    HPCT_EPI_RELU6 = 18           /* min(max(x, 0), 6): in place of RELU in a conv chain, or a unary step */
+    HPCT_EPI_RELU6 = 18,          /* min(max(x, 0), 6): in place of RELU in a conv chain, or a unary step */
+    HPCT_EPI_ABS = 19,            /* unary steps of an elementwise chain: |x| */
+    HPCT_EPI_NEG = 20,            /* -x */
+    HPCT_EPI_SQUARE = 21,         /* x * x */
+    HPCT_EPI_LOG = 22,            /* natural logarithm */
+    HPCT_EPI_SILU = 23,           /* x / (1 + exp(-x)) */
+    HPCT_EPI_HARDSWISH = 24       /* x * min(max(x + 3, 0), 6) / 6 */
 } hpct_epilogue;
 
 /* Row reductions (Table 1, Reduction). */

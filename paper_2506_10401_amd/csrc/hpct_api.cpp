@@ -450,6 +450,12 @@ int unary_code(hpct_epilogue e) {
         case HPCT_EPI_TANH: return kUnTanh;
         case HPCT_EPI_SIGMOID: return kUnSigmoid;
         case HPCT_EPI_RELU6: return kUnRelu6;
+        case HPCT_EPI_ABS: return kUnAbs;
+        case HPCT_EPI_NEG: return kUnNeg;
+        case HPCT_EPI_SQUARE: return kUnSquare;
+        case HPCT_EPI_LOG: return kUnLog;
+        case HPCT_EPI_SILU: return kUnSilu;
+        case HPCT_EPI_HARDSWISH: return kUnHardswish;
         default: return -1;
     }
 }
@@ -486,7 +492,7 @@ hpct_status plan_eltwise(const hpct_op_desc& d, hpct_plan& p) {
         un[i - first] = unary_code(d.epi[i]);
         if (un[i - first] < 0)
             return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: epilogues must be [ADD|MUL|SUB|DIV_TENSOR] followed by "
-                        "RELU, RELU6, GELU_TANH, SCALE_CONST, SQRT, SIN, COS, EXP, TANH or SIGMOID steps");
+                        "RELU, RELU6, GELU_TANH, SCALE_CONST, SQRT, SIN, COS, EXP, TANH, SIGMOID, ABS, NEG, SQUARE, LOG, SILU or HARDSWISH steps");
     }
     if (d.reduce != HPCT_RED_NONE) return fail(HPCT_ERR_UNSUPPORTED, "elementwise chain on views: no reduction is supported after it");
     const int need = bin >= 0 ? 2 : 1;
@@ -778,7 +784,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
     for (int e = 0; e < d.n_epi; ++e)
-        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_RELU6) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
+        if ((int)d.epi[e] < 0 || (int)d.epi[e] > (int)HPCT_EPI_HARDSWISH) return fail(HPCT_ERR_BAD_DESC, "unknown epilogue %d at position %d", (int)d.epi[e], e);
 
     hpct_plan tmp;
     std::memset(&tmp, 0, sizeof tmp);

@@ -57,9 +57,33 @@ __device__ __forceinline__ void unary_step(float (&v)[E], int code, float scale)
 #pragma unroll
             for (int i = 0; i < E; ++i) v[i] = 1.f / (1.f + expf(-v[i]));
             break;
-        default:  // kUnRelu6
+        case kUnRelu6:
 #pragma unroll
             for (int i = 0; i < E; ++i) v[i] = fminf(fmaxf(v[i], 0.f), 6.f);
+            break;
+        case kUnAbs:
+#pragma unroll
+            for (int i = 0; i < E; ++i) v[i] = fabsf(v[i]);
+            break;
+        case kUnNeg:
+#pragma unroll
+            for (int i = 0; i < E; ++i) v[i] = -v[i];
+            break;
+        case kUnSquare:
+#pragma unroll
+            for (int i = 0; i < E; ++i) v[i] = v[i] * v[i];
+            break;
+        case kUnLog:
+#pragma unroll
+            for (int i = 0; i < E; ++i) v[i] = logf(v[i]);
+            break;
+        case kUnSilu:
+#pragma unroll
+            for (int i = 0; i < E; ++i) v[i] = v[i] / (1.f + expf(-v[i]));
+            break;
+        default:  // kUnHardswish
+#pragma unroll
+            for (int i = 0; i < E; ++i) v[i] = v[i] * fminf(fmaxf(v[i] + 3.f, 0.f), 6.f) * (1.f / 6.f);
             break;
     }
 }

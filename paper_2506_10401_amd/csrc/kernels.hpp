@@ -74,7 +74,8 @@ hipError_t layout_launch(const LayoutParams& p, hipStream_t stream);
 constexpr int kEltwiseDims = 6;
 constexpr int kEltwiseSteps = 8;
 enum : int32_t { kEltAdd = 0, kEltMul = 1, kEltSub = 2, kEltDiv = 3, kEltNone = 4 };
-enum : int32_t { kUnRelu = 0, kUnGelu, kUnScale, kUnSqrt, kUnSin, kUnCos, kUnExp, kUnTanh, kUnSigmoid, kUnRelu6 };
+enum : int32_t { kUnRelu = 0, kUnGelu, kUnScale, kUnSqrt, kUnSin, kUnCos, kUnExp, kUnTanh, kUnSigmoid, kUnRelu6,
+                 kUnAbs, kUnNeg, kUnSquare, kUnLog, kUnSilu, kUnHardswish };   // 16 codes: four bits each in EltwiseParams::un
 struct EltwiseParams {
     const float* a; const float* b; float* out;
     int32_t nd;                      // collapsed dimensions, 1..kEltwiseDims

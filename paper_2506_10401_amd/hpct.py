@@ -26,7 +26,7 @@ HPCT_ANCHOR_NONE, HPCT_ANCHOR_GEMM, HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM, HPCT_ANCHOR
 HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL, HPCT_EPI_GELU_TANH, \
     HPCT_EPI_SCALE_CONST, HPCT_EPI_DROPOUT_HASH, HPCT_EPI_CAUSAL_MASK, HPCT_EPI_ADD_TENSOR, HPCT_EPI_MUL_TENSOR, \
     HPCT_EPI_SUB_TENSOR, HPCT_EPI_DIV_TENSOR, HPCT_EPI_SQRT, HPCT_EPI_SIN, HPCT_EPI_COS, HPCT_EPI_EXP, HPCT_EPI_TANH, \
-    HPCT_EPI_SIGMOID, HPCT_EPI_RELU6 = range(19)
+    HPCT_EPI_SIGMOID, HPCT_EPI_RELU6, HPCT_EPI_ABS, HPCT_EPI_NEG, HPCT_EPI_SQUARE, HPCT_EPI_LOG, HPCT_EPI_SILU, HPCT_EPI_HARDSWISH = range(25)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS, HPCT_RED_MAX_AXIS, \
     HPCT_RED_MIN_AXIS, HPCT_RED_MAXPOOL_HW, HPCT_RED_GROUPNORM_NCHW = range(14)
@@ -392,7 +392,8 @@ def maxpool(X, out, window, stride, pad=0, stream=None) -> None:
 _MAP_BINARY = {"add": HPCT_EPI_ADD_TENSOR, "mul": HPCT_EPI_MUL_TENSOR, "sub": HPCT_EPI_SUB_TENSOR, "div": HPCT_EPI_DIV_TENSOR}
 _MAP_UNARY = {"relu": HPCT_EPI_RELU, "gelu": HPCT_EPI_GELU_TANH, "scale": HPCT_EPI_SCALE_CONST, "sqrt": HPCT_EPI_SQRT,
               "sin": HPCT_EPI_SIN, "cos": HPCT_EPI_COS, "exp": HPCT_EPI_EXP, "tanh": HPCT_EPI_TANH,
-              "sigmoid": HPCT_EPI_SIGMOID, "relu6": HPCT_EPI_RELU6}
+              "sigmoid": HPCT_EPI_SIGMOID, "relu6": HPCT_EPI_RELU6, "abs": HPCT_EPI_ABS, "neg": HPCT_EPI_NEG,
+              "square": HPCT_EPI_SQUARE, "log": HPCT_EPI_LOG, "silu": HPCT_EPI_SILU, "hardswish": HPCT_EPI_HARDSWISH}
 
 
 def eltwise_map_plan(a_view, out, unary=(), binary=None, b_view=None, scale=1.0):

@@ -542,6 +542,16 @@ def test_gemm_transposed_weight_and_scale_plans():
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_BIAS_COL)))
 
 
+def test_eltwise_further_steps_plans():
+    for e in (H.HPCT_EPI_ABS, H.HPCT_EPI_NEG, H.HPCT_EPI_SQUARE, H.HPCT_EPI_LOG, H.HPCT_EPI_SILU, H.HPCT_EPI_HARDSWISH):
+        p = H.Plan(H.op_desc(H.HPCT_ANCHOR_NONE, [e, H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0, [(64, 128)], [(64, 128)]))
+        assert p.kernel_name == "eltwise_unary<vec4>"
+        # unary steps of elementwise chains only: no contraction chain takes them
+        expect(H.HPCT_ERR_UNSUPPORTED, H.op_desc(H.HPCT_ANCHOR_GEMM, [e], H.HPCT_RED_NONE, 0, [(64, 32), (32, 64)], [(64, 64)]))
+    d = H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_SIN], H.HPCT_RED_NONE, 0, [(7, 9)], [(7, 9)]); d.epi[0] = 25
+    expect(H.HPCT_ERR_BAD_DESC, d)
+
+
 def test_gemm_strided_x_plans():
     def g(xstride, M=512, K=256, N=512):
         return H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_BIAS_COL], H.HPCT_RED_NONE, 0,

@@ -1031,6 +1031,30 @@ def test_eltwise_unary_views_and_ranges():
     check_unary(wide, "wide", [("exp",), ("tanh",), ("sigmoid",), ("gelu",)])
 
 
+def test_eltwise_further_unary_steps():
+    a = dev(datagen.gen_normal(93, (7, 12, 20), 0.0, 3.0))
+    flat = host(a).reshape(-1)
+    # |x|, -x and x*x are exact (the product of two fp32 values rounded once)
+    for steps in (("abs",), ("neg",), ("square",), ("neg", "abs", "neg")):
+        out = torch.full(tuple(a.shape), float("nan"), device="cuda")
+        hpct.eltwise_map(a, out, steps)
+        want = ref.eltwise_map(flat, tuple(a.shape), tuple(a.stride()), steps)
+        assert np.array_equal(host(out), want.astype(np.float32)), steps
+    more = [("silu",), ("hardswish",), ("abs", "log"), ("square", "log"), ("silu", "scale", "hardswish"), ("abs", "sqrt", "silu", "neg", "exp")]
+    assert check_unary(a, "more", more) == {"eltwise_unary<vec4>"}
+    check_unary(a.permute(2, 0, 1), "more, permuted", more)
+    wide = dev(datagen.gen_uniform(89, (64, 100), -80.0, 80.0))
+    check_unary(wide, "wide", [("silu",), ("hardswish",)])
+    tiny = dev(datagen.gen_uniform(88, (64, 100), 1e-30, 1e30))
+    check_unary(tiny, "log over 60 decades", [("log",)])
+    # a binary op in front
+    b = dev(datagen.gen_uniform(87, (20,), 0.5, 2.0)).expand(7, 12, 20)
+    out = torch.full((7, 12, 20), float("nan"), device="cuda")
+    hpct.eltwise_map(a, out, ("hardswish", "square"), "mul", b)
+    want = ref.eltwise_map(flat, (7, 12, 20), (240, 20, 1), ("hardswish", "square"), "mul", view_flat(b), (0, 0, 1))
+    assert show("mul + hardswish + square", compare.pointwise(host(out), want))
+
+
 def test_eltwise_binary_then_steps():
     a = dev(datagen.gen_uniform(98, (33, 40), 0.5, 4.0))
     b = dev(datagen.gen_uniform(99, (40,), 0.5, 2.0)).expand(33, 40)
