@@ -494,6 +494,33 @@ void ref_maxpool2d_planes(const double *T, int64_t planes, int64_t H, int64_t W,
     }
 }
 
+/* ---- Reduction: average pooling with a k x k window, stride s and padding p
+ * (p < k) over the planes of an NCHW tensor (Table 1 "mean" over windows; the
+ * pooling of the transition layers of the Level-3 networks of Section 5.1):
+ *   out[pl][oy][ox] = (1 / k^2) sum over dy, dx in 0..k-1 of T[pl][oy s - p + dy][ox s - p + dx],
+ * positions outside the image counting as zeros (the divisor is always k^2), for
+ * oy < (H + 2p - k) / s + 1, ox < (W + 2p - k) / s + 1 (integer division). */
+void ref_avgpool2d_planes(const double *T, int64_t planes, int64_t H, int64_t W, int64_t k, int64_t s, int64_t p,
+                          double *out)
+{
+    const int64_t Ho = (H + 2 * p - k) / s + 1, Wo = (W + 2 * p - k) / s + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t pl = 0; pl < planes; ++pl) {
+        for (int64_t oy = 0; oy < Ho; ++oy) {
+            for (int64_t ox = 0; ox < Wo; ++ox) {
+                double acc = 0.0;
+                for (int64_t dy = 0; dy < k; ++dy)
+                    for (int64_t dx = 0; dx < k; ++dx) {
+                        int64_t iy = oy * s - p + dy, ix = ox * s - p + dx;
+                        if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+                        acc += T[(pl * H + iy) * W + ix];
+                    }
+                out[(pl * Ho + oy) * Wo + ox] = acc / (double)(k * k);
+            }
+        }
+    }
+}
+
 /* ---- Reduction (Table 1: "sum, mean" and the arg-reductions) over one axis of
  * a strided view.  The view has `nd` dims with `shape` and `stride` (elements,
  * >= 0); the output is the view with dim `axis` removed, row-major.

@@ -46,6 +46,7 @@ def lib():
             "ref_scale_shift_planes": [p, p, p, i64, i64, i64],
             "ref_maxpool2x2_planes": [p, i64, i64, i64, p],
             "ref_maxpool2d_planes": [p, i64, i64, i64, i64, i64, i64, p],
+            "ref_avgpool2d_planes": [p, i64, i64, i64, i64, i64, i64, p],
             "ref_groupnorm_nchw": [p, p, p, i64, i64, i64, i64, dbl, p],
             "ref_reduce_axis": [p, C.c_int32, p, p, C.c_int32, C.c_int32, p, p, p],
             "ref_eltwise_binary": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p],
@@ -296,6 +297,18 @@ def maxpool2d(T, k, stride, pad):
     out = np.empty((Nb, Cc, (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1), dtype=np.float64)
     if out.size:
         lib().ref_maxpool2d_planes(_ptr(T), Nb * Cc, H, W, k, stride, pad, _ptr(out))
+    return out
+
+
+def avgpool2d(T, k, stride, pad):
+    """k x k average pooling with stride and padding (pad < k; padding counts as zeros, the divisor is k*k) over the
+    last two dims of an fp64 NCHW array; output extent (H + 2 pad - k) // stride + 1."""
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    Nb, Cc, H, W = T.shape
+    assert 0 <= pad < k and stride >= 1 and H + 2 * pad >= k and W + 2 * pad >= k
+    out = np.empty((Nb, Cc, (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1), dtype=np.float64)
+    if out.size:
+        lib().ref_avgpool2d_planes(_ptr(T), Nb * Cc, H, W, k, stride, pad, _ptr(out))
     return out
 
 

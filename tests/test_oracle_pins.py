@@ -736,6 +736,26 @@ def test_maxpool2d_against_sliding_windows_and_special_cases():
     assert np.array_equal(ref.maxpool2d(T[:, :, :7, :], 7, 1, 0)[:, :, 0, 0], T[:, :, :7, :].max(axis=(2, 3)))
 
 
+def test_avgpool2d_against_sliding_windows_and_special_cases():
+    rng = np.random.default_rng(23)
+    for (H, W, k, s, p) in [(9, 11, 3, 2, 1), (8, 8, 2, 2, 0), (7, 10, 3, 1, 1), (12, 5, 5, 3, 2), (6, 6, 3, 2, 0), (10, 10, 7, 2, 3)]:
+        T = rng.standard_normal((2, 3, H, W)) + 1.0
+        P = np.zeros((2, 3, H + 2 * p, W + 2 * p))
+        P[:, :, p:p + H, p:p + W] = T
+        win = np.lib.stride_tricks.sliding_window_view(P, (k, k), axis=(2, 3))[:, :, ::s, ::s]
+        assert np.allclose(ref.avgpool2d(T, k, s, p), win.mean(axis=(4, 5)), rtol=0, atol=1e-14), (H, W, k, s, p)
+    # a window as large as the image: the global average pool of chain 2; a 1x1 window: the identity
+    T = rng.standard_normal((2, 2, 6, 6))
+    assert np.allclose(ref.avgpool2d(T, 6, 1, 0)[:, :, 0, 0], T.mean(axis=(2, 3)), rtol=0, atol=1e-15)
+    assert np.array_equal(ref.avgpool2d(T, 1, 1, 0), T)
+    # an image of ones, 3x3 / 1 / pad 1: 1 inside, 6/9 on the edges, 4/9 in the corners
+    O = ref.avgpool2d(np.ones((1, 1, 5, 5)), 3, 1, 1)[0, 0]
+    assert np.allclose(O[1:-1, 1:-1], 1.0) and np.allclose(O[0, 1:-1], 6.0 / 9.0) and np.allclose(O[0, 0], 4.0 / 9.0) and np.allclose(O[-1, -1], 4.0 / 9.0)
+    # linear: pool(2 a - 3 b) = 2 pool(a) - 3 pool(b)
+    A, B = rng.standard_normal((1, 2, 7, 9)), rng.standard_normal((1, 2, 7, 9))
+    assert np.allclose(ref.avgpool2d(2 * A - 3 * B, 3, 2, 1), 2 * ref.avgpool2d(A, 3, 2, 1) - 3 * ref.avgpool2d(B, 3, 2, 1), rtol=0, atol=1e-13)
+
+
 def test_reduce_axis_max_min_values():
     # against numpy on strided views; the value at the arg-reduction's index; min(x) = -max(-x); a ramp; infinities
     rng = np.random.default_rng(9)
