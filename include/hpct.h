@@ -64,8 +64,8 @@
  *                                                                                   int32 for the arg ops
  *   NONE  GROUPNORM_NCHW (groups, eps) [+RELU]         X[N,C,H,W], gamma[C],         [N,C,H,W]
  *         (reduce_before_epi = 1 with the ReLU)        beta[C] (or X alone)
- *   NONE  MAXPOOL_HW (window_hw, stride_hw, pad_hw,    X[N,C,H,W]                    [N,C,Ho,Wo]
- *         each square), no epilogue
+ *   NONE  MAXPOOL_HW | AVGPOOL_WIN_HW (window_hw,      X[N,C,H,W]                    [N,C,Ho,Wo]
+ *         stride_hw, pad_hw, each square), no epilogue
  *   CONVT2D_NCHW [+BIAS_COL] [+SCALE_SHIFT_CH]        in[N,C,H,W], wt[C,K,R,S],     [N,K,Ho,Wo]
  *         [+RELU|RELU6] (needs the workspace: the     bias[K], scale[K], shift[K]
  *         flipped filter and, for stride > 1, the
@@ -180,7 +180,9 @@ typedef enum {
     HPCT_RED_MIN_AXIS = 11,       /* minimum over dim `axis`, which is dropped (fp32) */
     HPCT_RED_MAXPOOL_HW = 12,     /* max over window_hw windows of dims 2,3 of NCHW at stride_hw with pad_hw (padding never
                                      wins; pad < window); output extent (H + 2 pad - window) / stride + 1.  No anchor. */
-    HPCT_RED_GROUPNORM_NCHW = 13  /* group normalisation of X[N,C,H,W] with `groups` groups of C / groups neighbouring channels:
+    HPCT_RED_AVGPOOL_WIN_HW = 14, /* mean over window_hw windows of dims 2,3 at stride_hw with pad_hw, positions outside the image
+                                     counting as zeros (the divisor is always window * window); extents as MAXPOOL_HW.  No anchor. */
+    HPCT_RED_GROUPNORM_NCHW = 13, /* group normalisation of X[N,C,H,W] with `groups` groups of C / groups neighbouring channels:
                                      (x - mean) / sqrt(biased var + eps) over each image's group, * gamma[c] + beta[c];
                                      groups = C is instance normalisation.  No anchor; reduce_before_epi = 1 with an epilogue. */
 } hpct_reduce;
@@ -207,7 +209,7 @@ typedef struct {
     int32_t dilation_hw[2];       /* conv only: tap kh reads input row h*stride - pad + kh*dilation; 0 means 1 */
     int32_t groups;               /* GROUPNORM_NCHW: the number of groups.  Conv: 0 or 1 = dense; C (with K = C and wt[K,1,R,S]) = depthwise, every channel
                                      filtered by its own R x R filter.  Other group counts are not supported. */
-    int32_t window_hw[2];         /* MAXPOOL_HW: the pooling window (square: both equal), 1..16 */
+    int32_t window_hw[2];         /* MAXPOOL_HW, AVGPOOL_WIN_HW: the pooling window (square: both equal), 1..16 */
 } hpct_op_desc;
 
 typedef struct hpct_plan hpct_plan;   /* opaque; host memory */

@@ -386,8 +386,8 @@ hpct_status plan_maxpool(const hpct_op_desc& d, hpct_plan& p) {
 
 // k x k max pooling with stride and padding of an NCHW tensor without an anchor.
 hpct_status plan_maxpool_gen(const hpct_op_desc& d, hpct_plan& p) {
-    if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL_HW takes no epilogues");
-    if (d.n_in != 1 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "MAXPOOL_HW takes 1 input and 1 output");
+    if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "MAXPOOL_HW / AVGPOOL_WIN_HW take no epilogues");
+    if (d.n_in != 1 || d.n_out != 1) return fail(HPCT_ERR_BAD_DESC, "MAXPOOL_HW / AVGPOOL_WIN_HW take 1 input and 1 output");
     const hpct_tensor_desc& X = d.in[0];
     if (X.ndim != 4) return fail(HPCT_ERR_SHAPE_MISMATCH, "X must be 4-D NCHW");
     const int32_t k = d.window_hw[0], st = d.stride_hw[0], pad = d.pad_hw[0];
@@ -403,7 +403,7 @@ hpct_status plan_maxpool_gen(const hpct_op_desc& d, hpct_plan& p) {
     REQUIRE_SHAPE(d.out[0], "out[0]", Nb, C, Ho, Wo);
     if (!contiguous(X) || !contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "only contiguous NCHW layouts are supported");
     p.kind = Kind::MaxPoolGen;
-    p.pool = PoolParams{Nb * C, (int32_t)H, (int32_t)W, k, st, pad};
+    p.pool = PoolParams{Nb * C, (int32_t)H, (int32_t)W, k, st, pad, d.reduce == HPCT_RED_AVGPOOL_WIN_HW ? 1 : 0};
     p.slot[0] = 0; p.slot[1] = p.slot[2] = p.slot[3] = p.slot[4] = p.slot[5] = -1;
     p.shape = maxpool_shape(p.pool);
     return HPCT_OK;
@@ -779,7 +779,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
     if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONVT2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
-    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_GROUPNORM_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_AVGPOOL_WIN_HW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
     if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
@@ -815,7 +815,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
         default:
             if (d.reduce == HPCT_RED_MEAN_LAST) return fail(HPCT_ERR_UNSUPPORTED, "MEAN_LAST is supported only after a GEMM anchor");
             if (d.reduce == HPCT_RED_MAXPOOL2_HW) { st = plan_maxpool(d, tmp); break; }
-            if (d.reduce == HPCT_RED_MAXPOOL_HW) { st = plan_maxpool_gen(d, tmp); break; }
+            if (d.reduce == HPCT_RED_MAXPOOL_HW || d.reduce == HPCT_RED_AVGPOOL_WIN_HW) { st = plan_maxpool_gen(d, tmp); break; }
             if (d.reduce == HPCT_RED_GROUPNORM_NCHW) { st = plan_groupnorm(d, tmp); break; }
             if (is_eltwise_chain(d)) st = plan_eltwise(d, tmp);
             else if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);

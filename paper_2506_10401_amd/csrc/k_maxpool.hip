@@ -1,7 +1,8 @@
-// Max pooling of NCHW planes with a k x k window, a stride and padding (Reduction class of the paper's
-// Table 1; the pooling layers of the networks that its Section 5.1 names as Level-3 tasks, e.g. the
-// 3 x 3 / stride 2 / pad 1 pooling behind a ResNet's first convolution).  Padding never wins: the maximum
-// is taken over the window's positions inside the image.  Memory-bound, exact.
+// Max and average pooling of NCHW planes with a k x k window, a stride and padding (Reduction class of the
+// paper's Table 1; the pooling layers of the networks that its Section 5.1 names as Level-3 tasks, e.g. the
+// 3 x 3 / stride 2 / pad 1 pooling behind a ResNet's first convolution).  Max: padding never wins, the maximum
+// is taken over the window's positions inside the image; exact.  Average (AVG instances): positions outside
+// the image count as zeros and the divisor is always k * k.  Memory-bound.
 //
 // maxpool3x3_rows: 3 x 3, pad 1, stride 1 or 2, whole quads on both sides - the stencil scheme of the
 // depthwise 3 x 3 kernel with max in place of multiply-add.  A wave owns 56 output columns x 16 output rows
@@ -23,7 +24,7 @@ constexpr int kCH = 4;       // output rows per lane
 
 struct PoolRowsGeom { int H, W, Ho, Wo, nseg, bands; int64_t items; };
 
-template <int ST>
+template <int ST, bool AVG>
 __global__ __launch_bounds__(kThreads) void maxpool3x3_rows(const float* __restrict__ in, float* __restrict__ out, PoolRowsGeom g) {
     constexpr int NQ = ST, NR = (kCH - 1) * ST + 3;   // input quads per lane and row; input rows per lane
     const int lane = threadIdx.x & 63;
@@ -61,7 +62,7 @@ __global__ __launch_bounds__(kThreads) void maxpool3x3_rows(const float* __restr
     for (int j = 0; j < NR; ++j) {
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
-            if (!ok[j][q]) v[j][q] = float4v{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            if (!AVG && !ok[j][q]) v[j][q] = float4v{-INFINITY, -INFINITY, -INFINITY, -INFINITY};   // (AVG: the zeros the load returned)
             x[j][1 + 4 * q] = v[j][q].x; x[j][2 + 4 * q] = v[j][q].y; x[j][3 + 4 * q] = v[j][q].z; x[j][4 + 4 * q] = v[j][q].w;
         }
         x[j][0] = dpp_mov<0x111>(v[j][NQ - 1].w);       // row_shr:1 - the last column of the lane to the left
@@ -70,17 +71,24 @@ __global__ __launch_bounds__(kThreads) void maxpool3x3_rows(const float* __restr
     float* __restrict__ po = out + plane * (int64_t)g.Ho * g.Wo + ox0;
 #pragma unroll
     for (int i = 0; i < kCH; ++i) {
-        float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        float m[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m[j] = AVG ? 0.f : -INFINITY;
 #pragma unroll
         for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
             for (int kw = 0; kw < 3; ++kw)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) m[j] = fmaxf(m[j], x[i * ST + kh][j * ST + kw]);
+                for (int j = 0; j < 4; ++j) m[j] = AVG ? m[j] + x[i * ST + kh][j * ST + kw] : fmaxf(m[j], x[i * ST + kh][j * ST + kw]);
+        if (AVG) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) m[j] *= (1.f / 9.f);
+        }
         if (comp && rr + i < g.Ho) store4_nt(po + (int64_t)(rr + i) * g.Wo, float4v{m[0], m[1], m[2], m[3]});
     }
 }
 
+template <bool AVG>
 __global__ __launch_bounds__(kThreads) void maxpool_any(const float* __restrict__ in, float* __restrict__ out, int64_t planes,
                                                         int H, int W, int Ho, int Wo, int k, int s, int p) {
     const int64_t total = planes * Ho * Wo;
@@ -90,16 +98,16 @@ __global__ __launch_bounds__(kThreads) void maxpool_any(const float* __restrict_
         const int oy = (int)(t % Ho);
         const int64_t plane = t / Ho;
         const float* src = in + plane * (int64_t)H * W;
-        float m = -INFINITY;
+        float m = AVG ? 0.f : -INFINITY;
         for (int dy = 0; dy < k; ++dy) {
             const int iy = oy * s - p + dy;
             if (iy < 0 || iy >= H) continue;
             for (int dx = 0; dx < k; ++dx) {
                 const int ix = ox * s - p + dx;
-                if (ix >= 0 && ix < W) m = fmaxf(m, src[(int64_t)iy * W + ix]);
+                if (ix >= 0 && ix < W) m = AVG ? m + src[(int64_t)iy * W + ix] : fmaxf(m, src[(int64_t)iy * W + ix]);
             }
         }
-        out[o] = m;
+        out[o] = AVG ? m / (float)(k * k) : m;
     }
 }
 
@@ -133,7 +141,7 @@ unsigned any_grid(const PoolParams& p) {
 }  // namespace
 
 LaunchShape maxpool_shape(const PoolParams& p) {
-    if (p.k == 2 && p.stride == 2 && p.pad == 0) return maxpool2_shape(p.planes, p.H, p.W);
+    if (!p.avg && p.k == 2 && p.stride == 2 && p.pad == 0) return maxpool2_shape(p.planes, p.H, p.W);
     LaunchShape s{};
     s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
     s.grid[1] = s.grid[2] = 1;
@@ -141,24 +149,31 @@ LaunchShape maxpool_shape(const PoolParams& p) {
     if (rows_ok(p)) {
         const PoolRowsGeom g = rows_geom(p);
         s.grid[0] = (uint32_t)((g.items + kThreads / 64 - 1) / (kThreads / 64));
-        s.kernel = p.stride == 2 ? "maxpool3x3_rows<stride2>" : "maxpool3x3_rows";
+        s.kernel = p.avg ? (p.stride == 2 ? "avgpool3x3_rows<stride2>" : "avgpool3x3_rows")
+                         : (p.stride == 2 ? "maxpool3x3_rows<stride2>" : "maxpool3x3_rows");
     } else {
         s.grid[0] = any_grid(p);
-        s.kernel = "maxpool_any";
+        s.kernel = p.avg ? "avgpool_any" : "maxpool_any";
     }
     return s;
 }
 
 hipError_t maxpool_launch(const PoolParams& p, const float* in, float* out, hipStream_t stream) {
-    if (p.k == 2 && p.stride == 2 && p.pad == 0) return maxpool2_launch(in, out, p.planes, p.H, p.W, stream);
+    if (!p.avg && p.k == 2 && p.stride == 2 && p.pad == 0) return maxpool2_launch(in, out, p.planes, p.H, p.W, stream);
     if (rows_ok(p)) {
         const PoolRowsGeom g = rows_geom(p);
         const dim3 grid((unsigned)((g.items + kThreads / 64 - 1) / (kThreads / 64))), block(kThreads);
-        if (p.stride == 2) hipLaunchKernelGGL(maxpool3x3_rows<2>, grid, block, 0, stream, in, out, g);
-        else hipLaunchKernelGGL(maxpool3x3_rows<1>, grid, block, 0, stream, in, out, g);
+        if (p.avg) {
+            if (p.stride == 2) hipLaunchKernelGGL((maxpool3x3_rows<2, true>), grid, block, 0, stream, in, out, g);
+            else hipLaunchKernelGGL((maxpool3x3_rows<1, true>), grid, block, 0, stream, in, out, g);
+        } else {
+            if (p.stride == 2) hipLaunchKernelGGL((maxpool3x3_rows<2, false>), grid, block, 0, stream, in, out, g);
+            else hipLaunchKernelGGL((maxpool3x3_rows<1, false>), grid, block, 0, stream, in, out, g);
+        }
     } else {
         const int Ho = (p.H + 2 * p.pad - p.k) / p.stride + 1, Wo = (p.W + 2 * p.pad - p.k) / p.stride + 1;
-        hipLaunchKernelGGL(maxpool_any, dim3(any_grid(p)), dim3(kThreads), 0, stream, in, out, p.planes, p.H, p.W, Ho, Wo, p.k, p.stride, p.pad);
+        if (p.avg) hipLaunchKernelGGL(maxpool_any<true>, dim3(any_grid(p)), dim3(kThreads), 0, stream, in, out, p.planes, p.H, p.W, Ho, Wo, p.k, p.stride, p.pad);
+        else hipLaunchKernelGGL(maxpool_any<false>, dim3(any_grid(p)), dim3(kThreads), 0, stream, in, out, p.planes, p.H, p.W, Ho, Wo, p.k, p.stride, p.pad);
     }
     return hipGetLastError();
 }

@@ -41,7 +41,7 @@ LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool);
 LaunchShape maxpool2_shape(int64_t planes, int32_t H, int32_t W);
 hipError_t maxpool2_launch(const float* X, float* out, int64_t planes, int32_t H, int32_t W, hipStream_t stream);
 // k_maxpool.hip: k x k max pooling with stride and padding (pad < k; padding never wins); 2 x 2 / 2 / 0 goes to maxpool2
-struct PoolParams { int64_t planes; int32_t H, W, k, stride, pad; };
+struct PoolParams { int64_t planes; int32_t H, W, k, stride, pad; int32_t avg; };   // avg: the mean with zero padding (divisor k*k) instead of the maximum
 LaunchShape maxpool_shape(const PoolParams& p);
 hipError_t maxpool_launch(const PoolParams& p, const float* in, float* out, hipStream_t stream);
 hipError_t affine_launch(const AffineParams& p, hipStream_t stream);

@@ -29,7 +29,7 @@ HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL
     HPCT_EPI_SIGMOID, HPCT_EPI_RELU6, HPCT_EPI_ABS, HPCT_EPI_NEG, HPCT_EPI_SQUARE, HPCT_EPI_LOG, HPCT_EPI_SILU, HPCT_EPI_HARDSWISH = range(25)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS, HPCT_RED_MAX_AXIS, \
-    HPCT_RED_MIN_AXIS, HPCT_RED_MAXPOOL_HW, HPCT_RED_GROUPNORM_NCHW = range(14)
+    HPCT_RED_MIN_AXIS, HPCT_RED_MAXPOOL_HW, HPCT_RED_GROUPNORM_NCHW, HPCT_RED_AVGPOOL_WIN_HW = range(15)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
 
 
@@ -380,6 +380,20 @@ def maxpool_plan(X, out, window, stride, pad=0):
         HPCT_ANCHOR_NONE, [], HPCT_RED_MAXPOOL_HW, 0, [_sh(X)], [_sh(out)], stride_hw=(stride, stride), pad_hw=(pad, pad),
         window_hw=(window, window)))
     return plan, [X]
+
+
+def avgpool_plan(X, out, window, stride, pad=0):
+    plan = _cached(("avgpool", _sh(X), window, stride, pad), lambda: op_desc(
+        HPCT_ANCHOR_NONE, [], HPCT_RED_AVGPOOL_WIN_HW, 0, [_sh(X)], [_sh(out)], stride_hw=(stride, stride), pad_hw=(pad, pad),
+        window_hw=(window, window)))
+    return plan, [X]
+
+
+def avgpool(X, out, window, stride, pad=0, stream=None) -> None:
+    """out[n,c,y,x] = mean of the window x window positions of X[n,c] from (y stride - pad, x stride - pad), positions
+    outside the image counting as zeros (divisor window * window); extents as maxpool."""
+    plan, ins = avgpool_plan(X, out, window, stride, pad)
+    plan.launch(ins, [out], stream)
 
 
 def maxpool(X, out, window, stride, pad=0, stream=None) -> None:

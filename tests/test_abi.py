@@ -468,7 +468,7 @@ def test_axis_reduction_errors():
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_ARGMAX_AXIS, out_dtype=H.HPCT_F32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS, out_dtype=H.HPCT_I32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_MAX_AXIS, out_dtype=H.HPCT_I32))
-    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 14))      # one past the last reduction
+    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 15))      # one past the last reduction
     d = cfg_desc(3); d.out[0].dtype = H.HPCT_I32          # int32 anywhere else
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.n_epi = 1; d.epi[0] = H.HPCT_EPI_RELU
@@ -762,6 +762,12 @@ def test_maxpool_plans_and_errors():
     for (shape, k, s, pad) in [((2, 3, 30, 30), 3, 2, 1), ((2, 3, 112, 112), 3, 2, 0), ((2, 3, 57, 57), 5, 3, 2), ((1, 1, 7, 7), 7, 1, 0),
                                ((2, 3, 112, 110), 3, 2, 1)]:
         assert H.Plan(pool_desc(shape, k, s, pad)).kernel_name == "maxpool_any"
+    # average pooling: the same kernels' AVG instances; 2x2 has no kernel of its own
+    def avg(shape, k, s_, pad):
+        d = pool_desc(shape, k, s_, pad); d.reduce = H.HPCT_RED_AVGPOOL_WIN_HW
+        return H.Plan(d).kernel_name
+    assert avg((32, 64, 112, 112), 3, 2, 1) == "avgpool3x3_rows<stride2>" and avg((8, 16, 56, 56), 3, 1, 1) == "avgpool3x3_rows"
+    assert avg((32, 64, 56, 56), 2, 2, 0) == "avgpool_any" and avg((2, 3, 57, 57), 5, 3, 2) == "avgpool_any"
     expect(H.HPCT_ERR_BAD_DESC, pool_desc((2, 3, 8, 8), 3, 2, 3))                    # padding as large as the window
     expect(H.HPCT_ERR_BAD_DESC, pool_desc((2, 3, 8, 8), 0, 1, 0, out_shape=(2, 3, 8, 8)))
     expect(H.HPCT_ERR_BAD_DESC, pool_desc((2, 3, 8, 8), 3, 0, 1, out_shape=(2, 3, 8, 8)))

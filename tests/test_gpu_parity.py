@@ -1215,6 +1215,30 @@ def test_maxpool_general_windows(shape, k, stride, pad):
     assert check_maxpool(shape, k, stride, pad) == "maxpool_any"
 
 
+def check_avgpool(shape, k, stride, pad, seed=0):
+    x = datagen.gen_normal(750 + seed, shape, 0.3, 1.0)
+    want = ref.avgpool2d(x, k, stride, pad)
+    mag = ref.avgpool2d(np.abs(x), k, stride, pad)
+    out = torch.full(want.shape, float("nan"), device="cuda")
+    plan, ins = hpct.avgpool_plan(dev(x), out, k, stride, pad)
+    plan.launch(ins, [out])
+    got = host(out)
+    # a mean of k*k fp32 terms: error far inside the contraction bound relative to the mean of magnitudes
+    assert show("avgpool %s %s" % (plan.kernel_name, (shape, k, stride, pad)), compare.contraction(got, want, mag + 1e-300))
+    assert np.all(np.abs(got - want) <= 1e-5 * mag + 1e-30)
+    return plan.kernel_name
+
+
+def test_avgpool_windows():
+    assert check_avgpool((32, 64, 112, 112), 3, 2, 1) == "avgpool3x3_rows<stride2>"
+    assert check_avgpool((32, 64, 56, 56), 3, 1, 1) == "avgpool3x3_rows"
+    assert check_avgpool((32, 64, 56, 56), 2, 2, 0) == "avgpool_any"
+    for (shape, k, stride, pad) in [((2, 3, 57, 112), 3, 2, 1), ((1, 2, 100, 48), 3, 1, 1), ((2, 2, 5, 52), 3, 1, 1), ((1, 3, 2, 400), 3, 2, 1)]:
+        assert check_avgpool(shape, k, stride, pad, seed=1).startswith("avgpool3x3_rows")
+    for (shape, k, stride, pad) in [((2, 3, 30, 30), 3, 2, 1), ((1, 3, 57, 57), 5, 3, 2), ((1, 1, 7, 7), 7, 1, 0), ((2, 2, 33, 31), 16, 5, 7), ((1, 2, 6, 40), 2, 1, 1)]:
+        assert check_avgpool(shape, k, stride, pad, seed=2) == "avgpool_any"
+
+
 # ---------------------------------------- depthwise conv (MobileNetV2's depthwise layer) and relu6
 def check_depthwise(N, C, H, W, R, stride, pad, dil=1, act="relu6", bias=True, affine=True, seed=0):
     x = datagen.gen_normal(300 + seed, (N, C, H, W), 0.0, 1.0)
