@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhpct.so")
-SOURCES = ["hpct_api.cpp", "k_layernorm.hip", "k_groupnorm.hip", "k_affine_pool.hip", "k_maxpool.hip", "k_gemm.hip", "k_gemm_tile.hip", "k_gemm_direct.hip", "k_conv2d.hip", "k_attention.hip", "k_layout.hip", "k_reduce.hip", "k_eltwise.hip", "k_dwconv.hip", "k_conv1x1.hip", "k_conv_fewc.hip", "k_convt_prep.hip"]
+SOURCES = ["hpct_api.cpp", "k_layernorm.hip", "k_groupnorm.hip", "k_affine_pool.hip", "k_maxpool.hip", "k_gemm.hip", "k_gemm_tile.hip", "k_gemm_direct.hip", "k_gemm_skinny.hip", "k_conv2d.hip", "k_attention.hip", "k_layout.hip", "k_reduce.hip", "k_eltwise.hip", "k_dwconv.hip", "k_conv1x1.hip", "k_conv_fewc.hip", "k_convt_prep.hip"]
 HEADERS = ["kernels.hpp", "prim.hpp", os.path.join("..", "..", "include", "hpct.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -367,6 +367,7 @@ hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
     hipError_t e;
     p.ksplit = 1;
     if (p.batch < 1) p.batch = 1;
+    if (p.skinny) return gemm_skinny_launch(p, stream);
     if (gemm_use_tile(p.M, p.K, p.N, p0.softmax, p.mean, p.batch)) {
         p.ksplit = gemm_ksplit(p.M, p.K, p.N, p.mean, p.batch);
         e = gemm_direct_ok(p.M, p.K, p.N, p.mean, p.wt, p.batch) ? gemm_direct_launch(p, stream) : gemm_tile_launch(p, stream);

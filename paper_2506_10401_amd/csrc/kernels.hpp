@@ -132,6 +132,7 @@ struct GemmParams {
     int32_t mean;         // reduce over the last dim instead of storing [M,N]
     int32_t softmax2;     // softmax over the M means
     float* ws;            // partial row sums (`mean`) or the K slices' partial products (ksplit > 1)
+    int32_t skinny;       // 1: the streaming kernel for a very small N or M (set by the plan from gemm_skinny_ok)
     int32_t ksplit;       // K slices of the tiled kernel, >= 1 (set by the plan from gemm_ksplit)
     float scale;          // (X W + bias) * scale before ReLU; 1 when the chain has no SCALE_CONST
     int32_t wt;           // W is stored transposed: element (k, n) at n * K + k (an [N,K] row-major array)
@@ -149,6 +150,10 @@ hipError_t gemm_launch(const GemmParams& p, hipStream_t stream);
 LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit, int32_t wt, int32_t batch = 1);
 int32_t gemm_tile_col_tiles(int32_t M, int32_t N, int32_t batch = 1);
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream);
+// k_gemm_skinny.hip: N <= 8, or M <= 8 with a transposed W: the large operand streamed row by row (HBM-bound)
+bool gemm_skinny_ok(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t dropout, int32_t wt);
+LaunchShape gemm_skinny_shape(int32_t M, int32_t K, int32_t N, int32_t wt, int32_t batch);
+hipError_t gemm_skinny_launch(const GemmParams& p, hipStream_t stream);
 // k_gemm_direct.hip: products with a short K, operands loaded straight into the MFMA layout (no LDS)
 bool gemm_direct_ok(int32_t M, int32_t K, int32_t N, int32_t mean, int32_t wt, int32_t batch);
 LaunchShape gemm_direct_shape(int32_t M, int32_t N, int32_t batch);

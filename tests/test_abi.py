@@ -552,6 +552,24 @@ def test_eltwise_further_steps_plans():
     expect(H.HPCT_ERR_BAD_DESC, d)
 
 
+def test_gemm_skinny_plans():
+    def g(M, K, N, wstride=None, red=H.HPCT_RED_NONE, epi=(H.HPCT_EPI_BIAS_COL,)):
+        return H.op_desc(H.HPCT_ANCHOR_GEMM, list(epi), red, 0, [(M, K), H.tensor_desc((K, N), wstride), (N,)], [(M, N)])
+    # a matrix times a vector: a wave per row of X, four rows per group; few long rows: a group per row
+    p = H.Plan(g(8192, 4096, 1))
+    assert p.kernel_name == "gemm_skinny<rows of X>" and p.launch_shape()[0] == (2048, 1, 1) and p.workspace_bytes == 0
+    p = H.Plan(g(256, 131072, 1))
+    assert p.kernel_name == "gemm_skinny<rows of X>" and p.launch_shape()[0] == (256, 1, 1)
+    assert H.Plan(g(8192, 4096, 8, wstride=(1, 4096))).kernel_name == "gemm_skinny<rows of X,wt>"
+    # a vector times a linear layer's transposed weight: the rows of W are streamed
+    p = H.Plan(g(1, 4096, 8192, wstride=(1, 4096)))
+    assert p.kernel_name == "gemm_skinny<rows of W>" and p.launch_shape()[0] == (2048, 1, 1)
+    # not: 9 columns, a row-major W under a small M, a softmax or dropout behind it, K % 4, small operands
+    for d in (g(8192, 4096, 9), g(1, 4096, 8192), g(8192, 4096, 4, red=H.HPCT_RED_SOFTMAX_LAST),
+              g(8192, 4096, 4, epi=(H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_DROPOUT_HASH)), g(8192, 4098, 1), g(512, 512, 1)):
+        assert not H.Plan(d).kernel_name.startswith("gemm_skinny")
+
+
 def test_gemm_strided_x_plans():
     def g(xstride, M=512, K=256, N=512):
         return H.op_desc(H.HPCT_ANCHOR_GEMM, [H.HPCT_EPI_BIAS_COL], H.HPCT_RED_NONE, 0,

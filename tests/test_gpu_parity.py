@@ -283,6 +283,50 @@ def test_gemm_strided_x(M, K, N):
         assert compare.contraction(host(out)[i], Zi, Di).ok, i
 
 
+@pytest.mark.parametrize("M,K,N,wt", [
+    (300, 4096, 1, False), (5000, 256, 3, False), (1024, 1028, 8, False), (64, 20000, 2, False), (4100, 512, 5, True), (33, 32768, 1, True),
+    (1, 4096, 600, True), (5, 1024, 2000, True), (8, 260, 5000, True), (2, 65536, 17, True)])
+def test_gemm_skinny_shapes(M, K, N, wt):
+    # matrix-vector products and tall-skinny shapes: the rows of the large operand are streamed (a wave or a work-group per row)
+    print("gemm skinny M=%d K=%d N=%d wt=%s" % (M, K, N, wt), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    got, name = run_gemm(t, wt=wt, relu=False)
+    assert name.startswith("gemm_skinny<"), name
+    # (with N = 1 the transposed storage is also row-major)
+    assert name == ("gemm_skinny<rows of W>" if M <= 8 and N > 8 else ("gemm_skinny<rows of X,wt>" if wt and N > 1 else "gemm_skinny<rows of X>"))
+    assert show("skinny %s" % name, compare.contraction(got, Z, Dn))
+    assert np.max(np.abs(got - Z) / Dn) < 1e-5
+    got, _ = run_gemm(t, wt=wt, relu="gelu", scale=0.5)
+    assert show("skinny + scale + gelu", compare.contraction(got, ref.gelu_tanh(ref.scale_const(Z, 0.5)), Dn * 0.6 + 1e-6))
+    Z0, D0 = ref.gemm_bias(t["X"], t["W"], None, want_norm=True)
+    got, _ = run_gemm(t, wt=wt, relu=True, bias=False)
+    assert show("skinny, no bias, relu", compare.contraction(got, ref.relu(Z0), D0))
+
+
+def test_gemm_skinny_batch_and_fallbacks():
+    B, M, K, N = 3, 700, 2048, 2
+    X = datagen.gen_normal(630, (B, M, K), 0.0, 1.0)
+    W = datagen.gen_normal(631, (B, K, N), 0.0, 1.0 / np.sqrt(K))
+    out = torch.full((B, M, N), float("nan"), device="cuda")
+    plan, ins = hpct.gemm_bias_relu_softmax_plan(dev(X), dev(W), None, out, relu=False, softmax=False)
+    assert plan.kernel_name == "gemm_skinny<rows of X>" and plan.launch_shape()[0] == (M, B, 1)
+    plan.launch(ins, [out])
+    for i in range(B):
+        Zi, Di = ref.gemm_bias(X[i], W[i], None, want_norm=True)
+        assert compare.contraction(host(out)[i], Zi, Di).ok, i
+    # with a softmax behind it, a row-major W for a small M, a K that is not a multiple of 4 or a small operand: the other kernels
+    t = datagen.make(1, M=300, K=4096, N=4)
+    _, name = run_gemm(t, softmax=True)
+    assert not name.startswith("gemm_skinny")
+    for (M2, K2, N2) in [(1, 4096, 600), (300, 4098, 1), (100, 512, 2)]:
+        t = datagen.make(1, M=M2, K=K2, N=N2)
+        Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+        got, name = run_gemm(t)
+        assert not name.startswith("gemm_skinny")
+        assert compare.contraction(got, ref.relu(Z), Dn).ok
+
+
 def test_gemm_short_k_direct_kernel():
     # operands straight into the MFMA layout: K below, at and between the 32-wide chunks, the dropout epilogue
     # (an integer decision per element), and a batch
