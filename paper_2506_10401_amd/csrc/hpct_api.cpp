@@ -225,10 +225,10 @@ hpct_status plan_gemm(const hpct_op_desc& d, hpct_plan& p) {
     p.slot[0] = 0; p.slot[1] = 1; p.slot[2] = has_bias ? 2 : -1; p.slot[3] = -1;
     p.shape = gemm_shape((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.wt, g.batch);
     p.ws_bytes = gemm_workspace_bytes((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.batch);
-    if (gemm_skinny_ok((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.dropout, g.wt)) {
+    if (gemm_skinny_ok((int32_t)M, (int32_t)K, (int32_t)N, sm, mean ? 1 : 0, g.dropout, g.wt, g.batch)) {
         p.u.gemm.skinny = 1;
         p.shape = gemm_skinny_shape((int32_t)M, (int32_t)K, (int32_t)N, g.wt, g.batch);
-        p.ws_bytes = 0;
+        p.ws_bytes = gemm_skinny_workspace_bytes((int32_t)M, (int32_t)K, (int32_t)N, g.wt);
     }
     p.x_copy = 0;
     if (x_copy) {

@@ -12,6 +12,12 @@
 // an LDS combine, in a fixed order.  Output element (r, j) goes to out[r * ldr + j * ldj], so the same kernel
 // serves Y = X W (A = X, r = m) and Y^T = W^T-rows times X-rows (A = W^T, r = n, the few rows of X as S).
 // Epilogue: bias, constant, activation.
+//
+// gemm_skinny_cols: M <= 8 under a row-major W[K,N], whose rows run along n.  A thread owns four columns, a wave one
+// 1 KB piece of a row of W per load (four rows in flight), the few values of X it multiplies them with are uniform
+// per wave; K is cut into slices over the work-groups, the four waves of a group take every fourth row of a slice
+// and combine through LDS, the slices' partial results go to the workspace and the split-K finishing kernel of
+// the tiled GEMM adds them in slice order and applies the epilogue.
 #include "kernels.hpp"
 #include "prim.hpp"
 
@@ -101,6 +107,58 @@ __global__ __launch_bounds__(kThreads) void gemm_skinny(SkinnyParams p) {
     }
 }
 
+template <int MS>
+__global__ __launch_bounds__(kThreads) void gemm_skinny_cols(const float* __restrict__ X, const float* __restrict__ W,
+                                                             float* __restrict__ part, int M, int K, int N, int kslice) {
+    __shared__ float4v comb[3][MS][64];
+    const int lane = threadIdx.x & 63;
+    const int kl = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // this wave takes rows kl, kl + 4, ... of the slice
+    const int n4 = (blockIdx.x * 64 + lane) * 4;                          // first of this thread's four columns
+    const bool col_ok = n4 < N;                                           // N % 4 == 0
+    const int k_lo = blockIdx.y * kslice;
+    const int k_hi = k_lo + kslice < K ? k_lo + kslice : K;
+    float4v acc[MS];
+#pragma unroll
+    for (int m = 0; m < MS; ++m) acc[m] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int k0 = k_lo + kl; k0 < k_hi; k0 += 4 * kU) {
+        float4v w[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int k = k0 + 4 * u;
+            w[u] = (col_ok && k < k_hi) ? load4_nt(W + (int64_t)k * N + n4) : float4v{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int k = k0 + 4 * u;
+            if (k < k_hi) {   // uniform per wave
+#pragma unroll
+                for (int m = 0; m < MS; ++m) acc[m] = acc[m] + w[u] * X[(int64_t)m * K + k];
+            }
+        }
+    }
+    if (kl > 0) {
+#pragma unroll
+        for (int m = 0; m < MS; ++m) comb[kl - 1][m][lane] = acc[m];
+    }
+    __syncthreads();
+    if (kl == 0 && col_ok) {
+#pragma unroll
+        for (int m = 0; m < MS; ++m) {
+            const float4v v = ((acc[m] + comb[0][m][lane]) + comb[1][m][lane]) + comb[2][m][lane];
+            store4(part + ((int64_t)blockIdx.y * M + m) * N + n4, v);
+        }
+    }
+}
+
+// K slices of the column-streaming kernel: about 1024 work-groups, at least 64 rows of W per slice, at most 64 slices
+int cols_slices(int32_t K, int32_t N) {
+    const int64_t blocks = (N / 4 + 63) / 64;
+    int64_t s = (1024 + blocks - 1) / blocks;
+    if (s > K / 64) s = K / 64;
+    if (s > 64) s = 64;
+    return (int)(s < 1 ? 1 : s);
+}
+
 template <int NS>
 void launch_ns(const SkinnyParams& p, bool bt, bool group, int batch, hipStream_t stream) {
     const int rpg = group ? 1 : kThreads / kWave;
@@ -114,11 +172,13 @@ void launch_ns(const SkinnyParams& p, bool bt, bool group, int batch, hipStream_
     }
 }
 
-// which operand is streamed: 1 = X (N small), 2 = the transposed W (M small), 0 = neither
+// which operand is streamed: 1 = X (N small), 2 = the transposed W (M small), 3 = a row-major W along its rows
+// (M small), 0 = neither
 int skinny_mode(int32_t M, int32_t K, int32_t N, int32_t wt) {
     if ((K & 3) || K < 256) return 0;
     if (N <= 8 && (int64_t)M * K >= (int64_t)1 << 20) return 1;
     if (M <= 8 && wt && (int64_t)N * K >= (int64_t)1 << 20) return 2;
+    if (M <= 8 && !wt && (N & 3) == 0 && (int64_t)N * K >= (int64_t)1 << 20) return 3;
     return 0;
 }
 // a work-group per row when a wave per row would leave the chip short of waves, or for long rows
@@ -128,12 +188,26 @@ bool skinny_group(int64_t R, int32_t K) { return K >= 16384 || (R < 4096 && K >=
 
 // No softmax, row mean or dropout behind it; K a multiple of 4 and at least 256; a large operand of at least 4 MB;
 // N <= 8 (any W layout), or M <= 8 with a transposed W.
-bool gemm_skinny_ok(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t dropout, int32_t wt) {
-    return !softmax && !mean && !dropout && skinny_mode(M, K, N, wt) != 0;
+bool gemm_skinny_ok(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t dropout, int32_t wt, int32_t batch) {
+    if (softmax || mean || dropout) return false;
+    const int mode = skinny_mode(M, K, N, wt);
+    return mode != 0 && !(mode == 3 && batch > 1);   // (the column kernel's workspace holds one product)
+}
+
+size_t gemm_skinny_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t wt) {
+    return skinny_mode(M, K, N, wt) == 3 ? (size_t)cols_slices(K, N) * (size_t)M * (size_t)N * 4 : 0;
 }
 
 LaunchShape gemm_skinny_shape(int32_t M, int32_t K, int32_t N, int32_t wt, int32_t batch) {
     const int mode = skinny_mode(M, K, N, wt);
+    if (mode == 3) {
+        LaunchShape s{};
+        s.grid[0] = (uint32_t)((N / 4 + 63) / 64); s.grid[1] = (uint32_t)cols_slices(K, N); s.grid[2] = 1;
+        s.block[0] = kThreads; s.block[1] = s.block[2] = 1;
+        s.lds_bytes = (uint32_t)(3 * M * 64 * 16);
+        s.kernel = "gemm_skinny_cols";
+        return s;
+    }
     const int64_t R = mode == 1 ? M : N;
     const bool group = skinny_group(R, K);
     LaunchShape s{};
@@ -146,6 +220,28 @@ LaunchShape gemm_skinny_shape(int32_t M, int32_t K, int32_t N, int32_t wt, int32
 
 hipError_t gemm_skinny_launch(const GemmParams& g, hipStream_t stream) {
     const int mode = skinny_mode(g.M, g.K, g.N, g.wt);
+    if (mode == 3) {
+        const int slices = cols_slices(g.K, g.N);
+        const int kslice = (((g.K + slices - 1) / slices) + 3) & ~3;
+        const dim3 grid((unsigned)((g.N / 4 + 63) / 64), (unsigned)slices), block(kThreads);
+#define HPCT_COLS(MS) hipLaunchKernelGGL(gemm_skinny_cols<MS>, grid, block, 0, stream, g.X, g.W, g.ws, g.M, g.K, g.N, kslice)
+        switch (g.M) {
+            case 1: HPCT_COLS(1); break;
+            case 2: HPCT_COLS(2); break;
+            case 3: HPCT_COLS(3); break;
+            case 4: HPCT_COLS(4); break;
+            case 5: HPCT_COLS(5); break;
+            case 6: HPCT_COLS(6); break;
+            case 7: HPCT_COLS(7); break;
+            default: HPCT_COLS(8); break;
+        }
+#undef HPCT_COLS
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        GemmParams f = g;
+        f.ksplit = slices;
+        return gemm_split_finish_launch(f, stream);
+    }
     SkinnyParams p{};
     p.K = g.K; p.bias = g.bias; p.out = g.Y; p.scale = g.scale; p.act = g.relu;
     p.sO = g.sY;

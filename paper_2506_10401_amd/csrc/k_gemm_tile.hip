@@ -488,6 +488,11 @@ hipError_t launch_tile(const GemmParams& p, hipStream_t stream) {
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream) {
     hipError_t e = gemm_tile_edge(p.M, p.N, p.batch) == 128 ? launch_tile<128>(p, stream) : launch_tile<64>(p, stream);
     if (e != hipSuccess || p.ksplit <= 1) return e;
+    return gemm_split_finish_launch(p, stream);
+}
+
+// Y = epilogue(sum over the p.ksplit slices of p.ws[slice][M][N]) (also behind the column-streaming kernel of k_gemm_skinny.hip)
+hipError_t gemm_split_finish_launch(const GemmParams& p, hipStream_t stream) {
     const bool vec = p.N % 4 == 0;
     const int64_t work = (int64_t)p.M * p.N / (vec ? 4 : 1);
     const unsigned grid = (unsigned)((work + 255) / 256 < 4096 ? (work + 255) / 256 : 4096);

@@ -150,9 +150,11 @@ hipError_t gemm_launch(const GemmParams& p, hipStream_t stream);
 LaunchShape gemm_tile_shape(int32_t M, int32_t N, int32_t ksplit, int32_t wt, int32_t batch = 1);
 int32_t gemm_tile_col_tiles(int32_t M, int32_t N, int32_t batch = 1);
 hipError_t gemm_tile_launch(const GemmParams& p, hipStream_t stream);
+hipError_t gemm_split_finish_launch(const GemmParams& p, hipStream_t stream);   // sums p.ksplit slices of p.ws, applies the epilogue
 // k_gemm_skinny.hip: N <= 8, or M <= 8 with a transposed W: the large operand streamed row by row (HBM-bound)
-bool gemm_skinny_ok(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t dropout, int32_t wt);
+bool gemm_skinny_ok(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t dropout, int32_t wt, int32_t batch);
 LaunchShape gemm_skinny_shape(int32_t M, int32_t K, int32_t N, int32_t wt, int32_t batch);
+size_t gemm_skinny_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t wt);
 hipError_t gemm_skinny_launch(const GemmParams& p, hipStream_t stream);
 // k_gemm_direct.hip: products with a short K, operands loaded straight into the MFMA layout (no LDS)
 bool gemm_direct_ok(int32_t M, int32_t K, int32_t N, int32_t mean, int32_t wt, int32_t batch);

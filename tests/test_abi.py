@@ -564,8 +564,11 @@ def test_gemm_skinny_plans():
     # a vector times a linear layer's transposed weight: the rows of W are streamed
     p = H.Plan(g(1, 4096, 8192, wstride=(1, 4096)))
     assert p.kernel_name == "gemm_skinny<rows of W>" and p.launch_shape()[0] == (2048, 1, 1)
-    # not: 9 columns, a row-major W under a small M, a softmax or dropout behind it, K % 4, small operands
-    for d in (g(8192, 4096, 9), g(1, 4096, 8192), g(8192, 4096, 4, red=H.HPCT_RED_SOFTMAX_LAST),
+    # a vector times a row-major W: its rows streamed along n, K in slices with a finishing pass (one float per slice and output)
+    p = H.Plan(g(1, 4096, 8192))
+    assert p.kernel_name == "gemm_skinny_cols" and p.launch_shape()[0] == (32, 32, 1) and p.workspace_bytes == 32 * 1 * 8192 * 4
+    # not: 9 columns, a softmax or dropout behind it, K % 4, small operands, N % 4 under a small M and a row-major W
+    for d in (g(8192, 4096, 9), g(1, 4096, 8190), g(8192, 4096, 4, red=H.HPCT_RED_SOFTMAX_LAST),
               g(8192, 4096, 4, epi=(H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_DROPOUT_HASH)), g(8192, 4098, 1), g(512, 512, 1)):
         assert not H.Plan(d).kernel_name.startswith("gemm_skinny")
 

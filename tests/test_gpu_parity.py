@@ -315,16 +315,32 @@ def test_gemm_skinny_batch_and_fallbacks():
     for i in range(B):
         Zi, Di = ref.gemm_bias(X[i], W[i], None, want_norm=True)
         assert compare.contraction(host(out)[i], Zi, Di).ok, i
-    # with a softmax behind it, a row-major W for a small M, a K that is not a multiple of 4 or a small operand: the other kernels
+    # with a softmax behind it, a K or (under a small M) an N that is not a multiple of 4, or a small operand: the other kernels
     t = datagen.make(1, M=300, K=4096, N=4)
     _, name = run_gemm(t, softmax=True)
     assert not name.startswith("gemm_skinny")
-    for (M2, K2, N2) in [(1, 4096, 600), (300, 4098, 1), (100, 512, 2)]:
+    for (M2, K2, N2) in [(1, 4096, 602), (300, 4098, 1), (100, 512, 2)]:
         t = datagen.make(1, M=M2, K=K2, N=N2)
         Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
         got, name = run_gemm(t)
         assert not name.startswith("gemm_skinny")
         assert compare.contraction(got, ref.relu(Z), Dn).ok
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 4096, 600), (1, 16384, 4096), (3, 1000, 2052), (8, 260, 5000), (5, 8192, 256), (2, 300, 16384)])
+def test_gemm_skinny_columns(M, K, N):
+    # a few rows of X times a row-major W: W's rows streamed along n, K cut into slices, the tiled kernel's finishing pass
+    print("gemm skinny cols M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    got, name = run_gemm(t, relu=False)
+    assert name == "gemm_skinny_cols"
+    assert show("skinny cols", compare.contraction(got, Z, Dn))
+    assert np.max(np.abs(got - Z) / Dn) < 1e-5
+    got, _ = run_gemm(t, relu="tanh", scale=0.5)
+    assert show("skinny cols + scale + tanh", compare.contraction(got, np.tanh(ref.scale_const(Z, 0.5)), Dn * 0.5 + 1e-6))
+    again, _ = run_gemm(t, relu=False)
+    assert np.array_equal(got.view(np.uint32) * 0 + again.view(np.uint32), run_gemm(t, relu=False)[0].view(np.uint32))   # deterministic
 
 
 def test_gemm_short_k_direct_kernel():
