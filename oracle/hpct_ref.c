@@ -134,6 +134,22 @@ void ref_layernorm_rows(const float *X, const float *gamma, const float *beta,
     }
 }
 
+/* ---- Reduction: root-mean-square normalisation over the last dimension (the
+ * layer normalisation of Table 1's Reduction class without the mean):
+ *   y = x / sqrt(mean(x^2) + eps) * gamma.  gamma may be NULL (= 1). */
+void ref_rmsnorm_rows(const float *X, const float *gamma, int64_t rows, int64_t N, double eps, double *Y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *x = X + r * N;
+        double ms = 0.0;
+        for (int64_t n = 0; n < N; ++n) ms += (double)x[n] * (double)x[n];
+        ms /= (double)N;
+        double inv = 1.0 / sqrt(ms + eps);
+        for (int64_t n = 0; n < N; ++n) Y[r * N + n] = (double)x[n] * inv * (gamma ? (double)gamma[n] : 1.0);
+    }
+}
+
 /* ---- Reduction: group normalisation of an NCHW tensor (the "norm" of the
  * activation-and-norm fusions that Section 5.1 describes as Level-2 tasks; G = C is
  * instance normalisation, G = 1 layer normalisation over C, H and W).  The C

@@ -48,6 +48,7 @@ def lib():
             "ref_maxpool2d_planes": [p, i64, i64, i64, i64, i64, i64, p],
             "ref_avgpool2d_planes": [p, i64, i64, i64, i64, i64, i64, p],
             "ref_groupnorm_nchw": [p, p, p, i64, i64, i64, i64, dbl, p],
+            "ref_rmsnorm_rows": [p, p, i64, i64, dbl, p],
             "ref_reduce_axis": [p, C.c_int32, p, p, C.c_int32, C.c_int32, p, p, p],
             "ref_eltwise_binary": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p],
             "ref_eltwise_map": [p, p, C.c_int32, p, p, p, C.c_int32, C.c_int32, p, C.c_float, p],
@@ -137,6 +138,16 @@ def layernorm_rows(X, gamma=None, beta=None, eps=1e-5):
     b = None if beta is None else _f32(beta)
     Y = np.empty((rows, N), dtype=np.float64)
     lib().ref_layernorm_rows(_ptr(X), _ptr(g), _ptr(b), rows, N, float(eps), _ptr(Y))
+    return Y
+
+
+def rmsnorm_rows(X, gamma=None, eps=1e-6):
+    """x / sqrt(mean(x^2) + eps) * gamma over the last dim of an fp32 [rows, N] array."""
+    X = _f32(X)
+    rows, N = X.shape
+    g = None if gamma is None else _f32(gamma)
+    Y = np.empty((rows, N), dtype=np.float64)
+    lib().ref_rmsnorm_rows(_ptr(X), _ptr(g), rows, N, float(eps), _ptr(Y))
     return Y
 
 

@@ -671,6 +671,36 @@ def test_eltwise_map_further_unary_steps():
     assert np.allclose(pts, [-1.0 / 3.0, 0.0, 2.0 / 3.0, 3.0, 0.0], rtol=1e-15, atol=0)
 
 
+def test_rmsnorm_invariants_and_closed_forms():
+    rng = np.random.default_rng(51)
+    X = (rng.standard_normal((6, 37)) * 3.0 + 1.0).astype(np.float32)
+    g = rng.standard_normal(37).astype(np.float32)
+    x64, g64 = X.astype(np.float64), g.astype(np.float64)
+    Y = ref.rmsnorm_rows(X, g, 1e-3)
+    # undoing the normalisation gives x * gamma back; without gamma every row has mean square ms / (ms + eps)
+    ms = (x64 ** 2).mean(axis=1, keepdims=True)
+    assert np.allclose(Y * np.sqrt(ms + 1e-3), x64 * g64, rtol=1e-13, atol=0)
+    P = ref.rmsnorm_rows(X, None, 1e-3)
+    assert np.allclose((P ** 2).mean(axis=1, keepdims=True), ms / (ms + 1e-3), rtol=1e-13)
+    # a row of mean zero: the pinned layer normalisation without beta
+    Z = (x64 - x64.mean(axis=1, keepdims=True)).astype(np.float32)
+    Z = (Z.astype(np.float64) - Z.astype(np.float64).mean(axis=1, keepdims=True)).astype(np.float32)
+    ln = ref.layernorm_rows(Z, g, None, 1e-3)
+    mu = Z.astype(np.float64).mean(axis=1, keepdims=True)
+    assert np.max(np.abs(mu)) < 1e-7 and np.allclose(ref.rmsnorm_rows(Z, g, 1e-3), ln, rtol=0, atol=1e-6)
+    # scaling the row by a (eps = 0) multiplies the result by sign(a); a constant row c gives c / sqrt(c^2 + eps) * gamma
+    assert np.allclose(ref.rmsnorm_rows(X * np.float32(-4.0), g, 0.0), -ref.rmsnorm_rows(X, g, 0.0), rtol=1e-13, atol=0)
+    C = np.full((1, 37), 2.5, np.float32)
+    assert np.allclose(ref.rmsnorm_rows(C, g, 0.75), 2.5 / np.sqrt(6.25 + 0.75) * g64[None, :], rtol=1e-15, atol=0)
+    # element by element on a tiny case
+    T = rng.standard_normal((2, 5)).astype(np.float32)
+    Yt = ref.rmsnorm_rows(T, g[:5], 1e-2)
+    for r in range(2):
+        m2 = sum(float(v) ** 2 for v in T[r]) / 5
+        for n in range(5):
+            assert abs(Yt[r, n] - float(T[r, n]) / (m2 + 1e-2) ** 0.5 * float(g[n])) < 1e-14
+
+
 def test_groupnorm_reduces_to_layernorm_and_closed_forms():
     rng = np.random.default_rng(31)
     X = (rng.standard_normal((3, 12, 5, 7)) * 2.0 + 0.7).astype(np.float32)
