@@ -62,6 +62,7 @@
  *         `axis`, no epilogue
  *                                                                                   (1-D input: shape [1]);
  *                                                                                   int32 for the arg ops
+ *   NONE  RMSNORM_LAST (eps), no epilogue              X[M,N], gamma[N] (or X alone) [M,N]
  *   NONE  GROUPNORM_NCHW (groups, eps) [+RELU]         X[N,C,H,W], gamma[C],         [N,C,H,W]
  *         (reduce_before_epi = 1 with the ReLU)        beta[C] (or X alone)
  *   NONE  MAXPOOL_HW | AVGPOOL_WIN_HW (window_hw,      X[N,C,H,W]                    [N,C,Ho,Wo]
@@ -180,6 +181,7 @@ typedef enum {
     HPCT_RED_MIN_AXIS = 11,       /* minimum over dim `axis`, which is dropped (fp32) */
     HPCT_RED_MAXPOOL_HW = 12,     /* max over window_hw windows of dims 2,3 of NCHW at stride_hw with pad_hw (padding never
                                      wins; pad < window); output extent (H + 2 pad - window) / stride + 1.  No anchor. */
+    HPCT_RED_RMSNORM_LAST = 15,   /* x / sqrt(mean(x^2) + eps) * gamma over the last dim of X[M,N] */
     HPCT_RED_AVGPOOL_WIN_HW = 14, /* mean over window_hw windows of dims 2,3 at stride_hw with pad_hw, positions outside the image
                                      counting as zeros (the divisor is always window * window); extents as MAXPOOL_HW.  No anchor. */
     HPCT_RED_GROUPNORM_NCHW = 13, /* group normalisation of X[N,C,H,W] with `groups` groups of C / groups neighbouring channels:

@@ -267,6 +267,20 @@ hpct_status plan_rows(const hpct_op_desc& d, hpct_plan& p) {
         p.shape = softmax_shape(M, (int32_t)N);
         return HPCT_OK;
     }
+    if (d.reduce == HPCT_RED_RMSNORM_LAST) {
+        if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "RMSNORM_LAST takes no epilogues");
+        if (d.n_in != 2 && d.n_in != 1) return fail(HPCT_ERR_BAD_DESC, "RMSNORM_LAST takes X and gamma (or X alone)");
+        if (d.n_in == 2) REQUIRE_SHAPE(d.in[1], "gamma", N);
+        for (int i = 0; i < d.n_in; ++i)
+            if (!contiguous(d.in[i])) return fail(HPCT_ERR_UNSUPPORTED, "in[%d]: only contiguous row-major layouts are supported", i);
+        if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous row-major layouts are supported");
+        if (!(d.eps >= 0.f)) return fail(HPCT_ERR_BAD_DESC, "eps must be >= 0");
+        p.kind = Kind::Layernorm;
+        p.u.ln = LayernormParams{nullptr, nullptr, nullptr, nullptr, M, (int32_t)N, d.eps, 0, 1};
+        p.slot[0] = 0; p.slot[1] = d.n_in == 2 ? 1 : -1; p.slot[2] = -1; p.slot[3] = -1;
+        p.shape = layernorm_shape(M, (int32_t)N, 1);
+        return HPCT_OK;
+    }
     bool gelu = false;
     if (d.n_epi == 1 && d.epi[0] == HPCT_EPI_GELU_TANH) gelu = true;
     else if (d.n_epi != 0) return fail(HPCT_ERR_UNSUPPORTED, "LAYERNORM_LAST: the only epilogue supported is GELU_TANH");
@@ -278,7 +292,7 @@ hpct_status plan_rows(const hpct_op_desc& d, hpct_plan& p) {
     if (!contiguous(d.out[0])) return fail(HPCT_ERR_UNSUPPORTED, "out[0]: only contiguous row-major layouts are supported");
     if (!(d.eps >= 0.f)) return fail(HPCT_ERR_BAD_DESC, "eps must be >= 0");
     p.kind = Kind::Layernorm;
-    p.u.ln = LayernormParams{nullptr, nullptr, nullptr, nullptr, M, (int32_t)N, d.eps, gelu ? 1 : 0};
+    p.u.ln = LayernormParams{nullptr, nullptr, nullptr, nullptr, M, (int32_t)N, d.eps, gelu ? 1 : 0, 0};
     p.slot[0] = 0; p.slot[1] = d.n_in == 3 ? 1 : -1; p.slot[2] = d.n_in == 3 ? 2 : -1; p.slot[3] = -1;
     p.shape = layernorm_shape(M, (int32_t)N);
     return HPCT_OK;
@@ -784,7 +798,7 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
     if (d.n_in < 1 || d.n_in > HPCT_MAX_IN) return fail(HPCT_ERR_BAD_DESC, "n_in = %d outside 1..%d", d.n_in, HPCT_MAX_IN);
     if (d.n_out < 1 || d.n_out > HPCT_MAX_OUT) return fail(HPCT_ERR_BAD_DESC, "n_out = %d outside 1..%d", d.n_out, HPCT_MAX_OUT);
     if ((int)d.anchor < 0 || (int)d.anchor > (int)HPCT_ANCHOR_CONVT2D_NCHW) return fail(HPCT_ERR_BAD_DESC, "unknown anchor %d", (int)d.anchor);
-    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_AVGPOOL_WIN_HW) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
+    if ((int)d.reduce < 0 || (int)d.reduce > (int)HPCT_RED_RMSNORM_LAST) return fail(HPCT_ERR_BAD_DESC, "unknown reduction %d", (int)d.reduce);
     if ((int)d.reduce2 < 0 || (int)d.reduce2 > (int)HPCT_RED_MIN_AXIS) return fail(HPCT_ERR_BAD_DESC, "unknown second reduction %d", (int)d.reduce2);
     if (d.reduce2 != HPCT_RED_NONE && d.anchor != HPCT_ANCHOR_GEMM)
         return fail(HPCT_ERR_UNSUPPORTED, "a second reduction is supported only after a GEMM anchor with MEAN_LAST");
@@ -822,9 +836,10 @@ hpct_status hpct_plan_create(const hpct_op_desc* desc, hpct_plan** out) {
             if (d.reduce == HPCT_RED_MAXPOOL2_HW) { st = plan_maxpool(d, tmp); break; }
             if (d.reduce == HPCT_RED_MAXPOOL_HW || d.reduce == HPCT_RED_AVGPOOL_WIN_HW) { st = plan_maxpool_gen(d, tmp); break; }
             if (d.reduce == HPCT_RED_GROUPNORM_NCHW) { st = plan_groupnorm(d, tmp); break; }
+            if (d.reduce == HPCT_RED_RMSNORM_LAST) { st = plan_rows(d, tmp); break; }
             if (is_eltwise_chain(d)) st = plan_eltwise(d, tmp);
             else if (d.reduce >= HPCT_RED_SUM_AXIS) st = plan_reduce(d, tmp);
-            else if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST) st = plan_rows(d, tmp);
+            else if (d.reduce == HPCT_RED_LAYERNORM_LAST || d.reduce == HPCT_RED_SOFTMAX_LAST || d.reduce == HPCT_RED_RMSNORM_LAST) st = plan_rows(d, tmp);
             else if (d.reduce == HPCT_RED_NONE && d.n_epi == 0 && d.n_in >= 1 &&
                      !(d.in[0].ndim == 4 && contiguous(d.in[0]))) st = plan_layout(d, tmp);
             else st = plan_affine(d, tmp);

@@ -11,7 +11,7 @@ namespace hpct {
 namespace {
 
 constexpr int kMaxVec = 16;  // float4 per thread held in registers
-constexpr int kLn = 0, kLnGelu = 1, kSoftmax = 2;  // row operations
+constexpr int kLn = 0, kLnGelu = 1, kSoftmax = 2, kRms = 3;  // row operations (kRms: x / sqrt(mean x^2 + eps), no mean)
 
 // The row operation on the VPT vectors a thread holds (vector i is element j = t + i*TPR of nv;
 // vectors with j >= nv do not exist).  Leaves the row's result in v; NW waves share `slots`.
@@ -35,6 +35,14 @@ __device__ __forceinline__ void row_op(float4v* v, int t, int nv, int N, float e
         const float inv = 1.0f / block_reduce<OpSum, NW>(s, slots);
 #pragma unroll
         for (int i = 0; i < VPT; ++i) v[i] = v[i] * inv;
+    } else if constexpr (OPK == kRms) {
+        float q = 0.f;   // (vectors beyond the row were loaded as zeros)
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) q += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+        const float ms = block_reduce<OpSum, NW>(q, slots) * (1.0f / (float)N);
+        const float rstd = fast_rsq(ms + eps);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) v[i] = v[i] * rstd;
     } else {
         float s = 0.f;
 #pragma unroll
@@ -150,7 +158,7 @@ __global__ __launch_bounds__(256) void rows_persist(const float* __restrict__ X,
 
 // Any N: a work-group per row, three strided passes over the row (the second
 // and third are served by the caches for rows of moderate length).
-template <bool GELU>
+template <bool GELU, bool RMS>
 __global__ __launch_bounds__(256) void layernorm_rows_any(const float* __restrict__ X, const float* __restrict__ gamma,
                                                           const float* __restrict__ beta, float* __restrict__ Y,
                                                           int64_t rows, int N, float eps) {
@@ -158,8 +166,8 @@ __global__ __launch_bounds__(256) void layernorm_rows_any(const float* __restric
     const int64_t row = blockIdx.x;
     const float* x = X + row * (int64_t)N;
     float s = 0.f;
-    for (int j = threadIdx.x; j < N; j += 256) s += x[j];
-    const float mu = block_reduce<OpSum, 4>(s, slots) / (float)N;
+    if (!RMS) for (int j = threadIdx.x; j < N; j += 256) s += x[j];
+    const float mu = RMS ? 0.f : block_reduce<OpSum, 4>(s, slots) / (float)N;
     float q = 0.f;
     for (int j = threadIdx.x; j < N; j += 256) { float d = x[j] - mu; q += d * d; }
     const float var = block_reduce<OpSum, 4>(q, slots) / (float)N;
@@ -258,22 +266,26 @@ void rows_shape(int64_t rows, int32_t N, LaunchShape& s, const char* const names
 
 }  // namespace
 
-LaunchShape layernorm_shape(int64_t rows, int32_t N) {
+LaunchShape layernorm_shape(int64_t rows, int32_t N, int32_t rms) {
     static const char* const names[4] = {"layernorm_rows_any", "layernorm_rows_vec<wave-per-row>", "layernorm_rows_persist",
                                          "layernorm_rows_vec<group-per-row>"};
+    static const char* const rnames[4] = {"rmsnorm_rows_any", "rmsnorm_rows_vec<wave-per-row>", "rmsnorm_rows_persist",
+                                          "rmsnorm_rows_vec<group-per-row>"};
     LaunchShape s{};
-    rows_shape(rows, N, s, names);
+    rows_shape(rows, N, s, rms ? rnames : names);
     return s;
 }
 
 hipError_t layernorm_launch(const LayernormParams& p, hipStream_t stream) {
     hipError_t e = hipSuccess;
-    if (p.gelu ? launch_rows<kLnGelu>(p, stream, &e) : launch_rows<kLn>(p, stream, &e)) return e;
+    if (p.rms ? launch_rows<kRms>(p, stream, &e) : (p.gelu ? launch_rows<kLnGelu>(p, stream, &e) : launch_rows<kLn>(p, stream, &e))) return e;
     dim3 grid((unsigned)p.rows), block(256);
-    if (p.gelu)
-        hipLaunchKernelGGL(layernorm_rows_any<true>, grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
+    if (p.rms)
+        hipLaunchKernelGGL((layernorm_rows_any<false, true>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
+    else if (p.gelu)
+        hipLaunchKernelGGL((layernorm_rows_any<true, false>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
     else
-        hipLaunchKernelGGL(layernorm_rows_any<false>, grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
+        hipLaunchKernelGGL((layernorm_rows_any<false, false>), grid, block, 0, stream, p.X, p.gamma, p.beta, p.Y, p.rows, p.N, p.eps);
     return hipGetLastError();
 }
 
@@ -290,7 +302,7 @@ LaunchShape softmax_shape(int64_t rows, int32_t N) {
 hipError_t softmax_launch(const SoftmaxParams& p, hipStream_t stream) {
     hipError_t e = hipSuccess;
     if (p.X != p.Y) {   // the register-resident kernels declare X and Y __restrict__
-        const LayernormParams q{p.X, nullptr, nullptr, p.Y, p.rows, p.N, 0.f, 0};
+        const LayernormParams q{p.X, nullptr, nullptr, p.Y, p.rows, p.N, 0.f, 0, 0};
         if (launch_rows<kSoftmax>(q, stream, &e)) return e;
     }
     hipLaunchKernelGGL(softmax_rows_any, dim3((unsigned)p.rows), dim3(256), 0, stream, p.X, p.Y, p.rows, p.N);

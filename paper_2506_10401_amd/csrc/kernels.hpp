@@ -20,8 +20,9 @@ struct LaunchShape {
 struct LayernormParams {
     const float* X; const float* gamma; const float* beta; float* Y;
     int64_t rows; int32_t N; float eps; int32_t gelu;
+    int32_t rms;   // root-mean-square normalisation: no mean, no beta
 };
-LaunchShape layernorm_shape(int64_t rows, int32_t N);
+LaunchShape layernorm_shape(int64_t rows, int32_t N, int32_t rms = 0);
 hipError_t layernorm_launch(const LayernormParams& p, hipStream_t stream);
 
 // ---- row softmax over the last dim (Table 1: Reduction)

@@ -29,7 +29,7 @@ HPCT_EPI_BIAS_COL, HPCT_EPI_SCALE_SHIFT_CH, HPCT_EPI_RELU, HPCT_EPI_ADD_RESIDUAL
     HPCT_EPI_SIGMOID, HPCT_EPI_RELU6, HPCT_EPI_ABS, HPCT_EPI_NEG, HPCT_EPI_SQUARE, HPCT_EPI_LOG, HPCT_EPI_SILU, HPCT_EPI_HARDSWISH = range(25)
 HPCT_RED_NONE, HPCT_RED_SOFTMAX_LAST, HPCT_RED_LAYERNORM_LAST, HPCT_RED_AVGPOOL_HW, HPCT_RED_MEAN_LAST, \
     HPCT_RED_MAXPOOL2_HW, HPCT_RED_SUM_AXIS, HPCT_RED_MEAN_AXIS, HPCT_RED_ARGMAX_AXIS, HPCT_RED_ARGMIN_AXIS, HPCT_RED_MAX_AXIS, \
-    HPCT_RED_MIN_AXIS, HPCT_RED_MAXPOOL_HW, HPCT_RED_GROUPNORM_NCHW, HPCT_RED_AVGPOOL_WIN_HW = range(15)
+    HPCT_RED_MIN_AXIS, HPCT_RED_MAXPOOL_HW, HPCT_RED_GROUPNORM_NCHW, HPCT_RED_AVGPOOL_WIN_HW, HPCT_RED_RMSNORM_LAST = range(16)
 HPCT_MAX_DIMS, HPCT_MAX_EPI, HPCT_MAX_IN, HPCT_MAX_OUT = 6, 8, 8, 2
 
 
@@ -356,6 +356,19 @@ def maxpool2x2_plan(X, out):
 def maxpool2x2(X, out, stream=None) -> None:
     """out[n,c,y,x] = max of the 2x2 window of X[n,c] at (2y, 2x); odd trailing rows / columns are dropped."""
     plan, ins = maxpool2x2_plan(X, out)
+    plan.launch(ins, [out], stream)
+
+
+def rmsnorm_plan(X, gamma, out, eps=1e-6):
+    ins = [X] + ([gamma] if gamma is not None else [])
+    plan = _cached(("rmsnorm", _sh(X), eps, gamma is not None), lambda: op_desc(
+        HPCT_ANCHOR_NONE, [], HPCT_RED_RMSNORM_LAST, 0, [_sh(t) for t in ins], [_sh(out)], eps=eps))
+    return plan, ins
+
+
+def rmsnorm(X, gamma, out, eps=1e-6, stream=None) -> None:
+    """out = X / sqrt(mean(X^2 over the last dim) + eps) * gamma (gamma may be None)."""
+    plan, ins = rmsnorm_plan(X, gamma, out, eps)
     plan.launch(ins, [out], stream)
 
 

@@ -468,7 +468,7 @@ def test_axis_reduction_errors():
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_ARGMAX_AXIS, out_dtype=H.HPCT_F32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS, out_dtype=H.HPCT_I32))
     expect(H.HPCT_ERR_UNSUPPORTED, reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_MAX_AXIS, out_dtype=H.HPCT_I32))
-    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 15))      # one past the last reduction
+    expect(H.HPCT_ERR_BAD_DESC, reduce_desc((4, 5), (5, 1), 1, 16))      # one past the last reduction
     d = cfg_desc(3); d.out[0].dtype = H.HPCT_I32          # int32 anywhere else
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     d = reduce_desc((4, 5), (5, 1), 1, H.HPCT_RED_SUM_AXIS); d.n_epi = 1; d.epi[0] = H.HPCT_EPI_RELU
@@ -739,6 +739,20 @@ def gn_desc(shape=(32, 64, 56, 56), groups=8, affine=True, relu=False, rbe=1, ep
     ins = [shape] + ([(Cc,), (Cc,)] if affine else [])
     return H.op_desc(H.HPCT_ANCHOR_NONE, [H.HPCT_EPI_RELU] if relu else [], H.HPCT_RED_GROUPNORM_NCHW, rbe, ins, [shape],
                      eps=eps, groups=groups)
+
+
+def test_rmsnorm_plans_and_errors():
+    def r(M, N, gamma=True, epi=(), eps=1e-6):
+        return H.op_desc(H.HPCT_ANCHOR_NONE, list(epi), H.HPCT_RED_RMSNORM_LAST, 0, [(M, N)] + ([(N,)] if gamma else []), [(M, N)], eps=eps)
+    assert H.Plan(r(8192, 4096)).kernel_name == "rmsnorm_rows_persist"
+    assert H.Plan(r(8192, 1024, gamma=False)).kernel_name == "rmsnorm_rows_vec<wave-per-row>"
+    assert H.Plan(r(100, 1001)).kernel_name == "rmsnorm_rows_any"
+    expect(H.HPCT_ERR_UNSUPPORTED, r(64, 64, epi=(H.HPCT_EPI_RELU,)))
+    expect(H.HPCT_ERR_BAD_DESC, r(64, 64, eps=-1.0))
+    d = r(64, 64); d.in_[1].shape[0] = 63
+    expect(H.HPCT_ERR_SHAPE_MISMATCH, d)
+    d = r(64, 64); d.n_in = 3
+    expect(H.HPCT_ERR_BAD_DESC, d)
 
 
 def test_groupnorm_plans_and_errors():

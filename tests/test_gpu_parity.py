@@ -1206,6 +1206,20 @@ def test_conv_transpose_tiles_with_a_2x2_filter_of_ones():
     assert np.array_equal(got[:, :, ::2, ::2], x) and np.all(got[:, :, 1::2, :] == 0) and np.all(got[:, :, :, 1::2] == 0)
 
 
+# ---------------------------------------- root-mean-square normalisation over the last dimension
+@pytest.mark.parametrize("M,N", [(8192, 4096), (300, 1024), (64, 256), (33, 1001), (5, 8192), (3, 16384), (2, 20000), (7, 4), (1, 1), (40, 2052)])
+def test_rmsnorm_rows(M, N):
+    print("rmsnorm M=%d N=%d" % (M, N), flush=True)
+    x = datagen.gen_normal(850, (M, N), 0.5, 2.0)
+    g = datagen.gen_normal(851, (N,), 1.0, 0.2)
+    for gamma in (g, None):
+        out = torch.full((M, N), float("nan"), device="cuda")
+        plan, ins = hpct.rmsnorm_plan(dev(x), None if gamma is None else dev(gamma), out, 1e-6)
+        plan.launch(ins, [out])
+        assert plan.kernel_name.startswith("rmsnorm_rows")
+        assert show("rmsnorm %s" % plan.kernel_name, compare.pointwise(host(out), ref.rmsnorm_rows(x, gamma, 1e-6)))
+
+
 # ---------------------------------------- group / instance normalisation of NCHW
 def check_groupnorm(shape, groups, affine=True, relu=False, eps=1e-5, seed=0):
     x = datagen.gen_normal(800 + seed, shape, 0.5, 2.0)
