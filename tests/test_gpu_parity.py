@@ -1480,6 +1480,44 @@ def test_sweep_depthwise_shapes():
         check_depthwise(N, C, H, W, R, stride, pad, dil, act=[False, "relu", "relu6"][int(r.integers(3))], seed=case)
 
 
+def test_sweep_pooling_and_norm_shapes():
+    r = _rng(20250610405)
+    for case in range(30):
+        k = int(r.choice([1, 2, 3, 3, 3, 5, 7]))
+        stride = int(r.choice([1, 2, 2, 3]))
+        pad = int(r.integers(0, k))
+        W = int(r.choice([int(r.integers(max(1, k - 2 * pad), 140)), 48, 56, 104, 112, 224]))
+        H = int(r.integers(max(1, k - 2 * pad), 40))
+        shape = (int(r.choice([1, 2, 3])), int(r.choice([1, 2, 5])), H, W)
+        print("sweep pool %d: %s" % (case, (shape, k, stride, pad)), flush=True)
+        check_maxpool(shape, k, stride, pad, seed=case)
+        check_avgpool(shape, k, stride, pad, seed=case)
+    for case in range(20):
+        C_ = int(r.choice([1, 2, 4, 6, 8, 12, 16]))
+        G = int(r.choice([g for g in (1, 2, 3, 4, 6, 8, 12, 16) if C_ % g == 0]))
+        shape = (int(r.choice([1, 2, 3])), C_, int(r.integers(1, 40)), int(r.choice([int(r.integers(1, 50)), 4, 8, 28, 56, 112])))
+        print("sweep groupnorm %d: %s G=%d" % (case, shape, G), flush=True)
+        check_groupnorm(shape, G, affine=bool(r.integers(2)), relu=bool(r.integers(2)), eps=float(r.choice([1e-5, 1e-3])), seed=case)
+
+
+def test_sweep_skinny_gemm_shapes():
+    r = _rng(20250610406)
+    for case in range(16):
+        small = int(r.integers(1, 9))
+        K = int(r.choice([256, 260, 1024, 4096, 20000])) if case % 4 else int(r.integers(64, 300)) * 4
+        big = int(r.integers((1 << 20) // K + 1, (1 << 20) // K + 600))
+        rows_of_x = bool(r.integers(2))
+        M, N = (big, small) if rows_of_x else (small, big)
+        wt = bool(r.integers(2))
+        t = datagen.make(1, M=M, K=K, N=N)
+        Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+        got, name = run_gemm(t, wt=wt, relu=False)
+        print("sweep skinny %d: M=%d K=%d N=%d wt=%s -> %s" % (case, M, K, N, wt, name), flush=True)
+        if rows_of_x or wt or N % 4 == 0:
+            assert name.startswith("gemm_skinny"), name
+        assert compare.contraction(got, Z, Dn).ok
+
+
 def test_sweep_attention_shapes():
     r = _rng(20250610404)
     for case in range(24):
