@@ -75,13 +75,13 @@ __global__ __launch_bounds__(NT) void groupnorm_rows(const float* __restrict__ X
             const int j = tid + u * NT;
             if (j < nv) {
                 const int c = g * Cg + (4 * j) / HW;
-                store4(y + 4 * j, gn_out<RELU>(v[u], mean, inv, gamma ? gamma[c] : 1.f, beta ? beta[c] : 0.f));
+                store4_nt(y + 4 * j, gn_out<RELU>(v[u], mean, inv, gamma ? gamma[c] : 1.f, beta ? beta[c] : 0.f));
             }
         }
     } else {
         for (int j = tid; j < nv; j += NT) {
             const int c = g * Cg + (4 * j) / HW;
-            store4(y + 4 * j, gn_out<RELU>(load4(x + 4 * j), mean, inv, gamma ? gamma[c] : 1.f, beta ? beta[c] : 0.f));
+            store4_nt(y + 4 * j, gn_out<RELU>(load4(x + 4 * j), mean, inv, gamma ? gamma[c] : 1.f, beta ? beta[c] : 0.f));
         }
     }
 }
