@@ -787,10 +787,14 @@ def pool_desc(shape, k, stride, pad, out_shape=None, epi=()):
 
 
 def test_maxpool_plans_and_errors():
-    # a ResNet's pooling: 3x3 / 2 / pad 1 on 112 x 112: a wave per 56 output columns x 16 output rows
+    # a ResNet's pooling: 3x3 / 2 / pad 1 on 112 x 112: a wave per 56 output columns x 8 output rows
     p = H.Plan(pool_desc((32, 64, 112, 112), 3, 2, 1))
-    assert p.kernel_name == "maxpool3x3_rows<stride2>" and p.launch_shape() == ((32 * 64 * 4 // 4, 1, 1), (256, 1, 1), 0)
+    assert p.kernel_name == "maxpool3x3_rows<stride2>" and p.launch_shape() == ((32 * 64 * 7 // 4, 1, 1), (256, 1, 1), 0)
     assert H.Plan(pool_desc((8, 16, 56, 56), 3, 1, 1)).kernel_name == "maxpool3x3_rows"
+    # narrow maps keep the register kernel down to three computing lanes (12 output columns)
+    assert H.Plan(pool_desc((8, 16, 28, 28), 3, 1, 1)).kernel_name == "maxpool3x3_rows"
+    assert H.Plan(pool_desc((8, 16, 24, 24), 3, 2, 1)).kernel_name == "maxpool3x3_rows<stride2>"
+    assert H.Plan(pool_desc((8, 16, 8, 8), 3, 1, 1)).kernel_name == "maxpool_any"
     # 2x2 / 2 / 0 is the VGG pooling's kernel
     assert H.Plan(pool_desc((32, 64, 56, 56), 2, 2, 0)).kernel_name == "maxpool2_planes<vec4>"
     # anything else: an output per thread

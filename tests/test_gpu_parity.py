@@ -1273,7 +1273,10 @@ def test_maxpool_full_size():
 @pytest.mark.parametrize("shape,k,stride,pad", [
     ((2, 3, 57, 112), 3, 2, 1), ((1, 2, 112, 104), 3, 2, 1), ((1, 4, 31, 96), 3, 2, 1), ((2, 2, 1, 104), 3, 2, 1), ((1, 2, 100, 336), 3, 2, 1),
     ((1, 3, 2, 400), 3, 2, 1), ((2, 3, 57, 56), 3, 1, 1), ((1, 5, 30, 112), 3, 1, 1), ((1, 2, 100, 48), 3, 1, 1), ((2, 2, 5, 52), 3, 1, 1),
-    ((1, 2, 1, 56), 3, 1, 1), ((1, 3, 29, 168), 3, 1, 1)])
+    ((1, 2, 1, 56), 3, 1, 1), ((1, 3, 29, 168), 3, 1, 1),
+    # narrow maps: few computing lanes, a second segment of one lane
+    ((2, 3, 20, 24), 3, 2, 1), ((1, 2, 9, 16), 3, 1, 1), ((2, 2, 33, 28), 3, 1, 1), ((1, 2, 40, 120), 3, 2, 1), ((1, 3, 7, 12), 3, 1, 1),
+    ((3, 5, 28, 32), 3, 2, 1)])
 def test_maxpool_3x3_register_variant(shape, k, stride, pad):
     print("maxpool rows %s" % ((shape, k, stride, pad),), flush=True)
     assert check_maxpool(shape, k, stride, pad).startswith("maxpool3x3_rows")
@@ -1283,7 +1286,7 @@ def test_maxpool_3x3_register_variant(shape, k, stride, pad):
 @pytest.mark.parametrize("shape,k,stride,pad", [
     ((2, 3, 30, 30), 3, 2, 1), ((2, 3, 17, 23), 3, 2, 0), ((1, 3, 57, 57), 5, 3, 2), ((1, 1, 7, 7), 7, 1, 0), ((2, 3, 20, 110), 3, 2, 1),
     ((1, 2, 9, 9), 1, 2, 0), ((3, 1, 5, 5), 4, 4, 0), ((1, 2, 6, 40), 2, 1, 1), ((1, 1, 3, 3), 3, 1, 2), ((2, 2, 33, 31), 16, 5, 7),
-    ((1, 1, 1, 1), 1, 1, 0)])
+    ((1, 1, 1, 1), 1, 1, 0), ((1, 2, 8, 8), 3, 1, 1), ((1, 2, 9, 20), 3, 2, 1)])
 def test_maxpool_general_windows(shape, k, stride, pad):
     print("maxpool any %s" % ((shape, k, stride, pad),), flush=True)
     assert check_maxpool(shape, k, stride, pad) == "maxpool_any"
@@ -1307,7 +1310,8 @@ def test_avgpool_windows():
     assert check_avgpool((32, 64, 112, 112), 3, 2, 1) == "avgpool3x3_rows<stride2>"
     assert check_avgpool((32, 64, 56, 56), 3, 1, 1) == "avgpool3x3_rows"
     assert check_avgpool((32, 64, 56, 56), 2, 2, 0) == "avgpool_any"
-    for (shape, k, stride, pad) in [((2, 3, 57, 112), 3, 2, 1), ((1, 2, 100, 48), 3, 1, 1), ((2, 2, 5, 52), 3, 1, 1), ((1, 3, 2, 400), 3, 2, 1)]:
+    for (shape, k, stride, pad) in [((2, 3, 57, 112), 3, 2, 1), ((1, 2, 100, 48), 3, 1, 1), ((2, 2, 5, 52), 3, 1, 1), ((1, 3, 2, 400), 3, 2, 1),
+                                    ((2, 3, 20, 24), 3, 2, 1), ((2, 2, 33, 28), 3, 1, 1), ((1, 2, 40, 120), 3, 2, 1)]:
         assert check_avgpool(shape, k, stride, pad, seed=1).startswith("avgpool3x3_rows")
     for (shape, k, stride, pad) in [((2, 3, 30, 30), 3, 2, 1), ((1, 3, 57, 57), 5, 3, 2), ((1, 1, 7, 7), 7, 1, 0), ((2, 2, 33, 31), 16, 5, 7), ((1, 2, 6, 40), 2, 1, 1)]:
         assert check_avgpool(shape, k, stride, pad, seed=2) == "avgpool_any"
