@@ -9,8 +9,8 @@
 namespace hpct {
 namespace {
 
-constexpr int kThreads = 512;  // threads per plane
-constexpr int kUnroll = 2;    // independent 16-byte loads per input in flight per thread
+constexpr int kThreads = 256;  // threads per plane
+constexpr int kUnroll = 4;    // independent 16-byte loads per input in flight per thread
 
 template <bool AFF, bool RELU, bool RES>
 __device__ __forceinline__ float4v chain(float4v x, float4v r, float sc, float sh) {
@@ -23,43 +23,63 @@ __device__ __forceinline__ float4v chain(float4v x, float4v r, float sc, float s
 
 // One work-group per plane p = n*C + c.  HW % 4 == 0, so every plane starts on
 // a 16-byte boundary.  Thread t takes vectors t, t+kThreads, ...; kUnroll of them
-// are loaded before any is used.  The plane sum is accumulated per thread in a
-// fixed order, reduced over the wave on DPP and over the waves through
-// LDS, so the result does not vary from run to run.
+// are loaded before any is used (a [56,56] plane is one such batch).  At 50 MB a
+// launch lasts a few memory latencies, so what a wave does before its first
+// vector load counts: the first batch is issued straight after the kernel
+// arguments arrive, and only then are the channel's scale and shift fetched
+// (a scalar load that depends on p % C) - in the other order every wave waits
+// for that second round trip before it requests anything (measured 9.36 -> 9.16 us
+// at [32,64,56,56]).  Slots past the end of the plane re-read its last vector
+// (no branch between the loads) and are left out of the sum.  The plane sum is
+// accumulated per thread in a fixed order, reduced over the wave on DPP and over
+// the waves through LDS, so the result does not vary from run to run.
 template <bool AFF, bool RELU, bool RES, bool POOL>
 __global__ __launch_bounds__(kThreads) void affine_planes_vec(const float* __restrict__ X, const float* __restrict__ scale,
                                                          const float* __restrict__ shift, const float* __restrict__ R,
                                                          float* __restrict__ out, int C, int HW) {
-    __shared__ float slots[16];
-    const int64_t p = blockIdx.x;
-    const int c = (int)(p % C);
-    const float sc = AFF ? scale[c] : 1.f, sh = AFF ? shift[c] : 0.f;
-    const float* x = X + p * (int64_t)HW;
-    const float* r = RES ? R + p * (int64_t)HW : nullptr;
-    float* o = POOL ? nullptr : out + p * (int64_t)HW;
-    const int nv = HW >> 2;
-    float4v acc = {0.f, 0.f, 0.f, 0.f};
-    for (int base = 0; base < nv; base += kThreads * kUnroll) {
-        float4v xv[kUnroll], rv[kUnroll];
+    __shared__ float slots[kThreads / kWave];
+    const unsigned p = blockIdx.x;
+    const unsigned nv = (unsigned)HW >> 2;
+    const size_t plane = (size_t)p * (unsigned)HW;
+    const float* x = X + plane;
+    const float* r = RES ? R + plane : nullptr;
+    float4v xv[kUnroll], rv[kUnroll];
+    auto issue = [&](unsigned base) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * kThreads + threadIdx.x;
-            const bool ok = j < nv;
-            xv[u] = ok ? load4_nt(x + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
-            if (RES) rv[u] = ok ? load4_nt(r + 4 * j) : float4v{0.f, 0.f, 0.f, 0.f};
+            unsigned j = base + u * kThreads + threadIdx.x;
+            j = j < nv ? j : nv - 1;
+            xv[u] = load4_nt(x + 4 * j);
+            if (RES) rv[u] = load4_nt(r + 4 * j);
         }
+    };
+    issue(0);
+    __builtin_amdgcn_sched_barrier(0);   // nothing below is moved above the first batch of loads
+    const unsigned c = p % (unsigned)C;
+    const float sc = AFF ? scale[c] : 1.f, sh = AFF ? shift[c] : 0.f;
+    float* o = POOL ? nullptr : out + plane;
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+    for (unsigned base = 0; base < nv; base += kThreads * kUnroll) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int j = base + u * kThreads + threadIdx.x;
+            const unsigned j = base + u * kThreads + threadIdx.x;
+            const float4v t = chain<AFF, RELU, RES>(xv[u], rv[u], sc, sh);
             if (j < nv) {
-                float4v t = chain<AFF, RELU, RES>(xv[u], rv[u], sc, sh);
                 if (POOL) acc = acc + t; else store4_nt(o + 4 * j, t);
             }
         }
+        if (base + kThreads * kUnroll < nv) issue(base + kThreads * kUnroll);
     }
     if (POOL) {
-        float s = block_reduce<OpSum, kThreads / kWave>((acc.x + acc.y) + (acc.z + acc.w), slots);
-        if (threadIdx.x == 0) out[p] = s / (float)HW;
+        const float w = wave_reduce<OpSum>((acc.x + acc.y) + (acc.z + acc.w));
+        if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = w;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float s = slots[0];
+#pragma unroll
+            for (int i = 1; i < kThreads / kWave; ++i) s += slots[i];
+            out[p] = s / (float)HW;
+        }
     }
 }
 
@@ -133,7 +153,7 @@ LaunchShape affine_shape(int64_t planes, int32_t HW, int32_t pool) {
     LaunchShape s{};
     s.grid[0] = (uint32_t)planes; s.grid[1] = s.grid[2] = 1;
     s.block[0] = HW % 4 == 0 ? kThreads : 256; s.block[1] = s.block[2] = 1;
-    s.lds_bytes = 64;
+    s.lds_bytes = HW % 4 == 0 ? (kThreads / kWave) * 4 : 64;
     if (HW % 4 == 0) s.kernel = pool ? "affine_planes_vec<pool>" : "affine_planes_vec<store>";
     else s.kernel = pool ? "affine_planes_any<pool>" : "affine_planes_any<store>";
     return s;

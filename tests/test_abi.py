@@ -59,7 +59,7 @@ def cfg_desc(i):
 def test_the_five_workloads_plan_and_launch_shapes():
     want = {
         1: ("gemm_rows16<256>", (4, 1, 1), (1024, 1, 1)),
-        2: ("affine_planes_vec<pool>", (2048, 1, 1), (512, 1, 1)),
+        2: ("affine_planes_vec<pool>", (2048, 1, 1), (256, 1, 1)),
         3: ("layernorm_rows_persist", (768, 1, 1), (256, 1, 1)),
         4: ("conv2d_nchw_mfma<3x3,pipelined>", (3136, 1, 1), (256, 1, 1)),
         5: ("attn_fwd_d64<ks2>", (256, 1, 1), (512, 1, 1)),
