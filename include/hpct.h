@@ -241,6 +241,21 @@ size_t hpct_plan_workspace_bytes(const hpct_plan *plan);
 hpct_status hpct_plan_launch(const hpct_plan *plan, const void *const *in_ptrs, void *const *out_ptrs,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same launch for callers that cannot allocate device memory and have none to pass: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation calls.  In place of a caller's workspace the plan's kernels use
+ * a scratch array of HPCT_NOALLOC_SCRATCH_BYTES that is part of the library's device image (each GPU the library runs
+ * on holds one copy from the first such launch on it until the process ends; the call that looks its address up runs
+ * once per device, on the first launch there that needs scratch).  No hipMalloc, hipFree or other allocating routine
+ * is called.  Plans whose hpct_plan_workspace_bytes exceeds HPCT_NOALLOC_SCRATCH_BYTES are refused with
+ * HPCT_ERR_WORKSPACE before anything is enqueued; plans that need no workspace launch exactly as hpct_plan_launch does.
+ * All such launches on one GPU share the one array: the kernels overwrite it and read back only what the same launch
+ * wrote, so nothing is cleared between calls, but two launches that overlap in time on one GPU (different streams,
+ * or threads without an ordering between them) race on it.  Results are bit-identical to hpct_plan_launch's.
+ * Other errors as hpct_plan_launch; HIP also when the scratch cannot be located on the current device. */
+#define HPCT_NOALLOC_SCRATCH_BYTES ((size_t)4 << 20)
+hpct_status hpct_plan_launch_noalloc(const hpct_plan *plan, const void *const *in_ptrs, void *const *out_ptrs,
+                                     void *hip_stream);
+
 /* Release a plan.  NULL is ignored. */
 void hpct_plan_destroy(hpct_plan *plan);
 

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "kernels.hpp"
@@ -29,6 +30,33 @@ void clear_err() { g_err[0] = 0; }
 enum class Kind { Gemm, Affine, Layernorm, Softmax, Conv, Attn, Layout, Reduce, Eltwise, MaxPool, DwConv, ConvT, MaxPoolGen, Groupnorm };
 
 constexpr int64_t kI32Max = 2147483647LL;
+
+// ---- the workspace of hpct_plan_launch_noalloc: one array in every GPU's memory, held until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+constexpr size_t kScratchBytes = HPCT_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];   // per device: that device's copy of `scratch`, looked up on first use
+
+// Address of the current device's scratch array (looked up once per device, with that device current).
+hipError_t scratch_address(void** out, int* device) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    *device = dev;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 }  // namespace
 
@@ -993,6 +1021,22 @@ hpct_status hpct_plan_launch(const hpct_plan* plan, const void* const* in_ptrs, 
     }
     if (e != hipSuccess) return fail(HPCT_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     return HPCT_OK;
+}
+
+hpct_status hpct_plan_launch_noalloc(const hpct_plan* plan, const void* const* in_ptrs, void* const* out_ptrs, void* hip_stream) {
+    clear_err();
+    if (!plan || !in_ptrs || !out_ptrs) return fail(HPCT_ERR_NULL, "hpct_plan_launch_noalloc: plan, in_ptrs and out_ptrs must not be NULL");
+    if (plan->ws_bytes > kScratchBytes)   // before any HIP call
+        return fail(HPCT_ERR_WORKSPACE, "this plan needs a workspace of %zu bytes; the built-in scratch of hpct_plan_launch_noalloc holds %zu",
+                    plan->ws_bytes, kScratchBytes);
+    void* ws = nullptr;
+    if (plan->ws_bytes) {
+        int dev = -1;
+        const hipError_t e = scratch_address(&ws, &dev);
+        if (e != hipSuccess) return fail(HPCT_ERR_HIP, "cannot locate the built-in scratch on device %d: %s", dev, hipGetErrorString(e));
+    }
+    // every workspace-using kernel sequence writes what it later reads, so nothing has to be cleared
+    return hpct_plan_launch(plan, in_ptrs, out_ptrs, ws, plan->ws_bytes, hip_stream);
 }
 
 void hpct_plan_destroy(hpct_plan* plan) { delete plan; }

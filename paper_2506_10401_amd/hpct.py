@@ -74,6 +74,8 @@ def load(path: Optional[str] = None):
     lib.hpct_plan_workspace_bytes.restype = C.c_size_t
     lib.hpct_plan_launch.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t, vp]
     lib.hpct_plan_launch.restype = C.c_int
+    lib.hpct_plan_launch_noalloc.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.hpct_plan_launch_noalloc.restype = C.c_int
     lib.hpct_plan_destroy.argtypes = [vp]
     lib.hpct_plan_destroy.restype = None
     lib.hpct_plan_kernel_name.argtypes = [vp]
@@ -223,6 +225,23 @@ class Plan:
                          workspace.data_ptr() if workspace is not None else 0,
                          workspace.numel() * workspace.element_size() if workspace is not None else 0)
 
+
+    def launch_noalloc(self, inputs, outputs, stream=None) -> None:
+        """hpct_plan_launch_noalloc: the same launch with the library's built-in scratch array for a workspace (no
+        allocation anywhere; refused when the plan needs more than NOALLOC_SCRATCH_BYTES)."""
+        import torch
+        for t in list(inputs) + list(outputs):
+            if not t.is_cuda or (t.dtype != torch.float32 and not (t.dtype == torch.int32 and any(t is o for o in outputs))):
+                raise HpctError(HPCT_ERR_BAD_DESC, "operands must be fp32 tensors (int32 for index outputs) in GPU memory")
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        ins = (C.c_void_p * max(1, len(inputs)))(*[t.data_ptr() for t in inputs])
+        outs = (C.c_void_p * max(1, len(outputs)))(*[t.data_ptr() for t in outputs])
+        st = load().hpct_plan_launch_noalloc(self._h, ins, outs, C.c_void_p(s))
+        if st != HPCT_OK:
+            raise HpctError(st, hpct_last_error())
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20   # HPCT_NOALLOC_SCRATCH_BYTES of include/hpct.h
 
 _plans: Dict[tuple, Plan] = {}
 
