@@ -9,8 +9,10 @@
  * of its Section 5.3) with an op descriptor; the library validates it, picks a
  * hand-written HIP kernel and enqueues it on the caller's stream: one kernel per
  * launch; two or three for the plans that report a workspace (the later ones finish
- * a reduction from the partial results the first left there) and two for a GEMM whose
- * softmax rows are wider than one work-group.
+ * a reduction from the partial results the first left there) and two for a GEMM with a
+ * row softmax whose rows are wider than one work-group or whose output has so few rows
+ * that the contraction is spread over many work-groups per row (the softmax then runs
+ * in place on the stored result).
  *
  * Conventions
  *  - All tensors are fp32 (the index output of an arg-reduction is int32), described by
@@ -36,8 +38,8 @@
  *         (X: any strided view; one that is not
  *         row-major is first copied to the workspace)
  *         [+DROPOUT_HASH] [+SOFTMAX_LAST] (one        (W row-major, strides (N,1),
- *         kernel for N <= 256, GEMM then an           or stored transposed as an
- *         in-place row softmax beyond)                [N,K] array: strides (1,K))
+ *         kernel for N <= 256 and many rows, else     or stored transposed as an
+ *         the GEMM then an in-place row softmax)      [N,K] array: strides (1,K))
  *   GEMM [+BIAS_COL] [+SCALE_CONST] [+RELU]           X[B,M,K], W[B,K,N] (each      [B,M,N]
  *         [+SOFTMAX_LAST]: a batch of products,       W[b] row-major or transposed,
  *         Y[b] = X[b] W[b] (B <= 65535), or one       batch stride K N) or W[K,N],

@@ -28,6 +28,10 @@ namespace {
 
 constexpr int BM = 16;
 constexpr int KG = 4;   // k-groups of waves
+// up to this many 16-row blocks the kernel whose waves share K (plus a softmax launch) beats this one: measured at
+// K = N = 256 with the softmax, 16-row kernel -> K-sharing kernel: M = 64 10.6 -> 5.3 us, 1024 11.3 -> 7.0, 2048 12.0 -> 10.3,
+// 4096 12.2 -> 17.5; at K = 1024, M = 64 30 -> 8.4
+constexpr int kKsplit16MaxRowBlocks = 128;
 
 // EXT: the instance that also carries the hash dropout and the row-sum output (kept out of the
 // plain instance, whose 128-register budget at 1024 threads it would overflow)
@@ -301,6 +305,109 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
     }
 }
 
+
+// ---- small outputs: the contraction split over the waves of a work-group ----------------------------
+// With few output rows the 16-row kernel above has only a handful of work-groups, each of which pulls
+// all of W through one compute unit's vector-memory path - measured at 64 x 256 x 256: 5.3 of its 8 us
+// pass before the last wave has issued its loads.  Here a work-group owns 16 rows x 32 columns and its
+// 16 waves split K between them (wave w takes the 16-k groups w, w + 16, ...), so 64 x 256 x 256 runs
+// on 32 compute units that each load 48 KB, and a wave's whole share is one step of loads.  Each wave
+// multiplies two 16 x 16 blocks (block b, lane column j = output column 2j + b: one 64-bit load of W
+// feeds both), the 16 partial tiles are added through LDS in wave order (fixed: bit-identical from run
+// to run) by the first 512 threads, which apply the epilogue and store along the rows.  A row softmax
+// cannot stay in the work-group any more; it follows as the in-place row kernel (a second launch).
+// Cross-group exchange through global memory inside one launch was measured instead and is far
+// slower: the release / acquire fences it needs write back and invalidate the whole L2 (15 - 35 us).
+// The column block is the fast grid index: the row blocks that share a slice of W are neighbours in
+// dispatch order modulo 8, i.e. they land on one XCD and that slice crosses into its L2 once.
+constexpr int KS_CT = 32;            // columns per work-group
+constexpr int KS_RS = KS_CT + 8;     // LDS row stride of a partial tile: the two lane halves of a 64-bit store hit disjoint banks
+
+template <bool VEC>
+__global__ __launch_bounds__(1024) void gemm_ksplit16(GemmParams p) {
+    const float* __restrict__ X = p.X + blockIdx.z * p.sX;
+    const float* __restrict__ W = p.W + blockIdx.z * p.sW;
+    float* __restrict__ Y = p.Y + blockIdx.z * p.sY;
+    const int M = p.M, K = p.K, N = p.N;
+    __shared__ __attribute__((aligned(16))) float part[16][16 * KS_RS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = lane >> 4, l16 = lane & 15;
+    const int c0 = blockIdx.x * KS_CT, m0 = blockIdx.y * BM;
+    const int mrow = m0 + l16, ncol = c0 + 2 * l16;
+    const int groups = (K + 15) >> 4;
+
+    float4v acc[2] = {float4v{0.f, 0.f, 0.f, 0.f}, float4v{0.f, 0.f, 0.f, 0.f}};
+    // element offsets fit 32 bits (the plan refuses operands of 2^31 elements or more)
+    const int arow = mrow * K, wcol = ncol;
+    const bool rok = mrow < M, cok0 = ncol < N, cok1 = ncol + 1 < N;
+    for (int g0 = wave; g0 < groups; g0 += 32) {   // two 16-k groups of this wave per trip, all their loads issued first
+        const bool two = g0 + 16 < groups;         // wave-uniform
+        float4v a[2];
+        float2v w[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (u == 1 && !two) break;
+            const int k = 16 * (g0 + 16 * u) + 4 * q;
+            const float* asrc = X + arow + k;
+            if (VEC) {
+                a[u] = load4((rok && k < K) ? asrc : X);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[u][e] = *((rok && k + e < K) ? asrc + e : X);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float* wsrc = W + (k + s) * N + wcol;
+                if (VEC) {
+                    w[u][s] = *reinterpret_cast<const float2v*>((k + s < K && cok0) ? wsrc : W);
+                } else {
+                    w[u][s][0] = *((k + s < K && cok0) ? wsrc : W);
+                    w[u][s][1] = *((k + s < K && cok1) ? wsrc + 1 : W);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (u == 1 && !two) break;
+            const int k = 16 * (g0 + 16 * u) + 4 * q;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (!(rok && k + e < K)) a[u][e] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (!(k + s < K && cok0)) w[u][s][0] = 0.f;
+                if (!(k + s < K && cok1)) w[u][s][1] = 0.f;
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) acc[b] = mfma_16x16x4(a[u][s], w[u][s][b], acc[b]);
+        }
+    }
+    // lane holds rows 4q .. 4q+3 (register r) of columns 2 l16 + b
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        *reinterpret_cast<float2v*>(&part[wave][(4 * q + r) * KS_RS + 2 * l16]) = float2v{acc[0][r], acc[1][r]};
+    __syncthreads();
+    if (tid < BM * KS_CT) {
+        const int row = tid / KS_CT, col = tid % KS_CT;
+        float v = part[0][row * KS_RS + col];
+#pragma unroll
+        for (int g = 1; g < 16; ++g) v += part[g][row * KS_RS + col];
+        const int m = m0 + row, c = c0 + col;
+        if (m < M && c < N) {
+            v = (v + (p.bias ? p.bias[c] : 0.f)) * p.scale;
+            v = activate(v, p.relu);
+            if (p.dropout) {
+                const uint64_t off = (uint64_t)m * (uint64_t)N + (uint64_t)c;
+                v = dropout_u(off + p.seed) < p.drop_t ? 0.f : v * p.keep_scale;
+            }
+            Y[(int64_t)m * N + c] = v;
+        }
+    }
+}
+
 int pick_bn(int32_t N) { return N <= 64 ? 64 : (N <= 128 ? 128 : 256); }
 
 template <int BN>
@@ -334,6 +441,13 @@ bool gemm_use_tile(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mea
     return tiles64 * gemm_ksplit(M, K, N, mean, batch) >= 128 && gemm_ksplit(M, K, N, mean, batch) > 1;
 }
 
+// Few row blocks and a K worth splitting: the kernel whose waves share K (threshold: see kKsplit16MaxRowBlocks).
+bool gemm_use_ksplit16(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt, int32_t batch) {
+    if (mean || wt || K < 64) return false;
+    if (gemm_use_tile(M, K, N, softmax, mean, batch)) return false;
+    return (int64_t)((M + BM - 1) / BM) * batch <= kKsplit16MaxRowBlocks;
+}
+
 int32_t gemm_col_tiles(int32_t M, int32_t K, int32_t N) {
     return gemm_use_tile(M, K, N, 0, 1) ? gemm_tile_col_tiles(M, N) : (N + pick_bn(N) - 1) / pick_bn(N);
 }
@@ -348,6 +462,14 @@ size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, in
 LaunchShape gemm_shape(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt, int32_t batch) {
     if (gemm_use_tile(M, K, N, softmax, mean, batch) && gemm_direct_ok(M, K, N, mean, wt, batch)) return gemm_direct_shape(M, N, batch);
     if (gemm_use_tile(M, K, N, softmax, mean, batch)) return gemm_tile_shape(M, N, gemm_ksplit(M, K, N, mean, batch), wt, batch);
+    if (gemm_use_ksplit16(M, K, N, softmax, mean, wt, batch)) {
+        LaunchShape s{};
+        s.grid[0] = (uint32_t)((N + KS_CT - 1) / KS_CT); s.grid[1] = (uint32_t)((M + BM - 1) / BM); s.grid[2] = (uint32_t)batch;
+        s.block[0] = 1024; s.block[1] = s.block[2] = 1;
+        s.lds_bytes = (uint32_t)(16 * 16 * KS_RS * 4);
+        s.kernel = "gemm_ksplit16<32>";
+        return s;
+    }
     const int bn = pick_bn(N);
     LaunchShape s{};
     s.grid[0] = (uint32_t)((M + BM - 1) / BM); s.grid[1] = (uint32_t)((N + bn - 1) / bn); s.grid[2] = (uint32_t)batch;
@@ -362,12 +484,21 @@ hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
     GemmParams p = p0;
     // rows wider than one work-group: the GEMM stores its epilogue's result, a second kernel takes
     // the row softmax of it in place
-    const bool split_softmax = p.softmax && p.N > kGemmSoftmaxMaxN;
+    if (p.batch < 1) p.batch = 1;
+    const bool ks16 = !p.skinny && gemm_use_ksplit16(p.M, p.K, p.N, p0.softmax, p.mean, p.wt, p.batch);
+    const bool split_softmax = p.softmax && (p.N > kGemmSoftmaxMaxN || ks16);
     if (split_softmax) p.softmax = 0;
     hipError_t e;
     p.ksplit = 1;
-    if (p.batch < 1) p.batch = 1;
     if (p.skinny) return gemm_skinny_launch(p, stream);
+    if (ks16) {
+        dim3 grid((unsigned)((p.N + KS_CT - 1) / KS_CT), (unsigned)((p.M + BM - 1) / BM), (unsigned)p.batch);
+        if (p.K % 4 == 0 && p.N % 2 == 0) hipLaunchKernelGGL(gemm_ksplit16<true>, grid, dim3(1024), 0, stream, p);
+        else hipLaunchKernelGGL(gemm_ksplit16<false>, grid, dim3(1024), 0, stream, p);
+        e = hipGetLastError();
+        if (e == hipSuccess && split_softmax) return softmax_launch(SoftmaxParams{p.Y, p.Y, (int64_t)p.M * p.batch, p.N}, stream);
+        return e;
+    }
     if (gemm_use_tile(p.M, p.K, p.N, p0.softmax, p.mean, p.batch)) {
         p.ksplit = gemm_ksplit(p.M, p.K, p.N, p.mean, p.batch);
         e = gemm_direct_ok(p.M, p.K, p.N, p.mean, p.wt, p.batch) ? gemm_direct_launch(p, stream) : gemm_tile_launch(p, stream);

@@ -142,6 +142,7 @@ struct GemmParams {
 };
 constexpr int kGemmSoftmaxMaxN = 256;
 bool gemm_use_tile(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t batch = 1);
+bool gemm_use_ksplit16(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t wt, int32_t batch = 1);
 int32_t gemm_ksplit(int32_t M, int32_t K, int32_t N, int32_t mean, int32_t batch = 1);
 size_t gemm_workspace_bytes(int32_t M, int32_t K, int32_t N, int32_t softmax, int32_t mean, int32_t batch = 1);
 int32_t gemm_col_tiles(int32_t M, int32_t K, int32_t N);

@@ -66,6 +66,12 @@ def load(path: Optional[str] = None):
     if not os.path.exists(path):
         from . import build as _build
         _build.build()
+    # torch first: its wheel carries a HIP runtime of its own, and the library must bind to the one that owns the
+    # tensors and streams it is handed (loaded in the other order, the two runtimes do not see each other's device)
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     vp = C.c_void_p
     lib.hpct_plan_create.argtypes = [C.POINTER(OpDesc), C.POINTER(vp)]

@@ -58,7 +58,7 @@ def cfg_desc(i):
 
 def test_the_five_workloads_plan_and_launch_shapes():
     want = {
-        1: ("gemm_rows16<256>", (4, 1, 1), (1024, 1, 1)),
+        1: ("gemm_ksplit16<32>", (8, 4, 1), (1024, 1, 1)),
         2: ("affine_planes_vec<pool>", (2048, 1, 1), (256, 1, 1)),
         3: ("layernorm_rows_persist", (768, 1, 1), (256, 1, 1)),
         4: ("conv2d_nchw_mfma<3x3,pipelined>", (3136, 1, 1), (256, 1, 1)),
@@ -182,6 +182,9 @@ def test_unsupported_but_well_formed():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     # (a softmax row wider than one work-group tile is supported: GEMM, then an in-place row softmax)
     d = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_SOFTMAX_LAST, 0, [(64, 256), (256, 512)], [(64, 512)])
+    assert H.Plan(d).kernel_name == "gemm_ksplit16<32>" and H.Plan(d).launch_shape()[0] == (16, 4, 1)
+    # (a short K keeps the 16-row kernel, whose work-group holds whole rows of up to 256 columns)
+    d = H.op_desc(H.HPCT_ANCHOR_GEMM, [], H.HPCT_RED_SOFTMAX_LAST, 0, [(64, 32), (32, 512)], [(64, 512)])
     assert H.Plan(d).kernel_name == "gemm_rows16<256>" and H.Plan(d).launch_shape()[0] == (4, 2, 1)
     # non-contiguous layouts
     d = cfg_desc(1); d.in_[1] = H.tensor_desc((256, 256), (1, 256))  # transposed W: an instance of its own
@@ -524,7 +527,9 @@ def test_gemm_transposed_weight_and_scale_plans():
     assert H.Plan(g(4096, 1024, 4096, (1, 1024))).kernel_name == "gemm_tile128<wt>"
     p = H.Plan(g(256, 2048, 256, (1, 2048)))
     assert p.kernel_name == "gemm_tile64<wt,split-k>" and p.workspace_bytes == H.Plan(g(256, 2048, 256, (256, 1))).workspace_bytes
-    assert H.Plan(g(64, 256, 256, (256, 1))).kernel_name == "gemm_rows16<256>"
+    assert H.Plan(g(64, 256, 256, (256, 1))).kernel_name == "gemm_ksplit16<32>"
+    assert H.Plan(g(64, 48, 256, (256, 1))).kernel_name == "gemm_rows16<256>"
+    assert H.Plan(g(2064, 256, 256, (256, 1), red=H.HPCT_RED_SOFTMAX_LAST)).kernel_name == "gemm_rows16<256>"   # more than 128 row blocks
     # any other W layout is refused; the bias and the output stay contiguous (a strided X is copied: its own test)
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (1, 512)))
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (512, 1)))
@@ -535,8 +540,9 @@ def test_gemm_transposed_weight_and_scale_plans():
     expect(H.HPCT_ERR_UNSUPPORTED, d)
     # Gemm-Scale: SCALE_CONST sits between the bias and the ReLU
     e = (H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_RELU)
-    assert H.Plan(g(64, 256, 256, (256, 1), e, scale=0.5)).kernel_name == "gemm_rows16<256>"
-    assert H.Plan(g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST,), scale=0.5)).kernel_name == "gemm_rows16<256>"
+    assert H.Plan(g(64, 256, 256, (256, 1), e, scale=0.5)).kernel_name == "gemm_ksplit16<32>"
+    assert H.Plan(g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST,), scale=0.5)).kernel_name == "gemm_ksplit16<32>"
+    assert H.Plan(g(64, 32, 256, (256, 1), e, scale=0.5)).kernel_name == "gemm_rows16<256>"
     assert H.Plan(g(4096, 1024, 4096, (1, 1024), e + (H.HPCT_EPI_DROPOUT_HASH,), scale=2.0)).kernel_name == "gemm_tile128<wt>"
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU, H.HPCT_EPI_SCALE_CONST)))
     expect(H.HPCT_ERR_UNSUPPORTED, g(64, 256, 256, (256, 1), (H.HPCT_EPI_SCALE_CONST, H.HPCT_EPI_BIAS_COL)))
@@ -612,8 +618,10 @@ def test_batched_gemm_plans():
     # 16 products of 256 x 128 x 256: tiles of all the matrices fill one grid
     p = H.Plan(g((16, 256, 128), (16, 128, 256), (16, 256, 256)))
     assert p.kernel_name == "gemm_tile64" and p.launch_shape()[0] == (16 * 4 * 4, 1, 1) and p.workspace_bytes == 0
-    # small matrices: the 16-row kernel with the batch in grid.z
+    # small matrices: the batch in grid.z of the kernel whose waves share K, or (short K) of the 16-row kernel
     p = H.Plan(g((3, 64, 256), (3, 256, 256), (3, 64, 256), red=H.HPCT_RED_SOFTMAX_LAST))
+    assert p.kernel_name == "gemm_ksplit16<32>" and p.launch_shape()[0] == (8, 4, 3)
+    p = H.Plan(g((3, 64, 32), (3, 32, 256), (3, 64, 256), red=H.HPCT_RED_SOFTMAX_LAST))
     assert p.kernel_name == "gemm_rows16<256>" and p.launch_shape()[0] == (4, 1, 3)
     # a short K: no LDS staging
     p = H.Plan(g((64, 512, 64), (64, 64, 512), (64, 512, 512)))

@@ -126,6 +126,30 @@ def run_gemm(t, wt=False, relu=True, softmax=False, bias=True, scale=None):
     return host(out), plan.kernel_name
 
 
+@pytest.mark.parametrize("M,K,N", [(64, 4096, 256), (48, 1000, 96), (130, 520, 34), (2048, 64, 64), (20, 4100, 31),
+                                   (16, 272, 32), (100, 528, 1000), (15, 65, 2), (1000, 260, 30)])
+def test_gemm_small_outputs_share_k_between_waves(M, K, N):
+    # the kernel for few output rows: 16 x 32 tiles, K dealt out to the 16 waves of a work-group in 16-k groups
+    # (none, one or two per wave and trip, ragged last groups, odd N without vector loads), with every epilogue,
+    # the softmax behind it as a second launch, and run-to-run bit identity of the fixed-order LDS combine
+    print("gemm small M=%d K=%d N=%d" % (M, K, N), flush=True)
+    t = datagen.make(1, M=M, K=K, N=N)
+    Z, Dn = ref.gemm_bias(t["X"], t["W"], t["bias"], want_norm=True)
+    got, name = run_gemm(t)
+    assert name == "gemm_ksplit16<32>", name
+    assert show("gemm+bias+relu", compare.contraction(got, ref.relu(Z), Dn))
+    assert np.max(np.abs(got - ref.relu(Z)) / Dn) < 1e-5
+    again, _ = run_gemm(t)
+    assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
+    got, _ = run_gemm(t, softmax=True)
+    assert show("softmax", compare.pointwise(got, ref.chain1(t["X"], t["W"], t["bias"])))
+    Z0, Dn0 = ref.gemm_bias(t["X"], t["W"], None, want_norm=True)
+    got, _ = run_gemm(t, relu=False, bias=False, scale=-0.75)
+    assert show("anchor * scale", compare.contraction(got, ref.scale_const(Z0, -0.75), Dn0 * 0.75))
+    got, _ = run_gemm(t, relu="gelu")
+    assert show("gelu", compare.contraction(got, ref.gelu_tanh(Z), Dn * 1.13 + 1e-6))
+
+
 def wt_name(plain):
     """kernel name of the transposed-W instance of `plain`"""
     if plain.startswith("gemm_rows16<"):
@@ -149,6 +173,10 @@ def test_gemm_transposed_weight(M, K, N):
     if plain_name == "gemm_direct":
         # the kernel for a short K takes a row-major W only; a transposed one goes to the tiled kernel
         assert name in ("gemm_tile128<wt>", "gemm_tile64<wt>")
+    elif plain_name.startswith("gemm_ksplit16"):
+        # so does the small-output kernel whose waves share K; a transposed W stays with the 16-row kernel
+        # (another summation order: both are checked against the CPU checker, not against each other)
+        assert name.startswith("gemm_rows16") and name.endswith(",wt>")
     else:
         # (with K = 1 or N = 1 the transposed storage is also row-major)
         assert name == (plain_name if K == 1 or N == 1 else wt_name(plain_name)), (name, plain_name)
@@ -422,7 +450,7 @@ def check_chain6(t, p, seed):
 def test_chain6_small_shapes(M, K, N):
     print("chain6 M=%d K=%d N=%d" % (M, K, N), flush=True)
     name = check_chain6(datagen.make(6, M=M, K=K, N=N), datagen.CHAIN6_P, datagen.CHAIN6_SEED)
-    assert name.startswith("gemm_rows16")
+    assert name.startswith(("gemm_rows16", "gemm_ksplit16"))
 
 
 @pytest.mark.parametrize("M,K,N", [(640, 72, 900), (513, 70, 1027), (1024, 8, 512), (520, 100, 1100), (129, 16, 4100),
@@ -867,6 +895,24 @@ def test_attention_other_head_dims(D, B, L, Lk):
         want, Dn = ref.attention(t["Q"], t["K"], t["V"], scale, want_norm=True, causal=causal)
         got = run_chain5(t, scale, causal=causal)
         assert show("causal" if causal else "plain", compare.contraction(got, want, Dn))
+
+
+@pytest.mark.parametrize("D,B,L,Lk,causal", [(64, 1, 8192, 8192, False), (64, 1, 8192, 8192, True),
+                                             (128, 1, 8192, 8192, False), (128, 1, 8192, 8192, True),
+                                             (64, 1, 4096, 6000, False), (64, 1, 4096, 6000, True),
+                                             (128, 1, 3000, 5001, False), (32, 2, 4099, 4099, True)])
+def test_attention_long_sequences(D, B, L, Lk, causal):
+    # sequences well beyond the 2048 of the fifth workload: many more key blocks per query (the running maximum and
+    # sum are rescaled over up to 128 blocks), query blocks beyond one XCD's share of a batch, Lq != Lk
+    print("long attention D=%d B=%d L=%d Lk=%d causal=%r" % (D, B, L, Lk, causal), flush=True)
+    t = datagen.make(5, B=B, L=L, Lk=Lk, D=D)
+    scale = 1.0 / np.sqrt(D)
+    want, Dn = ref.attention(t["Q"], t["K"], t["V"], scale, want_norm=True, causal=causal)
+    got = run_chain5(t, scale, causal=causal)
+    assert show("long %s" % ("causal" if causal else "plain"), compare.contraction(got, want, Dn))
+    assert np.max(np.abs(got - want) / Dn) < 1e-4
+    if causal:   # query 0 sees key 0 only
+        assert np.array_equal(got[:, 0], t["V"][:, 0])
 
 
 def test_attention_large_scores_do_not_overflow():
