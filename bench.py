@@ -19,7 +19,9 @@ Order of the run:
      longest chain first);
   4. the per-operator protocol: at least 100 launches of every chain in ten
      event brackets; `median_us` / `min_us` are over the brackets' per-launch
-     means; chain 1 also gets 1000 back-to-back launches in one bracket;
+     means; chain 1 also gets 1000 back-to-back launches in one bracket; and
+     `graph_replay_us`: 110 launches captured as one HIP graph and replayed,
+     i.e. the kernels back to back with no host work per launch;
   5. side measurements (layout transforms, axis reductions, the later chains),
      a HIP-graph replay of the step, and the CPU checker's timing.
 
@@ -104,6 +106,10 @@ def main() -> int:
         return 2
     hpct.load()
     torch.cuda.set_device(0)
+    # everything runs on one non-default stream, so the same launches can also be captured into HIP graphs
+    work = torch.cuda.Stream()
+    work.wait_stream(torch.cuda.current_stream())
+    torch.cuda.set_stream(work)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()  # noqa: E731
     which = [args.only] if args.only else [1, 2, 3, 4, 5]
     extras = not args.only and not args.skip_extra
@@ -217,27 +223,32 @@ def main() -> int:
     # brackets do not contain the host's launch latency after the synchronisation that precedes the timed region
     order = sorted(which, key=(5, 4, 3, 2, 1).index)
 
+    def capture(i, launches):
+        """`launches` launches of chain i, buffer sets in rotation, as one HIP graph on the work stream"""
+        fs = calls[i].calls
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=work):
+            for k in range(launches):
+                fs[k % len(fs)]()
+        return g
+
     def run_steps(K, record):
         out = {}
         for i in order:
+            seq = [calls[i].calls[k % len(calls[i])] for k in range(K)]   # the bound launches themselves: least host work per launch
+            e0, e1 = new_event(), new_event()
             if record:
-                out[i] = measure_nosync(calls[i], K, 1)
-            else:
-                for _ in range(K):
-                    calls[i]()
+                e0.record()
+            for f in seq:
+                f()
+            if record:
+                e1.record()
+                out[i] = ([(e0, e1)], [K])
         return out
 
-    def measure_nosync(call, launches, brackets):
-        brackets = max(1, min(brackets, launches))
-        sizes = [launches // brackets + (1 if b < launches % brackets else 0) for b in range(brackets)]
-        evs = [(new_event(), new_event()) for _ in sizes]
-        for (e0, e1), n in zip(evs, sizes):
-            e0.record()
-            for _ in range(n):
-                call()
-            e1.record()
-        return evs, sizes
-
+    # (Submitting a chain's K launches as one captured graph was tried for the timed region and is not used: the
+    # host-side graph launch sits inside the bracket and costs more than it saves at small K, and capturing between
+    # pre-roll and timed region leaves the GPU idle long enough for its clocks to drop again.)
     run_steps(args.warmup, False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -248,9 +259,27 @@ def main() -> int:
     clocks = read_clocks()
 
     # ---- 4. per-operator protocol
+    def graph_us(i, launches=110, replays=5):
+        """per-launch time of `launches` launches of chain i (buffer sets in rotation) captured once as a HIP graph and
+        replayed: the same kernels back to back with no host work between them"""
+        g = capture(i, launches)
+        g.replay()
+        torch.cuda.synchronize()
+        per = []
+        for _ in range(replays):
+            e0, e1 = new_event(), new_event()
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            per.append(1e3 * e0.elapsed_time(e1) / launches)
+        return statistics.median(per)
+
     proto = {}
     for i in which:
         proto[i] = measure(calls[i], max(PROTOCOL_LAUNCHES, args.steps), PROTOCOL_BRACKETS)
+        if extras:
+            proto[i]["graph_us"] = graph_us(i)
         if i == 1:
             proto[i]["amortised_us_1000"] = measure(calls[i], 1000, 1)["avg_us"]
         if len(calls[i]) > 1:   # the same launches on one buffer set: served by the last-level cache
@@ -279,6 +308,8 @@ def main() -> int:
                            "8.4 Mflop the launch is latency-bound, the fraction of the MFMA peak says so")
         if "cache_warm_median_us" in proto[i]:
             rec["cache_warm_median_us"] = round(proto[i]["cache_warm_median_us"], 3)
+        if "graph_us" in proto[i]:
+            rec["graph_replay_us"] = round(proto[i]["graph_us"], 3)
         rec["hbm_traffic_bytes"] = recorded_traffic(rec["kernel"])
         per_op.append(rec)
     dom = max(per_op, key=lambda r: r["avg_us"])
@@ -291,26 +322,20 @@ def main() -> int:
     # replayed K times: what a serving loop that cannot afford five launch calls per step would run
     graph_step = None
     if extras:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            rebound = [bound(i, sets[i][0]) for i in which]   # bound to the stream the capture runs on
-            for c in rebound:
+        step_calls = [calls[i].calls[0] for i in which]
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=work):
+            for c in step_calls:
                 c()
-            side.synchronize()
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                for c in rebound:
-                    c()
-            for _ in range(10):
-                graph.replay()
-            side.synchronize()
-            g0 = time.perf_counter()
-            for _ in range(args.steps):
-                graph.replay()
-            side.synchronize()
-            g1 = time.perf_counter()
-        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(10):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
         graph_step = dict(ms_per_step=round((g1 - g0) * 1e3 / args.steps, 4), launches_per_step=len(which),
                           note="one hipGraph replay per step (chains 2 and 3 on one buffer set, so warm in the last-level cache)")
 
@@ -383,6 +408,34 @@ def main() -> int:
         del pouts
         red("argmax_channels_32x64x56x56", xs, 1, "argmax", (32, 56, 56), nb_x + 32 * 3136 * 4)
         red("mean_channels_32x64x56x56", xs, 1, "mean", (32, 56, 56), nb_x + 32 * 3136 * 4)
+
+    # ---- what plain streaming kernels of the library reach at the sizes of the operators above (cold, rotating buffers):
+    # a row sum that only reads, and the copy the affine chain degenerates to.  A 26 MB or 51 MB launch lasts a few
+    # memory latencies, so its ceiling lies well below that of a 268 MB one; these lines say where.
+    floors = []
+    if extras and 2 in sets and 3 in sets:
+        def read_floor(name_, rows):
+            n = rows * 4096
+            pieces = [m.view(-1)[k * n:(k + 1) * n] for m in ms for k in range(m.numel() // n)]
+            pieces += [x.view(-1)[:n] for x in xs if x.numel() >= n]
+            pieces = pieces[:11]
+            made = []
+            for v in pieces:
+                o = torch.empty(rows, device="cuda")
+                made.append(hpct.reduce_axis_plan(v.view(rows, 4096), o, 1, "sum") + (o,))
+            kname, call_ = plan_calls(made)
+            floors.append(side_line(name_, kname, call_, n * 4 + rows * 4, "hbm", len(made)))
+        read_floor("read_only_row_sum_25.7MB", 1568)
+        read_floor("read_only_row_sum_51.4MB", 3136)
+        read_floor("read_only_row_sum_134MB", 8192)
+        couts = [torch.empty_like(x) for x in xs]
+        name, call = plan_calls([hpct.scale_shift_relu_add_pool_plan(x, None, None, None, o, relu=False, pool=False) + (o,)
+                                 for x, o in zip(xs, couts)])
+        floors.append(side_line("copy_25.7MB_to_25.7MB", name, call, 2 * nb_x, "hbm", len(xs)))
+        del couts
+        name, call = plan_calls([hpct.scale_shift_relu_add_pool_plan(m.view(32, 256, 64, 64), None, None, None, o.view(32, 256, 64, 64),
+                                                                     relu=False, pool=False) + (o.view(32, 256, 64, 64),) for m, o in zip(ms, mo)])
+        floors.append(side_line("copy_134MB_to_134MB", name, call, 2 * nb_m, "hbm", len(ms)))
 
     if extras:
         # ---- [Matmul, Dropout, Mean, Softmax] (Section 5.3 case study)
@@ -482,7 +535,7 @@ def main() -> int:
                preroll_ms=round(preroll_ms, 1), preroll_launches=preroll_launches,
                preroll_note="untimed launches of the conv and attention chains before the warm-up steps, until the GPU has "
                             "been busy for this long: the clocks settle over the first tens of milliseconds of heavy work",
-               per_op=per_op, roofline=roofline, clocks=clocks, layout_ops=layout_ops, reduce_ops=reduce_ops,
+               per_op=per_op, roofline=roofline, clocks=clocks, layout_ops=layout_ops, reduce_ops=reduce_ops, streaming_floors=floors,
                next_ops=next_ops, graph_step=graph_step)
     if other_ops:
         out["other_ops"] = other_ops

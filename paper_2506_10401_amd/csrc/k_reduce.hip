@@ -189,19 +189,27 @@ __global__ __launch_bounds__(kThreads) void reduce_cols(ReduceParams p, int tc_l
     __shared__ int si[OP == 0 ? 1 : kThreads * V];
     const int TC = 1 << tc_log2, TR = kThreads >> tc_log2;
     const int ct = threadIdx.x & (TC - 1), rg = threadIdx.x >> tc_log2;
-    const int64_t Lc = p.shape[p.nk - 1];
-    int64_t b = blockIdx.x;
-    const int64_t strip = b % strips; b /= strips;
-    const int chunk_id = (int)(b % p.split);
-    const int64_t rest0 = b / p.split;
-    const int64_t c = (strip * TC + ct) * V;
+    // every extent and the grid fit 32 bits (the plan refuses more than 2^31-1 outputs): 32-bit divisions, a few
+    // instructions each where the 64-bit ones are a routine of their own in front of the first load
+    const unsigned Lc = (unsigned)p.shape[p.nk - 1];
+    unsigned b = blockIdx.x;
+    // work-groups are dealt to the 8 XCDs in turn; with the plain numbering an XCD sees every 8th strip only, i.e.
+    // always the same few of its L2 channels.  Renumbered so that an XCD walks neighbouring strips (8192 x 4096 over
+    // axis 0 on 256-column strips: 30.2 -> 24.2 us)
+    if ((gridDim.x & 7) == 0) b = (b & 7) * (gridDim.x >> 3) + (b >> 3);
+    const unsigned strip = b % (unsigned)strips; b /= (unsigned)strips;
+    const int chunk_id = (int)(b % (unsigned)p.split);
+    const unsigned rest0 = b / (unsigned)p.split;
+    const int64_t c = (int64_t)(strip * TC + ct) * V;
     // offset of the other kept dimensions
-    int64_t rest = rest0, off = 0;
+    unsigned rest = rest0;
+    int64_t off = 0;
 #pragma unroll
     for (int d = kReduceDims - 2; d >= 0; --d) {
         if (d < p.nk - 1) {
-            const int64_t q = rest / p.shape[d];
-            off += (rest - q * p.shape[d]) * p.stride[d];
+            const unsigned ext = (unsigned)p.shape[d];
+            const unsigned q = rest / ext;
+            off += (int64_t)(rest - q * ext) * p.stride[d];
             rest = q;
         }
     }
@@ -274,7 +282,7 @@ __global__ __launch_bounds__(kThreads) void reduce_cols(ReduceParams p, int tc_l
                 a[v].merge(t);
             }
         }
-        const int64_t o = rest0 * Lc + c;
+        const int64_t o = (int64_t)rest0 * Lc + c;
         if (p.split == 1) {
 #pragma unroll
             for (int v = 0; v < V; ++v) emit<OP>(p, o + v, a[v]);
@@ -289,20 +297,40 @@ __global__ __launch_bounds__(kThreads) void reduce_cols(ReduceParams p, int tc_l
     }
 }
 
-// merges the p.split partial results of every output in chunk order
+// merges the p.split <= 64 partial results of every output: 16 lanes per output, lane l takes the pieces l, l + 16,
+// l + 32, l + 48 (all its loads in flight together - a thread that walks the pieces one after the other waits a
+// memory round trip for each: 0.4 us per piece), then the 16 lanes combine on DPP in a fixed order
 template <int OP>
 __global__ __launch_bounds__(kThreads) void reduce_finish(ReduceParams p) {
-    const int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (o >= p.outputs) return;
-    const float* wv = p.ws + o;
-    const int* wi = reinterpret_cast<const int*>(p.ws + (int64_t)p.split * p.outputs) + o;
-    Acc<OP> a;
-    for (int s = 0; s < p.split; ++s) {
-        Acc<OP> t;
-        if constexpr (OP == 0) t.s = wv[(int64_t)s * p.outputs]; else { t.v = wv[(int64_t)s * p.outputs]; t.i = wi[(int64_t)s * p.outputs]; }
-        if (s == 0) a = t; else a.merge(t);
+    const int64_t o = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 4;
+    const int l = threadIdx.x & 15;
+    const bool live = o < p.outputs;
+    const int64_t oc = live ? o : 0;
+    const float* wv = p.ws + oc;
+    const int* wi = reinterpret_cast<const int*>(p.ws + (int64_t)p.split * p.outputs) + oc;
+    float xv[4];
+    int xi[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int s = l + 16 * u;
+        const int64_t at = (int64_t)(s < p.split ? s : 0) * p.outputs;
+        xv[u] = wv[at];
+        if constexpr (OP != 0) xi[u] = wi[at];
     }
-    emit<OP>(p, o, a);
+    Acc<OP> a;   // the identity: 0 for a sum, (-+inf, no index) for the arg ops
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if (l + 16 * u < p.split) {
+            Acc<OP> t;
+            if constexpr (OP == 0) t.s = xv[u]; else { t.v = xv[u]; t.i = xi[u]; }
+            a.merge(t);
+        }
+    }
+    a.merge(dpp_acc<0xB1, OP>(a));
+    a.merge(dpp_acc<0x4E, OP>(a));
+    a.merge(dpp_acc<0x141, OP>(a));
+    a.merge(dpp_acc<0x140, OP>(a));
+    if (live && l == 0) emit<OP>(p, o, a);
 }
 
 // ---- no contiguous direction to exploit: a thread per output
@@ -357,7 +385,7 @@ hipError_t launch_op(const ReduceParams& p, hipStream_t stream) {
         if (p.split > 1) {
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL((reduce_finish<OP>), dim3((unsigned)((p.outputs + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, p);
+            hipLaunchKernelGGL((reduce_finish<OP>), dim3((unsigned)((p.outputs * 16 + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, p);
         }
     } else {
         hipLaunchKernelGGL((reduce_gather<OP>), dim3((unsigned)((p.outputs + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, p);
@@ -370,8 +398,9 @@ hipError_t launch_op(const ReduceParams& p, hipStream_t stream) {
 // Column kernel configuration.  Candidates in order of preference: wide strips first (a wave load
 // is one contiguous run, few row groups to merge), 128-bit access before 32-bit at equal width; the
 // first that gives about four work-groups per CU wins.  When none does (few outputs) the reduced
-// axis is split over work-groups instead, on 64-column strips, to about one work-group per CU:
-// measured on 8192 x 4096 over axis 0, 256 groups of 2048 rows beat 512 and 1024 smaller ones.
+// axis is split over work-groups instead, to about one work-group per CU: measured on 8192 x 4096
+// over axis 0 (with the XCD-aware numbering of the kernel), 256-column strips x 16 pieces 24.2 us,
+// 64-column strips x 4 pieces 24.9, 512 or 1024 smaller work-groups 24.7 - 25.3.
 void reduce_plan_cols(ReduceParams& p) {
     const int64_t Lc = p.shape[p.nk - 1];
     const int64_t rest = p.outputs / Lc;
@@ -385,10 +414,11 @@ void reduce_plan_cols(ReduceParams& p) {
         p.cols_v = c.v; p.cols_tc_log2 = c.tc;
         if (rest * ((Lc + strip - 1) / strip) >= 1024) return;
     }
-    // few outputs: 64-column strips, pieces of the reduced axis
+    // few outputs: pieces of the reduced axis on strips of up to 256 columns (a wave load is then one 1 KB run of a row)
     p.cols_v = vec ? 4 : 1;
-    p.cols_tc_log2 = vec ? 4 : 6;
-    const int64_t groups = rest * ((Lc + 63) / 64);
+    p.cols_tc_log2 = vec ? (Lc >= 256 ? 6 : (Lc >= 128 ? 5 : 4)) : 6;
+    const int64_t strip = (int64_t)p.cols_v << p.cols_tc_log2;
+    const int64_t groups = rest * ((Lc + strip - 1) / strip);
     const int tr = kThreads >> p.cols_tc_log2;
     int64_t split = (256 + groups - 1) / groups;
     const int64_t most = p.R / (2 * tr * kColsUnroll);   // at least two full unrolled passes per thread
