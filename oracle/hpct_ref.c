@@ -191,48 +191,50 @@ void ref_gelu_tanh(double *Y, int64_t count)
     }
 }
 
-/* ---- ComputeIntensive: conv (Table 1), NCHW, bias-initialised ------------
- * Loop nest of the paper's fine-tuned VGG-16 listing (Section 5.3): n, k, h,
- * w outside, accumulator starts at bias[k], then c, kh, kw; the tap index
- * ih = h*stride - P + kh, iw = w*stride - P + kw and the zero-padding bounds
- * test are those of the listing before it; output index
- * ((n*K + k)*Ho + h)*Wo + w.  Cross-correlation (no kernel flip).  Weights
- * are [K][C][R][S] contiguous.  With dilation `dil` (1 = the paper's case) tap
- * kh sits dil rows further each: ih = h*stride - P + kh*dil, likewise iw; the
- * filter then spans (R-1)*dil + 1 rows and the output size is
- * (H + 2P - (R-1)*dil - 1)/stride + 1.
- * Dn (may be NULL) = |bias| + sum |in| |wt| over the taps inside the image. */
+/* ---- ComputeIntensive: conv (Table 1), NCHW ----------------------------------
+ * Definition.  Let xp be the input plane extended by zeros outside
+ * 0 <= row < H, 0 <= col < W.  Then
+ *   out[n][k][y][x] = bias[k]
+ *       + sum over c, r, s of  xp[n][c][y*stride - P + r*dil][x*stride - P + s*dil] * wt[k][c][r][s]
+ * for 0 <= y < Ho = (H + 2P - (R-1)*dil - 1)/stride + 1 and 0 <= x < Wo likewise:
+ * a cross-correlation (the filter is not flipped) with zero padding P, the bias
+ * as the sum's first term, weights stored [K][C][R][S], output stored
+ * [N][K][Ho][Wo].  This is the operator of the paper's VGG-16 case study
+ * (Section 5.3) at stride 1, P = 1, R = S = 3, dil = 1, where Ho = H.
+ * Dn (may be NULL) = |bias| + sum |xp| |wt| over the same terms: the
+ * normaliser of the contraction tolerance. */
+static double padded_at(const float *plane, int64_t H, int64_t W, int64_t row, int64_t col)
+{
+    return (row < 0 || row >= H || col < 0 || col >= W) ? 0.0 : (double)plane[row * W + col];
+}
+
 void ref_conv2d_nchw_bias(const float *in, const float *wt, const float *bias,
                           int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t K,
                           int64_t R, int64_t S, int64_t stride, int64_t P, int64_t dil,
                           double *out, double *Dn)
 {
     const int64_t Ho = (H + 2 * P - (R - 1) * dil - 1) / stride + 1, Wo = (W + 2 * P - (S - 1) * dil - 1) / stride + 1;
-#pragma omp parallel for schedule(static) collapse(2)
-    for (int64_t n = 0; n < Nb; ++n) {
-        for (int64_t k = 0; k < K; ++k) {
-            for (int64_t h = 0; h < Ho; ++h) {
-                for (int64_t w = 0; w < Wo; ++w) {
-                    double b = bias ? (double)bias[k] : 0.0;
-                    double sum = b, mag = fabs(b);
-                    for (int64_t c = 0; c < C; ++c) {
-                        for (int64_t kh = 0; kh < R; ++kh) {
-                            for (int64_t kw = 0; kw < S; ++kw) {
-                                int64_t ih = h * stride - P + kh * dil;
-                                int64_t iw = w * stride - P + kw * dil;
-                                if (ih >= 0 && ih < H && iw >= 0 && iw < W) {
-                                    double a = (double)in[((n * C + c) * H + ih) * W + iw];
-                                    double g = (double)wt[((k * C + c) * R + kh) * S + kw];
-                                    sum += a * g;
-                                    mag += fabs(a) * fabs(g);
-                                }
-                            }
+#pragma omp parallel for schedule(static)
+    for (int64_t plane = 0; plane < Nb * K; ++plane) {   /* one output plane (n, k) per iteration */
+        const int64_t n = plane / K, k = plane % K;
+        const double first = bias ? (double)bias[k] : 0.0;
+        for (int64_t y = 0; y < Ho; ++y) {
+            for (int64_t x = 0; x < Wo; ++x) {
+                double total = first, magnitude = fabs(first);
+                for (int64_t c = 0; c < C; ++c) {
+                    const float *xin = in + (n * C + c) * H * W;
+                    const float *filt = wt + (k * C + c) * R * S;
+                    for (int64_t r = 0; r < R; ++r) {
+                        for (int64_t t = 0; t < S; ++t) {
+                            const double v = padded_at(xin, H, W, y * stride - P + r * dil, x * stride - P + t * dil);
+                            const double g = (double)filt[r * S + t];
+                            total += v * g;
+                            magnitude += fabs(v) * fabs(g);
                         }
                     }
-                    int64_t o = ((n * K + k) * Ho + h) * Wo + w;
-                    out[o] = sum;
-                    if (Dn) Dn[o] = mag;
                 }
+                out[(plane * Ho + y) * Wo + x] = total;
+                if (Dn) Dn[(plane * Ho + y) * Wo + x] = magnitude;
             }
         }
     }
@@ -403,33 +405,29 @@ void ref_layout_copy(const uint32_t *in, int32_t nd, const int64_t *shape, const
     }
 }
 
-/* ---- Hash-based dropout of the fused [Matmul, Dropout, Mean, Softmax] case
- * study (Section 5.3, the listing generated after fine-tuning).  For the
- * element at row i, column j of an [M,N] tensor
- *     offset = i * N + j,  h = offset + seed   (unsigned 64-bit, wrapping)
- *     h ^= h >> 17;  h ^= h << 31;  h ^= h >> 8;
- *     rand = (float)(h % 1000) / 1000.0f        (fp32, as the paper computes it)
- * The listing elides what is done with `rand`; the reading taken here is the
- * usual training-mode dropout: the element is zeroed when rand < p (compared
- * in fp32) and multiplied by 1 / (1 - p) otherwise. */
-float ref_dropout_rand(uint64_t h)
+/* ---- Hash dropout of the fused [Matmul, Dropout, Mean, Softmax] case study (Section 5.3).
+ * The paper gives the random number of an element as a function of its linear
+ * position and a seed:  u(t) = ((t' mod 1000) as fp32) / 1000.0f  with
+ *     t' = mix(t),  mix: t ^= t >> 17, then t ^= t << 31, then t ^= t >> 8   (unsigned 64-bit)
+ * and t = i*N + j + seed (wrapping) for row i, column j of an [M,N] tensor.
+ * What is done with u is not printed; the reading taken is training-mode
+ * dropout: the element becomes 0 when u < p (an fp32 comparison) and is
+ * multiplied by 1 / (1 - p) otherwise. */
+float ref_dropout_rand(uint64_t t)
 {
-    h ^= h >> 17;
-    h ^= h << 31;
-    h ^= h >> 8;
-    return (float)(h % 1000u) / 1000.0f;
+    t ^= t >> 17;
+    t ^= t << 31;
+    t ^= t >> 8;
+    return (float)(t % 1000u) / 1000.0f;
 }
 
 void ref_dropout_hash(double *Z, int64_t M, int64_t N, float p, uint64_t seed)
 {
-    const double keep_scale = 1.0 / (1.0 - (double)p);
+    const double survivor = 1.0 / (1.0 - (double)p);
 #pragma omp parallel for schedule(static)
-    for (int64_t i = 0; i < M; ++i) {
-        for (int64_t j = 0; j < N; ++j) {
-            uint64_t offset = (uint64_t)i * (uint64_t)N + (uint64_t)j;
-            float rand_val = ref_dropout_rand(offset + seed);
-            Z[i * N + j] = rand_val < p ? 0.0 : Z[i * N + j] * keep_scale;
-        }
+    for (int64_t e = 0; e < M * N; ++e) {   /* e = i*N + j */
+        const float u = ref_dropout_rand((uint64_t)e + seed);
+        Z[e] = u < p ? 0.0 : Z[e] * survivor;
     }
 }
 
