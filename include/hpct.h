@@ -125,7 +125,8 @@ typedef struct {
 typedef enum {
     HPCT_ANCHOR_NONE = 0,
     HPCT_ANCHOR_GEMM = 1,                 /* Z[m,n] = sum_k X[m,k] W[k,n] */
-    HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM = 2,  /* O = softmax_j(scale * Q K^T) V, per batch */
+    HPCT_ANCHOR_BGEMM_SOFTMAX_BGEMM = 2,  /* O = softmax_j(scale * Q K^T) V, per batch: two "matmul" (Table 1, ComputeIntensive,
+                                             in its batched form) around a "softmax" (Table 1, Reduction), fused */
     HPCT_ANCHOR_CONV2D_NCHW = 3,          /* cross-correlation, zero padding (Section 5.3 case study) */
     HPCT_ANCHOR_CONVT2D_NCHW = 4          /* transposed conv ("Conv-Trans", Section 5.2): in[n][c][ih][iw] is scattered through
                                              wt[c][k][kh][kw] to out[n][k][ih*stride - pad + kh*dilation][iw*stride - pad + kw*dilation];
@@ -138,7 +139,8 @@ typedef enum {
     HPCT_EPI_SCALE_SHIFT_CH = 1,  /* x * scale[c] + shift[c], c = dim 1 of NCHW (of the output, after a conv anchor) */
     HPCT_EPI_RELU = 2,            /* max(x, 0) */
     HPCT_EPI_ADD_RESIDUAL = 3,    /* + R, same shape as the running value */
-    HPCT_EPI_GELU_TANH = 4,       /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) */
+    HPCT_EPI_GELU_TANH = 4,       /* 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))): an activation of Table 1's Elementwise class
+                                     ("... relu and etc."), as in the activation-then-norm fusions of Section 4.1 */
     HPCT_EPI_SCALE_CONST = 5,     /* * desc.scale (after BIAS_COL in a GEMM chain; a step of an elementwise chain) */
     HPCT_EPI_DROPOUT_HASH = 6,    /* training-mode dropout with the hash mask of the Section 5.3 case study: for
                                      element (i, j) of an [M,N] value, h = i*N + j + dropout_seed (uint64, wrapping),
@@ -170,8 +172,9 @@ typedef enum {
 typedef enum {
     HPCT_RED_NONE = 0,
     HPCT_RED_SOFTMAX_LAST = 1,    /* exp(x - max) / sum exp(x - max) over the last dim */
-    HPCT_RED_LAYERNORM_LAST = 2,  /* (x - mean) / sqrt(biased var + eps) * gamma + beta over the last dim */
-    HPCT_RED_AVGPOOL_HW = 3,      /* mean over dims 2,3 of NCHW */
+    HPCT_RED_LAYERNORM_LAST = 2,  /* (x - mean) / sqrt(biased var + eps) * gamma + beta over the last dim: the "norm" of the
+                                     activation-followed-by-norm fusions of Section 4.1, built from Table 1's Reduction "mean" */
+    HPCT_RED_AVGPOOL_HW = 3,      /* mean over dims 2,3 of NCHW: Table 1, Reduction "mean" over the two spatial axes */
     HPCT_RED_MEAN_LAST = 4,       /* mean over the last dim, which is dropped: [M,N] -> [M].  GEMM anchor only. */
     HPCT_RED_MAXPOOL2_HW = 5,     /* max over non-overlapping 2x2 windows of dims 2,3 (stride 2; an odd last row or
                                      column is dropped): [N,K,Ho,Wo] -> [N,K,Ho/2,Wo/2].  After a conv anchor, or alone. */

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void gemm_direct(GemmParams p, int tiles_
     for (int i = 0; i < 4; ++i) a_off[i] = row_ok ? (unsigned)((l32 * K + 16 * h + 4 * i) * 4) : kOob;
 #pragma unroll
     for (int s = 0; s < 16; ++s) b_off[s] = col_ok ? (unsigned)(((16 * h + s) * N + 4 * l32) * 4) : kOob;   // k = 16 h + s
-    const __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X) + (int64_t)m0 * K, 0, 0x7fffffff, kWord3);
+    const int rows_here = M - m0 < 32 ? M - m0 : 32;   // rows of X this wave may touch
 
     float16v acc[4];
 #pragma unroll
@@ -85,13 +85,18 @@ __global__ __launch_bounds__(kThreads) void gemm_direct(GemmParams p, int tiles_
 
     for (int k0 = 0; k0 < K; k0 += DK) {
         const bool tail = k0 + DK > K;   // uniform; K % 4 == 0: a quad of k is inside or outside as a whole
-        const __amdgpu_buffer_rsrc_t b_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(W) + (int64_t)k0 * N + n0, 0, 0x7fffffff, kWord3);
+        // both descriptors end where their operand ends (seen from this chunk's base), so an offset that is wrong
+        // for any reason reads 0 instead of a neighbour: rows of X beyond the wave's, k beyond K, columns beyond W
+        const __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X) + (int64_t)m0 * K + k0, 0,
+                                                                              ((rows_here - 1) * K + (K - k0)) * 4, kWord3);
+        const __amdgpu_buffer_rsrc_t b_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(W) + (int64_t)k0 * N + n0, 0,
+                                                                              (int)(((int64_t)(K - k0) * N - n0) * 4), kWord3);
         float4v a[4], b[16];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             unsigned v = a_off[i];
             if (tail && k0 + 16 * h + 4 * i >= K) v = kOob;
-            a[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(a_rs, (int)v, k0 * 4, 0));
+            a[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(a_rs, (int)v, 0, 0));
         }
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
