@@ -12,16 +12,20 @@ Order of the run:
      kernels (default 600 ms of GPU time, `preroll_ms` in the output) that
      brings the GPU to its steady clocks whatever --warmup is;
   2. --warmup W untimed steps;
-  3. the timed region: exactly --steps K steps, launched grouped by chain, each
-     group inside one HIP-event bracket on the launch stream (a bracket costs
-     about a microsecond of its own, so short groups are not cut further);
-     `ms_per_step`, every `avg_us` and `roofline` come from here (the groups run
-     longest chain first);
-  4. the per-operator protocol: at least 100 launches of every chain in ten
-     event brackets; `median_us` / `min_us` are over the brackets' per-launch
-     means; chain 1 also gets 1000 back-to-back launches in one bracket; and
-     `graph_replay_us`: 110 launches captured as one HIP graph and replayed,
-     i.e. the kernels back to back with no host work per launch;
+  3. the timed region: exactly --steps K steps, launched grouped by chain (the
+     longest chain first), each group inside one HIP-event bracket on the
+     launch stream; `ms_per_step` and every `timed_region_avg_us` come from here;
+  4. the per-operator protocol, whatever --steps is: at least 100 launches of
+     every chain (400 for chains shorter than 20 us) in ten event brackets, each
+     chain behind 30 untimed ms of its own launches; `avg_us` is the
+     mean over all of them, `median_us` / `min_us` are over the brackets'
+     per-launch means; `frac`, `value` and `roofline` use `avg_us`.  (A bracket
+     costs about 2 us of its own, which is 1 % of a 20-launch group of a 9 us
+     kernel: with --steps 20 the timed region's own per-chain averages are that
+     much too long, and they are printed beside the protocol's.)  Chain 1 also
+     gets 1000 back-to-back launches in one bracket; `graph_replay_us` is 110
+     launches captured as one HIP graph and replayed, i.e. the kernels back to
+     back with no host work per launch;
   5. side measurements (layout transforms, axis reductions, the later chains),
      a HIP-graph replay of the step, and the CPU checker's timing.
 
@@ -97,6 +101,7 @@ def main() -> int:
         print("bench.py: --steps must be at least 1 and --warmup at least 0", file=sys.stderr)
         return 2
 
+    import gc
     import numpy as np
     import torch
     from paper_2506_10401_amd import datagen, hpct
@@ -197,6 +202,7 @@ def main() -> int:
         return plan.bind(ins, [o], workspace=s.get("ws"))
 
     calls = {i: Rotating(bound(i, s) for s in sets[i]) for i in which}
+    gc.disable()   # no collector pauses inside launch loops
 
     # ---- 1. pre-roll: the GPU raises its clocks over the first tens of milliseconds of heavy work; a short
     # warm-up would leave the timed region inside that ramp.  Untimed, reported.
@@ -275,9 +281,29 @@ def main() -> int:
             per.append(1e3 * e0.elapsed_time(e1) / launches)
         return statistics.median(per)
 
+    def settle(call, ms):
+        """untimed launches of `call` until the GPU has been busy with it for `ms` (see the pre-roll)"""
+        e0, e1 = new_event(), new_event()
+        e0.record()
+        while True:
+            for _ in range(25):
+                call()
+            e1.record()
+            e1.synchronize()
+            if e0.elapsed_time(e1) >= ms:
+                return
+
+    # whatever --steps is, every chain's figure comes from at least 100 launches in ten brackets; a bracket costs about
+    # 2 us of its own (the two markers, the first launch behind another kernel), so chains shorter than 20 us get 40
+    # launches per bracket.  Longest chains first, each chain behind 30 ms of its own launches: clocks and power
+    # budget follow the kind of work (matrix cores against memory) with a lag of milliseconds.
     proto = {}
-    for i in which:
-        proto[i] = measure(calls[i], max(PROTOCOL_LAUNCHES, args.steps), PROTOCOL_BRACKETS)
+    for i in order:
+        est = 1e3 * recorded[i][0][0][0].elapsed_time(recorded[i][0][0][1]) / args.steps
+        n = max(PROTOCOL_LAUNCHES, args.steps, 400 if est < 20.0 else 0)
+        if args.preroll_ms > 0:
+            settle(calls[i], 30.0)
+        proto[i] = measure(calls[i], n, PROTOCOL_BRACKETS)
         if extras:
             proto[i]["graph_us"] = graph_us(i)
         if i == 1:
@@ -291,7 +317,8 @@ def main() -> int:
     for i in which:
         evs, sizes = recorded[i]
         tot = [1e3 * e0.elapsed_time(e1) for e0, e1 in evs]
-        avg_us = sum(tot) / args.steps
+        timed_us = sum(tot) / args.steps      # the K launches of the timed region
+        avg_us = proto[i]["avg_us"]           # mean over the protocol's launches: what frac, value and roofline use
         op = OPS[i]
         ach, peak, unit = rate(op["bound"], op["bytes"] if op["bound"] == "hbm" else op["flop"], avg_us)
         fracs.append(ach / peak)
@@ -299,13 +326,13 @@ def main() -> int:
                    achieved=round(ach, 3), unit=unit, peak=peak, frac=round(ach / peak, 4), buffer_sets=len(sets[i]),
                    workspace_bytes=wsbytes[i],
                    median_us=round(proto[i]["median_us"], 3), min_us=round(proto[i]["min_us"], 3),
-                   protocol_avg_us=round(proto[i]["avg_us"], 3), protocol_launches=proto[i]["launches"],
-                   protocol_brackets=proto[i]["brackets"])
+                   launches=proto[i]["launches"], brackets=proto[i]["brackets"],
+                   timed_region_avg_us=round(timed_us, 3), timed_region_launches=args.steps)
         if "amortised_us_1000" in proto[i]:
             rec["amortised_us_1000"] = round(proto[i]["amortised_us_1000"], 3)
-            rec["note"] = ("avg_us: the K launches of the timed region; median_us / min_us: over ten brackets of >= 10 "
-                           "launches; amortised_us_1000: 1000 back-to-back launches in one event bracket / 1000. At "
-                           "8.4 Mflop the launch is latency-bound, the fraction of the MFMA peak says so")
+            rec["note"] = ("avg_us / median_us / min_us: ten brackets of 40 launches; timed_region_avg_us: the K launches of the "
+                           "timed region; amortised_us_1000: 1000 back-to-back launches in one event bracket / 1000. At "
+                           "8.4 Mflop the chain (two launches) is bound by the launch rate, the fraction of the MFMA peak says so")
         if "cache_warm_median_us" in proto[i]:
             rec["cache_warm_median_us"] = round(proto[i]["cache_warm_median_us"], 3)
         if "graph_us" in proto[i]:
@@ -352,7 +379,12 @@ def main() -> int:
     def side_line(op, kernel, call, work, bnd, nsets, note=None, launches=PROTOCOL_LAUNCHES):
         for _ in range(10):
             call()
+        if args.preroll_ms > 0:
+            settle(call, 30.0)
         m = measure(call, launches, PROTOCOL_BRACKETS)
+        if m["median_us"] < 20.0 and launches < 400:   # short kernels: 40 launches per bracket (a bracket costs about 2 us)
+            launches = 400
+            m = measure(call, launches, PROTOCOL_BRACKETS)
         ach, peak, unit = rate(bnd, work, m["median_us"])
         e = dict(op=op, kernel=kernel, avg_us=round(m["avg_us"], 3), median_us=round(m["median_us"], 3),
                  min_us=round(m["min_us"], 3), launches=launches, achieved=round(ach, 1 if bnd == "hbm" else 2), unit=unit,

@@ -38,6 +38,7 @@ __global__ __launch_bounds__(kThreads) void affine_planes_vec(const float* __res
                                                          const float* __restrict__ shift, const float* __restrict__ R,
                                                          float* __restrict__ out, int C, int HW) {
     __shared__ float slots[kThreads / kWave];
+    __builtin_assume(HW >= 4);   // (the launcher's precondition) no early exit in front of the argument loads: one scalar load fetches them all
     const unsigned p = blockIdx.x;
     const unsigned nv = (unsigned)HW >> 2;
     const size_t plane = (size_t)p * (unsigned)HW;

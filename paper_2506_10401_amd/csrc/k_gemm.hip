@@ -323,12 +323,19 @@ __global__ __launch_bounds__(BN * 4) void gemm_rows16(GemmParams p) {
 constexpr int KS_CT = 32;            // columns per work-group
 constexpr int KS_RS = KS_CT + 8;     // LDS row stride of a partial tile: the two lane halves of a 64-bit store hit disjoint banks
 
+// The hot arguments are plain leading parameters (13 dwords), so that they arrive preloaded in scalar registers with the
+// wave (build flag -amdgpu-kernarg-preload-count) and the first loads need no argument fetch; the dropout parameters,
+// used only in the epilogue, stay in memory.
+struct KsplitTail { int32_t dropout; uint32_t drop_t; float keep_scale; uint64_t seed; int32_t shared_w; };
+
 template <bool VEC>
-__global__ __launch_bounds__(1024) void gemm_ksplit16(GemmParams p) {
-    const float* __restrict__ X = p.X + blockIdx.z * p.sX;
-    const float* __restrict__ W = p.W + blockIdx.z * p.sW;
-    float* __restrict__ Y = p.Y + blockIdx.z * p.sY;
-    const int M = p.M, K = p.K, N = p.N;
+__global__ __launch_bounds__(1024) void gemm_ksplit16(const float* __restrict__ X0, const float* __restrict__ W0,
+                                                      const float* __restrict__ bias, float* __restrict__ Y0, int M, int K, int N,
+                                                      int act, float scale, KsplitTail tail) {
+    // blockIdx.z: the matrix of a batch (contiguous matrices; one W for all when shared_w)
+    const float* __restrict__ X = X0 + (int64_t)blockIdx.z * M * K;
+    const float* __restrict__ W = W0 + (tail.shared_w ? 0 : (int64_t)blockIdx.z * K * N);
+    float* __restrict__ Y = Y0 + (int64_t)blockIdx.z * M * N;
     __shared__ __attribute__((aligned(16))) float part[16][16 * KS_RS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q = lane >> 4, l16 = lane & 15;
@@ -397,11 +404,11 @@ __global__ __launch_bounds__(1024) void gemm_ksplit16(GemmParams p) {
         for (int g = 1; g < 16; ++g) v += part[g][row * KS_RS + col];
         const int m = m0 + row, c = c0 + col;
         if (m < M && c < N) {
-            v = (v + (p.bias ? p.bias[c] : 0.f)) * p.scale;
-            v = activate(v, p.relu);
-            if (p.dropout) {
+            v = (v + (bias ? bias[c] : 0.f)) * scale;
+            v = activate(v, act);
+            if (tail.dropout) {
                 const uint64_t off = (uint64_t)m * (uint64_t)N + (uint64_t)c;
-                v = dropout_u(off + p.seed) < p.drop_t ? 0.f : v * p.keep_scale;
+                v = dropout_u(off + tail.seed) < tail.drop_t ? 0.f : v * tail.keep_scale;
             }
             Y[(int64_t)m * N + c] = v;
         }
@@ -493,8 +500,11 @@ hipError_t gemm_launch(const GemmParams& p0, hipStream_t stream) {
     if (p.skinny) return gemm_skinny_launch(p, stream);
     if (ks16) {
         dim3 grid((unsigned)((p.N + KS_CT - 1) / KS_CT), (unsigned)((p.M + BM - 1) / BM), (unsigned)p.batch);
-        if (p.K % 4 == 0 && p.N % 2 == 0) hipLaunchKernelGGL(gemm_ksplit16<true>, grid, dim3(1024), 0, stream, p);
-        else hipLaunchKernelGGL(gemm_ksplit16<false>, grid, dim3(1024), 0, stream, p);
+        const KsplitTail tail{p.dropout, p.drop_t, p.keep_scale, p.seed, p.sW == 0 ? 1 : 0};
+        if (p.K % 4 == 0 && p.N % 2 == 0)
+            hipLaunchKernelGGL(gemm_ksplit16<true>, grid, dim3(1024), 0, stream, p.X, p.W, p.bias, p.Y, p.M, p.K, p.N, p.relu, p.scale, tail);
+        else
+            hipLaunchKernelGGL(gemm_ksplit16<false>, grid, dim3(1024), 0, stream, p.X, p.W, p.bias, p.Y, p.M, p.K, p.N, p.relu, p.scale, tail);
         e = hipGetLastError();
         if (e == hipSuccess && split_softmax) return softmax_launch(SoftmaxParams{p.Y, p.Y, (int64_t)p.M * p.batch, p.N}, stream);
         return e;
