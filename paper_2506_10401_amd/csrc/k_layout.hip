@@ -50,25 +50,32 @@ __global__ __launch_bounds__(256) void layout_rows(const float* __restrict__ in,
 // with power-of-two row pitches a straight sweep would keep hitting the same
 // memory channels.
 // VEC: sa, sb, the batch strides and both bases are multiples of 4 elements.
+// Work-group decode in 32-bit arithmetic from scalar arguments (tile counts and
+// extents are computed on the host): the decode precedes the first load of every
+// work-group, so its length is part of a short kernel's run time.
+struct TransposeBatch {
+    int32_t n;                         // batch dimensions, innermost first
+    uint32_t shape[kLayoutDims - 2];
+    int64_t sin[kLayoutDims - 2];
+    int64_t sout[kLayoutDims - 2];
+};
+
 template <int TA, int TB, bool VEC>
-__global__ __launch_bounds__(256) void layout_transpose(const float* __restrict__ in, float* __restrict__ out, LayoutParams p) {
+__global__ __launch_bounds__(256) void layout_transpose(const float* __restrict__ in, float* __restrict__ out, uint32_t La, uint32_t Lb,
+                                                        uint32_t ta, uint32_t tb, int64_t sa, int64_t sb, TransposeBatch bt) {
     __shared__ float tile[TA][TB + 1];
-    const int a_dim = p.nd - 1, b_dim = p.bdim;
-    const int64_t La = p.shape[a_dim], Lb = p.shape[b_dim];
-    const int64_t sa = p.sin[a_dim], sb = p.sout[b_dim];
-    const int64_t ta = (La + TA - 1) / TA, tb = (Lb + TB - 1) / TB;
-    int64_t w = blockIdx.x;
-    const int64_t x = w % tb; w /= tb;
-    const int64_t y = w % ta; w /= ta;
-    const int64_t b0 = ((x + y) % tb) * TB, a0 = y * TA;
+    uint32_t w = blockIdx.x;
+    const uint32_t x = w % tb; w /= tb;
+    const uint32_t y = w % ta; w /= ta;
+    const uint32_t b0 = ((x + y) % tb) * TB, a0 = y * TA;
     int64_t in_off = 0, out_off = 0;
 #pragma unroll
-    for (int d = kLayoutDims - 1; d >= 0; --d) {
-        if (d < p.nd && d != a_dim && d != b_dim) {
-            const int64_t q = w / p.shape[d];
-            const int64_t i = w - q * p.shape[d];
-            in_off += i * p.sin[d];
-            out_off += i * p.sout[d];
+    for (int d = 0; d < kLayoutDims - 2; ++d) {
+        if (d < bt.n) {
+            const uint32_t q = w / bt.shape[d];
+            const uint32_t i = w - q * bt.shape[d];
+            in_off += i * bt.sin[d];
+            out_off += i * bt.sout[d];
             w = q;
         }
     }
@@ -78,7 +85,7 @@ __global__ __launch_bounds__(256) void layout_transpose(const float* __restrict_
     const int r2 = threadIdx.x / (TA / 4), c2 = (threadIdx.x % (TA / 4)) * 4;
     if (VEC && a0 + TA <= La && b0 + TB <= Lb) {
         // interior tile (uniform per work-group): no bounds tests, so every load of the tile is issued at once
-        const float* src = in + in_off + (a0 + r1) * sa + b0 + c1;
+        const float* src = in + in_off + (int64_t)(a0 + r1) * sa + b0 + c1;
         float4v v[TA / RPP1];
 #pragma unroll
         for (int i = 0; i < TA / RPP1; ++i) v[i] = load4_nt(src + (int64_t)(RPP1 * i) * sa);
@@ -88,7 +95,7 @@ __global__ __launch_bounds__(256) void layout_transpose(const float* __restrict_
             tile[ar][c1] = v[i].x; tile[ar][c1 + 1] = v[i].y; tile[ar][c1 + 2] = v[i].z; tile[ar][c1 + 3] = v[i].w;
         }
         __syncthreads();
-        float* dst = out + out_off + (b0 + r2) * sb + a0 + c2;
+        float* dst = out + out_off + (int64_t)(b0 + r2) * sb + a0 + c2;
 #pragma unroll
         for (int i = 0; i < TB / RPP2; ++i) {
             const int br = r2 + RPP2 * i;
@@ -104,11 +111,11 @@ __global__ __launch_bounds__(256) void layout_transpose(const float* __restrict_
         float v[TA / RPP1][4];
 #pragma unroll
         for (int i = 0; i < TA / RPP1; ++i) {
-            const int64_t a = a0 + r1 + RPP1 * i;
-            const float* row = in + in_off + (a < La ? a : La - 1) * sa;
+            const uint32_t a = a0 + r1 + RPP1 * i;
+            const float* row = in + in_off + (int64_t)(a < La ? a : La - 1) * sa;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int64_t b = b0 + c1 + j;
+                const uint32_t b = b0 + c1 + j;
                 v[i][j] = row[b < Lb ? b : Lb - 1];
             }
         }
@@ -121,9 +128,9 @@ __global__ __launch_bounds__(256) void layout_transpose(const float* __restrict_
 #pragma unroll
     for (int i = 0; i < TB / RPP2; ++i) {  // write rows of b, contiguous along a
         const int br = r2 + RPP2 * i;
-        const int64_t b = b0 + br, a = a0 + c2;
+        const uint32_t b = b0 + br, a = a0 + c2;
         if (b < Lb) {
-            float* dst = out + out_off + b * sb + a;
+            float* dst = out + out_off + (int64_t)b * sb + a;
             if (VEC && a + 3 < La) {
                 store4_nt(dst, float4v{tile[c2][br], tile[c2 + 1][br], tile[c2 + 2][br], tile[c2 + 3][br]});
             } else {
@@ -146,8 +153,19 @@ void pick_tile(const LayoutParams& p, int& TA, int& TB) {
 
 template <int TA, int TB>
 void launch_transpose(const LayoutParams& p, dim3 grid, bool vec, hipStream_t stream) {
-    if (vec) hipLaunchKernelGGL((layout_transpose<TA, TB, true>), grid, dim3(256), 0, stream, p.in, p.out, p);
-    else hipLaunchKernelGGL((layout_transpose<TA, TB, false>), grid, dim3(256), 0, stream, p.in, p.out, p);
+    const int a_dim = p.nd - 1, b_dim = p.bdim;
+    const uint32_t La = (uint32_t)p.shape[a_dim], Lb = (uint32_t)p.shape[b_dim];
+    const uint32_t ta = (La + TA - 1) / TA, tb = (Lb + TB - 1) / TB;
+    TransposeBatch bt{};
+    for (int d = p.nd - 1; d >= 0; --d) {
+        if (d == a_dim || d == b_dim) continue;
+        bt.shape[bt.n] = (uint32_t)p.shape[d];
+        bt.sin[bt.n] = p.sin[d];
+        bt.sout[bt.n] = p.sout[d];
+        ++bt.n;
+    }
+    if (vec) hipLaunchKernelGGL((layout_transpose<TA, TB, true>), grid, dim3(256), 0, stream, p.in, p.out, La, Lb, ta, tb, p.sin[a_dim], p.sout[b_dim], bt);
+    else hipLaunchKernelGGL((layout_transpose<TA, TB, false>), grid, dim3(256), 0, stream, p.in, p.out, La, Lb, ta, tb, p.sin[a_dim], p.sout[b_dim], bt);
 }
 
 }  // namespace
@@ -186,6 +204,13 @@ hipError_t layout_launch(const LayoutParams& p, hipStream_t stream) {
             if (d != p.bdim) vec = vec && p.sin[d] % 4 == 0 && (d == p.nd - 1 || p.sout[d] % 4 == 0);
         int TA, TB;
         pick_tile(p, TA, TB);
+        // the kernel decodes its work-group index and tile coordinates in 32 bits
+        int64_t groups = 1;
+        for (int d = 0; d < p.nd; ++d) {
+            if (p.shape[d] > (int64_t)INT32_MAX - 128) return hipErrorInvalidValue;
+            groups *= d == p.nd - 1 ? (p.shape[d] + TA - 1) / TA : d == p.bdim ? (p.shape[d] + TB - 1) / TB : p.shape[d];
+            if (groups > INT32_MAX) return hipErrorInvalidValue;
+        }
         if (TA == 128) launch_transpose<128, 128>(p, grid, vec, stream);
         else if (TB == 128) launch_transpose<64, 128>(p, grid, vec, stream);
         else launch_transpose<64, 64>(p, grid, vec, stream);

@@ -1237,6 +1237,18 @@ def test_conv_transpose_ragged_shapes(N, C, H, W, K, R, stride, pad, dil):
     check_conv_transpose(N, C, H, W, K, R, stride, pad, dil, act="relu", bias=False, seed=2)
 
 
+@pytest.mark.parametrize("N,C,H,W,K,R,stride,pad", [(2, 16, 8, 8, 24, 1, 1, 0), (1, 64, 16, 16, 64, 1, 1, 0),   # -> the 1x1 streaming kernel
+                                                     (2, 3, 16, 32, 32, 3, 1, 1), (2, 4, 12, 64, 64, 3, 1, 1),   # few input channels
+                                                     (1, 2, 8, 224, 32, 3, 1, 1)])
+def test_conv_transpose_routes_through_the_specialised_conv_kernels(N, C, H, W, K, R, stride, pad):
+    # combinations that exist only through composition: the stride-1 conv that a transposed conv becomes may be taken
+    # by the kernels for 1x1 filters or for few input channels; each must see the flipped / regrouped operands correctly
+    print("conv transpose route %s" % ((N, C, H, W, K, R, stride, pad),), flush=True)
+    got, plan, ins, ws = check_conv_transpose(N, C, H, W, K, R, stride, pad, act="relu", affine=True, seed=3)
+    print("kernel", plan.kernel_name, flush=True)
+    check_conv_transpose(N, C, H, W, K, R, stride, pad, bias=False, seed=4)
+
+
 def test_conv_transpose_tiles_with_a_2x2_filter_of_ones():
     # stride = filter size would tile the output; with odd filters: a 1x1 filter of ones at stride 2 puts every input
     # on the even positions and zeros between them, exactly
