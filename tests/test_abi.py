@@ -270,10 +270,10 @@ def test_layout_transform_plans():
         return H.Plan(H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_NONE, 0, [H.tensor_desc(shape, stride)], [shape]))
     # NCHW -> NHWC collapses to [N, HW, C] and is a tiled transpose of C against HW
     p = plan((32, 56, 56, 64), (64 * 3136, 56, 1, 3136))
-    assert p.kernel_name == "layout_transpose<64x64>"
-    assert p.launch_shape()[0] == (32 * 49 * 1, 1, 1)  # 32 images x ceil(3136/64) x ceil(64/64) tiles
+    assert p.kernel_name == "layout_transpose<32x32>"
+    assert p.launch_shape()[0] == (32 * 98 * 2, 1, 1)  # 32 images x ceil(3136/32) x ceil(64/32) tiles
     assert plan((32, 64, 64, 64), (64 * 4096, 64, 1, 4096)).kernel_name == "layout_transpose<64x128>"
-    assert plan((100, 200), (1, 100)).kernel_name == "layout_transpose<64x64>"
+    assert plan((100, 200), (1, 100)).kernel_name == "layout_transpose<32x32>"
     assert plan((4096, 8192), (1, 4096)).kernel_name == "layout_transpose<128x128>"
     assert plan((8, 16, 32, 64), (16 * 32 * 64, 64, 16 * 64, 1)).kernel_name == "layout_rows<vec4>"
     assert plan((5, 7), (0, 1)).kernel_name == "layout_rows<scalar>"
