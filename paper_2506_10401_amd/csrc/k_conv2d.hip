@@ -109,7 +109,7 @@ constexpr int mode_iv(int mode) { return mode <= 2 ? 4 : (mode == 3 ? 2 : 1); }
 constexpr int mode_ipt(int mode) { return mode == 1 ? 2 : 4; }
 
 template <int R, int CC, int KT, int MODE, bool POOL, bool WIN>
-__global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict__ in, const float* __restrict__ wt,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE != 0 ? 5 : 4, MODE != 0 ? 5 : 8))) void conv2d_nchw_mfma(const float* __restrict__ in, const float* __restrict__ wt,
                                                         ConvEpi epi, float* __restrict__ out, ConvGeom g) {
     using cfg = Cfg<R, CC, KT>;
     constexpr bool FAST = MODE != 0;
@@ -128,7 +128,8 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     float* const addS = mulS + KT;                              // KT floats: per-channel addend
     float* const dumpS = addS + KT;                             // 4 floats nobody reads
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: what depends on it alone costs no vector ALU
     const int half = lane >> 5, l32 = lane & 31;
 
     // work item = (pixel tile, channel block); consecutive items (same tile, then
@@ -323,18 +324,28 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
     // B-fragment rows: one LDS pointer per (stage, chunk channel of this lane half, filter row), worked out
     // once, so that inside the chunk loop a fragment read is pointer + immediate (kw) and costs no vector ALU
     // instruction (with run-time pitches every (c, kh) pair was an add per chunk, not overlapped with the MFMAs)
-    const float* brow[NBUF][CC / 2][R];
+    // (kept as byte offsets the compiler cannot relate to each other: it would otherwise keep one pointer per row
+    // and re-derive the second stage's with a vector add in front of every read, inside the MFMA block)
+    unsigned brow[NBUF][CC / 2][R];
+    unsigned arow[NBUF];
+    auto lds_at = [&](unsigned bytes) { return reinterpret_cast<const float*>(reinterpret_cast<const char*>(lds) + bytes); };
 #pragma unroll
-    for (int b = 0; b < NBUF; ++b)
+    for (int b = 0; b < NBUF; ++b) {
 #pragma unroll
         for (int c = 0; c < CC / 2; ++c)
 #pragma unroll
-            for (int kh = 0; kh < R; ++kh) brow[b][c][kh] = inS(b) + b_base + c * g.ch_ld + kh * dl * g.ldw;
+            for (int kh = 0; kh < R; ++kh) {
+                brow[b][c][kh] = (unsigned)(NBUF * cfg::W_STAGE + b * in_stage + b_base + c * g.ch_ld + kh * dl * g.ldw) * 4u;
+                asm volatile("" : "+v"(brow[b][c][kh]));
+            }
+        arow[b] = (unsigned)(b * cfg::W_STAGE + a_base) * 4u;
+        asm volatile("" : "+v"(arow[b]));
+    }
     auto compute = [&](auto cur_tag) {
         constexpr int cur = decltype(cur_tag)::value;
         // waves inside their MFMA block win the issue arbitration over waves that are staging
         __builtin_amdgcn_s_setprio(1);
-        const float* aW = wS(cur) + a_base;
+        const float* aW = lds_at(arow[cur]);
 #pragma unroll
         for (int j = 0; j < HALF / VW; ++j) {
             float a[KB][VW];
@@ -354,7 +365,7 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
             for (int e = 0; e < VW; ++e) {
                 const int s = VW * j + e;  // MFMA step inside the chunk
                 const int c = s / TAPS, tap = s % TAPS;
-                const float b = brow[cur][c][tap / R][(tap % R) * dl];
+                const float b = lds_at(brow[cur][c][tap / R])[(tap % R) * dl];
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) acc[kb] = mfma_32x32x2(a[kb][e], b, acc[kb]);
             }
@@ -409,43 +420,84 @@ __global__ __launch_bounds__(256) void conv2d_nchw_mfma(const float* __restrict_
         }
     }
 
-    // ---- epilogue: register r of lane holds channel 8*(r/4) + 4*half + r%4 of the block
-    if (!POOL) {
-        if (p_ok) {
+    // ---- epilogue: register r of lane holds channel 8*(r/4) + 4*half + r%4 of the block.
+    // Vector-ALU instructions of one wave hold up the MFMAs of the others, so per register there is a multiply-add,
+    // the clamp and the store: the four channels of a register group are consecutive, so their factors come as
+    // 128-bit LDS reads issued together; a register's address is a scalar base (image, channel) plus one per-lane
+    // 32-bit offset worked out once; the activation is a template value behind a scalar switch.
+    auto finish = [&](auto relu_tag) {
+        constexpr int RELU = decltype(relu_tag)::value;
+        auto act = [](float v) {
+            if (RELU) v = fmaxf(v, 0.f);
+            if (RELU == 2) v = fminf(v, 6.f);
+            return v;
+        };
+        const int plane = POOL ? g.Hp * g.Wp : g.HoWo;   // elements of one output channel
+        // this lane's byte offset inside the 8-channel group of a register quartet (the host admits planes below 2^27 elements)
+        unsigned loff;
+        bool st_ok;
+        if (POOL) {
+            // lane = 8*row + column inside the block: the vertical partner of a window is lane ^ 8
+            // (a rotation by 8 inside the 16-lane DPP row), the horizontal one lane ^ 1
+            const int rp = oh >> 1, px = ow >> 1;
+            st_ok = (lane & 9) == 0 && rp < g.Hp && px < g.Wp;
+            loff = (unsigned)(4 * half * plane + rp * g.Wp + px) * 4u;
+        } else {
+            st_ok = p_ok;
+            loff = (unsigned)(4 * half * plane + p) * 4u;
+        }
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
+        for (int kb = 0; kb < KB; ++kb) {
+            const int kl0 = kb0 + kb * 32;   // scalar
+            float4v mul[4], add[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                mul[q] = *reinterpret_cast<const float4v*>(mulS + kl0 + 8 * q + 4 * half);
+                add[q] = *reinterpret_cast<const float4v*>(addS + kl0 + 8 * q + 4 * half);
+            }
+            float* const ob = out + ((int64_t)n * g.K + k0 + kl0) * plane;   // scalar
+            const bool whole = k0 + kl0 + 32 <= g.K;                         // scalar: all 32 channels of the block exist
+            float v[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                v[r] = act(acc[kb][r] * mul[r >> 2][r & 3] + add[r >> 2][r & 3]);
+                if (POOL) {
+                    v[r] = fmaxf(v[r], dpp_mov<0x128>(v[r]));  // row_ror:8
+                    v[r] = fmaxf(v[r], dpp_mov<0xB1>(v[r]));   // quad_perm [1,0,3,2]
+                }
+            }
+            // Channel of half 0 inside the block: kr = 8 * (r / 4) + r % 4.  Raw buffer stores: the descriptor covers the
+            // channels of this block that exist, a lane with nothing to store carries an offset beyond it and the
+            // hardware drops its store, so there is no predicate; a register's channel offset is a scalar operand.
+            // (The scalar operand takes no part in the range check: it is used only where all 32 channels exist.)
+            const int left = g.K - (k0 + kl0);   // scalar
+            if (plane <= (1 << 24)) {
+                const int chans = left >= 32 ? 32 : (left > 0 ? left : 0);
+                const int bytes = __builtin_amdgcn_readfirstlane(chans * plane * 4);   // (scalar already; keeps the descriptor in scalar registers)
+                __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(ob, 0, bytes, kBufWord3);
+                const unsigned voff = st_ok ? loff : kBufOob;
+                if (whole) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[r]), rs, (int)voff, (8 * (r >> 2) + (r & 3)) * plane * 4, 0);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v[r]), rs,
+                                                              (int)(st_ok ? loff + (unsigned)((8 * (r >> 2) + (r & 3)) * plane * 4) : kBufOob), 0, 0);
+                }
+            } else if (st_ok) {   // planes too large for a 32-bit descriptor
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int kl = kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                    const int k = k0 + kl;
-                    if (k < g.K) {
-                        float v = acc[kb][r] * mulS[kl] + addS[kl];
-                        if (epi.relu) v = fmaxf(v, 0.f);
-                        if (epi.relu == 2) v = fminf(v, 6.f);
-                        out[((int64_t)n * g.K + k) * g.HoWo + p] = v;
-                    }
+                    const int kr = 8 * (r >> 2) + (r & 3);
+                    if (kr + 4 * half < left) *reinterpret_cast<float*>(reinterpret_cast<char*>(ob + (int64_t)kr * plane) + loff) = v[r];
                 }
             }
         }
-    } else {
-        // lane = 8*row + column inside the block: the vertical partner of a window is lane ^ 8
-        // (a rotation by 8 inside the 16-lane DPP row), the horizontal one lane ^ 1
-        const int rp = oh >> 1, px = ow >> 1;
-        const bool st_ok = (lane & 9) == 0 && rp < g.Hp && px < g.Wp;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kl = kb0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                float v = acc[kb][r] * mulS[kl] + addS[kl];
-                if (epi.relu) v = fmaxf(v, 0.f);
-                if (epi.relu == 2) v = fminf(v, 6.f);
-                v = fmaxf(v, dpp_mov<0x128>(v));  // row_ror:8
-                v = fmaxf(v, dpp_mov<0xB1>(v));   // quad_perm [1,0,3,2]
-                const int k = k0 + kl;
-                if (st_ok && k < g.K) out[(((int64_t)n * g.K + k) * g.Hp + rp) * g.Wp + px] = v;
-            }
-    }
+    };
+    if (epi.relu == 0) finish(std::integral_constant<int, 0>{});
+    else if (epi.relu == 1) finish(std::integral_constant<int, 1>{});
+    else finish(std::integral_constant<int, 2>{});
 }
 
 // input channels per LDS chunk: 4 (x 9 taps = 18 MFMA steps per chunk for 3x3); a 1x1 filter has one
@@ -602,6 +654,11 @@ bool conv_supported(int32_t C, int32_t H, int32_t W, int32_t K, int32_t R, int32
     if (R != S || (R != 1 && R != 3 && R != 5 && R != 7)) { *why = "only square 1x1, 3x3, 5x5 and 7x7 filters are supported"; return false; }
     if (pad_h != pad_w) { *why = "padding must be the same in both directions"; return false; }
     if (pad_h > (R - 1) * dil_h) { *why = "padding larger than the (dilated) filter extent minus one"; return false; }
+    {   // the epilogue addresses a lane's element inside a group of 8 output channels with a 32-bit byte offset
+        const int re = (R - 1) * dil_h + 1;
+        const int64_t Ho = (H + 2 * pad_h - re) / stride_h + 1, Wo = (W + 2 * pad_w - re) / stride_w + 1;
+        if (Ho * Wo > ((int64_t)1 << 27)) { *why = "more than 2^27 output pixels per channel"; return false; }
+    }
     ConvParams p{};
     p.C = C; p.H = H; p.W = W; p.K = K; p.R = R; p.S = S; p.pad = pad_h; p.Nb = 1; p.stride = stride_h; p.dil = dil_h; p.pool = pool; p.win = conv_window_geometry(p);
     if (lds_any(p) > 160 * 1024) { *why = "the input of one 64-pixel tile does not fit in LDS (image too wide)"; return false; }

@@ -745,6 +745,15 @@ def test_conv_window_geometry_without_pooling(N, C, H, W, K, R, stride, pad, dil
     check_chain7(t, stride, pad, relu=False, pool=False, bias=False, affine=False, dil=dil)
 
 
+def test_conv_planes_above_2_to_24_pixels():
+    # the epilogue stores through a 32-bit buffer descriptor per 32 output channels; a plane of more than 2^24 pixels
+    # does not fit one and takes plain stores (two output channels: the ragged-channel test of that path too)
+    print("conv 5 x 4100 x 4100 -> 2", flush=True)
+    t = datagen.make(7, N=1, C=5, H=4100, W=4100, K=2, R=3, S=3)
+    _, name = check_chain7(t, 1, 1, pool=False)
+    assert name == "conv2d_nchw_mfma<3x3,general,window>"
+
+
 @pytest.mark.parametrize("N,C,H,W,K", [
     (32, 64, 56, 56, 64),        # a bottleneck's 1x1 at full size: memory-bound
     (32, 24, 56, 56, 144),       # a MobileNetV2 expansion: one chunk of 32 channels, 8 of them padding
