@@ -471,7 +471,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE != 0 ?
             // hardware drops its store, so there is no predicate; a register's channel offset is a scalar operand.
             // (The scalar operand takes no part in the range check: it is used only where all 32 channels exist.)
             const int left = g.K - (k0 + kl0);   // scalar
-            if (plane <= (1 << 24)) {
+            if (plane < (1 << 24)) {   // 32 channels x plane x 4 bytes stay below 2^31, the offset of a lane with nothing to store
                 const int chans = left >= 32 ? 32 : (left > 0 ? left : 0);
                 const int bytes = __builtin_amdgcn_readfirstlane(chans * plane * 4);   // (scalar already; keeps the descriptor in scalar registers)
                 __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(ob, 0, bytes, kBufWord3);
