@@ -161,6 +161,23 @@ def main() -> int:
         # further buffer sets for cache-cold timing: same values, rolled, in distinct memory
         return t if k == 0 else torch.roll(t.flatten(), 1001 * k).reshape(t.shape).contiguous()
 
+    def arena(tensors):
+        """copies of `tensors` carved out of ONE device allocation (4 KB-aligned pieces): the rotating buffer sets of a
+        memory-bound chain then sit in one mapping with large page fragments, where separate allocations of 26 MB
+        each cost chain 2 about 0.12 us per launch in address-translation misses (9.03 against 9.15 us)"""
+        shapes = [tuple(t) if isinstance(t, (tuple, list)) else tuple(t.shape) for t in tensors]   # a shape: uninitialised piece
+        numels = [int(torch.Size(sh).numel()) for sh in shapes]
+        sizes = [(n * 4 + 4095) // 4096 * 4096 for n in numels]
+        buf = torch.empty(sum(sizes) // 4, device="cuda", dtype=torch.float32)
+        out, off = [], 0
+        for t, sh, n, sz in zip(tensors, shapes, numels, sizes):
+            v = buf[off // 4: off // 4 + n].view(sh)
+            if torch.is_tensor(t):
+                v.copy_(t)
+            out.append(v)
+            off += sz
+        return out
+
     sets = {}
     if 1 in which:
         h = host[1]
@@ -169,11 +186,17 @@ def main() -> int:
         h = host[2]
         X, R, sc, sh = dev(h["X"]), dev(h["R"]), dev(h["scale"]), dev(h["shift"])
         n = LLC_BYTES * 2 // (2 * X.numel() * 4) + 1
-        sets[2] = [dict(ins=[rotated(X, k), sc, sh, rotated(R, k)], out=torch.empty(32, 64, device="cuda")) for k in range(n)]
+        Xs, Rs = [], []
+        for k in range(n):   # (one rolled copy at a time: the arena holds them, the temporaries go back to the allocator)
+            Xs.append(rotated(X, k)); Rs.append(rotated(R, k))
+        pieces = arena(Xs + Rs)
+        del Xs, Rs
+        sets[2] = [dict(ins=[pieces[k], sc, sh, pieces[n + k]], out=torch.empty(32, 64, device="cuda")) for k in range(n)]
     if 3 in which:
         h = host[3]
         X, g, b = dev(h["X"]), dev(h["gamma"]), dev(h["beta"])
-        sets[3] = [dict(ins=[rotated(X, k), g, b], out=torch.empty(8192, 4096, device="cuda")) for k in range(3)]
+        pieces = arena([rotated(X, k) for k in range(3)] + [(8192, 4096)] * 3)
+        sets[3] = [dict(ins=[pieces[k], g, b], out=pieces[3 + k]) for k in range(3)]
     if 4 in which:
         h = host[4]
         sets[4] = [dict(ins=[dev(h["in"]), dev(h["wt"]), dev(h["bias"])], out=torch.empty(32, 128, 56, 56, device="cuda"))]
@@ -408,7 +431,7 @@ def main() -> int:
         ms = [s["ins"][0] for s in sets[3]]                    # 3 matrices [8192,4096]
         mo = [s["out"] for s in sets[3]]                       # the layernorm outputs serve as destinations
         nb_x, nb_m = xs[0].numel() * 4, ms[0].numel() * 4
-        outs = [torch.empty(32, 56, 56, 64, device="cuda") for _ in xs]
+        outs = arena([(32, 56, 56, 64)] * len(xs))
         name, call = plan_calls([hpct.layout_transform_plan(x.permute(0, 2, 3, 1), o) + (o,) for x, o in zip(xs, outs)])
         layout_ops.append(side_line("nchw_to_nhwc_32x64x56x56", name, call, 2 * nb_x, "hbm", len(xs)))
         del outs
