@@ -84,6 +84,8 @@ def main() -> int:
                     help="GPU time of the untimed clock-settling stretch before the warm-up steps (0 switches it off)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU checker")
     ap.add_argument("--only", type=int, default=0, help="run a single chain (1..5) instead of all five")
+    ap.add_argument("--lib", default=None,
+                    help="another build of libhpct.so to load (A/B of a kernel against an earlier source); the JSON names it")
     ap.add_argument("--skip-extra", action="store_true",
                     help="leave out the side measurements (layout transforms, axis reductions, later chains, graph replay)")
     ap.add_argument("--with-other", action="store_true",
@@ -109,7 +111,7 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         return 2
-    hpct.load()
+    hpct.load(os.path.abspath(args.lib) if args.lib else None)
     torch.cuda.set_device(0)
     # everything runs on one non-default stream, so the same launches can also be captured into HIP graphs
     work = torch.cuda.Stream()
@@ -594,6 +596,8 @@ def main() -> int:
                next_ops=next_ops, graph_step=graph_step)
     if other_ops:
         out["other_ops"] = other_ops
+    if args.lib:
+        out["library"] = args.lib
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(host, which)
