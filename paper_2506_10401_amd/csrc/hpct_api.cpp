@@ -401,10 +401,12 @@ hpct_status plan_layout(const hpct_op_desc& d, hpct_plan& p) {
     }
     if (q.kind == 2) {
         // work-groups of the tiled transpose must fit a 32-bit grid
-        int64_t groups = ((q.shape[a] + 63) / 64) * ((q.shape[q.bdim] + 63) / 64);  // upper bound for every tile shape
+        int64_t groups = ((q.shape[a] + 31) / 32) * ((q.shape[q.bdim] + 31) / 32);  // upper bound for every tile shape
         for (int k = 0; k < a; ++k)
             if (k != q.bdim) groups *= q.shape[k];
-        if (groups > kI32Max) q.kind = 0, q.bdim = -1;
+        bool fits = groups <= kI32Max;
+        for (int k = 0; k < nd; ++k) fits = fits && q.shape[k] <= kI32Max - 128;   // (tile coordinates are 32-bit too)
+        if (!fits) q.kind = 0, q.bdim = -1;
     }
     p.kind = Kind::Layout;
     p.u.layout = q;

@@ -277,6 +277,9 @@ def test_layout_transform_plans():
     assert plan((4096, 8192), (1, 4096)).kernel_name == "layout_transpose<128x128>"
     assert plan((8, 16, 32, 64), (16 * 32 * 64, 64, 16 * 64, 1)).kernel_name == "layout_rows<vec4>"
     assert plan((5, 7), (0, 1)).kernel_name == "layout_rows<scalar>"
+    # the tiled transpose works with 32-bit tile coordinates: an extent beyond them falls back to the gather
+    assert plan((2, 3 * 10**9), (1, 2)).kernel_name == "layout_rows<scalar>"
+    assert plan((2, 2 * 10**9), (1, 2)).kernel_name == "layout_transpose<32x32>"
     assert plan((4, 6, 8, 4), (6 * 8 * 12, 8 * 12, 12, 3)).kernel_name == "layout_rows<scalar>"  # no unit stride anywhere
     # the output must be contiguous and of the view's shape
     d = H.op_desc(H.HPCT_ANCHOR_NONE, [], H.HPCT_RED_NONE, 0, [H.tensor_desc((4, 6), (1, 4))], [H.tensor_desc((4, 6), (1, 4))])
@@ -740,6 +743,17 @@ def test_conv_few_input_channels_plans():
     for d in (cd((32, 3, 224, 224), 48), cd((32, 3, 224, 224), 64, stride=3), cd((32, 3, 224, 224), 64, pad=0), cd((32, 3, 224, 220), 64, stride=2),
               cd((32, 3, 224, 224), 64, pool=True), cd((32, 3, 224, 222), 64), cd((32, 5, 224, 224), 64), cd((2, 3, 32, 32), 64)):
         assert H.Plan(d).kernel_name.startswith("conv2d_nchw_mfma<3x3")
+
+
+def test_conv_refuses_planes_beyond_its_32_bit_store_offsets():
+    # the conv epilogue addresses a lane's element inside a group of 8 output channels with a 32-bit byte offset:
+    # more than 2^27 output pixels per channel are refused when the plan is made (8 input channels: the MFMA kernel)
+    def cd(Hh, Ww):
+        return H.op_desc(H.HPCT_ANCHOR_CONV2D_NCHW, [H.HPCT_EPI_BIAS_COL, H.HPCT_EPI_RELU], H.HPCT_RED_NONE, 0,
+                         [(1, 8, Hh, Ww), (2, 8, 3, 3), (2,)], [(1, 2, Hh, Ww)], stride_hw=(1, 1), pad_hw=(1, 1))
+    assert H.Plan(cd(11000, 12000)).kernel_name.startswith("conv2d_nchw_mfma<3x3")   # 1.32e8 <= 2^27 = 1.34e8
+    e = expect(H.HPCT_ERR_UNSUPPORTED, cd(11500, 12000))
+    assert "2^27" in e.message
 
 
 def gn_desc(shape=(32, 64, 56, 56), groups=8, affine=True, relu=False, rbe=1, eps=1e-5):
