@@ -125,13 +125,19 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restric
     // address arithmetic, select or zero fill per block on the vector ALU, which does not overlap the MFMAs.
     float4v kreg[LD4], vreg[LD4];
     auto fetch = [&](int key0) {
-        const bool tail = key0 + KB > Lk;   // uniform
+        if (key0 + KB <= Lk) {   // uniform; a branch of its own, so that whole blocks pay no compare / select per load
 #pragma unroll
-        for (int i = 0; i < LD4; ++i) {
-            unsigned off = kv_off[i];
-            if (tail && key0 + (tid + i * NT) / (D / 4) >= Lk) off = 0x80000000u;
-            kreg[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(k_rs, (int)off, key0 * D * 4, 0));
-            vreg[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(v_rs, (int)off, key0 * D * 4, 0));
+            for (int i = 0; i < LD4; ++i) {
+                kreg[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(k_rs, (int)kv_off[i], key0 * D * 4, 0));
+                vreg[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(v_rs, (int)kv_off[i], key0 * D * 4, 0));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LD4; ++i) {
+                const unsigned off = key0 + (tid + i * NT) / (D / 4) >= Lk ? 0x80000000u : kv_off[i];
+                kreg[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(k_rs, (int)off, key0 * D * 4, 0));
+                vreg[i] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(v_rs, (int)off, key0 * D * 4, 0));
+            }
         }
     };
     auto stash = [&](auto buf_tag) {
@@ -157,6 +163,16 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restric
         const int nb = q_last / KB + 1;
         nblocks = nb < nblocks ? nb : nblocks;
     }
+    unsigned vrow[2][SUB][4];   // byte offset in LDS of V row (sub-block's first key + 4 half + 8 g), column l32, per stage
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+        for (int u = 0; u < SUB; ++u)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                vrow[b2][u][g4] = (unsigned)(2 * KB * KLD + b2 * KB * VLD + ((kgrp * SUB + u) * 32 + 4 * half + 8 * g4) * VLD + l32) * 4u;
+                asm volatile("" : "+v"(vrow[b2][u][g4]));
+            }
     auto block = [&](int t, auto cur_tag, auto next_tag) {   // stage index compile-time: fragment reads are base + immediate
         constexpr int cur = decltype(cur_tag)::value;
         if (t + 1 < nblocks) fetch((t + 1) * KB);
@@ -240,11 +256,12 @@ __global__ __launch_bounds__(64 * NQW * KS) void attn_fwd(const float* __restric
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
             if (skip[u]) continue;
-            const int kb = (kgrp * SUB + u) * 32;
-            const float* vbase = Vc + (kb + 4 * half) * VLD + l32;
+            // one byte offset per group of four fragment rows, kept opaque: the compiler would otherwise re-derive each
+            // group's address from one base with a vector add in front of its reads, inside the MFMA block (paired LDS
+            // reads only take 8-bit offsets)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float* vr = vbase + (8 * (r >> 2) + (r & 3)) * VLD;
+                const float* vr = reinterpret_cast<const float*>(reinterpret_cast<const char*>(lds) + vrow[cur][u][r >> 2]) + (r & 3) * VLD;
 #pragma unroll
                 for (int db = 0; db < DB; ++db) o[db] = mfma_32x32x2(vr[32 * db], s[u][r], o[db]);
             }
