@@ -5,7 +5,8 @@ A step is one pass of the whole hot path: one launch of each of the five fused
 chains (GEMM+bias+ReLU+softmax, affine+ReLU+residual+avg-pool, layernorm+GELU,
 conv3x3+bias+ReLU, GEMM-softmax-GEMM) at full size on seeded synthetic inputs
 already resident in HBM.  The memory-bound chains rotate over buffer sets whose
-total exceeds the 256 MB last-level cache, so their reads come from HBM.
+total exceeds the 256 MB last-level cache, so their reads come from HBM; a
+chain's sets are pieces of one device allocation.
 
 Order of the run:
   1. pre-roll: an untimed, disclosed stretch of the two long contraction
