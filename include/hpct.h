@@ -79,7 +79,8 @@
  *         then MAXPOOL2_HW or no reduction            bias[K], scale[K], shift[K]   [N,K,Ho/2,Wo/2]
  *         (square 1/3/5/7 filter, stride and                                         with MAXPOOL2_HW
  *         dilation <= 4, Ho = (H + 2 pad -
- *         (R-1) dilation - 1) / stride + 1)
+ *         (R-1) dilation - 1) / stride + 1;
+ *         Ho * Wo <= 2^27, else UNSUPPORTED)
  *   BGEMM_SOFTMAX_BGEMM [+SCALE_CONST: scores scaled  Q[B,L,D], K[B,Lk,D],          [B,L,D]
  *         by `scale`] [+CAUSAL_MASK] (D = 32, 64, 128) V[B,Lk,D]
  */
